@@ -1,0 +1,207 @@
+/*
+ * dn.h -- C ABI of libdn: training of fully connected feed-forward networks
+ * on one AMD MI355X (gfx950).
+ *
+ * The library runs the training loop the paper describes in its section "The
+ * Deep Netts Work-flow": feed forward, loss error assessment, back propagation
+ * through the layers in reverse order, and the learning-rate scaled update of
+ * the weights and biases of every neuron.  The neuron model (net input =
+ * weights . inputs + bias, output = activation(net input)) is that of the
+ * section "Deep Learning Overview".  The two methods the paper offloads -- the
+ * backward step of the fully connected layer and of the softmax output layer
+ * (section "How Deep Netts is parallelized with TornadoVM?") -- correspond to
+ * dn_backward / dn_update here; dn_train_epoch runs whole epochs with all state
+ * resident on the device, which removes the per-call host<->device copies the
+ * paper's task schedule performs and names as its main overhead (sections
+ * "Performance Analysis" and "Conclusions").
+ *
+ * Conventions
+ *   - All arithmetic and all tensors are fp32, row-major, contiguous.
+ *   - Layers l = 1..L, widths n_0 (input) .. n_L (output).  W_l is
+ *     [n_l][n_{l-1}], b_l is [n_l].  A batch of B samples is [B][n].
+ *   - Labels are int32 class ids in [0, n_L); targets are their one-hot rows
+ *     (for squared error too).
+ *   - "_dev" pointers are device memory, "_host" pointers host memory.
+ *   - The library never allocates or frees device memory: the caller hands it
+ *     one arena (dn_net_arena_bytes) that holds parameters, velocities,
+ *     gradients, activations, deltas and kernel workspace, and the caller owns
+ *     it and every other device buffer.  The arena must stay alive, and must
+ *     not be written by the caller, until dn_net_destroy.
+ *   - All device work is enqueued on the HIP stream given at creation.
+ *     dn_forward / dn_backward / dn_update return without waiting for it;
+ *     dn_set_params / dn_get_params / dn_get_grads / dn_train_epoch wait for
+ *     the stream before they return.
+ *   - Every function returns a dn_status; none throws or aborts.  Arguments
+ *     are validated on the host before anything is launched.
+ *   - A net is not thread safe; different nets may be used from different
+ *     threads.
+ */
+#ifndef DN_H
+#define DN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dn_net dn_net; /* opaque host-side handle */
+
+typedef enum {
+    DN_OK = 0,
+    DN_ERR_INVALID_ARG = 1, /* NULL pointer, value out of range, call out of order */
+    DN_ERR_SHAPE = 2,       /* widths / batch / arena size do not fit */
+    DN_ERR_UNSUPPORTED = 3, /* activation / loss combination not provided */
+    DN_ERR_OOM = 4,         /* host allocation of the handle failed */
+    DN_ERR_DEVICE = 5       /* a HIP call or a kernel reported an error */
+} dn_status;
+
+typedef enum {
+    DN_ACT_LINEAR = 0,
+    DN_ACT_SIGMOID = 1,
+    DN_ACT_TANH = 2,
+    DN_ACT_RELU = 3,
+    DN_ACT_SOFTMAX = 4 /* last layer only, and only with DN_LOSS_CROSS_ENTROPY */
+} dn_act;
+
+typedef enum {
+    DN_LOSS_MSE = 0,          /* per sample 1/2 sum_k (a_k - y_k)^2 */
+    DN_LOSS_CROSS_ENTROPY = 1 /* per sample -log softmax(z)[label]; needs a softmax last layer */
+} dn_loss;
+
+/* Short static description of a status code (never NULL). */
+const char *dn_status_string(dn_status s);
+
+/*
+ * Bytes of device arena a net of these widths needs for batches up to
+ * max_batch.  Returns 0 if the arguments are invalid (NULL, n_widths < 2, a
+ * width <= 0, max_batch <= 0, or sizes that overflow).
+ */
+size_t dn_net_arena_bytes(const int32_t *widths, int32_t n_widths, int32_t max_batch);
+
+/*
+ * Build a network (the paper's "build the artificial neural network" step;
+ * layer types and counts are the configuration parameters it lists).
+ *   widths      n_0..n_L, n_widths = L+1 >= 2, all > 0           (host)
+ *   acts        L activations, one per layer                     (host)
+ *   loss        loss function of the output layer
+ *   max_batch   largest batch any later call may pass
+ *   arena_dev   device memory, 256-byte aligned, >= dn_net_arena_bytes(...)
+ *   hip_stream  a hipStream_t (NULL = the default stream)
+ *   out         receives the handle
+ * Parameters, velocities and gradients start at zero; call dn_set_params.
+ * Errors: INVALID_ARG (NULL, bad enum, misaligned arena), SHAPE (widths,
+ * max_batch, arena too small), UNSUPPORTED (softmax not last / softmax without
+ * cross-entropy / cross-entropy without softmax), OOM, DEVICE.
+ */
+dn_status dn_net_create(const int32_t *widths, int32_t n_widths, const dn_act *acts,
+                        dn_loss loss, int32_t max_batch, void *arena_dev, size_t arena_bytes,
+                        void *hip_stream, dn_net **out);
+
+/* Free the host handle (waits for the stream first).  The arena is the caller's. */
+dn_status dn_net_destroy(dn_net *net);
+
+/*
+ * Copy parameters of layer `layer` (1..L) between host and device.  W_host is
+ * [n_l][n_{l-1}], b_host is [n_l]; either may be NULL to skip it.
+ * dn_set_params also zeroes that layer's velocity (the paper's "initialize the
+ * values of weights and biases" step is done by the caller, who passes the
+ * initial values here).  dn_get_grads reads the batch-mean gradients left by
+ * the last dn_backward.
+ */
+dn_status dn_set_params(dn_net *net, int32_t layer, const float *W_host, const float *b_host);
+dn_status dn_get_params(dn_net *net, int32_t layer, float *W_host, float *b_host);
+dn_status dn_get_grads(dn_net *net, int32_t layer, float *G_host, float *g_host);
+
+/*
+ * Feed forward (training part 1): A_0 = X; Z_l = A_{l-1} W_l^T + b_l;
+ * A_l = f_l(Z_l); softmax rows are exp(z - max z) / sum exp(z - max z).
+ *   X_dev    [batch][n_0]  (device; read only; must stay valid until the
+ *            matching dn_backward has been enqueued and the stream has passed it)
+ *   out_dev  [batch][n_L]  (device) receives A_L; may be NULL
+ * 1 <= batch <= max_batch, else DN_ERR_SHAPE.
+ */
+dn_status dn_forward(dn_net *net, const float *X_dev, int32_t batch, float *out_dev);
+
+/*
+ * Loss error assessment and back propagation (training parts 2 and 3, without
+ * the update) for the batch of the last dn_forward:
+ *   output layer    cross-entropy: Delta_L = P - Y ;  squared error:
+ *                   Delta_L = (A_L - Y) * f'_L(A_L)
+ *   hidden layers   Delta_{l-1} = (Delta_l W_l) * f'_{l-1}(A_{l-1}),  l = L..2
+ *   gradients       G_l = (1/B) Delta_l^T A_{l-1},  g_l = (1/B) column sums of Delta_l
+ * (for B = 1, G_l is the outer product delta x input that the paper's offloaded
+ * two-index loop fills).  Derivatives are taken from the stored activations:
+ * sigmoid a(1-a), tanh 1-a^2, ReLU [a>0], linear 1.
+ *   labels_dev [batch] int32 (device);  loss_dev (device, 1 float) receives the
+ *   batch-mean loss, may be NULL.  batch must equal the last dn_forward's batch
+ *   (DN_ERR_SHAPE); calling it before any dn_forward is DN_ERR_INVALID_ARG.
+ */
+dn_status dn_backward(dn_net *net, const int32_t *labels_dev, int32_t batch, float *loss_dev);
+
+/*
+ * Update from the gradients of the last dn_backward (the paper's
+ * learning-rate scaled weight and bias deltas):
+ *   dW_l <- momentum * dW_l - lr * G_l ;  W_l <- W_l + dW_l     (same for b_l)
+ * momentum = 0 is plain gradient descent.  lr >= 0 and 0 <= momentum < 1 and
+ * both finite, else DN_ERR_INVALID_ARG; DN_ERR_INVALID_ARG before any dn_backward.
+ */
+dn_status dn_update(dn_net *net, float lr, float momentum);
+
+/*
+ * One epoch: samples 0..n_samples-1 in index order, `batch` per step (the last
+ * step may be short and averages over its own size); each step is forward,
+ * loss + back propagation (every delta from the weights as they were before
+ * this step's update), update.  Nothing returns to the host between steps.
+ *   X_dev [n_samples][n_0], labels_dev [n_samples] int32     (device)
+ *   mean_loss_host  receives sum over steps of (step-mean loss * step size) /
+ *                   n_samples, each step's loss taken before its update; may be NULL
+ * Gradient buffers read by dn_get_grads are not maintained by this call.
+ * Errors: INVALID_ARG (NULL, n_samples <= 0, bad lr/momentum), SHAPE (batch
+ * outside 1..max_batch), DEVICE.
+ */
+dn_status dn_train_epoch(dn_net *net, const float *X_dev, const int32_t *labels_dev,
+                         int64_t n_samples, int32_t batch, float lr, float momentum,
+                         float *mean_loss_host);
+
+/*
+ * Measurement hooks (the paper times its two offloaded methods with wall-clock
+ * timers, section "Experimental Evaluation"; here the device itself is timed).
+ *
+ * dn_last_epoch_ms: milliseconds the device spent between the first and the
+ * last kernel of the last dn_train_epoch, from HIP events on the net's stream.
+ *
+ * dn_kernel_time: with dn_set_option("time_kernels", 1), every kernel launch of
+ * dn_train_epoch is bracketed by HIP events on the net's stream (up to 16384
+ * launches per epoch; later ones run untimed).  After the epoch this returns,
+ * for one kernel class, the summed duration and the number of timed launches.
+ */
+typedef enum {
+    DN_K_FORWARD = 0,     /* Z = A W^T + b, activation                       */
+    DN_K_DELTA = 1,       /* Delta_{l-1} = (Delta_l W_l) * f'                */
+    DN_K_GRAD_UPDATE = 2, /* G = Delta^T A / B fused with the weight update  */
+    DN_K_OUTPUT = 3,      /* softmax / loss / Delta_L and loss reduction     */
+    DN_K_BIAS = 4,        /* bias gradient and update                        */
+    DN_K_ONLINE = 5,      /* persistent batch-1 epoch kernel                 */
+    DN_K_CLASSES = 6
+} dn_kernel_class;
+
+dn_status dn_last_epoch_ms(dn_net *net, float *epoch_ms);
+dn_status dn_kernel_time(dn_net *net, int32_t kernel_class, float *ms_total, int64_t *launches);
+
+/*
+ * Tuning and diagnostics switches (all default 0):
+ *   "time_kernels"   1: collect per-launch times in dn_train_epoch (see above)
+ *   "gemm_variant"   -1 (default): pick the tile configuration of each
+ *                    contraction from its shape; >= 0: force that configuration
+ *   "online_mode"    0: choose automatically; 1: per-phase launches for batch 1;
+ *                    2: persistent whole-epoch kernel for batch 1
+ * Unknown names or values out of range give DN_ERR_INVALID_ARG.
+ */
+dn_status dn_set_option(dn_net *net, const char *name, int64_t value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DN_H */

@@ -1,0 +1,469 @@
+// Host side of libdn: argument validation, arena layout, the schedule of
+// kernel launches for each entry point of include/dn.h, and launch timing.
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "dn_internal.h"
+
+using namespace dn;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+constexpr int kMaxTimed = 16384;
+
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+// Offsets (bytes) of everything the arena holds.
+struct Layout {
+    std::vector<size_t> W, b;   // per layer, relative to the start of a parameter-shaped region
+    size_t region = 0;          // bytes of one parameter-shaped region (params / velocity / gradients)
+    std::vector<size_t> A, D;   // activations / deltas of layers 1..L, absolute
+    size_t off_params = 0, off_vel = 0, off_grads = 0;
+    size_t off_loss_rows = 0, off_scalars = 0;
+    size_t total = 0;
+};
+
+bool compute_layout(const int32_t *widths, int32_t n_widths, int32_t max_batch, Layout &lo)
+{
+    if (!widths || n_widths < 2 || max_batch <= 0) return false;
+    const int L = n_widths - 1;
+    for (int i = 0; i < n_widths; ++i)
+        if (widths[i] <= 0) return false;
+    lo.W.assign(L + 1, 0);
+    lo.b.assign(L + 1, 0);
+    lo.A.assign(L + 1, 0);
+    lo.D.assign(L + 1, 0);
+    const size_t lim = (size_t)1 << 46;  // refuse absurd sizes before they overflow
+    size_t p = 0;
+    for (int l = 1; l <= L; ++l) {
+        const size_t nw = (size_t)widths[l] * (size_t)widths[l - 1];
+        if (nw > lim / 4) return false;
+        lo.W[l] = p;
+        p += align_up(nw * sizeof(float));
+        lo.b[l] = p;
+        p += align_up((size_t)widths[l] * sizeof(float));
+        if (p > lim) return false;
+    }
+    lo.region = p;
+    size_t o = 0;
+    lo.off_params = o; o += lo.region;
+    lo.off_vel = o; o += lo.region;
+    lo.off_grads = o; o += lo.region;
+    for (int l = 1; l <= L; ++l) {
+        const size_t na = align_up((size_t)max_batch * (size_t)widths[l] * sizeof(float));
+        if (na > lim) return false;
+        lo.A[l] = o; o += na;
+        lo.D[l] = o; o += na;
+        if (o > lim) return false;
+    }
+    lo.off_loss_rows = o; o += align_up((size_t)max_batch * sizeof(float));
+    lo.off_scalars = o; o += kAlign;
+    lo.total = o;
+    return true;
+}
+
+struct TimedLaunch {
+    hipEvent_t start, stop;
+    int cls;
+};
+
+}  // namespace
+
+struct dn_net {
+    int L = 0;
+    std::vector<int32_t> n;     // widths n_0..n_L
+    std::vector<int32_t> act;   // act[l], l = 1..L (index 0 unused)
+    int loss = 0;
+    int max_batch = 0;
+    char *arena = nullptr;
+    Layout lo;
+    hipStream_t stream = nullptr;
+    // state of the split API
+    const float *X = nullptr;
+    int fwd_batch = 0;
+    bool have_fwd = false, have_bwd = false;
+    // options
+    int time_kernels = 0, gemm_variant = -1, online_mode = 0;
+    // timing
+    hipEvent_t ev_epoch0 = nullptr, ev_epoch1 = nullptr;
+    std::vector<TimedLaunch> pool;
+    int timed = 0;
+    float epoch_ms = 0.f;
+    double cls_ms[DN_K_CLASSES] = {0};
+    int64_t cls_launches[DN_K_CLASSES] = {0};
+
+    float *W(int l) const { return (float *)(arena + lo.off_params + lo.W[l]); }
+    float *b(int l) const { return (float *)(arena + lo.off_params + lo.b[l]); }
+    float *VW(int l) const { return (float *)(arena + lo.off_vel + lo.W[l]); }
+    float *Vb(int l) const { return (float *)(arena + lo.off_vel + lo.b[l]); }
+    float *GW(int l) const { return (float *)(arena + lo.off_grads + lo.W[l]); }
+    float *Gb(int l) const { return (float *)(arena + lo.off_grads + lo.b[l]); }
+    float *A(int l) const { return (float *)(arena + lo.A[l]); }
+    float *D(int l) const { return (float *)(arena + lo.D[l]); }
+    float *loss_rows() const { return (float *)(arena + lo.off_loss_rows); }
+    double *epoch_acc() const { return (double *)(arena + lo.off_scalars); }
+};
+
+namespace {
+
+#define DN_HIP(expr)                                   \
+    do {                                               \
+        hipError_t e_ = (expr);                        \
+        if (e_ != hipSuccess) return DN_ERR_DEVICE;    \
+    } while (0)
+
+bool rate_ok(float lr, float mu)
+{
+    return std::isfinite(lr) && std::isfinite(mu) && lr >= 0.f && mu >= 0.f && mu < 1.f;
+}
+
+// Brackets one launch with events when per-launch timing is on.
+struct ScopedTimer {
+    dn_net *net;
+    TimedLaunch *t = nullptr;
+    ScopedTimer(dn_net *n, int cls, bool enabled) : net(n)
+    {
+        if (!enabled || net->timed >= kMaxTimed) return;
+        if ((int)net->pool.size() <= net->timed) {
+            TimedLaunch tl{};
+            if (hipEventCreate(&tl.start) != hipSuccess) return;
+            if (hipEventCreate(&tl.stop) != hipSuccess) {
+                (void)hipEventDestroy(tl.start);
+                return;
+            }
+            net->pool.push_back(tl);
+        }
+        t = &net->pool[net->timed++];
+        t->cls = cls;
+        (void)hipEventRecord(t->start, net->stream);
+    }
+    ~ScopedTimer()
+    {
+        if (t) (void)hipEventRecord(t->stop, net->stream);
+    }
+};
+
+// Forward pass of one batch; leaves A_1..A_L in the arena.  The softmax layer's
+// row normalisation is left to the caller (it is fused with the loss in training).
+dn_status run_forward(dn_net *net, const float *X, int B, bool timing)
+{
+    for (int l = 1; l <= net->L; ++l) {
+        GemmArgs g{};
+        g.A = (l == 1) ? X : net->A(l - 1);
+        g.lda = net->n[l - 1];
+        g.B = net->W(l);
+        g.ldb = net->n[l - 1];
+        g.M = B; g.N = net->n[l]; g.K = net->n[l - 1];
+        g.C = net->A(l); g.ldc = net->n[l];
+        g.bias = net->b(l);
+        g.act = net->act[l];
+        ScopedTimer st(net, DN_K_FORWARD, timing);
+        DN_HIP(launch_gemm(GEMM_FWD, g, net->gemm_variant, net->stream));
+    }
+    return DN_OK;
+}
+
+// Back propagation of one batch from Delta_L.  mode GRAD_STORE leaves gradients in
+// the gradient region; the other modes update parameters in place, layer by layer,
+// each delta being propagated through W_l before W_l is touched.
+dn_status run_backward(dn_net *net, const float *X, int B, int mode, float lr, float mu, bool timing)
+{
+    const float scale = (mode == GRAD_STORE) ? 1.0f / (float)B : lr / (float)B;
+    for (int l = net->L; l >= 1; --l) {
+        if (l > 1) {
+            GemmArgs g{};
+            g.A = net->D(l); g.lda = net->n[l];
+            g.B = net->W(l); g.ldb = net->n[l - 1];
+            g.M = B; g.N = net->n[l - 1]; g.K = net->n[l];
+            g.C = net->D(l - 1); g.ldc = net->n[l - 1];
+            g.aux = net->A(l - 1);
+            g.act = net->act[l - 1];
+            ScopedTimer st(net, DN_K_DELTA, timing);
+            DN_HIP(launch_gemm(GEMM_DELTA, g, net->gemm_variant, net->stream));
+        }
+        {
+            ScopedTimer st(net, DN_K_BIAS, timing);
+            DN_HIP(launch_bias(net->D(l), B, net->n[l], net->Gb(l), net->b(l), net->Vb(l), scale, mu, mode,
+                               net->stream));
+        }
+        {
+            GemmArgs g{};
+            g.A = net->D(l); g.lda = net->n[l];
+            g.B = (l == 1) ? X : net->A(l - 1); g.ldb = net->n[l - 1];
+            g.M = net->n[l]; g.N = net->n[l - 1]; g.K = B;
+            g.C = (mode == GRAD_STORE) ? net->GW(l) : net->W(l);
+            g.ldc = net->n[l - 1];
+            g.V = net->VW(l);
+            g.scale = scale; g.mu = mu; g.mode = mode;
+            ScopedTimer st(net, DN_K_GRAD_UPDATE, timing);
+            DN_HIP(launch_gemm(GEMM_GRAD, g, net->gemm_variant, net->stream));
+        }
+    }
+    return DN_OK;
+}
+
+void collect_times(dn_net *net)
+{
+    for (int c = 0; c < DN_K_CLASSES; ++c) {
+        net->cls_ms[c] = 0.0;
+        net->cls_launches[c] = 0;
+    }
+    for (int i = 0; i < net->timed; ++i) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, net->pool[i].start, net->pool[i].stop) == hipSuccess) {
+            net->cls_ms[net->pool[i].cls] += ms;
+            net->cls_launches[net->pool[i].cls] += 1;
+        }
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *dn_status_string(dn_status s)
+{
+    switch (s) {
+    case DN_OK: return "ok";
+    case DN_ERR_INVALID_ARG: return "invalid argument";
+    case DN_ERR_SHAPE: return "shape mismatch";
+    case DN_ERR_UNSUPPORTED: return "unsupported activation/loss combination";
+    case DN_ERR_OOM: return "out of host memory";
+    case DN_ERR_DEVICE: return "device error";
+    default: return "unknown status";
+    }
+}
+
+size_t dn_net_arena_bytes(const int32_t *widths, int32_t n_widths, int32_t max_batch)
+{
+    Layout lo;
+    return compute_layout(widths, n_widths, max_batch, lo) ? lo.total : 0;
+}
+
+dn_status dn_net_create(const int32_t *widths, int32_t n_widths, const dn_act *acts, dn_loss loss,
+                        int32_t max_batch, void *arena_dev, size_t arena_bytes, void *hip_stream,
+                        dn_net **out)
+{
+    if (!out) return DN_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (!widths || !acts || !arena_dev) return DN_ERR_INVALID_ARG;
+    if (n_widths < 2 || max_batch <= 0) return DN_ERR_SHAPE;
+    for (int i = 0; i < n_widths; ++i)
+        if (widths[i] <= 0) return DN_ERR_SHAPE;
+    if (loss != DN_LOSS_MSE && loss != DN_LOSS_CROSS_ENTROPY) return DN_ERR_INVALID_ARG;
+    const int L = n_widths - 1;
+    for (int l = 0; l < L; ++l) {
+        if ((int)acts[l] < DN_ACT_LINEAR || (int)acts[l] > DN_ACT_SOFTMAX) return DN_ERR_INVALID_ARG;
+        if (acts[l] == DN_ACT_SOFTMAX && l != L - 1) return DN_ERR_UNSUPPORTED;
+    }
+    const bool softmax_last = acts[L - 1] == DN_ACT_SOFTMAX;
+    if (softmax_last != (loss == DN_LOSS_CROSS_ENTROPY)) return DN_ERR_UNSUPPORTED;
+    if (reinterpret_cast<uintptr_t>(arena_dev) % kAlign != 0) return DN_ERR_INVALID_ARG;
+    Layout lo;
+    if (!compute_layout(widths, n_widths, max_batch, lo)) return DN_ERR_SHAPE;
+    if (arena_bytes < lo.total) return DN_ERR_SHAPE;
+
+    dn_net *net = new (std::nothrow) dn_net();
+    if (!net) return DN_ERR_OOM;
+    try {
+        net->n.assign(widths, widths + n_widths);
+        net->act.assign(L + 1, 0);
+        for (int l = 1; l <= L; ++l) net->act[l] = (int)acts[l - 1];
+        net->lo = lo;
+    } catch (...) {
+        delete net;
+        return DN_ERR_OOM;
+    }
+    net->L = L;
+    net->loss = (int)loss;
+    net->max_batch = max_batch;
+    net->arena = (char *)arena_dev;
+    net->stream = (hipStream_t)hip_stream;
+    // parameters, velocities and gradients start at zero
+    if (hipMemsetAsync(net->arena, 0, 3 * lo.region, net->stream) != hipSuccess ||
+        hipMemsetAsync(net->arena + lo.off_scalars, 0, kAlign, net->stream) != hipSuccess ||
+        hipEventCreate(&net->ev_epoch0) != hipSuccess || hipEventCreate(&net->ev_epoch1) != hipSuccess ||
+        hipStreamSynchronize(net->stream) != hipSuccess) {
+        if (net->ev_epoch0) (void)hipEventDestroy(net->ev_epoch0);
+        if (net->ev_epoch1) (void)hipEventDestroy(net->ev_epoch1);
+        delete net;
+        return DN_ERR_DEVICE;
+    }
+    *out = net;
+    return DN_OK;
+}
+
+dn_status dn_net_destroy(dn_net *net)
+{
+    if (!net) return DN_ERR_INVALID_ARG;
+    dn_status st = DN_OK;
+    if (hipStreamSynchronize(net->stream) != hipSuccess) st = DN_ERR_DEVICE;
+    for (auto &t : net->pool) {
+        (void)hipEventDestroy(t.start);
+        (void)hipEventDestroy(t.stop);
+    }
+    (void)hipEventDestroy(net->ev_epoch0);
+    (void)hipEventDestroy(net->ev_epoch1);
+    delete net;
+    return st;
+}
+
+dn_status dn_set_params(dn_net *net, int32_t layer, const float *W_host, const float *b_host)
+{
+    if (!net || layer < 1 || layer > net->L) return DN_ERR_INVALID_ARG;
+    const size_t nw = (size_t)net->n[layer] * net->n[layer - 1], nb = (size_t)net->n[layer];
+    if (W_host) {
+        DN_HIP(hipMemcpyAsync(net->W(layer), W_host, nw * sizeof(float), hipMemcpyHostToDevice, net->stream));
+        DN_HIP(hipMemsetAsync(net->VW(layer), 0, nw * sizeof(float), net->stream));
+    }
+    if (b_host) {
+        DN_HIP(hipMemcpyAsync(net->b(layer), b_host, nb * sizeof(float), hipMemcpyHostToDevice, net->stream));
+        DN_HIP(hipMemsetAsync(net->Vb(layer), 0, nb * sizeof(float), net->stream));
+    }
+    DN_HIP(hipStreamSynchronize(net->stream));
+    return DN_OK;
+}
+
+static dn_status read_pair(dn_net *net, int32_t layer, const float *Wd, const float *bd, float *W_host,
+                           float *b_host)
+{
+    const size_t nw = (size_t)net->n[layer] * net->n[layer - 1], nb = (size_t)net->n[layer];
+    if (W_host) DN_HIP(hipMemcpyAsync(W_host, Wd, nw * sizeof(float), hipMemcpyDeviceToHost, net->stream));
+    if (b_host) DN_HIP(hipMemcpyAsync(b_host, bd, nb * sizeof(float), hipMemcpyDeviceToHost, net->stream));
+    DN_HIP(hipStreamSynchronize(net->stream));
+    return DN_OK;
+}
+
+dn_status dn_get_params(dn_net *net, int32_t layer, float *W_host, float *b_host)
+{
+    if (!net || layer < 1 || layer > net->L) return DN_ERR_INVALID_ARG;
+    return read_pair(net, layer, net->W(layer), net->b(layer), W_host, b_host);
+}
+
+dn_status dn_get_grads(dn_net *net, int32_t layer, float *G_host, float *g_host)
+{
+    if (!net || layer < 1 || layer > net->L) return DN_ERR_INVALID_ARG;
+    if (!net->have_bwd) return DN_ERR_INVALID_ARG;
+    return read_pair(net, layer, net->GW(layer), net->Gb(layer), G_host, g_host);
+}
+
+dn_status dn_forward(dn_net *net, const float *X_dev, int32_t batch, float *out_dev)
+{
+    if (!net || !X_dev) return DN_ERR_INVALID_ARG;
+    if (batch < 1 || batch > net->max_batch) return DN_ERR_SHAPE;
+    net->have_fwd = false;
+    net->have_bwd = false;
+    dn_status st = run_forward(net, X_dev, batch, false);
+    if (st != DN_OK) return st;
+    const int L = net->L;
+    if (net->loss == DN_LOSS_CROSS_ENTROPY)
+        DN_HIP(launch_output_delta(net->A(L), net->D(L), nullptr, net->loss_rows(), batch, net->n[L],
+                                   net->act[L], net->loss, OUT_SOFTMAX_ONLY, net->stream));
+    if (out_dev) DN_HIP(launch_copy(out_dev, net->A(L), (size_t)batch * net->n[L], net->stream));
+    net->X = X_dev;
+    net->fwd_batch = batch;
+    net->have_fwd = true;
+    return DN_OK;
+}
+
+dn_status dn_backward(dn_net *net, const int32_t *labels_dev, int32_t batch, float *loss_dev)
+{
+    if (!net || !labels_dev) return DN_ERR_INVALID_ARG;
+    if (!net->have_fwd) return DN_ERR_INVALID_ARG;
+    if (batch != net->fwd_batch) return DN_ERR_SHAPE;
+    const int L = net->L;
+    DN_HIP(launch_output_delta(net->A(L), net->D(L), labels_dev, net->loss_rows(), batch, net->n[L],
+                               net->act[L], net->loss, OUT_FROM_P, net->stream));
+    if (loss_dev) DN_HIP(launch_loss_reduce(net->loss_rows(), batch, loss_dev, nullptr, net->stream));
+    dn_status st = run_backward(net, net->X, batch, GRAD_STORE, 0.f, 0.f, false);
+    if (st != DN_OK) return st;
+    net->have_bwd = true;
+    return DN_OK;
+}
+
+dn_status dn_update(dn_net *net, float lr, float momentum)
+{
+    if (!net || !rate_ok(lr, momentum)) return DN_ERR_INVALID_ARG;
+    if (!net->have_bwd) return DN_ERR_INVALID_ARG;
+    // parameters, velocities and gradients are three regions of one shape (padding holds zeros)
+    DN_HIP(launch_update((float *)(net->arena + net->lo.off_params), (float *)(net->arena + net->lo.off_vel),
+                         (const float *)(net->arena + net->lo.off_grads), net->lo.region / sizeof(float), lr,
+                         momentum, net->stream));
+    return DN_OK;
+}
+
+dn_status dn_train_epoch(dn_net *net, const float *X_dev, const int32_t *labels_dev, int64_t n_samples,
+                         int32_t batch, float lr, float momentum, float *mean_loss_host)
+{
+    if (!net || !X_dev || !labels_dev || n_samples <= 0 || !rate_ok(lr, momentum)) return DN_ERR_INVALID_ARG;
+    if (batch < 1 || batch > net->max_batch) return DN_ERR_SHAPE;
+    net->have_fwd = net->have_bwd = false;  // activations / gradients of the split API are overwritten
+    const bool timing = net->time_kernels != 0;
+    net->timed = 0;
+    const int L = net->L;
+    DN_HIP(hipMemsetAsync(net->epoch_acc(), 0, sizeof(double), net->stream));
+    DN_HIP(hipEventRecord(net->ev_epoch0, net->stream));
+    for (int64_t s0 = 0; s0 < n_samples; s0 += batch) {
+        const int B = (int)((n_samples - s0) < batch ? (n_samples - s0) : batch);
+        const float *Xb = X_dev + (size_t)s0 * net->n[0];
+        const bool last = s0 + batch >= n_samples;
+        const int mode = (momentum != 0.f) ? GRAD_MOMENTUM : (last ? GRAD_SGD_KEEPV : GRAD_SGD);
+        dn_status st = run_forward(net, Xb, B, timing);
+        if (st != DN_OK) return st;
+        {
+            ScopedTimer t(net, DN_K_OUTPUT, timing);
+            DN_HIP(launch_output_delta(net->A(L), net->D(L), labels_dev + s0, net->loss_rows(), B, net->n[L],
+                                       net->act[L], net->loss, OUT_FUSED, net->stream));
+            DN_HIP(launch_loss_reduce(net->loss_rows(), B, nullptr, net->epoch_acc(), net->stream));
+        }
+        st = run_backward(net, Xb, B, mode, lr, momentum, timing);
+        if (st != DN_OK) return st;
+    }
+    DN_HIP(hipEventRecord(net->ev_epoch1, net->stream));
+    double acc = 0.0;
+    DN_HIP(hipMemcpyAsync(&acc, net->epoch_acc(), sizeof(double), hipMemcpyDeviceToHost, net->stream));
+    DN_HIP(hipStreamSynchronize(net->stream));
+    DN_HIP(hipEventElapsedTime(&net->epoch_ms, net->ev_epoch0, net->ev_epoch1));
+    collect_times(net);
+    if (mean_loss_host) *mean_loss_host = (float)(acc / (double)n_samples);
+    return DN_OK;
+}
+
+dn_status dn_last_epoch_ms(dn_net *net, float *epoch_ms)
+{
+    if (!net || !epoch_ms) return DN_ERR_INVALID_ARG;
+    *epoch_ms = net->epoch_ms;
+    return DN_OK;
+}
+
+dn_status dn_kernel_time(dn_net *net, int32_t kernel_class, float *ms_total, int64_t *launches)
+{
+    if (!net || kernel_class < 0 || kernel_class >= DN_K_CLASSES) return DN_ERR_INVALID_ARG;
+    if (ms_total) *ms_total = (float)net->cls_ms[kernel_class];
+    if (launches) *launches = net->cls_launches[kernel_class];
+    return DN_OK;
+}
+
+dn_status dn_set_option(dn_net *net, const char *name, int64_t value)
+{
+    if (!net || !name) return DN_ERR_INVALID_ARG;
+    if (!strcmp(name, "time_kernels")) {
+        if (value != 0 && value != 1) return DN_ERR_INVALID_ARG;
+        net->time_kernels = (int)value;
+    } else if (!strcmp(name, "gemm_variant")) {
+        if (value < -1 || value >= gemm_variant_count()) return DN_ERR_INVALID_ARG;
+        net->gemm_variant = (int)value;
+    } else if (!strcmp(name, "online_mode")) {
+        if (value < 0 || value > 2) return DN_ERR_INVALID_ARG;
+        net->online_mode = (int)value;
+    } else {
+        return DN_ERR_INVALID_ARG;
+    }
+    return DN_OK;
+}
+
+}  // extern "C"

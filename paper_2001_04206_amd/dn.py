@@ -1,0 +1,211 @@
+"""ctypes binding of libdn: same names as include/dn.h, argument marshalling only.
+
+PyTorch-ROCm is used for device memory (the arena and the data tensors) and for
+the HIP stream handle; no torch operator takes part in a training step.  The
+library must be built (``python -m paper_2001_04206_amd.build``); a missing
+library is an error, there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdn.so")
+
+DN_OK, DN_ERR_INVALID_ARG, DN_ERR_SHAPE, DN_ERR_UNSUPPORTED, DN_ERR_OOM, DN_ERR_DEVICE = range(6)
+DN_ACT_LINEAR, DN_ACT_SIGMOID, DN_ACT_TANH, DN_ACT_RELU, DN_ACT_SOFTMAX = range(5)
+DN_LOSS_MSE, DN_LOSS_CROSS_ENTROPY = 0, 1
+DN_K_FORWARD, DN_K_DELTA, DN_K_GRAD_UPDATE, DN_K_OUTPUT, DN_K_BIAS, DN_K_ONLINE = range(6)
+KERNEL_CLASS_NAMES = ["forward", "delta", "grad_update", "output", "bias", "online"]
+
+EXPORTS = [
+    "dn_status_string", "dn_net_arena_bytes", "dn_net_create", "dn_net_destroy", "dn_set_params",
+    "dn_get_params", "dn_get_grads", "dn_forward", "dn_backward", "dn_update", "dn_train_epoch",
+    "dn_last_epoch_ms", "dn_kernel_time", "dn_set_option",
+]
+
+_lib = None
+
+
+class DnError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s failed: %s (status %d)" % (where, status_string(status), status))
+
+
+def lib():
+    """Load libdn.so (raises if it has not been built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libdn.so is missing: build it with `python -m paper_2001_04206_amd.build`")
+        # PyTorch ships its own HIP runtime (same soname as the system one).  Import it
+        # first so that libdn binds to that copy: device pointers and streams handed
+        # over from torch are only meaningful inside the runtime that created them.
+        import torch  # noqa: F401
+        l = C.CDLL(LIB_PATH)
+        vp, i32, i64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float
+        l.dn_status_string.restype = C.c_char_p
+        l.dn_status_string.argtypes = [C.c_int]
+        l.dn_net_arena_bytes.restype = C.c_size_t
+        l.dn_net_arena_bytes.argtypes = [vp, i32, i32]
+        l.dn_net_create.argtypes = [vp, i32, vp, C.c_int, i32, vp, C.c_size_t, vp, C.POINTER(vp)]
+        l.dn_net_destroy.argtypes = [vp]
+        for f in (l.dn_set_params, l.dn_get_params, l.dn_get_grads):
+            f.argtypes = [vp, i32, vp, vp]
+        l.dn_forward.argtypes = [vp, vp, i32, vp]
+        l.dn_backward.argtypes = [vp, vp, i32, vp]
+        l.dn_update.argtypes = [vp, f32, f32]
+        l.dn_train_epoch.argtypes = [vp, vp, vp, i64, i32, f32, f32, C.POINTER(f32)]
+        l.dn_last_epoch_ms.argtypes = [vp, C.POINTER(f32)]
+        l.dn_kernel_time.argtypes = [vp, i32, C.POINTER(f32), C.POINTER(i64)]
+        l.dn_set_option.argtypes = [vp, C.c_char_p, i64]
+        for name in EXPORTS[2:]:
+            getattr(l, name).restype = C.c_int
+        _lib = l
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().dn_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str):
+    if status != DN_OK:
+        raise DnError(status, where)
+
+
+def _i32(a: Sequence[int]):
+    arr = np.ascontiguousarray(a, dtype=np.int32)
+    return arr, arr.ctypes.data_as(C.c_void_p)
+
+
+def dn_net_arena_bytes(widths: Sequence[int], max_batch: int) -> int:
+    arr, p = _i32(widths)
+    return int(lib().dn_net_arena_bytes(p, len(arr), int(max_batch)))
+
+
+def _dev_ptr(t, dtype, what: str):
+    import torch
+    if not isinstance(t, torch.Tensor) or not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise TypeError("%s must be a contiguous device tensor of dtype %s" % (what, dtype))
+    return C.c_void_p(t.data_ptr())
+
+
+class Net:
+    """One network on the current device.  Owns the arena tensor (torch
+    allocation) and the library handle; method names follow include/dn.h."""
+
+    def __init__(self, widths: Sequence[int], acts: Sequence[int], loss: int, max_batch: int,
+                 device: str = "cuda:0"):
+        import torch
+        self._torch = torch
+        self.widths = [int(w) for w in widths]
+        self.L = len(self.widths) - 1
+        self.max_batch = int(max_batch)
+        self.device = torch.device(device)
+        nbytes = dn_net_arena_bytes(self.widths, self.max_batch)
+        if nbytes == 0:
+            raise DnError(DN_ERR_SHAPE, "dn_net_arena_bytes")
+        self.arena = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        self.stream = torch.cuda.current_stream(self.device)
+        w_arr, w_p = _i32(self.widths)
+        a_arr, a_p = _i32(acts)
+        handle = C.c_void_p()
+        with torch.cuda.device(self.device):
+            st = lib().dn_net_create(w_p, len(w_arr), a_p, int(loss), self.max_batch,
+                                     C.c_void_p(self.arena.data_ptr()), nbytes,
+                                     C.c_void_p(self.stream.cuda_stream), C.byref(handle))
+        _check(st, "dn_net_create")
+        self._h = handle
+
+    def close(self):
+        if getattr(self, "_h", None):
+            lib().dn_net_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # -- parameters ------------------------------------------------------------
+    def dn_set_params(self, layer: int, W: Optional[np.ndarray], b: Optional[np.ndarray]):
+        Wc = None if W is None else np.ascontiguousarray(W, dtype=np.float32)
+        bc = None if b is None else np.ascontiguousarray(b, dtype=np.float32)
+        if Wc is not None and Wc.shape != (self.widths[layer], self.widths[layer - 1]):
+            raise DnError(DN_ERR_SHAPE, "dn_set_params")
+        if bc is not None and bc.shape != (self.widths[layer],):
+            raise DnError(DN_ERR_SHAPE, "dn_set_params")
+        _check(lib().dn_set_params(self._h, layer,
+                                   None if Wc is None else Wc.ctypes.data_as(C.c_void_p),
+                                   None if bc is None else bc.ctypes.data_as(C.c_void_p)), "dn_set_params")
+
+    def _get(self, fn, name, layer) -> Tuple[np.ndarray, np.ndarray]:
+        W = np.empty((self.widths[layer], self.widths[layer - 1]), dtype=np.float32)
+        b = np.empty(self.widths[layer], dtype=np.float32)
+        _check(fn(self._h, layer, W.ctypes.data_as(C.c_void_p), b.ctypes.data_as(C.c_void_p)), name)
+        return W, b
+
+    def dn_get_params(self, layer: int):
+        return self._get(lib().dn_get_params, "dn_get_params", layer)
+
+    def dn_get_grads(self, layer: int):
+        return self._get(lib().dn_get_grads, "dn_get_grads", layer)
+
+    def set_all(self, W: Sequence[np.ndarray], b: Sequence[np.ndarray]):
+        for l in range(1, self.L + 1):
+            self.dn_set_params(l, W[l - 1], b[l - 1])
+
+    def get_all(self) -> Tuple[List[np.ndarray], List[np.ndarray]]:
+        pairs = [self.dn_get_params(l) for l in range(1, self.L + 1)]
+        return [p[0] for p in pairs], [p[1] for p in pairs]
+
+    def get_all_grads(self):
+        pairs = [self.dn_get_grads(l) for l in range(1, self.L + 1)]
+        return [p[0] for p in pairs], [p[1] for p in pairs]
+
+    # -- the steps ---------------------------------------------------------------
+    def dn_forward(self, X, out=None):
+        t = self._torch
+        batch = int(X.shape[0])
+        _check(lib().dn_forward(self._h, _dev_ptr(X, t.float32, "X"), batch,
+                                None if out is None else _dev_ptr(out, t.float32, "out")), "dn_forward")
+
+    def dn_backward(self, labels, loss_out=None):
+        t = self._torch
+        _check(lib().dn_backward(self._h, _dev_ptr(labels, t.int32, "labels"), int(labels.shape[0]),
+                                 None if loss_out is None else _dev_ptr(loss_out, t.float32, "loss")),
+               "dn_backward")
+
+    def dn_update(self, lr: float, momentum: float):
+        _check(lib().dn_update(self._h, float(lr), float(momentum)), "dn_update")
+
+    def dn_train_epoch(self, X, labels, batch: int, lr: float, momentum: float,
+                       n_samples: Optional[int] = None) -> float:
+        t = self._torch
+        n = int(X.shape[0]) if n_samples is None else int(n_samples)
+        loss = C.c_float(0.0)
+        _check(lib().dn_train_epoch(self._h, _dev_ptr(X, t.float32, "X"), _dev_ptr(labels, t.int32, "labels"),
+                                    n, int(batch), float(lr), float(momentum), C.byref(loss)),
+               "dn_train_epoch")
+        return float(loss.value)
+
+    # -- measurement ---------------------------------------------------------------
+    def dn_last_epoch_ms(self) -> float:
+        ms = C.c_float(0.0)
+        _check(lib().dn_last_epoch_ms(self._h, C.byref(ms)), "dn_last_epoch_ms")
+        return float(ms.value)
+
+    def dn_kernel_time(self, kernel_class: int) -> Tuple[float, int]:
+        ms, n = C.c_float(0.0), C.c_int64(0)
+        _check(lib().dn_kernel_time(self._h, kernel_class, C.byref(ms), C.byref(n)), "dn_kernel_time")
+        return float(ms.value), int(n.value)
+
+    def dn_set_option(self, name: str, value: int):
+        _check(lib().dn_set_option(self._h, name.encode(), int(value)), "dn_set_option")

@@ -1,0 +1,29 @@
+"""Helpers shared by the GPU parity tests: error metric and case announcement."""
+import sys
+
+import numpy as np
+
+
+def announce(msg: str):
+    """Name the case on the real stderr (past pytest's capture) before a GPU step."""
+    sys.__stderr__.write("[gpu-case] " + msg + "\n")
+    sys.__stderr__.flush()
+
+
+def rel_err(got: np.ndarray, ref: np.ndarray):
+    """(relative L2 error, max abs error / max abs ref) of one tensor."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    tiny = 1e-30
+    l2 = np.linalg.norm(got - ref) / max(np.linalg.norm(ref), tiny)
+    mx = np.abs(got - ref).max() / max(np.abs(ref).max(), tiny) if ref.size else 0.0
+    return float(l2), float(mx)
+
+
+def assert_close(got, ref, tol, what):
+    assert np.all(np.isfinite(got)), what + ": non-finite values"
+    if not np.any(ref):            # an all-zero reference (e.g. zero-initialised bias gradient) must match exactly-ish
+        assert np.abs(got).max() <= 1e-12, what + ": expected zeros"
+        return
+    l2, mx = rel_err(got, ref)
+    assert l2 <= tol and mx <= tol, "%s: rel L2 %.3e, rel max %.3e > %.1e" % (what, l2, mx, tol)

@@ -1,0 +1,101 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every symbol include/dn.h declares, sizes arenas sanely and rejects bad
+arguments with status codes before touching the device."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2001_04206_amd import dn
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(dn.LIB_PATH):
+        from paper_2001_04206_amd import build
+        build.build()
+    return dn.lib()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "dn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dn_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(lib):
+    names = declared_functions()
+    assert set(names) == set(dn.EXPORTS)
+    for name in names:
+        assert getattr(lib, name) is not None
+
+
+def test_status_strings(lib):
+    seen = {dn.status_string(s) for s in range(6)}
+    assert len(seen) == 6 and dn.status_string(99) == "unknown status"
+
+
+def test_arena_bytes(lib):
+    assert dn.dn_net_arena_bytes([4, 16, 3], 1) > 3 * 4 * (4 * 16 + 16 + 16 * 3 + 3)
+    small, big = dn.dn_net_arena_bytes([784, 128, 10], 1), dn.dn_net_arena_bytes([784, 128, 10], 128)
+    assert big > small and small % 256 == 0 and big % 256 == 0
+    # activations and deltas of every layer scale with the batch
+    assert big - small >= 127 * 2 * 4 * 128
+    assert dn.dn_net_arena_bytes([4], 1) == 0
+    assert dn.dn_net_arena_bytes([4, 0, 3], 1) == 0
+    assert dn.dn_net_arena_bytes([4, -1], 1) == 0
+    assert dn.dn_net_arena_bytes([4, 3], 0) == 0
+    assert lib.dn_net_arena_bytes(None, 3, 1) == 0
+    assert dn.dn_net_arena_bytes([2 ** 31 - 1, 2 ** 31 - 1], 1) == 0      # absurd size is refused
+
+
+def _create(lib, widths, acts, loss, max_batch=4, arena=0x10000, nbytes=1 << 40, out=True):
+    w = np.asarray(widths, dtype=np.int32)
+    a = np.asarray(acts, dtype=np.int32)
+    h = C.c_void_p()
+    st = lib.dn_net_create(w.ctypes.data_as(C.c_void_p), len(w), a.ctypes.data_as(C.c_void_p), loss,
+                           max_batch, C.c_void_p(arena), nbytes, None, C.byref(h) if out else None)
+    return st, h
+
+
+def test_create_rejects_bad_arguments_before_touching_the_device(lib):
+    S, T, R, SM = dn.DN_ACT_SIGMOID, dn.DN_ACT_TANH, dn.DN_ACT_RELU, dn.DN_ACT_SOFTMAX
+    assert _create(lib, [4, 3], [S], dn.DN_LOSS_MSE, out=False)[0] == dn.DN_ERR_INVALID_ARG
+    assert _create(lib, [4, 3], [S], dn.DN_LOSS_MSE, arena=0)[0] == dn.DN_ERR_INVALID_ARG
+    assert _create(lib, [4, 3], [S], dn.DN_LOSS_MSE, arena=0x10010)[0] == dn.DN_ERR_INVALID_ARG   # misaligned
+    assert _create(lib, [4, 3], [S], 7)[0] == dn.DN_ERR_INVALID_ARG
+    assert _create(lib, [4, 3], [9], dn.DN_LOSS_MSE)[0] == dn.DN_ERR_INVALID_ARG
+    assert _create(lib, [4], [], dn.DN_LOSS_MSE)[0] == dn.DN_ERR_SHAPE
+    assert _create(lib, [4, 0, 3], [S, S], dn.DN_LOSS_MSE)[0] == dn.DN_ERR_SHAPE
+    assert _create(lib, [4, 3], [S], dn.DN_LOSS_MSE, max_batch=0)[0] == dn.DN_ERR_SHAPE
+    assert _create(lib, [4, 3], [S], dn.DN_LOSS_MSE, nbytes=16)[0] == dn.DN_ERR_SHAPE            # arena too small
+    assert _create(lib, [4, 5, 3], [SM, S], dn.DN_LOSS_MSE)[0] == dn.DN_ERR_UNSUPPORTED          # softmax not last
+    assert _create(lib, [4, 5, 3], [T, SM], dn.DN_LOSS_MSE)[0] == dn.DN_ERR_UNSUPPORTED          # softmax w/o CE
+    assert _create(lib, [4, 5, 3], [T, R], dn.DN_LOSS_CROSS_ENTROPY)[0] == dn.DN_ERR_UNSUPPORTED  # CE w/o softmax
+    st, h = _create(lib, [4, 3], [S], dn.DN_LOSS_MSE, out=True, arena=0)
+    assert h.value is None
+
+
+def test_null_handles_are_rejected(lib):
+    f = C.c_float(0)
+    assert lib.dn_net_destroy(None) == dn.DN_ERR_INVALID_ARG
+    assert lib.dn_forward(None, None, 1, None) == dn.DN_ERR_INVALID_ARG
+    assert lib.dn_backward(None, None, 1, None) == dn.DN_ERR_INVALID_ARG
+    assert lib.dn_update(None, 0.1, 0.0) == dn.DN_ERR_INVALID_ARG
+    assert lib.dn_train_epoch(None, None, None, 1, 1, 0.1, 0.0, C.byref(f)) == dn.DN_ERR_INVALID_ARG
+    assert lib.dn_set_params(None, 1, None, None) == dn.DN_ERR_INVALID_ARG
+    assert lib.dn_get_params(None, 1, None, None) == dn.DN_ERR_INVALID_ARG
+    assert lib.dn_get_grads(None, 1, None, None) == dn.DN_ERR_INVALID_ARG
+    assert lib.dn_last_epoch_ms(None, C.byref(f)) == dn.DN_ERR_INVALID_ARG
+    assert lib.dn_kernel_time(None, 0, C.byref(f), None) == dn.DN_ERR_INVALID_ARG
+    assert lib.dn_set_option(None, b"time_kernels", 1) == dn.DN_ERR_INVALID_ARG
+
+
+def test_binding_refuses_host_tensors(lib):
+    import torch
+    with pytest.raises(TypeError):
+        dn._dev_ptr(torch.zeros(3), torch.float32, "X")

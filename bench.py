@@ -1,0 +1,182 @@
+#!/usr/bin/env python3
+"""Throughput of dense-network training (forward + back propagation + update)
+on one MI355X, with the roofline fraction of the dominant kernel and the CPU
+checker timed beside it.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+A step is one training step (one batch) of the chosen workload; inputs and
+parameters are resident in device memory before the timed region starts.
+Prints one JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0        # MI355X HBM3E
+PEAK_MFMA_F32_TFLOPS = 157.3  # dense fp32 matrix rate: 256 CUs x 256 flop/clk x 2.4 GHz
+
+
+def workloads():
+    from paper_2001_04206_amd import synth
+    w = {
+        "cfg1_4_16_3_b1": (synth.iris_like, "latency"),
+        "cfg2_784_128_10_b1": (synth.digits_like_online, "hbm"),
+        "cfg3_784_128_10_b128": (synth.digits_like_minibatch, "mfma"),
+        "cfg4_4096x3_1000_b256": (synth.wide_relu, "mfma"),
+        "paper_340_100000_10_b1": (lambda: synth.paper_shape(n_samples=512), "hbm"),
+    }
+    for b in (1, 8, 32, 128, 512, 2048):
+        w["cfg5_1024x4_10_b%d" % b] = ((lambda b=b: synth.tanh_sweep(b)), "hbm" if b <= 32 else "mfma")
+    return w
+
+
+def step_costs(widths, batch, momentum):
+    """Algorithmic flops and bytes of one training step (fp32)."""
+    pw = sum(widths[l + 1] * widths[l] for l in range(len(widths) - 1))
+    p = pw + sum(widths[1:])
+    flops = {
+        "forward": 2.0 * batch * pw,
+        "delta": 2.0 * batch * (pw - widths[1] * widths[0]),
+        "grad_update": 2.0 * batch * pw,
+    }
+    # weights: forward read + backward read + write (+ velocity read + write);
+    # activations / deltas: written once, read by the next product and by the gradient
+    per_param = 20.0 if momentum != 0.0 else 12.0
+    act_bytes = 4.0 * batch * (widths[0] + 3 * sum(widths[1:]))
+    return flops, per_param * p + act_bytes
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=0, help="timed training steps (0: one pass over the data)")
+    ap.add_argument("--warmup", type=int, default=-1, help="untimed steps (-1: workload default)")
+    ap.add_argument("--workload", default="cfg4_4096x3_1000_b256")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-timing", action="store_true",
+                    help="leave per-launch events out of the timed region (roofline becomes null)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+
+    import numpy as np
+    import torch
+    from paper_2001_04206_amd import dn
+
+    table = workloads()
+    if args.workload not in table:
+        sys.exit("unknown workload %r; choose from %s" % (args.workload, ", ".join(sorted(table))))
+    make, bound = table[args.workload]
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    dn.lib()   # fails loudly if libdn.so has not been built
+
+    t0 = time.time()
+    w = make()
+    B, N = w.batch, w.n_samples
+    steps_per_pass = (N + B - 1) // B
+    steps = args.steps if args.steps > 0 else steps_per_pass
+    warmup = args.warmup if args.warmup >= 0 else min(steps_per_pass, 100 if B == 1 else 16)
+    sys.stderr.write("[bench] %s: %d samples, batch %d, %d timed steps, %d warm-up (inputs drawn in %.1fs)\n"
+                     % (w.name, N, B, steps, warmup, time.time() - t0))
+    sys.stderr.flush()
+
+    torch.cuda.set_device(0)
+    th = time.time()
+    X = torch.from_numpy(w.X).to("cuda:0")
+    y = torch.from_numpy(w.labels).to("cuda:0")
+    torch.cuda.synchronize()
+    h2d_s = time.time() - th
+    net = dn.Net(w.widths, w.acts, w.loss, B)
+
+    def run(n_steps):
+        """n_steps training steps, walking the data set in order and wrapping around."""
+        done, dev_ms, loss = 0, 0.0, float("nan")
+        while done < n_steps:
+            k = min(n_steps - done, steps_per_pass)
+            n = min(k * B, N)
+            loss = net.dn_train_epoch(X, y, B, w.lr, w.momentum, n_samples=n)
+            dev_ms += net.dn_last_epoch_ms()
+            done += k
+        return dev_ms, loss
+
+    net.set_all(w.W, w.b)
+    if warmup:
+        run(warmup)
+    net.set_all(w.W, w.b)            # timed region starts from the initial parameters
+    net.dn_set_option("time_kernels", 0 if args.no_kernel_timing else 1)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    dev_ms, loss = run(steps)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t1
+    samples = sum(min(B, N - ((s % steps_per_pass) * B)) for s in range(steps))
+    value = samples / wall
+
+    flops, step_bytes = step_costs(w.widths, B, w.momentum)
+    roofline = None
+    classes = {}
+    if not args.no_kernel_timing:
+        for cid, cname in enumerate(dn.KERNEL_CLASS_NAMES):
+            ms, n = net.dn_kernel_time(cid)
+            if n:
+                classes[cname] = {"ms": ms, "launches": n}
+        # per-launch figures of the last dn_train_epoch call (one pass or the remainder)
+        last_steps = steps % steps_per_pass or min(steps, steps_per_pass)
+        if bound == "mfma":
+            dom = max((c for c in classes if c in flops), key=lambda c: classes[c]["ms"], default=None)
+            if dom:
+                per_launch_ms = classes[dom]["ms"] / classes[dom]["launches"]
+                flop_per_launch = flops[dom] * last_steps / classes[dom]["launches"]
+                ach = flop_per_launch / (per_launch_ms * 1e-3) / 1e12
+                roofline = {"bound": "mfma", "kernel": dom, "achieved": ach, "peak": PEAK_MFMA_F32_TFLOPS,
+                            "unit": "TFLOP/s", "frac": ach / PEAK_MFMA_F32_TFLOPS, "traffic": None,
+                            "avg_launch_us": per_launch_ms * 1e3, "launches": classes[dom]["launches"]}
+        else:
+            total_ms = sum(c["ms"] for c in classes.values())
+            if total_ms > 0:
+                ach = step_bytes * last_steps / (total_ms * 1e-3) / 1e9
+                roofline = {"bound": "hbm", "kernel": "all kernels of a step", "achieved": ach,
+                            "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS, "traffic": None}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import dn_oracle
+        o = dn_oracle.Oracle("o32", w.widths, w.acts, w.loss)
+        o.set_params(w.W, w.b)
+        total_flop_per_sample = sum(flops.values()) / B
+        budget_flop = 1.0e11                      # ~10-30 s of the checker on a host of this class
+        n_cpu = int(max(B, min(N, budget_flop / total_flop_per_sample)) // B * B) or B
+        n_cpu = min(n_cpu, N)
+        tc = time.perf_counter()
+        o.train_epoch(w.X[:n_cpu], w.labels[:n_cpu], B, w.lr, w.momentum)
+        dtc = time.perf_counter() - tc
+        cpu = {"value": n_cpu / dtc, "unit": "samples/s", "cores": dn_oracle.threads(), "kind": "oracle",
+               "sample": "first %d samples (%d steps) of the same workload, %.1f s" % (n_cpu, (n_cpu + B - 1) // B, dtc)}
+
+    out = {
+        "metric": "training samples/sec (fwd+bwd+update)", "value": value, "unit": "samples/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": wall * 1e3 / steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": args.workload, "widths": w.widths, "batch": B, "lr": w.lr,
+                   "momentum": w.momentum, "samples": N},
+        "roofline": roofline, "cpu_baseline": cpu,
+        "device_ms_per_step": dev_ms / steps, "kernel_classes": classes,
+        "total_tflops": sum(flops.values()) * steps / wall / 1e12,
+        "step_algorithmic_bytes": step_bytes, "final_loss": loss, "h2d_seconds_once": h2d_s,
+    }
+    net.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

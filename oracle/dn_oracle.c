@@ -287,3 +287,11 @@ double PFX(train_epoch)(int L, const int32_t *n, const int32_t *acts, int loss, 
     free(A); free(D); free(G);
     return seen ? loss_total / (double)seen : 0.0;
 }
+
+/* Number of threads the loops above will use (1 without OpenMP). */
+#ifdef _OPENMP
+#include <omp.h>
+int PFX(threads)(void) { return omp_get_max_threads(); }
+#else
+int PFX(threads)(void) { return 1; }
+#endif

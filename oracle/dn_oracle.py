@@ -33,6 +33,13 @@ def _load():
     return _lib
 
 
+def threads() -> int:
+    """Threads the checker's loops run on (OpenMP max threads)."""
+    f = _load().o32_threads
+    f.restype = C.c_int
+    return int(f())
+
+
 class Oracle:
     def __init__(self, mode: str, widths: Sequence[int], acts: Sequence[int], loss: int):
         assert mode in ("o32", "o64")

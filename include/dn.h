@@ -180,11 +180,10 @@ dn_status dn_train_epoch(dn_net *net, const float *X_dev, const int32_t *labels_
 typedef enum {
     DN_K_FORWARD = 0,     /* Z = A W^T + b, activation                       */
     DN_K_DELTA = 1,       /* Delta_{l-1} = (Delta_l W_l) * f'                */
-    DN_K_GRAD_UPDATE = 2, /* G = Delta^T A / B fused with the weight update  */
+    DN_K_GRAD_UPDATE = 2, /* G = Delta^T A / B and bias gradient, fused with the update */
     DN_K_OUTPUT = 3,      /* softmax / loss / Delta_L and loss reduction     */
-    DN_K_BIAS = 4,        /* bias gradient and update                        */
-    DN_K_ONLINE = 5,      /* persistent batch-1 epoch kernel                 */
-    DN_K_CLASSES = 6
+    DN_K_ONLINE = 4,      /* persistent batch-1 epoch kernel                 */
+    DN_K_CLASSES = 5
 } dn_kernel_class;
 
 dn_status dn_last_epoch_ms(dn_net *net, float *epoch_ms);

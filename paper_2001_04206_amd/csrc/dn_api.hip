@@ -186,11 +186,6 @@ dn_status run_backward(dn_net *net, const float *X, int B, int mode, float lr, f
             DN_HIP(launch_gemm(GEMM_DELTA, g, net->gemm_variant, net->stream));
         }
         {
-            ScopedTimer st(net, DN_K_BIAS, timing);
-            DN_HIP(launch_bias(net->D(l), B, net->n[l], net->Gb(l), net->b(l), net->Vb(l), scale, mu, mode,
-                               net->stream));
-        }
-        {
             GemmArgs g{};
             g.A = net->D(l); g.lda = net->n[l];
             g.B = (l == 1) ? X : net->A(l - 1); g.ldb = net->n[l - 1];
@@ -198,6 +193,8 @@ dn_status run_backward(dn_net *net, const float *X, int B, int mode, float lr, f
             g.C = (mode == GRAD_STORE) ? net->GW(l) : net->W(l);
             g.ldc = net->n[l - 1];
             g.V = net->VW(l);
+            g.gb = (mode == GRAD_STORE) ? net->Gb(l) : net->b(l);   // bias gradient / update rides along
+            g.vb = net->Vb(l);
             g.scale = scale; g.mu = mu; g.mode = mode;
             ScopedTimer st(net, DN_K_GRAD_UPDATE, timing);
             DN_HIP(launch_gemm(GEMM_GRAD, g, net->gemm_variant, net->stream));

@@ -43,9 +43,10 @@ __device__ __forceinline__ float act_deriv(int act, float a)
     }
 }
 
-template <int BM_, int BN_, int KT_, int WM_, int WN_, int WK_>
+template <int BM_, int BN_, int KT_, int WM_, int WN_, int WK_, int R_>
 struct Tile {
-    static constexpr int BM = BM_, BN = BN_, KT = KT_, WM = WM_, WN = WN_, WK = WK_;
+    static constexpr int BM = BM_, BN = BN_, KT = KT_, WM = WM_, WN = WN_, WK = WK_, R = R_;
+    static_assert(R >= 1 && R <= 4, "register stages");
     static constexpr int NT = 64 * WM * WN * WK;
     static constexpr int WTM = BM / WM, WTN = BN / WN;  // wave tile
     static constexpr int TM = WTM / 32, TN = WTN / 32;  // 32x32 blocks per wave
@@ -63,66 +64,78 @@ struct Lds {
     static constexpr int FLOATS = KC ? ROWS * STRIDE : KT * STRIDE;
 };
 
-// Global -> register load of one operand tile (ROWS x KT), zero-filled outside
-// the matrix.  KC: rows of the matrix are rows of the tile, contiguous in k.
-// MC: rows of the stored matrix are k, contiguous along the tile's rows.
-template <bool KC, int ROWS, int KT, int NT>
+// Operand tiles travel global -> registers -> LDS.  KC: rows of the matrix are
+// rows of the tile, contiguous in k.  MC: rows of the stored matrix are k,
+// contiguous along the tile's own index.
+//
+// load_tile only issues loads: the address is clamped into the matrix so that
+// no branch and no use of the loaded value follows, and all loads of a tile
+// (and of the tiles behind it) stay in flight while the matrix cores work.
+// store_tile, called one or more k-steps later, replaces elements that lie
+// outside the matrix by zero and writes the tile to LDS.
+// VEC (chosen on the host, a separate instantiation so the fast path is straight-line
+// code) means that for both operands the contiguous extent and the leading dimension
+// are multiples of 4 and the base is 16-byte aligned; otherwise elements are loaded singly.
+template <bool KC, int ROWS, int KT>
+__device__ __forceinline__ void tile_coords(int f, int j, int r0, int k0, int &gr, int &gk)
+{
+    if (KC) {
+        gr = r0 + f / (KT / 4);
+        gk = k0 + (f % (KT / 4)) * 4 + j;
+    } else {
+        gk = k0 + f / (ROWS / 4);
+        gr = r0 + (f % (ROWS / 4)) * 4 + j;
+    }
+}
+
+template <bool KC, int ROWS, int KT, int NT, bool VEC>
 __device__ __forceinline__ void load_tile(v4f (&reg)[ROWS * KT / 4 / NT], const float *__restrict__ P,
-                                          int ld, int r0, int k0, int R, int K, bool vec_ok, int tid)
+                                          int ld, int r0, int k0, int R, int K, int tid)
 {
     constexpr int N = ROWS * KT / 4 / NT;
+    if (VEC) {
 #pragma unroll
-    for (int i = 0; i < N; ++i) {
-        const int f = tid + i * NT;
-        v4f v = {0.f, 0.f, 0.f, 0.f};
-        if (KC) {
-            const int r = f / (KT / 4), c = (f % (KT / 4)) * 4;
-            const int gr = r0 + r, gk = k0 + c;
-            if (gr < R) {
-                const float *src = P + (size_t)gr * ld + gk;
-                if (vec_ok && gk + 3 < K) {
-                    v = *reinterpret_cast<const v4f *>(src);
-                } else {
+        for (int i = 0; i < N; ++i) {
+            int gr, gk;
+            tile_coords<KC, ROWS, KT>(tid + i * NT, 0, r0, k0, gr, gk);
+            const bool ok = gr < R && gk < K;
+            const int cr = ok ? gr : 0, ck = ok ? gk : 0;
+            const float *src = KC ? P + (size_t)cr * ld + ck : P + (size_t)ck * ld + cr;
+            reg[i] = *reinterpret_cast<const v4f *>(src);
+        }
+    } else {
 #pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        if (gk + j < K) v[j] = src[j];
-                }
-            }
-        } else {
-            const int k = f / (ROWS / 4), c = (f % (ROWS / 4)) * 4;
-            const int gk = k0 + k, gr = r0 + c;
-            if (gk < K) {
-                const float *src = P + (size_t)gk * ld + gr;
-                if (vec_ok && gr + 3 < R) {
-                    v = *reinterpret_cast<const v4f *>(src);
-                } else {
+        for (int i = 0; i < N; ++i) {
 #pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        if (gr + j < R) v[j] = src[j];
-                }
+            for (int j = 0; j < 4; ++j) {
+                int gr, gk;
+                tile_coords<KC, ROWS, KT>(tid + i * NT, j, r0, k0, gr, gk);
+                const bool ok = gr < R && gk < K;
+                const int cr = ok ? gr : 0, ck = ok ? gk : 0;
+                reg[i][j] = KC ? P[(size_t)cr * ld + ck] : P[(size_t)ck * ld + cr];
             }
         }
-        reg[i] = v;
     }
 }
 
 template <bool KC, int ROWS, int KT, int NT>
-__device__ __forceinline__ void store_tile(float *__restrict__ S, const v4f (&reg)[ROWS * KT / 4 / NT], int tid)
+__device__ __forceinline__ void store_tile(float *__restrict__ S, const v4f (&reg)[ROWS * KT / 4 / NT], int r0,
+                                           int k0, int R, int K, int tid)
 {
     constexpr int N = ROWS * KT / 4 / NT;
     constexpr int STRIDE = Lds<KC, ROWS, KT>::STRIDE;
 #pragma unroll
     for (int i = 0; i < N; ++i) {
         const int f = tid + i * NT;
-        int off;
-        if (KC) {
-            const int r = f / (KT / 4), c = (f % (KT / 4)) * 4;
-            off = r * STRIDE + c;
-        } else {
-            const int k = f / (ROWS / 4), c = (f % (ROWS / 4)) * 4;
-            off = k * STRIDE + c;
+        v4f v = reg[i];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            int gr, gk;
+            tile_coords<KC, ROWS, KT>(f, j, r0, k0, gr, gk);
+            v[j] = (gr < R && gk < K) ? v[j] : 0.f;
         }
-        *reinterpret_cast<v4f *>(S + off) = reg[i];
+        const int off = KC ? (f / (KT / 4)) * STRIDE + (f % (KT / 4)) * 4 : (f / (ROWS / 4)) * STRIDE + (f % (ROWS / 4)) * 4;
+        *reinterpret_cast<v4f *>(S + off) = v;
     }
 }
 
@@ -142,33 +155,149 @@ __device__ __forceinline__ v4f fetch_frag(const float *__restrict__ S, int row, 
     }
 }
 
-template <class T, bool A_KC, bool B_KC, int KIND>
-__global__ __launch_bounds__(T::NT) void gemm_kernel(GemmArgs g, int tiles_m, int tiles_n)
+// Epilogue selector of the kernel template.
+enum Epi : int { EPI_FWD = 0, EPI_DELTA = 1, EPI_GRAD_STORE = 2, EPI_GRAD_SGD = 3, EPI_GRAD_SGD_KEEPV = 4, EPI_GRAD_MOMENTUM = 5 };
+
+// One element of the fused epilogue.  `pre_w` / `pre_v` are the values of the in-place
+// operands (W and velocity for the update modes, A_{l-1} for DELTA) that were fetched
+// before the k loop so their latency hides behind the contraction.
+template <int EPI>
+__device__ __forceinline__ void epilogue_store(const GemmArgs &g, size_t o, float s, float bias, float pre_w, float pre_v)
 {
-    constexpr int BM = T::BM, BN = T::BN, KT = T::KT, NT = T::NT;
+    if (EPI == EPI_FWD) {
+        g.C[o] = act_fn(g.act, s + bias);
+    } else if (EPI == EPI_DELTA) {
+        g.C[o] = s * act_deriv(g.act, pre_w);
+    } else if (EPI == EPI_GRAD_STORE) {
+        g.C[o] = s * g.scale;
+    } else if (EPI == EPI_GRAD_SGD) {
+        g.C[o] = pre_w + (-g.scale * s);
+    } else if (EPI == EPI_GRAD_SGD_KEEPV) {
+        const float dw = -g.scale * s;
+        g.V[o] = dw;
+        g.C[o] = pre_w + dw;
+    } else {
+        const float dw = g.mu * pre_v - g.scale * s;
+        g.V[o] = dw;
+        g.C[o] = pre_w + dw;
+    }
+}
+
+// Interior-tile variants of the tile movers: the tile lies wholly inside the matrix in its
+// own index and in k, so addresses are one wave-uniform base plus a per-lane offset that
+// never changes (no address arithmetic, no clamps, no masks inside the k loop).
+template <bool KC, int ROWS, int KT, int NT>
+__device__ __forceinline__ void lane_offsets(unsigned (&off)[ROWS * KT / 4 / NT], int ld, int tid)
+{
+#pragma unroll
+    for (int i = 0; i < ROWS * KT / 4 / NT; ++i) {
+        const int f = tid + i * NT;
+        off[i] = KC ? (unsigned)(f / (KT / 4)) * (unsigned)ld + (unsigned)(f % (KT / 4)) * 4u
+                    : (unsigned)(f / (ROWS / 4)) * (unsigned)ld + (unsigned)(f % (ROWS / 4)) * 4u;
+    }
+}
+
+template <int N>
+__device__ __forceinline__ void load_tile_fast(v4f (&reg)[N], const float *__restrict__ base, const unsigned (&off)[N])
+{
+#pragma unroll
+    for (int i = 0; i < N; ++i) reg[i] = *reinterpret_cast<const v4f *>(base + off[i]);
+}
+
+template <bool KC, int ROWS, int KT, int NT>
+__device__ __forceinline__ void store_tile_fast(float *__restrict__ S, const v4f (&reg)[ROWS * KT / 4 / NT], int tid)
+{
+    constexpr int STRIDE = Lds<KC, ROWS, KT>::STRIDE;
+#pragma unroll
+    for (int i = 0; i < ROWS * KT / 4 / NT; ++i) {
+        const int f = tid + i * NT;
+        const int off = KC ? (f / (KT / 4)) * STRIDE + (f % (KT / 4)) * 4 : (f / (ROWS / 4)) * STRIDE + (f % (ROWS / 4)) * 4;
+        *reinterpret_cast<v4f *>(S + off) = reg[i];
+    }
+}
+
+// Work of one workgroup on the tile at (m0, n0).  FAST: the tile is interior in m and n and
+// both operands are vector-loadable; only a ragged last k step takes the clamped path.
+template <class T, bool A_KC, bool B_KC, int EPI, bool VEC, bool FAST>
+__device__ __forceinline__ void gemm_tile(const GemmArgs &g, float *smem, const int m0, const int n0)
+{
+    constexpr int BM = T::BM, BN = T::BN, KT = T::KT, NT = T::NT, R = T::R;
     constexpr int TM = T::TM, TN = T::TN, WK = T::WK;
+    constexpr bool IS_GRAD = EPI >= EPI_GRAD_STORE;
+    constexpr bool PRE_W = EPI == EPI_DELTA || EPI >= EPI_GRAD_SGD;
+    constexpr bool PRE_V = EPI == EPI_GRAD_MOMENTUM;
     using LA = Lds<A_KC, BM, KT>;
     using LB = Lds<B_KC, BN, KT>;
     constexpr int STAGE = LA::FLOATS + LB::FLOATS;
-    constexpr int RED = (WK > 1) ? (WK / 2) * BM * BN : 0;
-    constexpr int SMEM = (2 * STAGE > RED) ? 2 * STAGE : RED;
-    __shared__ __attribute__((aligned(16))) float smem[SMEM];
-
-    // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous
-    // run of tiles (m fastest) so tiles sharing a B panel meet in one L2.
-    const int nt = tiles_m * tiles_n;
-    const int per_xcd = (nt + 7) / 8;
-    const int v = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
-    if (v >= nt) return;
-    const int m0 = (v % tiles_m) * BM, n0 = (v / tiles_m) * BN;
+    static_assert(!IS_GRAD || NT >= BM, "bias reduction needs one thread per tile row");
+    static_assert(VEC || !FAST, "the interior path needs vector loads");
+    constexpr int NA = BM * KT / 4 / NT, NB = BN * KT / 4 / NT;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int idx = lane & 31, h = lane >> 5;
     const int wk = wave / (T::WM * T::WN);
     const int wm = (wave % (T::WM * T::WN)) / T::WN, wn = wave % T::WN;
 
-    const bool a_vec = (g.lda % 4 == 0) && ((reinterpret_cast<uintptr_t>(g.A) & 15) == 0);
-    const bool b_vec = (g.ldb % 4 == 0) && ((reinterpret_cast<uintptr_t>(g.B) & 15) == 0);
+    const int nk = (g.K + KT - 1) / KT;
+
+    // R register stages keep R operand tiles in flight.  Every load below is issued
+    // unconditionally (tiles past the end of k are clamped loads that store_tile turns into
+    // zeros) so that the order of outstanding loads is the same on every path and the
+    // wait before each LDS store covers exactly the stage being stored, nothing younger.
+    v4f ra[R][NA], rb[R][NB];
+    unsigned offa[FAST ? NA : 1], offb[FAST ? NB : 1];
+    const float *tile_a = nullptr, *tile_b = nullptr;  // FAST: first element of the tile's k = 0 column / row
+    size_t kstep_a = 0, kstep_b = 0;                    // FAST: elements from one k step to the next
+    if (FAST) {
+        lane_offsets<A_KC, BM, KT, NT>(reinterpret_cast<unsigned (&)[NA]>(offa), g.lda, tid);
+        lane_offsets<B_KC, BN, KT, NT>(reinterpret_cast<unsigned (&)[NB]>(offb), g.ldb, tid);
+        tile_a = A_KC ? g.A + (size_t)m0 * g.lda : g.A + m0;
+        tile_b = B_KC ? g.B + (size_t)n0 * g.ldb : g.B + n0;
+        kstep_a = A_KC ? (size_t)KT : (size_t)KT * g.lda;
+        kstep_b = B_KC ? (size_t)KT : (size_t)KT * g.ldb;
+    }
+    // load / store of k step t into / from register stage s
+    auto load_step = [&](int s, int t) {
+        if (FAST && (t + 1) * KT <= g.K) {
+            load_tile_fast<NA>(ra[s], tile_a + (size_t)t * kstep_a, reinterpret_cast<const unsigned (&)[NA]>(offa));
+            load_tile_fast<NB>(rb[s], tile_b + (size_t)t * kstep_b, reinterpret_cast<const unsigned (&)[NB]>(offb));
+        } else {
+            load_tile<A_KC, BM, KT, NT, VEC>(ra[s], g.A, g.lda, m0, t * KT, g.M, g.K, tid);
+            load_tile<B_KC, BN, KT, NT, VEC>(rb[s], g.B, g.ldb, n0, t * KT, g.N, g.K, tid);
+        }
+    };
+    auto store_step = [&](int s, int t, float *dst) {
+        if (FAST && (t + 1) * KT <= g.K) {
+            store_tile_fast<A_KC, BM, KT, NT>(dst, ra[s], tid);
+            store_tile_fast<B_KC, BN, KT, NT>(dst + LA::FLOATS, rb[s], tid);
+        } else {
+            store_tile<A_KC, BM, KT, NT>(dst, ra[s], m0, t * KT, g.M, g.K, tid);
+            store_tile<B_KC, BN, KT, NT>(dst + LA::FLOATS, rb[s], n0, t * KT, g.N, g.K, tid);
+        }
+    };
+#pragma unroll
+    for (int s = 0; s < R; ++s) load_step(s, s);
+
+    // In-place operands of the epilogue, fetched now so their latency hides behind the k loop
+    // (all k-split wave groups fetch them; only group 0 uses them).
+    float pre_w[PRE_W ? TM : 1][PRE_W ? TN : 1][16], pre_v[PRE_V ? TM : 1][PRE_V ? TN : 1][16];
+    if (PRE_W) {
+        const float *src_w = (EPI == EPI_DELTA) ? g.aux : g.C;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int col = n0 + wn * T::WTN + j * 32 + idx;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = m0 + wm * T::WTM + i * 32 + 8 * (r / 4) + 4 * h + (r % 4);
+                    const bool ok = FAST || (col < g.N && row < g.M);   // clamp instead of branching
+                    const size_t o = ok ? (size_t)row * g.ldc + col : 0;
+                    if (PRE_W) pre_w[PRE_W ? i : 0][PRE_W ? j : 0][r] = src_w[o];
+                    if (PRE_V) pre_v[PRE_V ? i : 0][PRE_V ? j : 0][r] = g.V[o];
+                }
+            }
+    }
 
     v16f acc[TM][TN];
 #pragma unroll
@@ -177,46 +306,66 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(GemmArgs g, int tiles_m, in
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    float bsum = 0.f;  // GRAD: column sum of Delta for tile row `tid` (first tile column only)
+    const bool do_bias = IS_GRAD && n0 == 0 && tid < BM;
 
-    v4f ra[BM * KT / 4 / NT], rb[BN * KT / 4 / NT];
-    const int nk = (g.K + KT - 1) / KT;
-
-    load_tile<A_KC, BM, KT, NT>(ra, g.A, g.lda, m0, 0, g.M, g.K, a_vec, tid);
-    load_tile<B_KC, BN, KT, NT>(rb, g.B, g.ldb, n0, 0, g.N, g.K, b_vec, tid);
-    store_tile<A_KC, BM, KT, NT>(smem, ra, tid);
-    store_tile<B_KC, BN, KT, NT>(smem + LA::FLOATS, rb, tid);
+    store_step(0, 0, smem);
     __syncthreads();
 
-    for (int t = 0; t < nk; ++t) {
-        const float *As = smem + (t & 1) * STAGE;
-        const float *Bs = As + LA::FLOATS;
-        if (t + 1 < nk) {
-            load_tile<A_KC, BM, KT, NT>(ra, g.A, g.lda, m0, (t + 1) * KT, g.M, g.K, a_vec, tid);
-            load_tile<B_KC, BN, KT, NT>(rb, g.B, g.ldb, n0, (t + 1) * KT, g.N, g.K, b_vec, tid);
-        }
+    // k steps are processed in groups of R (a last partial group works on zero tiles).
+    for (int t0 = 0; t0 < nk; t0 += R) {
 #pragma unroll
-        for (int kk = 0; kk < KT / 8; kk += WK) {
-            v4f fa[TM], fb[TN];
+        for (int s = 0; s < R; ++s) {
+            const int t = t0 + s;
+            const float *As = smem + (t & 1) * STAGE;
+            const float *Bs = As + LA::FLOATS;
+            // registers of stage s were stored to LDS one step ago: refill them with tile t + R
+            load_step(s, t + R);
+            // Keep the instruction scheduler from sinking these loads below the matrix work
+            // (or hoisting the waits of the LDS store above it): the prefetch distance is the point.
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
-                fa[i] = fetch_frag<A_KC, BM, KT>(As, wm * T::WTM + i * 32 + idx, kk + wk, h);
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-                fb[j] = fetch_frag<B_KC, BN, KT>(Bs, wn * T::WTN + j * 32 + idx, kk + wk, h);
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
+            for (int kk = 0; kk < KT / 8; kk += WK) {
+                v4f fa[TM], fb[TN];
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
+                    fa[i] = fetch_frag<A_KC, BM, KT>(As, wm * T::WTM + i * 32 + idx, kk + wk, h);
 #pragma unroll
-                    for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][q], fb[j][q], acc[i][j], 0, 0, 0);
+                for (int j = 0; j < TN; ++j)
+                    fb[j] = fetch_frag<B_KC, BN, KT>(Bs, wn * T::WTN + j * 32 + idx, kk + wk, h);
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int j = 0; j < TN; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][q], fb[j][q], acc[i][j], 0, 0, 0);
+            }
+            if (IS_GRAD && do_bias) {  // A tile is stored [k][m]: rows beyond K and columns beyond M hold zeros
+#pragma unroll
+                for (int k = 0; k < KT; ++k) bsum += As[k * LA::STRIDE + tid];
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            store_step((s + 1) % R, t + 1, smem + ((t + 1) & 1) * STAGE);
+            __syncthreads();
         }
-        if (t + 1 < nk) {
-            float *An = smem + ((t + 1) & 1) * STAGE;
-            store_tile<A_KC, BM, KT, NT>(An, ra, tid);
-            store_tile<B_KC, BN, KT, NT>(An + LA::FLOATS, rb, tid);
+    }
+
+    if (IS_GRAD && do_bias && m0 + tid < g.M) {
+        const int o = m0 + tid;
+        if (EPI == EPI_GRAD_STORE) {
+            g.gb[o] = bsum * g.scale;
+        } else if (EPI == EPI_GRAD_SGD) {
+            g.gb[o] = g.gb[o] + (-g.scale * bsum);
+        } else if (EPI == EPI_GRAD_SGD_KEEPV) {
+            const float dw = -g.scale * bsum;
+            g.vb[o] = dw;
+            g.gb[o] = g.gb[o] + dw;
+        } else {
+            const float dw = g.mu * g.vb[o] - g.scale * bsum;
+            g.vb[o] = dw;
+            g.gb[o] = g.gb[o] + dw;
         }
-        __syncthreads();
     }
 
     // Sum the k-split partial tiles (tree over wk, through LDS).
@@ -254,77 +403,122 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(GemmArgs g, int tiles_m, in
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int col = n0 + wn * T::WTN + j * 32 + idx;
-            if (col >= g.N) continue;
+            if (!FAST && col >= g.N) continue;
             float bias = 0.f;
-            if (KIND == GEMM_FWD) bias = g.bias[col];
+            if (EPI == EPI_FWD) bias = g.bias[col];
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int row = m0 + wm * T::WTM + i * 32 + 8 * (r / 4) + 4 * h + (r % 4);
-                if (row >= g.M) continue;
-                const size_t o = (size_t)row * g.ldc + col;
-                const float s = acc[i][j][r];
-                if (KIND == GEMM_FWD) {
-                    g.C[o] = act_fn(g.act, s + bias);
-                } else if (KIND == GEMM_DELTA) {
-                    g.C[o] = s * act_deriv(g.act, g.aux[o]);
-                } else {
-                    if (g.mode == GRAD_STORE) {
-                        g.C[o] = s * g.scale;
-                    } else if (g.mode == GRAD_SGD) {
-                        g.C[o] = g.C[o] + (-g.scale * s);
-                    } else if (g.mode == GRAD_SGD_KEEPV) {
-                        const float dw = -g.scale * s;
-                        g.V[o] = dw;
-                        g.C[o] = g.C[o] + dw;
-                    } else {
-                        const float dw = g.mu * g.V[o] - g.scale * s;
-                        g.V[o] = dw;
-                        g.C[o] = g.C[o] + dw;
-                    }
-                }
+                if (!FAST && row >= g.M) continue;
+                epilogue_store<EPI>(g, (size_t)row * g.ldc + col, acc[i][j][r], bias,
+                                    pre_w[PRE_W ? i : 0][PRE_W ? j : 0][r], pre_v[PRE_V ? i : 0][PRE_V ? j : 0][r]);
             }
         }
     }
 }
 
+template <class T, bool A_KC, bool B_KC, int EPI, bool VEC>
+__global__ __launch_bounds__(T::NT) void gemm_kernel(GemmArgs g, int tiles_m, int tiles_n)
+{
+    extern __shared__ __attribute__((aligned(16))) float smem[];
+    // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous
+    // run of tiles (m fastest) so tiles sharing a B panel meet in one L2.
+    const int nt = tiles_m * tiles_n;
+    const int per_xcd = (nt + 7) / 8;
+    const int v = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    if (v >= nt) return;
+    const int m0 = (v % tiles_m) * T::BM, n0 = (v / tiles_m) * T::BN;
+    if (VEC && m0 + T::BM <= g.M && n0 + T::BN <= g.N)
+        gemm_tile<T, A_KC, B_KC, EPI, VEC, VEC>(g, smem, m0, n0);
+    else
+        gemm_tile<T, A_KC, B_KC, EPI, VEC, false>(g, smem, m0, n0);
+}
+
 // ---- tile configurations and dispatch ----------------------------------------
-using T128 = Tile<128, 128, 16, 2, 2, 1>;   // many-tile outputs (weight gradients, large batches)
-using T64K4 = Tile<64, 64, 32, 1, 1, 4>;    // few-tile outputs: batch x width with batch <= a few hundred
-using T32K4 = Tile<32, 64, 32, 1, 1, 4>;    // very small batches
+template <class T, bool A_KC, bool B_KC>
+constexpr size_t smem_bytes()
+{
+    constexpr int stage = Lds<A_KC, T::BM, T::KT>::FLOATS + Lds<B_KC, T::BN, T::KT>::FLOATS;
+    constexpr int red = (T::WK > 1) ? (T::WK / 2) * T::BM * T::BN : 0;
+    return sizeof(float) * (size_t)((2 * stage > red) ? 2 * stage : red);
+}
 
-static const char *kVariantNames[] = {"128x128x16_w2x2", "64x64x32_k4", "32x64x32_k4"};
-int gemm_variant_count() { return 3; }
-const char *gemm_variant_name(int v) { return (v >= 0 && v < 3) ? kVariantNames[v] : "?"; }
-
-template <class T, bool A_KC, bool B_KC, int KIND>
-static hipError_t launch_one(const GemmArgs &a, hipStream_t stream)
+template <class T, bool A_KC, bool B_KC, int EPI, bool VEC>
+static hipError_t launch_vec(const GemmArgs &a, hipStream_t stream)
 {
     const int tiles_m = (a.M + T::BM - 1) / T::BM, tiles_n = (a.N + T::BN - 1) / T::BN;
     const long nt = (long)tiles_m * tiles_n;
     const long grid = 8 * ((nt + 7) / 8);
     if (grid <= 0 || grid > 0x7fffffffL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((gemm_kernel<T, A_KC, B_KC, KIND>), dim3((unsigned)grid), dim3(T::NT), 0, stream, a,
+    constexpr size_t lds = smem_bytes<T, A_KC, B_KC>();
+    static_assert(lds <= 160 * 1024, "tile does not fit the 160 KB LDS of a CU");
+    static bool attr_set = false;  // raise the dynamic-LDS limit once per instantiation
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel<T, A_KC, B_KC, EPI, VEC>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((gemm_kernel<T, A_KC, B_KC, EPI, VEC>), dim3((unsigned)grid), dim3(T::NT), lds, stream, a,
                        tiles_m, tiles_n);
     return hipGetLastError();
+}
+
+//                BM   BN  KT  WM WN WK R
+using V0 = Tile<128, 128, 16, 2, 2, 1, 1>;  // short k, many tiles: weight gradients
+using V1 = Tile<128, 64, 16, 2, 2, 1, 2>;   // large batch x width products
+using V2 = Tile<64, 64, 64, 1, 1, 4, 2>;
+using V3 = Tile<64, 64, 32, 1, 1, 4, 2>;
+using V4 = Tile<32, 64, 32, 1, 1, 4, 2>;    // batch of a few hundred x width
+using V5 = Tile<32, 64, 64, 1, 1, 8, 2>;
+using V6 = Tile<32, 32, 64, 1, 1, 8, 2>;    // few output tiles: lean on the k split
+
+static const char *kVariantNames[] = {"128x128x16_r1", "128x64x16_r2",   "64x64x64_k4_r2", "64x64x32_k4_r2",
+                                      "32x64x32_k4_r2", "32x64x64_k8_r2", "32x32x64_k8_r2"};
+constexpr int kVariants = 7;
+int gemm_variant_count() { return kVariants; }
+const char *gemm_variant_name(int v) { return (v >= 0 && v < kVariants) ? kVariantNames[v] : "?"; }
+
+template <class T, bool A_KC, bool B_KC, int EPI>
+static hipError_t launch_one(const GemmArgs &a, hipStream_t stream)
+{
+    const bool a_vec = (a.lda % 4 == 0) && ((A_KC ? a.K : a.M) % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.A) & 15) == 0);
+    const bool b_vec = (a.ldb % 4 == 0) && ((B_KC ? a.K : a.N) % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.B) & 15) == 0);
+    if (a_vec && b_vec) return launch_vec<T, A_KC, B_KC, EPI, true>(a, stream);
+    // operands that cannot be loaded as float4 (widths not a multiple of 4) are small in
+    // practice: one tile shape serves them all
+    return launch_vec<V4, A_KC, B_KC, EPI, false>(a, stream);
 }
 
 template <class T>
 static hipError_t launch_kind(GemmKind kind, const GemmArgs &a, hipStream_t stream)
 {
     switch (kind) {
-    case GEMM_FWD: return launch_one<T, true, true, GEMM_FWD>(a, stream);
-    case GEMM_DELTA: return launch_one<T, true, false, GEMM_DELTA>(a, stream);
-    case GEMM_GRAD: return launch_one<T, false, false, GEMM_GRAD>(a, stream);
+    case GEMM_FWD: return launch_one<T, true, true, EPI_FWD>(a, stream);
+    case GEMM_DELTA: return launch_one<T, true, false, EPI_DELTA>(a, stream);
+    case GEMM_GRAD:
+        switch (a.mode) {
+        case GRAD_STORE: return launch_one<T, false, false, EPI_GRAD_STORE>(a, stream);
+        case GRAD_SGD: return launch_one<T, false, false, EPI_GRAD_SGD>(a, stream);
+        case GRAD_SGD_KEEPV: return launch_one<T, false, false, EPI_GRAD_SGD_KEEPV>(a, stream);
+        case GRAD_MOMENTUM: return launch_one<T, false, false, EPI_GRAD_MOMENTUM>(a, stream);
+        default: return hipErrorInvalidValue;
+        }
     default: return hipErrorInvalidValue;
     }
 }
 
+// Tile shape from the problem shape: prefer the largest tile that still gives every CU
+// (256 of them) at least one workgroup; outputs with few tiles use small tiles whose waves
+// split k among themselves.
 static int pick_variant(const GemmArgs &a)
 {
-    const long t128 = (long)((a.M + 127) / 128) * ((a.N + 127) / 128);
-    if (t128 >= 192) return 0;
-    if (a.M <= 32) return 2;
-    return 1;
+    auto tiles = [&](int bm, int bn) { return (long)((a.M + bm - 1) / bm) * ((a.N + bn - 1) / bn); };
+    if (a.K <= 512 && tiles(128, 128) >= 256) return 0;
+    if (tiles(128, 64) >= 256) return 1;
+    if (tiles(32, 64) >= 256) return 4;
+    if (tiles(32, 64) >= 128) return 5;
+    return 6;
 }
 
 hipError_t launch_gemm(GemmKind kind, const GemmArgs &a, int variant, hipStream_t stream)
@@ -332,9 +526,13 @@ hipError_t launch_gemm(GemmKind kind, const GemmArgs &a, int variant, hipStream_
     if (a.M <= 0 || a.N <= 0 || a.K <= 0) return hipErrorInvalidValue;
     if (variant < 0) variant = pick_variant(a);
     switch (variant) {
-    case 0: return launch_kind<T128>(kind, a, stream);
-    case 1: return launch_kind<T64K4>(kind, a, stream);
-    case 2: return launch_kind<T32K4>(kind, a, stream);
+    case 0: return launch_kind<V0>(kind, a, stream);
+    case 1: return launch_kind<V1>(kind, a, stream);
+    case 2: return launch_kind<V2>(kind, a, stream);
+    case 3: return launch_kind<V3>(kind, a, stream);
+    case 4: return launch_kind<V4>(kind, a, stream);
+    case 5: return launch_kind<V5>(kind, a, stream);
+    case 6: return launch_kind<V6>(kind, a, stream);
     default: return hipErrorInvalidValue;
     }
 }

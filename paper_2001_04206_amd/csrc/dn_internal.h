@@ -16,7 +16,8 @@ namespace dn {
 enum GemmKind : int {
     GEMM_FWD = 0,    // A = A_{l-1} [B][n_in] (KC), B = W_l [n_out][n_in] (KC): Z = A W^T; + bias, activation
     GEMM_DELTA = 1,  // A = Delta_l [B][n_l] (KC), B = W_l [n_l][n_{l-1}] (MC): (Delta W) * f'(A_{l-1})
-    GEMM_GRAD = 2,   // A = Delta_l stored [B][n_l] (MC), B = A_{l-1} stored [B][n_{l-1}] (MC): Delta^T A
+    GEMM_GRAD = 2,   // A = Delta_l stored [B][n_l] (MC), B = A_{l-1} stored [B][n_{l-1}] (MC): Delta^T A, and the
+                     // column sums of Delta (bias gradient) computed by the first tile column
     GEMM_KINDS = 3
 };
 
@@ -39,6 +40,8 @@ struct GemmArgs {
     int act;           // FWD: activation of this layer (softmax stores z) ; DELTA: activation of layer l-1
     const float *aux;  // DELTA: A_{l-1} [M][ldc]
     float *V;          // update modes: velocity, same shape as W
+    float *gb;         // GEMM_GRAD: bias gradient (GRAD_STORE) or bias b_l updated in place (update modes)
+    float *vb;         // GEMM_GRAD update modes: bias velocity
     float scale;       // GRAD_STORE: 1/B ; update modes: lr/B
     float mu;          // GRAD_MOMENTUM
     int mode;          // GradMode for GEMM_GRAD
@@ -63,9 +66,6 @@ hipError_t launch_output_delta(float *AL, float *DL, const int32_t *labels, floa
 // Sum loss_rows[0..B): *loss_mean_out = sum / B (if non-null); *epoch_acc += sum (if non-null).
 hipError_t launch_loss_reduce(const float *loss_rows, int B, float *loss_mean_out,
                               double *epoch_acc, hipStream_t stream);
-// Bias gradient / bias update from the column sums of Delta [B][n].
-hipError_t launch_bias(const float *D, int B, int n, float *g_out, float *b, float *vb,
-                       float scale, float mu, int mode, hipStream_t stream);
 // Elementwise update of a parameter vector from a stored gradient (dn_update).
 hipError_t launch_update(float *p, float *v, const float *g, size_t count, float lr, float mu,
                          hipStream_t stream);

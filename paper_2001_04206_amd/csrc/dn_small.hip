@@ -1,6 +1,6 @@
 // Row-wise and elementwise kernels of a training step: output-layer error
-// (softmax, loss, Delta_L), loss reduction, bias gradient / update, and the
-// elementwise parameter update used by dn_update.
+// (softmax, loss, Delta_L), loss reduction, and the elementwise parameter
+// update used by dn_update.
 #include "dn_internal.h"
 
 namespace dn {
@@ -114,37 +114,6 @@ __global__ __launch_bounds__(256) void loss_reduce_kernel(const float *__restric
     }
 }
 
-// Column sums of Delta [B][n]: a workgroup covers 64 columns with 4 row groups.
-// mode GRAD_STORE writes g = sum/B; the update modes apply it to b (and vb).
-__global__ __launch_bounds__(256) void bias_kernel(const float *__restrict__ D, int B, int n,
-                                                   float *__restrict__ g_out, float *__restrict__ b,
-                                                   float *__restrict__ vb, float scale, float mu, int mode)
-{
-    __shared__ float red[4][64];
-    const int c = blockIdx.x * 64 + (threadIdx.x & 63), rg = threadIdx.x >> 6;
-    float s = 0.f;
-    if (c < n)
-        for (int r = rg; r < B; r += 4) s += D[(size_t)r * n + c];
-    red[rg][threadIdx.x & 63] = s;
-    __syncthreads();
-    if (rg == 0 && c < n) {
-        const float t = (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
-        if (mode == GRAD_STORE) {
-            g_out[c] = t * scale;
-        } else if (mode == GRAD_SGD) {
-            b[c] = b[c] + (-scale * t);
-        } else if (mode == GRAD_SGD_KEEPV) {
-            const float dw = -scale * t;
-            vb[c] = dw;
-            b[c] = b[c] + dw;
-        } else {
-            const float dw = mu * vb[c] - scale * t;
-            vb[c] = dw;
-            b[c] = b[c] + dw;
-        }
-    }
-}
-
 __global__ __launch_bounds__(256) void update_kernel(float *__restrict__ p, float *__restrict__ v,
                                                      const float *__restrict__ g, size_t count, float lr,
                                                      float mu)
@@ -176,14 +145,6 @@ hipError_t launch_loss_reduce(const float *loss_rows, int B, float *loss_mean_ou
 {
     hipLaunchKernelGGL(loss_reduce_kernel, dim3(1), dim3(256), 0, stream, loss_rows, B, loss_mean_out,
                        epoch_acc);
-    return hipGetLastError();
-}
-
-hipError_t launch_bias(const float *D, int B, int n, float *g_out, float *b, float *vb, float scale,
-                       float mu, int mode, hipStream_t stream)
-{
-    hipLaunchKernelGGL(bias_kernel, dim3((n + 63) / 64), dim3(256), 0, stream, D, B, n, g_out, b, vb, scale,
-                       mu, mode);
     return hipGetLastError();
 }
 

@@ -19,8 +19,8 @@ LIB_PATH = os.path.join(_HERE, "libdn.so")
 DN_OK, DN_ERR_INVALID_ARG, DN_ERR_SHAPE, DN_ERR_UNSUPPORTED, DN_ERR_OOM, DN_ERR_DEVICE = range(6)
 DN_ACT_LINEAR, DN_ACT_SIGMOID, DN_ACT_TANH, DN_ACT_RELU, DN_ACT_SOFTMAX = range(5)
 DN_LOSS_MSE, DN_LOSS_CROSS_ENTROPY = 0, 1
-DN_K_FORWARD, DN_K_DELTA, DN_K_GRAD_UPDATE, DN_K_OUTPUT, DN_K_BIAS, DN_K_ONLINE = range(6)
-KERNEL_CLASS_NAMES = ["forward", "delta", "grad_update", "output", "bias", "online"]
+DN_K_FORWARD, DN_K_DELTA, DN_K_GRAD_UPDATE, DN_K_OUTPUT, DN_K_ONLINE = range(5)
+KERNEL_CLASS_NAMES = ["forward", "delta", "grad_update", "output", "online"]
 
 EXPORTS = [
     "dn_status_string", "dn_net_arena_bytes", "dn_net_create", "dn_net_destroy", "dn_set_params",
@@ -136,6 +136,8 @@ class Net:
 
     # -- parameters ------------------------------------------------------------
     def dn_set_params(self, layer: int, W: Optional[np.ndarray], b: Optional[np.ndarray]):
+        if not 1 <= layer <= self.L:
+            raise DnError(DN_ERR_INVALID_ARG, "dn_set_params")
         Wc = None if W is None else np.ascontiguousarray(W, dtype=np.float32)
         bc = None if b is None else np.ascontiguousarray(b, dtype=np.float32)
         if Wc is not None and Wc.shape != (self.widths[layer], self.widths[layer - 1]):
@@ -147,6 +149,8 @@ class Net:
                                    None if bc is None else bc.ctypes.data_as(C.c_void_p)), "dn_set_params")
 
     def _get(self, fn, name, layer) -> Tuple[np.ndarray, np.ndarray]:
+        if not 1 <= layer <= self.L:          # the host buffers below are sized from the layer's widths
+            raise DnError(DN_ERR_INVALID_ARG, name)
         W = np.empty((self.widths[layer], self.widths[layer - 1]), dtype=np.float32)
         b = np.empty(self.widths[layer], dtype=np.float32)
         _check(fn(self._h, layer, W.ctypes.data_as(C.c_void_p), b.ctypes.data_as(C.c_void_p)), name)

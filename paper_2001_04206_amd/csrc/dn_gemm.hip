@@ -16,6 +16,8 @@
 // instructions pairing k = j (h = 0) with k = 4 + j (h = 1): a lane then needs
 // four consecutive k values of its row, one 128-bit LDS read when the tile is
 // stored k-contiguous.
+#include <type_traits>
+
 #include "dn_internal.h"
 
 namespace dn {
@@ -43,9 +45,12 @@ __device__ __forceinline__ float act_deriv(int act, float a)
     }
 }
 
-template <int BM_, int BN_, int KT_, int WM_, int WN_, int WK_, int R_>
+template <int BM_, int BN_, int KT_, int WM_, int WN_, int WK_, int R_, int PC_ = 0, int OCC_ = 1, bool PV_ = true>
 struct Tile {
     static constexpr int BM = BM_, BN = BN_, KT = KT_, WM = WM_, WN = WN_, WK = WK_, R = R_;
+    static constexpr int PC = PC_;    // peeled k steps that carry the epilogue-operand prefetch (update kernels)
+    static constexpr int OCC = OCC_;  // waves per SIMD the register budget must allow
+    static constexpr bool PV = PV_;   // momentum update: prefetch the velocity too (else read it in the epilogue)
     static_assert(R >= 1 && R <= 4, "register stages");
     static constexpr int NT = 64 * WM * WN * WK;
     static constexpr int WTM = BM / WM, WTN = BN / WN;  // wave tile
@@ -216,6 +221,22 @@ __device__ __forceinline__ void store_tile_fast(float *__restrict__ S, const v4f
     }
 }
 
+// Emits the requested instruction order of one k step for the machine scheduler: FILL times
+// (BASE matrix instructions, then one LDS read while I < NRD, else one LDS write).
+template <int I, int FILL, int NRD, int BASE>
+struct SchedPattern {
+    static __device__ __forceinline__ void emit()
+    {
+        __builtin_amdgcn_sched_group_barrier(0x008, BASE, 0);
+        __builtin_amdgcn_sched_group_barrier(I < NRD ? 0x100 : 0x200, 1, 0);
+        SchedPattern<I + 1, FILL, NRD, BASE>::emit();
+    }
+};
+template <int FILL, int NRD, int BASE>
+struct SchedPattern<FILL, FILL, NRD, BASE> {
+    static __device__ __forceinline__ void emit() {}
+};
+
 // Work of one workgroup on the tile at (m0, n0).  FAST: the tile is interior in m and n and
 // both operands are vector-loadable; only a ragged last k step takes the clamped path.
 template <class T, bool A_KC, bool B_KC, int EPI, bool VEC, bool FAST>
@@ -225,11 +246,12 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, float *smem, const 
     constexpr int TM = T::TM, TN = T::TN, WK = T::WK;
     constexpr bool IS_GRAD = EPI >= EPI_GRAD_STORE;
     constexpr bool PRE_W = EPI == EPI_DELTA || EPI >= EPI_GRAD_SGD;
-    constexpr bool PRE_V = EPI == EPI_GRAD_MOMENTUM;
+    constexpr bool PRE_V = EPI == EPI_GRAD_MOMENTUM && T::PV;
     using LA = Lds<A_KC, BM, KT>;
     using LB = Lds<B_KC, BN, KT>;
     constexpr int STAGE = LA::FLOATS + LB::FLOATS;
     static_assert(!IS_GRAD || NT >= BM, "bias reduction needs one thread per tile row");
+    static_assert(!IS_GRAD || WK * BM <= 2 * (Lds<A_KC, BM, KT>::FLOATS + Lds<B_KC, BN, KT>::FLOATS), "bias scratch must fit the tile buffers");
     static_assert(VEC || !FAST, "the interior path needs vector loads");
     constexpr int NA = BM * KT / 4 / NT, NB = BN * KT / 4 / NT;
 
@@ -256,9 +278,10 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, float *smem, const 
         kstep_a = A_KC ? (size_t)KT : (size_t)KT * g.lda;
         kstep_b = B_KC ? (size_t)KT : (size_t)KT * g.ldb;
     }
-    // load / store of k step t into / from register stage s
-    auto load_step = [&](int s, int t) {
-        if (FAST && (t + 1) * KT <= g.K) {
+    // load / store of k step t into / from register stage s; `full` (compile time) promises
+    // that the step lies wholly inside k, so the interior path needs neither clamps nor masks
+    auto load_step = [&](auto full, int s, int t) {
+        if (FAST && decltype(full)::value) {
             load_tile_fast<NA>(ra[s], tile_a + (size_t)t * kstep_a, reinterpret_cast<const unsigned (&)[NA]>(offa));
             load_tile_fast<NB>(rb[s], tile_b + (size_t)t * kstep_b, reinterpret_cast<const unsigned (&)[NB]>(offb));
         } else {
@@ -266,8 +289,8 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, float *smem, const 
             load_tile<B_KC, BN, KT, NT, VEC>(rb[s], g.B, g.ldb, n0, t * KT, g.N, g.K, tid);
         }
     };
-    auto store_step = [&](int s, int t, float *dst) {
-        if (FAST && (t + 1) * KT <= g.K) {
+    auto store_step = [&](auto full, int s, int t, float *dst) {
+        if (FAST && decltype(full)::value) {
             store_tile_fast<A_KC, BM, KT, NT>(dst, ra[s], tid);
             store_tile_fast<B_KC, BN, KT, NT>(dst + LA::FLOATS, rb[s], tid);
         } else {
@@ -275,28 +298,36 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, float *smem, const 
             store_tile<B_KC, BN, KT, NT>(dst + LA::FLOATS, rb[s], n0, t * KT, g.N, g.K, tid);
         }
     };
+    using Full = std::integral_constant<bool, true>;
+    using Ragged = std::integral_constant<bool, false>;
 #pragma unroll
-    for (int s = 0; s < R; ++s) load_step(s, s);
+    for (int s = 0; s < R; ++s) load_step(Ragged{}, s, s);
 
-    // In-place operands of the epilogue, fetched now so their latency hides behind the k loop
-    // (all k-split wave groups fetch them; only group 0 uses them).
+    // In-place operands of the epilogue (W and velocity for the update modes, A_{l-1} for DELTA)
+    // are fetched while the k loop runs.  Loads return in issue order, so a burst of them issued
+    // before an operand-tile load would stall the k loop until the whole burst is back.  With
+    // PC > 0 the first PC k steps are peeled and each issues 1/PC of these loads *after* its own
+    // operand-tile loads: no tile load ever queues behind more than one small chunk.  With
+    // PC == 0 they are all issued up front (fine when they are few and L2-resident).
+    // (All k-split wave groups fetch them; only group 0 uses them.)
+    constexpr int PC = (IS_GRAD && PRE_W) ? T::PC : 0;
+    constexpr int NPRE = TM * TN * 16;
+    static_assert(PC == 0 || (PC % R == 0 && (NPRE * (PRE_V ? 2 : 1)) % PC == 0), "chunked prefetch must divide evenly");
     float pre_w[PRE_W ? TM : 1][PRE_W ? TN : 1][16], pre_v[PRE_V ? TM : 1][PRE_V ? TN : 1][16];
-    if (PRE_W) {
-        const float *src_w = (EPI == EPI_DELTA) ? g.aux : g.C;
+    const float *src_w = (EPI == EPI_DELTA) ? g.aux : g.C;
+    auto pre_load = [&](int q) {  // q in [0, NPRE * (1 or 2)): element q of (pre_w, then pre_v)
+        const int which = q / NPRE, e = q % NPRE;
+        const int i = e / (TN * 16), j = (e / 16) % TN, r = e % 16;
+        const int col = n0 + wn * T::WTN + j * 32 + idx;
+        const int row = m0 + wm * T::WTM + i * 32 + 8 * (r / 4) + 4 * h + (r % 4);
+        const bool ok = FAST || (col < g.N && row < g.M);  // clamp instead of branching
+        const size_t o = ok ? (size_t)row * g.ldc + col : 0;
+        if (which == 0) pre_w[PRE_W ? i : 0][PRE_W ? j : 0][r] = src_w[o];
+        else pre_v[PRE_V ? i : 0][PRE_V ? j : 0][r] = g.V[o];
+    };
+    if (PRE_W && PC == 0) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int col = n0 + wn * T::WTN + j * 32 + idx;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int row = m0 + wm * T::WTM + i * 32 + 8 * (r / 4) + 4 * h + (r % 4);
-                    const bool ok = FAST || (col < g.N && row < g.M);   // clamp instead of branching
-                    const size_t o = ok ? (size_t)row * g.ldc + col : 0;
-                    if (PRE_W) pre_w[PRE_W ? i : 0][PRE_W ? j : 0][r] = src_w[o];
-                    if (PRE_V) pre_v[PRE_V ? i : 0][PRE_V ? j : 0][r] = g.V[o];
-                }
-            }
+        for (int q = 0; q < NPRE * (PRE_V ? 2 : 1); ++q) pre_load(q);
     }
 
     v16f acc[TM][TN];
@@ -306,66 +337,137 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, float *smem, const 
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-    float bsum = 0.f;  // GRAD: column sum of Delta for tile row `tid` (first tile column only)
-    const bool do_bias = IS_GRAD && n0 == 0 && tid < BM;
+    // GRAD: the bias gradient is the column sum of Delta, i.e. the sum over k of this kernel's
+    // A operand.  Waves of the first tile column that sit in wave column 0 add up the A
+    // fragments they hold anyway (per lane: its row, its half of the k values).
+    float bs[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) bs[i] = 0.f;
+    const bool bias_wave = IS_GRAD && n0 == 0 && wn == 0;
 
-    store_step(0, 0, smem);
+    const float bias_on = bias_wave ? 1.f : 0.f;  // a factor, not a branch: each k step stays one basic block
+    store_step(Ragged{}, 0, 0, smem);
     __syncthreads();
 
-    // k steps are processed in groups of R (a last partial group works on zero tiles).
-    for (int t0 = 0; t0 < nk; t0 += R) {
+    // One k step: LDS buffer (t & 1) holds tile t; register stage s (stored one step ago) is
+    // refilled with tile t + R; stage (s + 1) % R, holding tile t + 1, goes to the other buffer.
+    // A wave cannot start a new matrix instruction while one is running (64 cycles each), but it
+    // can issue LDS and memory instructions in that shadow: the LDS reads of later fragment groups
+    // and the LDS writes of the next tile are therefore spread between the matrix instructions.
+    constexpr int G = KT / 8 / WK;                 // fragment groups (8 k values each) per wave and step
+    constexpr int NMF = G * 4 * TM * TN;           // matrix instructions per wave and step
+    constexpr int NRD = (G - 1) * (TM * (A_KC ? 1 : 2) + TN * (B_KC ? 1 : 2));  // LDS reads of groups 1..G-1
+    constexpr int NWR = NA + NB;                   // LDS writes of the next tile
+    constexpr int FILL = NRD + NWR;
+    constexpr int BASE = (NMF / (FILL + 1)) > 0 ? NMF / (FILL + 1) : 1;
+    auto k_step = [&](auto full, int s, int t, int chunk) {
+        const float *As = smem + (t & 1) * STAGE;
+        const float *Bs = As + LA::FLOATS;
+        v4f fa[G][TM], fb[G][TN];
 #pragma unroll
-        for (int s = 0; s < R; ++s) {
-            const int t = t0 + s;
-            const float *As = smem + (t & 1) * STAGE;
-            const float *Bs = As + LA::FLOATS;
-            // registers of stage s were stored to LDS one step ago: refill them with tile t + R
-            load_step(s, t + R);
-            // Keep the instruction scheduler from sinking these loads below the matrix work
-            // (or hoisting the waits of the LDS store above it): the prefetch distance is the point.
-            __builtin_amdgcn_sched_barrier(0);
+        for (int i = 0; i < TM; ++i) fa[0][i] = fetch_frag<A_KC, BM, KT>(As, wm * T::WTM + i * 32 + idx, wk, h);
 #pragma unroll
-            for (int kk = 0; kk < KT / 8; kk += WK) {
-                v4f fa[TM], fb[TN];
+        for (int j = 0; j < TN; ++j) fb[0][j] = fetch_frag<B_KC, BN, KT>(Bs, wn * T::WTN + j * 32 + idx, wk, h);
+        load_step(full, s, t + R);
+        if (PC > 0 && chunk >= 0) {
+            constexpr int PER = NPRE * (PRE_V ? 2 : 1) / (PC > 0 ? PC : 1);
+#pragma unroll
+            for (int q = 0; q < PER; ++q) pre_load(chunk * PER + q);
+        }
+        // Keep the instruction scheduler from sinking the global loads into the matrix work
+        // (the prefetch distance is the point).
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int gq = 1; gq < G; ++gq) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                fa[gq][i] = fetch_frag<A_KC, BM, KT>(As, wm * T::WTM + i * 32 + idx, gq * WK + wk, h);
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                fb[gq][j] = fetch_frag<B_KC, BN, KT>(Bs, wn * T::WTN + j * 32 + idx, gq * WK + wk, h);
+        }
+#pragma unroll
+        for (int gq = 0; gq < G; ++gq)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
-                    fa[i] = fetch_frag<A_KC, BM, KT>(As, wm * T::WTM + i * 32 + idx, kk + wk, h);
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    fb[j] = fetch_frag<B_KC, BN, KT>(Bs, wn * T::WTN + j * 32 + idx, kk + wk, h);
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[gq][i][q], fb[gq][j][q], acc[i][j], 0, 0, 0);
+        if (IS_GRAD) {
 #pragma unroll
-                for (int q = 0; q < 4; ++q)
+            for (int gq = 0; gq < G; ++gq)
 #pragma unroll
-                    for (int i = 0; i < TM; ++i)
+                for (int i = 0; i < TM; ++i)
+                    bs[i] += bias_on * ((fa[gq][i][0] + fa[gq][i][1]) + (fa[gq][i][2] + fa[gq][i][3]));
+        }
+        store_step(full, (s + 1) % R, t + 1, smem + ((t + 1) & 1) * STAGE);
+        // requested order inside this region: BASE matrix instructions, one LDS read (while any
+        // are left) or LDS write, and so on; then the remaining matrix instructions.
+        SchedPattern<0, FILL, NRD, BASE>::emit();
+        __builtin_amdgcn_sched_group_barrier(0x008, NMF - BASE * FILL > 0 ? NMF - BASE * FILL : 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        __syncthreads();
+    };
+
+    // A step t may take the mask-free form when the tile it stores (t + 1) and the tile it
+    // loads (t + R) lie wholly inside k.  Peeled steps carry the chunked prefetch; then full
+    // steps run in groups of R while they last; the rest (ragged tail, steps that load or store
+    // past the end, and a last partial group working on zero tiles) take the masked form.
+    const int nfull = g.K / KT;  // k steps 0 .. nfull-1 are wholly inside k
+    int t0 = 0;
+    if (PC > 0) {
+        if (FAST && PC + R <= nfull) {
 #pragma unroll
-                        for (int j = 0; j < TN; ++j)
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][q], fb[j][q], acc[i][j], 0, 0, 0);
-            }
-            if (IS_GRAD && do_bias) {  // A tile is stored [k][m]: rows beyond K and columns beyond M hold zeros
+            for (int c = 0; c < PC; ++c) k_step(Full{}, c % R, c, c);
+        } else {
 #pragma unroll
-                for (int k = 0; k < KT; ++k) bsum += As[k * LA::STRIDE + tid];
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            store_step((s + 1) % R, t + 1, smem + ((t + 1) & 1) * STAGE);
-            __syncthreads();
+            for (int c = 0; c < PC; ++c) k_step(Ragged{}, c % R, c, c);
+        }
+        t0 = PC;
+    }
+    if (FAST) {
+        for (; t0 + 2 * R <= nfull; t0 += R) {
+#pragma unroll
+            for (int s = 0; s < R; ++s) k_step(Full{}, s, t0 + s, -1);
         }
     }
+    for (; t0 < nk; t0 += R) {
+#pragma unroll
+        for (int s = 0; s < R; ++s) k_step(Ragged{}, s, t0 + s, -1);
+    }
 
-    if (IS_GRAD && do_bias && m0 + tid < g.M) {
-        const int o = m0 + tid;
-        if (EPI == EPI_GRAD_STORE) {
-            g.gb[o] = bsum * g.scale;
-        } else if (EPI == EPI_GRAD_SGD) {
-            g.gb[o] = g.gb[o] + (-g.scale * bsum);
-        } else if (EPI == EPI_GRAD_SGD_KEEPV) {
-            const float dw = -g.scale * bsum;
-            g.vb[o] = dw;
-            g.gb[o] = g.gb[o] + dw;
-        } else {
-            const float dw = g.mu * g.vb[o] - g.scale * bsum;
-            g.vb[o] = dw;
-            g.gb[o] = g.gb[o] + dw;
+    if (IS_GRAD) {
+        // Bias gradient: join the two k halves of each lane pair, then the k-split wave groups
+        // (fixed order, through LDS; the k loop ended with a barrier, so the tile buffers are free).
+#pragma unroll
+        for (int i = 0; i < TM; ++i) bs[i] += __shfl_xor(bs[i], 32, 64);
+        if (bias_wave && h == 0) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i) smem[wk * BM + wm * T::WTM + i * 32 + idx] = bs[i];
         }
+        __syncthreads();
+        if (n0 == 0 && tid < BM && m0 + tid < g.M) {
+            float bsum = 0.f;
+#pragma unroll
+            for (int w = 0; w < WK; ++w) bsum += smem[w * BM + tid];
+            const int o = m0 + tid;
+            if (EPI == EPI_GRAD_STORE) {
+                g.gb[o] = bsum * g.scale;
+            } else if (EPI == EPI_GRAD_SGD) {
+                g.gb[o] = g.gb[o] + (-g.scale * bsum);
+            } else if (EPI == EPI_GRAD_SGD_KEEPV) {
+                const float dw = -g.scale * bsum;
+                g.vb[o] = dw;
+                g.gb[o] = g.gb[o] + dw;
+            } else {
+                const float dw = g.mu * g.vb[o] - g.scale * bsum;
+                g.vb[o] = dw;
+                g.gb[o] = g.gb[o] + dw;
+            }
+        }
+        __syncthreads();
     }
 
     // Sum the k-split partial tiles (tree over wk, through LDS).
@@ -411,14 +513,16 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, float *smem, const 
                 const int row = m0 + wm * T::WTM + i * 32 + 8 * (r / 4) + 4 * h + (r % 4);
                 if (!FAST && row >= g.M) continue;
                 epilogue_store<EPI>(g, (size_t)row * g.ldc + col, acc[i][j][r], bias,
-                                    pre_w[PRE_W ? i : 0][PRE_W ? j : 0][r], pre_v[PRE_V ? i : 0][PRE_V ? j : 0][r]);
+                                    pre_w[PRE_W ? i : 0][PRE_W ? j : 0][r],
+                                    (EPI == EPI_GRAD_MOMENTUM && !PRE_V) ? g.V[(size_t)row * g.ldc + col]
+                                                                         : pre_v[PRE_V ? i : 0][PRE_V ? j : 0][r]);
             }
         }
     }
 }
 
 template <class T, bool A_KC, bool B_KC, int EPI, bool VEC>
-__global__ __launch_bounds__(T::NT) void gemm_kernel(GemmArgs g, int tiles_m, int tiles_n)
+__global__ __launch_bounds__(T::NT, T::OCC) void gemm_kernel(GemmArgs g, int tiles_m, int tiles_n)
 {
     extern __shared__ __attribute__((aligned(16))) float smem[];
     // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous
@@ -464,18 +568,19 @@ static hipError_t launch_vec(const GemmArgs &a, hipStream_t stream)
     return hipGetLastError();
 }
 
-//                BM   BN  KT  WM WN WK R
-using V0 = Tile<128, 128, 16, 2, 2, 1, 1>;  // short k, many tiles: weight gradients
-using V1 = Tile<128, 64, 16, 2, 2, 1, 2>;   // large batch x width products
+//                BM   BN  KT  WM WN WK R  PC
+using V0 = Tile<128, 128, 16, 2, 2, 1, 1>;      // short k, many tiles: weight gradients of small batches
+using V1 = Tile<128, 64, 16, 2, 2, 1, 2>;       // large batch x width products
 using V2 = Tile<64, 64, 64, 1, 1, 4, 2>;
 using V3 = Tile<64, 64, 32, 1, 1, 4, 2>;
-using V4 = Tile<32, 64, 32, 1, 1, 4, 2>;    // batch of a few hundred x width
+using V4 = Tile<32, 64, 32, 1, 1, 4, 2>;        // batch of a few hundred x width
 using V5 = Tile<32, 64, 64, 1, 1, 8, 2>;
-using V6 = Tile<32, 32, 64, 1, 1, 8, 2>;    // few output tiles: lean on the k split
+using V6 = Tile<32, 32, 64, 1, 1, 8, 2>;        // few output tiles: lean on the k split
+using V7 = Tile<128, 128, 16, 2, 2, 1, 2, 16>;  // weight gradients: epilogue operands fetched over 16 k steps
 
-static const char *kVariantNames[] = {"128x128x16_r1", "128x64x16_r2",   "64x64x64_k4_r2", "64x64x32_k4_r2",
-                                      "32x64x32_k4_r2", "32x64x64_k8_r2", "32x32x64_k8_r2"};
-constexpr int kVariants = 7;
+static const char *kVariantNames[] = {"128x128x16_r1",  "128x64x16_r2",   "64x64x64_k4_r2", "64x64x32_k4_r2",
+                                      "32x64x32_k4_r2", "32x64x64_k8_r2", "32x32x64_k8_r2", "128x128x16_r2_pc16"};
+constexpr int kVariants = 8;
 int gemm_variant_count() { return kVariants; }
 const char *gemm_variant_name(int v) { return (v >= 0 && v < kVariants) ? kVariantNames[v] : "?"; }
 
@@ -514,10 +619,9 @@ static hipError_t launch_kind(GemmKind kind, const GemmArgs &a, hipStream_t stre
 static int pick_variant(const GemmArgs &a)
 {
     auto tiles = [&](int bm, int bn) { return (long)((a.M + bm - 1) / bm) * ((a.N + bn - 1) / bn); };
-    if (a.K <= 512 && tiles(128, 128) >= 256) return 0;
+    if (a.K <= 512 && tiles(128, 128) >= 256) return a.K >= 192 ? 7 : 0;
     if (tiles(128, 64) >= 256) return 1;
     if (tiles(32, 64) >= 256) return 4;
-    if (tiles(32, 64) >= 128) return 5;
     return 6;
 }
 
@@ -533,6 +637,7 @@ hipError_t launch_gemm(GemmKind kind, const GemmArgs &a, int variant, hipStream_
     case 4: return launch_kind<V4>(kind, a, stream);
     case 5: return launch_kind<V5>(kind, a, stream);
     case 6: return launch_kind<V6>(kind, a, stream);
+    case 7: return launch_kind<V7>(kind, a, stream);
     default: return hipErrorInvalidValue;
     }
 }

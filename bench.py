@@ -141,11 +141,20 @@ def main():
                             "unit": "TFLOP/s", "frac": ach / PEAK_MFMA_F32_TFLOPS, "traffic": None,
                             "avg_launch_us": per_launch_ms * 1e3, "launches": classes[dom]["launches"]}
         else:
+            # every kernel of a step streams the parameters, so the whole step is the unit:
+            # algorithmic bytes of the timed steps / summed duration of their launches
             total_ms = sum(c["ms"] for c in classes.values())
+            if "online" in classes:          # one persistent launch covers the whole pass
+                timed_steps = last_steps
+            else:                            # per-launch events stop after a fixed number of launches
+                timed_steps = min(last_steps, classes["forward"]["launches"] // (len(w.widths) - 1))
             if total_ms > 0:
-                ach = step_bytes * last_steps / (total_ms * 1e-3) / 1e9
-                roofline = {"bound": "hbm", "kernel": "all kernels of a step", "achieved": ach,
-                            "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS, "traffic": None}
+                ach = step_bytes * timed_steps / (total_ms * 1e-3) / 1e9
+                roofline = {"bound": "hbm", "kernel": "online_epoch_kernel" if "online" in classes
+                            else "all kernels of a step", "achieved": ach,
+                            "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS, "traffic": None,
+                            "avg_launch_us": total_ms * 1e3 / sum(c["launches"] for c in classes.values()),
+                            "timed_steps": timed_steps}
 
     cpu = None
     if not args.no_cpu_baseline:

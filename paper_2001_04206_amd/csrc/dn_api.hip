@@ -24,6 +24,7 @@ struct Layout {
     std::vector<size_t> A, D;   // activations / deltas of layers 1..L, absolute
     size_t off_params = 0, off_vel = 0, off_grads = 0;
     size_t off_loss_rows = 0, off_scalars = 0;
+    size_t off_online = 0, online_bytes = 0;   // exchange buffers of the persistent batch-1 kernel
     size_t total = 0;
 };
 
@@ -62,6 +63,8 @@ bool compute_layout(const int32_t *widths, int32_t n_widths, int32_t max_batch, 
     }
     lo.off_loss_rows = o; o += align_up((size_t)max_batch * sizeof(float));
     lo.off_scalars = o; o += kAlign;
+    lo.online_bytes = online_exchange_bytes_bound(widths, L);
+    lo.off_online = o; o += align_up(lo.online_bytes);
     lo.total = o;
     return true;
 }
@@ -87,7 +90,12 @@ struct dn_net {
     int fwd_batch = 0;
     bool have_fwd = false, have_bwd = false;
     // options
-    int time_kernels = 0, gemm_variant = -1, online_mode = 0;
+    int time_kernels = 0, gemm_variant = -1, online_mode = 0, online_min_tile = ON_DEFAULT_MIN_TILE;
+    // persistent batch-1 kernel
+    OnlineGeom geom{};
+    bool online_ok = false;
+    uint32_t online_seq = 0;   // last step number stamped into the exchange buffers
+    int device_cus = 0;
     // timing
     hipEvent_t ev_epoch0 = nullptr, ev_epoch1 = nullptr;
     std::vector<TimedLaunch> pool;
@@ -106,6 +114,8 @@ struct dn_net {
     float *D(int l) const { return (float *)(arena + lo.D[l]); }
     float *loss_rows() const { return (float *)(arena + lo.off_loss_rows); }
     double *epoch_acc() const { return (double *)(arena + lo.off_scalars); }
+    int *abort_flag() const { return (int *)(arena + lo.off_scalars + sizeof(double)); }
+    unsigned long long *exchange() const { return (unsigned long long *)(arena + lo.off_online); }
 };
 
 namespace {
@@ -203,6 +213,47 @@ dn_status run_backward(dn_net *net, const float *X, int B, int mode, float lr, f
     return DN_OK;
 }
 
+// A whole batch-1 epoch in persistent-kernel launches of at most 2^30 steps each.
+dn_status run_online(dn_net *net, const float *X, const int32_t *labels, int64_t n_samples, float lr, float mu,
+                     bool timing)
+{
+    const OnlineGeom &g = net->geom;
+    const int L = net->L;
+    OnlinePlan p{};
+    p.L = L;
+    for (int l = 1; l <= L; ++l) {
+        OnlineLayer &y = p.layer[l];
+        y.W = net->W(l); y.b = net->b(l); y.VW = net->VW(l); y.Vb = net->Vb(l);
+        y.n_in = net->n[l - 1]; y.n_out = net->n[l]; y.act = net->act[l];
+        y.per = g.per[l]; y.P = g.P[l]; y.kf = g.kf[l]; y.seg = g.seg[l]; y.vec4 = g.vec4[l];
+        p.act_x[l] = net->exchange() + g.off_act[l];
+        p.part_x[l] = net->exchange() + g.off_part[l];
+        p.lds_a[l] = g.lds_a[l]; p.lds_own_a[l] = g.lds_own_a[l]; p.lds_own_d[l] = g.lds_own_d[l];
+    }
+    p.z_x = net->exchange() + g.off_z;
+    p.abort_flag = net->abort_flag();
+    p.loss_acc = net->epoch_acc();
+    p.lr = lr; p.mu = mu; p.loss = net->loss;
+    p.lds_x = g.lds_x; p.lds_out = g.lds_out; p.lds_kpart = g.lds_kpart; p.lds_tmp = g.lds_tmp;
+    const int64_t chunk = (int64_t)1 << 30;
+    for (int64_t s0 = 0; s0 < n_samples; s0 += chunk) {
+        const int64_t n = (n_samples - s0) < chunk ? (n_samples - s0) : chunk;
+        if ((uint64_t)net->online_seq + (uint64_t)n + 2 > 0xffffffffull) {   // step numbers would wrap
+            DN_HIP(hipMemsetAsync(net->exchange(), 0, net->lo.online_bytes, net->stream));
+            net->online_seq = 0;
+        }
+        p.X = X + (size_t)s0 * net->n[0];
+        p.labels = labels + s0;
+        p.n_samples = n;
+        p.keep_v = (s0 + n >= n_samples) ? 1 : 0;
+        p.seq0 = net->online_seq;
+        ScopedTimer st(net, DN_K_ONLINE, timing);
+        DN_HIP(launch_online_epoch(g, p, net->stream));
+        net->online_seq += (uint32_t)n;
+    }
+    return DN_OK;
+}
+
 void collect_times(dn_net *net)
 {
     for (int c = 0; c < DN_K_CLASSES; ++c) {
@@ -280,9 +331,19 @@ dn_status dn_net_create(const int32_t *widths, int32_t n_widths, const dn_act *a
     net->max_batch = max_batch;
     net->arena = (char *)arena_dev;
     net->stream = (hipStream_t)hip_stream;
-    // parameters, velocities and gradients start at zero
+    // persistent batch-1 kernel: slices per workgroup, if the net fits it and the device has the units
+    if (lo.online_bytes > 0 && online_geometry(net->n.data(), L, net->online_min_tile, net->geom)) {
+        int dev = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&net->device_cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess)
+            net->online_ok = net->geom.grid <= net->device_cus && online_prepare(net->geom) == hipSuccess;
+        (void)hipGetLastError();
+    }
+    // parameters, velocities and gradients start at zero; exchange words start unstamped
     if (hipMemsetAsync(net->arena, 0, 3 * lo.region, net->stream) != hipSuccess ||
         hipMemsetAsync(net->arena + lo.off_scalars, 0, kAlign, net->stream) != hipSuccess ||
+        (lo.online_bytes > 0 &&
+         hipMemsetAsync(net->arena + lo.off_online, 0, lo.online_bytes, net->stream) != hipSuccess) ||
         hipEventCreate(&net->ev_epoch0) != hipSuccess || hipEventCreate(&net->ev_epoch1) != hipSuccess ||
         hipStreamSynchronize(net->stream) != hipSuccess) {
         if (net->ev_epoch0) (void)hipEventDestroy(net->ev_epoch0);
@@ -402,9 +463,15 @@ dn_status dn_train_epoch(dn_net *net, const float *X_dev, const int32_t *labels_
     const bool timing = net->time_kernels != 0;
     net->timed = 0;
     const int L = net->L;
-    DN_HIP(hipMemsetAsync(net->epoch_acc(), 0, sizeof(double), net->stream));
+    const bool persistent = batch == 1 && net->online_mode != 1 && net->online_ok;
+    if (batch == 1 && net->online_mode == 2 && !net->online_ok) return DN_ERR_UNSUPPORTED;
+    DN_HIP(hipMemsetAsync(net->epoch_acc(), 0, sizeof(double) + sizeof(int), net->stream));
     DN_HIP(hipEventRecord(net->ev_epoch0, net->stream));
-    for (int64_t s0 = 0; s0 < n_samples; s0 += batch) {
+    if (persistent) {
+        dn_status st = run_online(net, X_dev, labels_dev, n_samples, lr, momentum, timing);
+        if (st != DN_OK) return st;
+    }
+    for (int64_t s0 = persistent ? n_samples : 0; s0 < n_samples; s0 += batch) {
         const int B = (int)((n_samples - s0) < batch ? (n_samples - s0) : batch);
         const float *Xb = X_dev + (size_t)s0 * net->n[0];
         const bool last = s0 + batch >= n_samples;
@@ -421,11 +488,13 @@ dn_status dn_train_epoch(dn_net *net, const float *X_dev, const int32_t *labels_
         if (st != DN_OK) return st;
     }
     DN_HIP(hipEventRecord(net->ev_epoch1, net->stream));
-    double acc = 0.0;
-    DN_HIP(hipMemcpyAsync(&acc, net->epoch_acc(), sizeof(double), hipMemcpyDeviceToHost, net->stream));
+    struct { double acc; int aborted; int pad; } res = {0.0, 0, 0};
+    DN_HIP(hipMemcpyAsync(&res, net->epoch_acc(), sizeof(double) + sizeof(int), hipMemcpyDeviceToHost, net->stream));
     DN_HIP(hipStreamSynchronize(net->stream));
     DN_HIP(hipEventElapsedTime(&net->epoch_ms, net->ev_epoch0, net->ev_epoch1));
     collect_times(net);
+    if (res.aborted) return DN_ERR_DEVICE;   // a workgroup of the persistent kernel gave up waiting
+    const double acc = res.acc;
     if (mean_loss_host) *mean_loss_host = (float)(acc / (double)n_samples);
     return DN_OK;
 }
@@ -457,6 +526,16 @@ dn_status dn_set_option(dn_net *net, const char *name, int64_t value)
     } else if (!strcmp(name, "online_mode")) {
         if (value < 0 || value > 2) return DN_ERR_INVALID_ARG;
         net->online_mode = (int)value;
+    } else if (!strcmp(name, "online_min_tile")) {
+        if (value < 1 || value > ((int64_t)1 << 30) || net->lo.online_bytes == 0) return DN_ERR_INVALID_ARG;
+        OnlineGeom g;
+        if (!online_geometry(net->n.data(), net->L, (int)value, g) || g.grid > net->device_cus ||
+            online_prepare(g) != hipSuccess)
+            return DN_ERR_INVALID_ARG;
+        if (hipStreamSynchronize(net->stream) != hipSuccess) return DN_ERR_DEVICE;
+        net->geom = g;
+        net->online_min_tile = (int)value;
+        net->online_ok = true;
     } else {
         return DN_ERR_INVALID_ARG;
     }

@@ -71,4 +71,59 @@ hipError_t launch_update(float *p, float *v, const float *g, size_t count, float
                          hipStream_t stream);
 hipError_t launch_copy(float *dst, const float *src, size_t count, hipStream_t stream);
 
+// ---- persistent batch-1 epoch kernel (dn_online.hip) ----------------------------
+constexpr int ON_MAX_L = 8;         // layers
+constexpr int ON_MAX_WG = 256;      // workgroups (one per compute unit)
+constexpr int ON_MAX_NL = 128;      // width of the output layer
+constexpr int ON_THREADS = 512;     // threads per workgroup
+constexpr int ON_TMP_FLOATS = 4096; // reduction scratch in LDS
+constexpr size_t ON_MAX_LDS_BYTES = 144 * 1024;
+constexpr int ON_DEFAULT_MIN_TILE = 4096;  // weights a workgroup should own per layer before rows are spread further
+
+// How the layers are cut into per-workgroup slices, where the exchange buffers sit inside
+// the exchange region (in 64-bit words) and where each piece of LDS starts (in floats).
+struct OnlineGeom {
+    bool ok;
+    int L, grid;
+    int per[ON_MAX_L + 1];    // rows per workgroup (layers < L); columns per workgroup (layer L)
+    int P[ON_MAX_L + 1];      // workgroups that own a slice of the layer
+    int kf[ON_MAX_L + 1];     // forward: segments a row's dot product is split into
+    int seg[ON_MAX_L + 1];    // forward: segment length
+    int vec4[ON_MAX_L + 1];   // rows are whole float4s
+    size_t off_act[ON_MAX_L + 1], off_part[ON_MAX_L + 1], off_z, words;
+    int lds_x, lds_a[ON_MAX_L + 1], lds_own_a[ON_MAX_L + 1], lds_own_d[ON_MAX_L + 1];
+    int lds_out, lds_kpart, lds_tmp, lds_floats;
+};
+
+struct OnlineLayer {
+    float *W, *b, *VW, *Vb;
+    int n_in, n_out, act, per, P, kf, seg, vec4;
+};
+
+struct OnlinePlan {
+    int L;
+    OnlineLayer layer[ON_MAX_L + 1];            // 1..L
+    unsigned long long *act_x[ON_MAX_L + 1];    // [2][n_l]            activations of layers 1..L-2
+    unsigned long long *part_x[ON_MAX_L + 1];   // [2][P_l][n_{l-1}]   partials of W_l^T delta_l, l = 2..L-1
+    unsigned long long *z_x;                    // [2][P_L][n_L]       partials of the output net inputs
+    int *abort_flag;
+    double *loss_acc;
+    const float *X;
+    const int32_t *labels;
+    int64_t n_samples;
+    float lr, mu;
+    int loss, keep_v;
+    uint32_t seq0;                              // step numbers seq0+1 .. seq0+n_samples stamp the exchange words
+    int lds_x, lds_a[ON_MAX_L + 1], lds_own_a[ON_MAX_L + 1], lds_own_d[ON_MAX_L + 1];
+    int lds_out, lds_kpart, lds_tmp;
+};
+
+// Slices and buffer offsets for widths n[0..L]; false if the net does not fit the kernel
+// (too many layers, output layer too wide, LDS).
+bool online_geometry(const int32_t *n, int L, int min_tile, OnlineGeom &g);
+// Upper bound of the exchange region in bytes for any min_tile (0 if the net can never fit).
+size_t online_exchange_bytes_bound(const int32_t *n, int L);
+hipError_t online_prepare(const OnlineGeom &g);
+hipError_t launch_online_epoch(const OnlineGeom &g, const OnlinePlan &plan, hipStream_t stream);
+
 }  // namespace dn

@@ -1,0 +1,784 @@
+// Per-sample (batch 1) training as ONE persistent kernel per epoch.
+//
+// With one sample per step every phase of back propagation is a matrix-vector
+// product that depends on the previous phase, and the next step depends on this
+// step's update, so a step is a chain of short phases.  Launching a kernel per
+// phase makes the chain cost a launch per link.  Here up to 256 workgroups (one
+// per compute unit) stay resident for the whole epoch and each OWNS a fixed slice
+// of every layer:
+//
+//   layers 1..L-1   a block of rows of W_l (a block of that layer's neurons):
+//                   forward   a_l[rows]   = f(W_l[rows,:] a_{l-1} + b_l[rows])   (needs all of a_{l-1})
+//                   backward  one sweep over the same rows reads each weight once and
+//                             (i) adds W_l[r,:] delta_l[r] into this workgroup's partial of W_l^T delta_l,
+//                             (ii) writes W_l[r,:] - lr delta_l[r] a_{l-1}  -- the two-index
+//                             (inputs x outputs) loop the paper offloads, fused with the update
+//   layer L         the block of COLUMNS of W_L that matches its rows of layer L-1
+//                   (its own hidden units feed these columns), so the last layer needs
+//                   no input exchange: forward gives a partial of z_L (n_L numbers),
+//                   backward gives delta_{L-1} for its own units directly.
+//
+// What has to cross between workgroups is small: the activations of layers
+// 1..L-2, one n_L-vector of partial net inputs per workgroup, and the partials of
+// W_l^T delta_l for l = 2..L-1.  It is exchanged through device memory as 64-bit
+// words {value, step number}: a consumer polls the word until the step number is
+// the current one, so publishing and signalling are a single store and a single
+// load apart (no grid-wide barrier).  Two copies of every exchange buffer, used
+// on alternating steps, keep a fast producer from overwriting a word a slow
+// consumer has not read yet: before a workgroup publishes step s+2 it has
+// consumed data that every one of its consumers published after they finished
+// reading step s.
+//
+// Every wait is bounded: a poll that does not complete within kSpinLimit
+// attempts raises an abort flag that ends every workgroup, and the host reports
+// DN_ERR_DEVICE.  All sums are taken in a fixed order, so an epoch is
+// reproducible bit for bit.
+#include <algorithm>
+
+#include "dn_internal.h"
+
+namespace dn {
+namespace {
+
+typedef unsigned long long u64;
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+constexpr int kThreads = ON_THREADS;
+constexpr int kWaves = kThreads / 64;
+constexpr int kSpinLimit = 1 << 21;   // polls of ~0.5 us each: about a second
+constexpr int kPollBatch = 4;         // words each thread keeps in flight while polling
+constexpr int kTmp = ON_TMP_FLOATS;
+
+enum UpdMode : int { UPD_SGD = 0, UPD_KEEPV = 1, UPD_MOMENTUM = 2 };
+
+__device__ __forceinline__ void ll_store(u64 *p, float v, uint32_t seq)
+{
+    const u64 word = ((u64)seq << 32) | (u64)__float_as_uint(v);
+    __hip_atomic_store(p, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ u64 ll_load(const u64 *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+__device__ __forceinline__ float act_fn(int act, float z)
+{
+    switch (act) {
+    case DN_ACT_SIGMOID: return 1.0f / (1.0f + expf(-z));
+    case DN_ACT_TANH: return tanhf(z);
+    case DN_ACT_RELU: return z > 0.0f ? z : 0.0f;
+    default: return z;
+    }
+}
+
+__device__ __forceinline__ float act_deriv(int act, float a)
+{
+    switch (act) {
+    case DN_ACT_SIGMOID: return a * (1.0f - a);
+    case DN_ACT_TANH: return 1.0f - a * a;
+    case DN_ACT_RELU: return a > 0.0f ? 1.0f : 0.0f;
+    default: return 1.0f;
+    }
+}
+
+// dW = mu dW - g ; w += dW, with g already scaled by the learning rate.
+__device__ __forceinline__ float apply_update(float w, float g, float &v, float mu, int mode)
+{
+    if (mode == UPD_SGD) return w - g;
+    v = (mode == UPD_MOMENTUM) ? mu * v - g : -g;
+    return w + v;
+}
+
+// Polls `total` exchange words; word q lives at addr(q) and its value goes to sink(q, value).
+// Each thread keeps kPollBatch loads in flight and re-reads only the words that are not
+// yet stamped with `seq`.  On a timeout (or when another workgroup has already given up)
+// *s_abort is set; the caller tests it after its next barrier.
+template <class Addr, class Sink>
+__device__ __forceinline__ void poll_words(int total, uint32_t seq, Addr addr, Sink sink, int *abort_flag,
+                                           volatile int *s_abort)
+{
+    for (int q0 = threadIdx.x; q0 < total; q0 += kThreads * kPollBatch) {
+        u64 v[kPollBatch];
+        bool ok[kPollBatch];
+#pragma unroll
+        for (int u = 0; u < kPollBatch; ++u) {
+            const int q = q0 + u * kThreads;
+            v[u] = ll_load(addr(q < total ? q : q0));
+        }
+        bool all = true;
+#pragma unroll
+        for (int u = 0; u < kPollBatch; ++u) {
+            ok[u] = (q0 + u * kThreads >= total) || (uint32_t)(v[u] >> 32) == seq;
+            all = all && ok[u];
+        }
+        int spins = 0;
+        while (!all) {
+            all = true;
+#pragma unroll
+            for (int u = 0; u < kPollBatch; ++u) {
+                if (!ok[u]) {
+                    v[u] = ll_load(addr(q0 + u * kThreads));
+                    ok[u] = (uint32_t)(v[u] >> 32) == seq;
+                    all = all && ok[u];
+                }
+            }
+            if (all) break;
+            ++spins;
+            if (spins > kSpinLimit) {
+                __hip_atomic_store(abort_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                *s_abort = 1;
+                break;
+            }
+            if ((spins & 255) == 0 &&
+                __hip_atomic_load(abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+                *s_abort = 1;
+                break;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kPollBatch; ++u) {
+            const int q = q0 + u * kThreads;
+            if (q < total) sink(q, __uint_as_float((uint32_t)v[u]));
+        }
+    }
+}
+
+// out[e] = sum over w < P of the word at src[w * stride + base + e], e < count, summed in a
+// fixed order: 16 lanes per element each add every 16th partial, then a 4-step butterfly.
+// `scale_fn(e, sum)` finishes the element.  tmp holds kTmp floats.  Ends with a barrier.
+template <class Finish>
+__device__ __forceinline__ void gather_partials(const u64 *src, int P, int stride, int base, int count,
+                                                uint32_t seq, float *tmp, Finish finish, int *abort_flag,
+                                                volatile int *s_abort)
+{
+    const int ecap = kTmp / P;   // elements per pass (P <= ON_MAX_WG <= kTmp)
+    for (int e0 = 0; e0 < count; e0 += ecap) {
+        const int ne = min(ecap, count - e0);
+        poll_words(
+            ne * P, seq,
+            [&](int q) { const int ww = q / ne, e = q - ww * ne; return src + (size_t)ww * stride + base + e0 + e; },
+            [&](int q, float val) { const int ww = q / ne, e = q - ww * ne; tmp[e * P + ww] = val; },
+            abort_flag, s_abort);
+        __syncthreads();
+        const int g = threadIdx.x & 15;
+        for (int e = threadIdx.x >> 4; e < ne; e += kThreads / 16) {
+            float s = 0.f;
+            for (int ww = g; ww < P; ww += 16) s += tmp[e * P + ww];
+            s += __shfl_xor(s, 8, 16);
+            s += __shfl_xor(s, 4, 16);
+            s += __shfl_xor(s, 2, 16);
+            s += __shfl_xor(s, 1, 16);
+            if (g == 0) finish(e0 + e, s);
+        }
+        __syncthreads();
+    }
+}
+
+// Forward of a block of rows: kpart[r * kf + ks] = sum over segment ks of W[r0 + r][k] xin[k].
+// One wave per (row, segment); a wave works on four of them at a time so that their loads
+// are in flight together.  Loads are unconditional (clamped addresses, masked values).
+template <int VEC>
+__device__ __forceinline__ void fwd_rows(const float *__restrict__ W, int n_in, int r0, int nr, int kf, int seg,
+                                         const float *xin, float *kpart)
+{
+    constexpr int RU = 4;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int items = nr * kf;
+    for (int it0 = wave; it0 < items; it0 += kWaves * RU) {
+        float acc[RU];
+        const float *wp[RU];
+        int kbeg[RU], kend[RU];
+#pragma unroll
+        for (int u = 0; u < RU; ++u) {
+            const int it = it0 + u * kWaves;
+            const bool on = it < items;
+            const int r = on ? it / kf : 0;
+            const int ks = on ? it - r * kf : 0;
+            kbeg[u] = ks * seg;
+            kend[u] = on ? min(n_in, kbeg[u] + seg) : 0;
+            wp[u] = W + (size_t)(r0 + r) * n_in;
+            acc[u] = 0.f;
+        }
+        for (int kk = lane * VEC; kk < seg; kk += 64 * VEC) {
+#pragma unroll
+            for (int u = 0; u < RU; ++u) {
+                const int k = kbeg[u] + kk;
+                const bool in = k < kend[u];
+                const int kc = in ? k : 0;
+                if (VEC == 4) {
+                    const v4f wv = *(const v4f *)(wp[u] + kc);
+                    const v4f xv = *(const v4f *)(xin + kc);
+                    const float d = wv.x * xv.x + wv.y * xv.y + wv.z * xv.z + wv.w * xv.w;
+                    acc[u] += in ? d : 0.f;
+                } else {
+                    const float d = wp[u][kc] * xin[kc];
+                    acc[u] += in ? d : 0.f;
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < RU; ++u) {
+            const float s = wave_sum(acc[u]);
+            const int it = it0 + u * kWaves;
+            if (lane == 0 && it < items) kpart[it] = s;
+        }
+    }
+}
+
+// Backward sweep over a block of rows of a layer whose input layer needs a delta:
+// every weight is read once; s[k] accumulates W[r][k] delta[r] over the block's rows and the
+// weight is rewritten with the update.  Waves split the columns in chunks of 64*VEC and,
+// when there are fewer chunks than waves, the rows as well (partials meet in sred).
+// The block's partial of W^T delta is published to part_out[k], k < n_in.
+template <int VEC>
+__device__ __forceinline__ void bwd_rows(float *__restrict__ W, float *__restrict__ V, int n_in, int r0, int nr,
+                                         const float *dl, const float *ain, float lr, float mu, int mode,
+                                         float *sred, u64 *part_out, uint32_t seq)
+{
+    constexpr int RU = 4;
+    constexpr int CW = 64 * VEC;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int C = (n_in + CW - 1) / CW;
+    int RG, rg, c_first, c_step;
+    if (C >= kWaves) {
+        RG = 1; rg = 0; c_first = wave; c_step = kWaves;
+    } else {
+        RG = kWaves / C; rg = wave / C; c_first = wave - rg * C; c_step = C;   // one chunk per wave
+        if (rg >= RG) c_first = C;                                             // spare waves idle
+    }
+    for (int c = c_first; c < C; c += c_step) {
+        const int k = c * CW + lane * VEC;
+        const bool kin = k < n_in;
+        const int kc = kin ? k : 0;
+        float a[VEC], s[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) { a[e] = ain[kc + e]; s[e] = 0.f; }
+        for (int r = rg; r < nr; r += RG * RU) {
+            float wv[RU][VEC], vv[RU][VEC];
+#pragma unroll
+            for (int u = 0; u < RU; ++u) {
+                const int ru = r + u * RG;
+                const int rc = ru < nr ? ru : r;
+                const float *wp = W + (size_t)(r0 + rc) * n_in + kc;
+                if (VEC == 4) {
+                    const v4f t = *(const v4f *)wp;
+                    wv[u][0] = t.x; wv[u][1 % VEC] = t.y; wv[u][2 % VEC] = t.z; wv[u][3 % VEC] = t.w;
+                } else {
+                    wv[u][0] = wp[0];
+                }
+            }
+            if (mode == UPD_MOMENTUM) {
+#pragma unroll
+                for (int u = 0; u < RU; ++u) {
+                    const int ru = r + u * RG;
+                    const int rc = ru < nr ? ru : r;
+                    const float *vp = V + (size_t)(r0 + rc) * n_in + kc;
+                    if (VEC == 4) {
+                        const v4f t = *(const v4f *)vp;
+                        vv[u][0] = t.x; vv[u][1 % VEC] = t.y; vv[u][2 % VEC] = t.z; vv[u][3 % VEC] = t.w;
+                    } else {
+                        vv[u][0] = vp[0];
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int u = 0; u < RU; ++u)
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) vv[u][e] = 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < RU; ++u) {
+                const int ru = r + u * RG;
+                if (ru < nr) {
+                    const float d = dl[ru];
+                    const float ld = lr * d;
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) {
+                        s[e] += wv[u][e] * d;
+                        wv[u][e] = apply_update(wv[u][e], ld * a[e], vv[u][e], mu, mode);
+                    }
+                    if (kin) {
+                        float *wp = W + (size_t)(r0 + ru) * n_in + k;
+                        float *vp = V + (size_t)(r0 + ru) * n_in + k;
+                        if (VEC == 4) {
+                            v4f t; t.x = wv[u][0]; t.y = wv[u][1 % VEC]; t.z = wv[u][2 % VEC]; t.w = wv[u][3 % VEC];
+                            *(v4f *)wp = t;
+                            if (mode != UPD_SGD) {
+                                v4f q; q.x = vv[u][0]; q.y = vv[u][1 % VEC]; q.z = vv[u][2 % VEC]; q.w = vv[u][3 % VEC];
+                                *(v4f *)vp = q;
+                            }
+                        } else {
+                            wp[0] = wv[u][0];
+                            if (mode != UPD_SGD) vp[0] = vv[u][0];
+                        }
+                    }
+                }
+            }
+        }
+        if (kin) {
+            if (RG == 1) {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) ll_store(part_out + k + e, s[e], seq);
+            } else {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) sred[rg * n_in + k + e] = s[e];
+            }
+        }
+    }
+    if (RG > 1) {
+        __syncthreads();
+        for (int j = threadIdx.x; j < n_in; j += kThreads) {
+            float t = 0.f;
+            for (int g = 0; g < RG; ++g) t += sred[g * n_in + j];
+            ll_store(part_out + j, t, seq);
+        }
+    }
+}
+
+// Backward of a block of rows of the first layer (no delta is needed for the input): the
+// block is a contiguous run of nr * n_in weights, updated in place.
+template <int VEC>
+__device__ __forceinline__ void bwd_flat(float *__restrict__ W, float *__restrict__ V, int n_in, int r0, int nr,
+                                         const float *dl, const float *ain, float lr, float mu, int mode)
+{
+    constexpr int RU = 4;
+    float *Wb = W + (size_t)r0 * n_in;
+    float *Vb = V + (size_t)r0 * n_in;
+    const int total = nr * n_in;
+    for (int i0 = threadIdx.x * VEC; i0 < total; i0 += kThreads * VEC * RU) {
+        float wv[RU][VEC], vv[RU][VEC];
+#pragma unroll
+        for (int u = 0; u < RU; ++u) {
+            const int i = i0 + u * kThreads * VEC;
+            const int ic = i < total ? i : i0;
+            if (VEC == 4) {
+                const v4f t = *(const v4f *)(Wb + ic);
+                wv[u][0] = t.x; wv[u][1 % VEC] = t.y; wv[u][2 % VEC] = t.z; wv[u][3 % VEC] = t.w;
+            } else {
+                wv[u][0] = Wb[ic];
+            }
+        }
+        if (mode == UPD_MOMENTUM) {
+#pragma unroll
+            for (int u = 0; u < RU; ++u) {
+                const int i = i0 + u * kThreads * VEC;
+                const int ic = i < total ? i : i0;
+                if (VEC == 4) {
+                    const v4f t = *(const v4f *)(Vb + ic);
+                    vv[u][0] = t.x; vv[u][1 % VEC] = t.y; vv[u][2 % VEC] = t.z; vv[u][3 % VEC] = t.w;
+                } else {
+                    vv[u][0] = Vb[ic];
+                }
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < RU; ++u)
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) vv[u][e] = 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < RU; ++u) {
+            const int i = i0 + u * kThreads * VEC;
+            if (i < total) {
+                const int r = (int)((unsigned)i / (unsigned)n_in);
+                const int k = i - r * n_in;
+                const float ld = lr * dl[r];
+#pragma unroll
+                for (int e = 0; e < VEC; ++e)
+                    wv[u][e] = apply_update(wv[u][e], ld * ain[k + e], vv[u][e], mu, mode);
+                if (VEC == 4) {
+                    v4f t; t.x = wv[u][0]; t.y = wv[u][1 % VEC]; t.z = wv[u][2 % VEC]; t.w = wv[u][3 % VEC];
+                    *(v4f *)(Wb + i) = t;
+                    if (mode != UPD_SGD) {
+                        v4f q; q.x = vv[u][0]; q.y = vv[u][1 % VEC]; q.z = vv[u][2 % VEC]; q.w = vv[u][3 % VEC];
+                        *(v4f *)(Vb + i) = q;
+                    }
+                } else {
+                    Wb[i] = wv[u][0];
+                    if (mode != UPD_SGD) Vb[i] = vv[u][0];
+                }
+            }
+        }
+    }
+}
+
+// Last layer, forward: this workgroup's partial of z_L from its own columns c0..c0+nc of W_L.
+__device__ __forceinline__ void fwd_cols(const float *__restrict__ W, int n_in, int nL, int c0, int nc,
+                                         const float *a_own, u64 *zout, uint32_t seq)
+{
+    constexpr int JU = 4;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    for (int k = wave; k < nL; k += kWaves) {
+        const float *wp = W + (size_t)k * n_in + c0;
+        float acc = 0.f;
+        for (int j0 = lane; j0 < nc; j0 += 64 * JU) {
+            float wv[JU];
+#pragma unroll
+            for (int u = 0; u < JU; ++u) {
+                const int j = j0 + u * 64;
+                wv[u] = wp[j < nc ? j : j0];
+            }
+#pragma unroll
+            for (int u = 0; u < JU; ++u) {
+                const int j = j0 + u * 64;
+                acc += j < nc ? wv[u] * a_own[j] : 0.f;
+            }
+        }
+        acc = wave_sum(acc);
+        if (lane == 0) ll_store(zout + k, acc, seq);
+    }
+}
+
+// Last layer, backward: for each own column j: s_j = sum_k W_L[k][j] delta_L[k] from the
+// weights before the update, then the column is updated.  d_own[j] = s_j f'(a_own[j]) when
+// a previous layer exists.
+__device__ __forceinline__ void bwd_cols(float *__restrict__ W, float *__restrict__ V, int n_in, int nL, int c0,
+                                         int nc, const float *a_own, const float *dL, float lr, float mu,
+                                         int mode, float *d_own, int act_prev)
+{
+    constexpr int KB = 16;
+    for (int j = threadIdx.x; j < nc; j += kThreads) {
+        const float a = a_own[j];
+        float s = 0.f;
+        for (int k0 = 0; k0 < nL; k0 += KB) {
+            float wv[KB], vv[KB];
+#pragma unroll
+            for (int u = 0; u < KB; ++u) {
+                const int k = min(k0 + u, nL - 1);
+                wv[u] = W[(size_t)k * n_in + c0 + j];
+            }
+            if (mode == UPD_MOMENTUM) {
+#pragma unroll
+                for (int u = 0; u < KB; ++u) {
+                    const int k = min(k0 + u, nL - 1);
+                    vv[u] = V[(size_t)k * n_in + c0 + j];
+                }
+            } else {
+#pragma unroll
+                for (int u = 0; u < KB; ++u) vv[u] = 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < KB; ++u) {
+                const int k = k0 + u;
+                if (k < nL) {
+                    const float d = dL[k];
+                    s += wv[u] * d;
+                    const float nw = apply_update(wv[u], (lr * d) * a, vv[u], mu, mode);
+                    W[(size_t)k * n_in + c0 + j] = nw;
+                    if (mode != UPD_SGD) V[(size_t)k * n_in + c0 + j] = vv[u];
+                }
+            }
+        }
+        if (d_own) d_own[j] = s * act_deriv(act_prev, a);
+    }
+}
+
+__global__ __launch_bounds__(ON_THREADS) void online_epoch_kernel(OnlinePlan p)
+{
+    extern __shared__ __align__(16) float lds[];
+    __shared__ int s_abort;
+    const int w = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int L = p.L;
+    const int n0 = p.layer[1].n_in;
+    const int nL = p.layer[L].n_out;
+    const OnlineLayer &last = p.layer[L];
+
+    // slices owned by this workgroup
+    const int c0 = w * last.per;                                  // columns of W_L
+    const int nc = max(0, min(last.per, last.n_in - c0));
+    bool any = (w == 0) || nc > 0;
+    for (int l = 1; l < L; ++l) any = any || (w * p.layer[l].per < p.layer[l].n_out);
+    if (!any) return;
+    const bool need_x = (L == 1) ? (nc > 0) : (w * p.layer[1].per < p.layer[1].n_out);
+    const bool need_z = (w == 0) || nc > 0;
+
+    float *xa0 = lds + p.lds_x;
+    float *zL = lds + p.lds_out, *dL = zL + ON_MAX_NL, *bL = dL + ON_MAX_NL, *vbL = bL + ON_MAX_NL;
+    float *kpart = lds + p.lds_kpart;
+    float *tmp = lds + p.lds_tmp;
+    const int n0p = (n0 + 3) & ~3;
+
+    if (tid == 0) s_abort = 0;
+    for (int k = tid; k < nL; k += kThreads) {
+        bL[k] = last.b[k];
+        vbL[k] = last.Vb[k];
+    }
+    if (need_x)
+        for (int k = tid; k < n0; k += kThreads) xa0[k] = p.X[k];
+    int y_cur = p.labels[0];
+    double loss_acc = 0.0;
+    __syncthreads();
+
+    constexpr int XR = 4;
+    for (int64_t s = 0; s < p.n_samples; ++s) {
+        const uint32_t seq = p.seq0 + 1u + (uint32_t)s;
+        const int par = (int)(seq & 1u);
+        const int mode = (p.mu != 0.f) ? UPD_MOMENTUM : ((p.keep_v && s == p.n_samples - 1) ? UPD_KEEPV : UPD_SGD);
+        const float *x = xa0 + (size_t)(s & 1) * n0p;
+        float xr[XR];
+        int y_next = 0;
+        bool aborted = false;
+        const bool more = s + 1 < p.n_samples;
+
+#define DN_PREFETCH_X()                                                                           \
+        do {                                                                                      \
+            if (more) {                                                                           \
+                const float *xn = p.X + (size_t)(s + 1) * n0;                                     \
+                _Pragma("unroll") for (int u = 0; u < XR; ++u) {                                  \
+                    const int k = tid + u * kThreads;                                             \
+                    xr[u] = (need_x && k < n0) ? xn[k] : 0.f;                                     \
+                }                                                                                 \
+                y_next = p.labels[s + 1];                                                         \
+            }                                                                                     \
+        } while (0)
+
+        // ---- forward through the row-split layers 1..L-1 -------------------------------
+        for (int l = 1; l < L; ++l) {
+            const OnlineLayer &ly = p.layer[l];
+            const int r0 = w * ly.per;
+            const int nr = max(0, min(ly.per, ly.n_out - r0));
+            if (nr > 0) {
+                const float *xin = x;
+                if (l > 1) {
+                    float *dst = lds + p.lds_a[l - 1];
+                    const u64 *src = p.act_x[l - 1] + (size_t)par * ly.n_in;
+                    poll_words(ly.n_in, seq, [&](int q) { return src + q; }, [&](int q, float v) { dst[q] = v; },
+                               p.abort_flag, &s_abort);
+                    __syncthreads();
+                    if (s_abort) { aborted = true; break; }
+                    xin = dst;
+                }
+                if (ly.vec4) fwd_rows<4>(ly.W, ly.n_in, r0, nr, ly.kf, ly.seg, xin, kpart);
+                else fwd_rows<1>(ly.W, ly.n_in, r0, nr, ly.kf, ly.seg, xin, kpart);
+                __syncthreads();
+                float *a_own = lds + p.lds_own_a[l];
+                for (int r = tid; r < nr; r += kThreads) {
+                    float z = ly.b[r0 + r];
+                    for (int ks = 0; ks < ly.kf; ++ks) z += kpart[r * ly.kf + ks];
+                    const float a = act_fn(ly.act, z);
+                    a_own[r] = a;
+                    if (l <= L - 2) ll_store(p.act_x[l] + (size_t)par * ly.n_out + r0 + r, a, seq);
+                }
+                __syncthreads();
+            }
+            if (l == 1) DN_PREFETCH_X();
+        }
+        if (aborted) break;
+
+        // ---- last layer: partial net inputs from own columns ---------------------------
+        const float *a_last = (L == 1) ? (x + c0) : (lds + p.lds_own_a[L - 1]);
+        if (nc > 0)
+            fwd_cols(last.W, last.n_in, nL, c0, nc, a_last, p.z_x + ((size_t)par * last.P + w) * nL, seq);
+        if (L == 1) DN_PREFETCH_X();
+
+        // ---- output layer: z_L, loss, Delta_L (every owner of last-layer columns repeats it) ----
+        if (need_z) {
+            gather_partials(p.z_x + (size_t)par * last.P * nL, last.P, nL, 0, nL, seq, tmp,
+                            [&](int k, float sum) { zL[k] = sum + bL[k]; }, p.abort_flag, &s_abort);
+            if (s_abort) break;
+            if (wave == 0) {
+                int y = y_cur;
+                y = y < 0 ? 0 : (y >= nL ? nL - 1 : y);
+                const int k0 = lane, k1 = lane + 64;
+                const float z0 = k0 < nL ? zL[k0] : -INFINITY, z1 = k1 < nL ? zL[k1] : -INFINITY;
+                float d0, d1, e;
+                if (p.loss == DN_LOSS_CROSS_ENTROPY) {
+                    const float m = wave_max(fmaxf(z0, z1));
+                    const float e0 = k0 < nL ? expf(z0 - m) : 0.f, e1 = k1 < nL ? expf(z1 - m) : 0.f;
+                    const float sum = wave_sum(e0 + e1);
+                    const float inv = 1.0f / sum;
+                    d0 = e0 * inv - (k0 == y ? 1.0f : 0.0f);
+                    d1 = e1 * inv - (k1 == y ? 1.0f : 0.0f);
+                    e = logf(sum) - (zL[y] - m);
+                } else {
+                    const float a0 = act_fn(last.act, z0), a1 = act_fn(last.act, z1);
+                    const float f0 = a0 - (k0 == y ? 1.0f : 0.0f), f1 = a1 - (k1 == y ? 1.0f : 0.0f);
+                    d0 = f0 * act_deriv(last.act, a0);
+                    d1 = f1 * act_deriv(last.act, a1);
+                    e = wave_sum((k0 < nL ? 0.5f * f0 * f0 : 0.f) + (k1 < nL ? 0.5f * f1 * f1 : 0.f));
+                }
+                if (k0 < nL) {
+                    dL[k0] = d0;
+                    bL[k0] = apply_update(bL[k0], p.lr * d0, vbL[k0], p.mu, mode);
+                }
+                if (k1 < nL) {
+                    dL[k1] = d1;
+                    bL[k1] = apply_update(bL[k1], p.lr * d1, vbL[k1], p.mu, mode);
+                }
+                if (lane == 0) loss_acc += (double)e;
+            }
+            __syncthreads();
+            if (nc > 0) {
+                bwd_cols(last.W, last.VW, last.n_in, nL, c0, nc, a_last, dL, p.lr, p.mu, mode,
+                         (L >= 2) ? (lds + p.lds_own_d[L - 1]) : nullptr, (L >= 2) ? p.layer[L - 1].act : 0);
+                __syncthreads();
+            }
+        }
+
+        // ---- backward through the row-split layers L-1..1 ------------------------------
+        for (int l = L - 1; l >= 1; --l) {
+            const OnlineLayer &ly = p.layer[l];
+            const int r0 = w * ly.per;
+            const int nr = max(0, min(ly.per, ly.n_out - r0));
+            if (nr <= 0) continue;
+            float *d_own = lds + p.lds_own_d[l];
+            const float *a_own = lds + p.lds_own_a[l];
+            if (l < L - 1) {
+                const OnlineLayer &up = p.layer[l + 1];
+                gather_partials(p.part_x[l + 1] + (size_t)par * up.P * ly.n_out, up.P, ly.n_out, r0, nr, seq, tmp,
+                                [&](int r, float sum) { d_own[r] = sum * act_deriv(ly.act, a_own[r]); },
+                                p.abort_flag, &s_abort);
+                if (s_abort) { aborted = true; break; }
+            }
+            const float *ain = (l == 1) ? x : (lds + p.lds_a[l - 1]);
+            if (l >= 2) {
+                u64 *pout = p.part_x[l] + ((size_t)par * ly.P + w) * ly.n_in;
+                if (ly.vec4) bwd_rows<4>(ly.W, ly.VW, ly.n_in, r0, nr, d_own, ain, p.lr, p.mu, mode, tmp, pout, seq);
+                else bwd_rows<1>(ly.W, ly.VW, ly.n_in, r0, nr, d_own, ain, p.lr, p.mu, mode, tmp, pout, seq);
+            } else {
+                if (ly.vec4) bwd_flat<4>(ly.W, ly.VW, ly.n_in, r0, nr, d_own, ain, p.lr, p.mu, mode);
+                else bwd_flat<1>(ly.W, ly.VW, ly.n_in, r0, nr, d_own, ain, p.lr, p.mu, mode);
+            }
+            for (int r = tid; r < nr; r += kThreads) {
+                float vb = (mode == UPD_MOMENTUM) ? ly.Vb[r0 + r] : 0.f;
+                ly.b[r0 + r] = apply_update(ly.b[r0 + r], p.lr * d_own[r], vb, p.mu, mode);
+                if (mode != UPD_SGD) ly.Vb[r0 + r] = vb;
+            }
+            __syncthreads();
+        }
+        if (aborted) break;
+
+        // ---- next sample into the other input buffer ------------------------------------
+        if (more) {
+            float *xn = xa0 + (size_t)((s + 1) & 1) * n0p;
+            if (need_x) {
+#pragma unroll
+                for (int u = 0; u < XR; ++u) {
+                    const int k = tid + u * kThreads;
+                    if (k < n0) xn[k] = xr[u];
+                }
+                for (int k = tid + XR * kThreads; k < n0; k += kThreads) xn[k] = p.X[(size_t)(s + 1) * n0 + k];
+            }
+            y_cur = y_next;
+        }
+        __syncthreads();
+    }
+#undef DN_PREFETCH_X
+
+    if (w == 0) {
+        if (tid == 0) *p.loss_acc += loss_acc;
+        for (int k = tid; k < nL; k += kThreads) {
+            last.b[k] = bL[k];
+            if (p.mu != 0.f || p.keep_v) last.Vb[k] = vbL[k];
+        }
+    }
+}
+
+}  // namespace
+
+// ---- host side -------------------------------------------------------------------
+
+bool online_geometry(const int32_t *n, int L, int min_tile, OnlineGeom &g)
+{
+    g = OnlineGeom{};
+    if (L < 1 || L > ON_MAX_L) return false;
+    if (n[L] > ON_MAX_NL) return false;
+    if (min_tile < 1) min_tile = 1;
+    auto cdiv = [](int64_t a, int64_t b) { return (int)((a + b - 1) / b); };
+    g.L = L;
+    int grid = 1;
+    for (int l = 1; l <= L; ++l) {
+        // rows (layers < L) or, for a one-layer net, input columns of the last layer
+        const int units = (l < L) ? n[l] : n[L - 1];
+        const int other = (l < L) ? n[l - 1] : n[L];
+        int per;
+        if (l == L && L >= 2) {
+            per = g.per[L - 1];   // the last layer's column blocks are the row blocks of layer L-1
+        } else {
+            per = std::max(cdiv(units, ON_MAX_WG), cdiv(min_tile, other));
+            per = std::min(per, units);
+        }
+        if ((int64_t)per * n[l - 1] > ((int64_t)1 << 30)) return false;
+        g.per[l] = per;
+        g.P[l] = cdiv(units, per);
+        grid = std::max(grid, g.P[l]);
+        const bool vec4 = (n[l - 1] % 4) == 0;
+        g.vec4[l] = vec4 ? 1 : 0;
+        if (l < L) {
+            int kf = per >= kWaves ? 1 : kWaves / per;
+            const int vec = vec4 ? 4 : 1;
+            int seg = cdiv(n[l - 1], kf);
+            seg = cdiv(seg, 64 * vec) * 64 * vec;           // whole wave strides
+            kf = cdiv(n[l - 1], seg);
+            g.kf[l] = kf;
+            g.seg[l] = seg;
+        }
+    }
+    g.grid = grid;
+    // exchange buffers (64-bit words, two copies each)
+    size_t words = 0;
+    for (int l = 1; l <= L - 2; ++l) { g.off_act[l] = words; words += 2 * (size_t)n[l]; }
+    for (int l = 2; l <= L - 1; ++l) { g.off_part[l] = words; words += 2 * (size_t)g.P[l] * n[l - 1]; }
+    g.off_z = words; words += 2 * (size_t)g.P[L] * n[L];
+    g.words = words;
+    // LDS (floats; every piece a multiple of 4)
+    auto pad4 = [](int v) { return (v + 3) & ~3; };
+    int f = 0;
+    g.lds_x = f; f += 2 * pad4(n[0]);
+    for (int l = 1; l <= L - 2; ++l) { g.lds_a[l] = f; f += pad4(n[l]); }
+    int kp = 16;
+    for (int l = 1; l <= L - 1; ++l) {
+        g.lds_own_a[l] = f; f += pad4(g.per[l]);
+        g.lds_own_d[l] = f; f += pad4(g.per[l]);
+        kp = std::max(kp, g.per[l] * g.kf[l]);
+    }
+    g.lds_out = f; f += 4 * ON_MAX_NL;
+    g.lds_kpart = f; f += pad4(kp);
+    g.lds_tmp = f; f += ON_TMP_FLOATS;
+    g.lds_floats = f;
+    if ((size_t)f * sizeof(float) > ON_MAX_LDS_BYTES) return false;
+    g.ok = true;
+    return true;
+}
+
+size_t online_exchange_bytes_bound(const int32_t *n, int L)
+{
+    if (L < 1 || L > ON_MAX_L || n[L] > ON_MAX_NL) return 0;
+    size_t words = 0;
+    for (int l = 1; l <= L - 2; ++l) words += 2 * (size_t)n[l];
+    for (int l = 2; l <= L - 1; ++l) words += 2 * (size_t)ON_MAX_WG * n[l - 1];
+    words += 2 * (size_t)ON_MAX_WG * n[L];
+    const size_t bytes = words * sizeof(u64);
+    return bytes > ((size_t)1 << 30) ? 0 : bytes;
+}
+
+hipError_t online_prepare(const OnlineGeom &g)
+{
+    return hipFuncSetAttribute((const void *)online_epoch_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                               (int)(g.lds_floats * sizeof(float)));
+}
+
+hipError_t launch_online_epoch(const OnlineGeom &g, const OnlinePlan &plan, hipStream_t stream)
+{
+    OnlinePlan p = plan;
+    void *args[] = {&p};
+    return hipLaunchCooperativeKernel((const void *)online_epoch_kernel, dim3(g.grid), dim3(ON_THREADS), args,
+                                      (unsigned)(g.lds_floats * sizeof(float)), stream);
+}
+
+}  // namespace dn

@@ -1,0 +1,158 @@
+"""GPU parity of per-sample (batch 1) training through dn_train_epoch, in both of its
+schedules: the persistent whole-epoch kernel ("online_mode" 2) and one launch per
+phase ("online_mode" 1), each against the CPU checker (fp32 storage, fp64 sums) on the
+same seeded inputs.  Tolerances: 1e-4 after the first steps, 1e-3 after an epoch."""
+import numpy as np
+import pytest
+
+from oracle.dn_oracle import Oracle
+from paper_2001_04206_amd import synth
+from parity_util import announce, assert_close
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+LIN, SIG, TANH, RELU, SOFTMAX = 0, 1, 2, 3, 4
+MSE, CE = 0, 1
+PER_PHASE, PERSISTENT = 1, 2
+
+
+@pytest.fixture(scope="module")
+def dnlib():
+    from paper_2001_04206_amd import dn
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    dn.lib()
+    return dn
+
+
+def run_pair(dn, w, n, passes, mode, min_tile=None, tol=1e-4, biases=True):
+    """`passes` = list of momenta; one pass over the first n samples per entry."""
+    if biases:
+        rng = np.random.default_rng(11)
+        w.b = [rng.standard_normal(k).astype(np.float32) * 0.1 for k in w.widths[1:]]
+    net = dn.Net(w.widths, w.acts, w.loss, 1)
+    net.set_all(w.W, w.b)
+    net.dn_set_option("online_mode", mode)
+    if min_tile is not None:
+        net.dn_set_option("online_min_tile", min_tile)
+    o = Oracle("o32", w.widths, w.acts, w.loss)
+    o.set_params(w.W, w.b)
+    X = torch.from_numpy(w.X[:n]).to("cuda:0")
+    y = torch.from_numpy(w.labels[:n]).to("cuda:0")
+    for mu in passes:
+        got = net.dn_train_epoch(X, y, 1, w.lr, mu)
+        ref, _ = o.train_epoch(w.X[:n], w.labels[:n], 1, w.lr, mu)
+        assert np.isfinite(got)
+        assert abs(got - ref) <= tol * max(abs(ref), 1e-6), (got, ref)
+    W, b = net.get_all()
+    Wr, br = o.get_params()
+    for l in range(net.L):
+        assert_close(W[l], Wr[l], tol, "W_%d" % (l + 1))
+        assert_close(b[l], br[l], tol, "b_%d" % (l + 1))
+    net.close()
+    return W, b
+
+
+SHAPES = [
+    # widths, acts, loss
+    ([4, 16, 3], [SIG, SIG], MSE),
+    ([37, 70, 5], [TANH, LIN], MSE),                        # rows that are not whole float4s
+    ([130, 67, 129, 11], [RELU, SIG, SOFTMAX], CE),
+    ([20, 40, 30, 50, 24, 6], [TANH, SIG, RELU, TANH, SOFTMAX], CE),
+    ([300, 10], [SOFTMAX], CE),                             # one layer
+    ([9, 1], [SIG], MSE),
+    ([1, 1, 2], [TANH, SOFTMAX], CE),
+    ([64, 2048, 1024, 10], [TANH, TANH, SOFTMAX], CE),      # column chunks < waves: rows split across waves
+    ([16, 4100, 24, 10], [TANH, RELU, SOFTMAX], CE),        # column chunks >= waves (float4 rows)
+    ([16, 1030, 24, 128], [SIG, TANH, SOFTMAX], CE),        # column chunks >= waves (scalar rows), widest output
+    ([340, 3000, 10], [TANH, SOFTMAX], CE),                 # the paper's benchmark shape, narrower hidden layer
+]
+
+
+@pytest.mark.parametrize("widths,acts,loss", SHAPES)
+@pytest.mark.parametrize("min_tile", [None, 16])
+def test_persistent_epochs_match_checker(dnlib, widths, acts, loss, min_tile):
+    announce("online persistent widths=%s min_tile=%s" % (widths, min_tile))
+    w = synth.make("online", widths, acts, loss, n_samples=48, features="normal", init="xavier_uniform",
+                   batch=1, lr=0.005, momentum=0.0, seed=4)
+    # plain SGD pass (leaves velocity = last step's delta), then two momentum passes on top of it
+    run_pair(dnlib, w, 48, [0.0, 0.5, 0.5], PERSISTENT, min_tile)
+
+
+@pytest.mark.parametrize("widths,acts,loss", SHAPES[:6])
+def test_per_phase_epochs_match_checker(dnlib, widths, acts, loss):
+    announce("online per-phase widths=%s" % (widths,))
+    w = synth.make("online", widths, acts, loss, n_samples=48, features="normal", init="xavier_uniform",
+                   batch=1, lr=0.005, momentum=0.0, seed=4)
+    run_pair(dnlib, w, 48, [0.0, 0.5, 0.5], PER_PHASE)
+
+
+def test_single_sample_epoch(dnlib):
+    announce("online persistent, one sample")
+    w = synth.make("online", [12, 20, 4], [TANH, SOFTMAX], CE, n_samples=1, features="normal",
+                   init="xavier_uniform", batch=1, lr=0.05, momentum=0.0, seed=2)
+    run_pair(dnlib, w, 1, [0.0, 0.5], PERSISTENT, 16)
+
+
+def test_persistent_is_bitwise_reproducible(dnlib):
+    announce("online persistent determinism")
+    w = synth.tanh_sweep(1, n_samples=300)
+    outs = []
+    for _ in range(2):
+        net = dnlib.Net(w.widths, w.acts, w.loss, 1)
+        net.set_all(w.W, w.b)
+        net.dn_set_option("online_mode", PERSISTENT)
+        X = torch.from_numpy(w.X).to("cuda:0")
+        y = torch.from_numpy(w.labels).to("cuda:0")
+        loss = net.dn_train_epoch(X, y, 1, w.lr, w.momentum)
+        outs.append((loss, net.get_all()))
+        net.close()
+    assert outs[0][0] == outs[1][0]
+    for a, b in zip(outs[0][1][0] + outs[0][1][1], outs[1][1][0] + outs[1][1][1]):
+        assert np.array_equal(a, b)
+
+
+def test_persistent_not_available_is_reported(dnlib):
+    announce("online persistent refused for a wide output layer")
+    w = synth.make("online", [8, 12, 300], [TANH, SOFTMAX], CE, n_samples=4, features="normal",
+                   init="xavier_uniform", batch=1, lr=0.05, momentum=0.0, seed=2)
+    net = dnlib.Net(w.widths, w.acts, w.loss, 1)
+    net.set_all(w.W, w.b)
+    net.dn_set_option("online_mode", PERSISTENT)
+    X = torch.from_numpy(w.X).to("cuda:0")
+    y = torch.from_numpy(w.labels).to("cuda:0")
+    with pytest.raises(dnlib.DnError) as e:
+        net.dn_train_epoch(X, y, 1, 0.05, 0.0)
+    assert e.value.status == dnlib.DN_ERR_UNSUPPORTED
+    net.dn_set_option("online_mode", 0)          # automatic choice falls back to per-phase launches
+    assert np.isfinite(net.dn_train_epoch(X, y, 1, 0.05, 0.0))
+    net.close()
+
+
+# ------------------------------------------------- the named batch-1 workloads ----
+
+def test_iris_like_ten_epochs_persistent(dnlib):
+    announce("cfg1 4-16-3 B=1, 10 epochs, persistent")
+    w = synth.iris_like()
+    run_pair(dnlib, w, w.n_samples, [0.0] * 10, PERSISTENT, tol=1e-3, biases=False)
+
+
+def test_digits_like_online_prefix_per_phase(dnlib):
+    announce("cfg2 784-128-10 B=1, first 1500 steps, per-phase launches")
+    w = synth.digits_like_online(n_samples=1500)
+    run_pair(dnlib, w, 1500, [0.0], PER_PHASE, tol=1e-3, biases=False)
+
+
+def test_tanh_sweep_b1_prefix_persistent(dnlib):
+    announce("cfg5 1024x4-10 B=1, first 2048 steps, persistent")
+    w = synth.tanh_sweep(1, n_samples=2048)
+    W, b = run_pair(dnlib, w, 2048, [0.0], PERSISTENT, tol=1e-3, biases=False)
+    assert abs(float(b[-1].sum())) < 1e-4      # softmax + cross-entropy conserves the output bias sum
+
+
+def test_paper_shape_first_steps(dnlib):
+    """340 -> 100000 (tanh) -> 10 softmax, the network of the paper's benchmark application,
+    full size, every weight compared after 24 steps."""
+    announce("paper shape 340-100000-10 B=1, 24 steps, persistent")
+    w = synth.paper_shape(n_samples=24)
+    run_pair(dnlib, w, 24, [0.0], PERSISTENT, tol=1e-4, biases=False)

@@ -195,7 +195,13 @@ dn_status dn_kernel_time(dn_net *net, int32_t kernel_class, float *ms_total, int
  *   "gemm_variant"   -1 (default): pick the tile configuration of each
  *                    contraction from its shape; >= 0: force that configuration
  *   "online_mode"    0: choose automatically; 1: per-phase launches for batch 1;
- *                    2: persistent whole-epoch kernel for batch 1
+ *                    2: persistent whole-epoch kernel for batch 1 (dn_train_epoch
+ *                    returns DN_ERR_UNSUPPORTED if the net does not fit it: more than
+ *                    8 layers, an output layer wider than 128, or too wide for LDS)
+ *   "online_min_tile"  weights of one layer a workgroup of the persistent kernel should
+ *                    own before the layer is spread over more workgroups (default 4096)
+ *   "online_resident"  1 (default): the persistent kernel keeps its weight slices in LDS
+ *                    when they fit; 0: always stream them from device memory
  * Unknown names or values out of range give DN_ERR_INVALID_ARG.
  */
 dn_status dn_set_option(dn_net *net, const char *name, int64_t value);

@@ -90,7 +90,8 @@ struct dn_net {
     int fwd_batch = 0;
     bool have_fwd = false, have_bwd = false;
     // options
-    int time_kernels = 0, gemm_variant = -1, online_mode = 0, online_min_tile = ON_DEFAULT_MIN_TILE;
+    int time_kernels = 0, gemm_variant = -1, online_mode = 0, online_min_tile = ON_DEFAULT_MIN_TILE,
+        online_resident = 1;
     // persistent batch-1 kernel
     OnlineGeom geom{};
     bool online_ok = false;
@@ -217,8 +218,9 @@ dn_status run_backward(dn_net *net, const float *X, int B, int mode, float lr, f
 dn_status run_online(dn_net *net, const float *X, const int32_t *labels, int64_t n_samples, float lr, float mu,
                      bool timing)
 {
-    const OnlineGeom &g = net->geom;
     const int L = net->L;
+    OnlineGeom g;   // same slices as net->geom; LDS residency depends on whether velocities are read
+    if (!online_geometry(net->n.data(), L, net->online_min_tile, mu != 0.f, g)) return DN_ERR_UNSUPPORTED;
     OnlinePlan p{};
     p.L = L;
     for (int l = 1; l <= L; ++l) {
@@ -229,11 +231,14 @@ dn_status run_online(dn_net *net, const float *X, const int32_t *labels, int64_t
         p.act_x[l] = net->exchange() + g.off_act[l];
         p.part_x[l] = net->exchange() + g.off_part[l];
         p.lds_a[l] = g.lds_a[l]; p.lds_own_a[l] = g.lds_own_a[l]; p.lds_own_d[l] = g.lds_own_d[l];
+        p.lds_b[l] = g.lds_b[l]; p.lds_w[l] = g.lds_w[l]; p.lds_v[l] = g.lds_v[l];
     }
     p.z_x = net->exchange() + g.off_z;
     p.abort_flag = net->abort_flag();
     p.loss_acc = net->epoch_acc();
     p.lr = lr; p.mu = mu; p.loss = net->loss;
+    p.resident = (net->online_resident != 0) ? g.resident : 0;
+    if (!p.resident && g.resident) g.lds_floats = g.lds_w[1];   // slice images are laid out last: drop them
     p.lds_x = g.lds_x; p.lds_out = g.lds_out; p.lds_kpart = g.lds_kpart; p.lds_tmp = g.lds_tmp;
     const int64_t chunk = (int64_t)1 << 30;
     for (int64_t s0 = 0; s0 < n_samples; s0 += chunk) {
@@ -332,11 +337,11 @@ dn_status dn_net_create(const int32_t *widths, int32_t n_widths, const dn_act *a
     net->arena = (char *)arena_dev;
     net->stream = (hipStream_t)hip_stream;
     // persistent batch-1 kernel: slices per workgroup, if the net fits it and the device has the units
-    if (lo.online_bytes > 0 && online_geometry(net->n.data(), L, net->online_min_tile, net->geom)) {
+    if (lo.online_bytes > 0 && online_geometry(net->n.data(), L, net->online_min_tile, false, net->geom)) {
         int dev = 0;
         if (hipGetDevice(&dev) == hipSuccess &&
             hipDeviceGetAttribute(&net->device_cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess)
-            net->online_ok = net->geom.grid <= net->device_cus && online_prepare(net->geom) == hipSuccess;
+            net->online_ok = net->geom.grid <= net->device_cus && online_prepare() == hipSuccess;
         (void)hipGetLastError();
     }
     // parameters, velocities and gradients start at zero; exchange words start unstamped
@@ -529,13 +534,15 @@ dn_status dn_set_option(dn_net *net, const char *name, int64_t value)
     } else if (!strcmp(name, "online_min_tile")) {
         if (value < 1 || value > ((int64_t)1 << 30) || net->lo.online_bytes == 0) return DN_ERR_INVALID_ARG;
         OnlineGeom g;
-        if (!online_geometry(net->n.data(), net->L, (int)value, g) || g.grid > net->device_cus ||
-            online_prepare(g) != hipSuccess)
+        if (!online_geometry(net->n.data(), net->L, (int)value, false, g) || g.grid > net->device_cus)
             return DN_ERR_INVALID_ARG;
         if (hipStreamSynchronize(net->stream) != hipSuccess) return DN_ERR_DEVICE;
         net->geom = g;
         net->online_min_tile = (int)value;
         net->online_ok = true;
+    } else if (!strcmp(name, "online_resident")) {
+        if (value != 0 && value != 1) return DN_ERR_INVALID_ARG;
+        net->online_resident = (int)value;
     } else {
         return DN_ERR_INVALID_ARG;
     }

@@ -77,7 +77,7 @@ constexpr int ON_MAX_WG = 256;      // workgroups (one per compute unit)
 constexpr int ON_MAX_NL = 128;      // width of the output layer
 constexpr int ON_THREADS = 512;     // threads per workgroup
 constexpr int ON_TMP_FLOATS = 4096; // reduction scratch in LDS
-constexpr size_t ON_MAX_LDS_BYTES = 144 * 1024;
+constexpr size_t ON_MAX_LDS_BYTES = 156 * 1024;
 constexpr int ON_DEFAULT_MIN_TILE = 4096;  // weights a workgroup should own per layer before rows are spread further
 
 // How the layers are cut into per-workgroup slices, where the exchange buffers sit inside
@@ -92,6 +92,9 @@ struct OnlineGeom {
     int vec4[ON_MAX_L + 1];   // rows are whole float4s
     size_t off_act[ON_MAX_L + 1], off_part[ON_MAX_L + 1], off_z, words;
     int lds_x, lds_a[ON_MAX_L + 1], lds_own_a[ON_MAX_L + 1], lds_own_d[ON_MAX_L + 1];
+    int lds_b[ON_MAX_L + 1];  // own biases, then their velocities
+    int lds_w[ON_MAX_L + 1], lds_v[ON_MAX_L + 1];   // own weight / velocity slices when resident
+    int resident;
     int lds_out, lds_kpart, lds_tmp, lds_floats;
 };
 
@@ -115,15 +118,18 @@ struct OnlinePlan {
     int loss, keep_v;
     uint32_t seq0;                              // step numbers seq0+1 .. seq0+n_samples stamp the exchange words
     int lds_x, lds_a[ON_MAX_L + 1], lds_own_a[ON_MAX_L + 1], lds_own_d[ON_MAX_L + 1];
+    int lds_b[ON_MAX_L + 1], lds_w[ON_MAX_L + 1], lds_v[ON_MAX_L + 1];
+    int resident;                               // weight slices are kept in LDS for the whole launch
     int lds_out, lds_kpart, lds_tmp;
 };
 
 // Slices and buffer offsets for widths n[0..L]; false if the net does not fit the kernel
-// (too many layers, output layer too wide, LDS).
-bool online_geometry(const int32_t *n, int L, int min_tile, OnlineGeom &g);
+// (too many layers, output layer too wide, LDS).  want_v: velocity slices are read every step
+// (momentum), so they must fit in LDS next to the weights for the slices to be resident.
+bool online_geometry(const int32_t *n, int L, int min_tile, bool want_v, OnlineGeom &g);
 // Upper bound of the exchange region in bytes for any min_tile (0 if the net can never fit).
 size_t online_exchange_bytes_bound(const int32_t *n, int L);
-hipError_t online_prepare(const OnlineGeom &g);
+hipError_t online_prepare();
 hipError_t launch_online_epoch(const OnlineGeom &g, const OnlinePlan &plan, hipStream_t stream);
 
 }  // namespace dn

@@ -29,6 +29,13 @@
 // consumed data that every one of its consumers published after they finished
 // reading step s.
 //
+// A workgroup's slices never change hands, so when they fit (with the velocity slices
+// when momentum is used) they are copied into LDS at the start of the epoch and written
+// back once at its end: weights of small and medium nets then never touch device memory
+// between steps and a step costs little more than its exchanges.  Larger slices stay in
+// device memory and are streamed (each weight read once forward, read and written once
+// backward).
+//
 // Every wait is bounded: a poll that does not complete within kSpinLimit
 // attempts raises an abort flag that ends every workgroup, and the host reports
 // DN_ERR_DEVICE.  All sums are taken in a fixed order, so an epoch is
@@ -189,11 +196,12 @@ __device__ __forceinline__ void gather_partials(const u64 *src, int P, int strid
     }
 }
 
-// Forward of a block of rows: kpart[r * kf + ks] = sum over segment ks of W[r0 + r][k] xin[k].
+// Forward of a block of rows (Wt = first row of the block, in LDS or device memory):
+// kpart[r * kf + ks] = sum over segment ks of Wt[r][k] xin[k].
 // One wave per (row, segment); a wave works on four of them at a time so that their loads
 // are in flight together.  Loads are unconditional (clamped addresses, masked values).
 template <int VEC>
-__device__ __forceinline__ void fwd_rows(const float *__restrict__ W, int n_in, int r0, int nr, int kf, int seg,
+__device__ __forceinline__ void fwd_rows(const float *__restrict__ Wt, int n_in, int nr, int kf, int seg,
                                          const float *xin, float *kpart)
 {
     constexpr int RU = 4;
@@ -211,7 +219,7 @@ __device__ __forceinline__ void fwd_rows(const float *__restrict__ W, int n_in, 
             const int ks = on ? it - r * kf : 0;
             kbeg[u] = ks * seg;
             kend[u] = on ? min(n_in, kbeg[u] + seg) : 0;
-            wp[u] = W + (size_t)(r0 + r) * n_in;
+            wp[u] = Wt + (size_t)r * n_in;
             acc[u] = 0.f;
         }
         for (int kk = lane * VEC; kk < seg; kk += 64 * VEC) {
@@ -246,7 +254,7 @@ __device__ __forceinline__ void fwd_rows(const float *__restrict__ W, int n_in, 
 // when there are fewer chunks than waves, the rows as well (partials meet in sred).
 // The block's partial of W^T delta is published to part_out[k], k < n_in.
 template <int VEC>
-__device__ __forceinline__ void bwd_rows(float *__restrict__ W, float *__restrict__ V, int n_in, int r0, int nr,
+__device__ __forceinline__ void bwd_rows(float *__restrict__ Wt, float *Vt, int n_in, int nr,
                                          const float *dl, const float *ain, float lr, float mu, int mode,
                                          float *sred, u64 *part_out, uint32_t seq)
 {
@@ -274,7 +282,7 @@ __device__ __forceinline__ void bwd_rows(float *__restrict__ W, float *__restric
             for (int u = 0; u < RU; ++u) {
                 const int ru = r + u * RG;
                 const int rc = ru < nr ? ru : r;
-                const float *wp = W + (size_t)(r0 + rc) * n_in + kc;
+                const float *wp = Wt + (size_t)rc * n_in + kc;
                 if (VEC == 4) {
                     const v4f t = *(const v4f *)wp;
                     wv[u][0] = t.x; wv[u][1 % VEC] = t.y; wv[u][2 % VEC] = t.z; wv[u][3 % VEC] = t.w;
@@ -287,7 +295,7 @@ __device__ __forceinline__ void bwd_rows(float *__restrict__ W, float *__restric
                 for (int u = 0; u < RU; ++u) {
                     const int ru = r + u * RG;
                     const int rc = ru < nr ? ru : r;
-                    const float *vp = V + (size_t)(r0 + rc) * n_in + kc;
+                    const float *vp = Vt + (size_t)rc * n_in + kc;
                     if (VEC == 4) {
                         const v4f t = *(const v4f *)vp;
                         vv[u][0] = t.x; vv[u][1 % VEC] = t.y; vv[u][2 % VEC] = t.z; vv[u][3 % VEC] = t.w;
@@ -313,8 +321,8 @@ __device__ __forceinline__ void bwd_rows(float *__restrict__ W, float *__restric
                         wv[u][e] = apply_update(wv[u][e], ld * a[e], vv[u][e], mu, mode);
                     }
                     if (kin) {
-                        float *wp = W + (size_t)(r0 + ru) * n_in + k;
-                        float *vp = V + (size_t)(r0 + ru) * n_in + k;
+                        float *wp = Wt + (size_t)ru * n_in + k;
+                        float *vp = Vt + (size_t)ru * n_in + k;
                         if (VEC == 4) {
                             v4f t; t.x = wv[u][0]; t.y = wv[u][1 % VEC]; t.z = wv[u][2 % VEC]; t.w = wv[u][3 % VEC];
                             *(v4f *)wp = t;
@@ -353,12 +361,10 @@ __device__ __forceinline__ void bwd_rows(float *__restrict__ W, float *__restric
 // Backward of a block of rows of the first layer (no delta is needed for the input): the
 // block is a contiguous run of nr * n_in weights, updated in place.
 template <int VEC>
-__device__ __forceinline__ void bwd_flat(float *__restrict__ W, float *__restrict__ V, int n_in, int r0, int nr,
+__device__ __forceinline__ void bwd_flat(float *__restrict__ Wb, float *Vb, int n_in, int nr,
                                          const float *dl, const float *ain, float lr, float mu, int mode)
 {
     constexpr int RU = 4;
-    float *Wb = W + (size_t)r0 * n_in;
-    float *Vb = V + (size_t)r0 * n_in;
     const int total = nr * n_in;
     for (int i0 = threadIdx.x * VEC; i0 < total; i0 += kThreads * VEC * RU) {
         float wv[RU][VEC], vv[RU][VEC];
@@ -417,14 +423,15 @@ __device__ __forceinline__ void bwd_flat(float *__restrict__ W, float *__restric
     }
 }
 
-// Last layer, forward: this workgroup's partial of z_L from its own columns c0..c0+nc of W_L.
-__device__ __forceinline__ void fwd_cols(const float *__restrict__ W, int n_in, int nL, int c0, int nc,
+// Last layer, forward: this workgroup's partial of z_L from its nc own columns of W_L
+// (Wt = first own column of row 0, rows `stride` apart).
+__device__ __forceinline__ void fwd_cols(const float *__restrict__ Wt, int stride, int nL, int nc,
                                          const float *a_own, u64 *zout, uint32_t seq)
 {
     constexpr int JU = 4;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     for (int k = wave; k < nL; k += kWaves) {
-        const float *wp = W + (size_t)k * n_in + c0;
+        const float *wp = Wt + (size_t)k * stride;
         float acc = 0.f;
         for (int j0 = lane; j0 < nc; j0 += 64 * JU) {
             float wv[JU];
@@ -447,7 +454,7 @@ __device__ __forceinline__ void fwd_cols(const float *__restrict__ W, int n_in, 
 // Last layer, backward: for each own column j: s_j = sum_k W_L[k][j] delta_L[k] from the
 // weights before the update, then the column is updated.  d_own[j] = s_j f'(a_own[j]) when
 // a previous layer exists.
-__device__ __forceinline__ void bwd_cols(float *__restrict__ W, float *__restrict__ V, int n_in, int nL, int c0,
+__device__ __forceinline__ void bwd_cols(float *__restrict__ Wt, int stride, float *Vt, int vstride, int nL,
                                          int nc, const float *a_own, const float *dL, float lr, float mu,
                                          int mode, float *d_own, int act_prev)
 {
@@ -460,13 +467,13 @@ __device__ __forceinline__ void bwd_cols(float *__restrict__ W, float *__restric
 #pragma unroll
             for (int u = 0; u < KB; ++u) {
                 const int k = min(k0 + u, nL - 1);
-                wv[u] = W[(size_t)k * n_in + c0 + j];
+                wv[u] = Wt[(size_t)k * stride + j];
             }
             if (mode == UPD_MOMENTUM) {
 #pragma unroll
                 for (int u = 0; u < KB; ++u) {
                     const int k = min(k0 + u, nL - 1);
-                    vv[u] = V[(size_t)k * n_in + c0 + j];
+                    vv[u] = Vt[(size_t)k * vstride + j];
                 }
             } else {
 #pragma unroll
@@ -479,13 +486,19 @@ __device__ __forceinline__ void bwd_cols(float *__restrict__ W, float *__restric
                     const float d = dL[k];
                     s += wv[u] * d;
                     const float nw = apply_update(wv[u], (lr * d) * a, vv[u], mu, mode);
-                    W[(size_t)k * n_in + c0 + j] = nw;
-                    if (mode != UPD_SGD) V[(size_t)k * n_in + c0 + j] = vv[u];
+                    Wt[(size_t)k * stride + j] = nw;
+                    if (mode != UPD_SGD) Vt[(size_t)k * vstride + j] = vv[u];
                 }
             }
         }
         if (d_own) d_own[j] = s * act_deriv(act_prev, a);
     }
+}
+
+// Copies between a block of device memory rows and its LDS image (count floats, contiguous).
+__device__ __forceinline__ void copy_floats(float *dst, const float *src, int count)
+{
+    for (int i = threadIdx.x; i < count; i += kThreads) dst[i] = src[i];
 }
 
 __global__ __launch_bounds__(ON_THREADS) void online_epoch_kernel(OnlinePlan p)
@@ -497,10 +510,13 @@ __global__ __launch_bounds__(ON_THREADS) void online_epoch_kernel(OnlinePlan p)
     const int n0 = p.layer[1].n_in;
     const int nL = p.layer[L].n_out;
     const OnlineLayer &last = p.layer[L];
+    const bool res = p.resident != 0;          // weight slices live in LDS
+    const bool vres = res && p.mu != 0.f;      // velocity slices too
 
     // slices owned by this workgroup
     const int c0 = w * last.per;                                  // columns of W_L
     const int nc = max(0, min(last.per, last.n_in - c0));
+    const int ncp = (last.per + 3) & ~3;                          // row pitch of the LDS image of those columns
     bool any = (w == 0) || nc > 0;
     for (int l = 1; l < L; ++l) any = any || (w * p.layer[l].per < p.layer[l].n_out);
     if (!any) return;
@@ -513,11 +529,30 @@ __global__ __launch_bounds__(ON_THREADS) void online_epoch_kernel(OnlinePlan p)
     float *tmp = lds + p.lds_tmp;
     const int n0p = (n0 + 3) & ~3;
 
+    // ---- prologue: biases of own rows (always) and own weight slices (if resident) into LDS ----
     if (tid == 0) s_abort = 0;
     for (int k = tid; k < nL; k += kThreads) {
         bL[k] = last.b[k];
         vbL[k] = last.Vb[k];
     }
+    for (int l = 1; l < L; ++l) {
+        const OnlineLayer &ly = p.layer[l];
+        const int r0 = w * ly.per;
+        const int nr = max(0, min(ly.per, ly.n_out - r0));
+        float *bl = lds + p.lds_b[l], *vbl = bl + ((ly.per + 3) & ~3);
+        for (int r = tid; r < nr; r += kThreads) {
+            bl[r] = ly.b[r0 + r];
+            vbl[r] = ly.Vb[r0 + r];
+        }
+        if (res && nr > 0) copy_floats(lds + p.lds_w[l], ly.W + (size_t)r0 * ly.n_in, nr * ly.n_in);
+        if (vres && nr > 0) copy_floats(lds + p.lds_v[l], ly.VW + (size_t)r0 * ly.n_in, nr * ly.n_in);
+    }
+    if (res)
+        for (int i = tid; i < nL * nc; i += kThreads) {
+            const int k = i / nc, j = i - k * nc;
+            lds[p.lds_w[L] + k * ncp + j] = last.W[(size_t)k * last.n_in + c0 + j];
+            if (vres) lds[p.lds_v[L] + k * ncp + j] = last.VW[(size_t)k * last.n_in + c0 + j];
+        }
     if (need_x)
         for (int k = tid; k < n0; k += kThreads) xa0[k] = p.X[k];
     int y_cur = p.labels[0];
@@ -563,12 +598,20 @@ __global__ __launch_bounds__(ON_THREADS) void online_epoch_kernel(OnlinePlan p)
                     if (s_abort) { aborted = true; break; }
                     xin = dst;
                 }
-                if (ly.vec4) fwd_rows<4>(ly.W, ly.n_in, r0, nr, ly.kf, ly.seg, xin, kpart);
-                else fwd_rows<1>(ly.W, ly.n_in, r0, nr, ly.kf, ly.seg, xin, kpart);
+                if (res) {
+                    const float *Wt = lds + p.lds_w[l];
+                    if (ly.vec4) fwd_rows<4>(Wt, ly.n_in, nr, ly.kf, ly.seg, xin, kpart);
+                    else fwd_rows<1>(Wt, ly.n_in, nr, ly.kf, ly.seg, xin, kpart);
+                } else {
+                    const float *Wt = ly.W + (size_t)r0 * ly.n_in;
+                    if (ly.vec4) fwd_rows<4>(Wt, ly.n_in, nr, ly.kf, ly.seg, xin, kpart);
+                    else fwd_rows<1>(Wt, ly.n_in, nr, ly.kf, ly.seg, xin, kpart);
+                }
                 __syncthreads();
                 float *a_own = lds + p.lds_own_a[l];
+                const float *bl = lds + p.lds_b[l];
                 for (int r = tid; r < nr; r += kThreads) {
-                    float z = ly.b[r0 + r];
+                    float z = bl[r];
                     for (int ks = 0; ks < ly.kf; ++ks) z += kpart[r * ly.kf + ks];
                     const float a = act_fn(ly.act, z);
                     a_own[r] = a;
@@ -582,8 +625,11 @@ __global__ __launch_bounds__(ON_THREADS) void online_epoch_kernel(OnlinePlan p)
 
         // ---- last layer: partial net inputs from own columns ---------------------------
         const float *a_last = (L == 1) ? (x + c0) : (lds + p.lds_own_a[L - 1]);
-        if (nc > 0)
-            fwd_cols(last.W, last.n_in, nL, c0, nc, a_last, p.z_x + ((size_t)par * last.P + w) * nL, seq);
+        if (nc > 0) {
+            u64 *zout = p.z_x + ((size_t)par * last.P + w) * nL;
+            if (res) fwd_cols(lds + p.lds_w[L], ncp, nL, nc, a_last, zout, seq);
+            else fwd_cols(last.W + c0, last.n_in, nL, nc, a_last, zout, seq);
+        }
         if (L == 1) DN_PREFETCH_X();
 
         // ---- output layer: z_L, loss, Delta_L (every owner of last-layer columns repeats it) ----
@@ -624,8 +670,16 @@ __global__ __launch_bounds__(ON_THREADS) void online_epoch_kernel(OnlinePlan p)
             }
             __syncthreads();
             if (nc > 0) {
-                bwd_cols(last.W, last.VW, last.n_in, nL, c0, nc, a_last, dL, p.lr, p.mu, mode,
-                         (L >= 2) ? (lds + p.lds_own_d[L - 1]) : nullptr, (L >= 2) ? p.layer[L - 1].act : 0);
+                float *d_prev = (L >= 2) ? (lds + p.lds_own_d[L - 1]) : nullptr;
+                const int act_prev = (L >= 2) ? p.layer[L - 1].act : 0;
+                float *Vt = vres ? (lds + p.lds_v[L]) : (last.VW + c0);
+                const int vstride = vres ? ncp : last.n_in;
+                if (res)
+                    bwd_cols(lds + p.lds_w[L], ncp, Vt, vstride, nL, nc, a_last, dL, p.lr, p.mu, mode, d_prev,
+                             act_prev);
+                else
+                    bwd_cols(last.W + c0, last.n_in, Vt, vstride, nL, nc, a_last, dL, p.lr, p.mu, mode, d_prev,
+                             act_prev);
                 __syncthreads();
             }
         }
@@ -646,18 +700,26 @@ __global__ __launch_bounds__(ON_THREADS) void online_epoch_kernel(OnlinePlan p)
                 if (s_abort) { aborted = true; break; }
             }
             const float *ain = (l == 1) ? x : (lds + p.lds_a[l - 1]);
-            if (l >= 2) {
-                u64 *pout = p.part_x[l] + ((size_t)par * ly.P + w) * ly.n_in;
-                if (ly.vec4) bwd_rows<4>(ly.W, ly.VW, ly.n_in, r0, nr, d_own, ain, p.lr, p.mu, mode, tmp, pout, seq);
-                else bwd_rows<1>(ly.W, ly.VW, ly.n_in, r0, nr, d_own, ain, p.lr, p.mu, mode, tmp, pout, seq);
-            } else {
-                if (ly.vec4) bwd_flat<4>(ly.W, ly.VW, ly.n_in, r0, nr, d_own, ain, p.lr, p.mu, mode);
-                else bwd_flat<1>(ly.W, ly.VW, ly.n_in, r0, nr, d_own, ain, p.lr, p.mu, mode);
-            }
+            float *Vt = vres ? (lds + p.lds_v[l]) : (ly.VW + (size_t)r0 * ly.n_in);
+            u64 *pout = (l >= 2) ? p.part_x[l] + ((size_t)par * ly.P + w) * ly.n_in : nullptr;
+#define DN_BWD_ROWS(WT)                                                                                       \
+            do {                                                                                              \
+                if (l >= 2) {                                                                                 \
+                    if (ly.vec4) bwd_rows<4>(WT, Vt, ly.n_in, nr, d_own, ain, p.lr, p.mu, mode, tmp, pout, seq); \
+                    else bwd_rows<1>(WT, Vt, ly.n_in, nr, d_own, ain, p.lr, p.mu, mode, tmp, pout, seq);      \
+                } else {                                                                                      \
+                    if (ly.vec4) bwd_flat<4>(WT, Vt, ly.n_in, nr, d_own, ain, p.lr, p.mu, mode);              \
+                    else bwd_flat<1>(WT, Vt, ly.n_in, nr, d_own, ain, p.lr, p.mu, mode);                      \
+                }                                                                                             \
+            } while (0)
+            if (res) DN_BWD_ROWS(lds + p.lds_w[l]);
+            else DN_BWD_ROWS(ly.W + (size_t)r0 * ly.n_in);
+#undef DN_BWD_ROWS
+            float *bl = lds + p.lds_b[l], *vbl = bl + ((ly.per + 3) & ~3);
             for (int r = tid; r < nr; r += kThreads) {
-                float vb = (mode == UPD_MOMENTUM) ? ly.Vb[r0 + r] : 0.f;
-                ly.b[r0 + r] = apply_update(ly.b[r0 + r], p.lr * d_own[r], vb, p.mu, mode);
-                if (mode != UPD_SGD) ly.Vb[r0 + r] = vb;
+                float vb = vbl[r];
+                bl[r] = apply_update(bl[r], p.lr * d_own[r], vb, p.mu, mode);
+                if (mode != UPD_SGD) vbl[r] = vb;
             }
             __syncthreads();
         }
@@ -680,11 +742,32 @@ __global__ __launch_bounds__(ON_THREADS) void online_epoch_kernel(OnlinePlan p)
     }
 #undef DN_PREFETCH_X
 
+    // ---- epilogue: LDS images back to device memory -------------------------------------
+    __syncthreads();
+    const bool v_touched = p.mu != 0.f || p.keep_v;
+    for (int l = 1; l < L; ++l) {
+        const OnlineLayer &ly = p.layer[l];
+        const int r0 = w * ly.per;
+        const int nr = max(0, min(ly.per, ly.n_out - r0));
+        const float *bl = lds + p.lds_b[l], *vbl = bl + ((ly.per + 3) & ~3);
+        for (int r = tid; r < nr; r += kThreads) {
+            ly.b[r0 + r] = bl[r];
+            if (v_touched) ly.Vb[r0 + r] = vbl[r];
+        }
+        if (res && nr > 0) copy_floats(ly.W + (size_t)r0 * ly.n_in, lds + p.lds_w[l], nr * ly.n_in);
+        if (vres && nr > 0) copy_floats(ly.VW + (size_t)r0 * ly.n_in, lds + p.lds_v[l], nr * ly.n_in);
+    }
+    if (res)
+        for (int i = tid; i < nL * nc; i += kThreads) {
+            const int k = i / nc, j = i - k * nc;
+            last.W[(size_t)k * last.n_in + c0 + j] = lds[p.lds_w[L] + k * ncp + j];
+            if (vres) last.VW[(size_t)k * last.n_in + c0 + j] = lds[p.lds_v[L] + k * ncp + j];
+        }
     if (w == 0) {
         if (tid == 0) *p.loss_acc += loss_acc;
         for (int k = tid; k < nL; k += kThreads) {
             last.b[k] = bL[k];
-            if (p.mu != 0.f || p.keep_v) last.Vb[k] = vbL[k];
+            if (v_touched) last.Vb[k] = vbL[k];
         }
     }
 }
@@ -693,13 +776,14 @@ __global__ __launch_bounds__(ON_THREADS) void online_epoch_kernel(OnlinePlan p)
 
 // ---- host side -------------------------------------------------------------------
 
-bool online_geometry(const int32_t *n, int L, int min_tile, OnlineGeom &g)
+bool online_geometry(const int32_t *n, int L, int min_tile, bool want_v, OnlineGeom &g)
 {
     g = OnlineGeom{};
     if (L < 1 || L > ON_MAX_L) return false;
     if (n[L] > ON_MAX_NL) return false;
     if (min_tile < 1) min_tile = 1;
     auto cdiv = [](int64_t a, int64_t b) { return (int)((a + b - 1) / b); };
+    auto pad4 = [](int v) { return (v + 3) & ~3; };
     g.L = L;
     int grid = 1;
     for (int l = 1; l <= L; ++l) {
@@ -737,21 +821,34 @@ bool online_geometry(const int32_t *n, int L, int min_tile, OnlineGeom &g)
     g.off_z = words; words += 2 * (size_t)g.P[L] * n[L];
     g.words = words;
     // LDS (floats; every piece a multiple of 4)
-    auto pad4 = [](int v) { return (v + 3) & ~3; };
-    int f = 0;
-    g.lds_x = f; f += 2 * pad4(n[0]);
-    for (int l = 1; l <= L - 2; ++l) { g.lds_a[l] = f; f += pad4(n[l]); }
+    int64_t f = 0;
+    g.lds_x = (int)f; f += 2 * pad4(n[0]);
+    for (int l = 1; l <= L - 2; ++l) { g.lds_a[l] = (int)f; f += pad4(n[l]); }
     int kp = 16;
     for (int l = 1; l <= L - 1; ++l) {
-        g.lds_own_a[l] = f; f += pad4(g.per[l]);
-        g.lds_own_d[l] = f; f += pad4(g.per[l]);
+        g.lds_own_a[l] = (int)f; f += pad4(g.per[l]);
+        g.lds_own_d[l] = (int)f; f += pad4(g.per[l]);
+        g.lds_b[l] = (int)f; f += 2 * pad4(g.per[l]);
         kp = std::max(kp, g.per[l] * g.kf[l]);
     }
-    g.lds_out = f; f += 4 * ON_MAX_NL;
-    g.lds_kpart = f; f += pad4(kp);
-    g.lds_tmp = f; f += ON_TMP_FLOATS;
-    g.lds_floats = f;
-    if ((size_t)f * sizeof(float) > ON_MAX_LDS_BYTES) return false;
+    g.lds_out = (int)f; f += 4 * ON_MAX_NL;
+    g.lds_kpart = (int)f; f += pad4(kp);
+    g.lds_tmp = (int)f; f += ON_TMP_FLOATS;
+    if (f * (int64_t)sizeof(float) > (int64_t)ON_MAX_LDS_BYTES) return false;
+    // the workgroup's weight slices (and velocity slices) in LDS, if they fit
+    int64_t tiles = 0;
+    for (int l = 1; l <= L - 1; ++l) tiles += (int64_t)g.per[l] * pad4(n[l - 1]);
+    tiles += (int64_t)n[L] * pad4(g.per[L]);
+    const int64_t copies = want_v ? 2 : 1;
+    if ((f + copies * tiles) * (int64_t)sizeof(float) <= (int64_t)ON_MAX_LDS_BYTES) {
+        g.resident = 1;
+        for (int l = 1; l <= L; ++l) {
+            const int64_t t = (l < L) ? (int64_t)g.per[l] * pad4(n[l - 1]) : (int64_t)n[L] * pad4(g.per[L]);
+            g.lds_w[l] = (int)f; f += t;
+            if (want_v) { g.lds_v[l] = (int)f; f += t; }
+        }
+    }
+    g.lds_floats = (int)f;
     g.ok = true;
     return true;
 }
@@ -767,10 +864,10 @@ size_t online_exchange_bytes_bound(const int32_t *n, int L)
     return bytes > ((size_t)1 << 30) ? 0 : bytes;
 }
 
-hipError_t online_prepare(const OnlineGeom &g)
+hipError_t online_prepare()
 {
     return hipFuncSetAttribute((const void *)online_epoch_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                               (int)(g.lds_floats * sizeof(float)));
+                               (int)ON_MAX_LDS_BYTES);
 }
 
 hipError_t launch_online_epoch(const OnlineGeom &g, const OnlinePlan &plan, hipStream_t stream)

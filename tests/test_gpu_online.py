@@ -25,7 +25,7 @@ def dnlib():
     return dn
 
 
-def run_pair(dn, w, n, passes, mode, min_tile=None, tol=1e-4, biases=True):
+def run_pair(dn, w, n, passes, mode, min_tile=None, tol=1e-4, biases=True, resident=1):
     """`passes` = list of momenta; one pass over the first n samples per entry."""
     if biases:
         rng = np.random.default_rng(11)
@@ -35,6 +35,7 @@ def run_pair(dn, w, n, passes, mode, min_tile=None, tol=1e-4, biases=True):
     net.dn_set_option("online_mode", mode)
     if min_tile is not None:
         net.dn_set_option("online_min_tile", min_tile)
+    net.dn_set_option("online_resident", resident)
     o = Oracle("o32", w.widths, w.acts, w.loss)
     o.set_params(w.W, w.b)
     X = torch.from_numpy(w.X[:n]).to("cuda:0")
@@ -71,12 +72,15 @@ SHAPES = [
 
 @pytest.mark.parametrize("widths,acts,loss", SHAPES)
 @pytest.mark.parametrize("min_tile", [None, 16])
-def test_persistent_epochs_match_checker(dnlib, widths, acts, loss, min_tile):
-    announce("online persistent widths=%s min_tile=%s" % (widths, min_tile))
+@pytest.mark.parametrize("resident", [1, 0])
+def test_persistent_epochs_match_checker(dnlib, widths, acts, loss, min_tile, resident):
+    """resident=1 keeps the workgroups' weight slices in LDS where they fit (all of these shapes
+    except the widest); resident=0 streams them from device memory."""
+    announce("online persistent widths=%s min_tile=%s resident=%d" % (widths, min_tile, resident))
     w = synth.make("online", widths, acts, loss, n_samples=48, features="normal", init="xavier_uniform",
                    batch=1, lr=0.005, momentum=0.0, seed=4)
     # plain SGD pass (leaves velocity = last step's delta), then two momentum passes on top of it
-    run_pair(dnlib, w, 48, [0.0, 0.5, 0.5], PERSISTENT, min_tile)
+    run_pair(dnlib, w, 48, [0.0, 0.5, 0.5], PERSISTENT, min_tile, resident=resident)
 
 
 @pytest.mark.parametrize("widths,acts,loss", SHAPES[:6])

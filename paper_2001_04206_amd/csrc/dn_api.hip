@@ -227,7 +227,7 @@ dn_status run_online(dn_net *net, const float *X, const int32_t *labels, int64_t
         OnlineLayer &y = p.layer[l];
         y.W = net->W(l); y.b = net->b(l); y.VW = net->VW(l); y.Vb = net->Vb(l);
         y.n_in = net->n[l - 1]; y.n_out = net->n[l]; y.act = net->act[l];
-        y.per = g.per[l]; y.P = g.P[l]; y.kf = g.kf[l]; y.seg = g.seg[l]; y.vec4 = g.vec4[l];
+        y.per = g.per[l]; y.P = g.P[l]; y.kshift = g.kshift[l]; y.seg = g.seg[l]; y.vec4 = g.vec4[l];
         p.act_x[l] = net->exchange() + g.off_act[l];
         p.part_x[l] = net->exchange() + g.off_part[l];
         p.lds_a[l] = g.lds_a[l]; p.lds_own_a[l] = g.lds_own_a[l]; p.lds_own_d[l] = g.lds_own_d[l];

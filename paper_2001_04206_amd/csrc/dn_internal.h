@@ -87,7 +87,8 @@ struct OnlineGeom {
     int L, grid;
     int per[ON_MAX_L + 1];    // rows per workgroup (layers < L); columns per workgroup (layer L)
     int P[ON_MAX_L + 1];      // workgroups that own a slice of the layer
-    int kf[ON_MAX_L + 1];     // forward: segments a row's dot product is split into
+    int kf[ON_MAX_L + 1];     // forward: segments a row's dot product is split into (a power of two)
+    int kshift[ON_MAX_L + 1]; // log2 of it
     int seg[ON_MAX_L + 1];    // forward: segment length
     int vec4[ON_MAX_L + 1];   // rows are whole float4s
     size_t off_act[ON_MAX_L + 1], off_part[ON_MAX_L + 1], off_z, words;
@@ -100,7 +101,7 @@ struct OnlineGeom {
 
 struct OnlineLayer {
     float *W, *b, *VW, *Vb;
-    int n_in, n_out, act, per, P, kf, seg, vec4;
+    int n_in, n_out, act, per, P, kshift, seg, vec4;
 };
 
 struct OnlinePlan {

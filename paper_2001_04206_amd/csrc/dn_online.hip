@@ -69,17 +69,47 @@ __device__ __forceinline__ u64 ll_load(const u64 *p)
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// Wave-wide reductions with data-parallel-primitive moves (no LDS traffic): butterflies inside
+// each row of 16 lanes, then the row totals are carried across rows; lane 63 ends up with the
+// result, which is broadcast through a scalar register.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_move(float v, float identity)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, identity),
+                                                                 __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xf,
+                                                                 false));
+}
+
 __device__ __forceinline__ float wave_sum(float v)
 {
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
-    return v;
+    v += dpp_move<0xB1, 0xf>(v, 0.f);    // quad_perm [1,0,3,2]
+    v += dpp_move<0x4E, 0xf>(v, 0.f);    // quad_perm [2,3,0,1]
+    v += dpp_move<0x141, 0xf>(v, 0.f);   // row_half_mirror
+    v += dpp_move<0x140, 0xf>(v, 0.f);   // row_mirror: every lane of a row holds the row's sum
+    v += dpp_move<0x142, 0xa>(v, 0.f);   // row_bcast:15 into rows 1 and 3
+    v += dpp_move<0x143, 0xc>(v, 0.f);   // row_bcast:31 into rows 2 and 3
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
 }
 
 __device__ __forceinline__ float wave_max(float v)
 {
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    const float ninf = -INFINITY;
+    v = fmaxf(v, dpp_move<0xB1, 0xf>(v, ninf));
+    v = fmaxf(v, dpp_move<0x4E, 0xf>(v, ninf));
+    v = fmaxf(v, dpp_move<0x141, 0xf>(v, ninf));
+    v = fmaxf(v, dpp_move<0x140, 0xf>(v, ninf));
+    v = fmaxf(v, dpp_move<0x142, 0xa>(v, ninf));
+    v = fmaxf(v, dpp_move<0x143, 0xc>(v, ninf));
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
+}
+
+// Sum over each aligned group of 16 lanes (a DPP row); every lane of the group gets it.
+__device__ __forceinline__ float row16_sum(float v)
+{
+    v += dpp_move<0xB1, 0xf>(v, 0.f);
+    v += dpp_move<0x4E, 0xf>(v, 0.f);
+    v += dpp_move<0x141, 0xf>(v, 0.f);
+    v += dpp_move<0x140, 0xf>(v, 0.f);
     return v;
 }
 
@@ -125,7 +155,8 @@ __device__ __forceinline__ void poll_words(int total, uint32_t seq, Addr addr, S
 #pragma unroll
         for (int u = 0; u < kPollBatch; ++u) {
             const int q = q0 + u * kThreads;
-            v[u] = ll_load(addr(q < total ? q : q0));
+            v[u] = 0;
+            if (q < total) v[u] = ll_load(addr(q));
         }
         bool all = true;
 #pragma unroll
@@ -166,30 +197,73 @@ __device__ __forceinline__ void poll_words(int total, uint32_t seq, Addr addr, S
 }
 
 // out[e] = sum over w < P of the word at src[w * stride + base + e], e < count, summed in a
-// fixed order: 16 lanes per element each add every 16th partial, then a 4-step butterfly.
+// fixed order: 16 lanes per element each add every 16th partial, then a butterfly over the 16.
 // `scale_fn(e, sum)` finishes the element.  tmp holds kTmp floats.  Ends with a barrier.
 template <class Finish>
 __device__ __forceinline__ void gather_partials(const u64 *src, int P, int stride, int base, int count,
                                                 uint32_t seq, float *tmp, Finish finish, int *abort_flag,
                                                 volatile int *s_abort)
 {
-    const int ecap = kTmp / P;   // elements per pass (P <= ON_MAX_WG <= kTmp)
+    const int ecap = min(kTmp / P, kThreads);   // elements per pass (P <= ON_MAX_WG <= kTmp)
     for (int e0 = 0; e0 < count; e0 += ecap) {
         const int ne = min(ecap, count - e0);
-        poll_words(
-            ne * P, seq,
-            [&](int q) { const int ww = q / ne, e = q - ww * ne; return src + (size_t)ww * stride + base + e0 + e; },
-            [&](int q, float val) { const int ww = q / ne, e = q - ww * ne; tmp[e * P + ww] = val; },
-            abort_flag, s_abort);
+        // threads form groups of G = 2^lg >= ne lanes; a group reads the ne words of one producer
+        const int lg = 32 - __clz(ne - 1), G = 1 << lg;
+        const int e = threadIdx.x & (G - 1), ww0 = threadIdx.x >> lg, wstep = kThreads >> lg;
+        if (e < ne) {
+            const u64 *col = src + base + e0 + e;
+            for (int wb = ww0; wb < P; wb += wstep * kPollBatch) {
+                u64 v[kPollBatch];
+                bool ok[kPollBatch];
+                bool all = true;
+#pragma unroll
+                for (int u = 0; u < kPollBatch; ++u) {
+                    const int ww = wb + u * wstep;
+                    v[u] = 0;
+                    ok[u] = true;
+                    if (ww < P) {
+                        v[u] = ll_load(col + (size_t)ww * stride);
+                        ok[u] = (uint32_t)(v[u] >> 32) == seq;
+                    }
+                    all = all && ok[u];
+                }
+                int spins = 0;
+                while (!all) {
+                    all = true;
+#pragma unroll
+                    for (int u = 0; u < kPollBatch; ++u) {
+                        if (!ok[u]) {
+                            v[u] = ll_load(col + (size_t)(wb + u * wstep) * stride);
+                            ok[u] = (uint32_t)(v[u] >> 32) == seq;
+                            all = all && ok[u];
+                        }
+                    }
+                    if (all) break;
+                    ++spins;
+                    if (spins > kSpinLimit) {
+                        __hip_atomic_store(abort_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        *s_abort = 1;
+                        break;
+                    }
+                    if ((spins & 255) == 0 &&
+                        __hip_atomic_load(abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+                        *s_abort = 1;
+                        break;
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < kPollBatch; ++u) {
+                    const int ww = wb + u * wstep;
+                    if (ww < P) tmp[e * P + ww] = __uint_as_float((uint32_t)v[u]);
+                }
+            }
+        }
         __syncthreads();
         const int g = threadIdx.x & 15;
         for (int e = threadIdx.x >> 4; e < ne; e += kThreads / 16) {
             float s = 0.f;
             for (int ww = g; ww < P; ww += 16) s += tmp[e * P + ww];
-            s += __shfl_xor(s, 8, 16);
-            s += __shfl_xor(s, 4, 16);
-            s += __shfl_xor(s, 2, 16);
-            s += __shfl_xor(s, 1, 16);
+            s = row16_sum(s);
             if (g == 0) finish(e0 + e, s);
         }
         __syncthreads();
@@ -198,13 +272,13 @@ __device__ __forceinline__ void gather_partials(const u64 *src, int P, int strid
 
 // Forward of a block of rows (Wt = first row of the block, in LDS or device memory):
 // kpart[r * kf + ks] = sum over segment ks of Wt[r][k] xin[k].
-// One wave per (row, segment); a wave works on four of them at a time so that their loads
-// are in flight together.  Loads are unconditional (clamped addresses, masked values).
-template <int VEC>
-__device__ __forceinline__ void fwd_rows(const float *__restrict__ Wt, int n_in, int nr, int kf, int seg,
+// One wave per (row, segment), kf = 2^kshift segments per row; a wave works on RU of them at a
+// time so that their loads are in flight together.  Loads are unconditional (clamped addresses, masked values).
+template <int VEC, int RU>
+__device__ __forceinline__ void fwd_rows(const float *__restrict__ Wt, int n_in, int nr, int kshift, int seg,
                                          const float *xin, float *kpart)
 {
-    constexpr int RU = 4;
+    const int kf = 1 << kshift;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int items = nr * kf;
     for (int it0 = wave; it0 < items; it0 += kWaves * RU) {
@@ -215,8 +289,8 @@ __device__ __forceinline__ void fwd_rows(const float *__restrict__ Wt, int n_in,
         for (int u = 0; u < RU; ++u) {
             const int it = it0 + u * kWaves;
             const bool on = it < items;
-            const int r = on ? it / kf : 0;
-            const int ks = on ? it - r * kf : 0;
+            const int r = on ? it >> kshift : 0;
+            const int ks = on ? it & (kf - 1) : 0;
             kbeg[u] = ks * seg;
             kend[u] = on ? min(n_in, kbeg[u] + seg) : 0;
             wp[u] = Wt + (size_t)r * n_in;
@@ -253,12 +327,11 @@ __device__ __forceinline__ void fwd_rows(const float *__restrict__ Wt, int n_in,
 // weight is rewritten with the update.  Waves split the columns in chunks of 64*VEC and,
 // when there are fewer chunks than waves, the rows as well (partials meet in sred).
 // The block's partial of W^T delta is published to part_out[k], k < n_in.
-template <int VEC>
+template <int VEC, int RU>
 __device__ __forceinline__ void bwd_rows(float *__restrict__ Wt, float *Vt, int n_in, int nr,
                                          const float *dl, const float *ain, float lr, float mu, int mode,
                                          float *sred, u64 *part_out, uint32_t seq)
 {
-    constexpr int RU = 4;
     constexpr int CW = 64 * VEC;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int C = (n_in + CW - 1) / CW;
@@ -360,12 +433,12 @@ __device__ __forceinline__ void bwd_rows(float *__restrict__ Wt, float *Vt, int 
 
 // Backward of a block of rows of the first layer (no delta is needed for the input): the
 // block is a contiguous run of nr * n_in weights, updated in place.
-template <int VEC>
+template <int VEC, int RU>
 __device__ __forceinline__ void bwd_flat(float *__restrict__ Wb, float *Vb, int n_in, int nr,
                                          const float *dl, const float *ain, float lr, float mu, int mode)
 {
-    constexpr int RU = 4;
     const int total = nr * n_in;
+    const float inv_n = 1.0f / (float)n_in;
     for (int i0 = threadIdx.x * VEC; i0 < total; i0 += kThreads * VEC * RU) {
         float wv[RU][VEC], vv[RU][VEC];
 #pragma unroll
@@ -401,7 +474,16 @@ __device__ __forceinline__ void bwd_flat(float *__restrict__ Wb, float *Vb, int 
         for (int u = 0; u < RU; ++u) {
             const int i = i0 + u * kThreads * VEC;
             if (i < total) {
-                const int r = (int)((unsigned)i / (unsigned)n_in);
+                // row of element i: below 2^22 elements a float estimate is off by at most one
+                // row and is corrected exactly; larger blocks divide
+                int r;
+                if (total < (1 << 22)) {
+                    r = min((int)((float)i * inv_n), nr - 1);
+                    if (r * n_in > i) --r;
+                    else if ((r + 1) * n_in <= i) ++r;
+                } else {
+                    r = (int)((unsigned)i / (unsigned)n_in);
+                }
                 const int k = i - r * n_in;
                 const float ld = lr * dl[r];
 #pragma unroll
@@ -600,19 +682,24 @@ __global__ __launch_bounds__(ON_THREADS) void online_epoch_kernel(OnlinePlan p)
                 }
                 if (res) {
                     const float *Wt = lds + p.lds_w[l];
-                    if (ly.vec4) fwd_rows<4>(Wt, ly.n_in, nr, ly.kf, ly.seg, xin, kpart);
-                    else fwd_rows<1>(Wt, ly.n_in, nr, ly.kf, ly.seg, xin, kpart);
+                    if ((nr << ly.kshift) <= kWaves) {      // one (row, segment) per wave: no batching needed
+                        if (ly.vec4) fwd_rows<4, 1>(Wt, ly.n_in, nr, ly.kshift, ly.seg, xin, kpart);
+                        else fwd_rows<1, 1>(Wt, ly.n_in, nr, ly.kshift, ly.seg, xin, kpart);
+                    } else {
+                        if (ly.vec4) fwd_rows<4, 4>(Wt, ly.n_in, nr, ly.kshift, ly.seg, xin, kpart);
+                        else fwd_rows<1, 4>(Wt, ly.n_in, nr, ly.kshift, ly.seg, xin, kpart);
+                    }
                 } else {
                     const float *Wt = ly.W + (size_t)r0 * ly.n_in;
-                    if (ly.vec4) fwd_rows<4>(Wt, ly.n_in, nr, ly.kf, ly.seg, xin, kpart);
-                    else fwd_rows<1>(Wt, ly.n_in, nr, ly.kf, ly.seg, xin, kpart);
+                    if (ly.vec4) fwd_rows<4, 4>(Wt, ly.n_in, nr, ly.kshift, ly.seg, xin, kpart);
+                    else fwd_rows<1, 4>(Wt, ly.n_in, nr, ly.kshift, ly.seg, xin, kpart);
                 }
                 __syncthreads();
                 float *a_own = lds + p.lds_own_a[l];
                 const float *bl = lds + p.lds_b[l];
                 for (int r = tid; r < nr; r += kThreads) {
                     float z = bl[r];
-                    for (int ks = 0; ks < ly.kf; ++ks) z += kpart[r * ly.kf + ks];
+                    for (int ks = 0; ks < (1 << ly.kshift); ++ks) z += kpart[(r << ly.kshift) + ks];
                     const float a = act_fn(ly.act, z);
                     a_own[r] = a;
                     if (l <= L - 2) ll_store(p.act_x[l] + (size_t)par * ly.n_out + r0 + r, a, seq);
@@ -702,18 +789,26 @@ __global__ __launch_bounds__(ON_THREADS) void online_epoch_kernel(OnlinePlan p)
             const float *ain = (l == 1) ? x : (lds + p.lds_a[l - 1]);
             float *Vt = vres ? (lds + p.lds_v[l]) : (ly.VW + (size_t)r0 * ly.n_in);
             u64 *pout = (l >= 2) ? p.part_x[l] + ((size_t)par * ly.P + w) * ly.n_in : nullptr;
-#define DN_BWD_ROWS(WT)                                                                                       \
+#define DN_BWD_ROWS(WT, RU)                                                                                   \
             do {                                                                                              \
                 if (l >= 2) {                                                                                 \
-                    if (ly.vec4) bwd_rows<4>(WT, Vt, ly.n_in, nr, d_own, ain, p.lr, p.mu, mode, tmp, pout, seq); \
-                    else bwd_rows<1>(WT, Vt, ly.n_in, nr, d_own, ain, p.lr, p.mu, mode, tmp, pout, seq);      \
+                    if (ly.vec4) bwd_rows<4, RU>(WT, Vt, ly.n_in, nr, d_own, ain, p.lr, p.mu, mode, tmp, pout, seq); \
+                    else bwd_rows<1, RU>(WT, Vt, ly.n_in, nr, d_own, ain, p.lr, p.mu, mode, tmp, pout, seq);  \
                 } else {                                                                                      \
-                    if (ly.vec4) bwd_flat<4>(WT, Vt, ly.n_in, nr, d_own, ain, p.lr, p.mu, mode);              \
-                    else bwd_flat<1>(WT, Vt, ly.n_in, nr, d_own, ain, p.lr, p.mu, mode);                      \
+                    if (ly.vec4) bwd_flat<4, RU>(WT, Vt, ly.n_in, nr, d_own, ain, p.lr, p.mu, mode);          \
+                    else bwd_flat<1, RU>(WT, Vt, ly.n_in, nr, d_own, ain, p.lr, p.mu, mode);                  \
                 }                                                                                             \
             } while (0)
-            if (res) DN_BWD_ROWS(lds + p.lds_w[l]);
-            else DN_BWD_ROWS(ly.W + (size_t)r0 * ly.n_in);
+            if (res) {
+                // small slices: one row (or one vector) per wave (thread), no batching of loads needed
+                const int vec = ly.vec4 ? 4 : 1;
+                const int C = (ly.n_in + 64 * vec - 1) / (64 * vec);
+                const bool small = (l >= 2) ? (nr <= (C >= kWaves ? 1 : kWaves / C)) : (nr * ly.n_in <= kThreads * vec);
+                if (small) DN_BWD_ROWS(lds + p.lds_w[l], 1);
+                else DN_BWD_ROWS(lds + p.lds_w[l], 4);
+            } else {
+                DN_BWD_ROWS(ly.W + (size_t)r0 * ly.n_in, 4);
+            }
 #undef DN_BWD_ROWS
             float *bl = lds + p.lds_b[l], *vbl = bl + ((ly.per + 3) & ~3);
             for (int r = tid; r < nr; r += kThreads) {
@@ -804,13 +899,18 @@ bool online_geometry(const int32_t *n, int L, int min_tile, bool want_v, OnlineG
         const bool vec4 = (n[l - 1] % 4) == 0;
         g.vec4[l] = vec4 ? 1 : 0;
         if (l < L) {
-            int kf = per >= kWaves ? 1 : kWaves / per;
+            // forward: a row's dot product is cut into 2^kshift segments of whole wave strides so
+            // that a small block still occupies every wave
             const int vec = vec4 ? 4 : 1;
-            int seg = cdiv(n[l - 1], kf);
-            seg = cdiv(seg, 64 * vec) * 64 * vec;           // whole wave strides
-            kf = cdiv(n[l - 1], seg);
+            int kf = 1;
+            while (kf * 2 * per <= kWaves) kf *= 2;
+            auto seg_of = [&](int f) { return cdiv(cdiv(n[l - 1], f), 64 * vec) * 64 * vec; };
+            while (kf > 1 && (int64_t)seg_of(kf) * (kf - 1) >= n[l - 1]) kf /= 2;   // no empty segments
+            g.seg[l] = seg_of(kf);
             g.kf[l] = kf;
-            g.seg[l] = seg;
+            int sh = 0;
+            while ((1 << sh) < kf) ++sh;
+            g.kshift[l] = sh;
         }
     }
     g.grid = grid;

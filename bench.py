@@ -55,6 +55,28 @@ def step_costs(widths, batch, momentum):
     return flops, per_param * p + act_bytes
 
 
+def hbm_traffic(workload):
+    """HBM bytes of the workload's dominant kernel from the committed profiler counter summary
+    (profiles/<workload>_hbm_traffic.txt): (bytes, 'launch' | 'step'), or None when there is no
+    summary or the kernel's source has changed since the counters were taken."""
+    import hashlib
+    path = os.path.join(ROOT, "profiles", workload + "_hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    kv = {}
+    for line in open(path):
+        if not line.startswith("#") and ":" in line:
+            k, v = line.split(":", 1)
+            kv[k.strip()] = v.strip()
+    try:
+        src = os.path.join(ROOT, kv["source_file"])
+        if hashlib.sha256(open(src, "rb").read()).hexdigest() != kv["source_sha256"]:
+            return None
+        return float(kv["traffic_bytes"]), kv["per"]
+    except (KeyError, OSError, ValueError):
+        return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -62,8 +84,11 @@ def main():
     ap.add_argument("--warmup", type=int, default=-1, help="untimed steps (-1: workload default)")
     ap.add_argument("--workload", default="cfg4_4096x3_1000_b256")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
+                    help="instead of a workload: copy MIB mebibytes device to device three times and exit "
+                         "(a plain copy of known size, to scale the profiler's HBM byte counters)")
     ap.add_argument("--no-kernel-timing", action="store_true",
-                    help="leave per-launch events out of the timed region (roofline becomes null)")
+                    help="skip the second, event-bracketed pass over the same steps (roofline becomes null)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
@@ -71,6 +96,18 @@ def main():
     import numpy as np
     import torch
     from paper_2001_04206_amd import dn
+
+    if args.calibrate_copy > 0:
+        assert torch.cuda.is_available(), "bench.py needs the GPU"
+        n = args.calibrate_copy * (1 << 20)
+        src = torch.ones(n, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes": n, "copies": 3}))
+        return
 
     table = workloads()
     if args.workload not in table:
@@ -112,7 +149,7 @@ def main():
     if warmup:
         run(warmup)
     net.set_all(w.W, w.b)            # timed region starts from the initial parameters
-    net.dn_set_option("time_kernels", 0 if args.no_kernel_timing else 1)
+    net.dn_set_option("time_kernels", 0)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     dev_ms, loss = run(steps)
@@ -120,6 +157,18 @@ def main():
     wall = time.perf_counter() - t1
     samples = sum(min(B, N - ((s % steps_per_pass) * B)) for s in range(steps))
     value = samples / wall
+
+    # The same steps once more, from the same initial parameters, with every kernel launch
+    # bracketed by HIP events on the library's stream: per-kernel durations for the roofline.
+    # (Kept out of the throughput figure above: an event pair per launch costs microseconds,
+    # which is most of a step for the small workloads.)
+    if not args.no_kernel_timing:
+        net.set_all(w.W, w.b)
+        net.dn_set_option("time_kernels", 1)
+        torch.cuda.synchronize()
+        run(steps)
+        torch.cuda.synchronize()
+        net.dn_set_option("time_kernels", 0)
 
     flops, step_bytes = step_costs(w.widths, B, w.momentum)
     roofline = None
@@ -155,6 +204,11 @@ def main():
                             "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS, "traffic": None,
                             "avg_launch_us": total_ms * 1e3 / sum(c["launches"] for c in classes.values()),
                             "timed_steps": timed_steps}
+
+    if roofline is not None:
+        t = hbm_traffic(args.workload)
+        if t is not None:     # per launch, like `achieved`: a persistent launch covers timed_steps steps
+            roofline["traffic"] = t[0] * (roofline.get("timed_steps", 1) if t[1] == "step" else 1)
 
     cpu = None
     if not args.no_cpu_baseline:

@@ -194,6 +194,8 @@ dn_status dn_kernel_time(dn_net *net, int32_t kernel_class, float *ms_total, int
  *   "time_kernels"   1: collect per-launch times in dn_train_epoch (see above)
  *   "gemm_variant"   -1 (default): pick the tile configuration of each
  *                    contraction from its shape; >= 0: force that configuration
+ *   "split_k"        1 (default): forward / delta products with few output tiles split k across
+ *                    workgroups (partials summed in a fixed order); 0: never
  *   "online_mode"    0: choose automatically; 1: per-phase launches for batch 1;
  *                    2: persistent whole-epoch kernel for batch 1 (dn_train_epoch
  *                    returns DN_ERR_UNSUPPORTED if the net does not fit it: more than

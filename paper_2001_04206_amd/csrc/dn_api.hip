@@ -25,6 +25,7 @@ struct Layout {
     size_t off_params = 0, off_vel = 0, off_grads = 0;
     size_t off_loss_rows = 0, off_scalars = 0;
     size_t off_online = 0, online_bytes = 0;   // exchange buffers of the persistent batch-1 kernel
+    size_t off_gemm_ws = 0, off_gemm_counters = 0;   // partial tiles / arrival counters of k-split contractions
     size_t total = 0;
 };
 
@@ -65,6 +66,8 @@ bool compute_layout(const int32_t *widths, int32_t n_widths, int32_t max_batch, 
     lo.off_scalars = o; o += kAlign;
     lo.online_bytes = online_exchange_bytes_bound(widths, L);
     lo.off_online = o; o += align_up(lo.online_bytes);
+    lo.off_gemm_ws = o; o += align_up(GEMM_WS_FLOATS * sizeof(float));
+    lo.off_gemm_counters = o; o += align_up(GEMM_COUNTERS * sizeof(unsigned));
     lo.total = o;
     return true;
 }
@@ -91,7 +94,7 @@ struct dn_net {
     bool have_fwd = false, have_bwd = false;
     // options
     int time_kernels = 0, gemm_variant = -1, online_mode = 0, online_min_tile = ON_DEFAULT_MIN_TILE,
-        online_resident = 1;
+        online_resident = 1, split_k_on = 1;
     // persistent batch-1 kernel
     OnlineGeom geom{};
     bool online_ok = false;
@@ -117,6 +120,13 @@ struct dn_net {
     double *epoch_acc() const { return (double *)(arena + lo.off_scalars); }
     int *abort_flag() const { return (int *)(arena + lo.off_scalars + sizeof(double)); }
     unsigned long long *exchange() const { return (unsigned long long *)(arena + lo.off_online); }
+    void split_k(GemmArgs &g) const
+    {
+        g.ws = split_k_on ? (float *)(arena + lo.off_gemm_ws) : nullptr;
+        g.counters = (unsigned *)(arena + lo.off_gemm_counters);
+        g.ws_floats = GEMM_WS_FLOATS;
+        g.n_counters = GEMM_COUNTERS;
+    }
 };
 
 namespace {
@@ -172,6 +182,7 @@ dn_status run_forward(dn_net *net, const float *X, int B, bool timing)
         g.C = net->A(l); g.ldc = net->n[l];
         g.bias = net->b(l);
         g.act = net->act[l];
+        net->split_k(g);
         ScopedTimer st(net, DN_K_FORWARD, timing);
         DN_HIP(launch_gemm(GEMM_FWD, g, net->gemm_variant, net->stream));
     }
@@ -193,6 +204,7 @@ dn_status run_backward(dn_net *net, const float *X, int B, int mode, float lr, f
             g.C = net->D(l - 1); g.ldc = net->n[l - 1];
             g.aux = net->A(l - 1);
             g.act = net->act[l - 1];
+            net->split_k(g);
             ScopedTimer st(net, DN_K_DELTA, timing);
             DN_HIP(launch_gemm(GEMM_DELTA, g, net->gemm_variant, net->stream));
         }
@@ -349,6 +361,7 @@ dn_status dn_net_create(const int32_t *widths, int32_t n_widths, const dn_act *a
         hipMemsetAsync(net->arena + lo.off_scalars, 0, kAlign, net->stream) != hipSuccess ||
         (lo.online_bytes > 0 &&
          hipMemsetAsync(net->arena + lo.off_online, 0, lo.online_bytes, net->stream) != hipSuccess) ||
+        hipMemsetAsync(net->arena + lo.off_gemm_counters, 0, GEMM_COUNTERS * sizeof(unsigned), net->stream) != hipSuccess ||
         hipEventCreate(&net->ev_epoch0) != hipSuccess || hipEventCreate(&net->ev_epoch1) != hipSuccess ||
         hipStreamSynchronize(net->stream) != hipSuccess) {
         if (net->ev_epoch0) (void)hipEventDestroy(net->ev_epoch0);
@@ -540,6 +553,9 @@ dn_status dn_set_option(dn_net *net, const char *name, int64_t value)
         net->geom = g;
         net->online_min_tile = (int)value;
         net->online_ok = true;
+    } else if (!strcmp(name, "split_k")) {
+        if (value != 0 && value != 1) return DN_ERR_INVALID_ARG;
+        net->split_k_on = (int)value;
     } else if (!strcmp(name, "online_resident")) {
         if (value != 0 && value != 1) return DN_ERR_INVALID_ARG;
         net->online_resident = (int)value;

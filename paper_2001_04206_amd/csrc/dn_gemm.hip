@@ -240,8 +240,19 @@ struct SchedPattern<FILL, FILL, NRD, BASE> {
 // Work of one workgroup on the tile at (m0, n0).  FAST: the tile is interior in m and n and
 // both operands are vector-loadable; only a ragged last k step takes the clamped path.
 template <class T, bool A_KC, bool B_KC, int EPI, bool VEC, bool FAST>
-__device__ __forceinline__ void gemm_tile(const GemmArgs &g, float *smem, const int m0, const int n0)
+__device__ __forceinline__ void gemm_tile(const GemmArgs &g0, float *smem, const int m0, const int n0, const int tile_id,
+                                          const int split)
 {
+    // k split across workgroups: this one contracts k steps [split * per, (split + 1) * per) of the
+    // KT-step sequence, i.e. the same product on operands advanced along k and a shorter K.
+    GemmArgs g = g0;
+    if (g0.sk > 1) {
+        const int per = (((g0.K + T::KT - 1) / T::KT) + g0.sk - 1) / g0.sk * T::KT;
+        const int kb = split * per;
+        g.A = A_KC ? g0.A + kb : g0.A + (size_t)kb * g0.lda;
+        g.B = B_KC ? g0.B + kb : g0.B + (size_t)kb * g0.ldb;
+        g.K = min(per, g0.K - kb);
+    }
     constexpr int BM = T::BM, BN = T::BN, KT = T::KT, NT = T::NT, R = T::R;
     constexpr int TM = T::TM, TN = T::TN, WK = T::WK;
     constexpr bool IS_GRAD = EPI >= EPI_GRAD_STORE;
@@ -496,8 +507,62 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, float *smem, const 
             }
             __syncthreads();
         }
-        if (wk != 0) return;
     }
+    const bool lead = WK == 1 || wk == 0;   // waves that hold the workgroup's tile
+
+    // k split across workgroups: every workgroup leaves its partial tile in the workspace and
+    // counts itself in; the one that arrives last adds the partials in split order (so the sum
+    // does not depend on arrival order) and runs the epilogue.  Partials travel as relaxed
+    // device-scope atomic stores / loads, which go through to memory and bypass the per-XCD L2,
+    // so no cache write-back or invalidation is needed (either would throw away the operand
+    // panels the other workgroups of the XCD are working from); the stores are complete before
+    // the workgroup counts itself in.
+    if (g0.sk > 1) {
+        const int wpos = wm * T::WN + wn;
+        const size_t tile_floats = (size_t)BM * BN;
+        float *mine = g0.ws + ((size_t)tile_id * g0.sk + split) * tile_floats + (size_t)wpos * TM * TN * 1024;
+        if (lead) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        __hip_atomic_store(&mine[((i * TN + j) * 16 + r) * 64 + lane], acc[i][j][r], __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // waits for this wave's stores
+        __syncthreads();
+        int *s_last = reinterpret_cast<int *>(smem);
+        if (tid == 0) {
+            const unsigned old = __hip_atomic_fetch_add(&g0.counters[tile_id], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            *s_last = (old == (unsigned)(g0.sk - 1)) ? 1 : 0;
+        }
+        __syncthreads();
+        if (*s_last == 0) return;
+        if (tid == 0)   // ready for the next launch
+            __hip_atomic_store(&g0.counters[tile_id], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (lead) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+            for (int sp = 0; sp < g0.sk; ++sp) {
+                const float *src = g0.ws + ((size_t)tile_id * g0.sk + sp) * tile_floats + (size_t)wpos * TM * TN * 1024;
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            acc[i][j][r] += __hip_atomic_load(&src[((i * TN + j) * 16 + r) * 64 + lane], __ATOMIC_RELAXED,
+                                                              __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    }
+    if (!lead) return;
 
     // Epilogue.  Lanes of one register cover 32 consecutive columns of one row.
 #pragma unroll
@@ -528,14 +593,17 @@ __global__ __launch_bounds__(T::NT, T::OCC) void gemm_kernel(GemmArgs g, int til
     // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous
     // run of tiles (m fastest) so tiles sharing a B panel meet in one L2.
     const int nt = tiles_m * tiles_n;
-    const int per_xcd = (nt + 7) / 8;
-    const int v = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
-    if (v >= nt) return;
+    const int sk = g.sk > 1 ? g.sk : 1;
+    const int nwork = nt * sk;           // (tile, k split) pairs, splits of a tile adjacent
+    const int per_xcd = (nwork + 7) / 8;
+    const int u = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    if (u >= nwork) return;
+    const int v = u / sk, split = u - v * sk;
     const int m0 = (v % tiles_m) * T::BM, n0 = (v / tiles_m) * T::BN;
     if (VEC && m0 + T::BM <= g.M && n0 + T::BN <= g.N)
-        gemm_tile<T, A_KC, B_KC, EPI, VEC, VEC>(g, smem, m0, n0);
+        gemm_tile<T, A_KC, B_KC, EPI, VEC, VEC>(g, smem, m0, n0, v, split);
     else
-        gemm_tile<T, A_KC, B_KC, EPI, VEC, false>(g, smem, m0, n0);
+        gemm_tile<T, A_KC, B_KC, EPI, VEC, false>(g, smem, m0, n0, v, split);
 }
 
 // ---- tile configurations and dispatch ----------------------------------------
@@ -552,7 +620,22 @@ static hipError_t launch_vec(const GemmArgs &a, hipStream_t stream)
 {
     const int tiles_m = (a.M + T::BM - 1) / T::BM, tiles_n = (a.N + T::BN - 1) / T::BN;
     const long nt = (long)tiles_m * tiles_n;
-    const long grid = 8 * ((nt + 7) / 8);
+    // Few output tiles and a long k: split k across workgroups until about two per CU are busy.
+    GemmArgs b = a;
+    b.sk = 1;
+    if (EPI <= EPI_DELTA && a.ws && a.counters && nt < 256 && nt <= a.n_counters) {
+        const int nk = (a.K + T::KT - 1) / T::KT;
+        int sk = (int)(512 / nt);
+        if (sk > 16) sk = 16;
+        if (sk > nk / 2) sk = nk / 2;          // at least two k steps each
+        while (sk > 1 && (size_t)nt * sk * T::BM * T::BN > a.ws_floats) --sk;
+        if (sk > 1) {
+            const int per = (nk + sk - 1) / sk;
+            sk = (nk + per - 1) / per;         // no empty splits
+        }
+        b.sk = sk > 1 ? sk : 1;
+    }
+    const long grid = 8 * ((nt * b.sk + 7) / 8);
     if (grid <= 0 || grid > 0x7fffffffL) return hipErrorInvalidValue;
     constexpr size_t lds = smem_bytes<T, A_KC, B_KC>();
     static_assert(lds <= 160 * 1024, "tile does not fit the 160 KB LDS of a CU");
@@ -563,7 +646,7 @@ static hipError_t launch_vec(const GemmArgs &a, hipStream_t stream)
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((gemm_kernel<T, A_KC, B_KC, EPI, VEC>), dim3((unsigned)grid), dim3(T::NT), lds, stream, a,
+    hipLaunchKernelGGL((gemm_kernel<T, A_KC, B_KC, EPI, VEC>), dim3((unsigned)grid), dim3(T::NT), lds, stream, b,
                        tiles_m, tiles_n);
     return hipGetLastError();
 }
@@ -577,10 +660,16 @@ using V4 = Tile<32, 64, 32, 1, 1, 4, 2>;        // batch of a few hundred x widt
 using V5 = Tile<32, 64, 64, 1, 1, 8, 2>;
 using V6 = Tile<32, 32, 64, 1, 1, 8, 2>;        // few output tiles: lean on the k split
 using V7 = Tile<128, 128, 16, 2, 2, 1, 2, 16>;  // weight gradients: epilogue operands fetched over 16 k steps
+using V8 = Tile<128, 64, 16, 2, 2, 1, 2, 16, 2>;  // weight gradients, two workgroups per CU: one's epilogue under the other's k loop
+using V9 = Tile<64, 64, 16, 2, 2, 1, 2, 8, 4>;    // weight gradients, four workgroups per CU
+using V10 = Tile<64, 64, 32, 2, 2, 1, 2, 4, 4>;
+using V11 = Tile<64, 128, 16, 2, 2, 1, 2, 16, 2>;
+using V12 = Tile<64, 64, 16, 2, 2, 1, 1, 8, 4>;
 
 static const char *kVariantNames[] = {"128x128x16_r1",  "128x64x16_r2",   "64x64x64_k4_r2", "64x64x32_k4_r2",
-                                      "32x64x32_k4_r2", "32x64x64_k8_r2", "32x32x64_k8_r2", "128x128x16_r2_pc16"};
-constexpr int kVariants = 8;
+                                      "32x64x32_k4_r2", "32x64x64_k8_r2", "32x32x64_k8_r2", "128x128x16_r2_pc16",
+                                      "128x64x16_r2_pc16_o2", "64x64x16_r2_pc8_o4", "64x64x32_r2_pc4_o4", "64x128x16_r2_pc16_o2", "64x64x16_r1_pc8_o4"};
+constexpr int kVariants = 13;
 int gemm_variant_count() { return kVariants; }
 const char *gemm_variant_name(int v) { return (v >= 0 && v < kVariants) ? kVariantNames[v] : "?"; }
 
@@ -616,19 +705,23 @@ static hipError_t launch_kind(GemmKind kind, const GemmArgs &a, hipStream_t stre
 // Tile shape from the problem shape: prefer the largest tile that still gives every CU
 // (256 of them) at least one workgroup; outputs with few tiles use small tiles whose waves
 // split k among themselves.
-static int pick_variant(const GemmArgs &a)
+static int pick_variant(GemmKind kind, const GemmArgs &a)
 {
     auto tiles = [&](int bm, int bn) { return (long)((a.M + bm - 1) / bm) * ((a.N + bn - 1) / bn); };
+    // 64x64 tiles with four workgroups per CU let one workgroup's prologue / epilogue traffic run
+    // under another's matrix work: best whenever there are enough of them (weight gradients with
+    // their read-modify-write epilogue need one per CU, the other products two).
+    if (tiles(64, 64) >= (kind == GEMM_GRAD ? 256 : 512)) return 9;
     if (a.K <= 512 && tiles(128, 128) >= 256) return a.K >= 192 ? 7 : 0;
     if (tiles(128, 64) >= 256) return 1;
-    if (tiles(32, 64) >= 256) return 4;
+    if (tiles(32, 64) > 256) return 4;
     return 6;
 }
 
 hipError_t launch_gemm(GemmKind kind, const GemmArgs &a, int variant, hipStream_t stream)
 {
     if (a.M <= 0 || a.N <= 0 || a.K <= 0) return hipErrorInvalidValue;
-    if (variant < 0) variant = pick_variant(a);
+    if (variant < 0) variant = pick_variant(kind, a);
     switch (variant) {
     case 0: return launch_kind<V0>(kind, a, stream);
     case 1: return launch_kind<V1>(kind, a, stream);
@@ -638,6 +731,11 @@ hipError_t launch_gemm(GemmKind kind, const GemmArgs &a, int variant, hipStream_
     case 5: return launch_kind<V5>(kind, a, stream);
     case 6: return launch_kind<V6>(kind, a, stream);
     case 7: return launch_kind<V7>(kind, a, stream);
+    case 8: return launch_kind<V8>(kind, a, stream);
+    case 9: return launch_kind<V9>(kind, a, stream);
+    case 10: return launch_kind<V10>(kind, a, stream);
+    case 11: return launch_kind<V11>(kind, a, stream);
+    case 12: return launch_kind<V12>(kind, a, stream);
     default: return hipErrorInvalidValue;
     }
 }

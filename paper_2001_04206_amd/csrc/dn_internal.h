@@ -45,7 +45,18 @@ struct GemmArgs {
     float scale;       // GRAD_STORE: 1/B ; update modes: lr/B
     float mu;          // GRAD_MOMENTUM
     int mode;          // GradMode for GEMM_GRAD
+    // k split across workgroups (FWD / DELTA with few output tiles): workspace for the partial
+    // tiles and one arrival counter per tile (zero before the launch; left zero by it).
+    // ws == nullptr: never split.  sk is chosen by launch_gemm.
+    float *ws;
+    unsigned *counters;
+    size_t ws_floats;  // capacity of ws
+    int n_counters;    // capacity of counters
+    int sk;
 };
+
+constexpr size_t GEMM_WS_FLOATS = (size_t)2 << 20;  // 8 MB of partial tiles
+constexpr int GEMM_COUNTERS = 1024;
 
 // Enqueue one contraction on `stream`.  Returns hipSuccess or the launch error.
 // `variant` < 0 picks a tile configuration from the shape; >= 0 forces one.

@@ -40,11 +40,12 @@ def make_pair(dn, w, max_batch):
     return net, o
 
 
-def check_one_step(dn, w, B, lr, mu, tol=STEP_TOL, variant=-1, second_step=True):
+def check_one_step(dn, w, B, lr, mu, tol=STEP_TOL, variant=-1, second_step=True, split_k=1):
     """forward / backward / update through the split API, compared tensor by tensor."""
     net, o = make_pair(dn, w, B)
     if variant >= 0:
         net.dn_set_option("gemm_variant", variant)
+    net.dn_set_option("split_k", split_k)
     X, y = to_dev(w)
     nL = w.widths[-1]
     for step in range(2 if second_step else 1):
@@ -110,7 +111,7 @@ SMALL_CASES = [
 
 
 @pytest.mark.parametrize("widths,acts,loss,B", SMALL_CASES)
-@pytest.mark.parametrize("variant", [-1, 0, 1, 2, 3, 4, 5, 6, 7])
+@pytest.mark.parametrize("variant", [-1, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12])
 def test_one_step_small_and_ragged(dnlib, widths, acts, loss, B, variant):
     announce("one_step_small widths=%s acts=%s loss=%d B=%d variant=%d" % (widths, acts, loss, B, variant))
     w = synth.make("small", widths, acts, loss, n_samples=2 * B, features="normal",
@@ -118,6 +119,40 @@ def test_one_step_small_and_ragged(dnlib, widths, acts, loss, B, variant):
     rng = np.random.default_rng(5)
     w.b = [rng.standard_normal(n).astype(np.float32) * 0.1 for n in widths[1:]]   # non-zero biases
     check_one_step(dnlib, w, B, lr=0.1, mu=0.9, variant=variant)
+
+
+SPLIT_K_CASES = [
+    # long contractions with few output tiles: forward / delta products split k across workgroups
+    ([1000, 300, 52, 10], [TANH, RELU, SOFTMAX], CE, 40),
+    ([517, 259, 33, 7], [SIG, TANH, SOFTMAX], CE, 5),        # scalar-load path, ragged everywhere
+    ([2048, 96, 10], [TANH, SOFTMAX], CE, 64),
+    ([1536, 1024, 3], [RELU, LIN], MSE, 16),
+]
+
+
+@pytest.mark.parametrize("widths,acts,loss,B", SPLIT_K_CASES)
+@pytest.mark.parametrize("variant", [-1, 2, 4, 5, 6, 9])
+@pytest.mark.parametrize("split_k", [1, 0])
+def test_one_step_split_k(dnlib, widths, acts, loss, B, variant, split_k):
+    announce("one_step_split_k widths=%s B=%d variant=%d split_k=%d" % (widths, B, variant, split_k))
+    w = synth.make("splitk", widths, acts, loss, n_samples=2 * B, features="normal",
+                   init="xavier_uniform", batch=B, lr=0.05, momentum=0.9, seed=7)
+    check_one_step(dnlib, w, B, lr=0.05, mu=0.9, variant=variant, split_k=split_k)
+
+
+def test_split_k_is_bitwise_reproducible(dnlib):
+    announce("determinism: k split across workgroups, two runs")
+    w = synth.tanh_sweep(32, n_samples=256)
+    outs = []
+    for _ in range(2):
+        net = dnlib.Net(w.widths, w.acts, w.loss, w.batch)
+        net.set_all(w.W, w.b)
+        X, y = to_dev(w)
+        net.dn_train_epoch(X, y, w.batch, w.lr, w.momentum)
+        outs.append(net.get_all())
+        net.close()
+    for a, b in zip(outs[0][0] + outs[0][1], outs[1][0] + outs[1][1]):
+        assert np.array_equal(a, b)
 
 
 # --------------------------------------------------- the five named workloads ----

@@ -106,8 +106,8 @@ struct OnlineGeom {
     int lds_x, lds_a[ON_MAX_L + 1], lds_own_a[ON_MAX_L + 1], lds_own_d[ON_MAX_L + 1];
     int lds_b[ON_MAX_L + 1];  // own biases, then their velocities
     int lds_w[ON_MAX_L + 1], lds_v[ON_MAX_L + 1];   // own weight / velocity slices when resident
-    int resident;
-    int lds_out, lds_kpart, lds_tmp, lds_floats;
+    int resident;             // bit l: layer l's slices are kept in LDS
+    int lds_out, lds_kpart, lds_tmp, lds_work_floats, lds_floats;
 };
 
 struct OnlineLayer {
@@ -131,7 +131,7 @@ struct OnlinePlan {
     uint32_t seq0;                              // step numbers seq0+1 .. seq0+n_samples stamp the exchange words
     int lds_x, lds_a[ON_MAX_L + 1], lds_own_a[ON_MAX_L + 1], lds_own_d[ON_MAX_L + 1];
     int lds_b[ON_MAX_L + 1], lds_w[ON_MAX_L + 1], lds_v[ON_MAX_L + 1];
-    int resident;                               // weight slices are kept in LDS for the whole launch
+    int resident;                               // bit l: layer l's weight slice is kept in LDS for the whole launch
     int lds_out, lds_kpart, lds_tmp;
 };
 

@@ -592,8 +592,9 @@ __global__ __launch_bounds__(ON_THREADS) void online_epoch_kernel(OnlinePlan p)
     const int n0 = p.layer[1].n_in;
     const int nL = p.layer[L].n_out;
     const OnlineLayer &last = p.layer[L];
-    const bool res = p.resident != 0;          // weight slices live in LDS
-    const bool vres = res && p.mu != 0.f;      // velocity slices too
+    // layer l's weight slice lives in LDS (bit l of p.resident), and with momentum its velocity slice too
+    auto res_of = [&](int l) { return ((p.resident >> l) & 1) != 0; };
+    const bool with_v = p.mu != 0.f;
 
     // slices owned by this workgroup
     const int c0 = w * last.per;                                  // columns of W_L
@@ -626,14 +627,15 @@ __global__ __launch_bounds__(ON_THREADS) void online_epoch_kernel(OnlinePlan p)
             bl[r] = ly.b[r0 + r];
             vbl[r] = ly.Vb[r0 + r];
         }
-        if (res && nr > 0) copy_floats(lds + p.lds_w[l], ly.W + (size_t)r0 * ly.n_in, nr * ly.n_in);
-        if (vres && nr > 0) copy_floats(lds + p.lds_v[l], ly.VW + (size_t)r0 * ly.n_in, nr * ly.n_in);
+        if (res_of(l) && nr > 0) copy_floats(lds + p.lds_w[l], ly.W + (size_t)r0 * ly.n_in, nr * ly.n_in);
+        if (res_of(l) && with_v && nr > 0) copy_floats(lds + p.lds_v[l], ly.VW + (size_t)r0 * ly.n_in, nr * ly.n_in);
     }
-    if (res)
+    const bool res_last = res_of(L), vres_last = res_last && with_v;
+    if (res_last)
         for (int i = tid; i < nL * nc; i += kThreads) {
             const int k = i / nc, j = i - k * nc;
             lds[p.lds_w[L] + k * ncp + j] = last.W[(size_t)k * last.n_in + c0 + j];
-            if (vres) lds[p.lds_v[L] + k * ncp + j] = last.VW[(size_t)k * last.n_in + c0 + j];
+            if (vres_last) lds[p.lds_v[L] + k * ncp + j] = last.VW[(size_t)k * last.n_in + c0 + j];
         }
     if (need_x)
         for (int k = tid; k < n0; k += kThreads) xa0[k] = p.X[k];
@@ -680,7 +682,7 @@ __global__ __launch_bounds__(ON_THREADS) void online_epoch_kernel(OnlinePlan p)
                     if (s_abort) { aborted = true; break; }
                     xin = dst;
                 }
-                if (res) {
+                if (res_of(l)) {
                     const float *Wt = lds + p.lds_w[l];
                     if ((nr << ly.kshift) <= kWaves) {      // one (row, segment) per wave: no batching needed
                         if (ly.vec4) fwd_rows<4, 1>(Wt, ly.n_in, nr, ly.kshift, ly.seg, xin, kpart);
@@ -690,7 +692,7 @@ __global__ __launch_bounds__(ON_THREADS) void online_epoch_kernel(OnlinePlan p)
                         else fwd_rows<1, 4>(Wt, ly.n_in, nr, ly.kshift, ly.seg, xin, kpart);
                     }
                 } else {
-                    const float *Wt = ly.W + (size_t)r0 * ly.n_in;
+                    const float *Wt = ly.W + (size_t)r0 * ly.n_in;   // streamed: four rows of loads in flight per wave (two and eight measured slower)
                     if (ly.vec4) fwd_rows<4, 4>(Wt, ly.n_in, nr, ly.kshift, ly.seg, xin, kpart);
                     else fwd_rows<1, 4>(Wt, ly.n_in, nr, ly.kshift, ly.seg, xin, kpart);
                 }
@@ -714,7 +716,7 @@ __global__ __launch_bounds__(ON_THREADS) void online_epoch_kernel(OnlinePlan p)
         const float *a_last = (L == 1) ? (x + c0) : (lds + p.lds_own_a[L - 1]);
         if (nc > 0) {
             u64 *zout = p.z_x + ((size_t)par * last.P + w) * nL;
-            if (res) fwd_cols(lds + p.lds_w[L], ncp, nL, nc, a_last, zout, seq);
+            if (res_last) fwd_cols(lds + p.lds_w[L], ncp, nL, nc, a_last, zout, seq);
             else fwd_cols(last.W + c0, last.n_in, nL, nc, a_last, zout, seq);
         }
         if (L == 1) DN_PREFETCH_X();
@@ -759,9 +761,9 @@ __global__ __launch_bounds__(ON_THREADS) void online_epoch_kernel(OnlinePlan p)
             if (nc > 0) {
                 float *d_prev = (L >= 2) ? (lds + p.lds_own_d[L - 1]) : nullptr;
                 const int act_prev = (L >= 2) ? p.layer[L - 1].act : 0;
-                float *Vt = vres ? (lds + p.lds_v[L]) : (last.VW + c0);
-                const int vstride = vres ? ncp : last.n_in;
-                if (res)
+                float *Vt = vres_last ? (lds + p.lds_v[L]) : (last.VW + c0);
+                const int vstride = vres_last ? ncp : last.n_in;
+                if (res_last)
                     bwd_cols(lds + p.lds_w[L], ncp, Vt, vstride, nL, nc, a_last, dL, p.lr, p.mu, mode, d_prev,
                              act_prev);
                 else
@@ -787,7 +789,8 @@ __global__ __launch_bounds__(ON_THREADS) void online_epoch_kernel(OnlinePlan p)
                 if (s_abort) { aborted = true; break; }
             }
             const float *ain = (l == 1) ? x : (lds + p.lds_a[l - 1]);
-            float *Vt = vres ? (lds + p.lds_v[l]) : (ly.VW + (size_t)r0 * ly.n_in);
+            const bool res = res_of(l);
+            float *Vt = (res && with_v) ? (lds + p.lds_v[l]) : (ly.VW + (size_t)r0 * ly.n_in);
             u64 *pout = (l >= 2) ? p.part_x[l] + ((size_t)par * ly.P + w) * ly.n_in : nullptr;
 #define DN_BWD_ROWS(WT, RU)                                                                                   \
             do {                                                                                              \
@@ -849,14 +852,14 @@ __global__ __launch_bounds__(ON_THREADS) void online_epoch_kernel(OnlinePlan p)
             ly.b[r0 + r] = bl[r];
             if (v_touched) ly.Vb[r0 + r] = vbl[r];
         }
-        if (res && nr > 0) copy_floats(ly.W + (size_t)r0 * ly.n_in, lds + p.lds_w[l], nr * ly.n_in);
-        if (vres && nr > 0) copy_floats(ly.VW + (size_t)r0 * ly.n_in, lds + p.lds_v[l], nr * ly.n_in);
+        if (res_of(l) && nr > 0) copy_floats(ly.W + (size_t)r0 * ly.n_in, lds + p.lds_w[l], nr * ly.n_in);
+        if (res_of(l) && with_v && nr > 0) copy_floats(ly.VW + (size_t)r0 * ly.n_in, lds + p.lds_v[l], nr * ly.n_in);
     }
-    if (res)
+    if (res_last)
         for (int i = tid; i < nL * nc; i += kThreads) {
             const int k = i / nc, j = i - k * nc;
             last.W[(size_t)k * last.n_in + c0 + j] = lds[p.lds_w[L] + k * ncp + j];
-            if (vres) last.VW[(size_t)k * last.n_in + c0 + j] = lds[p.lds_v[L] + k * ncp + j];
+            if (vres_last) last.VW[(size_t)k * last.n_in + c0 + j] = lds[p.lds_v[L] + k * ncp + j];
         }
     if (w == 0) {
         if (tid == 0) *p.loss_acc += loss_acc;
@@ -935,18 +938,25 @@ bool online_geometry(const int32_t *n, int L, int min_tile, bool want_v, OnlineG
     g.lds_kpart = (int)f; f += pad4(kp);
     g.lds_tmp = (int)f; f += ON_TMP_FLOATS;
     if (f * (int64_t)sizeof(float) > (int64_t)ON_MAX_LDS_BYTES) return false;
-    // the workgroup's weight slices (and velocity slices) in LDS, if they fit
-    int64_t tiles = 0;
-    for (int l = 1; l <= L - 1; ++l) tiles += (int64_t)g.per[l] * pad4(n[l - 1]);
-    tiles += (int64_t)n[L] * pad4(g.per[L]);
+    g.lds_work_floats = (int)f;
+    // The workgroup's weight slices (with their velocity slices when those are read every step)
+    // go to LDS layer by layer, smallest first, while they fit.
     const int64_t copies = want_v ? 2 : 1;
-    if ((f + copies * tiles) * (int64_t)sizeof(float) <= (int64_t)ON_MAX_LDS_BYTES) {
-        g.resident = 1;
+    const int64_t budget = (int64_t)ON_MAX_LDS_BYTES / (int64_t)sizeof(float);
+    bool taken[ON_MAX_L + 1] = {false};
+    for (;;) {
+        int best = 0;
+        int64_t best_t = 0;
         for (int l = 1; l <= L; ++l) {
+            if (taken[l]) continue;
             const int64_t t = (l < L) ? (int64_t)g.per[l] * pad4(n[l - 1]) : (int64_t)n[L] * pad4(g.per[L]);
-            g.lds_w[l] = (int)f; f += t;
-            if (want_v) { g.lds_v[l] = (int)f; f += t; }
+            if (best == 0 || t < best_t) { best = l; best_t = t; }
         }
+        if (best == 0 || f + copies * best_t > budget) break;
+        taken[best] = true;
+        g.resident |= 1 << best;
+        g.lds_w[best] = (int)f; f += best_t;
+        if (want_v) { g.lds_v[best] = (int)f; f += best_t; }
     }
     g.lds_floats = (int)f;
     g.ok = true;

@@ -166,6 +166,34 @@ dn_status dn_train_epoch(dn_net *net, const float *X_dev, const int32_t *labels_
                          float *mean_loss_host);
 
 /*
+ * Training run with the work-flow's stopping rule: the configuration parameters the paper
+ * lists include "the maximum error that can be tolerated", and back propagation goes on
+ * while the loss error assessment finds the network above it.  Here the rule is applied per
+ * epoch: epochs of dn_train_epoch are run until an epoch's loss (as dn_train_epoch reports
+ * it) is <= max_error or max_epochs epochs have run.
+ *   epochs_run_host   receives the number of epochs run (>= 1); may be NULL
+ *   last_loss_host    receives the last epoch's loss; may be NULL
+ * Errors: those of dn_train_epoch; INVALID_ARG also for max_epochs <= 0 or a NaN max_error.
+ */
+dn_status dn_train(dn_net *net, const float *X_dev, const int32_t *labels_dev, int64_t n_samples,
+                   int32_t batch, float lr, float momentum, float max_error, int32_t max_epochs,
+                   int32_t *epochs_run_host, float *last_loss_host);
+
+/*
+ * Loss error assessment without training (the paper's benchmark application ends with a test
+ * of the trained network on the held-out part of its data set): feed forward over
+ * n_samples samples in chunks of `batch` at the current parameters.
+ *   mean_loss_host   receives the mean loss per sample; may be NULL
+ *   correct_host     receives the number of samples whose largest output is at the label's
+ *                    index (lowest index among equal outputs); may be NULL
+ * Parameters are not changed; activations left by dn_forward are overwritten (a following
+ * dn_backward needs a new dn_forward).  Errors: INVALID_ARG (NULL, n_samples <= 0), SHAPE
+ * (batch outside 1..max_batch), DEVICE.
+ */
+dn_status dn_evaluate(dn_net *net, const float *X_dev, const int32_t *labels_dev, int64_t n_samples,
+                      int32_t batch, float *mean_loss_host, int64_t *correct_host);
+
+/*
  * Measurement hooks (the paper times its two offloaded methods with wall-clock
  * timers, section "Experimental Evaluation"; here the device itself is timed).
  *

@@ -288,6 +288,51 @@ double PFX(train_epoch)(int L, const int32_t *n, const int32_t *acts, int loss, 
     return seen ? loss_total / (double)seen : 0.0;
 }
 
+/*
+ * Loss error assessment without training (the work-flow's comparison of the
+ * network output with the desired output through the loss function, and the
+ * paper's test step on held-out data): forward pass over all N samples at the
+ * current parameters.  Returns the mean loss; *correct receives the number of
+ * samples whose largest output sits at the label's index (the lowest index wins
+ * a tie; outputs are compared as stored).
+ */
+double PFX(evaluate)(int L, const int32_t *n, const int32_t *acts, int loss, const real *params,
+                     const real *X, const int32_t *labels, int64_t N, int64_t *correct)
+{
+    const int chunk = 64;
+    const int nL = n[L];
+    const size_t na = PFX(act_count)(L, n, chunk);
+    real *A = (real *)malloc(na * sizeof(real));
+    if (!A)
+        return NAN;
+    double loss_total = 0.0;
+    int64_t hits = 0;
+    for (int64_t s0 = 0; s0 < N; s0 += chunk) {
+        const int b = (int)((N - s0) < chunk ? (N - s0) : chunk);
+        forward_impl(L, n, acts, params, X + (size_t)s0 * (size_t)n[0], b, A, 0.0, NULL);
+        const real *AL = A + a_offset(n, L, b);
+        for (int s = 0; s < b; ++s) {
+            const real *a = AL + (size_t)s * nL;
+            const int y = labels[s0 + s];
+            if (loss == LOSS_CE) {
+                loss_total += -log((double)a[y] > 0.0 ? (double)a[y] : 1e-300);
+            } else {
+                for (int o = 0; o < nL; ++o) {
+                    double diff = (double)a[o] - (o == y ? 1.0 : 0.0);
+                    loss_total += 0.5 * diff * diff;
+                }
+            }
+            int best = 0;
+            for (int o = 1; o < nL; ++o)
+                if (a[o] > a[best]) best = o;
+            if (best == y) hits++;
+        }
+    }
+    free(A);
+    if (correct) *correct = hits;
+    return N > 0 ? loss_total / (double)N : 0.0;
+}
+
 /* Number of threads the loops above will use (1 without OpenMP). */
 #ifdef _OPENMP
 #include <omp.h>

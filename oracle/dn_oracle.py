@@ -59,6 +59,7 @@ class Oracle:
         self._backward = f("backward"); self._backward.restype = C.c_double
         self._update = f("update"); self._update.restype = None
         self._train_epoch = f("train_epoch"); self._train_epoch.restype = C.c_double
+        self._evaluate = f("evaluate"); self._evaluate.restype = C.c_double
         self.P = int(self._param_count(C.c_int(self.L), self._ip(self.widths)))
         self.params = np.zeros(self.P, dtype=self.dtype)
         self.vel = np.zeros(self.P, dtype=self.dtype)
@@ -152,6 +153,27 @@ class Oracle:
                                  C.c_int(batch), self._real(lr), self._real(momentum),
                                  C.c_int64(steps_limit), C.c_double(kink_eps), C.byref(kinks))
         return float(loss), int(kinks.value)
+
+    def evaluate(self, X: np.ndarray, labels: np.ndarray) -> Tuple[float, int]:
+        """(mean loss, number of samples whose largest output is at the label) at the current parameters."""
+        X = np.ascontiguousarray(X, dtype=self.dtype)
+        labels = np.ascontiguousarray(labels, dtype=np.int32)
+        correct = C.c_int64(0)
+        loss = self._evaluate(C.c_int(self.L), self._ip(self.widths), self._ip(self.acts), C.c_int(self.loss),
+                              self._rp(self.params), self._rp(X), self._ip(labels), C.c_int64(X.shape[0]),
+                              C.byref(correct))
+        return float(loss), int(correct.value)
+
+    def train(self, X: np.ndarray, labels: np.ndarray, batch: int, lr: float, momentum: float,
+              max_error: float, max_epochs: int) -> Tuple[int, float, List[float]]:
+        """Epochs until the epoch loss is at most max_error (the work-flow's maximum-error
+        parameter) or max_epochs have run: (epochs run, last epoch loss, all epoch losses)."""
+        losses = []
+        for _ in range(max_epochs):
+            losses.append(self.train_epoch(X, labels, batch, lr, momentum)[0])
+            if losses[-1] <= max_error:
+                break
+        return len(losses), losses[-1], losses
 
     def loss_value(self, X: np.ndarray, labels: np.ndarray) -> float:
         """Batch-mean loss at the current parameters (forward + loss only)."""

@@ -23,7 +23,7 @@ struct Layout {
     size_t region = 0;          // bytes of one parameter-shaped region (params / velocity / gradients)
     std::vector<size_t> A, D;   // activations / deltas of layers 1..L, absolute
     size_t off_params = 0, off_vel = 0, off_grads = 0;
-    size_t off_loss_rows = 0, off_scalars = 0;
+    size_t off_loss_rows = 0, off_hit_rows = 0, off_scalars = 0;
     size_t off_online = 0, online_bytes = 0;   // exchange buffers of the persistent batch-1 kernel
     size_t off_gemm_ws = 0, off_gemm_counters = 0;   // partial tiles / arrival counters of k-split contractions
     size_t total = 0;
@@ -63,6 +63,7 @@ bool compute_layout(const int32_t *widths, int32_t n_widths, int32_t max_batch, 
         if (o > lim) return false;
     }
     lo.off_loss_rows = o; o += align_up((size_t)max_batch * sizeof(float));
+    lo.off_hit_rows = o; o += align_up((size_t)max_batch * sizeof(float));
     lo.off_scalars = o; o += kAlign;
     lo.online_bytes = online_exchange_bytes_bound(widths, L);
     lo.off_online = o; o += align_up(lo.online_bytes);
@@ -117,6 +118,8 @@ struct dn_net {
     float *A(int l) const { return (float *)(arena + lo.A[l]); }
     float *D(int l) const { return (float *)(arena + lo.D[l]); }
     float *loss_rows() const { return (float *)(arena + lo.off_loss_rows); }
+    float *hit_rows() const { return (float *)(arena + lo.off_hit_rows); }
+    double *hit_acc() const { return (double *)(arena + lo.off_scalars + 16); }   // after epoch_acc and the abort flag
     double *epoch_acc() const { return (double *)(arena + lo.off_scalars); }
     int *abort_flag() const { return (int *)(arena + lo.off_scalars + sizeof(double)); }
     unsigned long long *exchange() const { return (unsigned long long *)(arena + lo.off_online); }
@@ -514,6 +517,49 @@ dn_status dn_train_epoch(dn_net *net, const float *X_dev, const int32_t *labels_
     if (res.aborted) return DN_ERR_DEVICE;   // a workgroup of the persistent kernel gave up waiting
     const double acc = res.acc;
     if (mean_loss_host) *mean_loss_host = (float)(acc / (double)n_samples);
+    return DN_OK;
+}
+
+dn_status dn_train(dn_net *net, const float *X_dev, const int32_t *labels_dev, int64_t n_samples, int32_t batch,
+                   float lr, float momentum, float max_error, int32_t max_epochs, int32_t *epochs_run_host,
+                   float *last_loss_host)
+{
+    if (!net || max_epochs <= 0 || std::isnan(max_error)) return DN_ERR_INVALID_ARG;
+    float loss = 0.f;
+    int32_t e = 0;
+    while (e < max_epochs) {
+        dn_status st = dn_train_epoch(net, X_dev, labels_dev, n_samples, batch, lr, momentum, &loss);
+        if (st != DN_OK) return st;
+        ++e;
+        if (loss <= max_error) break;
+    }
+    if (epochs_run_host) *epochs_run_host = e;
+    if (last_loss_host) *last_loss_host = loss;
+    return DN_OK;
+}
+
+dn_status dn_evaluate(dn_net *net, const float *X_dev, const int32_t *labels_dev, int64_t n_samples, int32_t batch,
+                      float *mean_loss_host, int64_t *correct_host)
+{
+    if (!net || !X_dev || !labels_dev || n_samples <= 0) return DN_ERR_INVALID_ARG;
+    if (batch < 1 || batch > net->max_batch) return DN_ERR_SHAPE;
+    net->have_fwd = net->have_bwd = false;  // the activations of the split API are overwritten
+    const int L = net->L;
+    DN_HIP(hipMemsetAsync(net->epoch_acc(), 0, 24, net->stream));
+    for (int64_t s0 = 0; s0 < n_samples; s0 += batch) {
+        const int B = (int)((n_samples - s0) < batch ? (n_samples - s0) : batch);
+        dn_status st = run_forward(net, X_dev + (size_t)s0 * net->n[0], B, false);
+        if (st != DN_OK) return st;
+        DN_HIP(launch_output_delta(net->A(L), net->D(L), labels_dev + s0, net->loss_rows(), B, net->n[L],
+                                   net->act[L], net->loss, OUT_EVAL, net->stream, net->hit_rows()));
+        DN_HIP(launch_loss_reduce(net->loss_rows(), B, nullptr, net->epoch_acc(), net->stream));
+        DN_HIP(launch_loss_reduce(net->hit_rows(), B, nullptr, net->hit_acc(), net->stream));
+    }
+    struct { double loss; int aborted; int pad; double hits; } res = {0.0, 0, 0, 0.0};
+    DN_HIP(hipMemcpyAsync(&res, net->epoch_acc(), 24, hipMemcpyDeviceToHost, net->stream));
+    DN_HIP(hipStreamSynchronize(net->stream));
+    if (mean_loss_host) *mean_loss_host = (float)(res.loss / (double)n_samples);
+    if (correct_host) *correct_host = (int64_t)(res.hits + 0.5);
     return DN_OK;
 }
 

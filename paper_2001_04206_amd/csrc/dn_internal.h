@@ -70,10 +70,13 @@ const char *gemm_variant_name(int variant);
 enum OutPhase : int {
     OUT_FUSED = 0,         // z -> p, Delta_L, loss            (training step)
     OUT_SOFTMAX_ONLY = 1,  // z -> p                           (dn_forward; labels unused)
-    OUT_FROM_P = 2         // p -> Delta_L, loss               (dn_backward)
+    OUT_FROM_P = 2,        // p -> Delta_L, loss               (dn_backward)
+    OUT_EVAL = 3           // z (cross-entropy) or a (squared error) -> loss and hit flag, rows untouched (dn_evaluate)
 };
+// hit_rows (OUT_EVAL only): 1.0 where the row's largest output is at the label, else 0.0.
 hipError_t launch_output_delta(float *AL, float *DL, const int32_t *labels, float *loss_rows,
-                               int B, int nL, int act, int loss, int phase, hipStream_t stream);
+                               int B, int nL, int act, int loss, int phase, hipStream_t stream,
+                               float *hit_rows = nullptr);
 // Sum loss_rows[0..B): *loss_mean_out = sum / B (if non-null); *epoch_acc += sum (if non-null).
 hipError_t launch_loss_reduce(const float *loss_rows, int B, float *loss_mean_out,
                               double *epoch_acc, hipStream_t stream);

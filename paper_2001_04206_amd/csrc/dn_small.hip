@@ -57,7 +57,7 @@ __device__ __forceinline__ float deriv_from_output(int act, float a)
 __global__ __launch_bounds__(256) void output_delta_kernel(float *__restrict__ AL, float *__restrict__ DL,
                                                            const int32_t *__restrict__ labels,
                                                            float *__restrict__ loss_rows, int nL, int act,
-                                                           int loss, int phase)
+                                                           int loss, int phase, float *__restrict__ hit_rows)
 {
     __shared__ float red[4];
     const int s = blockIdx.x, tid = threadIdx.x;
@@ -65,6 +65,36 @@ __global__ __launch_bounds__(256) void output_delta_kernel(float *__restrict__ A
     float *d = DL + (size_t)s * nL;
     int y = (phase == OUT_SOFTMAX_ONLY) ? 0 : labels[s];
     y = y < 0 ? 0 : (y >= nL ? nL - 1 : y);  // labels are the caller's; never index outside the row
+    if (phase == OUT_EVAL) {
+        // loss and hit flag only; the largest output wins, the lowest index among equals
+        // (softmax is monotone, so for cross-entropy the net inputs z are compared)
+        float m = -INFINITY;
+        for (int o = tid; o < nL; o += 256) m = fmaxf(m, a[o]);
+        m = block_max(m, red);
+        float first = (float)nL;
+        for (int o = tid; o < nL; o += 256)
+            if (a[o] == m) { first = (float)o; break; }
+        first = -block_max(-first, red);
+        float e;
+        if (loss == DN_LOSS_CROSS_ENTROPY) {
+            float sum = 0.f;
+            for (int o = tid; o < nL; o += 256) sum += expf(a[o] - m);
+            sum = block_sum(sum, red);
+            e = logf(sum) - (a[y] - m);
+        } else {
+            e = 0.f;
+            for (int o = tid; o < nL; o += 256) {
+                const float diff = a[o] - (o == y ? 1.0f : 0.0f);
+                e += 0.5f * diff * diff;
+            }
+            e = block_sum(e, red);
+        }
+        if (tid == 0) {
+            loss_rows[s] = e;
+            hit_rows[s] = ((int)first == y) ? 1.0f : 0.0f;
+        }
+        return;
+    }
     if (loss == DN_LOSS_CROSS_ENTROPY && phase != OUT_FROM_P) {
         float m = -INFINITY;
         for (int o = tid; o < nL; o += 256) m = fmaxf(m, a[o]);
@@ -133,10 +163,11 @@ __global__ __launch_bounds__(256) void copy_kernel(float *__restrict__ dst, cons
 }
 
 hipError_t launch_output_delta(float *AL, float *DL, const int32_t *labels, float *loss_rows, int B,
-                               int nL, int act, int loss, int phase, hipStream_t stream)
+                               int nL, int act, int loss, int phase, hipStream_t stream, float *hit_rows)
 {
+    if (phase == OUT_EVAL && !hit_rows) return hipErrorInvalidValue;
     hipLaunchKernelGGL(output_delta_kernel, dim3(B), dim3(256), 0, stream, AL, DL, labels, loss_rows, nL, act,
-                       loss, phase);
+                       loss, phase, hit_rows);
     return hipGetLastError();
 }
 

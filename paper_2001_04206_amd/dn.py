@@ -25,6 +25,7 @@ KERNEL_CLASS_NAMES = ["forward", "delta", "grad_update", "output", "online"]
 EXPORTS = [
     "dn_status_string", "dn_net_arena_bytes", "dn_net_create", "dn_net_destroy", "dn_set_params",
     "dn_get_params", "dn_get_grads", "dn_forward", "dn_backward", "dn_update", "dn_train_epoch",
+    "dn_train", "dn_evaluate",
     "dn_last_epoch_ms", "dn_kernel_time", "dn_set_option",
 ]
 
@@ -61,6 +62,8 @@ def lib():
         l.dn_backward.argtypes = [vp, vp, i32, vp]
         l.dn_update.argtypes = [vp, f32, f32]
         l.dn_train_epoch.argtypes = [vp, vp, vp, i64, i32, f32, f32, C.POINTER(f32)]
+        l.dn_train.argtypes = [vp, vp, vp, i64, i32, f32, f32, f32, i32, C.POINTER(i32), C.POINTER(f32)]
+        l.dn_evaluate.argtypes = [vp, vp, vp, i64, i32, C.POINTER(f32), C.POINTER(i64)]
         l.dn_last_epoch_ms.argtypes = [vp, C.POINTER(f32)]
         l.dn_kernel_time.argtypes = [vp, i32, C.POINTER(f32), C.POINTER(i64)]
         l.dn_set_option.argtypes = [vp, C.c_char_p, i64]
@@ -199,6 +202,26 @@ class Net:
                                     n, int(batch), float(lr), float(momentum), C.byref(loss)),
                "dn_train_epoch")
         return float(loss.value)
+
+    def dn_train(self, X, labels, batch: int, lr: float, momentum: float, max_error: float,
+                 max_epochs: int, n_samples: Optional[int] = None) -> Tuple[int, float]:
+        """(epochs run, last epoch loss)."""
+        t = self._torch
+        n = int(X.shape[0]) if n_samples is None else int(n_samples)
+        epochs, loss = C.c_int32(0), C.c_float(0.0)
+        _check(lib().dn_train(self._h, _dev_ptr(X, t.float32, "X"), _dev_ptr(labels, t.int32, "labels"), n,
+                              int(batch), float(lr), float(momentum), float(max_error), int(max_epochs),
+                              C.byref(epochs), C.byref(loss)), "dn_train")
+        return int(epochs.value), float(loss.value)
+
+    def dn_evaluate(self, X, labels, batch: int, n_samples: Optional[int] = None) -> Tuple[float, int]:
+        """(mean loss, number of samples whose largest output is at the label)."""
+        t = self._torch
+        n = int(X.shape[0]) if n_samples is None else int(n_samples)
+        loss, correct = C.c_float(0.0), C.c_int64(0)
+        _check(lib().dn_evaluate(self._h, _dev_ptr(X, t.float32, "X"), _dev_ptr(labels, t.int32, "labels"), n,
+                                 int(batch), C.byref(loss), C.byref(correct)), "dn_evaluate")
+        return float(loss.value), int(correct.value)
 
     # -- measurement ---------------------------------------------------------------
     def dn_last_epoch_ms(self) -> float:

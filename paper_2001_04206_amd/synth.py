@@ -138,3 +138,18 @@ def paper_shape(n_samples: int = 64, seed: int = 0, hidden: int = 100000) -> Wor
     return make("mlp_340_%d_10_online" % hidden, [340, hidden, 10], [ACT_TANH, ACT_SOFTMAX],
                 LOSS_CROSS_ENTROPY, n_samples=n_samples, features="uniform01",
                 init="xavier_uniform", batch=1, lr=0.01, momentum=0.0, seed=seed)
+
+
+def learnable(widths: Sequence[int] = (20, 32, 4), n_samples: int = 400, batch: int = 8, lr: float = 0.1,
+              momentum: float = 0.0, seed: int = 0) -> Workload:
+    """A task with signal, for the loss-gated training loop and the held-out test: labels are the
+    index of the largest of n_L fixed random projections of the features (all other workloads
+    have random labels, on which the loss cannot fall).  Extra draw after the usual ones: the
+    projection matrix."""
+    acts = [ACT_TANH] * (len(widths) - 2) + [ACT_SOFTMAX]
+    w = make("learnable", widths, acts, LOSS_CROSS_ENTROPY, n_samples=n_samples, features="normal",
+             init="xavier_uniform", batch=batch, lr=lr, momentum=momentum, seed=seed)
+    rng = np.random.default_rng(seed + 1000003)
+    T = rng.standard_normal((w.widths[0], w.widths[-1]))
+    w.labels = np.ascontiguousarray(np.argmax(w.X.astype(np.float64) @ T, axis=1).astype(np.int32))
+    return w

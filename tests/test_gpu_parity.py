@@ -303,3 +303,53 @@ def test_same_seed_twice_is_bitwise_identical(dnlib):
         net.close()
     for a, b in zip(outs[0][0] + outs[0][1], outs[1][0] + outs[1][1]):
         assert np.array_equal(a, b)
+
+
+# ---------------------------------------------- evaluation and the stopping rule ----
+
+@pytest.mark.parametrize("widths,acts,loss", [([20, 32, 4], [TANH, SOFTMAX], CE), ([37, 70, 5], [RELU, SIG], MSE),
+                                              ([300, 10], [SOFTMAX], CE), ([64, 200, 300], [TANH, SOFTMAX], CE)])
+def test_evaluate_matches_checker(dnlib, widths, acts, loss):
+    announce("evaluate widths=%s" % (widths,))
+    w = synth.make("eval", widths, acts, loss, n_samples=333, features="normal", init="xavier_uniform",
+                   batch=50, lr=0.1, momentum=0.0, seed=12)
+    net, o = make_pair(dnlib, w, 50)
+    X, y = to_dev(w)
+    before = net.get_all()
+    got_loss, got_hits = net.dn_evaluate(X, y, 50)          # 6 chunks of 50 and one of 33
+    ref_loss, ref_hits = o.evaluate(w.X, w.labels)
+    assert abs(got_loss - ref_loss) <= STEP_TOL * abs(ref_loss)
+    # a hit is an argmax: samples whose two largest outputs are closer than rounding may fall either way
+    out = np.sort(o.forward(w.X)[-1].astype(np.float64), axis=1)
+    near_ties = int(np.sum(out[:, -1] - out[:, -2] < 1e-5 * np.abs(out[:, -1])))
+    assert abs(got_hits - ref_hits) <= near_ties, (got_hits, ref_hits, near_ties)
+    after = net.get_all()
+    for a, b in zip(before[0] + before[1], after[0] + after[1]):
+        assert np.array_equal(a, b)
+    net.close()
+
+
+@pytest.mark.parametrize("batch", [1, 8])
+def test_train_until_max_error_matches_checker(dnlib, batch):
+    announce("train until max error, batch %d" % batch)
+    w = synth.learnable(batch=batch)
+    net, o = make_pair(dnlib, w, batch)
+    X, y = to_dev(w)
+    _, _, losses = o.train(w.X, w.labels, batch, w.lr, w.momentum, -1.0, 10)
+    k = next(i for i in range(1, 10) if losses[i] < min(losses[:i]))
+    threshold = 0.5 * (losses[k] + min(losses[:k]))         # midway: rounding cannot move the stopping epoch
+    epochs, last = net.dn_train(X, y, batch, w.lr, w.momentum, threshold, 10)
+    assert epochs == k + 1
+    assert abs(last - losses[k]) <= EPOCH_TOL * abs(losses[k])
+    o.set_params(w.W, w.b)
+    o.train(w.X, w.labels, batch, w.lr, w.momentum, threshold, 10)
+    W, b = net.get_all(); Wr, br = o.get_params()
+    for l in range(net.L):
+        assert_close(W[l], Wr[l], EPOCH_TOL, "W_%d" % (l + 1))
+        assert_close(b[l], br[l], EPOCH_TOL, "b_%d" % (l + 1))
+    # never reaching the threshold runs max_epochs; bad arguments are refused
+    assert net.dn_train(X, y, batch, w.lr, w.momentum, -1.0, 2)[0] == 2
+    with pytest.raises(dnlib.DnError) as e:
+        net.dn_train(X, y, batch, w.lr, w.momentum, 0.1, 0)
+    assert e.value.status == dnlib.DN_ERR_INVALID_ARG
+    net.close()

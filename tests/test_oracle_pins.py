@@ -411,3 +411,60 @@ def test_kink_census_counts_small_relu_net_inputs():
     _, kinks = o.train_epoch(X, np.zeros(3, dtype=np.int32), batch=1, lr=0.0, momentum=0.0,
                              kink_eps=1e-5)
     assert kinks == 2       # hidden unit 0 on samples 0 and 2
+
+
+# ------------------------------------------------- evaluation and stopping rule ----
+
+@pytest.mark.parametrize("acts,loss", [([TANH, SOFTMAX], CE), ([SIG, SIG], MSE), ([SOFTMAX], CE)])
+def test_evaluate_matches_library_loss_and_argmax(acts, loss):
+    """Mean loss from scipy's log-sum-exp / a direct squared-error formula, hits from numpy's
+    argmax, both on a library forward pass; 157 samples span several of the checker's chunks."""
+    from scipy.special import logsumexp
+    rng = np.random.default_rng(21)
+    widths = [6, 9, 5] if len(acts) == 2 else [6, 5]
+    W, b = rand_net(rng, widths)
+    X = rng.standard_normal((157, widths[0]))
+    labels = rng.integers(0, widths[-1], size=157).astype(np.int32)
+    o = Oracle("o64", widths, acts, loss)
+    o.set_params(W, b)
+    got_loss, got_hits = o.evaluate(X, labels)
+    outs = np_forward(W, b, acts, X)
+    if loss == CE:
+        a_prev = outs[-2] if len(acts) > 1 else X
+        z = a_prev @ W[-1].T + b[-1]
+        want = float(np.mean(logsumexp(z, axis=1) - z[np.arange(157), labels]))
+    else:
+        want = float(np.mean(0.5 * np.sum((outs[-1] - onehot(labels, widths[-1])) ** 2, axis=1)))
+    assert abs(got_loss - want) <= 1e-12 * max(1.0, abs(want))
+    assert got_hits == int(np.sum(np.argmax(outs[-1], axis=1) == labels))
+
+
+def test_evaluate_counts_ties_for_the_lowest_index_and_leaves_parameters_alone():
+    o = Oracle("o64", [2, 3], [LIN], MSE)
+    o.set_params([np.zeros((3, 2))], [np.array([0.5, 0.5, 0.1])])      # outputs 0.5, 0.5, 0.1 for any input
+    before = o.params.copy()
+    X = np.ones((3, 2))
+    loss, hits = o.evaluate(X, np.array([0, 1, 2], dtype=np.int32))
+    assert hits == 1                                                    # only label 0 is the (first) largest
+    want = np.mean([0.5 * (0.25 + 0.25 + 0.01), 0.5 * (0.25 + 0.25 + 0.01), 0.5 * (0.25 + 0.25 + 0.81)])
+    assert abs(loss - want) < 1e-15
+    assert np.array_equal(before, o.params)
+
+
+def test_training_until_max_error_stops_at_the_first_epoch_below_it():
+    from paper_2001_04206_amd import synth
+    w = synth.learnable()
+    o = Oracle("o64", w.widths, w.acts, w.loss)
+    o.set_params(w.W, w.b)
+    _, _, losses = o.train(w.X, w.labels, w.batch, w.lr, w.momentum, max_error=-1.0, max_epochs=12)
+    assert len(losses) == 12 and losses[-1] < 0.5 * losses[0]           # the task has signal: the loss falls
+    k = next(i for i in range(1, 12) if losses[i] < losses[i - 1] and losses[i] < min(losses[:i]))
+    threshold = 0.5 * (losses[k] + min(losses[:k]))                     # first crossed by epoch k+1
+    o.set_params(w.W, w.b)
+    epochs, last, again = o.train(w.X, w.labels, w.batch, w.lr, w.momentum, threshold, 12)
+    assert epochs == k + 1 and last == losses[k] and again == losses[:k + 1]
+    # the held-out part is predicted better than chance after training
+    o.set_params(w.W, w.b)
+    o.train(w.X[:360], w.labels[:360], w.batch, w.lr, w.momentum, -1.0, 12)
+    _, hits = o.evaluate(w.X[360:], w.labels[360:])
+    assert hits > 40 * 0.5

@@ -84,6 +84,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=-1, help="untimed steps (-1: workload default)")
     ap.add_argument("--workload", default="cfg4_4096x3_1000_b256")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--per-call-offload", action="store_true",
+                    help="instead of a workload: time the paper's execution model (host operands copied in, one "
+                         "layer's backward step for one sample, results copied out) on the two layers of its "
+                         "340-100000-10 network, and exit")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="instead of a workload: copy MIB mebibytes device to device three times and exit "
                          "(a plain copy of known size, to scale the profiler's HBM byte counters)")
@@ -107,6 +111,33 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"calibrate_copy_bytes": n, "copies": 3}))
+        return
+
+    if args.per_call_offload:
+        assert torch.cuda.is_available(), "bench.py needs the GPU"
+        dn.lib()
+        calls = args.steps if args.steps > 0 else 20
+        out = {"mode": "per-call offload of one layer's backward step (copy in, kernel, copy out)",
+               "calls": calls, "host_memory": "pinned", "layers": {}}
+        rng = np.random.default_rng(0)
+        for name, (co, ci) in {"softmax_output_10x100000": (10, 100000), "fully_connected_100000x340": (100000, 340)}.items():
+            pin = lambda a: torch.from_numpy(a).pin_memory()
+            d, x = pin(rng.standard_normal(co).astype(np.float32)), pin(rng.random(ci, dtype=np.float32))
+            G, dW, dB = (torch.empty(n, dtype=torch.float32).pin_memory() for n in (co * ci, co * ci, co))
+            ws = torch.empty(dn.lib().dn_layer_backward_workspace_bytes(co, ci), dtype=torch.uint8, device="cuda:0")
+            for _ in range(3):
+                dn.dn_layer_backward_host(d, x, 0.01, G, dW, dB, ws)
+            t = np.array([dn.dn_layer_backward_host(d, x, 0.01, G, dW, dB, ws) for _ in range(calls)])
+            t0 = time.perf_counter()
+            for _ in range(calls):
+                dn.dn_layer_backward_host(d, x, 0.01, G, dW, dB, ws)
+            wall = (time.perf_counter() - t0) / calls
+            mean = t.mean(axis=0)
+            out["layers"][name] = {"copy_in_ms": float(mean[0]), "kernel_ms": float(mean[1]), "copy_out_ms": float(mean[2]),
+                                   "wall_ms_per_call": wall * 1e3, "bytes_out": 4 * (2 * co * ci + co),
+                                   "kernel_GBps": 4 * (2 * co * ci) / (mean[1] * 1e-3) / 1e9,
+                                   "copy_out_GBps": 4 * (2 * co * ci + co) / (mean[2] * 1e-3) / 1e9}
+        print(json.dumps(out))
         return
 
     table = workloads()

@@ -194,6 +194,35 @@ dn_status dn_evaluate(dn_net *net, const float *X_dev, const int32_t *labels_dev
                       int32_t batch, float *mean_loss_host, int64_t *correct_host);
 
 /*
+ * The paper's offloaded method, call for call (section "How Deep Netts is parallelized with
+ * TornadoVM?"): the backward step of one layer for one sample as a task that streams its
+ * operands in from the host, runs the two-index (inputs x outputs) loop on the device and
+ * streams the results out again:
+ *     gradients[o][i]    = deltas[o] * inputs[i]
+ *     deltaWeights[o][i] = -learning_rate * gradients[o][i]
+ *     deltaBiases[o]     = -learning_rate * deltas[o]
+ * (the argument list is the one the paper prints for its softmax output layer: deltas, inputs,
+ * gradients, deltaWeights, deltaBiases, colsOut, colsInput, learningRate; the sign is the
+ * reading "the delta is what gets added to the weight").  It exists to measure that execution
+ * model -- copies around every call -- next to the device-resident dn_train_epoch; the paper
+ * finds the copies dominate for small data and names their removal as future work.
+ *   deltas_host [cols_out], inputs_host [cols_input]                              (host, read)
+ *   gradients_host, delta_weights_host [cols_out][cols_input], delta_biases_host [cols_out]
+ *                                                                                 (host, written)
+ *   workspace_dev   device memory, 256-byte aligned, >= dn_layer_backward_workspace_bytes(...)
+ *   hip_stream      stream to work on (NULL = default); the call returns after it has drained
+ *   ms_copy_in / ms_kernel / ms_copy_out   device times of the three stages; each may be NULL
+ * Errors: INVALID_ARG (NULL, non-finite rate, misaligned workspace), SHAPE (sizes <= 0, more
+ * than 2^31 weights, workspace too small), DEVICE.
+ */
+size_t dn_layer_backward_workspace_bytes(int32_t cols_out, int32_t cols_input);
+dn_status dn_layer_backward_host(const float *deltas_host, const float *inputs_host, float learning_rate,
+                                 int32_t cols_out, int32_t cols_input, float *gradients_host,
+                                 float *delta_weights_host, float *delta_biases_host, void *workspace_dev,
+                                 size_t workspace_bytes, void *hip_stream, float *ms_copy_in, float *ms_kernel,
+                                 float *ms_copy_out);
+
+/*
  * Measurement hooks (the paper times its two offloaded methods with wall-clock
  * timers, section "Experimental Evaluation"; here the device itself is timed).
  *

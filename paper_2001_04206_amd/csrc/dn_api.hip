@@ -563,6 +563,67 @@ dn_status dn_evaluate(dn_net *net, const float *X_dev, const int32_t *labels_dev
     return DN_OK;
 }
 
+size_t dn_layer_backward_workspace_bytes(int32_t cols_out, int32_t cols_input)
+{
+    if (cols_out <= 0 || cols_input <= 0) return 0;
+    const size_t nw = (size_t)cols_out * (size_t)cols_input;
+    if (nw > ((size_t)1 << 31)) return 0;
+    return align_up((size_t)cols_out * 4) * 2 + align_up((size_t)cols_input * 4) + 2 * align_up(nw * 4);
+}
+
+dn_status dn_layer_backward_host(const float *deltas_host, const float *inputs_host, float learning_rate,
+                                 int32_t cols_out, int32_t cols_input, float *gradients_host,
+                                 float *delta_weights_host, float *delta_biases_host, void *workspace_dev,
+                                 size_t workspace_bytes, void *hip_stream, float *ms_copy_in, float *ms_kernel,
+                                 float *ms_copy_out)
+{
+    if (!deltas_host || !inputs_host || !gradients_host || !delta_weights_host || !delta_biases_host ||
+        !workspace_dev || !std::isfinite(learning_rate))
+        return DN_ERR_INVALID_ARG;
+    const size_t need = dn_layer_backward_workspace_bytes(cols_out, cols_input);
+    if (need == 0 || workspace_bytes < need) return DN_ERR_SHAPE;
+    if (reinterpret_cast<uintptr_t>(workspace_dev) % kAlign != 0) return DN_ERR_INVALID_ARG;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const size_t nw = (size_t)cols_out * (size_t)cols_input;
+    char *w = (char *)workspace_dev;
+    float *d_dev = (float *)w; w += align_up((size_t)cols_out * 4);
+    float *db_dev = (float *)w; w += align_up((size_t)cols_out * 4);
+    float *x_dev = (float *)w; w += align_up((size_t)cols_input * 4);
+    float *g_dev = (float *)w; w += align_up(nw * 4);
+    float *dw_dev = (float *)w;
+    hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
+    dn_status st = DN_OK;
+    for (auto &e : ev)
+        if (hipEventCreate(&e) != hipSuccess) st = DN_ERR_DEVICE;
+    auto ok = [&](hipError_t e) { if (e != hipSuccess) st = DN_ERR_DEVICE; return st == DN_OK; };
+    if (st == DN_OK) {
+        // the task schedule of the paper: stream in, run the task, stream out
+        ok(hipEventRecord(ev[0], stream)) &&
+        ok(hipMemcpyAsync(d_dev, deltas_host, (size_t)cols_out * 4, hipMemcpyHostToDevice, stream)) &&
+        ok(hipMemcpyAsync(x_dev, inputs_host, (size_t)cols_input * 4, hipMemcpyHostToDevice, stream)) &&
+        ok(hipEventRecord(ev[1], stream)) &&
+        ok(launch_layer_backward(d_dev, x_dev, learning_rate, cols_out, cols_input, g_dev, dw_dev, db_dev, stream)) &&
+        ok(hipEventRecord(ev[2], stream)) &&
+        ok(hipMemcpyAsync(gradients_host, g_dev, nw * 4, hipMemcpyDeviceToHost, stream)) &&
+        ok(hipMemcpyAsync(delta_weights_host, dw_dev, nw * 4, hipMemcpyDeviceToHost, stream)) &&
+        ok(hipMemcpyAsync(delta_biases_host, db_dev, (size_t)cols_out * 4, hipMemcpyDeviceToHost, stream)) &&
+        ok(hipEventRecord(ev[3], stream)) &&
+        ok(hipStreamSynchronize(stream));
+    }
+    if (st == DN_OK) {
+        float a = 0.f, b = 0.f, c = 0.f;
+        if (hipEventElapsedTime(&a, ev[0], ev[1]) != hipSuccess || hipEventElapsedTime(&b, ev[1], ev[2]) != hipSuccess ||
+            hipEventElapsedTime(&c, ev[2], ev[3]) != hipSuccess)
+            st = DN_ERR_DEVICE;
+        if (ms_copy_in) *ms_copy_in = a;
+        if (ms_kernel) *ms_kernel = b;
+        if (ms_copy_out) *ms_copy_out = c;
+    }
+    for (auto &e : ev)
+        if (e) (void)hipEventDestroy(e);
+    return st;
+}
+
 dn_status dn_last_epoch_ms(dn_net *net, float *epoch_ms)
 {
     if (!net || !epoch_ms) return DN_ERR_INVALID_ARG;

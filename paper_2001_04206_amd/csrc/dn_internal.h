@@ -84,6 +84,9 @@ hipError_t launch_loss_reduce(const float *loss_rows, int B, float *loss_mean_ou
 hipError_t launch_update(float *p, float *v, const float *g, size_t count, float lr, float mu,
                          hipStream_t stream);
 hipError_t launch_copy(float *dst, const float *src, size_t count, hipStream_t stream);
+// One sample's backward outputs of one layer (gradients, lr-scaled weight and bias deltas).
+hipError_t launch_layer_backward(const float *deltas, const float *inputs, float lr, int cols_out, int cols_in,
+                                 float *G, float *dW, float *dB, hipStream_t stream);
 
 // ---- persistent batch-1 epoch kernel (dn_online.hip) ----------------------------
 constexpr int ON_MAX_L = 8;         // layers

@@ -179,6 +179,54 @@ hipError_t launch_loss_reduce(const float *loss_rows, int B, float *loss_mean_ou
     return hipGetLastError();
 }
 
+// The two-index (inputs x outputs) loop of the paper's offloaded backward method for one
+// sample: gradients[o][i] = deltas[o] * inputs[i], deltaWeights[o][i] = -lr * gradients[o][i],
+// deltaBiases[o] = -lr * deltas[o].  One thread per run of four (VEC) or one weight.
+template <int VEC>
+__global__ __launch_bounds__(256) void layer_backward_kernel(const float *__restrict__ deltas,
+                                                             const float *__restrict__ inputs, float lr,
+                                                             int cols_out, int cols_in, float *__restrict__ G,
+                                                             float *__restrict__ dW, float *__restrict__ dB)
+{
+    typedef float v4 __attribute__((ext_vector_type(4)));
+    const size_t total = (size_t)cols_out * (size_t)cols_in / VEC;
+    for (size_t q = (size_t)blockIdx.x * 256 + threadIdx.x; q < total; q += (size_t)gridDim.x * 256) {
+        const size_t e = q * VEC;
+        const int o = (int)(e / (size_t)cols_in);
+        const int i = (int)(e - (size_t)o * cols_in);
+        const float d = deltas[o];
+        if (VEC == 4) {
+            const v4 x = *reinterpret_cast<const v4 *>(inputs + i);
+            const v4 g = x * d;
+            *reinterpret_cast<v4 *>(G + e) = g;
+            *reinterpret_cast<v4 *>(dW + e) = g * (-lr);
+        } else {
+            const float g = d * inputs[i];
+            G[e] = g;
+            dW[e] = -lr * g;
+        }
+    }
+    for (size_t o = (size_t)blockIdx.x * 256 + threadIdx.x; o < (size_t)cols_out; o += (size_t)gridDim.x * 256)
+        dB[o] = -lr * deltas[o];
+}
+
+hipError_t launch_layer_backward(const float *deltas, const float *inputs, float lr, int cols_out, int cols_in,
+                                 float *G, float *dW, float *dB, hipStream_t stream)
+{
+    const bool vec = cols_in % 4 == 0;
+    size_t work = (size_t)cols_out * cols_in / (vec ? 4 : 1);
+    size_t g = (work + 255) / 256;
+    if (g > 256 * 32) g = 256 * 32;
+    if (g < 1) g = 1;
+    if (vec)
+        hipLaunchKernelGGL(layer_backward_kernel<4>, dim3((unsigned)g), dim3(256), 0, stream, deltas, inputs, lr,
+                           cols_out, cols_in, G, dW, dB);
+    else
+        hipLaunchKernelGGL(layer_backward_kernel<1>, dim3((unsigned)g), dim3(256), 0, stream, deltas, inputs, lr,
+                           cols_out, cols_in, G, dW, dB);
+    return hipGetLastError();
+}
+
 static unsigned grid_for(size_t count)
 {
     size_t g = (count + 255) / 256;

@@ -25,7 +25,7 @@ KERNEL_CLASS_NAMES = ["forward", "delta", "grad_update", "output", "online"]
 EXPORTS = [
     "dn_status_string", "dn_net_arena_bytes", "dn_net_create", "dn_net_destroy", "dn_set_params",
     "dn_get_params", "dn_get_grads", "dn_forward", "dn_backward", "dn_update", "dn_train_epoch",
-    "dn_train", "dn_evaluate",
+    "dn_train", "dn_evaluate", "dn_layer_backward_workspace_bytes", "dn_layer_backward_host",
     "dn_last_epoch_ms", "dn_kernel_time", "dn_set_option",
 ]
 
@@ -64,11 +64,16 @@ def lib():
         l.dn_train_epoch.argtypes = [vp, vp, vp, i64, i32, f32, f32, C.POINTER(f32)]
         l.dn_train.argtypes = [vp, vp, vp, i64, i32, f32, f32, f32, i32, C.POINTER(i32), C.POINTER(f32)]
         l.dn_evaluate.argtypes = [vp, vp, vp, i64, i32, C.POINTER(f32), C.POINTER(i64)]
+        l.dn_layer_backward_workspace_bytes.restype = C.c_size_t
+        l.dn_layer_backward_workspace_bytes.argtypes = [i32, i32]
+        l.dn_layer_backward_host.argtypes = [vp, vp, f32, i32, i32, vp, vp, vp, vp, C.c_size_t, vp,
+                                             C.POINTER(f32), C.POINTER(f32), C.POINTER(f32)]
         l.dn_last_epoch_ms.argtypes = [vp, C.POINTER(f32)]
         l.dn_kernel_time.argtypes = [vp, i32, C.POINTER(f32), C.POINTER(i64)]
         l.dn_set_option.argtypes = [vp, C.c_char_p, i64]
         for name in EXPORTS[2:]:
-            getattr(l, name).restype = C.c_int
+            if name != "dn_layer_backward_workspace_bytes":
+                getattr(l, name).restype = C.c_int
         _lib = l
     return _lib
 
@@ -97,6 +102,43 @@ def _dev_ptr(t, dtype, what: str):
     if not isinstance(t, torch.Tensor) or not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
         raise TypeError("%s must be a contiguous device tensor of dtype %s" % (what, dtype))
     return C.c_void_p(t.data_ptr())
+
+
+def dn_layer_backward_host(deltas, inputs, learning_rate: float, gradients, delta_weights, delta_biases,
+                           workspace=None):
+    """One layer's backward step for one sample with host buffers copied in and out around the
+    kernel.  All arrays are host tensors (torch CPU float32, pinned or not) or numpy float32
+    arrays; `workspace` is a device uint8 tensor (allocated here if None).  Returns the device
+    milliseconds of (copy in, kernel, copy out)."""
+    import torch
+
+    def host_ptr(a, n, what):
+        if isinstance(a, torch.Tensor):
+            if a.is_cuda or a.dtype != torch.float32 or not a.is_contiguous() or a.numel() != n:
+                raise TypeError("%s must be a contiguous host float32 tensor of %d elements" % (what, n))
+            return C.c_void_p(a.data_ptr())
+        if not isinstance(a, np.ndarray) or a.dtype != np.float32 or not a.flags["C_CONTIGUOUS"] or a.size != n:
+            raise TypeError("%s must be a contiguous float32 array of %d elements" % (what, n))
+        return a.ctypes.data_as(C.c_void_p)
+
+    cols_out = int(deltas.shape[0])
+    cols_in = int(inputs.shape[0])
+    need = int(lib().dn_layer_backward_workspace_bytes(cols_out, cols_in))
+    if need == 0:
+        raise DnError(DN_ERR_SHAPE, "dn_layer_backward_workspace_bytes")
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device="cuda:0")
+    stream = torch.cuda.current_stream(workspace.device)
+    t = [C.c_float(0.0), C.c_float(0.0), C.c_float(0.0)]
+    with torch.cuda.device(workspace.device):
+        st = lib().dn_layer_backward_host(
+            host_ptr(deltas, cols_out, "deltas"), host_ptr(inputs, cols_in, "inputs"), float(learning_rate),
+            cols_out, cols_in, host_ptr(gradients, cols_out * cols_in, "gradients"),
+            host_ptr(delta_weights, cols_out * cols_in, "delta_weights"),
+            host_ptr(delta_biases, cols_out, "delta_biases"), C.c_void_p(workspace.data_ptr()),
+            int(workspace.numel()), C.c_void_p(stream.cuda_stream), C.byref(t[0]), C.byref(t[1]), C.byref(t[2]))
+    _check(st, "dn_layer_backward_host")
+    return t[0].value, t[1].value, t[2].value
 
 
 class Net:

@@ -99,3 +99,23 @@ def test_binding_refuses_host_tensors(lib):
     import torch
     with pytest.raises(TypeError):
         dn._dev_ptr(torch.zeros(3), torch.float32, "X")
+
+
+def test_layer_backward_host_argument_checks(lib):
+    assert lib.dn_layer_backward_workspace_bytes(0, 5) == 0
+    assert lib.dn_layer_backward_workspace_bytes(5, -1) == 0
+    assert lib.dn_layer_backward_workspace_bytes(1 << 20, 1 << 20) == 0          # more than 2^31 weights
+    need = lib.dn_layer_backward_workspace_bytes(10, 340)
+    assert need >= 4 * (10 + 10 + 340 + 2 * 3400) and need % 256 == 0
+    buf = (C.c_float * 3400)()
+    vp = lambda a: C.cast(a, C.c_void_p)
+    args = lambda ws, nbytes, co=10, ci=340, lr=0.1, d=buf: (
+        vp(d) if d is not None else None, vp(buf), C.c_float(lr), co, ci, vp(buf), vp(buf), vp(buf), C.c_void_p(ws),
+        nbytes, None, None, None, None)
+    f = lib.dn_layer_backward_host
+    assert f(*args(0x10000, need, d=None)) == dn.DN_ERR_INVALID_ARG               # NULL operand
+    assert f(*args(0, need)) == dn.DN_ERR_INVALID_ARG                             # NULL workspace
+    assert f(*args(0x10000, need, lr=float("nan"))) == dn.DN_ERR_INVALID_ARG
+    assert f(*args(0x10000, need - 1)) == dn.DN_ERR_SHAPE                         # workspace too small
+    assert f(*args(0x10000, need, co=0)) == dn.DN_ERR_SHAPE
+    assert f(*args(0x10010, need)) == dn.DN_ERR_INVALID_ARG                       # misaligned workspace

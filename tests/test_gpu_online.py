@@ -160,3 +160,35 @@ def test_paper_shape_first_steps(dnlib):
     announce("paper shape 340-100000-10 B=1, 24 steps, persistent")
     w = synth.paper_shape(n_samples=24)
     run_pair(dnlib, w, 24, [0.0], PERSISTENT, tol=1e-4, biases=False)
+
+
+# ------------------------------- the paper's per-call execution model (copies around every call) ----
+
+@pytest.mark.parametrize("cols_out,cols_in,pinned", [(10, 1000, False), (340, 1001, True), (3, 4, False), (1, 1, True)])
+def test_layer_backward_host_matches_checker(dnlib, cols_out, cols_in, pinned):
+    """One sample's backward outputs of one layer.  Reference: the checker's batch-1 gradient of a
+    one-layer linear net whose output delta is the given vector (squared error with targets
+    chosen so that a - y = deltas), i.e. the pinned rank-1 outer product delta x input."""
+    announce("layer_backward_host %dx%d pinned=%s" % (cols_out, cols_in, pinned))
+    rng = np.random.default_rng(3)
+    deltas = rng.standard_normal(cols_out).astype(np.float32)
+    inputs = rng.standard_normal(cols_in).astype(np.float32)
+    lr = np.float32(0.05)
+    # checker: linear layer, squared error; with W = 0 and b = deltas + onehot(label) the output
+    # delta (a - y) f' is exactly `deltas`
+    o = Oracle("o32", [cols_in, cols_out], [LIN], MSE)
+    b = deltas.astype(np.float64).copy(); b[0] += 1.0
+    o.set_params([np.zeros((cols_out, cols_in))], [b])
+    o.forward(inputs[None, :]); o.backward(np.zeros(1, dtype=np.int32))
+    if not np.allclose(o.deltas()[0][0], deltas, rtol=0, atol=1e-6):       # fp32 rounding of b - 1
+        pytest.skip("checker delta does not reproduce the given vector exactly enough")
+    Gr, gr = o.get_grads()
+    mk = (lambda n: torch.empty(n, dtype=torch.float32).pin_memory()) if pinned else (lambda n: np.empty(n, dtype=np.float32))
+    G, dW, dB = mk(cols_out * cols_in), mk(cols_out * cols_in), mk(cols_out)
+    d_in = torch.from_numpy(o.deltas()[0][0].copy()) if pinned else o.deltas()[0][0].copy()
+    ms = dnlib.dn_layer_backward_host(d_in, torch.from_numpy(inputs) if pinned else inputs, float(lr), G, dW, dB)
+    assert all(t >= 0.0 for t in ms)
+    G, dW, dB = (np.asarray(t).reshape(-1) for t in (G, dW, dB))
+    assert_close(G.reshape(cols_out, cols_in), Gr[0], 1e-6, "gradients")
+    assert_close(dW.reshape(cols_out, cols_in), -np.float64(lr) * Gr[0].astype(np.float64), 1e-6, "deltaWeights")
+    assert_close(dB, -np.float64(lr) * gr[0].astype(np.float64), 1e-6, "deltaBiases")

@@ -662,14 +662,11 @@ using V6 = Tile<32, 32, 64, 1, 1, 8, 2>;        // few output tiles: lean on the
 using V7 = Tile<128, 128, 16, 2, 2, 1, 2, 16>;  // weight gradients: epilogue operands fetched over 16 k steps
 using V8 = Tile<128, 64, 16, 2, 2, 1, 2, 16, 2>;  // weight gradients, two workgroups per CU: one's epilogue under the other's k loop
 using V9 = Tile<64, 64, 16, 2, 2, 1, 2, 8, 4>;    // weight gradients, four workgroups per CU
-using V10 = Tile<64, 64, 32, 2, 2, 1, 2, 4, 4>;
-using V11 = Tile<64, 128, 16, 2, 2, 1, 2, 16, 2>;
-using V12 = Tile<64, 64, 16, 2, 2, 1, 1, 8, 4>;
 
 static const char *kVariantNames[] = {"128x128x16_r1",  "128x64x16_r2",   "64x64x64_k4_r2", "64x64x32_k4_r2",
                                       "32x64x32_k4_r2", "32x64x64_k8_r2", "32x32x64_k8_r2", "128x128x16_r2_pc16",
-                                      "128x64x16_r2_pc16_o2", "64x64x16_r2_pc8_o4", "64x64x32_r2_pc4_o4", "64x128x16_r2_pc16_o2", "64x64x16_r1_pc8_o4"};
-constexpr int kVariants = 13;
+                                      "128x64x16_r2_pc16_o2", "64x64x16_r2_pc8_o4"};
+constexpr int kVariants = 10;
 int gemm_variant_count() { return kVariants; }
 const char *gemm_variant_name(int v) { return (v >= 0 && v < kVariants) ? kVariantNames[v] : "?"; }
 
@@ -733,9 +730,6 @@ hipError_t launch_gemm(GemmKind kind, const GemmArgs &a, int variant, hipStream_
     case 7: return launch_kind<V7>(kind, a, stream);
     case 8: return launch_kind<V8>(kind, a, stream);
     case 9: return launch_kind<V9>(kind, a, stream);
-    case 10: return launch_kind<V10>(kind, a, stream);
-    case 11: return launch_kind<V11>(kind, a, stream);
-    case 12: return launch_kind<V12>(kind, a, stream);
     default: return hipErrorInvalidValue;
     }
 }

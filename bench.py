@@ -211,6 +211,8 @@ def main():
                 classes[cname] = {"ms": ms, "launches": n}
         # per-launch figures of the last dn_train_epoch call (one pass or the remainder)
         last_steps = steps % steps_per_pass or min(steps, steps_per_pass)
+        if "online" in classes:      # a persistent whole-epoch kernel ran: no matrix instructions, one launch
+            bound = "hbm"
         if bound == "mfma":
             dom = max((c for c in classes if c in flops), key=lambda c: classes[c]["ms"], default=None)
             if dom:
@@ -230,7 +232,7 @@ def main():
                 timed_steps = min(last_steps, classes["forward"]["launches"] // (len(w.widths) - 1))
             if total_ms > 0:
                 ach = step_bytes * timed_steps / (total_ms * 1e-3) / 1e9
-                roofline = {"bound": "hbm", "kernel": "online_epoch_kernel" if "online" in classes
+                roofline = {"bound": "hbm", "kernel": ("online_epoch_kernel" if B == 1 else "batch_epoch_kernel") if "online" in classes
                             else "all kernels of a step", "achieved": ach,
                             "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS, "traffic": None,
                             "avg_launch_us": total_ms * 1e3 / sum(c["launches"] for c in classes.values()),

@@ -26,6 +26,7 @@ struct Layout {
     size_t off_loss_rows = 0, off_hit_rows = 0, off_scalars = 0;
     size_t off_online = 0, online_bytes = 0;   // exchange buffers of the persistent batch-1 kernel
     size_t off_gemm_ws = 0, off_gemm_counters = 0;   // partial tiles / arrival counters of k-split contractions
+    size_t off_batch = 0, batch_bytes = 0;           // exchange buffers of the persistent minibatch kernel
     size_t total = 0;
 };
 
@@ -69,6 +70,8 @@ bool compute_layout(const int32_t *widths, int32_t n_widths, int32_t max_batch, 
     lo.off_online = o; o += align_up(lo.online_bytes);
     lo.off_gemm_ws = o; o += align_up(GEMM_WS_FLOATS * sizeof(float));
     lo.off_gemm_counters = o; o += align_up(GEMM_COUNTERS * sizeof(unsigned));
+    lo.batch_bytes = batch_exchange_bytes_bound(widths, L, max_batch);
+    lo.off_batch = o; o += align_up(lo.batch_bytes);
     lo.total = o;
     return true;
 }
@@ -100,6 +103,10 @@ struct dn_net {
     OnlineGeom geom{};
     bool online_ok = false;
     uint32_t online_seq = 0;   // last step number stamped into the exchange buffers
+    // persistent minibatch kernel (one- and two-layer nets)
+    bool batch_ok = false;
+    int batch_mode = 0;
+    uint32_t batch_seq = 0;
     int device_cus = 0;
     // timing
     hipEvent_t ev_epoch0 = nullptr, ev_epoch1 = nullptr;
@@ -123,6 +130,7 @@ struct dn_net {
     double *epoch_acc() const { return (double *)(arena + lo.off_scalars); }
     int *abort_flag() const { return (int *)(arena + lo.off_scalars + sizeof(double)); }
     unsigned long long *exchange() const { return (unsigned long long *)(arena + lo.off_online); }
+    unsigned long long *batch_exchange() const { return (unsigned long long *)(arena + lo.off_batch); }
     void split_k(GemmArgs &g) const
     {
         g.ws = split_k_on ? (float *)(arena + lo.off_gemm_ws) : nullptr;
@@ -274,6 +282,60 @@ dn_status run_online(dn_net *net, const float *X, const int32_t *labels, int64_t
     return DN_OK;
 }
 
+// Automatic choice between the persistent minibatch kernel and one launch per product: the
+// persistent kernel does its products on the vector units, so it only pays while a step is
+// launch bound, i.e. while the step's contraction work is small.
+bool batch_pays(const dn_net *net, int batch)
+{
+    double flop = 0.0;
+    for (int l = 1; l <= net->L; ++l) flop += 6.0 * batch * (double)net->n[l] * (double)net->n[l - 1];
+    return flop <= 4.0e8;
+}
+
+// A whole minibatch epoch of a one- or two-layer net in persistent-kernel launches.
+dn_status run_batch_persistent(dn_net *net, const float *X, const int32_t *labels, int64_t n_samples, int batch,
+                               float lr, float mu, bool timing)
+{
+    const int L = net->L;
+    BatchGeom g;
+    if (!batch_geometry(net->n.data(), L, net->max_batch, net->online_min_tile, mu != 0.f, g)) return DN_ERR_UNSUPPORTED;
+    BatchPlan p{};
+    p.L = L;
+    if (L == 2) { p.W1 = net->W(1); p.b1 = net->b(1); p.VW1 = net->VW(1); p.Vb1 = net->Vb(1); p.act1 = net->act[1]; }
+    p.W2 = net->W(L); p.b2 = net->b(L); p.VW2 = net->VW(L); p.Vb2 = net->Vb(L); p.actL = net->act[L];
+    p.n0 = net->n[0]; p.n_mid = net->n[L - 1]; p.nL = net->n[L];
+    p.per = g.per; p.P = g.P; p.spw = g.spw; p.max_batch = net->max_batch;
+    p.z_x = net->batch_exchange() + g.off_z;
+    p.d_x = net->batch_exchange() + g.off_d;
+    p.abort_flag = net->abort_flag();
+    p.loss_acc = net->epoch_acc();
+    p.batch = batch;
+    p.lr = lr; p.mu = mu; p.loss = net->loss; p.with_v = (mu != 0.f) ? 1 : 0;
+    p.lds_w1 = g.lds_w1; p.lds_v1 = g.lds_v1; p.lds_b1 = g.lds_b1; p.lds_w2 = g.lds_w2; p.lds_v2 = g.lds_v2;
+    p.lds_bL = g.lds_bL; p.lds_a1 = g.lds_a1; p.lds_d1 = g.lds_d1; p.lds_d2 = g.lds_d2; p.lds_zs = g.lds_zs;
+    p.lds_tmp = g.lds_tmp;
+    const int64_t chunk_steps = (int64_t)1 << 30;
+    const int64_t total_steps = (n_samples + batch - 1) / batch;
+    for (int64_t t0 = 0; t0 < total_steps; t0 += chunk_steps) {
+        const int64_t nt = (total_steps - t0) < chunk_steps ? (total_steps - t0) : chunk_steps;
+        if ((uint64_t)net->batch_seq + (uint64_t)nt + 2 > 0xffffffffull) {   // step numbers would wrap
+            DN_HIP(hipMemsetAsync(net->batch_exchange(), 0, net->lo.batch_bytes, net->stream));
+            net->batch_seq = 0;
+        }
+        const int64_t s0 = t0 * batch;
+        const int64_t n = ((t0 + nt) * batch < n_samples ? (t0 + nt) * batch : n_samples) - s0;
+        p.X = X + (size_t)s0 * net->n[0];
+        p.labels = labels + s0;
+        p.n_samples = n;
+        p.keep_v = (t0 + nt >= total_steps) ? 1 : 0;
+        p.seq0 = net->batch_seq;
+        ScopedTimer st(net, DN_K_ONLINE, timing);
+        DN_HIP(launch_batch_epoch(g, p, net->stream));
+        net->batch_seq += (uint32_t)nt;
+    }
+    return DN_OK;
+}
+
 void collect_times(dn_net *net)
 {
     for (int c = 0; c < DN_K_CLASSES; ++c) {
@@ -351,12 +413,23 @@ dn_status dn_net_create(const int32_t *widths, int32_t n_widths, const dn_act *a
     net->max_batch = max_batch;
     net->arena = (char *)arena_dev;
     net->stream = (hipStream_t)hip_stream;
-    // persistent batch-1 kernel: slices per workgroup, if the net fits it and the device has the units
-    if (lo.online_bytes > 0 && online_geometry(net->n.data(), L, net->online_min_tile, false, net->geom)) {
+    // persistent kernels: slices per workgroup, if the net fits them and the device has the units
+    {
         int dev = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&net->device_cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess)
-            net->online_ok = net->geom.grid <= net->device_cus && online_prepare() == hipSuccess;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&net->device_cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+            net->device_cus = 0;
+        (void)hipGetLastError();
+    }
+    if (net->device_cus > 0 && lo.online_bytes > 0 &&
+        online_geometry(net->n.data(), L, net->online_min_tile, false, net->geom)) {
+        net->online_ok = net->geom.grid <= net->device_cus && online_prepare() == hipSuccess;
+        (void)hipGetLastError();
+    }
+    if (lo.batch_bytes > 0 && net->device_cus > 0) {
+        BatchGeom bg;
+        net->batch_ok = batch_geometry(net->n.data(), L, max_batch, net->online_min_tile, true, bg) &&
+                        bg.grid <= net->device_cus && batch_prepare() == hipSuccess;
         (void)hipGetLastError();
     }
     // parameters, velocities and gradients start at zero; exchange words start unstamped
@@ -365,6 +438,8 @@ dn_status dn_net_create(const int32_t *widths, int32_t n_widths, const dn_act *a
         (lo.online_bytes > 0 &&
          hipMemsetAsync(net->arena + lo.off_online, 0, lo.online_bytes, net->stream) != hipSuccess) ||
         hipMemsetAsync(net->arena + lo.off_gemm_counters, 0, GEMM_COUNTERS * sizeof(unsigned), net->stream) != hipSuccess ||
+        (lo.batch_bytes > 0 &&
+         hipMemsetAsync(net->arena + lo.off_batch, 0, lo.batch_bytes, net->stream) != hipSuccess) ||
         hipEventCreate(&net->ev_epoch0) != hipSuccess || hipEventCreate(&net->ev_epoch1) != hipSuccess ||
         hipStreamSynchronize(net->stream) != hipSuccess) {
         if (net->ev_epoch0) (void)hipEventDestroy(net->ev_epoch0);
@@ -484,13 +559,20 @@ dn_status dn_train_epoch(dn_net *net, const float *X_dev, const int32_t *labels_
     const bool timing = net->time_kernels != 0;
     net->timed = 0;
     const int L = net->L;
-    const bool persistent = batch == 1 && net->online_mode != 1 && net->online_ok;
+    bool persistent = batch == 1 && net->online_mode != 1 && net->online_ok;
     if (batch == 1 && net->online_mode == 2 && !net->online_ok) return DN_ERR_UNSUPPORTED;
+    const bool pbatch = batch > 1 && net->batch_mode != 1 && net->batch_ok &&
+                        (net->batch_mode == 2 || batch_pays(net, batch));
+    if (batch > 1 && net->batch_mode == 2 && !net->batch_ok) return DN_ERR_UNSUPPORTED;
     DN_HIP(hipMemsetAsync(net->epoch_acc(), 0, sizeof(double) + sizeof(int), net->stream));
     DN_HIP(hipEventRecord(net->ev_epoch0, net->stream));
     if (persistent) {
         dn_status st = run_online(net, X_dev, labels_dev, n_samples, lr, momentum, timing);
         if (st != DN_OK) return st;
+    } else if (pbatch) {
+        dn_status st = run_batch_persistent(net, X_dev, labels_dev, n_samples, batch, lr, momentum, timing);
+        if (st != DN_OK) return st;
+        persistent = true;
     }
     for (int64_t s0 = persistent ? n_samples : 0; s0 < n_samples; s0 += batch) {
         const int B = (int)((n_samples - s0) < batch ? (n_samples - s0) : batch);
@@ -660,6 +742,9 @@ dn_status dn_set_option(dn_net *net, const char *name, int64_t value)
         net->geom = g;
         net->online_min_tile = (int)value;
         net->online_ok = true;
+    } else if (!strcmp(name, "batch_mode")) {
+        if (value < 0 || value > 2) return DN_ERR_INVALID_ARG;
+        net->batch_mode = (int)value;
     } else if (!strcmp(name, "split_k")) {
         if (value != 0 && value != 1) return DN_ERR_INVALID_ARG;
         net->split_k_on = (int)value;

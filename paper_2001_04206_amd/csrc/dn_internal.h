@@ -141,6 +141,47 @@ struct OnlinePlan {
     int lds_out, lds_kpart, lds_tmp;
 };
 
+// ---- persistent minibatch epoch kernel for nets of one or two layers (dn_online.hip) ----
+// Same ownership as the per-sample kernel (rows of W_1, matching columns of the last layer),
+// B samples per step.  With at most two layers the only data that crosses workgroups are the
+// partial net inputs of the output layer and its deltas.
+constexpr int PB_MAX_BATCH = 256;
+constexpr int PB_MAX_N0 = 2048;       // a sample's features are held in registers: 8 float4 per lane
+constexpr int PB_MAX_ROWS = 16;       // rows of W_1 per workgroup
+constexpr int PB_MAX_OUT_FLOATS = 8192;   // batch x (n_L + 1) in LDS
+
+struct BatchGeom {
+    bool ok;
+    int L, grid, per, P, spw;   // per: hidden units (L = 2) or input features (L = 1) per workgroup; spw: samples per workgroup in the output stage
+    size_t off_z, off_d, words;
+    int lds_w1, lds_v1, lds_b1, lds_w2, lds_v2, lds_bL, lds_a1, lds_d1, lds_d2, lds_zs, lds_tmp, lds_floats;
+};
+
+struct BatchPlan {
+    int L;
+    float *W1, *b1, *VW1, *Vb1;     // L = 2 only
+    float *W2, *b2, *VW2, *Vb2;     // the last layer [nL][n_mid]
+    int n0, n_mid, nL, act1, actL;  // n_mid: width feeding the last layer (n_1, or n_0 when L = 1)
+    int per, P, spw, max_batch;
+    unsigned long long *z_x;        // [2][P][max_batch * nL]     partial net inputs of the output layer
+    unsigned long long *d_x;        // [2][max_batch * (nL + 1)]  output deltas and per-sample losses
+    int *abort_flag;
+    double *loss_acc;
+    const float *X;
+    const int32_t *labels;
+    int64_t n_samples;
+    int batch;
+    float lr, mu;
+    int loss, keep_v, with_v;
+    uint32_t seq0;
+    int lds_w1, lds_v1, lds_b1, lds_w2, lds_v2, lds_bL, lds_a1, lds_d1, lds_d2, lds_zs, lds_tmp;
+};
+
+bool batch_geometry(const int32_t *n, int L, int max_batch, int min_tile, bool want_v, BatchGeom &g);
+size_t batch_exchange_bytes_bound(const int32_t *n, int L, int max_batch);
+hipError_t batch_prepare();
+hipError_t launch_batch_epoch(const BatchGeom &g, const BatchPlan &plan, hipStream_t stream);
+
 // Slices and buffer offsets for widths n[0..L]; false if the net does not fit the kernel
 // (too many layers, output layer too wide, LDS).  want_v: velocity slices are read every step
 // (momentum), so they must fit in LDS next to the weights for the slices to be resident.

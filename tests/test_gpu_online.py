@@ -192,3 +192,83 @@ def test_layer_backward_host_matches_checker(dnlib, cols_out, cols_in, pinned):
     assert_close(G.reshape(cols_out, cols_in), Gr[0], 1e-6, "gradients")
     assert_close(dW.reshape(cols_out, cols_in), -np.float64(lr) * Gr[0].astype(np.float64), 1e-6, "deltaWeights")
     assert_close(dB, -np.float64(lr) * gr[0].astype(np.float64), 1e-6, "deltaBiases")
+
+
+# ------------------------------ minibatches of one- and two-layer nets: persistent kernel ----
+
+BATCH_SHAPES = [
+    # widths, acts, loss, batch, samples
+    ([4, 16, 3], [SIG, SIG], MSE, 7, 30),                  # short last batch (30 = 4 x 7 + 2)
+    ([784, 128, 10], [RELU, SOFTMAX], CE, 128, 300),       # the 784-128-10 minibatch workload, short last batch
+    ([36, 70, 5], [TANH, LIN], MSE, 33, 99),
+    ([300, 10], [SOFTMAX], CE, 64, 200),                   # one layer: input features split over workgroups
+    ([12, 1], [SIG], MSE, 5, 23),
+    ([2048, 40, 128], [TANH, SOFTMAX], CE, 16, 48),        # widest input and output the kernel takes
+    ([8, 1000, 7], [SIG, SOFTMAX], CE, 256, 512),          # many hidden units, largest batch
+]
+
+
+@pytest.mark.parametrize("widths,acts,loss,B,n", BATCH_SHAPES)
+@pytest.mark.parametrize("min_tile", [None, 64])
+def test_persistent_minibatch_epochs_match_checker(dnlib, widths, acts, loss, B, n, min_tile):
+    announce("persistent minibatch widths=%s B=%d min_tile=%s" % (widths, B, min_tile))
+    w = synth.make("pbatch", widths, acts, loss, n_samples=n, features="normal", init="xavier_uniform",
+                   batch=B, lr=0.02, momentum=0.0, seed=6)
+    rng = np.random.default_rng(13)
+    w.b = [rng.standard_normal(k).astype(np.float32) * 0.1 for k in w.widths[1:]]
+    net = dnlib.Net(w.widths, w.acts, w.loss, B)
+    net.set_all(w.W, w.b)
+    net.dn_set_option("batch_mode", 2)
+    if min_tile is not None:
+        net.dn_set_option("online_min_tile", min_tile)
+    o = Oracle("o32", w.widths, w.acts, w.loss)
+    o.set_params(w.W, w.b)
+    X = torch.from_numpy(w.X).to("cuda:0")
+    y = torch.from_numpy(w.labels).to("cuda:0")
+    for mu in (0.0, 0.7, 0.7):       # plain pass (leaves the last step's velocity), then momentum on top of it
+        got = net.dn_train_epoch(X, y, B, w.lr, mu)
+        ref, _ = o.train_epoch(w.X, w.labels, B, w.lr, mu)
+        assert abs(got - ref) <= 1e-4 * max(abs(ref), 1e-6), (got, ref)
+    W, b = net.get_all()
+    Wr, br = o.get_params()
+    for l in range(net.L):
+        assert_close(W[l], Wr[l], 1e-4, "W_%d" % (l + 1))
+        assert_close(b[l], br[l], 1e-4, "b_%d" % (l + 1))
+    net.close()
+
+
+def test_persistent_minibatch_refused_for_three_layers(dnlib):
+    announce("persistent minibatch refused for a three-layer net")
+    w = synth.make("pbatch", [8, 12, 9, 4], [TANH, TANH, SOFTMAX], CE, n_samples=8, features="normal",
+                   init="xavier_uniform", batch=4, lr=0.05, momentum=0.0, seed=2)
+    net = dnlib.Net(w.widths, w.acts, w.loss, 4)
+    net.set_all(w.W, w.b)
+    net.dn_set_option("batch_mode", 2)
+    X = torch.from_numpy(w.X).to("cuda:0")
+    y = torch.from_numpy(w.labels).to("cuda:0")
+    with pytest.raises(dnlib.DnError) as e:
+        net.dn_train_epoch(X, y, 4, 0.05, 0.0)
+    assert e.value.status == dnlib.DN_ERR_UNSUPPORTED
+    net.dn_set_option("batch_mode", 0)
+    assert np.isfinite(net.dn_train_epoch(X, y, 4, 0.05, 0.0))
+    net.close()
+
+
+def test_persistent_minibatch_is_bitwise_reproducible_and_close_to_per_launch(dnlib):
+    announce("persistent minibatch determinism, and agreement with one launch per product")
+    w = synth.digits_like_minibatch(n_samples=1000)
+    outs = []
+    for mode in (2, 2, 1):
+        net = dnlib.Net(w.widths, w.acts, w.loss, w.batch)
+        net.set_all(w.W, w.b)
+        net.dn_set_option("batch_mode", mode)
+        X = torch.from_numpy(w.X).to("cuda:0")
+        y = torch.from_numpy(w.labels).to("cuda:0")
+        loss = net.dn_train_epoch(X, y, w.batch, w.lr, w.momentum)
+        outs.append((loss, net.get_all()))
+        net.close()
+    assert outs[0][0] == outs[1][0]
+    for a, b in zip(outs[0][1][0] + outs[0][1][1], outs[1][1][0] + outs[1][1][1]):
+        assert np.array_equal(a, b)
+    for a, b in zip(outs[0][1][0] + outs[0][1][1], outs[2][1][0] + outs[2][1][1]):
+        assert_close(a, b, 1e-4, "persistent vs per-launch")

@@ -625,7 +625,7 @@ static hipError_t launch_vec(const GemmArgs &a, hipStream_t stream)
     b.sk = 1;
     if (EPI <= EPI_DELTA && a.ws && a.counters && nt < 256 && nt <= a.n_counters) {
         const int nk = (a.K + T::KT - 1) / T::KT;
-        int sk = (int)(512 / nt);
+        int sk = (int)(256 / nt);
         if (sk > 16) sk = 16;
         if (sk > nk / 2) sk = nk / 2;          // at least two k steps each
         while (sk > 1 && (size_t)nt * sk * T::BM * T::BN > a.ws_floats) --sk;

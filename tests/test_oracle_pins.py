@@ -468,3 +468,43 @@ def test_training_until_max_error_stops_at_the_first_epoch_below_it():
     o.train(w.X[:360], w.labels[:360], w.batch, w.lr, w.momentum, -1.0, 12)
     _, hits = o.evaluate(w.X[360:], w.labels[360:])
     assert hits > 40 * 0.5
+
+
+# ----------------------------------------------- what the paper itself prints ----
+
+def _paper_numbers():
+    import os
+    kv = {}
+    for line in open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "paper_benchmark.txt")):
+        if not line.startswith("#") and "=" in line:
+            k, v = line.split("=", 1)
+            kv[k.strip()] = v.strip()
+    return kv
+
+
+def test_paper_shape_workload_is_the_papers_network():
+    """The synthetic stand-in for the paper's benchmark has the shape, activations and loss the paper
+    states, and the per-sample weight gradients of its two layers have the sizes of the two offloaded
+    methods' outputs (outputs x inputs: 10 x 100000 and 100000 x 340)."""
+    from paper_2001_04206_amd import synth
+    kv = _paper_numbers()
+    w = synth.paper_shape(n_samples=2)
+    assert w.widths == [int(kv["input_features"]), int(kv["fully_connected_neurons"]), int(kv["output_categories"])]
+    assert w.acts == [TANH, SOFTMAX] and kv["fully_connected_activation"] == "tanh" and kv["output_activation"] == "softmax"
+    assert w.loss == CE and kv["loss"] == "cross_entropy" and w.batch == 1
+    o = Oracle("o32", w.widths, w.acts, w.loss)
+    o.set_params(w.W, w.b)
+    o.forward(w.X[:1]); o.backward(w.labels[:1])
+    G, _ = o.get_grads()
+    assert G[1].shape == (10, 100000) and G[0].shape == (100000, 340)
+    # rank-1: the softmax layer's gradient is its delta times the hidden activations
+    d = o.deltas()
+    np.testing.assert_allclose(G[1], np.outer(d[1][0], o.forward(w.X[:1])[0][0]), rtol=1e-6, atol=1e-12)
+
+
+def test_paper_timings_are_consistent_with_its_stated_speedups():
+    kv = _paper_numbers()
+    assert round(float(kv["softmax_backward_original_ms"]) / float(kv["softmax_backward_offloaded_ms"])) == int(kv["softmax_backward_speedup"])
+    ratio = float(kv["fully_connected_backward_original_ms"]) / float(kv["fully_connected_backward_offloaded_ms"])
+    assert abs(ratio - float(kv["fully_connected_backward_speedup"])) < 0.01
+    assert abs(float(kv["large_dataset_bytes"]) / float(kv["small_dataset_bytes"]) - float(kv["large_dataset_factor"])) < 0.5

@@ -257,12 +257,13 @@ dn_status dn_kernel_time(dn_net *net, int32_t kernel_class, float *ms_total, int
  *                    2: persistent whole-epoch kernel for batch 1 (dn_train_epoch
  *                    returns DN_ERR_UNSUPPORTED if the net does not fit it: more than
  *                    8 layers, an output layer wider than 128, or too wide for LDS)
- *   "batch_mode"     minibatches of nets with one or two layers: 0: choose automatically (the
- *                    persistent whole-epoch minibatch kernel while a step is launch bound);
- *                    1: always one launch per product; 2: always the persistent kernel
- *                    (DN_ERR_UNSUPPORTED from dn_train_epoch if the net does not fit it: more
- *                    than two layers, max_batch > 256, n_0 > 2048 or not a multiple of 4,
- *                    output wider than 128, LDS)
+ *   "batch_mode"     minibatches: 0: choose automatically (a persistent whole-epoch minibatch
+ *                    kernel while a step is launch bound); 1: always one launch per product;
+ *                    2: always a persistent kernel (DN_ERR_UNSUPPORTED from dn_train_epoch if
+ *                    the net fits none.  One or two layers: max_batch <= 256, n_0 <= 2048 and a
+ *                    multiple of 4, output width <= 128, LDS.  Three to eight layers: momentum 0,
+ *                    max_batch <= 64, every width but the last a multiple of 4, output width
+ *                    <= 128, LDS)
  *   "online_min_tile"  weights of one layer a workgroup of the persistent kernel should
  *                    own before the layer is spread over more workgroups (default 4096)
  *   "online_resident"  1 (default): the persistent kernel keeps its weight slices in LDS

@@ -27,6 +27,7 @@ struct Layout {
     size_t off_online = 0, online_bytes = 0;   // exchange buffers of the persistent batch-1 kernel
     size_t off_gemm_ws = 0, off_gemm_counters = 0;   // partial tiles / arrival counters of k-split contractions
     size_t off_batch = 0, batch_bytes = 0;           // exchange buffers of the persistent minibatch kernel
+    size_t off_deep = 0, deep_bytes = 0;             // exchange buffers of the persistent minibatch kernel for deeper nets
     size_t total = 0;
 };
 
@@ -72,6 +73,8 @@ bool compute_layout(const int32_t *widths, int32_t n_widths, int32_t max_batch, 
     lo.off_gemm_counters = o; o += align_up(GEMM_COUNTERS * sizeof(unsigned));
     lo.batch_bytes = batch_exchange_bytes_bound(widths, L, max_batch);
     lo.off_batch = o; o += align_up(lo.batch_bytes);
+    lo.deep_bytes = deep_exchange_bytes_bound(widths, L, max_batch);
+    lo.off_deep = o; o += align_up(lo.deep_bytes);
     lo.total = o;
     return true;
 }
@@ -104,9 +107,9 @@ struct dn_net {
     bool online_ok = false;
     uint32_t online_seq = 0;   // last step number stamped into the exchange buffers
     // persistent minibatch kernel (one- and two-layer nets)
-    bool batch_ok = false;
+    bool batch_ok = false, deep_ok = false;
     int batch_mode = 0;
-    uint32_t batch_seq = 0;
+    uint32_t batch_seq = 0, deep_seq = 0;
     int device_cus = 0;
     // timing
     hipEvent_t ev_epoch0 = nullptr, ev_epoch1 = nullptr;
@@ -131,6 +134,7 @@ struct dn_net {
     int *abort_flag() const { return (int *)(arena + lo.off_scalars + sizeof(double)); }
     unsigned long long *exchange() const { return (unsigned long long *)(arena + lo.off_online); }
     unsigned long long *batch_exchange() const { return (unsigned long long *)(arena + lo.off_batch); }
+    char *deep_exchange() const { return arena + lo.off_deep; }
     void split_k(GemmArgs &g) const
     {
         g.ws = split_k_on ? (float *)(arena + lo.off_gemm_ws) : nullptr;
@@ -292,6 +296,13 @@ bool batch_pays(const dn_net *net, int batch)
     return flop <= 4.0e8;
 }
 
+// The same question for the deeper-net kernel, which reads whole activation / delta matrices of
+// the batch past the L2 in every phase: it pays while those matrices are small.
+bool deep_pays(const dn_net *net, int batch)
+{
+    return batch <= 32;
+}
+
 // A whole minibatch epoch of a one- or two-layer net in persistent-kernel launches.
 dn_status run_batch_persistent(dn_net *net, const float *X, const int32_t *labels, int64_t n_samples, int batch,
                                float lr, float mu, bool timing)
@@ -332,6 +343,57 @@ dn_status run_batch_persistent(dn_net *net, const float *X, const int32_t *label
         ScopedTimer st(net, DN_K_ONLINE, timing);
         DN_HIP(launch_batch_epoch(g, p, net->stream));
         net->batch_seq += (uint32_t)nt;
+    }
+    return DN_OK;
+}
+
+// A whole plain-gradient-descent minibatch epoch of a net of three or more layers in
+// persistent-kernel launches.
+dn_status run_deep_persistent(dn_net *net, const float *X, const int32_t *labels, int64_t n_samples, int batch,
+                              float lr, bool timing)
+{
+    const int L = net->L;
+    DeepGeom g;
+    if (!deep_geometry(net->n.data(), L, net->max_batch, net->online_min_tile, g)) return DN_ERR_UNSUPPORTED;
+    DeepPlan p{};
+    p.L = L;
+    char *ex = net->deep_exchange();
+    for (int l = 1; l <= L; ++l) {
+        DeepLayer &y = p.layer[l];
+        y.W = net->W(l); y.b = net->b(l); y.VW = net->VW(l); y.Vb = net->Vb(l);
+        y.n_in = net->n[l - 1]; y.n_out = net->n[l]; y.act = net->act[l];
+        y.per = g.per[l]; y.P = g.P[l];
+        p.ea[l] = (float *)(ex + g.off_ea[l]); p.ed[l] = (float *)(ex + g.off_ed[l]);
+        p.fa[l] = (unsigned long long *)(ex + g.off_fa[l]); p.fd[l] = (unsigned long long *)(ex + g.off_fd[l]);
+        p.lds_r[l] = g.lds_r[l]; p.lds_ct[l] = g.lds_ct[l]; p.lds_b[l] = g.lds_b[l]; p.lds_a[l] = g.lds_a[l];
+        p.lds_dl[l] = g.lds_dl[l];
+    }
+    p.grid = g.grid; p.spw = g.spw; p.max_batch = net->max_batch; p.halves = g.halves;
+    p.z_x = (unsigned long long *)(ex + g.off_z);
+    p.d_x = (unsigned long long *)(ex + g.off_d);
+    p.abort_flag = net->abort_flag();
+    p.loss_acc = net->epoch_acc();
+    p.batch = batch;
+    p.lr = lr; p.loss = net->loss;
+    p.lds_w2 = g.lds_w2; p.lds_bL = g.lds_bL; p.lds_d2 = g.lds_d2; p.lds_zs = g.lds_zs; p.lds_tmp = g.lds_tmp;
+    const int64_t chunk_steps = (int64_t)1 << 30;
+    const int64_t total_steps = (n_samples + batch - 1) / batch;
+    for (int64_t t0 = 0; t0 < total_steps; t0 += chunk_steps) {
+        const int64_t nt = (total_steps - t0) < chunk_steps ? (total_steps - t0) : chunk_steps;
+        if ((uint64_t)net->deep_seq + (uint64_t)nt + 2 > 0xffffffffull) {
+            DN_HIP(hipMemsetAsync(net->deep_exchange(), 0, net->lo.deep_bytes, net->stream));
+            net->deep_seq = 0;
+        }
+        const int64_t s0 = t0 * batch;
+        const int64_t n = ((t0 + nt) * batch < n_samples ? (t0 + nt) * batch : n_samples) - s0;
+        p.X = X + (size_t)s0 * net->n[0];
+        p.labels = labels + s0;
+        p.n_samples = n;
+        p.keep_v = (t0 + nt >= total_steps) ? 1 : 0;
+        p.seq0 = net->deep_seq;
+        ScopedTimer st(net, DN_K_ONLINE, timing);
+        DN_HIP(launch_deep_epoch(g, p, net->stream));
+        net->deep_seq += (uint32_t)nt;
     }
     return DN_OK;
 }
@@ -432,6 +494,12 @@ dn_status dn_net_create(const int32_t *widths, int32_t n_widths, const dn_act *a
                         bg.grid <= net->device_cus && batch_prepare() == hipSuccess;
         (void)hipGetLastError();
     }
+    if (lo.deep_bytes > 0 && net->device_cus > 0) {
+        DeepGeom dg;
+        net->deep_ok = deep_geometry(net->n.data(), L, max_batch, net->online_min_tile, dg) &&
+                       dg.grid <= net->device_cus && deep_prepare() == hipSuccess;
+        (void)hipGetLastError();
+    }
     // parameters, velocities and gradients start at zero; exchange words start unstamped
     if (hipMemsetAsync(net->arena, 0, 3 * lo.region, net->stream) != hipSuccess ||
         hipMemsetAsync(net->arena + lo.off_scalars, 0, kAlign, net->stream) != hipSuccess ||
@@ -440,6 +508,8 @@ dn_status dn_net_create(const int32_t *widths, int32_t n_widths, const dn_act *a
         hipMemsetAsync(net->arena + lo.off_gemm_counters, 0, GEMM_COUNTERS * sizeof(unsigned), net->stream) != hipSuccess ||
         (lo.batch_bytes > 0 &&
          hipMemsetAsync(net->arena + lo.off_batch, 0, lo.batch_bytes, net->stream) != hipSuccess) ||
+        (lo.deep_bytes > 0 &&
+         hipMemsetAsync(net->arena + lo.off_deep, 0, lo.deep_bytes, net->stream) != hipSuccess) ||
         hipEventCreate(&net->ev_epoch0) != hipSuccess || hipEventCreate(&net->ev_epoch1) != hipSuccess ||
         hipStreamSynchronize(net->stream) != hipSuccess) {
         if (net->ev_epoch0) (void)hipEventDestroy(net->ev_epoch0);
@@ -563,7 +633,9 @@ dn_status dn_train_epoch(dn_net *net, const float *X_dev, const int32_t *labels_
     if (batch == 1 && net->online_mode == 2 && !net->online_ok) return DN_ERR_UNSUPPORTED;
     const bool pbatch = batch > 1 && net->batch_mode != 1 && net->batch_ok &&
                         (net->batch_mode == 2 || batch_pays(net, batch));
-    if (batch > 1 && net->batch_mode == 2 && !net->batch_ok) return DN_ERR_UNSUPPORTED;
+    const bool pdeep = batch > 1 && net->batch_mode != 1 && net->deep_ok && momentum == 0.f &&
+                       (net->batch_mode == 2 || deep_pays(net, batch));
+    if (batch > 1 && net->batch_mode == 2 && !pbatch && !pdeep) return DN_ERR_UNSUPPORTED;
     DN_HIP(hipMemsetAsync(net->epoch_acc(), 0, sizeof(double) + sizeof(int), net->stream));
     DN_HIP(hipEventRecord(net->ev_epoch0, net->stream));
     if (persistent) {
@@ -571,6 +643,10 @@ dn_status dn_train_epoch(dn_net *net, const float *X_dev, const int32_t *labels_
         if (st != DN_OK) return st;
     } else if (pbatch) {
         dn_status st = run_batch_persistent(net, X_dev, labels_dev, n_samples, batch, lr, momentum, timing);
+        if (st != DN_OK) return st;
+        persistent = true;
+    } else if (pdeep) {
+        dn_status st = run_deep_persistent(net, X_dev, labels_dev, n_samples, batch, lr, timing);
         if (st != DN_OK) return st;
         persistent = true;
     }

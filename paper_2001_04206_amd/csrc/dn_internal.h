@@ -182,6 +182,53 @@ size_t batch_exchange_bytes_bound(const int32_t *n, int L, int max_batch);
 hipError_t batch_prepare();
 hipError_t launch_batch_epoch(const BatchGeom &g, const BatchPlan &plan, hipStream_t stream);
 
+// ---- persistent minibatch epoch kernel for deeper nets, plain gradient descent (dn_online.hip) ----
+// Every hidden layer is owned by rows as before; to keep the backward pass free of partial sums
+// over workgroups, a workgroup also keeps, for each layer l >= 2, a second copy of the weights that
+// leave its own units of layer l-1 (the columns of W_l, stored transposed) and updates both copies
+// with the same arithmetic.  What crosses workgroups is then only whole activation / delta matrices
+// of the batch, written once and read by everyone.
+constexpr int PD_MAX_BATCH = 64;
+
+struct DeepGeom {
+    bool ok;
+    int L, grid, spw, halves;
+    int per[ON_MAX_L + 1], P[ON_MAX_L + 1];
+    size_t off_z, off_d, off_ea[ON_MAX_L + 1], off_ed[ON_MAX_L + 1], off_fa[ON_MAX_L + 1], off_fd[ON_MAX_L + 1], bytes;
+    int lds_r[ON_MAX_L + 1], lds_ct[ON_MAX_L + 1], lds_b[ON_MAX_L + 1], lds_a[ON_MAX_L + 1], lds_dl[ON_MAX_L + 1];
+    int lds_w2, lds_bL, lds_d2, lds_zs, lds_tmp, lds_floats;
+};
+
+struct DeepLayer {
+    float *W, *b, *VW, *Vb;
+    int n_in, n_out, act, per, P;
+};
+
+struct DeepPlan {
+    int L;
+    DeepLayer layer[ON_MAX_L + 1];
+    int grid, spw, max_batch, halves;
+    unsigned long long *z_x, *d_x;                 // as in the two-layer kernel, over `grid` producers
+    float *ea[ON_MAX_L + 1], *ed[ON_MAX_L + 1];    // [2][max_batch][n_l]: activations (l = 1..L-2), deltas (l = 2..L-1)
+    unsigned long long *fa[ON_MAX_L + 1], *fd[ON_MAX_L + 1];   // [2][grid] "my slice is written" stamps
+    int *abort_flag;
+    double *loss_acc;
+    const float *X;
+    const int32_t *labels;
+    int64_t n_samples;
+    int batch;
+    float lr;
+    int loss, keep_v;
+    uint32_t seq0;
+    int lds_r[ON_MAX_L + 1], lds_ct[ON_MAX_L + 1], lds_b[ON_MAX_L + 1], lds_a[ON_MAX_L + 1], lds_dl[ON_MAX_L + 1];
+    int lds_w2, lds_bL, lds_d2, lds_zs, lds_tmp;
+};
+
+bool deep_geometry(const int32_t *n, int L, int max_batch, int min_tile, DeepGeom &g);
+size_t deep_exchange_bytes_bound(const int32_t *n, int L, int max_batch);
+hipError_t deep_prepare();
+hipError_t launch_deep_epoch(const DeepGeom &g, const DeepPlan &plan, hipStream_t stream);
+
 // Slices and buffer offsets for widths n[0..L]; false if the net does not fit the kernel
 // (too many layers, output layer too wide, LDS).  want_v: velocity slices are read every step
 // (momentum), so they must fit in LDS next to the weights for the slices to be resident.

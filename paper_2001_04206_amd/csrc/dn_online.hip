@@ -1231,6 +1231,443 @@ __global__ __launch_bounds__(ON_THREADS) void batch_epoch_kernel(BatchPlan p)
     }
 }
 
+
+// ---- minibatch epochs of deeper nets (plain gradient descent) as one persistent kernel ----
+
+// How a matrix in device memory is read: plainly (the caller's X, read-only), or with relaxed
+// device-scope atomic loads that bypass the per-XCD L2 (matrices other workgroups wrote moments
+// ago).  (Invalidating the caches once per exchange and then loading plainly was measured: the
+// invalidation alone costs about 10 us per exchange, more than the bypassing loads.)
+struct PlainLoad {
+    static __device__ __forceinline__ v4f ld(const float *p) { return *(const v4f *)p; }
+};
+struct CoherentLoad {
+    static __device__ __forceinline__ v4f ld(const float *p)
+    {
+        v4f v;
+        v.x = __hip_atomic_load(p + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        v.y = __hip_atomic_load(p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        v.z = __hip_atomic_load(p + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        v.w = __hip_atomic_load(p + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return v;
+    }
+};
+
+// out(b, r) = sum_k T[r][k] * M[b][k] for the nr rows of an LDS tile T (pitch n) and every row b
+// of a device matrix M (Bs x n, pitch n): sixteen lanes per row of M, four rows of M per wave at a
+// time, four tile rows per pass over M.  fin(b, r, sum) finishes an element.
+template <class Load, class Fin>
+__device__ __forceinline__ void tile_times_rows(const float *__restrict__ M, int n, int Bs, const float *T, int nr, Fin fin)
+{
+    constexpr int MAXIT = PD_MAX_BATCH / (kWaves * 4);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int sg = lane >> 4, g = lane & 15;
+    const int nk4 = n / 4;
+    const int nit = (Bs + kWaves * 4 - 1) / (kWaves * 4);
+    const int nchunk = (nk4 + 255) / 256;
+    for (int rc = 0; rc < nr; rc += 4) {
+        float acc[MAXIT][4];
+#pragma unroll
+        for (int i = 0; i < MAXIT; ++i)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) acc[i][q] = 0.f;
+        for (int c = 0; c < nchunk; ++c) {
+#pragma unroll
+            for (int it = 0; it < MAXIT; ++it) {
+                if (it < nit && it * (kWaves * 4) + wave * 4 < Bs) {   // waves whose four slots are all past the batch sit out
+                    const int b = min(it * (kWaves * 4) + wave * 4 + sg, Bs - 1);
+                    v4f x[16];
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) {
+                        const int k4 = (c * 16 + j) * 16 + g;
+                        x[j] = Load::ld(M + (size_t)b * n + (k4 < nk4 ? k4 : 0) * 4);
+                    }
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        if (rc + q < nr) {
+                            float t = 0.f;
+#pragma unroll
+                            for (int j = 0; j < 16; ++j) {
+                                const int k4 = (c * 16 + j) * 16 + g;
+                                if (k4 < nk4) {
+                                    const v4f wv = *(const v4f *)(T + (rc + q) * n + k4 * 4);
+                                    t += wv.x * x[j].x + wv.y * x[j].y + wv.z * x[j].z + wv.w * x[j].w;
+                                }
+                            }
+                            acc[it][q] += t;
+                        }
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int it = 0; it < MAXIT; ++it) {
+            if (it < nit && it * (kWaves * 4) + wave * 4 < Bs) {
+                const int b = it * (kWaves * 4) + wave * 4 + sg;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    if (rc + q < nr) {
+                        const float sum = row16_sum(acc[it][q]);
+                        if (g == 0 && b < Bs) fin(b, rc + q, sum);
+                    }
+                }
+            }
+        }
+    }
+}
+
+template <int NQ, class Load>
+__device__ __forceinline__ void rank_accumulate(v4f (&acc)[4], const float *__restrict__ Mcol, int n, int bbeg, int bend,
+                                                int Bs, const float *D, int dper, int rc)
+{
+    for (int bb0 = bbeg; bb0 < bend; bb0 += 8) {
+        v4f x[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) x[u] = Load::ld(Mcol + (size_t)min(bb0 + u, Bs - 1) * n);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const float on = (bb0 + u < bend) ? 1.f : 0.f;
+            const float *dr = D + min(bb0 + u, Bs - 1) * dper + rc;
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) acc[q] += x[u] * (dr[q] * on);
+        }
+    }
+}
+
+// T[r][k] -= scale * sum_b D[b][r] * M[b][k] for an LDS tile T (nr rows, pitch n), D in LDS
+// (pitch dper), M a device matrix (Bs x n).  With `halves` == 2 the samples are split between the
+// two halves of the workgroup (second half hands its sums over through tmp).  On the last step of
+// a plain-gradient-descent epoch (keepv) the applied change is also written to Vrows (device rows
+// of the velocity, pitch n), if given.  Contains barriers: call from uniform control flow.
+template <class Load>
+__device__ __forceinline__ void tile_rank_update(float *T, float *Vrows, int n, int nr, const float *D, int dper,
+                                                 const float *__restrict__ M, int Bs, float scale, bool keepv, float *tmp,
+                                                 int halves)
+{
+    const int tid = threadIdx.x;
+    const int nk4 = n / 4;
+    const int half = (halves == 2 && tid >= kThreads / 2) ? 1 : 0;
+    const int t0 = halves == 2 ? tid - half * (kThreads / 2) : tid;
+    const int tstep = halves == 2 ? kThreads / 2 : kThreads;
+    const int bmid = halves == 2 ? (Bs + 1) / 2 : Bs;
+    const int bbeg = half ? bmid : 0, bend = half ? Bs : bmid;
+    for (int rc = 0; rc < nr; rc += 4) {
+        for (int kb = 0; kb < nk4; kb += tstep) {
+            const int k4 = kb + t0;
+            const bool on = k4 < nk4;
+            v4f acc[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) acc[q] = (v4f){0.f, 0.f, 0.f, 0.f};
+            if (on) {
+                const float *Mcol = M + k4 * 4;
+                switch (min(4, nr - rc)) {
+                case 1: rank_accumulate<1, Load>(acc, Mcol, n, bbeg, bend, Bs, D, dper, rc); break;
+                case 2: rank_accumulate<2, Load>(acc, Mcol, n, bbeg, bend, Bs, D, dper, rc); break;
+                case 3: rank_accumulate<3, Load>(acc, Mcol, n, bbeg, bend, Bs, D, dper, rc); break;
+                default: rank_accumulate<4, Load>(acc, Mcol, n, bbeg, bend, Bs, D, dper, rc); break;
+                }
+            }
+            if (halves == 2) {
+                if (half == 1 && on) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) *(v4f *)(tmp + q * n + k4 * 4) = acc[q];
+                }
+                __syncthreads();
+                if (half == 0 && on) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) acc[q] += *(const v4f *)(tmp + q * n + k4 * 4);
+                }
+            }
+            if (half == 0 && on) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int r = rc + q;
+                    if (r < nr) {
+                        const int idx = r * n + k4 * 4;
+                        const v4f wv = *(const v4f *)(T + idx);
+                        const v4f dv = acc[q] * (-scale);
+                        *(v4f *)(T + idx) = wv + dv;
+                        if (keepv && Vrows) *(v4f *)(Vrows + (size_t)r * n + k4 * 4) = dv;
+                    }
+                }
+            }
+            if (halves == 2) __syncthreads();
+        }
+    }
+}
+
+__global__ __launch_bounds__(ON_THREADS) void deep_batch_epoch_kernel(DeepPlan p)
+{
+    extern __shared__ __align__(16) float lds[];
+    __shared__ int s_abort;
+    const int w = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int L = p.L, nL = p.layer[L].n_out, nL1 = nL + 1, maxB = p.max_batch, n0 = p.layer[1].n_in;
+    const DeepLayer &last = p.layer[L];
+    const int perL = p.layer[L - 1].per;                 // own units of layer L-1 = own columns of W_L
+    const int cL = w * perL;
+    const int ncL = max(0, min(perL, last.n_in - cL));
+    float *w2 = lds + p.lds_w2, *bL = lds + p.lds_bL, *d2 = lds + p.lds_d2, *zs = lds + p.lds_zs, *tmp = lds + p.lds_tmp;
+    auto own_c0 = [&](int l) { return w * p.layer[l].per; };
+    auto own_nr = [&](int l) { return max(0, min(p.layer[l].per, p.layer[l].n_out - w * p.layer[l].per)); };
+
+    // ---- prologue: own slices into LDS ----
+    if (tid == 0) s_abort = 0;
+    for (int k = tid; k < nL; k += kThreads) bL[k] = last.b[k];
+    for (int l = 1; l < L; ++l) {
+        const DeepLayer &ly = p.layer[l];
+        const int c0 = own_c0(l), nr = own_nr(l);
+        float *bl = lds + p.lds_b[l];
+        for (int r = tid; r < nr; r += kThreads) bl[r] = ly.b[c0 + r];
+        if (nr > 0) copy_floats(lds + p.lds_r[l], ly.W + (size_t)c0 * ly.n_in, nr * ly.n_in);
+        if (l >= 2) {   // transposed copy of the weights leaving this workgroup's units of layer l-1
+            const int cp = own_c0(l - 1), np = own_nr(l - 1);
+            float *ct = lds + p.lds_ct[l];
+            for (int i = tid; i < np * ly.n_out; i += kThreads) {
+                const int j = i / ly.n_out, o = i - j * ly.n_out;
+                ct[j * ly.n_out + o] = ly.W[(size_t)o * ly.n_in + cp + j];
+            }
+        }
+    }
+    for (int i = tid; i < nL * ncL; i += kThreads) {
+        const int k = i / ncL, j = i - k * ncL;
+        w2[k * perL + j] = last.W[(size_t)k * last.n_in + cL + j];
+    }
+    double loss_acc = 0.0;
+    float pf_sink = 0.f;
+    __syncthreads();
+
+    const int64_t nsteps = (p.n_samples + p.batch - 1) / p.batch;
+    for (int64_t step = 0; step < nsteps; ++step) {
+        const int64_t s0 = step * p.batch;
+        const int Bs = (int)min((int64_t)p.batch, p.n_samples - s0);
+        const uint32_t seq = p.seq0 + 1u + (uint32_t)step;
+        const int par = (int)(seq & 1u);
+        const bool keepv = p.keep_v && step == nsteps - 1;
+        const float scale = p.lr / (float)Bs;
+        const float *Xb = p.X + (size_t)s0 * n0;
+        const int32_t *yb = p.labels + s0;
+        bool aborted = false;
+
+        // ---- forward through the hidden layers ----
+        for (int l = 1; l < L; ++l) {
+            const DeepLayer &ly = p.layer[l];
+            const int c0 = own_c0(l), nr = own_nr(l);
+            float *a_own = lds + p.lds_a[l];
+            if (nr > 0) {
+                const float *bl = lds + p.lds_b[l];
+                const float *T = lds + p.lds_r[l];
+                const int per = ly.per, act = ly.act;
+                auto fin = [&](int b, int r, float sum) { a_own[b * per + r] = act_fn(act, sum + bl[r]); };
+                if (l == 1) {
+                    tile_times_rows<PlainLoad>(Xb, ly.n_in, Bs, T, nr, fin);
+                } else {
+                    const u64 *flags = p.fa[l - 1] + (size_t)par * p.grid;
+                    poll_words(p.layer[l - 1].P, seq, [&](int q) { return flags + q; }, [&](int, float) {}, p.abort_flag,
+                               &s_abort);
+                    __syncthreads();
+                    if (s_abort) { aborted = true; break; }
+                    tile_times_rows<CoherentLoad>(p.ea[l - 1] + (size_t)par * maxB * ly.n_in, ly.n_in, Bs, T, nr, fin);
+                }
+            }
+            __syncthreads();
+            if (l <= L - 2 && nr > 0) {   // publish the own slice, then say so
+                float *dst = p.ea[l] + (size_t)par * maxB * ly.n_out;
+                for (int q = tid; q < Bs * nr; q += kThreads) {
+                    const int b = q / nr, r = q - b * nr;
+                    __hip_atomic_store(dst + (size_t)b * ly.n_out + c0 + r, a_own[b * ly.per + r], __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+                }
+                __syncthreads();   // every thread's stores are complete
+                if (tid == 0) ll_store(p.fa[l] + (size_t)par * p.grid + w, 0.f, seq);
+            }
+        }
+        if (aborted) break;
+
+        // ---- output layer: partial net inputs from own columns (every workgroup publishes) ----
+        const float *aL = lds + p.lds_a[L - 1];
+        {
+            u64 *zout = p.z_x + ((size_t)par * p.grid + w) * ((size_t)maxB * nL);
+            for (int q = tid; q < Bs * nL; q += kThreads) {
+                const int b = q / nL, k = q - b * nL;
+                float z = 0.f;
+                for (int j = 0; j < ncL; ++j) z += w2[k * perL + j] * aL[b * perL + j];
+                ll_store(zout + q, z, seq);
+            }
+        }
+        if (step + 1 < nsteps) {   // next batch towards the L2, one word per 128-byte line
+            const int64_t s1 = s0 + p.batch;
+            const int64_t words = (int64_t)min((int64_t)p.batch, p.n_samples - s1) * n0;
+            const float *Xn = p.X + (size_t)s1 * n0;
+            const int nlocal = (p.grid + 7) / 8, local = w / 8;
+            for (int64_t line = (int64_t)local * kThreads + tid; line * 32 < words; line += (int64_t)nlocal * kThreads)
+                pf_sink += Xn[line * 32];
+        }
+        const int b0 = w * p.spw;
+        const int nb = max(0, min(p.spw, Bs - b0));
+        if (nb > 0) {
+            gather_partials(p.z_x + (size_t)par * p.grid * ((size_t)maxB * nL), p.grid, maxB * nL, b0 * nL, nb * nL, seq,
+                            tmp, [&](int e, float sum) { zs[e] = sum; }, p.abort_flag, &s_abort);
+            if (s_abort) break;
+            for (int bb = wave; bb < nb; bb += kWaves) {
+                const float *z = zs + bb * nL;
+                int y = yb[b0 + bb];
+                y = y < 0 ? 0 : (y >= nL ? nL - 1 : y);
+                const int k0 = lane, k1 = lane + 64;
+                const float z0 = k0 < nL ? z[k0] + bL[k0] : -INFINITY, z1 = k1 < nL ? z[k1] + bL[k1] : -INFINITY;
+                float d0, d1v, e;
+                if (p.loss == DN_LOSS_CROSS_ENTROPY) {
+                    const float m = wave_max(fmaxf(z0, z1));
+                    const float e0 = k0 < nL ? expf(z0 - m) : 0.f, e1 = k1 < nL ? expf(z1 - m) : 0.f;
+                    const float sum = wave_sum(e0 + e1);
+                    const float inv = 1.0f / sum;
+                    d0 = e0 * inv - (k0 == y ? 1.0f : 0.0f);
+                    d1v = e1 * inv - (k1 == y ? 1.0f : 0.0f);
+                    e = logf(sum) - ((z[y] + bL[y]) - m);
+                } else {
+                    const float a0 = act_fn(last.act, z0), a1v = act_fn(last.act, z1);
+                    const float f0 = a0 - (k0 == y ? 1.0f : 0.0f), f1 = a1v - (k1 == y ? 1.0f : 0.0f);
+                    d0 = f0 * act_deriv(last.act, a0);
+                    d1v = f1 * act_deriv(last.act, a1v);
+                    e = wave_sum((k0 < nL ? 0.5f * f0 * f0 : 0.f) + (k1 < nL ? 0.5f * f1 * f1 : 0.f));
+                }
+                u64 *dout = p.d_x + (size_t)par * ((size_t)maxB * nL1) + (size_t)(b0 + bb) * nL1;
+                if (k0 < nL) ll_store(dout + k0, d0, seq);
+                if (k1 < nL) ll_store(dout + k1, d1v, seq);
+                if (lane == 0) ll_store(dout + nL, e, seq);
+            }
+        }
+        {
+            const u64 *dsrc = p.d_x + (size_t)par * ((size_t)maxB * nL1);
+            poll_words(Bs * nL1, seq, [&](int q) { return dsrc + q; }, [&](int q, float v) { d2[q] = v; }, p.abort_flag,
+                       &s_abort);
+        }
+        __syncthreads();
+        if (s_abort) break;
+        if (w == 0 && wave == 0) {
+            double part = 0.0;
+            for (int b = lane; b < Bs; b += 64) part += (double)d2[b * nL1 + nL];
+#pragma unroll
+            for (int o = 32; o >= 1; o >>= 1) part += __shfl_xor(part, o, 64);
+            loss_acc += part;
+        }
+        for (int t = tid; t < nL * 16; t += kThreads) {
+            const int k = t >> 4, gq = t & 15;
+            float g = 0.f;
+            for (int b = gq; b < Bs; b += 16) g += d2[b * nL1 + k];
+            g = row16_sum(g);
+            if (gq == 0) {
+                const float dv = -scale * g;
+                bL[k] += dv;
+                if (keepv && w == 0) last.Vb[k] = dv;
+            }
+        }
+        // deltas of the own units of layer L-1 through the last layer's weights before their update
+        {
+            float *dl = lds + p.lds_dl[L - 1];
+            const int actp = p.layer[L - 1].act;
+            for (int q = tid; q < Bs * ncL; q += kThreads) {
+                const int b = q / ncL, j = q - b * ncL;
+                float sacc = 0.f;
+                for (int k = 0; k < nL; ++k) sacc += w2[k * perL + j] * d2[b * nL1 + k];
+                dl[b * perL + j] = sacc * act_deriv(actp, aL[b * perL + j]);
+            }
+        }
+        __syncthreads();
+        for (int t = tid; t < nL * ncL * 16; t += kThreads) {
+            const int q = t >> 4, gq = t & 15;
+            const int k = q / ncL, j = q - k * ncL;
+            float g = 0.f;
+            for (int b = gq; b < Bs; b += 16) g += d2[b * nL1 + k] * aL[b * perL + j];
+            g = row16_sum(g);
+            if (gq == 0) {
+                const float dv = -scale * g;
+                w2[k * perL + j] += dv;
+                if (keepv) last.VW[(size_t)k * last.n_in + cL + j] = dv;
+            }
+        }
+
+        // ---- backward through the hidden layers ----
+        for (int l = L - 1; l >= 1; --l) {
+            const DeepLayer &ly = p.layer[l];
+            const int c0 = own_c0(l), nr = own_nr(l);
+            float *dl = lds + p.lds_dl[l];
+            if (l >= 2 && nr > 0) {   // everyone needs this layer's deltas: publish the own slice
+                float *dst = p.ed[l] + (size_t)par * maxB * ly.n_out;
+                for (int q = tid; q < Bs * nr; q += kThreads) {
+                    const int b = q / nr, r = q - b * nr;
+                    __hip_atomic_store(dst + (size_t)b * ly.n_out + c0 + r, dl[b * ly.per + r], __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+                }
+                __syncthreads();
+                if (tid == 0) ll_store(p.fd[l] + (size_t)par * p.grid + w, 0.f, seq);
+            }
+            if (nr > 0) {   // own rows of W_l and their biases
+                float *Vrows = ly.VW + (size_t)c0 * ly.n_in;
+                if (l == 1)
+                    tile_rank_update<PlainLoad>(lds + p.lds_r[l], Vrows, ly.n_in, nr, dl, ly.per, Xb, Bs, scale, keepv, tmp,
+                                                p.halves);
+                else
+                    tile_rank_update<CoherentLoad>(lds + p.lds_r[l], Vrows, ly.n_in, nr, dl, ly.per,
+                                                   p.ea[l - 1] + (size_t)par * maxB * ly.n_in, Bs, scale, keepv, tmp,
+                                                   p.halves);
+                float *bl = lds + p.lds_b[l];
+                for (int t = tid; t < nr * 16; t += kThreads) {
+                    const int r = t >> 4, gq = t & 15;
+                    float g = 0.f;
+                    for (int b = gq; b < Bs; b += 16) g += dl[b * ly.per + r];
+                    g = row16_sum(g);
+                    if (gq == 0) {
+                        const float dv = -scale * g;
+                        bl[r] += dv;
+                        if (keepv) ly.Vb[c0 + r] = dv;
+                    }
+                }
+            }
+            if (l >= 2) {
+                const DeepLayer &lp = p.layer[l - 1];
+                const int np = own_nr(l - 1);
+                if (np > 0) {   // deltas of the own units of layer l-1, then the second copy's update
+                    const u64 *flags = p.fd[l] + (size_t)par * p.grid;
+                    poll_words(ly.P, seq, [&](int q) { return flags + q; }, [&](int, float) {}, p.abort_flag, &s_abort);
+                    __syncthreads();
+                    if (s_abort) { aborted = true; break; }
+                    const float *Dm = p.ed[l] + (size_t)par * maxB * ly.n_out;
+                    float *dp = lds + p.lds_dl[l - 1];
+                    const float *ap = lds + p.lds_a[l - 1];
+                    const int pper = lp.per, actp = lp.act;
+                    tile_times_rows<CoherentLoad>(Dm, ly.n_out, Bs, lds + p.lds_ct[l], np, [&](int b, int j, float sum) {
+                        dp[b * pper + j] = sum * act_deriv(actp, ap[b * pper + j]);
+                    });
+                    __syncthreads();
+                    tile_rank_update<CoherentLoad>(lds + p.lds_ct[l], nullptr, ly.n_out, np, ap, pper, Dm, Bs, scale, false,
+                                                   tmp, p.halves);
+                }
+            }
+            __syncthreads();
+        }
+        if (aborted) break;
+    }
+
+    // ---- epilogue: LDS images back to device memory ----
+    __syncthreads();
+    for (int l = 1; l < L; ++l) {
+        const DeepLayer &ly = p.layer[l];
+        const int c0 = own_c0(l), nr = own_nr(l);
+        const float *bl = lds + p.lds_b[l];
+        for (int r = tid; r < nr; r += kThreads) ly.b[c0 + r] = bl[r];
+        if (nr > 0) copy_floats(ly.W + (size_t)c0 * ly.n_in, lds + p.lds_r[l], nr * ly.n_in);
+    }
+    for (int i = tid; i < nL * ncL; i += kThreads) {
+        const int k = i / ncL, j = i - k * ncL;
+        last.W[(size_t)k * last.n_in + cL + j] = w2[k * perL + j];
+    }
+    if (pf_sink == 1.2345678e-30f) *p.abort_flag = 0;
+    if (w == 0) {
+        if (tid == 0) *p.loss_acc += loss_acc;
+        for (int k = tid; k < nL; k += kThreads) last.b[k] = bL[k];
+    }
+}
+
 }  // namespace
 
 // ---- host side -------------------------------------------------------------------
@@ -1412,6 +1849,91 @@ hipError_t launch_batch_epoch(const BatchGeom &g, const BatchPlan &plan, hipStre
     BatchPlan p = plan;
     void *args[] = {&p};
     return hipLaunchCooperativeKernel((const void *)batch_epoch_kernel, dim3(g.grid), dim3(ON_THREADS), args,
+                                      (unsigned)(g.lds_floats * sizeof(float)), stream);
+}
+
+bool deep_geometry(const int32_t *n, int L, int max_batch, int min_tile, DeepGeom &g)
+{
+    g = DeepGeom{};
+    if (L < 3 || L > ON_MAX_L) return false;
+    const int nL = n[L];
+    if (nL > ON_MAX_NL || max_batch < 2 || max_batch > PD_MAX_BATCH) return false;
+    for (int l = 0; l < L; ++l)
+        if (n[l] % 4 != 0) return false;     // tile rows are read as float4
+    if (min_tile < 1) min_tile = 1;
+    auto cdiv = [](int64_t a, int64_t b) { return (int)((a + b - 1) / b); };
+    auto pad4 = [](int v) { return (v + 3) & ~3; };
+    g.L = L;
+    int grid = 1, nmax = 0;
+    for (int l = 1; l < L; ++l) {
+        int per = std::max(cdiv(n[l], ON_MAX_WG), cdiv(min_tile, (int64_t)n[l - 1] * max_batch));
+        per = std::min(per, n[l]);
+        g.per[l] = per;
+        g.P[l] = cdiv(n[l], per);
+        grid = std::max(grid, g.P[l]);
+        nmax = std::max(nmax, std::max(n[l - 1], n[l]));
+    }
+    g.per[L] = g.per[L - 1];
+    g.P[L] = g.P[L - 1];
+    g.grid = grid;
+    g.spw = cdiv(max_batch, grid);
+    // the two halves of a workgroup split the samples of a rank-B update only if every tile allows it
+    g.halves = (2 * (nmax / 4) <= kThreads && 4 * nmax <= kTmp) ? 2 : 1;
+    size_t bytes = 0;
+    auto take = [&](size_t b) { const size_t o = bytes; bytes += (b + 255) / 256 * 256; return o; };
+    g.off_z = take(2 * (size_t)grid * max_batch * nL * sizeof(u64));
+    g.off_d = take(2 * (size_t)max_batch * (nL + 1) * sizeof(u64));
+    for (int l = 1; l <= L - 1; ++l) {
+        if (l <= L - 2) { g.off_ea[l] = take(2 * (size_t)max_batch * n[l] * sizeof(float)); g.off_fa[l] = take(2 * (size_t)grid * sizeof(u64)); }
+        if (l >= 2) { g.off_ed[l] = take(2 * (size_t)max_batch * n[l] * sizeof(float)); g.off_fd[l] = take(2 * (size_t)grid * sizeof(u64)); }
+    }
+    g.bytes = bytes;
+    int64_t f = 0;
+    for (int l = 1; l < L; ++l) {
+        g.lds_r[l] = (int)f; f += pad4(g.per[l] * n[l - 1]);
+        if (l >= 2) { g.lds_ct[l] = (int)f; f += pad4(g.per[l - 1] * n[l]); }
+        g.lds_b[l] = (int)f; f += pad4(g.per[l]);
+        g.lds_a[l] = (int)f; f += pad4(max_batch * g.per[l]);
+        g.lds_dl[l] = (int)f; f += pad4(max_batch * g.per[l]);
+    }
+    g.lds_w2 = (int)f; f += pad4(nL * g.per[L - 1]);
+    g.lds_bL = (int)f; f += ON_MAX_NL;
+    g.lds_d2 = (int)f; f += pad4(max_batch * (nL + 1));
+    g.lds_zs = (int)f; f += pad4(g.spw * nL);
+    g.lds_tmp = (int)f; f += ON_TMP_FLOATS;
+    if (f * (int64_t)sizeof(float) > (int64_t)ON_MAX_LDS_BYTES) return false;
+    g.lds_floats = (int)f;
+    g.ok = true;
+    return true;
+}
+
+size_t deep_exchange_bytes_bound(const int32_t *n, int L, int max_batch)
+{
+    if (L < 3 || L > ON_MAX_L || n[L] > ON_MAX_NL || max_batch < 2 || max_batch > PD_MAX_BATCH) return 0;
+    for (int l = 0; l < L; ++l)
+        if (n[l] % 4 != 0) return 0;
+    size_t bytes = 0;
+    auto take = [&](size_t b) { bytes += (b + 255) / 256 * 256; };
+    take(2 * (size_t)ON_MAX_WG * max_batch * n[L] * sizeof(u64));
+    take(2 * (size_t)max_batch * (n[L] + 1) * sizeof(u64));
+    for (int l = 1; l <= L - 1; ++l) {
+        take(2 * (size_t)max_batch * n[l] * sizeof(float)); take(2 * (size_t)ON_MAX_WG * sizeof(u64));
+        take(2 * (size_t)max_batch * n[l] * sizeof(float)); take(2 * (size_t)ON_MAX_WG * sizeof(u64));
+    }
+    return bytes > ((size_t)1 << 30) ? 0 : bytes;
+}
+
+hipError_t deep_prepare()
+{
+    return hipFuncSetAttribute((const void *)deep_batch_epoch_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                               (int)ON_MAX_LDS_BYTES);
+}
+
+hipError_t launch_deep_epoch(const DeepGeom &g, const DeepPlan &plan, hipStream_t stream)
+{
+    DeepPlan p = plan;
+    void *args[] = {&p};
+    return hipLaunchCooperativeKernel((const void *)deep_batch_epoch_kernel, dim3(g.grid), dim3(ON_THREADS), args,
                                       (unsigned)(g.lds_floats * sizeof(float)), stream);
 }
 

@@ -272,3 +272,67 @@ def test_persistent_minibatch_is_bitwise_reproducible_and_close_to_per_launch(dn
         assert np.array_equal(a, b)
     for a, b in zip(outs[0][1][0] + outs[0][1][1], outs[2][1][0] + outs[2][1][1]):
         assert_close(a, b, 1e-4, "persistent vs per-launch")
+
+
+# ------------------------------ minibatches of deeper nets, plain gradient descent: persistent kernel ----
+
+DEEP_SHAPES = [
+    # widths, acts, loss, batch, samples
+    ([64, 96, 80, 10], [TANH, RELU, SOFTMAX], CE, 8, 44),               # short last batch
+    ([20, 40, 32, 52, 24, 6], [TANH, SIG, RELU, TANH, SOFTMAX], CE, 5, 25),
+    ([1024, 1024, 1024, 1024, 10], [TANH, TANH, TANH, SOFTMAX], CE, 8, 24),   # the batch-size sweep's net
+    ([128, 2048, 64, 3], [SIG, TANH, SIG], MSE, 64, 128),               # widest batch; rows longer than 1024
+    ([16, 1000, 24, 128], [RELU, TANH, SOFTMAX], CE, 32, 64),
+]
+
+
+@pytest.mark.parametrize("widths,acts,loss,B,n", DEEP_SHAPES)
+@pytest.mark.parametrize("min_tile", [None, 64])
+def test_persistent_deep_minibatch_epochs_match_checker(dnlib, widths, acts, loss, B, n, min_tile):
+    announce("persistent deep minibatch widths=%s B=%d min_tile=%s" % (widths, B, min_tile))
+    w = synth.make("pdeep", widths, acts, loss, n_samples=n, features="normal", init="xavier_uniform",
+                   batch=B, lr=0.02, momentum=0.0, seed=8)
+    rng = np.random.default_rng(17)
+    w.b = [rng.standard_normal(k).astype(np.float32) * 0.1 for k in w.widths[1:]]
+    net = dnlib.Net(w.widths, w.acts, w.loss, B)
+    net.set_all(w.W, w.b)
+    net.dn_set_option("batch_mode", 2)
+    if min_tile is not None:
+        net.dn_set_option("online_min_tile", min_tile)
+    o = Oracle("o32", w.widths, w.acts, w.loss)
+    o.set_params(w.W, w.b)
+    X = torch.from_numpy(w.X).to("cuda:0")
+    y = torch.from_numpy(w.labels).to("cuda:0")
+    for _ in range(2):
+        got = net.dn_train_epoch(X, y, B, w.lr, 0.0)
+        ref, _ = o.train_epoch(w.X, w.labels, B, w.lr, 0.0)
+        assert abs(got - ref) <= 1e-4 * max(abs(ref), 1e-6), (got, ref)
+    # a momentum pass afterwards (one launch per product) starts from the velocity the plain pass left
+    net.dn_set_option("batch_mode", 0)
+    got = net.dn_train_epoch(X, y, B, w.lr, 0.5)
+    ref, _ = o.train_epoch(w.X, w.labels, B, w.lr, 0.5)
+    assert abs(got - ref) <= 1e-4 * max(abs(ref), 1e-6), (got, ref)
+    W, b = net.get_all()
+    Wr, br = o.get_params()
+    for l in range(net.L):
+        assert_close(W[l], Wr[l], 1e-4, "W_%d" % (l + 1))
+        assert_close(b[l], br[l], 1e-4, "b_%d" % (l + 1))
+    net.close()
+
+
+def test_persistent_deep_minibatch_is_bitwise_reproducible(dnlib):
+    announce("persistent deep minibatch determinism")
+    w = synth.tanh_sweep(8, n_samples=320)
+    outs = []
+    for _ in range(2):
+        net = dnlib.Net(w.widths, w.acts, w.loss, 8)
+        net.set_all(w.W, w.b)
+        net.dn_set_option("batch_mode", 2)
+        X = torch.from_numpy(w.X).to("cuda:0")
+        y = torch.from_numpy(w.labels).to("cuda:0")
+        loss = net.dn_train_epoch(X, y, 8, w.lr, 0.0)
+        outs.append((loss, net.get_all()))
+        net.close()
+    assert outs[0][0] == outs[1][0]
+    for a, b in zip(outs[0][1][0] + outs[0][1][1], outs[1][1][0] + outs[1][1][1]):
+        assert np.array_equal(a, b)

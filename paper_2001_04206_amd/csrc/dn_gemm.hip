@@ -662,11 +662,12 @@ using V6 = Tile<32, 32, 64, 1, 1, 8, 2>;        // few output tiles: lean on the
 using V7 = Tile<128, 128, 16, 2, 2, 1, 2, 16>;  // weight gradients: epilogue operands fetched over 16 k steps
 using V8 = Tile<128, 64, 16, 2, 2, 1, 2, 16, 2>;  // weight gradients, two workgroups per CU: one's epilogue under the other's k loop
 using V9 = Tile<64, 64, 16, 2, 2, 1, 2, 8, 4>;    // weight gradients, four workgroups per CU
+using V10 = Tile<64, 64, 32, 2, 2, 2, 2, 0, 2>;   // weight gradients over long k (large batches): k split between two wave groups
 
 static const char *kVariantNames[] = {"128x128x16_r1",  "128x64x16_r2",   "64x64x64_k4_r2", "64x64x32_k4_r2",
                                       "32x64x32_k4_r2", "32x64x64_k8_r2", "32x32x64_k8_r2", "128x128x16_r2_pc16",
-                                      "128x64x16_r2_pc16_o2", "64x64x16_r2_pc8_o4"};
-constexpr int kVariants = 10;
+                                      "128x64x16_r2_pc16_o2", "64x64x16_r2_pc8_o4", "64x64x32_k2_r2_o2"};
+constexpr int kVariants = 11;
 int gemm_variant_count() { return kVariants; }
 const char *gemm_variant_name(int v) { return (v >= 0 && v < kVariants) ? kVariantNames[v] : "?"; }
 
@@ -708,6 +709,7 @@ static int pick_variant(GemmKind kind, const GemmArgs &a)
     // 64x64 tiles with four workgroups per CU let one workgroup's prologue / epilogue traffic run
     // under another's matrix work: best whenever there are enough of them (weight gradients with
     // their read-modify-write epilogue need one per CU, the other products two).
+    if (kind == GEMM_GRAD && a.K > 512 && tiles(64, 64) >= 256) return 10;
     if (tiles(64, 64) >= (kind == GEMM_GRAD ? 256 : 512)) return 9;
     if (a.K <= 512 && tiles(128, 128) >= 256) return a.K >= 192 ? 7 : 0;
     if (tiles(128, 64) >= 256) return 1;
@@ -730,6 +732,7 @@ hipError_t launch_gemm(GemmKind kind, const GemmArgs &a, int variant, hipStream_
     case 7: return launch_kind<V7>(kind, a, stream);
     case 8: return launch_kind<V8>(kind, a, stream);
     case 9: return launch_kind<V9>(kind, a, stream);
+    case 10: return launch_kind<V10>(kind, a, stream);
     default: return hipErrorInvalidValue;
     }
 }

@@ -706,11 +706,13 @@ static hipError_t launch_kind(GemmKind kind, const GemmArgs &a, hipStream_t stre
 static int pick_variant(GemmKind kind, const GemmArgs &a)
 {
     auto tiles = [&](int bm, int bn) { return (long)((a.M + bm - 1) / bm) * ((a.N + bn - 1) / bn); };
-    // 64x64 tiles with four workgroups per CU let one workgroup's prologue / epilogue traffic run
-    // under another's matrix work: best whenever there are enough of them (weight gradients with
-    // their read-modify-write epilogue need one per CU, the other products two).
-    if (kind == GEMM_GRAD && a.K > 512 && tiles(64, 64) >= 256) return 10;
-    if (tiles(64, 64) >= (kind == GEMM_GRAD ? 256 : 512)) return 9;
+    // 64x64 tiles at several workgroups per CU let one workgroup's prologue / epilogue traffic run
+    // under another's matrix work.  Weight gradients (read-modify-write epilogue): the k = batch
+    // loop is short, so the epilogue operands are prefetched in chunks (variant 9); over a long k
+    // (large batches) two wave groups split each k step instead (variant 10).  Forward and delta
+    // products always have a long k.
+    if (kind == GEMM_GRAD && tiles(64, 64) >= 256) return a.K > 512 ? 10 : 9;
+    if (kind != GEMM_GRAD && tiles(64, 64) >= 256) return 10;
     if (a.K <= 512 && tiles(128, 128) >= 256) return a.K >= 192 ? 7 : 0;
     if (tiles(128, 64) >= 256) return 1;
     if (tiles(32, 64) > 256) return 4;

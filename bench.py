@@ -95,7 +95,7 @@ def main():
                     help="skip the second, event-bracketed pass over the same steps (roofline becomes null)")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+        sys.exit("bench.py measures one GPU: the library has no multi-GPU path (run with --gpus 1)")
 
     import numpy as np
     import torch

@@ -1,5 +1,5 @@
 """GPU parity: libdn (through its C ABI) against the CPU checker on the same
-seeded inputs.  Tolerances are the ones the task fixes: relative error 1e-4 on
+seeded inputs.  Tolerances: relative error 1e-4 on
 gradients and on weights after one step, 1e-3 on weights and loss after an
 epoch (relative L2 per tensor and max-abs relative to the tensor's max).
 The reference is the checker's fp32-storage / fp64-accumulate mode."""

@@ -457,7 +457,7 @@ def test_training_until_max_error_stops_at_the_first_epoch_below_it():
     o = Oracle("o64", w.widths, w.acts, w.loss)
     o.set_params(w.W, w.b)
     _, _, losses = o.train(w.X, w.labels, w.batch, w.lr, w.momentum, max_error=-1.0, max_epochs=12)
-    assert len(losses) == 12 and losses[-1] < 0.5 * losses[0]           # the task has signal: the loss falls
+    assert len(losses) == 12 and losses[-1] < 0.5 * losses[0]           # the labels carry signal: the loss falls
     k = next(i for i in range(1, 12) if losses[i] < losses[i - 1] and losses[i] < min(losses[:i]))
     threshold = 0.5 * (losses[k] + min(losses[:k]))                     # first crossed by epoch k+1
     o.set_params(w.W, w.b)

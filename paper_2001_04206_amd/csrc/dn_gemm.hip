@@ -590,8 +590,12 @@ template <class T, bool A_KC, bool B_KC, int EPI, bool VEC>
 __global__ __launch_bounds__(T::NT, T::OCC) void gemm_kernel(GemmArgs g, int tiles_m, int tiles_n)
 {
     extern __shared__ __attribute__((aligned(16))) float smem[];
-    // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous
-    // run of tiles (m fastest) so tiles sharing a B panel meet in one L2.
+    // Workgroups are dealt round-robin to the 8 XCDs; each XCD gets a contiguous run of tiles so
+    // that tiles sharing operand panels meet in one L2.  Tiles are ordered in groups of GN tile
+    // columns, m next, the columns of the group fastest: the ~128 tiles an XCD works on at a time
+    // then form a compact block (16 x 8 tiles: 24 operand panels) rather than two full tile
+    // columns (66 panels), which matters for the weight-gradient product, whose streaming
+    // read-modify-write of W and the velocity keeps evicting the panels from the L2.
     const int nt = tiles_m * tiles_n;
     const int sk = g.sk > 1 ? g.sk : 1;
     const int nwork = nt * sk;           // (tile, k split) pairs, splits of a tile adjacent
@@ -599,7 +603,12 @@ __global__ __launch_bounds__(T::NT, T::OCC) void gemm_kernel(GemmArgs g, int til
     const int u = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
     if (u >= nwork) return;
     const int v = u / sk, split = u - v * sk;
-    const int m0 = (v % tiles_m) * T::BM, n0 = (v / tiles_m) * T::BN;
+    constexpr int GN = 8;
+    const int group = v / (tiles_m * GN);
+    const int r = v - group * (tiles_m * GN);
+    const int gn = min(GN, tiles_n - group * GN);
+    const int tm = r / gn, tn = group * GN + (r - tm * gn);
+    const int m0 = tm * T::BM, n0 = tn * T::BN;
     if (VEC && m0 + T::BM <= g.M && n0 + T::BN <= g.N)
         gemm_tile<T, A_KC, B_KC, EPI, VEC, VEC>(g, smem, m0, n0, v, split);
     else

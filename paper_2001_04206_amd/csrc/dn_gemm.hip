@@ -672,11 +672,12 @@ using V7 = Tile<128, 128, 16, 2, 2, 1, 2, 16>;  // weight gradients: epilogue op
 using V8 = Tile<128, 64, 16, 2, 2, 1, 2, 16, 2>;  // weight gradients, two workgroups per CU: one's epilogue under the other's k loop
 using V9 = Tile<64, 64, 16, 2, 2, 1, 2, 8, 4>;    // weight gradients, four workgroups per CU
 using V10 = Tile<64, 64, 32, 2, 2, 2, 2, 0, 2>;   // weight gradients over long k (large batches): k split between two wave groups
+using V11 = Tile<64, 64, 16, 2, 2, 1, 2, 8, 3>;   // as V9 with three workgroups per CU: the momentum update then needs no register spills
 
 static const char *kVariantNames[] = {"128x128x16_r1",  "128x64x16_r2",   "64x64x64_k4_r2", "64x64x32_k4_r2",
                                       "32x64x32_k4_r2", "32x64x64_k8_r2", "32x32x64_k8_r2", "128x128x16_r2_pc16",
-                                      "128x64x16_r2_pc16_o2", "64x64x16_r2_pc8_o4", "64x64x32_k2_r2_o2"};
-constexpr int kVariants = 11;
+                                      "128x64x16_r2_pc16_o2", "64x64x16_r2_pc8_o4", "64x64x32_k2_r2_o2", "64x64x16_r2_pc8_o3"};
+constexpr int kVariants = 12;
 int gemm_variant_count() { return kVariants; }
 const char *gemm_variant_name(int v) { return (v >= 0 && v < kVariants) ? kVariantNames[v] : "?"; }
 
@@ -717,10 +718,12 @@ static int pick_variant(GemmKind kind, const GemmArgs &a)
     auto tiles = [&](int bm, int bn) { return (long)((a.M + bm - 1) / bm) * ((a.N + bn - 1) / bn); };
     // 64x64 tiles at several workgroups per CU let one workgroup's prologue / epilogue traffic run
     // under another's matrix work.  Weight gradients (read-modify-write epilogue): the k = batch
-    // loop is short, so the epilogue operands are prefetched in chunks (variant 9); over a long k
-    // (large batches) two wave groups split each k step instead (variant 10).  Forward and delta
-    // products always have a long k.
-    if (kind == GEMM_GRAD && tiles(64, 64) >= 256) return a.K > 512 ? 10 : 9;
+    // loop is short, so the epilogue operands are prefetched in chunks (variant 11: three
+    // workgroups per CU, whose register budget holds the prefetched W and velocity without
+    // spills; variant 9, four per CU, spills and is ~6 % slower); over a long k (large batches)
+    // two wave groups split each k step instead (variant 10).  Forward and delta products always
+    // have a long k.
+    if (kind == GEMM_GRAD && tiles(64, 64) >= 256) return a.K > 512 ? 10 : 11;
     if (kind != GEMM_GRAD && tiles(64, 64) >= 256) return 10;
     if (a.K <= 512 && tiles(128, 128) >= 256) return a.K >= 192 ? 7 : 0;
     if (tiles(128, 64) >= 256) return 1;
@@ -744,6 +747,7 @@ hipError_t launch_gemm(GemmKind kind, const GemmArgs &a, int variant, hipStream_
     case 8: return launch_kind<V8>(kind, a, stream);
     case 9: return launch_kind<V9>(kind, a, stream);
     case 10: return launch_kind<V10>(kind, a, stream);
+    case 11: return launch_kind<V11>(kind, a, stream);
     default: return hipErrorInvalidValue;
     }
 }

@@ -111,7 +111,7 @@ SMALL_CASES = [
 
 
 @pytest.mark.parametrize("widths,acts,loss,B", SMALL_CASES)
-@pytest.mark.parametrize("variant", [-1, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10])
+@pytest.mark.parametrize("variant", [-1, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11])
 def test_one_step_small_and_ragged(dnlib, widths, acts, loss, B, variant):
     announce("one_step_small widths=%s acts=%s loss=%d B=%d variant=%d" % (widths, acts, loss, B, variant))
     w = synth.make("small", widths, acts, loss, n_samples=2 * B, features="normal",

@@ -23,7 +23,7 @@ struct Layout {
     size_t region = 0;          // bytes of one parameter-shaped region (params / velocity / gradients)
     std::vector<size_t> A, D;   // activations / deltas of layers 1..L, absolute
     size_t off_params = 0, off_vel = 0, off_grads = 0;
-    size_t off_loss_rows = 0, off_hit_rows = 0, off_scalars = 0;
+    size_t off_loss_rows = 0, off_hit_rows = 0, off_loss_sums = 0, off_scalars = 0;
     size_t off_online = 0, online_bytes = 0;   // exchange buffers of the persistent batch-1 kernel
     size_t off_gemm_ws = 0, off_gemm_counters = 0;   // partial tiles / arrival counters of k-split contractions
     size_t off_batch = 0, batch_bytes = 0;           // exchange buffers of the persistent minibatch kernel
@@ -66,6 +66,7 @@ bool compute_layout(const int32_t *widths, int32_t n_widths, int32_t max_batch, 
     }
     lo.off_loss_rows = o; o += align_up((size_t)max_batch * sizeof(float));
     lo.off_hit_rows = o; o += align_up((size_t)max_batch * sizeof(float));
+    lo.off_loss_sums = o; o += align_up((size_t)max_batch * sizeof(double));
     lo.off_scalars = o; o += kAlign;
     lo.online_bytes = online_exchange_bytes_bound(widths, L);
     lo.off_online = o; o += align_up(lo.online_bytes);
@@ -129,6 +130,7 @@ struct dn_net {
     float *D(int l) const { return (float *)(arena + lo.D[l]); }
     float *loss_rows() const { return (float *)(arena + lo.off_loss_rows); }
     float *hit_rows() const { return (float *)(arena + lo.off_hit_rows); }
+    double *loss_sums() const { return (double *)(arena + lo.off_loss_sums); }
     double *hit_acc() const { return (double *)(arena + lo.off_scalars + 16); }   // after epoch_acc and the abort flag
     double *epoch_acc() const { return (double *)(arena + lo.off_scalars); }
     int *abort_flag() const { return (int *)(arena + lo.off_scalars + sizeof(double)); }
@@ -650,6 +652,10 @@ dn_status dn_train_epoch(dn_net *net, const float *X_dev, const int32_t *labels_
         if (st != DN_OK) return st;
         persistent = true;
     }
+    // Launch-per-product path.  The epoch's loss is kept as one running sum per batch row, added
+    // to by the output kernel of each step, and reduced once after the last step.
+    const int rows_used = (int)(n_samples < batch ? n_samples : batch);
+    if (!persistent) DN_HIP(hipMemsetAsync(net->loss_sums(), 0, (size_t)rows_used * sizeof(double), net->stream));
     for (int64_t s0 = persistent ? n_samples : 0; s0 < n_samples; s0 += batch) {
         const int B = (int)((n_samples - s0) < batch ? (n_samples - s0) : batch);
         const float *Xb = X_dev + (size_t)s0 * net->n[0];
@@ -660,12 +666,12 @@ dn_status dn_train_epoch(dn_net *net, const float *X_dev, const int32_t *labels_
         {
             ScopedTimer t(net, DN_K_OUTPUT, timing);
             DN_HIP(launch_output_delta(net->A(L), net->D(L), labels_dev + s0, net->loss_rows(), B, net->n[L],
-                                       net->act[L], net->loss, OUT_FUSED, net->stream));
-            DN_HIP(launch_loss_reduce(net->loss_rows(), B, nullptr, net->epoch_acc(), net->stream));
+                                       net->act[L], net->loss, OUT_FUSED, net->stream, nullptr, net->loss_sums()));
         }
         st = run_backward(net, Xb, B, mode, lr, momentum, timing);
         if (st != DN_OK) return st;
     }
+    if (!persistent) DN_HIP(launch_loss_sums_reduce(net->loss_sums(), rows_used, net->epoch_acc(), net->stream));
     DN_HIP(hipEventRecord(net->ev_epoch1, net->stream));
     struct { double acc; int aborted; int pad; } res = {0.0, 0, 0};
     DN_HIP(hipMemcpyAsync(&res, net->epoch_acc(), sizeof(double) + sizeof(int), hipMemcpyDeviceToHost, net->stream));

@@ -74,12 +74,15 @@ enum OutPhase : int {
     OUT_EVAL = 3           // z (cross-entropy) or a (squared error) -> loss and hit flag, rows untouched (dn_evaluate)
 };
 // hit_rows (OUT_EVAL only): 1.0 where the row's largest output is at the label, else 0.0.
+// loss_sums (optional, phases that produce a loss): loss_sums[row] += the row's loss.
 hipError_t launch_output_delta(float *AL, float *DL, const int32_t *labels, float *loss_rows,
                                int B, int nL, int act, int loss, int phase, hipStream_t stream,
-                               float *hit_rows = nullptr);
+                               float *hit_rows = nullptr, double *loss_sums = nullptr);
 // Sum loss_rows[0..B): *loss_mean_out = sum / B (if non-null); *epoch_acc += sum (if non-null).
 hipError_t launch_loss_reduce(const float *loss_rows, int B, float *loss_mean_out,
                               double *epoch_acc, hipStream_t stream);
+// *epoch_acc += sum of loss_sums[0..B) (the per-row running sums of launch_output_delta).
+hipError_t launch_loss_sums_reduce(const double *loss_sums, int B, double *epoch_acc, hipStream_t stream);
 // Elementwise update of a parameter vector from a stored gradient (dn_update).
 hipError_t launch_update(float *p, float *v, const float *g, size_t count, float lr, float mu,
                          hipStream_t stream);

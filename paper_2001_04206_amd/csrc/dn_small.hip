@@ -54,10 +54,14 @@ __device__ __forceinline__ float deriv_from_output(int act, float a)
 // Phase OUT_SOFTMAX_ONLY does only z -> p (no labels needed); phase OUT_FROM_P starts from
 // a row that already holds p: Delta_L = p - y, loss = -log p_y.
 // Squared error: the row holds a = f(z); Delta_L = (a - y) f'(a), loss = 1/2 sum (a - y)^2.
+// With `loss_sums` the sample's loss is also added to loss_sums[s] (one running sum per batch
+// row, so no two workgroups touch the same word): an epoch then needs one reduction at its end
+// instead of one per step.
 __global__ __launch_bounds__(256) void output_delta_kernel(float *__restrict__ AL, float *__restrict__ DL,
                                                            const int32_t *__restrict__ labels,
                                                            float *__restrict__ loss_rows, int nL, int act,
-                                                           int loss, int phase, float *__restrict__ hit_rows)
+                                                           int loss, int phase, float *__restrict__ hit_rows,
+                                                           double *__restrict__ loss_sums)
 {
     __shared__ float red[4];
     const int s = blockIdx.x, tid = threadIdx.x;
@@ -110,7 +114,11 @@ __global__ __launch_bounds__(256) void output_delta_kernel(float *__restrict__ A
             a[o] = p;
             if (phase == OUT_FUSED) d[o] = p - (o == y ? 1.0f : 0.0f);
         }
-        if (phase == OUT_FUSED && tid == 0) loss_rows[s] = logf(sum) - (zy - m);
+        if (phase == OUT_FUSED && tid == 0) {
+            const float e = logf(sum) - (zy - m);
+            loss_rows[s] = e;
+            if (loss_sums) loss_sums[s] += (double)e;
+        }
     } else if (loss == DN_LOSS_CROSS_ENTROPY) {
         for (int o = tid; o < nL; o += 256) d[o] = a[o] - (o == y ? 1.0f : 0.0f);
         if (tid == 0) loss_rows[s] = -logf(fmaxf(a[y], 1e-37f));
@@ -122,11 +130,15 @@ __global__ __launch_bounds__(256) void output_delta_kernel(float *__restrict__ A
             d[o] = diff * deriv_from_output(act, a[o]);
         }
         e = block_sum(e, red);
-        if (tid == 0) loss_rows[s] = e;
+        if (tid == 0) {
+            loss_rows[s] = e;
+            if (loss_sums) loss_sums[s] += (double)e;
+        }
     }
 }
 
-__global__ __launch_bounds__(256) void loss_reduce_kernel(const float *__restrict__ loss_rows, int B,
+template <class In>
+__global__ __launch_bounds__(256) void loss_reduce_kernel(const In *__restrict__ loss_rows, int B,
                                                           float *__restrict__ mean_out,
                                                           double *__restrict__ epoch_acc)
 {
@@ -163,18 +175,26 @@ __global__ __launch_bounds__(256) void copy_kernel(float *__restrict__ dst, cons
 }
 
 hipError_t launch_output_delta(float *AL, float *DL, const int32_t *labels, float *loss_rows, int B,
-                               int nL, int act, int loss, int phase, hipStream_t stream, float *hit_rows)
+                               int nL, int act, int loss, int phase, hipStream_t stream, float *hit_rows,
+                               double *loss_sums)
 {
     if (phase == OUT_EVAL && !hit_rows) return hipErrorInvalidValue;
     hipLaunchKernelGGL(output_delta_kernel, dim3(B), dim3(256), 0, stream, AL, DL, labels, loss_rows, nL, act,
-                       loss, phase, hit_rows);
+                       loss, phase, hit_rows, loss_sums);
     return hipGetLastError();
 }
 
 hipError_t launch_loss_reduce(const float *loss_rows, int B, float *loss_mean_out, double *epoch_acc,
                               hipStream_t stream)
 {
-    hipLaunchKernelGGL(loss_reduce_kernel, dim3(1), dim3(256), 0, stream, loss_rows, B, loss_mean_out,
+    hipLaunchKernelGGL(loss_reduce_kernel<float>, dim3(1), dim3(256), 0, stream, loss_rows, B, loss_mean_out,
+                       epoch_acc);
+    return hipGetLastError();
+}
+
+hipError_t launch_loss_sums_reduce(const double *loss_sums, int B, double *epoch_acc, hipStream_t stream)
+{
+    hipLaunchKernelGGL(loss_reduce_kernel<double>, dim3(1), dim3(256), 0, stream, loss_sums, B, (float *)nullptr,
                        epoch_acc);
     return hipGetLastError();
 }

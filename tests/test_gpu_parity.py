@@ -88,7 +88,13 @@ def check_epochs(dn, w, n_samples, epochs=1, tol=EPOCH_TOL, steps_note=""):
     Wr, br = o.get_params()
     for l in range(net.L):
         assert_close(W[l], Wr[l], tol, "W_%d after %d epoch(s) %s (kink census %d)" % (l + 1, epochs, steps_note, kinks))
-        assert_close(b[l], br[l], tol, "b_%d after %d epoch(s) %s" % (l + 1, epochs, steps_note))
+        # A ReLU net input within rounding of zero may take the other value of the derivative on
+        # the two sides.  One such flip moves single elements of the upstream biases by about
+        # lr |dA| / B; the biases start at zero and are small, so measured against their largest
+        # element that can exceed tol, while the tensor as a whole (L2) stays within tol.
+        tol_max = 10 * tol if kinks > 0 else tol
+        assert_close(b[l], br[l], tol, "b_%d after %d epoch(s) %s (kink census %d)" % (l + 1, epochs, steps_note, kinks),
+                     tol_max=tol_max)
     net.close()
     return W, b
 

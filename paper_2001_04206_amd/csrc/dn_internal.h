@@ -83,6 +83,15 @@ hipError_t launch_loss_reduce(const float *loss_rows, int B, float *loss_mean_ou
                               double *epoch_acc, hipStream_t stream);
 // *epoch_acc += sum of loss_sums[0..B) (the per-row running sums of launch_output_delta).
 hipError_t launch_loss_sums_reduce(const double *loss_sums, int B, double *epoch_acc, hipStream_t stream);
+// Products of a layer with at most 16 outputs, without the matrix cores (same results as
+// launch_gemm's GEMM_DELTA / GEMM_GRAD for that layer, same fused stores and updates).
+bool narrow_layer(int n_out);
+// C[b][j] = f'(Aprev[b][j]) * sum_o D[b][o] W[o][j];  D [B][nl], W [nl][nin], Aprev and C [B][nin], all dense.
+hipError_t launch_narrow_delta(const float *D, const float *W, const float *Aprev, float *C, int B, int nl, int nin,
+                               int act, hipStream_t stream);
+// sum_b D[b][o] Aprev[b][j] into C / V [nl][nin] and the column sums of D into gb / vb, per GradMode.
+hipError_t launch_narrow_grad(const float *D, const float *Aprev, float *C, float *V, float *gb, float *vb, int B,
+                              int nl, int nin, int mode, float scale, float mu, hipStream_t stream);
 // Elementwise update of a parameter vector from a stored gradient (dn_update).
 hipError_t launch_update(float *p, float *v, const float *g, size_t count, float lr, float mu,
                          hipStream_t stream);

@@ -247,6 +247,173 @@ hipError_t launch_layer_backward(const float *deltas, const float *inputs, float
     return hipGetLastError();
 }
 
+// ---- layers with at most 16 outputs (the 10-class output layer of the benchmark nets) ----------
+// Their delta and gradient products have one side of at most 16: on 32- or 64-wide matrix-core
+// tiles most of the work would be padding, and a width that is not a multiple of four rules out
+// vector loads there.  These kernels use plain FMAs instead; both are bound by launch latency.
+constexpr int kNarrow = 16;
+
+// Delta_{l-1}[b][j] = f'(A_{l-1}[b][j]) * sum_o Delta_l[b][o] W_l[o][j] for n_l <= 16.
+// One thread per VEC adjacent columns j; it keeps its columns of W_l in registers and walks the
+// rows of its block's row range (row addresses are uniform, so Delta_l comes through scalar loads).
+template <int VEC>
+__global__ __launch_bounds__(256) void narrow_delta_kernel(const float *__restrict__ D, const float *__restrict__ W,
+                                                           const float *__restrict__ Aprev, float *__restrict__ C,
+                                                           int B, int nl, int nin, int act, int rows_per_block)
+{
+    const int j = (blockIdx.x * 256 + threadIdx.x) * VEC;
+    if (j >= nin) return;
+    typedef float vec_t __attribute__((ext_vector_type(VEC)));
+    vec_t w[kNarrow];
+#pragma unroll
+    for (int o = 0; o < kNarrow; ++o) {
+        w[o] = 0.f;
+        if (o < nl) w[o] = *reinterpret_cast<const vec_t *>(W + (size_t)o * nin + j);
+    }
+    const int b0 = blockIdx.y * rows_per_block;
+    const int b1 = min(B, b0 + rows_per_block);
+    for (int b = b0; b < b1; ++b) {
+        const float *d = D + (size_t)b * nl;
+        vec_t sum = 0.f;
+#pragma unroll
+        for (int o = 0; o < kNarrow; ++o) {
+            if (o < nl) {
+                const float dv = d[o];
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) sum[v] = fmaf(dv, w[o][v], sum[v]);
+            }
+        }
+        const size_t e = (size_t)b * nin + j;
+        const vec_t a = *reinterpret_cast<const vec_t *>(Aprev + e);
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) sum[v] *= deriv_from_output(act, a[v]);
+        *reinterpret_cast<vec_t *>(C + e) = sum;
+    }
+}
+
+// acc[o][j] = sum_b Delta_l[b][o] A_{l-1}[b][j] for n_l <= 16, then the same fused store / update
+// as the matrix-core gradient product.  The output is small (n_l x n_{l-1}) and the sum runs over
+// the batch, so the parallelism is taken from both: a workgroup owns VEC adjacent columns j, its
+// 256 threads take the rows b, b + 256, ... and the threads' partial sums are added in a fixed
+// order (lane butterfly, then the four waves).  A_{l-1} is read in 16-byte pieces, one row per
+// lane; it is small enough to come from the L2 for all but the first reader of a line.  One
+// extra workgroup (the last) does the bias: column sums of Delta_l.
+struct NarrowGradArgs {
+    const float *D, *Aprev;
+    float *C, *V, *gb, *vb;
+    int B, nl, nin, mode;
+    float scale, mu;
+};
+
+__device__ __forceinline__ void narrow_apply(int mode, float scale, float mu, float sum, float *c, float *v)
+{
+    if (mode == GRAD_STORE) {
+        *c = sum * scale;
+    } else if (mode == GRAD_SGD) {
+        *c = *c + (-scale * sum);
+    } else if (mode == GRAD_SGD_KEEPV) {
+        const float dw = -scale * sum;
+        *v = dw;
+        *c = *c + dw;
+    } else {
+        const float dw = mu * *v - scale * sum;
+        *v = dw;
+        *c = *c + dw;
+    }
+}
+
+template <int VEC>
+__global__ __launch_bounds__(256) void narrow_grad_kernel(NarrowGradArgs g)
+{
+    typedef float vec_t __attribute__((ext_vector_type(VEC)));
+    __shared__ float red[4][kNarrow * VEC];   // per wave: [o][column]
+    __shared__ float flat[256];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    if (blockIdx.x == gridDim.x - 1) {
+        // bias: thread (o, rg) adds rows rg, rg + 16, ... of column o; thread o then adds the 16 partials
+        const int o = tid % kNarrow, rg = tid / kNarrow;
+        float part = 0.f;
+        if (o < g.nl)
+            for (int b = rg; b < g.B; b += 256 / kNarrow) part += g.D[(size_t)b * g.nl + o];
+        flat[tid] = part;
+        __syncthreads();
+        if (tid < g.nl) {
+            float sum = 0.f;
+            for (int k = 0; k < 256 / kNarrow; ++k) sum += flat[k * kNarrow + tid];
+            narrow_apply(g.mode, g.scale, g.mu, sum, g.gb + tid, g.vb + tid);
+        }
+        return;
+    }
+    const int j = blockIdx.x * VEC;   // the grid has one workgroup per column group
+    float acc[kNarrow][VEC];
+#pragma unroll
+    for (int o = 0; o < kNarrow; ++o)
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) acc[o][v] = 0.f;
+    for (int b = tid; b < g.B; b += 256) {
+        const vec_t a = *reinterpret_cast<const vec_t *>(g.Aprev + (size_t)b * g.nin + j);
+        const float *d = g.D + (size_t)b * g.nl;
+#pragma unroll
+        for (int o = 0; o < kNarrow; ++o) {
+            if (o < g.nl) {
+                const float dv = d[o];
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) acc[o][v] = fmaf(dv, a[v], acc[o][v]);
+            }
+        }
+    }
+#pragma unroll
+    for (int o = 0; o < kNarrow; ++o)
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+#pragma unroll
+            for (int off = 1; off < 64; off *= 2) acc[o][v] += __shfl_xor(acc[o][v], off, 64);
+            if (lane == 0) red[wave][o * VEC + v] = acc[o][v];
+        }
+    __syncthreads();
+    if (tid < g.nl * VEC) {
+        const int o = tid / VEC, v = tid % VEC;
+        const float sum = (red[0][tid] + red[1][tid]) + (red[2][tid] + red[3][tid]);
+        const size_t at = (size_t)o * g.nin + j + v;
+        narrow_apply(g.mode, g.scale, g.mu, sum, g.C + at, g.V + at);
+    }
+}
+
+bool narrow_layer(int n_out) { return n_out >= 1 && n_out <= kNarrow; }
+
+hipError_t launch_narrow_delta(const float *D, const float *W, const float *Aprev, float *C, int B, int nl, int nin,
+                               int act, hipStream_t stream)
+{
+    if (!narrow_layer(nl) || B < 1 || nin < 1) return hipErrorInvalidValue;
+    const bool vec = nin % 4 == 0 && ((reinterpret_cast<uintptr_t>(W) | reinterpret_cast<uintptr_t>(Aprev) |
+                                        reinterpret_cast<uintptr_t>(C)) & 15) == 0;
+    const int groups = vec ? nin / 4 : nin;
+    const unsigned gx = (unsigned)((groups + 255) / 256);
+    int rows = (int)(((long)B * gx + 511) / 512);   // about 512 workgroups
+    if (rows < 4) rows = 4;
+    const unsigned gy = (unsigned)((B + rows - 1) / rows);
+    if (vec)
+        hipLaunchKernelGGL(narrow_delta_kernel<4>, dim3(gx, gy), dim3(256), 0, stream, D, W, Aprev, C, B, nl, nin, act, rows);
+    else
+        hipLaunchKernelGGL(narrow_delta_kernel<1>, dim3(gx, gy), dim3(256), 0, stream, D, W, Aprev, C, B, nl, nin, act, rows);
+    return hipGetLastError();
+}
+
+hipError_t launch_narrow_grad(const float *D, const float *Aprev, float *C, float *V, float *gb, float *vb, int B,
+                              int nl, int nin, int mode, float scale, float mu, hipStream_t stream)
+{
+    if (!narrow_layer(nl) || B < 1 || nin < 1) return hipErrorInvalidValue;
+    const bool vec = nin % 4 == 0 && ((reinterpret_cast<uintptr_t>(Aprev) | reinterpret_cast<uintptr_t>(C) |
+                                        reinterpret_cast<uintptr_t>(V)) & 15) == 0;
+    NarrowGradArgs g{D, Aprev, C, V, gb, vb, B, nl, nin, mode, scale, mu};
+    const unsigned grid = (unsigned)(vec ? nin / 4 : nin) + 1;
+    if (vec)
+        hipLaunchKernelGGL(narrow_grad_kernel<4>, dim3(grid), dim3(256), 0, stream, g);
+    else
+        hipLaunchKernelGGL(narrow_grad_kernel<1>, dim3(grid), dim3(256), 0, stream, g);
+    return hipGetLastError();
+}
+
 static unsigned grid_for(size_t count)
 {
     size_t g = (count + 255) / 256;

@@ -146,6 +146,36 @@ def test_one_step_split_k(dnlib, widths, acts, loss, B, variant, split_k):
     check_one_step(dnlib, w, B, lr=0.05, mu=0.9, variant=variant, split_k=split_k)
 
 
+NARROW_CASES = [
+    # layers of at most 16 outputs take plain-FMA kernels for their delta product and, from batch
+    # 512, for their gradient: vector (width % 4 == 0) and scalar paths, ragged batches
+    ([64, 128, 10], [TANH, SOFTMAX], CE, 512),
+    ([33, 70, 5], [RELU, LIN], MSE, 515),
+    ([40, 16, 16], [SIG, SIG], MSE, 777),          # both layers narrow
+    ([130, 67, 3], [TANH, SOFTMAX], CE, 1030),     # scalar path, several rows per thread
+]
+
+
+@pytest.mark.parametrize("widths,acts,loss,B", NARROW_CASES)
+def test_one_step_narrow_layers(dnlib, widths, acts, loss, B):
+    announce("one_step_narrow widths=%s acts=%s loss=%d B=%d" % (widths, acts, loss, B))
+    w = synth.make("narrow", widths, acts, loss, n_samples=2 * B, features="normal",
+                   init="xavier_uniform", batch=B, lr=0.1, momentum=0.9, seed=11)
+    rng = np.random.default_rng(13)
+    w.b = [rng.standard_normal(n).astype(np.float32) * 0.1 for n in widths[1:]]
+    check_one_step(dnlib, w, B, lr=0.1, mu=0.9)
+
+
+@pytest.mark.parametrize("momentum", [0.0, 0.9])
+def test_epoch_narrow_layers(dnlib, momentum):
+    # fused update modes of the narrow gradient kernel: plain steps, the last step that leaves
+    # the velocity behind, and momentum; short last batch
+    announce("epoch narrow 48-96-10 B=600 momentum=%g" % momentum)
+    w = synth.make("narrow_epoch", [48, 96, 10], [TANH, SOFTMAX], CE, n_samples=2000, features="normal",
+                   init="xavier_uniform", batch=600, lr=0.1, momentum=momentum, seed=17)
+    check_epochs(dnlib, w, 2000, epochs=2)
+
+
 def test_split_k_is_bitwise_reproducible(dnlib):
     announce("determinism: k split across workgroups, two runs")
     w = synth.tanh_sweep(32, n_samples=256)

@@ -187,9 +187,10 @@ struct ScopedTimer {
 
 // Forward pass of one batch; leaves A_1..A_L in the arena.  The softmax layer's
 // row normalisation is left to the caller (it is fused with the loss in training).
-dn_status run_forward(dn_net *net, const float *X, int B, bool timing)
+dn_status run_forward(dn_net *net, const float *X, int B, bool timing, int last_layer = -1)
 {
-    for (int l = 1; l <= net->L; ++l) {
+    if (last_layer < 0) last_layer = net->L;
+    for (int l = 1; l <= last_layer; ++l) {
         GemmArgs g{};
         g.A = (l == 1) ? X : net->A(l - 1);
         g.lda = net->n[l - 1];
@@ -661,12 +662,19 @@ dn_status dn_train_epoch(dn_net *net, const float *X_dev, const int32_t *labels_
         const float *Xb = X_dev + (size_t)s0 * net->n[0];
         const bool last = s0 + batch >= n_samples;
         const int mode = (momentum != 0.f) ? GRAD_MOMENTUM : (last ? GRAD_SGD_KEEPV : GRAD_SGD);
-        dn_status st = run_forward(net, Xb, B, timing);
+        // a last layer of at most 16 outputs: its forward product and the output error in one launch
+        const bool fused_out = net->gemm_variant < 0 && narrow_layer(net->n[L]);
+        dn_status st = run_forward(net, Xb, B, timing, fused_out ? L - 1 : L);
         if (st != DN_OK) return st;
         {
             ScopedTimer t(net, DN_K_OUTPUT, timing);
-            DN_HIP(launch_output_delta(net->A(L), net->D(L), labels_dev + s0, net->loss_rows(), B, net->n[L],
-                                       net->act[L], net->loss, OUT_FUSED, net->stream, nullptr, net->loss_sums()));
+            if (fused_out)
+                DN_HIP(launch_narrow_output(L == 1 ? Xb : net->A(L - 1), net->W(L), net->b(L), labels_dev + s0, net->A(L),
+                                            net->D(L), net->loss_rows(), net->loss_sums(), B, net->n[L], net->n[L - 1],
+                                            net->act[L], net->loss, net->stream));
+            else
+                DN_HIP(launch_output_delta(net->A(L), net->D(L), labels_dev + s0, net->loss_rows(), B, net->n[L],
+                                           net->act[L], net->loss, OUT_FUSED, net->stream, nullptr, net->loss_sums()));
         }
         st = run_backward(net, Xb, B, mode, lr, momentum, timing);
         if (st != DN_OK) return st;

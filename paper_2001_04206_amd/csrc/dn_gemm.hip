@@ -741,9 +741,7 @@ hipError_t launch_gemm(GemmKind kind, const GemmArgs &a, int variant, hipStream_
         // a layer with at most 16 outputs (dense operands): plain-FMA kernels, no tiles to pad
         if (kind == GEMM_DELTA && narrow_layer(a.K) && a.lda == a.K && a.ldb == a.N && a.ldc == a.N)
             return launch_narrow_delta(a.A, a.B, a.aux, a.C, a.M, a.K, a.N, a.act, stream);
-        // (the gradient only from batch 512: below that its butterfly costs more than the padding,
-        // 16 us against 11 us at batch 128; at batch 2048 it is 28 us against 73 us)
-        if (kind == GEMM_GRAD && narrow_layer(a.M) && a.K >= 512 && a.lda == a.M && a.ldb == a.N && a.ldc == a.N)
+        if (kind == GEMM_GRAD && narrow_layer(a.M) && a.lda == a.M && a.ldb == a.N && a.ldc == a.N)
             return launch_narrow_grad(a.A, a.B, a.C, a.V, a.gb, a.vb, a.K, a.M, a.N, a.mode, a.scale, a.mu, stream);
         variant = pick_variant(kind, a);
     }

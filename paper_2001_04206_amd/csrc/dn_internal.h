@@ -92,6 +92,11 @@ hipError_t launch_narrow_delta(const float *D, const float *W, const float *Apre
 // sum_b D[b][o] Aprev[b][j] into C / V [nl][nin] and the column sums of D into gb / vb, per GradMode.
 hipError_t launch_narrow_grad(const float *D, const float *Aprev, float *C, float *V, float *gb, float *vb, int B,
                               int nl, int nin, int mode, float scale, float mu, hipStream_t stream);
+// Last layer with at most 16 outputs, training step: forward product, then softmax / loss / Delta_L as
+// launch_output_delta's phase OUT_FUSED, in one launch.  Aprev [B][nin], W [nl][nin], AL and DL [B][nl].
+hipError_t launch_narrow_output(const float *Aprev, const float *W, const float *bias, const int32_t *labels,
+                                float *AL, float *DL, float *loss_rows, double *loss_sums, int B, int nl, int nin,
+                                int act, int loss, hipStream_t stream);
 // Elementwise update of a parameter vector from a stored gradient (dn_update).
 hipError_t launch_update(float *p, float *v, const float *g, size_t count, float lr, float mu,
                          hipStream_t stream);

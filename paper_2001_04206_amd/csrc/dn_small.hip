@@ -2,22 +2,9 @@
 // (softmax, loss, Delta_L), loss reduction, and the elementwise parameter
 // update used by dn_update.
 #include "dn_internal.h"
+#include "dn_wave.h"
 
 namespace dn {
-
-__device__ __forceinline__ float wave_sum(float v)
-{
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
-    return v;
-}
-
-__device__ __forceinline__ float wave_max(float v)
-{
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-    return v;
-}
 
 // Block-wide reductions over 256 threads (4 waves); every thread gets the result.
 __device__ __forceinline__ float block_sum(float v, float *red)
@@ -36,6 +23,16 @@ __device__ __forceinline__ float block_max(float v, float *red)
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
     __syncthreads();
     return fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+}
+
+__device__ __forceinline__ float activate(int act, float z)
+{
+    switch (act) {
+    case DN_ACT_SIGMOID: return 1.0f / (1.0f + expf(-z));
+    case DN_ACT_TANH: return tanhf(z);
+    case DN_ACT_RELU: return z > 0.0f ? z : 0.0f;
+    default: return z;
+    }
 }
 
 __device__ __forceinline__ float deriv_from_output(int act, float a)
@@ -327,19 +324,26 @@ __global__ __launch_bounds__(256) void narrow_grad_kernel(NarrowGradArgs g)
 {
     typedef float vec_t __attribute__((ext_vector_type(VEC)));
     __shared__ float red[4][kNarrow * VEC];   // per wave: [o][column]
-    __shared__ float flat[256];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     if (blockIdx.x == gridDim.x - 1) {
-        // bias: thread (o, rg) adds rows rg, rg + 16, ... of column o; thread o then adds the 16 partials
-        const int o = tid % kNarrow, rg = tid / kNarrow;
-        float part = 0.f;
-        if (o < g.nl)
-            for (int b = rg; b < g.B; b += 256 / kNarrow) part += g.D[(size_t)b * g.nl + o];
-        flat[tid] = part;
+        // bias: the same sum with 1 in the place of A_{l-1}
+        float part[kNarrow];
+#pragma unroll
+        for (int o = 0; o < kNarrow; ++o) part[o] = 0.f;
+        for (int b = tid; b < g.B; b += 256) {
+            const float *d = g.D + (size_t)b * g.nl;
+#pragma unroll
+            for (int o = 0; o < kNarrow; ++o)
+                if (o < g.nl) part[o] += d[o];
+        }
+#pragma unroll
+        for (int o = 0; o < kNarrow; ++o) {
+            const float total = wave_sum(part[o]);
+            if (lane == 0) red[wave][o] = total;
+        }
         __syncthreads();
         if (tid < g.nl) {
-            float sum = 0.f;
-            for (int k = 0; k < 256 / kNarrow; ++k) sum += flat[k * kNarrow + tid];
+            const float sum = (red[0][tid] + red[1][tid]) + (red[2][tid] + red[3][tid]);
             narrow_apply(g.mode, g.scale, g.mu, sum, g.gb + tid, g.vb + tid);
         }
         return;
@@ -366,9 +370,8 @@ __global__ __launch_bounds__(256) void narrow_grad_kernel(NarrowGradArgs g)
     for (int o = 0; o < kNarrow; ++o)
 #pragma unroll
         for (int v = 0; v < VEC; ++v) {
-#pragma unroll
-            for (int off = 1; off < 64; off *= 2) acc[o][v] += __shfl_xor(acc[o][v], off, 64);
-            if (lane == 0) red[wave][o * VEC + v] = acc[o][v];
+            const float total = wave_sum(acc[o][v]);
+            if (lane == 0) red[wave][o * VEC + v] = total;
         }
     __syncthreads();
     if (tid < g.nl * VEC) {
@@ -380,6 +383,138 @@ __global__ __launch_bounds__(256) void narrow_grad_kernel(NarrowGradArgs g)
 }
 
 bool narrow_layer(int n_out) { return n_out >= 1 && n_out <= kNarrow; }
+
+// Forward pass and output error of a last layer with at most 16 outputs in one launch:
+// z = A_{L-1} W_L^T + b_L, then what output_delta_kernel's phase OUT_FUSED does with the row
+// (softmax, loss, Delta_L; or activation, loss, Delta_L for squared error).  A workgroup takes R
+// rows of the batch; its 256 threads split k (each W_L element a lane loads serves R rows), the
+// R * n_L dot products are summed across each wave and then across the four waves through LDS,
+// and wave w finishes rows w, w + 4, ... with every lane holding the row's z.
+struct NarrowOutArgs {
+    const float *Aprev, *W, *bias;
+    const int32_t *labels;
+    float *AL, *DL, *loss_rows;
+    double *loss_sums;
+    int B, nl, nin, act, loss;
+};
+
+template <int R, int VEC>
+__global__ __launch_bounds__(256) void narrow_output_kernel(NarrowOutArgs g)
+{
+    typedef float vec_t __attribute__((ext_vector_type(VEC)));
+    __shared__ float part[4][R][kNarrow];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int row0 = blockIdx.x * R;
+    // what the last phase needs, requested before the k loop so that it is there by then
+    const float my_bias = lane < g.nl ? g.bias[lane] : 0.f;
+    int label[(R + 3) / 4];
+#pragma unroll
+    for (int i = 0; i < (R + 3) / 4; ++i) label[i] = g.labels[min(row0 + wave + 4 * i, g.B - 1)];
+    float acc[R][kNarrow];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int o = 0; o < kNarrow; ++o) acc[r][o] = 0.f;
+    for (int k = threadIdx.x * VEC; k < g.nin; k += 256 * VEC) {
+        vec_t a[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r)   // rows past the batch repeat the last row; their results are dropped
+            a[r] = *reinterpret_cast<const vec_t *>(g.Aprev + (size_t)min(row0 + r, g.B - 1) * g.nin + k);
+#pragma unroll
+        for (int o = 0; o < kNarrow; ++o) {
+            if (o < g.nl) {
+                const vec_t w = *reinterpret_cast<const vec_t *>(g.W + (size_t)o * g.nin + k);
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) acc[r][o] = fmaf(a[r][v], w[v], acc[r][o]);
+            }
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int o = 0; o < kNarrow; ++o) {
+            const float total = (o < g.nl) ? wave_sum(acc[r][o]) : 0.f;
+            if (lane == 0) part[wave][r][o] = total;
+        }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < (R + 3) / 4; ++i) {
+        const int r = wave + 4 * i;
+        const int row = row0 + r;
+        if (r >= R || row >= g.B) continue;
+        float z[kNarrow];
+#pragma unroll
+        for (int o = 0; o < kNarrow; ++o) {
+            const float b = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, my_bias), o));
+            z[o] = ((part[0][r][o] + part[1][r][o]) + (part[2][r][o] + part[3][r][o])) + b;
+        }
+        int y = label[i];
+        y = y < 0 ? 0 : (y >= g.nl ? g.nl - 1 : y);
+        float mine = 0.f, e;   // lane o keeps output o
+        if (g.loss == DN_LOSS_CROSS_ENTROPY) {
+            float m = -INFINITY, zy = 0.f;
+#pragma unroll
+            for (int o = 0; o < kNarrow; ++o)
+                if (o < g.nl) {
+                    m = fmaxf(m, z[o]);
+                    zy = (o == y) ? z[o] : zy;
+                }
+            float sum = 0.f;
+#pragma unroll
+            for (int o = 0; o < kNarrow; ++o)
+                if (o < g.nl) {
+                    z[o] = expf(z[o] - m);
+                    sum += z[o];
+                }
+            const float inv = 1.0f / sum;
+#pragma unroll
+            for (int o = 0; o < kNarrow; ++o) mine = (o == lane) ? z[o] * inv : mine;
+            e = logf(sum) - (zy - m);
+            if (lane < g.nl) {
+                g.AL[(size_t)row * g.nl + lane] = mine;
+                g.DL[(size_t)row * g.nl + lane] = mine - (lane == y ? 1.0f : 0.0f);
+            }
+        } else {
+            e = 0.f;
+#pragma unroll
+            for (int o = 0; o < kNarrow; ++o)
+                if (o < g.nl) {
+                    const float a = activate(g.act, z[o]);
+                    const float diff = a - (o == y ? 1.0f : 0.0f);
+                    e += 0.5f * diff * diff;
+                    mine = (o == lane) ? a : mine;
+                }
+            if (lane < g.nl) {
+                const float diff = mine - (lane == y ? 1.0f : 0.0f);
+                g.AL[(size_t)row * g.nl + lane] = mine;
+                g.DL[(size_t)row * g.nl + lane] = diff * deriv_from_output(g.act, mine);
+            }
+        }
+        if (lane == 0) {
+            g.loss_rows[row] = e;
+            if (g.loss_sums) g.loss_sums[row] += (double)e;
+        }
+    }
+}
+
+hipError_t launch_narrow_output(const float *Aprev, const float *W, const float *bias, const int32_t *labels,
+                                float *AL, float *DL, float *loss_rows, double *loss_sums, int B, int nl, int nin,
+                                int act, int loss, hipStream_t stream)
+{
+    if (!narrow_layer(nl) || B < 1 || nin < 1) return hipErrorInvalidValue;
+    const bool vec = nin % 4 == 0 && ((reinterpret_cast<uintptr_t>(Aprev) | reinterpret_cast<uintptr_t>(W)) & 15) == 0;
+    NarrowOutArgs g{Aprev, W, bias, labels, AL, DL, loss_rows, loss_sums, B, nl, nin, act, loss};
+    const int R = B > 1024 ? 4 : 1;
+    const unsigned grid = (unsigned)((B + R - 1) / R);
+    if (R == 4 && vec) hipLaunchKernelGGL((narrow_output_kernel<4, 4>), dim3(grid), dim3(256), 0, stream, g);
+    else if (R == 4) hipLaunchKernelGGL((narrow_output_kernel<4, 1>), dim3(grid), dim3(256), 0, stream, g);
+    else if (vec) hipLaunchKernelGGL((narrow_output_kernel<1, 4>), dim3(grid), dim3(256), 0, stream, g);
+    else hipLaunchKernelGGL((narrow_output_kernel<1, 1>), dim3(grid), dim3(256), 0, stream, g);
+    return hipGetLastError();
+}
+
 
 hipError_t launch_narrow_delta(const float *D, const float *W, const float *Aprev, float *C, int B, int nl, int nin,
                                int act, hipStream_t stream)

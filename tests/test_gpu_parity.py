@@ -147,8 +147,8 @@ def test_one_step_split_k(dnlib, widths, acts, loss, B, variant, split_k):
 
 
 NARROW_CASES = [
-    # layers of at most 16 outputs take plain-FMA kernels for their delta product and, from batch
-    # 512, for their gradient: vector (width % 4 == 0) and scalar paths, ragged batches
+    # layers of at most 16 outputs take plain-FMA kernels for their delta and gradient products:
+    # vector (width % 4 == 0) and scalar paths, batches beyond one row per thread, ragged
     ([64, 128, 10], [TANH, SOFTMAX], CE, 512),
     ([33, 70, 5], [RELU, LIN], MSE, 515),
     ([40, 16, 16], [SIG, SIG], MSE, 777),          # both layers narrow
@@ -166,14 +166,37 @@ def test_one_step_narrow_layers(dnlib, widths, acts, loss, B):
     check_one_step(dnlib, w, B, lr=0.1, mu=0.9)
 
 
-@pytest.mark.parametrize("momentum", [0.0, 0.9])
-def test_epoch_narrow_layers(dnlib, momentum):
-    # fused update modes of the narrow gradient kernel: plain steps, the last step that leaves
-    # the velocity behind, and momentum; short last batch
-    announce("epoch narrow 48-96-10 B=600 momentum=%g" % momentum)
-    w = synth.make("narrow_epoch", [48, 96, 10], [TANH, SOFTMAX], CE, n_samples=2000, features="normal",
-                   init="xavier_uniform", batch=600, lr=0.1, momentum=momentum, seed=17)
-    check_epochs(dnlib, w, 2000, epochs=2)
+NARROW_EPOCHS = [
+    # widths, acts, loss, batch, samples, momentum: training steps through the fused forward + output
+    # kernel of a narrow last layer and the fused update modes of the narrow gradient kernel
+    # (plain steps, the last step that leaves the velocity behind, momentum), short last batches
+    ([48, 96, 10], [TANH, SOFTMAX], CE, 600, 2000, 0.0),
+    ([48, 96, 10], [TANH, SOFTMAX], CE, 600, 2000, 0.9),
+    ([30, 50, 7], [RELU, SIG], MSE, 64, 300, 0.9),            # squared error, several rows per workgroup
+    ([21, 33, 16], [TANH, TANH], MSE, 1100, 2500, 0.0),       # four rows per wave, scalar loads
+    ([24, 5], [SOFTMAX], CE, 1500, 4000, 0.9),                # single layer: the input is the batch itself
+]
+
+
+@pytest.mark.parametrize("widths,acts,loss,batch,n,momentum", NARROW_EPOCHS)
+def test_epoch_narrow_layers(dnlib, widths, acts, loss, batch, n, momentum):
+    announce("epoch narrow widths=%s loss=%d B=%d n=%d momentum=%g" % (widths, loss, batch, n, momentum))
+    w = synth.make("narrow_epoch", widths, acts, loss, n_samples=n, features="normal",
+                   init="xavier_uniform", batch=batch, lr=0.05, momentum=momentum, seed=17)
+    net, o = make_pair(dnlib, w, w.batch)
+    net.dn_set_option("batch_mode", 1)      # one launch per product, not the persistent kernels
+    X, y = to_dev(w)
+    for e in range(2):
+        got = net.dn_train_epoch(X, y, w.batch, w.lr, w.momentum)
+        ref, kinks = o.train_epoch(w.X, w.labels, w.batch, w.lr, w.momentum, kink_eps=1e-5)
+        assert abs(got - ref) <= EPOCH_TOL * abs(ref), "epoch %d loss %r vs %r" % (e, got, ref)
+    W, b = net.get_all()
+    Wr, br = o.get_params()
+    for l in range(net.L):
+        assert_close(W[l], Wr[l], EPOCH_TOL, "W_%d (kink census %d)" % (l + 1, kinks))
+        assert_close(b[l], br[l], EPOCH_TOL, "b_%d (kink census %d)" % (l + 1, kinks),
+                     tol_max=10 * EPOCH_TOL if kinks > 0 else EPOCH_TOL)
+    net.close()
 
 
 def test_split_k_is_bitwise_reproducible(dnlib):

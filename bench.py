@@ -48,6 +48,11 @@ def step_costs(widths, batch, momentum):
         "delta": 2.0 * batch * (pw - widths[1] * widths[0]),
         "grad_update": 2.0 * batch * pw,
     }
+    if widths[-1] <= 16:
+        # a last layer of at most 16 outputs: its forward product runs inside the output-error launch
+        last = 2.0 * batch * widths[-1] * widths[-2]
+        flops["forward"] -= last
+        flops["output"] = last
     # weights: forward read + backward read + write (+ velocity read + write);
     # activations / deltas: written once, read by the next product and by the gradient
     per_param = 20.0 if momentum != 0.0 else 12.0
@@ -229,7 +234,7 @@ def main():
             if "online" in classes:          # one persistent launch covers the whole pass
                 timed_steps = last_steps
             else:                            # per-launch events stop after a fixed number of launches
-                timed_steps = min(last_steps, classes["forward"]["launches"] // (len(w.widths) - 1))
+                timed_steps = min(last_steps, classes["output"]["launches"])   # one output-error launch per step
             if total_ms > 0:
                 ach = step_bytes * timed_steps / (total_ms * 1e-3) / 1e9
                 roofline = {"bound": "hbm", "kernel": ("online_epoch_kernel" if B == 1 else "batch_epoch_kernel") if "online" in classes

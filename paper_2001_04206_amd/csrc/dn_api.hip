@@ -303,7 +303,8 @@ bool batch_pays(const dn_net *net, int batch)
 // the batch past the L2 in every phase: it pays while those matrices are small.
 bool deep_pays(const dn_net *net, int batch)
 {
-    return batch <= 32;
+    (void)net;
+    return batch <= 24;   // 1024-1024-1024-1024-10: 74 against 100 us/step at batch 16, 104 against 101 at batch 32
 }
 
 // A whole minibatch epoch of a one- or two-layer net in persistent-kernel launches.

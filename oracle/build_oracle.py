@@ -1,6 +1,6 @@
-"""Compile the CPU checker (oracle/dn_oracle.c) into oracle/libdn_oracle.so.
+"""Compile the CPU checker (oracle/dn_oracle.c, oracle/dn_conv_oracle.c) into oracle/libdn_oracle.so.
 
-The C file is built twice into one shared object: once with fp32 storage and
+Each C file is built twice into one shared object: once with fp32 storage and
 fp64 accumulation (symbols o32_*), once all-fp64 (symbols o64_*).  Flags avoid
 -march=native and fused contraction so the library gives the same bits on any
 x86-64-v3 host.  Test infrastructure only.
@@ -13,22 +13,23 @@ import sys
 import tempfile
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SRC = os.path.join(HERE, "dn_oracle.c")
+SRCS = [os.path.join(HERE, "dn_oracle.c"), os.path.join(HERE, "dn_conv_oracle.c")]
 LIB = os.path.join(HERE, "libdn_oracle.so")
 CFLAGS = ["-O3", "-march=x86-64-v3", "-ffp-contract=off", "-fopenmp", "-fPIC", "-std=c11",
           "-Wall", "-Wextra"]
 
 
 def build(force: bool = True) -> str:
-    if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= os.path.getmtime(SRC):
+    if not force and os.path.exists(LIB) and all(os.path.getmtime(LIB) >= os.path.getmtime(s) for s in SRCS):
         return LIB
     with tempfile.TemporaryDirectory() as tmp:
         objs = []
-        for store, pfx in (("float", "o32_"), ("double", "o64_")):
-            obj = os.path.join(tmp, pfx + "oracle.o")
-            cmd = ["gcc", *CFLAGS, "-DSTORE_T=" + store, "-DPFX(x)=" + pfx + "##x", "-c", SRC, "-o", obj]
-            subprocess.run(cmd, check=True)
-            objs.append(obj)
+        for src in SRCS:
+            for store, pfx in (("float", "o32_"), ("double", "o64_")):
+                obj = os.path.join(tmp, pfx + os.path.basename(src) + ".o")
+                cmd = ["gcc", *CFLAGS, "-DSTORE_T=" + store, "-DPFX(x)=" + pfx + "##x", "-c", src, "-o", obj]
+                subprocess.run(cmd, check=True)
+                objs.append(obj)
         subprocess.run(["gcc", "-shared", "-fopenmp", "-o", LIB, *objs, "-lm"], check=True)
     return LIB
 

@@ -222,6 +222,48 @@ dn_status dn_layer_backward_host(const float *deltas_host, const float *inputs_h
                                  size_t workspace_bytes, void *hip_stream, float *ms_copy_in, float *ms_kernel,
                                  float *ms_copy_out);
 
+/* ---- convolutional and maximum-pooling layers ---------------------------------
+ * The two remaining layer types of the engine ("Deep Netts Deep Learning
+ * Engine": fully connected, convolutional, maximum pooling, softmax output), which
+ * the paper leaves on the CPU and names as the next to accelerate ("Summary").  It
+ * gives no formulas for them; these are the usual definitions:
+ *   images [batch][channel][row][column] (row-major, dense), filters
+ *   [c_out][c_in][kh][kw], zero padding `pad` on all four sides, one stride for
+ *   both directions, the filter applied without flipping:
+ *     y[b][o][i][j] = f(bias[o] + sum_{c,u,v} W[o][c][u][v] x[b][c][i*stride+u-pad][j*stride+v-pad])
+ *   with h_out = (h + 2 pad - kh) / stride + 1 (rounded down), w_out alike.
+ *   Backward, from dA = dE/dy of every sample: delta = dA * f'(y) (f' from the stored
+ *   output), dW and dbias = means over the batch of the per-sample gradients (as for
+ *   the dense layers), dX = dE/dx per sample.
+ *   Pooling: window k x k, stride s, no padding, h_out = (h - k) / s + 1; backward
+ *   adds dY to the position of each window's maximum (the first in row-major window
+ *   order among equals); windows may overlap.
+ * These calls are stateless: every pointer is device memory owned by the caller, work
+ * is enqueued on `hip_stream` (NULL = default stream) and nothing is synchronised.
+ * All tensors fp32.
+ * Errors: NULL pointers (dX_dev may be NULL: then no input gradient is computed),
+ * sizes < 1, kh or kw > 7, pad >= kh or kw, an empty output, or more than 2^31 - 1
+ * elements in a tensor -> DN_ERR_INVALID_ARG; softmax as activation ->
+ * DN_ERR_UNSUPPORTED; launch failures -> DN_ERR_DEVICE.
+ */
+dn_status dn_conv_forward(const float *X_dev, const float *W_dev, const float *bias_dev, float *Y_dev,
+                          int32_t batch, int32_t c_in, int32_t h, int32_t w, int32_t c_out, int32_t kh,
+                          int32_t kw, int32_t stride, int32_t pad, dn_act act, void *hip_stream);
+/* delta_dev [batch][c_out][h_out][w_out] is written (the layer's error term, also
+ * the workspace of the other outputs); dW_dev [c_out][c_in][kh][kw], dbias_dev [c_out],
+ * dX_dev [batch][c_in][h][w] or NULL.  Sums are taken in a fixed order: results
+ * are bitwise reproducible. */
+dn_status dn_conv_backward(const float *X_dev, const float *W_dev, const float *Y_dev, const float *dA_dev,
+                           float *delta_dev, float *dX_dev, float *dW_dev, float *dbias_dev, int32_t batch,
+                           int32_t c_in, int32_t h, int32_t w, int32_t c_out, int32_t kh, int32_t kw,
+                           int32_t stride, int32_t pad, dn_act act, void *hip_stream);
+dn_status dn_maxpool_forward(const float *X_dev, float *Y_dev, int32_t batch, int32_t channels, int32_t h,
+                             int32_t w, int32_t k, int32_t stride, void *hip_stream);
+/* dX_dev [batch][channels][h][w] is overwritten (not accumulated into). */
+dn_status dn_maxpool_backward(const float *X_dev, const float *dY_dev, float *dX_dev, int32_t batch,
+                              int32_t channels, int32_t h, int32_t w, int32_t k, int32_t stride,
+                              void *hip_stream);
+
 /*
  * Measurement hooks (the paper times its two offloaded methods with wall-clock
  * timers, section "Experimental Evaluation"; here the device itself is timed).

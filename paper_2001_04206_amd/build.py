@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdn.so")
-SOURCES = ["dn_api.hip", "dn_gemm.hip", "dn_small.hip", "dn_online.hip"]
+SOURCES = ["dn_api.hip", "dn_gemm.hip", "dn_small.hip", "dn_online.hip", "dn_conv.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # keep the compiler from forming packed fp32 instructions

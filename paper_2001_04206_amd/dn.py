@@ -27,6 +27,7 @@ EXPORTS = [
     "dn_get_params", "dn_get_grads", "dn_forward", "dn_backward", "dn_update", "dn_train_epoch",
     "dn_train", "dn_evaluate", "dn_layer_backward_workspace_bytes", "dn_layer_backward_host",
     "dn_last_epoch_ms", "dn_kernel_time", "dn_set_option",
+    "dn_conv_forward", "dn_conv_backward", "dn_maxpool_forward", "dn_maxpool_backward",
 ]
 
 _lib = None
@@ -139,6 +140,81 @@ def dn_layer_backward_host(deltas, inputs, learning_rate: float, gradients, delt
             int(workspace.numel()), C.c_void_p(stream.cuda_stream), C.byref(t[0]), C.byref(t[1]), C.byref(t[2]))
     _check(st, "dn_layer_backward_host")
     return t[0].value, t[1].value, t[2].value
+
+
+def _shape_check(t, shape, what):
+    if tuple(t.shape) != tuple(shape):
+        raise TypeError("%s must have shape %s, not %s" % (what, tuple(shape), tuple(t.shape)))
+
+
+def conv_out_size(n: int, k: int, stride: int, pad: int) -> int:
+    return (n + 2 * pad - k) // stride + 1
+
+
+def dn_conv_forward(X, W, bias, Y, stride: int, pad: int, act: int):
+    """Y = f(conv(X, W) + bias).  X [B][Cin][H][W], W [Cout][Cin][KH][KW], bias [Cout],
+    Y [B][Cout][Ho][Wo]: contiguous float32 device tensors.  Enqueued on torch's current stream."""
+    import torch
+    B, Cin, H, Wd = (int(v) for v in X.shape)
+    Cout, Cin2, KH, KW = (int(v) for v in W.shape)
+    if Cin2 != Cin:
+        raise TypeError("filter channels do not match the input")
+    _shape_check(bias, (Cout,), "bias")
+    _shape_check(Y, (B, Cout, conv_out_size(H, KH, stride, pad), conv_out_size(Wd, KW, stride, pad)), "Y")
+    f32 = torch.float32
+    with torch.cuda.device(X.device):
+        stream = torch.cuda.current_stream(X.device)
+        _check(lib().dn_conv_forward(_dev_ptr(X, f32, "X"), _dev_ptr(W, f32, "W"), _dev_ptr(bias, f32, "bias"),
+                                     _dev_ptr(Y, f32, "Y"), B, Cin, H, Wd, Cout, KH, KW, int(stride), int(pad),
+                                     int(act), C.c_void_p(stream.cuda_stream)), "dn_conv_forward")
+
+
+def dn_conv_backward(X, W, Y, dA, delta, dX, dW, dbias, stride: int, pad: int, act: int):
+    """delta = dA * f'(Y); dW, dbias = batch means of the parameter gradients; dX (or None) = dE/dX."""
+    import torch
+    B, Cin, H, Wd = (int(v) for v in X.shape)
+    Cout, Cin2, KH, KW = (int(v) for v in W.shape)
+    if Cin2 != Cin:
+        raise TypeError("filter channels do not match the input")
+    yshape = (B, Cout, conv_out_size(H, KH, stride, pad), conv_out_size(Wd, KW, stride, pad))
+    for t, name in ((Y, "Y"), (dA, "dA"), (delta, "delta")):
+        _shape_check(t, yshape, name)
+    _shape_check(dW, W.shape, "dW")
+    _shape_check(dbias, (Cout,), "dbias")
+    if dX is not None:
+        _shape_check(dX, X.shape, "dX")
+    f32 = torch.float32
+    with torch.cuda.device(X.device):
+        stream = torch.cuda.current_stream(X.device)
+        _check(lib().dn_conv_backward(_dev_ptr(X, f32, "X"), _dev_ptr(W, f32, "W"), _dev_ptr(Y, f32, "Y"),
+                                      _dev_ptr(dA, f32, "dA"), _dev_ptr(delta, f32, "delta"),
+                                      None if dX is None else _dev_ptr(dX, f32, "dX"), _dev_ptr(dW, f32, "dW"),
+                                      _dev_ptr(dbias, f32, "dbias"), B, Cin, H, Wd, Cout, KH, KW, int(stride),
+                                      int(pad), int(act), C.c_void_p(stream.cuda_stream)), "dn_conv_backward")
+
+
+def dn_maxpool_forward(X, Y, k: int, stride: int):
+    import torch
+    B, Cn, H, Wd = (int(v) for v in X.shape)
+    _shape_check(Y, (B, Cn, (H - k) // stride + 1, (Wd - k) // stride + 1), "Y")
+    f32 = torch.float32
+    with torch.cuda.device(X.device):
+        stream = torch.cuda.current_stream(X.device)
+        _check(lib().dn_maxpool_forward(_dev_ptr(X, f32, "X"), _dev_ptr(Y, f32, "Y"), B, Cn, H, Wd, int(k),
+                                        int(stride), C.c_void_p(stream.cuda_stream)), "dn_maxpool_forward")
+
+
+def dn_maxpool_backward(X, dY, dX, k: int, stride: int):
+    import torch
+    B, Cn, H, Wd = (int(v) for v in X.shape)
+    _shape_check(dY, (B, Cn, (H - k) // stride + 1, (Wd - k) // stride + 1), "dY")
+    _shape_check(dX, X.shape, "dX")
+    f32 = torch.float32
+    with torch.cuda.device(X.device):
+        stream = torch.cuda.current_stream(X.device)
+        _check(lib().dn_maxpool_backward(_dev_ptr(X, f32, "X"), _dev_ptr(dY, f32, "dY"), _dev_ptr(dX, f32, "dX"),
+                                         B, Cn, H, Wd, int(k), int(stride), C.c_void_p(stream.cuda_stream)),
+               "dn_maxpool_backward")
 
 
 class Net:

@@ -119,3 +119,30 @@ def test_layer_backward_host_argument_checks(lib):
     assert f(*args(0x10000, need - 1)) == dn.DN_ERR_SHAPE                         # workspace too small
     assert f(*args(0x10000, need, co=0)) == dn.DN_ERR_SHAPE
     assert f(*args(0x10010, need)) == dn.DN_ERR_INVALID_ARG                       # misaligned workspace
+
+
+def test_conv_and_pool_argument_checks(lib):
+    """Bad arguments are refused before anything is enqueued (dummy non-NULL pointers)."""
+    p = C.c_void_p(0x1000)
+    conv = lambda **k: lib.dn_conv_forward(p, p, p, p, k.get("B", 2), k.get("Cin", 3), k.get("H", 8), k.get("W", 8),
+                                           k.get("Cout", 4), k.get("KH", 3), k.get("KW", 3), k.get("stride", 1),
+                                           k.get("pad", 1), k.get("act", 2), None)
+    assert lib.dn_conv_forward(None, p, p, p, 2, 3, 8, 8, 4, 3, 3, 1, 1, 2, None) == dn.DN_ERR_INVALID_ARG
+    assert conv(B=0) == dn.DN_ERR_INVALID_ARG
+    assert conv(KH=8) == dn.DN_ERR_INVALID_ARG            # filter edge above 7
+    assert conv(pad=3) == dn.DN_ERR_INVALID_ARG           # padding as wide as the filter
+    assert conv(stride=0) == dn.DN_ERR_INVALID_ARG
+    assert conv(H=1, pad=0) == dn.DN_ERR_INVALID_ARG      # empty output
+    assert conv(act=4) == dn.DN_ERR_UNSUPPORTED           # softmax is not a convolutional activation
+    assert conv(B=60000, Cin=64, H=64, W=64) == dn.DN_ERR_INVALID_ARG   # more than 2^31 - 1 elements
+    back = lambda dW, **k: lib.dn_conv_backward(p, p, p, p, p, None, dW, p, 2, 3, 8, 8, 4, k.get("KH", 3), 3, 1, 1, 2,
+                                                None)
+    assert back(None) == dn.DN_ERR_INVALID_ARG
+    assert back(p, KH=9) == dn.DN_ERR_INVALID_ARG
+    pool = lambda **k: lib.dn_maxpool_forward(p, p, k.get("B", 2), 3, k.get("H", 8), 8, k.get("k", 2),
+                                              k.get("stride", 2), None)
+    assert lib.dn_maxpool_forward(p, None, 2, 3, 8, 8, 2, 2, None) == dn.DN_ERR_INVALID_ARG
+    assert pool(k=9) == dn.DN_ERR_INVALID_ARG             # window larger than the image
+    assert pool(stride=0) == dn.DN_ERR_INVALID_ARG
+    assert pool(B=40000) == dn.DN_ERR_INVALID_ARG         # more planes than the launch grid holds
+    assert lib.dn_maxpool_backward(p, p, None, 2, 3, 8, 8, 2, 2, None) == dn.DN_ERR_INVALID_ARG

@@ -1,0 +1,106 @@
+"""GPU parity of the convolutional and max-pooling layers against the CPU checker
+(fp32 storage, fp64 accumulation), element by element, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import dn_conv_oracle as co
+from paper_2001_04206_amd import dn
+from parity_util import announce, assert_close
+
+pytestmark = pytest.mark.gpu
+
+LIN, SIG, TANH, RELU = 0, 1, 2, 3
+TOL = 1e-4
+
+CONV_CASES = [
+    # B, Cin, H, W, Cout, KH, KW, stride, pad, act
+    (2, 3, 7, 6, 4, 3, 2, 1, 0, TANH),
+    (1, 1, 5, 5, 1, 3, 3, 1, 1, LIN),
+    (3, 2, 9, 8, 5, 3, 3, 2, 1, SIG),            # stride 2, channel count not a multiple of the group of 4
+    (2, 4, 6, 10, 3, 5, 5, 1, 2, RELU),
+    (5, 6, 19, 23, 7, 7, 7, 1, 3, TANH),          # largest filter, several workgroups per image
+    (4, 3, 33, 31, 9, 3, 3, 3, 0, TANH),          # stride 3, ragged
+    (1, 16, 1, 1, 8, 1, 1, 1, 0, SIG),            # one-pixel images: a dense layer
+    (16, 8, 28, 28, 16, 5, 5, 1, 0, RELU),        # the size of a small image classifier's second layer
+]
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+@pytest.mark.parametrize("B,Cin,H,W,Cout,KH,KW,stride,pad,act", CONV_CASES)
+def test_conv_forward_and_backward(B, Cin, H, W, Cout, KH, KW, stride, pad, act):
+    announce("conv B=%d Cin=%d %dx%d Cout=%d k=%dx%d stride=%d pad=%d act=%d" % (B, Cin, H, W, Cout, KH, KW, stride, pad, act))
+    rng = np.random.default_rng(21)
+    X = rng.standard_normal((B, Cin, H, W)).astype(np.float32)
+    Wt = (rng.standard_normal((Cout, Cin, KH, KW)) / np.sqrt(Cin * KH * KW)).astype(np.float32)
+    b = (rng.standard_normal(Cout) * 0.1).astype(np.float32)
+    Yr = co.conv_forward("o32", X, Wt, b, stride, pad, act)
+    dA = rng.standard_normal(Yr.shape).astype(np.float32)
+    delta_r, dX_r, dW_r, db_r = co.conv_backward("o32", X, Wt, Yr, dA, stride, pad, act)
+
+    Xd, Wd, bd = dev(X), dev(Wt), dev(b)
+    Y = torch.full(Yr.shape, float("nan"), dtype=torch.float32, device="cuda:0")
+    dn.dn_conv_forward(Xd, Wd, bd, Y, stride, pad, act)
+    assert_close(Y.cpu().numpy(), Yr, TOL, "Y")
+    # backward from the checker's own output, so both sides differentiate at the same point
+    Yd, dAd = dev(Yr), dev(dA)
+    delta = torch.full(Yr.shape, float("nan"), dtype=torch.float32, device="cuda:0")
+    dX = torch.full(X.shape, float("nan"), dtype=torch.float32, device="cuda:0")
+    dW = torch.full(Wt.shape, float("nan"), dtype=torch.float32, device="cuda:0")
+    db = torch.full((Cout,), float("nan"), dtype=torch.float32, device="cuda:0")
+    dn.dn_conv_backward(Xd, Wd, Yd, dAd, delta, dX, dW, db, stride, pad, act)
+    assert_close(delta.cpu().numpy(), delta_r, TOL, "delta")
+    assert_close(dW.cpu().numpy(), dW_r, TOL, "dW")
+    assert_close(db.cpu().numpy(), db_r, TOL, "dbias")
+    assert_close(dX.cpu().numpy(), dX_r, TOL, "dX")
+    # without an input gradient the other outputs are the same bits
+    dW2 = torch.zeros_like(dW)
+    db2 = torch.zeros_like(db)
+    dn.dn_conv_backward(Xd, Wd, Yd, dAd, delta, None, dW2, db2, stride, pad, act)
+    assert torch.equal(dW2, dW) and torch.equal(db2, db)
+
+
+POOL_CASES = [((2, 3, 8, 8), 2, 2), ((1, 2, 7, 9), 3, 2), ((2, 1, 6, 6), 3, 1), ((1, 1, 5, 5), 5, 1),
+              ((2, 2, 9, 7), 2, 3), ((3, 5, 33, 47), 3, 2), ((16, 16, 24, 24), 2, 2), ((2, 2, 4, 5), 1, 1)]
+
+
+@pytest.mark.parametrize("shape,k,s", POOL_CASES)
+def test_maxpool_forward_and_backward(shape, k, s):
+    announce("maxpool shape=%s k=%d stride=%d" % (shape, k, s))
+    rng = np.random.default_rng(22)
+    # few distinct values: many windows hold equal maxima, so the tie rule is exercised
+    X = rng.integers(-3, 4, size=shape).astype(np.float32)
+    Yr = co.maxpool_forward("o32", X, k, s)
+    dY = rng.standard_normal(Yr.shape).astype(np.float32)
+    dXr = co.maxpool_backward("o32", X, dY, k, s)
+    Xd = dev(X)
+    Y = torch.full(Yr.shape, float("nan"), dtype=torch.float32, device="cuda:0")
+    dn.dn_maxpool_forward(Xd, Y, k, s)
+    assert np.array_equal(Y.cpu().numpy(), Yr)                    # a selection: exact
+    dX = torch.full(shape, float("nan"), dtype=torch.float32, device="cuda:0")
+    dn.dn_maxpool_backward(Xd, dev(dY), dX, k, s)
+    got = dX.cpu().numpy()
+    assert np.array_equal(got != 0, dXr != 0)                     # the same positions receive gradient
+    if s >= k:
+        assert np.array_equal(got, dXr)                           # windows do not overlap: values are moved, not added
+    else:
+        np.testing.assert_allclose(got, dXr, rtol=1e-6, atol=1e-6)   # sums of up to ceil(k/s)^2 terms
+
+
+def test_conv_backward_is_bitwise_reproducible():
+    announce("conv determinism")
+    rng = np.random.default_rng(23)
+    X = dev(rng.standard_normal((8, 6, 20, 20)).astype(np.float32))
+    Wt = dev(rng.standard_normal((10, 6, 3, 3)).astype(np.float32))
+    Y = dev(rng.standard_normal((8, 10, 20, 20)).astype(np.float32))
+    dA = dev(rng.standard_normal((8, 10, 20, 20)).astype(np.float32))
+    outs = []
+    for _ in range(2):
+        delta, dX, dW, db = torch.empty_like(Y), torch.empty_like(X), torch.empty_like(Wt), torch.empty(10, device="cuda:0")
+        dn.dn_conv_backward(X, Wt, Y, dA, delta, dX, dW, db, 1, 1, TANH)
+        outs.append((dX.clone(), dW.clone(), db.clone()))
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)

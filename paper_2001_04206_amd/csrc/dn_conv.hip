@@ -36,42 +36,54 @@ struct ConvShape {
     int B, Cin, H, W, Cout, KH, KW, stride, pad, Ho, Wo, act;
 };
 
+constexpr int kStageFloats = 8192;   // filter values staged in LDS at a time (32 KB)
+
 // y[b][o][i][j] for CO output channels o at a time: a thread owns one pixel (b, i, j) of a group of
-// CO channels, so each input value it loads serves CO filters; filter values are uniform across
-// the wave (scalar loads).  Adjacent threads own adjacent j: input rows are read coalesced.
+// CO channels, so each input value it loads serves CO filters.  The group's filter values are
+// staged through LDS, a range of input channels at a time, laid out [channel][tap][CO] so that a
+// thread reads the CO values of a tap as 16-byte broadcasts.  Adjacent threads own adjacent j:
+// input rows are read coalesced.
 template <int CO>
 __global__ __launch_bounds__(256) void conv_forward_kernel(ConvShape s, const float *__restrict__ X,
                                                            const float *__restrict__ Wt,
                                                            const float *__restrict__ bias, float *__restrict__ Y)
 {
-    const int pix = s.Ho * s.Wo;
+    __shared__ __attribute__((aligned(16))) float wl[kStageFloats];
+    const int pix = s.Ho * s.Wo, taps = s.KH * s.KW;
     const int p = blockIdx.x * 256 + threadIdx.x;
     const int og = blockIdx.y, b = blockIdx.z;
-    if (p >= pix) return;
-    const int i = p / s.Wo, j = p - i * s.Wo;
+    const bool live = p < pix;
+    const int i = live ? p / s.Wo : 0, j = live ? p - i * s.Wo : 0;
     float acc[CO];
-    int oc[CO];
 #pragma unroll
-    for (int q = 0; q < CO; ++q) {
-        oc[q] = min(og * CO + q, s.Cout - 1);   // channels past the end repeat the last one; not stored
-        acc[q] = bias[oc[q]];
-    }
+    for (int q = 0; q < CO; ++q) acc[q] = bias[min(og * CO + q, s.Cout - 1)];   // past the end: repeats, not stored
     const int r0 = i * s.stride - s.pad, c0 = j * s.stride - s.pad;
-    for (int ci = 0; ci < s.Cin; ++ci) {
-        const float *x = X + ((size_t)b * s.Cin + ci) * s.H * s.W;
-        for (int u = 0; u < s.KH; ++u) {
-            const int r = r0 + u;
-            if (r < 0 || r >= s.H) continue;
-            for (int v = 0; v < s.KW; ++v) {
-                const int c = c0 + v;
-                if (c < 0 || c >= s.W) continue;
-                const float xv = x[(size_t)r * s.W + c];
+    const int per_stage = max(1, kStageFloats / (taps * CO));   // input channels per stage
+    for (int ci0 = 0; ci0 < s.Cin; ci0 += per_stage) {
+        const int n = min(per_stage, s.Cin - ci0);
+        __syncthreads();   // the previous stage has been used
+        for (int e = threadIdx.x; e < n * taps * CO; e += 256) {
+            const int q = e % CO, tap = (e / CO) % taps, cl = e / (CO * taps);
+            wl[e] = Wt[((size_t)min(og * CO + q, s.Cout - 1) * s.Cin + ci0 + cl) * taps + tap];
+        }
+        __syncthreads();
+        if (!live) continue;
+        // the taps that fall inside the image, once per thread instead of a test per tap
+        const int u_lo = max(0, -r0), u_hi = min(s.KH, s.H - r0), v_lo = max(0, -c0), v_hi = min(s.KW, s.W - c0);
+        for (int cl = 0; cl < n; ++cl) {
+            const float *x = X + ((size_t)b * s.Cin + ci0 + cl) * s.H * s.W + (size_t)r0 * s.W + c0;
+            const float *wc = wl + (size_t)cl * taps * CO;
+            for (int u = u_lo; u < u_hi; ++u) {
+                for (int v = v_lo; v < v_hi; ++v) {
+                    const float xv = x[u * s.W + v];
+                    const float *wq = wc + (u * s.KW + v) * CO;
 #pragma unroll
-                for (int q = 0; q < CO; ++q)
-                    acc[q] = fmaf(Wt[(((size_t)oc[q] * s.Cin + ci) * s.KH + u) * s.KW + v], xv, acc[q]);
+                    for (int q = 0; q < CO; ++q) acc[q] = fmaf(wq[q], xv, acc[q]);
+                }
             }
         }
     }
+    if (!live) return;
 #pragma unroll
     for (int q = 0; q < CO; ++q)
         if (og * CO + q < s.Cout) Y[((size_t)b * s.Cout + og * CO + q) * pix + p] = conv_act(s.act, acc[q]);
@@ -84,93 +96,140 @@ __global__ __launch_bounds__(256) void conv_delta_kernel(const float *__restrict
         delta[e] = dA[e] * conv_deriv(act, Y[e]);
 }
 
-// dW[o][c][u][v] = (1/B) sum_{b,i,j} delta[b][o][i][j] x[b][c][i*stride+u-pad][j*stride+v-pad]:
-// one workgroup per (o, c) pair holds all kh x kw sums; its threads take the positions (b, i, j)
-// in turn (adjacent threads adjacent j), each delta value a thread loads serving the whole
-// filter window; the threads' partial sums are then added in a fixed order.  Workgroups past the
-// (o, c) pairs, one per output channel, add up delta for the bias.
+// dW[o][c][u][v] = (1/B) sum_{b,i,j} delta[b][o][i][j] x[b][c][i*stride+u-pad][j*stride+v-pad].
+// A workgroup owns one input channel c, a group of CO output channels and a chunk of the batch's
+// images, and holds all CO x kh x kw sums of that chunk in registers: its threads take the
+// positions (b, i, j) in turn (adjacent threads adjacent j); every input value a thread loads
+// serves CO filters and every delta value the whole filter window.  The threads' sums are added
+// in a fixed order (lane butterfly, then the four waves) and written to part[chunk][o][c][u][v];
+// conv_dw_reduce_kernel adds the chunks in order and divides by the batch.  Chunks exist so
+// that layers with few channels still fill the device.
+template <int KMAX, int CO>
 __global__ __launch_bounds__(256) void conv_dw_kernel(ConvShape s, const float *__restrict__ X,
-                                                      const float *__restrict__ delta, float *__restrict__ dW,
-                                                      float *__restrict__ dbias)
+                                                      const float *__restrict__ delta, float *__restrict__ part,
+                                                      int images_per_chunk)
 {
-    __shared__ float red[4];
+    __shared__ float red[4][CO * KMAX * KMAX];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int pix = s.Ho * s.Wo;
-    const int total = s.B * pix;
-    const float inv_b = 1.0f / (float)s.B;
-    if ((int)blockIdx.x >= s.Cout * s.Cin) {
-        const int o = blockIdx.x - s.Cout * s.Cin;
-        float part = 0.f;
-        for (int t = tid; t < total; t += 256) {
-            const int b = t / pix, p = t - b * pix;
-            part += delta[((size_t)b * s.Cout + o) * pix + p];
-        }
-        part = wave_sum(part);
-        if (lane == 0) red[wave] = part;
-        __syncthreads();
-        if (tid == 0) dbias[o] = ((red[0] + red[1]) + (red[2] + red[3])) * inv_b;
-        return;
-    }
-    const int o = blockIdx.x / s.Cin, c = blockIdx.x - o * s.Cin;
-    float acc[kMaxFilter][kMaxFilter];
+    const int c = blockIdx.x % s.Cin, og = blockIdx.x / s.Cin;
+    const int b0 = blockIdx.y * images_per_chunk, b1 = min(s.B, b0 + images_per_chunk);
+    const int total = (b1 - b0) * pix;
+    int oc[CO];
 #pragma unroll
-    for (int u = 0; u < kMaxFilter; ++u)
+    for (int q = 0; q < CO; ++q) oc[q] = min(og * CO + q, s.Cout - 1);   // past the end: repeats, not stored
+    float acc[CO][KMAX][KMAX];
 #pragma unroll
-        for (int v = 0; v < kMaxFilter; ++v) acc[u][v] = 0.f;
+    for (int q = 0; q < CO; ++q)
+#pragma unroll
+        for (int u = 0; u < KMAX; ++u)
+#pragma unroll
+            for (int v = 0; v < KMAX; ++v) acc[q][u][v] = 0.f;
     for (int t = tid; t < total; t += 256) {
-        const int b = t / pix, p = t - b * pix;
+        const int b = b0 + t / pix, p = t % pix;
         const int i = p / s.Wo, j = p - i * s.Wo;
-        const float d = delta[((size_t)b * s.Cout + o) * pix + p];
+        float d[CO];
+#pragma unroll
+        for (int q = 0; q < CO; ++q) d[q] = delta[((size_t)b * s.Cout + oc[q]) * pix + p];
         const float *x = X + ((size_t)b * s.Cin + c) * s.H * s.W;
         const int r0 = i * s.stride - s.pad, c0 = j * s.stride - s.pad;
 #pragma unroll
-        for (int u = 0; u < kMaxFilter; ++u) {
+        for (int u = 0; u < KMAX; ++u) {
             if (u < s.KH) {
                 const int r = r0 + u;
                 const bool row_ok = r >= 0 && r < s.H;
 #pragma unroll
-                for (int v = 0; v < kMaxFilter; ++v) {
+                for (int v = 0; v < KMAX; ++v) {
                     if (v < s.KW) {
                         const int cc = c0 + v;
                         const bool ok = row_ok && cc >= 0 && cc < s.W;
                         const float xv = ok ? x[(size_t)r * s.W + cc] : 0.f;
-                        acc[u][v] = fmaf(d, xv, acc[u][v]);
+#pragma unroll
+                        for (int q = 0; q < CO; ++q) acc[q][u][v] = fmaf(d[q], xv, acc[q][u][v]);
                     }
                 }
             }
         }
     }
 #pragma unroll
-    for (int u = 0; u < kMaxFilter; ++u) {
+    for (int q = 0; q < CO; ++q)
 #pragma unroll
-        for (int v = 0; v < kMaxFilter; ++v) {
-            if (u < s.KH && v < s.KW) {   // uniform
-                const float w_sum = wave_sum(acc[u][v]);
-                __syncthreads();            // red is free again
-                if (lane == 0) red[wave] = w_sum;
-                __syncthreads();
-                if (tid == 0)
-                    dW[(((size_t)o * s.Cin + c) * s.KH + u) * s.KW + v] = ((red[0] + red[1]) + (red[2] + red[3])) * inv_b;
+        for (int u = 0; u < KMAX; ++u)
+#pragma unroll
+            for (int v = 0; v < KMAX; ++v) {
+                if (u < s.KH && v < s.KW) {   // uniform
+                    const float w_sum = wave_sum(acc[q][u][v]);
+                    if (lane == 0) red[wave][(q * KMAX + u) * KMAX + v] = w_sum;
+                }
             }
-        }
+    __syncthreads();
+    const size_t filt = (size_t)s.Cout * s.Cin * s.KH * s.KW;
+    for (int e = tid; e < CO * KMAX * KMAX; e += 256) {
+        const int q = e / (KMAX * KMAX), u = (e / KMAX) % KMAX, v = e % KMAX;
+        if (u < s.KH && v < s.KW && og * CO + q < s.Cout)
+            part[(size_t)blockIdx.y * filt + (((size_t)(og * CO + q) * s.Cin + c) * s.KH + u) * s.KW + v] =
+                (red[0][e] + red[1][e]) + (red[2][e] + red[3][e]);
     }
 }
 
+// dW = (1/B) sum over chunks (in order) of part; one thread per filter element.
+__global__ __launch_bounds__(256) void conv_dw_reduce_kernel(const float *__restrict__ part, float *__restrict__ dW,
+                                                             size_t filt, int chunks, float inv_b)
+{
+    const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= filt) return;
+    float sum = 0.f;
+    for (int k = 0; k < chunks; ++k) sum += part[(size_t)k * filt + e];
+    dW[e] = sum * inv_b;
+}
+
+// dbias[o] = (1/B) sum_{b,i,j} delta[b][o][i][j]: one workgroup per output channel.
+__global__ __launch_bounds__(256) void conv_dbias_kernel(ConvShape s, const float *__restrict__ delta,
+                                                         float *__restrict__ dbias)
+{
+    __shared__ float red[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int pix = s.Ho * s.Wo, total = s.B * pix, o = blockIdx.x;
+    float part = 0.f;
+    for (int t = tid; t < total; t += 256) {
+        const int b = t / pix, p = t - b * pix;
+        part += delta[((size_t)b * s.Cout + o) * pix + p];
+    }
+    part = wave_sum(part);
+    if (lane == 0) red[wave] = part;
+    __syncthreads();
+    if (tid == 0) dbias[o] = ((red[0] + red[1]) + (red[2] + red[3])) / (float)s.B;
+}
+
 // dX[b][c][r][col] = sum over (o, u, v) with r = i*stride+u-pad, col = j*stride+v-pad of
-// delta[b][o][i][j] W[o][c][u][v]: a thread owns one input pixel of one channel.
+// delta[b][o][i][j] W[o][c][u][v]: a thread owns one input pixel of a group of CI channels, so each
+// delta value it loads serves CI filters.  The group's filter values are staged through LDS, a
+// range of output channels at a time, laid out [output channel][tap][CI].
+template <int CI>
 __global__ __launch_bounds__(256) void conv_dx_kernel(ConvShape s, const float *__restrict__ Wt,
                                                       const float *__restrict__ delta, float *__restrict__ dX)
 {
+    __shared__ __attribute__((aligned(16))) float wl[kStageFloats];
     const int hw = s.H * s.W;
     const int p = blockIdx.x * 256 + threadIdx.x;
-    const int c = blockIdx.y, b = blockIdx.z;
-    if (p >= hw) return;
-    const int r = p / s.W, col = p - r * s.W;
+    const int cg = blockIdx.y, b = blockIdx.z;
+    const bool live = p < hw;
+    const int r = live ? p / s.W : 0, col = live ? p - r * s.W : 0;
     const int pix = s.Ho * s.Wo;
-    float acc = 0.f;
-    for (int o = 0; o < s.Cout; ++o) {
-        const float *d = delta + ((size_t)b * s.Cout + o) * pix;
-        const float *wf = Wt + ((size_t)o * s.Cin + c) * s.KH * s.KW;
+    const int taps = s.KH * s.KW;
+    float acc[CI];
+#pragma unroll
+    for (int q = 0; q < CI; ++q) acc[q] = 0.f;
+    const int per_stage = max(1, kStageFloats / (taps * CI));   // output channels per stage
+    for (int o0 = 0; o0 < s.Cout; o0 += per_stage) {
+        const int n = min(per_stage, s.Cout - o0);
+        __syncthreads();   // the previous stage has been used
+        for (int e = threadIdx.x; e < n * taps * CI; e += 256) {
+            const int q = e % CI, tap = (e / CI) % taps, ol = e / (CI * taps);
+            wl[e] = Wt[((size_t)(o0 + ol) * s.Cin + min(cg * CI + q, s.Cin - 1)) * taps + tap];   // past the end: repeats
+        }
+        __syncthreads();
+        if (!live) continue;
         for (int u = 0; u < s.KH; ++u) {
             const int ri = r + s.pad - u;
             if (ri < 0 || ri % s.stride != 0) continue;
@@ -181,11 +240,21 @@ __global__ __launch_bounds__(256) void conv_dx_kernel(ConvShape s, const float *
                 if (cj < 0 || cj % s.stride != 0) continue;
                 const int j = cj / s.stride;
                 if (j >= s.Wo) continue;
-                acc = fmaf(d[(size_t)i * s.Wo + j], wf[u * s.KW + v], acc);
+                const float *d = delta + ((size_t)b * s.Cout + o0) * pix + (size_t)i * s.Wo + j;
+                const float *wt = wl + (size_t)(u * s.KW + v) * CI;
+                for (int ol = 0; ol < n; ++ol) {
+                    const float dv = d[(size_t)ol * pix];
+                    const float *wq = wt + (size_t)ol * taps * CI;
+#pragma unroll
+                    for (int q = 0; q < CI; ++q) acc[q] = fmaf(dv, wq[q], acc[q]);
+                }
             }
         }
     }
-    dX[((size_t)b * s.Cin + c) * hw + p] = acc;
+    if (!live) return;
+#pragma unroll
+    for (int q = 0; q < CI; ++q)
+        if (cg * CI + q < s.Cin) dX[((size_t)b * s.Cin + cg * CI + q) * hw + p] = acc[q];
 }
 
 struct PoolShape {
@@ -265,6 +334,29 @@ dn_status pool_shape(int B, int C, int H, int W, int K, int stride, PoolShape &s
 
 dn_status launched() { return hipGetLastError() == hipSuccess ? DN_OK : DN_ERR_DEVICE; }
 
+// How the weight-gradient kernel splits the batch: CO output channels per workgroup by filter
+// size, and as many chunks of images as it takes to put about a thousand workgroups on the device.
+struct DwPlan {
+    int co, groups, chunks, images_per_chunk;
+    size_t filt;
+};
+
+DwPlan dw_plan(const ConvShape &s)
+{
+    DwPlan p;
+    const int kmax = s.KH > s.KW ? s.KH : s.KW;
+    p.co = kmax <= 3 ? 8 : (kmax <= 5 ? 4 : 2);
+    p.groups = (s.Cout + p.co - 1) / p.co;
+    const long per_chunk = (long)p.groups * s.Cin;
+    long chunks = (1024 + per_chunk - 1) / per_chunk;
+    if (chunks > s.B) chunks = s.B;
+    if (chunks < 1) chunks = 1;
+    p.images_per_chunk = (int)((s.B + chunks - 1) / chunks);
+    p.chunks = (s.B + p.images_per_chunk - 1) / p.images_per_chunk;
+    p.filt = (size_t)s.Cout * s.Cin * s.KH * s.KW;
+    return p;
+}
+
 }  // namespace
 
 }  // namespace dn
@@ -281,35 +373,68 @@ dn_status dn_conv_forward(const float *X_dev, const float *W_dev, const float *b
     ConvShape s;
     const dn_status st = conv_shape(batch, c_in, h, w, c_out, kh, kw, stride, pad, (int)act, s);
     if (st != DN_OK) return st;
-    constexpr int CO = 4;
-    const dim3 grid((unsigned)((s.Ho * s.Wo + 255) / 256), (unsigned)((s.Cout + CO - 1) / CO), (unsigned)s.B);
-    hipLaunchKernelGGL(conv_forward_kernel<CO>, grid, dim3(256), 0, (hipStream_t)hip_stream, s, X_dev, W_dev, bias_dev,
-                       Y_dev);
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const int co = s.Cout >= 8 ? 8 : 4;
+    const dim3 grid((unsigned)((s.Ho * s.Wo + 255) / 256), (unsigned)((s.Cout + co - 1) / co), (unsigned)s.B);
+    if (co == 8)
+        hipLaunchKernelGGL(conv_forward_kernel<8>, grid, dim3(256), 0, stream, s, X_dev, W_dev, bias_dev, Y_dev);
+    else
+        hipLaunchKernelGGL(conv_forward_kernel<4>, grid, dim3(256), 0, stream, s, X_dev, W_dev, bias_dev, Y_dev);
     return launched();
 }
 
-dn_status dn_conv_backward(const float *X_dev, const float *W_dev, const float *Y_dev, const float *dA_dev,
-                           float *delta_dev, float *dX_dev, float *dW_dev, float *dbias_dev, int32_t batch,
-                           int32_t c_in, int32_t h, int32_t w, int32_t c_out, int32_t kh, int32_t kw, int32_t stride,
-                           int32_t pad, dn_act act, void *hip_stream)
+size_t dn_conv_backward_workspace_bytes(int32_t batch, int32_t c_in, int32_t h, int32_t w, int32_t c_out, int32_t kh,
+                                        int32_t kw, int32_t stride, int32_t pad)
 {
-    if (!X_dev || !W_dev || !Y_dev || !dA_dev || !delta_dev || !dW_dev || !dbias_dev) return DN_ERR_INVALID_ARG;
+    ConvShape s;
+    if (conv_shape(batch, c_in, h, w, c_out, kh, kw, stride, pad, DN_ACT_LINEAR, s) != DN_OK) return 0;
+    const DwPlan p = dw_plan(s);
+    return p.filt * (size_t)p.chunks * sizeof(float);
+}
+
+dn_status dn_conv_backward(const float *X_dev, const float *W_dev, const float *Y_dev, const float *dA_dev,
+                           float *delta_dev, float *dX_dev, float *dW_dev, float *dbias_dev, void *workspace_dev,
+                           size_t workspace_bytes, int32_t batch, int32_t c_in, int32_t h, int32_t w, int32_t c_out,
+                           int32_t kh, int32_t kw, int32_t stride, int32_t pad, dn_act act, void *hip_stream)
+{
+    if (!X_dev || !W_dev || !Y_dev || !dA_dev || !delta_dev || !dW_dev || !dbias_dev || !workspace_dev)
+        return DN_ERR_INVALID_ARG;
     ConvShape s;
     const dn_status st = conv_shape(batch, c_in, h, w, c_out, kh, kw, stride, pad, (int)act, s);
     if (st != DN_OK) return st;
+    const DwPlan p = dw_plan(s);
+    if (workspace_bytes < p.filt * (size_t)p.chunks * sizeof(float)) return DN_ERR_SHAPE;
+    if ((reinterpret_cast<uintptr_t>(workspace_dev) & 3) != 0) return DN_ERR_INVALID_ARG;
     hipStream_t stream = (hipStream_t)hip_stream;
+    float *part = static_cast<float *>(workspace_dev);
     const size_t ny = (size_t)s.B * s.Cout * s.Ho * s.Wo;
     size_t blocks = (ny + 255) / 256;
     if (blocks > 256 * 16) blocks = 256 * 16;
     hipLaunchKernelGGL(conv_delta_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, dA_dev, Y_dev, delta_dev, ny,
                        s.act);
     if (launched() != DN_OK) return DN_ERR_DEVICE;
-    hipLaunchKernelGGL(conv_dw_kernel, dim3((unsigned)(s.Cout * s.Cin + s.Cout)), dim3(256), 0, stream, s, X_dev,
-                       delta_dev, dW_dev, dbias_dev);
+    const dim3 grid_dw((unsigned)(p.groups * s.Cin), (unsigned)p.chunks);
+    if (p.co == 8)
+        hipLaunchKernelGGL((conv_dw_kernel<3, 8>), grid_dw, dim3(256), 0, stream, s, X_dev, delta_dev, part,
+                           p.images_per_chunk);
+    else if (p.co == 4)
+        hipLaunchKernelGGL((conv_dw_kernel<5, 4>), grid_dw, dim3(256), 0, stream, s, X_dev, delta_dev, part,
+                           p.images_per_chunk);
+    else
+        hipLaunchKernelGGL((conv_dw_kernel<7, 2>), grid_dw, dim3(256), 0, stream, s, X_dev, delta_dev, part,
+                           p.images_per_chunk);
+    if (launched() != DN_OK) return DN_ERR_DEVICE;
+    hipLaunchKernelGGL(conv_dw_reduce_kernel, dim3((unsigned)((p.filt + 255) / 256)), dim3(256), 0, stream, part, dW_dev,
+                       p.filt, p.chunks, 1.0f / (float)s.B);
+    if (launched() != DN_OK) return DN_ERR_DEVICE;
+    hipLaunchKernelGGL(conv_dbias_kernel, dim3((unsigned)s.Cout), dim3(256), 0, stream, s, delta_dev, dbias_dev);
     if (launched() != DN_OK) return DN_ERR_DEVICE;
     if (dX_dev) {
-        const dim3 grid((unsigned)((s.H * s.W + 255) / 256), (unsigned)s.Cin, (unsigned)s.B);
-        hipLaunchKernelGGL(conv_dx_kernel, grid, dim3(256), 0, stream, s, W_dev, delta_dev, dX_dev);
+        const int ci = s.Cin >= 8 ? 8 : (s.Cin >= 2 ? 4 : 1);
+        const dim3 grid((unsigned)((s.H * s.W + 255) / 256), (unsigned)((s.Cin + ci - 1) / ci), (unsigned)s.B);
+        if (ci == 8) hipLaunchKernelGGL(conv_dx_kernel<8>, grid, dim3(256), 0, stream, s, W_dev, delta_dev, dX_dev);
+        else if (ci == 4) hipLaunchKernelGGL(conv_dx_kernel<4>, grid, dim3(256), 0, stream, s, W_dev, delta_dev, dX_dev);
+        else hipLaunchKernelGGL(conv_dx_kernel<1>, grid, dim3(256), 0, stream, s, W_dev, delta_dev, dX_dev);
         if (launched() != DN_OK) return DN_ERR_DEVICE;
     }
     return DN_OK;

@@ -27,7 +27,8 @@ EXPORTS = [
     "dn_get_params", "dn_get_grads", "dn_forward", "dn_backward", "dn_update", "dn_train_epoch",
     "dn_train", "dn_evaluate", "dn_layer_backward_workspace_bytes", "dn_layer_backward_host",
     "dn_last_epoch_ms", "dn_kernel_time", "dn_set_option",
-    "dn_conv_forward", "dn_conv_backward", "dn_maxpool_forward", "dn_maxpool_backward",
+    "dn_conv_forward", "dn_conv_backward_workspace_bytes", "dn_conv_backward", "dn_maxpool_forward",
+    "dn_maxpool_backward",
 ]
 
 _lib = None
@@ -73,7 +74,9 @@ def lib():
         l.dn_kernel_time.argtypes = [vp, i32, C.POINTER(f32), C.POINTER(i64)]
         l.dn_set_option.argtypes = [vp, C.c_char_p, i64]
         for name in EXPORTS[2:]:
-            if name != "dn_layer_backward_workspace_bytes":
+            if name.endswith("_workspace_bytes"):
+                getattr(l, name).restype = C.c_size_t
+            else:
                 getattr(l, name).restype = C.c_int
         _lib = l
     return _lib
@@ -169,8 +172,9 @@ def dn_conv_forward(X, W, bias, Y, stride: int, pad: int, act: int):
                                      int(act), C.c_void_p(stream.cuda_stream)), "dn_conv_forward")
 
 
-def dn_conv_backward(X, W, Y, dA, delta, dX, dW, dbias, stride: int, pad: int, act: int):
-    """delta = dA * f'(Y); dW, dbias = batch means of the parameter gradients; dX (or None) = dE/dX."""
+def dn_conv_backward(X, W, Y, dA, delta, dX, dW, dbias, stride: int, pad: int, act: int, workspace=None):
+    """delta = dA * f'(Y); dW, dbias = batch means of the parameter gradients; dX (or None) = dE/dX.
+    `workspace`: a device uint8 tensor of dn_conv_backward_workspace_bytes(...) bytes (allocated here if None)."""
     import torch
     B, Cin, H, Wd = (int(v) for v in X.shape)
     Cout, Cin2, KH, KW = (int(v) for v in W.shape)
@@ -184,12 +188,18 @@ def dn_conv_backward(X, W, Y, dA, delta, dX, dW, dbias, stride: int, pad: int, a
     if dX is not None:
         _shape_check(dX, X.shape, "dX")
     f32 = torch.float32
+    need = int(lib().dn_conv_backward_workspace_bytes(B, Cin, H, Wd, Cout, KH, KW, int(stride), int(pad)))
+    if need == 0:
+        raise DnError(DN_ERR_INVALID_ARG, "dn_conv_backward_workspace_bytes")
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
     with torch.cuda.device(X.device):
         stream = torch.cuda.current_stream(X.device)
         _check(lib().dn_conv_backward(_dev_ptr(X, f32, "X"), _dev_ptr(W, f32, "W"), _dev_ptr(Y, f32, "Y"),
                                       _dev_ptr(dA, f32, "dA"), _dev_ptr(delta, f32, "delta"),
                                       None if dX is None else _dev_ptr(dX, f32, "dX"), _dev_ptr(dW, f32, "dW"),
-                                      _dev_ptr(dbias, f32, "dbias"), B, Cin, H, Wd, Cout, KH, KW, int(stride),
+                                      _dev_ptr(dbias, f32, "dbias"), _dev_ptr(workspace, torch.uint8, "workspace"),
+                                      C.c_size_t(int(workspace.numel())), B, Cin, H, Wd, Cout, KH, KW, int(stride),
                                       int(pad), int(act), C.c_void_p(stream.cuda_stream)), "dn_conv_backward")
 
 

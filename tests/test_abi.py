@@ -135,10 +135,15 @@ def test_conv_and_pool_argument_checks(lib):
     assert conv(H=1, pad=0) == dn.DN_ERR_INVALID_ARG      # empty output
     assert conv(act=4) == dn.DN_ERR_UNSUPPORTED           # softmax is not a convolutional activation
     assert conv(B=60000, Cin=64, H=64, W=64) == dn.DN_ERR_INVALID_ARG   # more than 2^31 - 1 elements
-    back = lambda dW, **k: lib.dn_conv_backward(p, p, p, p, p, None, dW, p, 2, 3, 8, 8, 4, k.get("KH", 3), 3, 1, 1, 2,
-                                                None)
+    need = lib.dn_conv_backward_workspace_bytes(2, 3, 8, 8, 4, 3, 3, 1, 1)
+    assert need >= 4 * 4 * 3 * 3 * 3 and need % 4 == 0
+    assert lib.dn_conv_backward_workspace_bytes(2, 3, 8, 8, 4, 9, 3, 1, 1) == 0
+    back = lambda dW, **k: lib.dn_conv_backward(p, p, p, p, p, None, dW, p, k.get("ws", p), C.c_size_t(k.get("nbytes", need)),
+                                                2, 3, 8, 8, 4, k.get("KH", 3), 3, 1, 1, 2, None)
     assert back(None) == dn.DN_ERR_INVALID_ARG
     assert back(p, KH=9) == dn.DN_ERR_INVALID_ARG
+    assert back(p, ws=None) == dn.DN_ERR_INVALID_ARG
+    assert back(p, nbytes=need - 4) == dn.DN_ERR_SHAPE        # workspace too small
     pool = lambda **k: lib.dn_maxpool_forward(p, p, k.get("B", 2), 3, k.get("H", 8), 8, k.get("k", 2),
                                               k.get("stride", 2), None)
     assert lib.dn_maxpool_forward(p, None, 2, 3, 8, 8, 2, 2, None) == dn.DN_ERR_INVALID_ARG

@@ -172,6 +172,97 @@ __global__ __launch_bounds__(256) void conv_dw_kernel(ConvShape s, const float *
     }
 }
 
+// The same for stride 1, where consecutive output rows share all but one row of their input
+// windows: a thread owns one output column j of one image and walks down the rows, keeping the
+// kh x kw window in registers and loading only its new bottom row per step (no index arithmetic
+// in the loop).  Window rows sit at the bottom of a KMAX-row register array so that the row that
+// is replaced has a fixed register position whatever kh is.
+template <int KMAX, int CO>
+__global__ __launch_bounds__(256) void conv_dw_slide_kernel(ConvShape s, const float *__restrict__ X,
+                                                            const float *__restrict__ delta, float *__restrict__ part,
+                                                            int images_per_chunk)
+{
+    __shared__ float red[4][CO * KMAX * KMAX];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int pix = s.Ho * s.Wo;
+    const int c = blockIdx.x % s.Cin, og = blockIdx.x / s.Cin;
+    const int b0 = blockIdx.y * images_per_chunk, b1 = min(s.B, b0 + images_per_chunk);
+    const int total = (b1 - b0) * s.Wo;
+    const int off = KMAX - s.KH;   // window row u lives at index u + off
+    int oc[CO];
+#pragma unroll
+    for (int q = 0; q < CO; ++q) oc[q] = min(og * CO + q, s.Cout - 1);   // past the end: repeats, not stored
+    float acc[CO][KMAX][KMAX];
+#pragma unroll
+    for (int q = 0; q < CO; ++q)
+#pragma unroll
+        for (int u = 0; u < KMAX; ++u)
+#pragma unroll
+            for (int v = 0; v < KMAX; ++v) acc[q][u][v] = 0.f;
+    for (int t = tid; t < total; t += 256) {
+        const int b = b0 + t / s.Wo, j = t % s.Wo;
+        const float *x = X + ((size_t)b * s.Cin + c) * s.H * s.W;
+        const float *d = delta + (size_t)b * s.Cout * pix + j;
+        const int c0 = j - s.pad;
+        bool col_ok[KMAX];
+#pragma unroll
+        for (int v = 0; v < KMAX; ++v) col_ok[v] = v < s.KW && c0 + v >= 0 && c0 + v < s.W;
+        float win[KMAX][KMAX];
+        // the window of output row -1: its rows 1 .. kh-1 are rows 0 .. kh-2 of output row 0
+#pragma unroll
+        for (int u = 0; u < KMAX; ++u) {
+            const int r = -1 - s.pad + (u - off);
+            const bool row_ok = u >= off && r >= 0 && r < s.H;
+#pragma unroll
+            for (int v = 0; v < KMAX; ++v) win[u][v] = (row_ok && col_ok[v]) ? x[(size_t)r * s.W + c0 + v] : 0.f;
+        }
+        for (int i = 0; i < s.Ho; ++i) {
+#pragma unroll
+            for (int u = 0; u < KMAX - 1; ++u)
+#pragma unroll
+                for (int v = 0; v < KMAX; ++v) win[u][v] = win[u + 1][v];
+            const int r = i - s.pad + s.KH - 1;
+            const bool row_ok = r >= 0 && r < s.H;
+#pragma unroll
+            for (int v = 0; v < KMAX; ++v) win[KMAX - 1][v] = (row_ok && col_ok[v]) ? x[(size_t)r * s.W + c0 + v] : 0.f;
+            float dv[CO];
+#pragma unroll
+            for (int q = 0; q < CO; ++q) dv[q] = d[(size_t)oc[q] * pix + (size_t)i * s.Wo];
+#pragma unroll
+            for (int u = 0; u < KMAX; ++u) {
+                if (u >= off) {
+#pragma unroll
+                    for (int v = 0; v < KMAX; ++v) {
+                        if (v < s.KW) {
+#pragma unroll
+                            for (int q = 0; q < CO; ++q) acc[q][u][v] = fmaf(dv[q], win[u][v], acc[q][u][v]);
+                        }
+                    }
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < CO; ++q)
+#pragma unroll
+        for (int u = 0; u < KMAX; ++u)
+#pragma unroll
+            for (int v = 0; v < KMAX; ++v) {
+                if (u >= off && v < s.KW) {   // uniform
+                    const float w_sum = wave_sum(acc[q][u][v]);
+                    if (lane == 0) red[wave][(q * KMAX + u) * KMAX + v] = w_sum;
+                }
+            }
+    __syncthreads();
+    const size_t filt = (size_t)s.Cout * s.Cin * s.KH * s.KW;
+    for (int e = tid; e < CO * KMAX * KMAX; e += 256) {
+        const int q = e / (KMAX * KMAX), u = (e / KMAX) % KMAX, v = e % KMAX;
+        if (u >= off && v < s.KW && og * CO + q < s.Cout)
+            part[(size_t)blockIdx.y * filt + (((size_t)(og * CO + q) * s.Cin + c) * s.KH + (u - off)) * s.KW + v] =
+                (red[0][e] + red[1][e]) + (red[2][e] + red[3][e]);
+    }
+}
+
 // dW = (1/B) sum over chunks (in order) of part; one thread per filter element.
 __global__ __launch_bounds__(256) void conv_dw_reduce_kernel(const float *__restrict__ part, float *__restrict__ dW,
                                                              size_t filt, int chunks, float inv_b)
@@ -230,6 +321,25 @@ __global__ __launch_bounds__(256) void conv_dx_kernel(ConvShape s, const float *
         }
         __syncthreads();
         if (!live) continue;
+        if (s.stride == 1) {
+            // output rows i = r + pad - u and columns j = col + pad - v inside the output: the
+            // valid taps form a rectangle, found once per thread
+            const int u_lo = max(0, r + s.pad - s.Ho + 1), u_hi = min(s.KH, r + s.pad + 1);
+            const int v_lo = max(0, col + s.pad - s.Wo + 1), v_hi = min(s.KW, col + s.pad + 1);
+            const float *d0 = delta + ((size_t)b * s.Cout + o0) * pix + (size_t)(r + s.pad) * s.Wo + (col + s.pad);
+            for (int ol = 0; ol < n; ++ol) {
+                const float *d = d0 + (size_t)ol * pix;
+                const float *wo = wl + (size_t)ol * taps * CI;
+                for (int u = u_lo; u < u_hi; ++u)
+                    for (int v = v_lo; v < v_hi; ++v) {
+                        const float dv = d[-(u * s.Wo + v)];
+                        const float *wq = wo + (u * s.KW + v) * CI;
+#pragma unroll
+                        for (int q = 0; q < CI; ++q) acc[q] = fmaf(dv, wq[q], acc[q]);
+                    }
+            }
+            continue;
+        }
         for (int u = 0; u < s.KH; ++u) {
             const int ri = r + s.pad - u;
             if (ri < 0 || ri % s.stride != 0) continue;
@@ -414,7 +524,16 @@ dn_status dn_conv_backward(const float *X_dev, const float *W_dev, const float *
                        s.act);
     if (launched() != DN_OK) return DN_ERR_DEVICE;
     const dim3 grid_dw((unsigned)(p.groups * s.Cin), (unsigned)p.chunks);
-    if (p.co == 8)
+    if (s.stride == 1 && p.co == 8)
+        hipLaunchKernelGGL((conv_dw_slide_kernel<3, 8>), grid_dw, dim3(256), 0, stream, s, X_dev, delta_dev, part,
+                           p.images_per_chunk);
+    else if (s.stride == 1 && p.co == 4)
+        hipLaunchKernelGGL((conv_dw_slide_kernel<5, 4>), grid_dw, dim3(256), 0, stream, s, X_dev, delta_dev, part,
+                           p.images_per_chunk);
+    else if (s.stride == 1)
+        hipLaunchKernelGGL((conv_dw_slide_kernel<7, 2>), grid_dw, dim3(256), 0, stream, s, X_dev, delta_dev, part,
+                           p.images_per_chunk);
+    else if (p.co == 8)
         hipLaunchKernelGGL((conv_dw_kernel<3, 8>), grid_dw, dim3(256), 0, stream, s, X_dev, delta_dev, part,
                            p.images_per_chunk);
     else if (p.co == 4)

@@ -39,6 +39,99 @@ def workloads():
     return w
 
 
+PEAK_VALU_F32_TFLOPS = 157.3  # fp32 vector rate: 256 CUs x 128 lanes x 2 flop x 2.4 GHz (needs packed fp32 instructions; plain v_fma_f32 gives half)
+
+# A convolutional layer followed by 2x2 max pooling, batch of images resident on the device.
+# name: (batch, c_in, h, w, c_out, k, stride, pad)
+CONV_WORKLOADS = {
+    "conv_32x32x32_to_64_k3_b128": (128, 32, 32, 32, 64, 3, 1, 1),
+    "conv_1x28x28_to_6_k5_b128": (128, 1, 28, 28, 6, 5, 1, 0),
+}
+
+
+def bench_conv(args, shape):
+    """One step = forward and backward of the layer pair on one batch: convolution (ReLU), pooling,
+    pooling backward, convolution backward (delta, filter / bias gradients, input gradient)."""
+    import numpy as np
+    import torch
+    from paper_2001_04206_amd import dn
+    B, Cin, H, W, Cout, K, stride, pad = shape
+    act = 3   # ReLU
+    rng = np.random.default_rng(0)
+    Xh = rng.standard_normal((B, Cin, H, W)).astype(np.float32)
+    Wh = (rng.standard_normal((Cout, Cin, K, K)) * np.sqrt(2.0 / (Cin * K * K))).astype(np.float32)
+    bh = np.zeros(Cout, dtype=np.float32)
+    Ho, Wo = dn.conv_out_size(H, K, stride, pad), dn.conv_out_size(W, K, stride, pad)
+    dPh = rng.standard_normal((B, Cout, Ho // 2, Wo // 2)).astype(np.float32)
+    dev = lambda a: torch.from_numpy(a).to("cuda:0")
+    X, Wt, b, dP = dev(Xh), dev(Wh), dev(bh), dev(dPh)
+    Y = torch.empty(B, Cout, Ho, Wo, device="cuda:0")
+    P = torch.empty(B, Cout, Ho // 2, Wo // 2, device="cuda:0")
+    dY, delta, dX, dW, db = torch.empty_like(Y), torch.empty_like(Y), torch.empty_like(X), torch.empty_like(Wt), torch.empty_like(b)
+    ws = torch.empty(dn.lib().dn_conv_backward_workspace_bytes(B, Cin, H, W, Cout, K, K, stride, pad), dtype=torch.uint8,
+                     device="cuda:0")
+
+    def step():
+        dn.dn_conv_forward(X, Wt, b, Y, stride, pad, act)
+        dn.dn_maxpool_forward(Y, P, 2, 2)
+        dn.dn_maxpool_backward(Y, dP, dY, 2, 2)
+        dn.dn_conv_backward(X, Wt, Y, dY, delta, dX, dW, db, stride, pad, act, workspace=ws)
+
+    steps = args.steps if args.steps > 0 else 200
+    warmup = args.warmup if args.warmup >= 0 else 10
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    # the same steps with the four calls bracketed by events on the stream they are enqueued on
+    names = ["conv_forward", "maxpool_forward", "maxpool_backward", "conv_backward"]
+    ms = dict.fromkeys(names, 0.0)
+    if not args.no_kernel_timing:
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(5)]
+        for _ in range(min(steps, 50)):
+            ev[0].record(); dn.dn_conv_forward(X, Wt, b, Y, stride, pad, act)
+            ev[1].record(); dn.dn_maxpool_forward(Y, P, 2, 2)
+            ev[2].record(); dn.dn_maxpool_backward(Y, dP, dY, 2, 2)
+            ev[3].record(); dn.dn_conv_backward(X, Wt, Y, dY, delta, dX, dW, db, stride, pad, act, workspace=ws)
+            ev[4].record(); torch.cuda.synchronize()
+            for i, n in enumerate(names):
+                ms[n] += ev[i].elapsed_time(ev[i + 1]) / min(steps, 50)
+    fwd_flop = 2.0 * B * Cout * Ho * Wo * Cin * K * K
+    roofline = None
+    if not args.no_kernel_timing:
+        ach = 2.0 * fwd_flop / (ms["conv_backward"] * 1e-3) / 1e12   # filter gradient + input gradient
+        roofline = {"bound": "alu", "kernel": "conv_backward (delta, filter / bias gradient, input gradient: four launches)",
+                    "achieved": ach, "peak": PEAK_VALU_F32_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_VALU_F32_TFLOPS,
+                    "traffic": None, "avg_launch_us": ms["conv_backward"] * 1e3}
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import dn_conv_oracle as co
+        n = 1
+        while True:   # grow the sample until the checker works for about ten seconds
+            t1 = time.perf_counter()
+            Yo = co.conv_forward("o32", Xh[:n], Wh, bh, stride, pad, act)
+            Po = co.maxpool_forward("o32", Yo, 2, 2)
+            dYo = co.maxpool_backward("o32", Yo, dPh[:n], 2, 2)
+            co.conv_backward("o32", Xh[:n], Wh, Yo, dYo, stride, pad, act)
+            dt = time.perf_counter() - t1
+            if dt >= 5.0 or n >= B:
+                break
+            n = min(B, max(n + 1, int(n * min(8.0, 10.0 / max(dt, 1e-3)))))
+        cpu = {"value": n / dt, "unit": "samples/s", "cores": 1, "kind": "oracle",
+               "sample": "first %d images of the same batch, %.1f s" % (n, dt)}
+    return {"metric": "layer-pair samples/sec (convolution + max pooling, fwd+bwd)", "value": B * steps / wall,
+            "unit": "samples/s", "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": wall / steps * 1e3,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "config": {"workload": args.workload, "batch": B, "c_in": Cin, "h": H, "w": W, "c_out": Cout, "filter": K,
+                       "stride": stride, "pad": pad, "pool": "2x2 stride 2", "activation": "relu"},
+            "roofline": roofline, "cpu_baseline": cpu,
+            "call_ms": ms, "total_tflops": 3.0 * fwd_flop * steps / wall / 1e12}
+
+
 def step_costs(widths, batch, momentum):
     """Algorithmic flops and bytes of one training step (fp32)."""
     pw = sum(widths[l + 1] * widths[l] for l in range(len(widths) - 1))
@@ -145,9 +238,15 @@ def main():
         print(json.dumps(out))
         return
 
+    if args.workload in CONV_WORKLOADS:
+        assert torch.cuda.is_available(), "bench.py needs the GPU"
+        dn.lib()
+        print(json.dumps(bench_conv(args, CONV_WORKLOADS[args.workload])))
+        return
+
     table = workloads()
     if args.workload not in table:
-        sys.exit("unknown workload %r; choose from %s" % (args.workload, ", ".join(sorted(table))))
+        sys.exit("unknown workload %r; choose from %s" % (args.workload, ", ".join(sorted(list(table) + list(CONV_WORKLOADS)))))
     make, bound = table[args.workload]
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     dn.lib()   # fails loudly if libdn.so has not been built

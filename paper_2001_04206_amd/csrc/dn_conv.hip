@@ -109,7 +109,7 @@ __global__ __launch_bounds__(256) void conv_dw_kernel(ConvShape s, const float *
                                                       const float *__restrict__ delta, float *__restrict__ part,
                                                       int images_per_chunk)
 {
-    __shared__ float red[4][CO * KMAX * KMAX];
+    __shared__ float red[4][CO * KMAX * KMAX + CO];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int pix = s.Ho * s.Wo;
     const int c = blockIdx.x % s.Cin, og = blockIdx.x / s.Cin;
@@ -125,12 +125,18 @@ __global__ __launch_bounds__(256) void conv_dw_kernel(ConvShape s, const float *
         for (int u = 0; u < KMAX; ++u)
 #pragma unroll
             for (int v = 0; v < KMAX; ++v) acc[q][u][v] = 0.f;
+    float bsum[CO];   // the chunk's sum of delta per channel: the bias gradient (kept by the workgroups of c = 0)
+#pragma unroll
+    for (int q = 0; q < CO; ++q) bsum[q] = 0.f;
     for (int t = tid; t < total; t += 256) {
         const int b = b0 + t / pix, p = t % pix;
         const int i = p / s.Wo, j = p - i * s.Wo;
         float d[CO];
 #pragma unroll
-        for (int q = 0; q < CO; ++q) d[q] = delta[((size_t)b * s.Cout + oc[q]) * pix + p];
+        for (int q = 0; q < CO; ++q) {
+            d[q] = delta[((size_t)b * s.Cout + oc[q]) * pix + p];
+            bsum[q] += d[q];
+        }
         const float *x = X + ((size_t)b * s.Cin + c) * s.H * s.W;
         const int r0 = i * s.stride - s.pad, c0 = j * s.stride - s.pad;
 #pragma unroll
@@ -162,12 +168,24 @@ __global__ __launch_bounds__(256) void conv_dw_kernel(ConvShape s, const float *
                     if (lane == 0) red[wave][(q * KMAX + u) * KMAX + v] = w_sum;
                 }
             }
+    if (c == 0) {
+#pragma unroll
+        for (int q = 0; q < CO; ++q) {
+            const float b_sum = wave_sum(bsum[q]);
+            if (lane == 0) red[wave][CO * KMAX * KMAX + q] = b_sum;
+        }
+    }
     __syncthreads();
     const size_t filt = (size_t)s.Cout * s.Cin * s.KH * s.KW;
+    const size_t per_chunk = filt + s.Cout;   // filter sums, then bias sums
+    if (c == 0 && tid < CO && og * CO + tid < s.Cout) {
+        const int e = CO * KMAX * KMAX + tid;
+        part[(size_t)blockIdx.y * per_chunk + filt + og * CO + tid] = (red[0][e] + red[1][e]) + (red[2][e] + red[3][e]);
+    }
     for (int e = tid; e < CO * KMAX * KMAX; e += 256) {
         const int q = e / (KMAX * KMAX), u = (e / KMAX) % KMAX, v = e % KMAX;
         if (u < s.KH && v < s.KW && og * CO + q < s.Cout)
-            part[(size_t)blockIdx.y * filt + (((size_t)(og * CO + q) * s.Cin + c) * s.KH + u) * s.KW + v] =
+            part[(size_t)blockIdx.y * per_chunk + (((size_t)(og * CO + q) * s.Cin + c) * s.KH + u) * s.KW + v] =
                 (red[0][e] + red[1][e]) + (red[2][e] + red[3][e]);
     }
 }
@@ -182,7 +200,7 @@ __global__ __launch_bounds__(256) void conv_dw_slide_kernel(ConvShape s, const f
                                                             const float *__restrict__ delta, float *__restrict__ part,
                                                             int images_per_chunk)
 {
-    __shared__ float red[4][CO * KMAX * KMAX];
+    __shared__ float red[4][CO * KMAX * KMAX + CO];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int pix = s.Ho * s.Wo;
     const int c = blockIdx.x % s.Cin, og = blockIdx.x / s.Cin;
@@ -199,6 +217,9 @@ __global__ __launch_bounds__(256) void conv_dw_slide_kernel(ConvShape s, const f
         for (int u = 0; u < KMAX; ++u)
 #pragma unroll
             for (int v = 0; v < KMAX; ++v) acc[q][u][v] = 0.f;
+    float bsum[CO];   // the chunk's sum of delta per channel: the bias gradient (kept by the workgroups of c = 0)
+#pragma unroll
+    for (int q = 0; q < CO; ++q) bsum[q] = 0.f;
     for (int t = tid; t < total; t += 256) {
         const int b = b0 + t / s.Wo, j = t % s.Wo;
         const float *x = X + ((size_t)b * s.Cin + c) * s.H * s.W;
@@ -227,7 +248,10 @@ __global__ __launch_bounds__(256) void conv_dw_slide_kernel(ConvShape s, const f
             for (int v = 0; v < KMAX; ++v) win[KMAX - 1][v] = (row_ok && col_ok[v]) ? x[(size_t)r * s.W + c0 + v] : 0.f;
             float dv[CO];
 #pragma unroll
-            for (int q = 0; q < CO; ++q) dv[q] = d[(size_t)oc[q] * pix + (size_t)i * s.Wo];
+            for (int q = 0; q < CO; ++q) {
+                dv[q] = d[(size_t)oc[q] * pix + (size_t)i * s.Wo];
+                bsum[q] += dv[q];
+            }
 #pragma unroll
             for (int u = 0; u < KMAX; ++u) {
                 if (u >= off) {
@@ -253,43 +277,40 @@ __global__ __launch_bounds__(256) void conv_dw_slide_kernel(ConvShape s, const f
                     if (lane == 0) red[wave][(q * KMAX + u) * KMAX + v] = w_sum;
                 }
             }
+    if (c == 0) {
+#pragma unroll
+        for (int q = 0; q < CO; ++q) {
+            const float b_sum = wave_sum(bsum[q]);
+            if (lane == 0) red[wave][CO * KMAX * KMAX + q] = b_sum;
+        }
+    }
     __syncthreads();
     const size_t filt = (size_t)s.Cout * s.Cin * s.KH * s.KW;
+    const size_t per_chunk = filt + s.Cout;   // filter sums, then bias sums
+    if (c == 0 && tid < CO && og * CO + tid < s.Cout) {
+        const int e = CO * KMAX * KMAX + tid;
+        part[(size_t)blockIdx.y * per_chunk + filt + og * CO + tid] = (red[0][e] + red[1][e]) + (red[2][e] + red[3][e]);
+    }
     for (int e = tid; e < CO * KMAX * KMAX; e += 256) {
         const int q = e / (KMAX * KMAX), u = (e / KMAX) % KMAX, v = e % KMAX;
         if (u >= off && v < s.KW && og * CO + q < s.Cout)
-            part[(size_t)blockIdx.y * filt + (((size_t)(og * CO + q) * s.Cin + c) * s.KH + (u - off)) * s.KW + v] =
+            part[(size_t)blockIdx.y * per_chunk + (((size_t)(og * CO + q) * s.Cin + c) * s.KH + (u - off)) * s.KW + v] =
                 (red[0][e] + red[1][e]) + (red[2][e] + red[3][e]);
     }
 }
 
-// dW = (1/B) sum over chunks (in order) of part; one thread per filter element.
+// dW and dbias = (1/B) sum over chunks (in order) of part; one thread per filter element / channel.
 __global__ __launch_bounds__(256) void conv_dw_reduce_kernel(const float *__restrict__ part, float *__restrict__ dW,
-                                                             size_t filt, int chunks, float inv_b)
+                                                             float *__restrict__ dbias, size_t filt, int c_out,
+                                                             int chunks, float inv_b)
 {
     const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (e >= filt) return;
+    const size_t per_chunk = filt + c_out;
+    if (e >= per_chunk) return;
     float sum = 0.f;
-    for (int k = 0; k < chunks; ++k) sum += part[(size_t)k * filt + e];
-    dW[e] = sum * inv_b;
-}
-
-// dbias[o] = (1/B) sum_{b,i,j} delta[b][o][i][j]: one workgroup per output channel.
-__global__ __launch_bounds__(256) void conv_dbias_kernel(ConvShape s, const float *__restrict__ delta,
-                                                         float *__restrict__ dbias)
-{
-    __shared__ float red[4];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int pix = s.Ho * s.Wo, total = s.B * pix, o = blockIdx.x;
-    float part = 0.f;
-    for (int t = tid; t < total; t += 256) {
-        const int b = t / pix, p = t - b * pix;
-        part += delta[((size_t)b * s.Cout + o) * pix + p];
-    }
-    part = wave_sum(part);
-    if (lane == 0) red[wave] = part;
-    __syncthreads();
-    if (tid == 0) dbias[o] = ((red[0] + red[1]) + (red[2] + red[3])) / (float)s.B;
+    for (int k = 0; k < chunks; ++k) sum += part[(size_t)k * per_chunk + e];
+    if (e < filt) dW[e] = sum * inv_b;
+    else dbias[e - filt] = sum * inv_b;
 }
 
 // dX[b][c][r][col] = sum over (o, u, v) with r = i*stride+u-pad, col = j*stride+v-pad of
@@ -499,7 +520,7 @@ size_t dn_conv_backward_workspace_bytes(int32_t batch, int32_t c_in, int32_t h, 
     ConvShape s;
     if (conv_shape(batch, c_in, h, w, c_out, kh, kw, stride, pad, DN_ACT_LINEAR, s) != DN_OK) return 0;
     const DwPlan p = dw_plan(s);
-    return p.filt * (size_t)p.chunks * sizeof(float);
+    return (p.filt + (size_t)s.Cout) * (size_t)p.chunks * sizeof(float);
 }
 
 dn_status dn_conv_backward(const float *X_dev, const float *W_dev, const float *Y_dev, const float *dA_dev,
@@ -513,7 +534,7 @@ dn_status dn_conv_backward(const float *X_dev, const float *W_dev, const float *
     const dn_status st = conv_shape(batch, c_in, h, w, c_out, kh, kw, stride, pad, (int)act, s);
     if (st != DN_OK) return st;
     const DwPlan p = dw_plan(s);
-    if (workspace_bytes < p.filt * (size_t)p.chunks * sizeof(float)) return DN_ERR_SHAPE;
+    if (workspace_bytes < (p.filt + (size_t)s.Cout) * (size_t)p.chunks * sizeof(float)) return DN_ERR_SHAPE;
     if ((reinterpret_cast<uintptr_t>(workspace_dev) & 3) != 0) return DN_ERR_INVALID_ARG;
     hipStream_t stream = (hipStream_t)hip_stream;
     float *part = static_cast<float *>(workspace_dev);
@@ -543,10 +564,8 @@ dn_status dn_conv_backward(const float *X_dev, const float *W_dev, const float *
         hipLaunchKernelGGL((conv_dw_kernel<7, 2>), grid_dw, dim3(256), 0, stream, s, X_dev, delta_dev, part,
                            p.images_per_chunk);
     if (launched() != DN_OK) return DN_ERR_DEVICE;
-    hipLaunchKernelGGL(conv_dw_reduce_kernel, dim3((unsigned)((p.filt + 255) / 256)), dim3(256), 0, stream, part, dW_dev,
-                       p.filt, p.chunks, 1.0f / (float)s.B);
-    if (launched() != DN_OK) return DN_ERR_DEVICE;
-    hipLaunchKernelGGL(conv_dbias_kernel, dim3((unsigned)s.Cout), dim3(256), 0, stream, s, delta_dev, dbias_dev);
+    hipLaunchKernelGGL(conv_dw_reduce_kernel, dim3((unsigned)((p.filt + s.Cout + 255) / 256)), dim3(256), 0, stream, part,
+                       dW_dev, dbias_dev, p.filt, s.Cout, p.chunks, 1.0f / (float)s.B);
     if (launched() != DN_OK) return DN_ERR_DEVICE;
     if (dX_dev) {
         const int ci = s.Cin >= 8 ? 8 : (s.Cin >= 2 ? 4 : 1);

@@ -89,6 +89,110 @@ __global__ __launch_bounds__(256) void conv_forward_kernel(ConvShape s, const fl
         if (og * CO + q < s.Cout) Y[((size_t)b * s.Cout + og * CO + q) * pix + p] = conv_act(s.act, acc[q]);
 }
 
+// Stride 1, both directions.  The forward product and the input gradient of a stride-1 layer are
+// the same computation, a correlation of a multi-channel image with a filter bank:
+//   out[b][oc][i][j] = fin(bias[oc] + sum_{ic,u,v} w(oc, ic, u, v) in[b][ic][i+u-pad_h][j+v-pad_w])
+// forward: in = x, w = W[oc][ic][u][v], pads = pad; input gradient: in = delta, oc = the layer's input
+// channel, ic = its output channel, w = W[ic][oc][kh-1-u][kw-1-v] (the flipped filter),
+// pads = kh-1-pad and kw-1-pad, no bias, no activation.
+// A thread owns RT consecutive output rows of one column j for a group of CO output channels.  Per
+// input channel it loads the RT + kh - 1 input rows of its kw columns once into registers and
+// uses each value for up to kh x CO products; filter values come from LDS ([ic][tap][CO], staged a
+// range of input channels at a time) as 16-byte broadcasts.  No index arithmetic or bounds tests
+// in the product loops: rows and columns outside the image are loaded as zeros.
+struct CorrShape {
+    int B, Cin, H, W, Cout, KH, KW, pad_h, pad_w, Ho, Wo, act;
+    int w_out_stride, w_in_stride, flip;   // filter element (oc, ic, tap) at oc*w_out_stride + ic*w_in_stride + tap'
+};
+
+template <int CO, int RT, int KMAX>
+__global__ __launch_bounds__(256) void corr_rows_kernel(CorrShape s, const float *__restrict__ In,
+                                                        const float *__restrict__ Wt, const float *__restrict__ bias,
+                                                        float *__restrict__ Out)
+{
+    __shared__ __attribute__((aligned(16))) float wl[kStageFloats];
+    const int taps = s.KH * s.KW;
+    const int tiles = (s.Ho + RT - 1) / RT;
+    const int p = blockIdx.x * 256 + threadIdx.x;
+    const int og = blockIdx.y, b = blockIdx.z;
+    const bool live = p < tiles * s.Wo;
+    const int tile = live ? p / s.Wo : 0, j = live ? p - tile * s.Wo : 0;
+    const int i0 = tile * RT;
+    float acc[RT][CO];
+#pragma unroll
+    for (int q = 0; q < CO; ++q) {
+        const float bq = bias ? bias[min(og * CO + q, s.Cout - 1)] : 0.f;   // past the end: repeats, not stored
+#pragma unroll
+        for (int t = 0; t < RT; ++t) acc[t][q] = bq;
+    }
+    const int c0 = j - s.pad_w, r0 = i0 - s.pad_h;
+    bool col_ok[KMAX];
+#pragma unroll
+    for (int v = 0; v < KMAX; ++v) col_ok[v] = live && v < s.KW && c0 + v >= 0 && c0 + v < s.W;
+    const int per_stage = max(1, kStageFloats / (taps * CO));   // input channels per stage
+    for (int ic0 = 0; ic0 < s.Cin; ic0 += per_stage) {
+        const int n = min(per_stage, s.Cin - ic0);
+        __syncthreads();   // the previous stage has been used
+        for (int e = threadIdx.x; e < n * taps * CO; e += 256) {
+            const int q = e % CO, tap = (e / CO) % taps, cl = e / (CO * taps);
+            wl[e] = Wt[(size_t)min(og * CO + q, s.Cout - 1) * s.w_out_stride + (size_t)(ic0 + cl) * s.w_in_stride +
+                       (s.flip ? taps - 1 - tap : tap)];
+        }
+        __syncthreads();
+        for (int cl = 0; cl < n; ++cl) {
+            const float *x = In + ((size_t)b * s.Cin + ic0 + cl) * s.H * s.W;
+            float xw[RT + KMAX - 1][KMAX];
+#pragma unroll
+            for (int k = 0; k < RT + KMAX - 1; ++k) {
+                const int r = r0 + k;
+                const bool row_ok = k < RT + s.KH - 1 && r >= 0 && r < s.H;
+#pragma unroll
+                for (int v = 0; v < KMAX; ++v) xw[k][v] = (row_ok && col_ok[v]) ? x[(size_t)r * s.W + c0 + v] : 0.f;
+            }
+            const float *wc = wl + (size_t)cl * taps * CO;
+#pragma unroll
+            for (int u = 0; u < KMAX; ++u) {
+                if (u < s.KH) {
+#pragma unroll
+                    for (int v = 0; v < KMAX; ++v) {
+                        if (v < s.KW) {
+                            const float *wq = wc + (u * s.KW + v) * CO;
+                            float w8[CO];
+#pragma unroll
+                            for (int q = 0; q < CO; ++q) w8[q] = wq[q];
+#pragma unroll
+                            for (int t = 0; t < RT; ++t)
+#pragma unroll
+                                for (int q = 0; q < CO; ++q) acc[t][q] = fmaf(w8[q], xw[t + u][v], acc[t][q]);
+                        }
+                    }
+                }
+            }
+        }
+    }
+    if (!live) return;
+#pragma unroll
+    for (int t = 0; t < RT; ++t)
+#pragma unroll
+        for (int q = 0; q < CO; ++q)
+            if (i0 + t < s.Ho && og * CO + q < s.Cout)
+                Out[(((size_t)b * s.Cout + og * CO + q) * s.Ho + i0 + t) * s.Wo + j] = conv_act(s.act, acc[t][q]);
+}
+
+template <int CO>
+hipError_t launch_corr_rows(const CorrShape &s, const float *In, const float *Wt, const float *bias, float *Out,
+                            hipStream_t stream)
+{
+    const int kmax = s.KH > s.KW ? s.KH : s.KW;
+    const int rt = kmax <= 5 ? 4 : 2;
+    const int tiles = (s.Ho + rt - 1) / rt;
+    const dim3 grid((unsigned)((tiles * s.Wo + 255) / 256), (unsigned)((s.Cout + CO - 1) / CO), (unsigned)s.B);
+    if (kmax <= 3) hipLaunchKernelGGL((corr_rows_kernel<CO, 4, 3>), grid, dim3(256), 0, stream, s, In, Wt, bias, Out);
+    else if (kmax <= 5) hipLaunchKernelGGL((corr_rows_kernel<CO, 4, 5>), grid, dim3(256), 0, stream, s, In, Wt, bias, Out);
+    else hipLaunchKernelGGL((corr_rows_kernel<CO, 2, 7>), grid, dim3(256), 0, stream, s, In, Wt, bias, Out);
+    return hipGetLastError();
+}
+
 __global__ __launch_bounds__(256) void conv_delta_kernel(const float *__restrict__ dA, const float *__restrict__ Y,
                                                          float *__restrict__ delta, size_t count, int act)
 {
@@ -506,6 +610,13 @@ dn_status dn_conv_forward(const float *X_dev, const float *W_dev, const float *b
     if (st != DN_OK) return st;
     hipStream_t stream = (hipStream_t)hip_stream;
     const int co = s.Cout >= 8 ? 8 : 4;
+    if (s.stride == 1) {
+        const int taps = s.KH * s.KW;
+        const CorrShape c{s.B, s.Cin, s.H, s.W, s.Cout, s.KH, s.KW, s.pad, s.pad, s.Ho, s.Wo, s.act, s.Cin * taps, taps, 0};
+        const hipError_t e = co == 8 ? launch_corr_rows<8>(c, X_dev, W_dev, bias_dev, Y_dev, stream)
+                                     : launch_corr_rows<4>(c, X_dev, W_dev, bias_dev, Y_dev, stream);
+        return e == hipSuccess ? DN_OK : DN_ERR_DEVICE;
+    }
     const dim3 grid((unsigned)((s.Ho * s.Wo + 255) / 256), (unsigned)((s.Cout + co - 1) / co), (unsigned)s.B);
     if (co == 8)
         hipLaunchKernelGGL(conv_forward_kernel<8>, grid, dim3(256), 0, stream, s, X_dev, W_dev, bias_dev, Y_dev);
@@ -567,7 +678,15 @@ dn_status dn_conv_backward(const float *X_dev, const float *W_dev, const float *
     hipLaunchKernelGGL(conv_dw_reduce_kernel, dim3((unsigned)((p.filt + s.Cout + 255) / 256)), dim3(256), 0, stream, part,
                        dW_dev, dbias_dev, p.filt, s.Cout, p.chunks, 1.0f / (float)s.B);
     if (launched() != DN_OK) return DN_ERR_DEVICE;
-    if (dX_dev) {
+    if (dX_dev && s.stride == 1) {
+        // the input gradient as a correlation of delta with the flipped filters
+        const int taps = s.KH * s.KW;
+        const CorrShape c{s.B, s.Cout, s.Ho, s.Wo, s.Cin, s.KH, s.KW, s.KH - 1 - s.pad, s.KW - 1 - s.pad, s.H, s.W,
+                          DN_ACT_LINEAR, taps, s.Cin * taps, 1};
+        const hipError_t e = s.Cin >= 8 ? launch_corr_rows<8>(c, delta_dev, W_dev, nullptr, dX_dev, stream)
+                                        : launch_corr_rows<4>(c, delta_dev, W_dev, nullptr, dX_dev, stream);
+        if (e != hipSuccess) return DN_ERR_DEVICE;
+    } else if (dX_dev) {
         const int ci = s.Cin >= 8 ? 8 : (s.Cin >= 2 ? 4 : 1);
         const dim3 grid((unsigned)((s.H * s.W + 255) / 256), (unsigned)((s.Cin + ci - 1) / ci), (unsigned)s.B);
         if (ci == 8) hipLaunchKernelGGL(conv_dx_kernel<8>, grid, dim3(256), 0, stream, s, W_dev, delta_dev, dX_dev);

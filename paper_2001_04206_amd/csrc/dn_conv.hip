@@ -541,6 +541,35 @@ __global__ __launch_bounds__(256) void maxpool_backward_kernel(PoolShape s, cons
     dX[(size_t)plane * hw + p] = acc;
 }
 
+// Windows that tile the image exactly (stride = k, h and w multiples of k): every input pixel
+// belongs to one window, so a thread owns a window, finds its first maximum and writes all of the
+// window's input gradients (dY at the maximum, zero elsewhere).
+__global__ __launch_bounds__(256) void maxpool_backward_tiles_kernel(PoolShape s, const float *__restrict__ X,
+                                                                     const float *__restrict__ dY,
+                                                                     float *__restrict__ dX)
+{
+    const int pix = s.Ho * s.Wo;
+    const int p = blockIdx.x * 256 + threadIdx.x, plane = blockIdx.y;
+    if (p >= pix) return;
+    const int i = p / s.Wo, j = p - i * s.Wo;
+    const size_t base = (size_t)plane * s.H * s.W + (size_t)(i * s.K) * s.W + j * s.K;
+    const float *x = X + base;
+    float m = x[0];
+    int best = 0;
+    for (int u = 0; u < s.K; ++u)
+        for (int v = 0; v < s.K; ++v) {
+            const float xv = x[(size_t)u * s.W + v];
+            if (xv > m) {   // strictly greater: the first maximum wins
+                m = xv;
+                best = u * s.K + v;
+            }
+        }
+    const float g = dY[(size_t)plane * pix + p];
+    float *d = dX + base;
+    for (int u = 0; u < s.K; ++u)
+        for (int v = 0; v < s.K; ++v) d[(size_t)u * s.W + v] = (u * s.K + v == best) ? g : 0.f;
+}
+
 bool fits_int(long long v) { return v >= 1 && v <= 0x7fffffffLL; }
 
 dn_status conv_shape(int B, int Cin, int H, int W, int Cout, int KH, int KW, int stride, int pad, int act, ConvShape &s)
@@ -716,6 +745,12 @@ dn_status dn_maxpool_backward(const float *X_dev, const float *dY_dev, float *dX
     PoolShape s;
     const dn_status st = pool_shape(batch, channels, h, w, k, stride, s);
     if (st != DN_OK) return st;
+    if (s.stride == s.K && s.H % s.K == 0 && s.W % s.K == 0) {
+        const dim3 grid((unsigned)((s.Ho * s.Wo + 255) / 256), (unsigned)s.planes);
+        hipLaunchKernelGGL(maxpool_backward_tiles_kernel, grid, dim3(256), 0, (hipStream_t)hip_stream, s, X_dev, dY_dev,
+                           dX_dev);
+        return launched();
+    }
     const dim3 grid((unsigned)((s.H * s.W + 255) / 256), (unsigned)s.planes);
     hipLaunchKernelGGL(maxpool_backward_kernel, grid, dim3(256), 0, (hipStream_t)hip_stream, s, X_dev, dY_dev, dX_dev);
     return launched();

@@ -63,6 +63,40 @@ def test_conv_forward_and_backward(B, Cin, H, W, Cout, KH, KW, stride, pad, act)
     assert torch.equal(dW2, dW) and torch.equal(db2, db)
 
 
+def test_conv_and_pool_at_the_benchmark_shape():
+    """The layer pair bench.py times (128 x 32 x 32 x 32 -> 64 channels, 3x3, pad 1, ReLU, then 2x2
+    pooling), in the same launch configuration, every element against the checker."""
+    announce("conv + pool at the benchmark shape")
+    B, Cin, H, W, Cout, K = 128, 32, 32, 32, 64, 3
+    rng = np.random.default_rng(0)
+    X = rng.standard_normal((B, Cin, H, W)).astype(np.float32)
+    Wt = (rng.standard_normal((Cout, Cin, K, K)) * np.sqrt(2.0 / (Cin * K * K))).astype(np.float32)
+    b = (rng.standard_normal(Cout) * 0.1).astype(np.float32)
+    dP = rng.standard_normal((B, Cout, H // 2, W // 2)).astype(np.float32)
+    Yr = co.conv_forward("o32", X, Wt, b, 1, 1, RELU)
+    Pr = co.maxpool_forward("o32", Yr, 2, 2)
+    dYr = co.maxpool_backward("o32", Yr, dP, 2, 2)
+    delta_r, dX_r, dW_r, db_r = co.conv_backward("o32", X, Wt, Yr, dYr, 1, 1, RELU)
+    Xd, Wd = dev(X), dev(Wt)
+    Y = torch.empty(Yr.shape, dtype=torch.float32, device="cuda:0")
+    dn.dn_conv_forward(Xd, Wd, dev(b), Y, 1, 1, RELU)
+    assert_close(Y.cpu().numpy(), Yr, TOL, "Y")
+    # pooling and the backward pass from the checker's activations: a ReLU output within rounding
+    # of zero would otherwise put the two sides on different branches
+    Yd = dev(Yr)
+    P, dY = torch.empty(Pr.shape, dtype=torch.float32, device="cuda:0"), torch.empty_like(Yd)
+    dn.dn_maxpool_forward(Yd, P, 2, 2)
+    assert np.array_equal(P.cpu().numpy(), Pr)
+    dn.dn_maxpool_backward(Yd, dev(dP), dY, 2, 2)
+    assert np.array_equal(dY.cpu().numpy(), dYr)
+    delta, dX, dW, db = torch.empty_like(Yd), torch.empty_like(Xd), torch.empty_like(Wd), torch.empty(Cout, device="cuda:0")
+    dn.dn_conv_backward(Xd, Wd, Yd, dY, delta, dX, dW, db, 1, 1, RELU)
+    assert_close(delta.cpu().numpy(), delta_r, TOL, "delta")
+    assert_close(dW.cpu().numpy(), dW_r, TOL, "dW")
+    assert_close(db.cpu().numpy(), db_r, TOL, "dbias")
+    assert_close(dX.cpu().numpy(), dX_r, TOL, "dX")
+
+
 POOL_CASES = [((2, 3, 8, 8), 2, 2), ((1, 2, 7, 9), 3, 2), ((2, 1, 6, 6), 3, 1), ((1, 1, 5, 5), 5, 1),
               ((2, 2, 9, 7), 2, 3), ((3, 5, 33, 47), 3, 2), ((16, 16, 24, 24), 2, 2), ((2, 2, 4, 5), 1, 1)]
 

@@ -193,6 +193,189 @@ hipError_t launch_corr_rows(const CorrShape &s, const float *In, const float *Wt
     return hipGetLastError();
 }
 
+// The same correlation (stride 1) on the matrix cores, for layers wide enough to fill their 32 x 32
+// tiles.  Per image it is the product out[oc][pixel] = sum_k w[oc][k] patch[k][pixel] with
+// k = (input channel, tap).  A workgroup owns 32 OT output channels x (8 output rows x 32 columns);
+// wave r of its four owns output rows 2r and 2r + 1: 2 OT accumulator tiles of 32 channels x 32
+// pixels.  One matrix instruction (32x32x2) takes two k values: lane (idx, h) supplies, for k slot h,
+// the filter value of channel idx and the input value under pixel idx.  The two slots are two
+// input channels at the same tap, so the input value's LDS address is the pixel's base plus one
+// offset per (channel pair, tap) and there is no index arithmetic in the loop; every filter value
+// read from LDS serves two instructions and so does every input value (OT = 2).  Input channels
+// are staged through LDS eight at a time: the filters as [k][32 OT channels] with a row stride of
+// 80 words (staging writes run along k for a few channels at a time: stride 16 mod 32 spreads them
+// over the banks), the input as [channel][8 + kh - 1 rows][32 + kw - 1 columns], zeros outside
+// the image.  Filters must be stored [oc][ic][tap] (w_in_stride = taps, no flip): the input
+// gradient passes a flipped, transposed copy (conv_flip_filters_kernel).
+constexpr int MC_COLS = 32, MC_IC = 8, MC_WSTRIDE = 80;
+typedef float v16f_t __attribute__((ext_vector_type(16)));
+
+template <int OT, int RW, int KS>   // KS: filter edge known at compile time (3: the tap loop is unrolled), 0: any
+__global__ __launch_bounds__(256) void corr_mfma_kernel(CorrShape s, const float *__restrict__ In,
+                                                        const float *__restrict__ Wt, const float *__restrict__ bias,
+                                                        float *__restrict__ Out)
+{
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    constexpr int OC = 32 * OT, MC_ROWS = 4 * RW;
+    const int taps = s.KH * s.KW, kstage = MC_IC * taps;
+    const int prow = MC_ROWS + s.KH - 1, pcol = MC_COLS + s.KW - 1;   // staged input patch per channel
+    float *wl = lds;                                   // [kstage][MC_WSTRIDE]
+    float *pl = lds + (size_t)kstage * MC_WSTRIDE;     // [MC_IC][prow][pcol]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int idx = lane & 31, h = lane >> 5;
+    const int col_tiles = (s.Wo + MC_COLS - 1) / MC_COLS;
+    const int i0 = (blockIdx.x / col_tiles) * MC_ROWS, j0 = (blockIdx.x % col_tiles) * MC_COLS;
+    const int oc0 = blockIdx.y * OC, b = blockIdx.z;
+    v16f_t acc[OT][RW];
+#pragma unroll
+    for (int t = 0; t < OT; ++t)
+#pragma unroll
+        for (int q = 0; q < RW; ++q)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[t][q][r] = 0.f;
+    const int r_in0 = i0 - s.pad_h, c_in0 = j0 - s.pad_w;   // image position of the patch's corner
+    // staging roles: filters - four threads per output channel, each every fourth k of the stage;
+    // input - one thread per patch column, a wave per patch row in turn
+    const int w_ocl = tid >> 2, w_k0 = tid & 3;
+    const bool w_on = w_ocl < OC;
+    const int w_oc = min(oc0 + w_ocl, s.Cout - 1);
+    const bool w_real = oc0 + w_ocl < s.Cout;
+    for (int ic0 = 0; ic0 < s.Cin; ic0 += MC_IC) {
+        const int kvalid = min(MC_IC, s.Cin - ic0) * taps;   // k values of this stage that exist
+        __syncthreads();   // the previous stage has been used
+        // (loads in batches, all of a batch in flight before the first is stored)
+        constexpr int WB = 9, PB = 6;
+        if (w_on) {
+            const float *src = Wt + (size_t)w_oc * s.w_out_stride + (size_t)ic0 * taps;
+            for (int k0 = w_k0; k0 < kstage; k0 += 4 * WB) {
+                float tmp[WB];
+#pragma unroll
+                for (int m = 0; m < WB; ++m) {
+                    const int kl = k0 + 4 * m;
+                    tmp[m] = (w_real && kl < kvalid) ? src[kl] : 0.f;
+                }
+#pragma unroll
+                for (int m = 0; m < WB; ++m) {
+                    const int kl = k0 + 4 * m;
+                    if (kl < kstage) wl[kl * MC_WSTRIDE + w_ocl] = tmp[m];
+                }
+            }
+        }
+        for (int row0 = wave; row0 < MC_IC * prow; row0 += 4 * PB) {
+            float tmp[PB];
+#pragma unroll
+            for (int m = 0; m < PB; ++m) {
+                const int row = row0 + 4 * m;
+                const int icl = row / prow, pr = row - icl * prow;   // uniform across the wave
+                const int r = r_in0 + pr, c = c_in0 + lane, ic = ic0 + icl;
+                const bool ok = row < MC_IC * prow && lane < pcol && ic < s.Cin && r >= 0 && r < s.H && c >= 0 && c < s.W;
+                tmp[m] = ok ? In[(((size_t)b * s.Cin + ic) * s.H + r) * s.W + c] : 0.f;
+            }
+#pragma unroll
+            for (int m = 0; m < PB; ++m) {
+                const int row = row0 + 4 * m;
+                if (row < MC_IC * prow && lane < pcol) pl[row * pcol + lane] = tmp[m];
+            }
+        }
+        __syncthreads();
+        // k slot h of every instruction: input channel 2 * pair + h at one tap
+        const float *wa = wl + (size_t)(h * taps) * MC_WSTRIDE + idx;
+        const float *pb = pl + (size_t)h * prow * pcol + (RW * wave) * pcol + idx;
+#pragma unroll
+        for (int pair = 0; pair < MC_IC / 2; ++pair) {
+            const float *wp = wa + (size_t)(2 * pair * taps) * MC_WSTRIDE;
+            const float *pp = pb + (size_t)(2 * pair) * prow * pcol;
+            auto one_tap = [&](int tap, int po) {   // po: patch offset u * pcol + v of the tap
+                float xv[RW];
+#pragma unroll
+                for (int q = 0; q < RW; ++q) xv[q] = pp[po + q * pcol];
+                const float *wq = wp + tap * MC_WSTRIDE;
+#pragma unroll
+                for (int t = 0; t < OT; ++t) {
+                    const float wv = wq[32 * t];
+#pragma unroll
+                    for (int q = 0; q < RW; ++q)
+                        acc[t][q] = __builtin_amdgcn_mfma_f32_32x32x2f32(wv, xv[q], acc[t][q], 0, 0, 0);
+                }
+            };
+            if (KS > 0) {
+#pragma unroll
+                for (int u = 0; u < KS; ++u)
+#pragma unroll
+                    for (int v = 0; v < KS; ++v) one_tap(u * KS + v, u * pcol + v);
+            } else {
+                for (int u = 0; u < s.KH; ++u)
+                    for (int v = 0; v < s.KW; ++v) one_tap(u * s.KW + v, u * pcol + v);
+            }
+        }
+    }
+    // register r of lane (idx, h): output channel 8 (r / 4) + 4 h + r % 4 of the tile, pixel idx of the row
+    const int j = j0 + idx;
+    if (j >= s.Wo) return;
+#pragma unroll
+    for (int q = 0; q < RW; ++q) {
+        const int i = i0 + RW * wave + q;
+        if (i >= s.Ho) continue;
+#pragma unroll
+        for (int t = 0; t < OT; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int oc = oc0 + 32 * t + 8 * (r >> 2) + 4 * h + (r & 3);
+                if (oc < s.Cout)
+                    Out[(((size_t)b * s.Cout + oc) * s.Ho + i) * s.Wo + j] = conv_act(s.act, acc[t][q][r] + (bias ? bias[oc] : 0.f));
+            }
+    }
+}
+
+// Wide enough for the matrix-core form?  (Narrow layers would mostly multiply padding.)
+bool corr_mfma_fits(const CorrShape &s)
+{
+    return s.Cout >= 32 && s.Cin >= 8 && s.Wo >= 16 && s.w_in_stride == s.KH * s.KW && !s.flip;
+}
+
+template <int OT, int RW, int KS>
+hipError_t launch_corr_mfma_as(const CorrShape &s, const float *In, const float *Wt, const float *bias, float *Out,
+                               hipStream_t stream)
+{
+    constexpr int rows = 4 * RW;
+    const int taps = s.KH * s.KW;
+    const size_t lds = sizeof(float) * ((size_t)MC_IC * taps * MC_WSTRIDE +
+                                        (size_t)MC_IC * (rows + s.KH - 1) * (MC_COLS + s.KW - 1));
+    static bool attr_set = false;   // 7 x 7 filters need up to 146 KB, more than the default limit of dynamic LDS
+    if (!attr_set) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&corr_mfma_kernel<OT, RW, KS>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const dim3 grid((unsigned)(((s.Ho + rows - 1) / rows) * ((s.Wo + MC_COLS - 1) / MC_COLS)),
+                    (unsigned)((s.Cout + 32 * OT - 1) / (32 * OT)), (unsigned)s.B);
+    hipLaunchKernelGGL((corr_mfma_kernel<OT, RW, KS>), grid, dim3(256), lds, stream, s, In, Wt, bias, Out);
+    return hipGetLastError();
+}
+
+hipError_t launch_corr_mfma(const CorrShape &s, const float *In, const float *Wt, const float *bias, float *Out,
+                            hipStream_t stream)
+{
+    const bool k3 = s.KH == 3 && s.KW == 3;
+    if (s.Cout > 32)
+        return k3 ? launch_corr_mfma_as<2, 2, 3>(s, In, Wt, bias, Out, stream)
+                  : launch_corr_mfma_as<2, 2, 0>(s, In, Wt, bias, Out, stream);
+    return k3 ? launch_corr_mfma_as<1, 2, 3>(s, In, Wt, bias, Out, stream)
+              : launch_corr_mfma_as<1, 2, 0>(s, In, Wt, bias, Out, stream);
+}
+
+// Wf[c][o][tap] = W[o][c][taps - 1 - tap]: the filters of the input gradient seen as a correlation.
+__global__ __launch_bounds__(256) void conv_flip_filters_kernel(const float *__restrict__ Wt, float *__restrict__ Wf,
+                                                                int c_out, int c_in, int taps)
+{
+    const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= (size_t)c_out * c_in * taps) return;
+    const int tap = (int)(e % taps);
+    const int o = (int)((e / taps) % c_out), c = (int)(e / ((size_t)taps * c_out));
+    Wf[e] = Wt[((size_t)o * c_in + c) * taps + (taps - 1 - tap)];
+}
+
 __global__ __launch_bounds__(256) void conv_delta_kernel(const float *__restrict__ dA, const float *__restrict__ Y,
                                                          float *__restrict__ delta, size_t count, int act)
 {
@@ -642,8 +825,9 @@ dn_status dn_conv_forward(const float *X_dev, const float *W_dev, const float *b
     if (s.stride == 1) {
         const int taps = s.KH * s.KW;
         const CorrShape c{s.B, s.Cin, s.H, s.W, s.Cout, s.KH, s.KW, s.pad, s.pad, s.Ho, s.Wo, s.act, s.Cin * taps, taps, 0};
-        const hipError_t e = co == 8 ? launch_corr_rows<8>(c, X_dev, W_dev, bias_dev, Y_dev, stream)
-                                     : launch_corr_rows<4>(c, X_dev, W_dev, bias_dev, Y_dev, stream);
+        const hipError_t e = corr_mfma_fits(c) ? launch_corr_mfma(c, X_dev, W_dev, bias_dev, Y_dev, stream)
+                             : co == 8         ? launch_corr_rows<8>(c, X_dev, W_dev, bias_dev, Y_dev, stream)
+                                               : launch_corr_rows<4>(c, X_dev, W_dev, bias_dev, Y_dev, stream);
         return e == hipSuccess ? DN_OK : DN_ERR_DEVICE;
     }
     const dim3 grid((unsigned)((s.Ho * s.Wo + 255) / 256), (unsigned)((s.Cout + co - 1) / co), (unsigned)s.B);
@@ -712,8 +896,19 @@ dn_status dn_conv_backward(const float *X_dev, const float *W_dev, const float *
         const int taps = s.KH * s.KW;
         const CorrShape c{s.B, s.Cout, s.Ho, s.Wo, s.Cin, s.KH, s.KW, s.KH - 1 - s.pad, s.KW - 1 - s.pad, s.H, s.W,
                           DN_ACT_LINEAR, taps, s.Cin * taps, 1};
-        const hipError_t e = s.Cin >= 8 ? launch_corr_rows<8>(c, delta_dev, W_dev, nullptr, dX_dev, stream)
-                                        : launch_corr_rows<4>(c, delta_dev, W_dev, nullptr, dX_dev, stream);
+        // on the matrix cores with a flipped, transposed copy of the filters (in the workspace, whose partial
+        // sums have been consumed by now)
+        const CorrShape cm{c.B, c.Cin, c.H, c.W, c.Cout, c.KH, c.KW, c.pad_h, c.pad_w, c.Ho, c.Wo, c.act, s.Cout * taps, taps, 0};
+        hipError_t e;
+        if (corr_mfma_fits(cm)) {
+            hipLaunchKernelGGL(conv_flip_filters_kernel, dim3((unsigned)((p.filt + 255) / 256)), dim3(256), 0, stream, W_dev,
+                               part, s.Cout, s.Cin, taps);
+            e = hipGetLastError();
+            if (e == hipSuccess) e = launch_corr_mfma(cm, delta_dev, part, nullptr, dX_dev, stream);
+        } else {
+            e = s.Cin >= 8 ? launch_corr_rows<8>(c, delta_dev, W_dev, nullptr, dX_dev, stream)
+                           : launch_corr_rows<4>(c, delta_dev, W_dev, nullptr, dX_dev, stream);
+        }
         if (e != hipSuccess) return DN_ERR_DEVICE;
     } else if (dX_dev) {
         const int ci = s.Cin >= 8 ? 8 : (s.Cin >= 2 ? 4 : 1);

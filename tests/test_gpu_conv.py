@@ -23,6 +23,11 @@ CONV_CASES = [
     (4, 3, 33, 31, 9, 3, 3, 3, 0, TANH),          # stride 3, ragged
     (1, 16, 1, 1, 8, 1, 1, 1, 0, SIG),            # one-pixel images: a dense layer
     (16, 8, 28, 28, 16, 5, 5, 1, 0, RELU),        # the size of a small image classifier's second layer
+    # wide enough for the matrix-core form (>= 32 output channels, >= 8 input channels, >= 16 columns):
+    (2, 9, 21, 19, 35, 3, 3, 1, 1, TANH),         # forward on the matrix cores; ragged channels, rows and columns
+    (2, 40, 18, 37, 33, 5, 3, 1, 2, SIG),         # forward and input gradient; non-square filter, two column tiles
+    (1, 8, 20, 40, 32, 7, 7, 1, 3, TANH),         # largest filter: the biggest LDS stage
+    (3, 64, 16, 16, 64, 3, 3, 1, 0, RELU),        # no padding: the input gradient pads by kh - 1
 ]
 
 

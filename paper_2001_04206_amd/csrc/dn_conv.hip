@@ -799,6 +799,12 @@ DwPlan dw_plan(const ConvShape &s)
     if (chunks > s.B) chunks = s.B;
     if (chunks < 1) chunks = 1;
     p.images_per_chunk = (int)((s.B + chunks - 1) / chunks);
+    // the stride-1 kernel gives a thread one output column of one image: a chunk should hold enough
+    // images to keep a workgroup's 256 threads busy
+    if (s.stride == 1) {
+        const int fill = (256 + s.Wo - 1) / s.Wo;
+        if (p.images_per_chunk < fill) p.images_per_chunk = fill < s.B ? fill : s.B;
+    }
     p.chunks = (s.B + p.images_per_chunk - 1) / p.images_per_chunk;
     p.filt = (size_t)s.Cout * s.Cin * s.KH * s.KW;
     return p;

@@ -1,8 +1,10 @@
 // Convolutional and maximum-pooling layers, forward and backward, as stateless calls on device
 // tensors (the layer types the paper's engine offers besides the fully connected and softmax ones
 // and names as the next to accelerate; it gives no formulas, these are the usual definitions, stated
-// in include/dn.h).  Direct (gather) form throughout: every output element is owned by one thread or
-// one workgroup, so nothing is accumulated with atomics and every sum has a fixed order.
+// in include/dn.h).  Gather form throughout: every output element is owned by one thread, wave or
+// workgroup, so nothing is accumulated with atomics and every sum has a fixed order.  Stride-1
+// layers wide enough for 32 x 32 tiles run their forward product and input gradient on the matrix
+// cores (corr_mfma_kernel); everything else uses register-tiled vector kernels.
 #include "dn_internal.h"
 #include "dn_wave.h"
 

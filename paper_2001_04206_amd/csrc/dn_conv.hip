@@ -588,16 +588,212 @@ __global__ __launch_bounds__(256) void conv_dw_slide_kernel(ConvShape s, const f
     }
 }
 
+// The stride-1 filter gradient of 3 x 3 filters on the matrix cores, for wide layers.  Per image it
+// is the product dW[oc][n] = sum_pixel delta[oc][pixel] xs[n][pixel] with n = (input channel, tap) and
+// xs the input shifted by the tap.  A workgroup of four waves owns 64 output channels, a group of up
+// to 17 input channels (153 columns n in five 32-column tiles) and a part of the batch's pixels
+// (one image, or a band of its rows).  Wave w owns column tile w over all pixels and column tile
+// 4 over a quarter of them (the four quarters are added through LDS at the end, in wave order),
+// each for both 32-channel halves: four accumulator tiles.  One matrix instruction takes two
+// pixels: lane (idx, h) supplies delta of channel idx and the input under its column, both at
+// pixel 2 t + h; one input value read from LDS serves both channel halves.  The pixels are walked
+// in blocks of 4 output rows x 32 columns staged through LDS - delta as [channel][128 pixels] (row
+// stride 129 words; read from memory 16 bytes at a time), the input as [channel][6][34] with zeros
+// outside the image - all of a block's loads requested before the first is stored.  A column's
+// LDS address is a per-lane base (its channel and tap, and the lane's pixel of the pair) plus a
+// constant per pixel pair.  The partial result goes to part[chunk][oc][ic][tap] like the other
+// filter-gradient kernels', the bias sums (input-channel group 0: sums of the delta values the
+// workgroup stages) behind it; conv_dw_reduce_kernel adds the chunks.
+constexpr int DWM_THREADS = 256, DWM_IG = 17, DWM_DSTRIDE = 129, DWM_PROW = 6, DWM_PCOL = 34;
+constexpr int DWM_DP = (2048 + DWM_THREADS - 1) / DWM_THREADS;                               // delta pieces per thread
+constexpr int DWM_XP = (DWM_IG * DWM_PROW * DWM_PCOL + DWM_THREADS - 1) / DWM_THREADS;   // input values per thread
+
+__global__ __launch_bounds__(DWM_THREADS, 3) void conv_dw_mfma_kernel(ConvShape s, const float *__restrict__ X,
+                                                                      const float *__restrict__ delta,
+                                                                      float *__restrict__ part, int ig, int bands,
+                                                                      int rows_per_band, int images_per_chunk,
+                                                                      int delta_vec)
+{
+    __shared__ __attribute__((aligned(16))) float dl[64 * DWM_DSTRIDE];
+    __shared__ float xl[DWM_IG * DWM_PROW * DWM_PCOL];
+    constexpr int taps = 9;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int idx = lane & 31, h = lane >> 5;
+    const int groups = (s.Cin + ig - 1) / ig;
+    const int icg = blockIdx.x % groups, ocg = blockIdx.x / groups;
+    const int ic0 = icg * ig, oc0 = ocg * 64;
+    const int nic = min(ig, s.Cin - ic0);   // input channels of this workgroup that exist
+    const int band = blockIdx.y % bands;
+    const int b_lo = (blockIdx.y / bands) * images_per_chunk, b_hi = min(s.B, b_lo + images_per_chunk);
+    const int row_lo = band * rows_per_band, row_hi = min(s.Ho, row_lo + rows_per_band);
+    const int pix = s.Ho * s.Wo;
+    // a column's channel and tap as an offset into the staged input (0 for columns past the last one)
+    auto column_base = [&](int n) {
+        const int n_ic = n / taps, n_tap = n - n_ic * taps;
+        return n < nic * taps ? (n_ic * DWM_PROW + n_tap / 3) * DWM_PCOL + n_tap % 3 : 0;
+    };
+    const int n_own = 32 * wave + idx, n_shared = 128 + idx;
+    const bool shared_on = nic * taps > 128;   // the fifth tile has columns
+    const float *xb = xl + column_base(n_own) + h;
+    const float *xs = xl + column_base(n_shared) + h;
+    const float *da = dl + idx * DWM_DSTRIDE + h;
+    v16f_t acc0, acc1, acc2, acc3;   // own tile: channels 0..31, 32..63; shared tile likewise
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc0[r] = acc1[r] = acc2[r] = acc3[r] = 0.f;
+    typedef float v4_t __attribute__((ext_vector_type(4)));
+    float bsum[DWM_DP];   // sums of the delta values this thread stages, per staged piece (a piece has one channel)
+#pragma unroll
+    for (int m = 0; m < DWM_DP; ++m) bsum[m] = 0.f;
+    for (int b = b_lo; b < b_hi; ++b)
+    for (int i0 = row_lo; i0 < row_hi; i0 += 4)
+        for (int j0 = 0; j0 < s.Wo; j0 += 32) {
+            __syncthreads();   // the previous block has been used
+            // The staging indices are recomputed from the thread index in every block rather than
+            // kept in registers across the product loop (the empty asm hides that they repeat).
+            int st = tid;
+            asm volatile("" : "+v"(st));
+            // delta: 64 channels x 4 rows x 8 pieces of four pixels = 2048 pieces; input: nic x 6 x 34 values
+            v4_t dreg[DWM_DP];
+            float xreg[DWM_XP];
+            const float *dblk = delta + ((size_t)b * s.Cout + oc0) * pix + (size_t)i0 * s.Wo + j0;
+#pragma unroll
+            for (int m = 0; m < DWM_DP; ++m) {
+                const int e = st + DWM_THREADS * m;
+                const int q = e & 7, row = (e >> 3) & 3, ocl = e >> 5;
+                const bool ok = e < 2048 && oc0 + ocl < s.Cout && i0 + row < row_hi && j0 + 4 * q < s.Wo;   // w_out is a multiple of 4
+                v4_t v = {0.f, 0.f, 0.f, 0.f};
+                if (ok) {
+                    const float *src = dblk + (unsigned)(ocl * pix + row * s.Wo + 4 * q);
+                    if (delta_vec) v = *reinterpret_cast<const v4_t *>(src);   // the caller's pointer is 16-byte aligned
+                    else { v[0] = src[0]; v[1] = src[1]; v[2] = src[2]; v[3] = src[3]; }
+                }
+                dreg[m] = v;
+            }
+            const float *xblk = X + ((size_t)b * s.Cin + ic0) * s.H * s.W;
+#pragma unroll
+            for (int m = 0; m < DWM_XP; ++m) {
+                const int e = st + DWM_THREADS * m;
+                const int c = e % DWM_PCOL, pr = (e / DWM_PCOL) % DWM_PROW, icl = e / (DWM_PCOL * DWM_PROW);
+                const int r_img = i0 - s.pad + pr, c_img = j0 - s.pad + c;
+                // rows beyond the band carry no delta of this workgroup but are still inputs of its last rows
+                const bool ok = icl < nic && r_img >= 0 && r_img < s.H && c_img >= 0 && c_img < s.W;
+                xreg[m] = ok ? xblk[(unsigned)((icl * s.H + r_img) * s.W + c_img)] : 0.f;
+            }
+#pragma unroll
+            for (int m = 0; m < DWM_DP; ++m) {
+                const int e = st + DWM_THREADS * m;
+                if (e < 2048) {
+                    float *dst = dl + (e >> 5) * DWM_DSTRIDE + ((e >> 3) & 3) * 32 + 4 * (e & 7);
+                    dst[0] = dreg[m][0]; dst[1] = dreg[m][1]; dst[2] = dreg[m][2]; dst[3] = dreg[m][3];
+                    bsum[m] += (dreg[m][0] + dreg[m][1]) + (dreg[m][2] + dreg[m][3]);
+                }
+            }
+#pragma unroll
+            for (int m = 0; m < DWM_XP; ++m) {
+                const int e = st + DWM_THREADS * m;
+                if (e < DWM_IG * DWM_PROW * DWM_PCOL) xl[e] = xreg[m];
+            }
+            __syncthreads();
+            // 64 pixel pairs: pair t holds pixels 2 t and 2 t + 1 of block row t / 16; the wave
+            // multiplies the shared tile over block row `wave`.  (The lane's half h is in its base
+            // addresses, so every offset below is a constant.)
+#pragma unroll
+            for (int row = 0; row < 4; ++row) {
+                if (row == wave && shared_on) {
+#pragma unroll
+                    for (int t = 16 * row; t < 16 * row + 16; ++t) {
+                        const int xo = (t >> 4) * DWM_PCOL + ((2 * t) & 31);
+                        const float d0 = da[2 * t], d1 = da[32 * DWM_DSTRIDE + 2 * t];
+                        const float x = xb[xo], x4 = xs[xo];
+                        acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(d0, x, acc0, 0, 0, 0);
+                        acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(d1, x, acc1, 0, 0, 0);
+                        acc2 = __builtin_amdgcn_mfma_f32_32x32x2f32(d0, x4, acc2, 0, 0, 0);
+                        acc3 = __builtin_amdgcn_mfma_f32_32x32x2f32(d1, x4, acc3, 0, 0, 0);
+                    }
+                } else {
+#pragma unroll
+                    for (int t = 16 * row; t < 16 * row + 16; ++t) {
+                        const float x = xb[(t >> 4) * DWM_PCOL + ((2 * t) & 31)];
+                        acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(da[2 * t], x, acc0, 0, 0, 0);
+                        acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(da[32 * DWM_DSTRIDE + 2 * t], x, acc1, 0, 0, 0);
+                    }
+                }
+            }
+        }
+    // register r of lane (idx, h): output channel 8 (r / 4) + 4 h + r % 4 of the tile, the lane's column
+    const size_t filt = (size_t)s.Cout * s.Cin * taps;
+    const size_t per_chunk = filt + s.Cout;
+    float *out = part + (size_t)blockIdx.y * per_chunk;
+    if (n_own < nic * taps) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int ocl = 8 * (r >> 2) + 4 * h + (r & 3);
+            if (oc0 + ocl < s.Cout) out[((size_t)(oc0 + ocl) * s.Cin + ic0) * taps + n_own] = acc0[r];
+            if (oc0 + 32 + ocl < s.Cout) out[((size_t)(oc0 + 32 + ocl) * s.Cin + ic0) * taps + n_own] = acc1[r];
+        }
+    }
+    // the shared tile: every wave leaves its quarter in LDS as [wave][register][lane]; wave w
+    // then adds the four quarters of registers 8 w .. 8 w + 7 (of 32: both channel halves)
+    __syncthreads();
+    float *quarter = dl;   // 4 * 32 * 64 words
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        quarter[(wave * 32 + r) * 64 + lane] = acc2[r];
+        quarter[(wave * 32 + 16 + r) * 64 + lane] = acc3[r];
+    }
+    __syncthreads();
+    if (n_shared < nic * taps) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int rr = 8 * wave + k;   // 0..15: channels 0..31, 16..31: channels 32..63
+            float sum = quarter[rr * 64 + lane];
+#pragma unroll
+            for (int w = 1; w < 4; ++w) sum += quarter[(w * 32 + rr) * 64 + lane];
+            const int r = rr & 15;
+            const int ocl = 32 * (rr >> 4) + 8 * (r >> 2) + 4 * h + (r & 3);
+            if (oc0 + ocl < s.Cout) out[((size_t)(oc0 + ocl) * s.Cin + ic0) * taps + n_shared] = sum;
+        }
+    }
+    if (icg == 0) {
+        // piece e = tid + 256 m belongs to channel e >> 5: add the pieces per channel through LDS, in order
+        __syncthreads();
+        float *red = dl;   // [2048] piece sums
+#pragma unroll
+        for (int m = 0; m < DWM_DP; ++m) {
+            const int e = tid + DWM_THREADS * m;
+            if (e < 2048) red[e] = bsum[m];
+        }
+        __syncthreads();
+        if (tid < 64 && oc0 + tid < s.Cout) {
+            float sum = 0.f;
+            for (int k = 0; k < 32; ++k) sum += red[tid * 32 + k];
+            out[filt + oc0 + tid] = sum;
+        }
+    }
+}
+
 // dW and dbias = (1/B) sum over chunks (in order) of part; one thread per filter element / channel.
 __global__ __launch_bounds__(256) void conv_dw_reduce_kernel(const float *__restrict__ part, float *__restrict__ dW,
                                                              float *__restrict__ dbias, size_t filt, int c_out,
                                                              int chunks, float inv_b)
 {
-    const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
+    // 32 elements per block; the chunks are cut into 8 runs, one per group of 32 threads, whose
+    // sums are added in run order
+    __shared__ float run_sum[8][32];
+    const int el = threadIdx.x & 31, run = threadIdx.x >> 5;
+    const size_t e = (size_t)blockIdx.x * 32 + el;
     const size_t per_chunk = filt + c_out;
-    if (e >= per_chunk) return;
+    const int per_run = (chunks + 7) / 8;
+    const int k_lo = run * per_run, k_hi = min(chunks, k_lo + per_run);
     float sum = 0.f;
-    for (int k = 0; k < chunks; ++k) sum += part[(size_t)k * per_chunk + e];
+    if (e < per_chunk) {
+#pragma unroll 8
+        for (int k = k_lo; k < k_hi; ++k) sum += part[(size_t)k * per_chunk + e];
+    }
+    run_sum[run][el] = sum;
+    __syncthreads();
+    if (run != 0 || e >= per_chunk) return;
+    for (int r = 1; r < 8; ++r) sum += run_sum[r][el];
     if (e < filt) dW[e] = sum * inv_b;
     else dbias[e - filt] = sum * inv_b;
 }
@@ -788,6 +984,7 @@ dn_status launched() { return hipGetLastError() == hipSuccess ? DN_OK : DN_ERR_D
 struct DwPlan {
     int co, groups, chunks, images_per_chunk;
     size_t filt;
+    int mfma_ig, bands, rows_per_band;   // mfma_ig > 0: the matrix-core kernel (chunks = batch x bands)
 };
 
 DwPlan dw_plan(const ConvShape &s)
@@ -809,6 +1006,32 @@ DwPlan dw_plan(const ConvShape &s)
     }
     p.chunks = (s.B + p.images_per_chunk - 1) / p.images_per_chunk;
     p.filt = (size_t)s.Cout * s.Cin * s.KH * s.KW;
+    p.mfma_ig = 0;
+    p.bands = 1;
+    p.rows_per_band = s.Ho;
+    if (s.stride == 1 && s.KH == 3 && s.KW == 3 && s.Cout >= 32 && s.Cin >= 8 && s.Wo >= 16 && s.Wo % 4 == 0) {
+        const int groups = (s.Cin + DWM_IG - 1) / DWM_IG;
+        const int ig = (s.Cin + groups - 1) / groups;   // even groups
+        // about three workgroups per CU: several images per chunk if the batch gives more, else
+        // one image per chunk cut into bands of rows
+        const long wg_per_image = (long)groups * ((s.Cout + 63) / 64);
+        const long want = 768;
+        int ipc = (int)(wg_per_image * s.B / want);
+        if (ipc < 1) ipc = 1;
+        int bands = ipc > 1 ? 1 : (int)((want + wg_per_image * s.B - 1) / (wg_per_image * s.B));
+        const int max_bands = (s.Ho + 3) / 4;
+        if (bands > max_bands) bands = max_bands;
+        const int rows = ((s.Ho + bands - 1) / bands + 3) / 4 * 4;   // whole blocks of four rows
+        bands = (s.Ho + rows - 1) / rows;
+        const int image_groups = (s.B + ipc - 1) / ipc;
+        if (wg_per_image * image_groups * bands >= 192) {   // else too few workgroups to be worth it
+            p.mfma_ig = ig;
+            p.bands = bands;
+            p.rows_per_band = rows;
+            p.images_per_chunk = ipc;
+            p.chunks = image_groups * bands;
+        }
+    }
     return p;
 }
 
@@ -877,7 +1100,13 @@ dn_status dn_conv_backward(const float *X_dev, const float *W_dev, const float *
                        s.act);
     if (launched() != DN_OK) return DN_ERR_DEVICE;
     const dim3 grid_dw((unsigned)(p.groups * s.Cin), (unsigned)p.chunks);
-    if (s.stride == 1 && p.co == 8)
+    if (p.mfma_ig > 0) {
+        const int groups = (s.Cin + p.mfma_ig - 1) / p.mfma_ig;
+        const dim3 grid((unsigned)(groups * ((s.Cout + 63) / 64)), (unsigned)p.chunks);
+        hipLaunchKernelGGL(conv_dw_mfma_kernel, grid, dim3(DWM_THREADS), 0, stream, s, X_dev, delta_dev, part, p.mfma_ig,
+                           p.bands, p.rows_per_band, p.images_per_chunk,
+                           (int)(reinterpret_cast<uintptr_t>(delta_dev) % 16 == 0));
+    } else if (s.stride == 1 && p.co == 8)
         hipLaunchKernelGGL((conv_dw_slide_kernel<3, 8>), grid_dw, dim3(256), 0, stream, s, X_dev, delta_dev, part,
                            p.images_per_chunk);
     else if (s.stride == 1 && p.co == 4)
@@ -896,7 +1125,7 @@ dn_status dn_conv_backward(const float *X_dev, const float *W_dev, const float *
         hipLaunchKernelGGL((conv_dw_kernel<7, 2>), grid_dw, dim3(256), 0, stream, s, X_dev, delta_dev, part,
                            p.images_per_chunk);
     if (launched() != DN_OK) return DN_ERR_DEVICE;
-    hipLaunchKernelGGL(conv_dw_reduce_kernel, dim3((unsigned)((p.filt + s.Cout + 255) / 256)), dim3(256), 0, stream, part,
+    hipLaunchKernelGGL(conv_dw_reduce_kernel, dim3((unsigned)((p.filt + s.Cout + 31) / 32)), dim3(256), 0, stream, part,
                        dW_dev, dbias_dev, p.filt, s.Cout, p.chunks, 1.0f / (float)s.B);
     if (launched() != DN_OK) return DN_ERR_DEVICE;
     if (dX_dev && s.stride == 1) {

@@ -28,6 +28,11 @@ CONV_CASES = [
     (2, 40, 18, 37, 33, 5, 3, 1, 2, SIG),         # forward and input gradient; non-square filter, two column tiles
     (1, 8, 20, 40, 32, 7, 7, 1, 3, TANH),         # largest filter: the biggest LDS stage
     (3, 64, 16, 16, 64, 3, 3, 1, 0, RELU),        # no padding: the input gradient pads by kh - 1
+    # 3 x 3, stride 1, output width a multiple of 4 and enough workgroups: the filter gradient on the matrix cores
+    (16, 20, 22, 20, 35, 3, 3, 1, 1, TANH),       # two channel groups of 10 (no fifth tile), ragged bands and channels
+    (16, 33, 9, 36, 70, 3, 3, 1, 1, SIG),         # groups of 17 and 16, two channel blocks, two column blocks
+    (48, 16, 18, 18, 64, 3, 3, 1, 0, RELU),       # no padding, one group of 16
+    (96, 68, 4, 16, 256, 3, 3, 1, 1, TANH),       # two images per chunk
 ]
 
 
@@ -66,6 +71,30 @@ def test_conv_forward_and_backward(B, Cin, H, W, Cout, KH, KW, stride, pad, act)
     db2 = torch.zeros_like(db)
     dn.dn_conv_backward(Xd, Wd, Yd, dAd, delta, None, dW2, db2, stride, pad, act)
     assert torch.equal(dW2, dW) and torch.equal(db2, db)
+
+
+def test_conv_filter_gradient_with_unaligned_delta():
+    """The matrix-core filter gradient reads delta 16 bytes at a time only if the caller's buffer
+    allows it: a delta buffer that starts 4 bytes past an aligned address gives the same bits."""
+    announce("conv filter gradient, delta buffer not 16-byte aligned")
+    B, Cin, H, W, Cout, K = 16, 20, 22, 20, 35, 3
+    rng = np.random.default_rng(5)
+    X = rng.standard_normal((B, Cin, H, W)).astype(np.float32)
+    Wt = (rng.standard_normal((Cout, Cin, K, K)) / np.sqrt(Cin * K * K)).astype(np.float32)
+    Y = rng.standard_normal((B, Cout, H, W)).astype(np.float32)
+    dA = rng.standard_normal(Y.shape).astype(np.float32)
+    Xd, Wd, Yd, dAd = dev(X), dev(Wt), dev(Y), dev(dA)
+    outs = []
+    for shift in (0, 1):
+        buf = torch.zeros(Y.size + 4, dtype=torch.float32, device="cuda:0")
+        delta = buf[shift:shift + Y.size].view(Y.shape)
+        assert delta.data_ptr() % 16 == 4 * shift
+        dW = torch.zeros(Wt.shape, dtype=torch.float32, device="cuda:0")
+        db = torch.zeros((Cout,), dtype=torch.float32, device="cuda:0")
+        dn.dn_conv_backward(Xd, Wd, Yd, dAd, delta, None, dW, db, 1, 1, TANH)
+        outs.append((delta.clone(), dW, db))
+    for a, b in zip(outs[0], outs[1]):
+        assert torch.equal(a, b)
 
 
 def test_conv_and_pool_at_the_benchmark_shape():

@@ -242,9 +242,54 @@ __global__ __launch_bounds__(256) void corr_mfma_kernel(CorrShape s, const float
     const bool w_on = w_ocl < OC;
     const int w_oc = min(oc0 + w_ocl, s.Cout - 1);
     const bool w_real = oc0 + w_ocl < s.Cout;
+    // 3 x 3 filters: every load of a stage is requested at once, into registers, before the
+    // first value is stored; the staging indices are recomputed from the thread
+    // index every time rather than kept in registers across the product loop (the empty asm hides
+    // that they repeat)
+    constexpr int PROW3 = MC_ROWS + 2, PCOL3 = MC_COLS + 2, NP3 = MC_IC * PROW3 * PCOL3;
+    constexpr int XP3 = KS == 3 ? (NP3 + 255) / 256 : 1, WP3 = KS == 3 ? MC_IC * 9 / 4 : 1;
+    [[maybe_unused]] float wreg[WP3], xreg[XP3];
+    [[maybe_unused]] auto stage_request = [&](int ic0) {
+        const int st = tid;
+        const int kvalid = min(MC_IC, s.Cin - ic0) * 9;
+        const int ocl = st >> 2, kq = st & 3;
+        const bool real = ocl < OC && oc0 + ocl < s.Cout;
+        const float *src = Wt + (size_t)min(oc0 + ocl, s.Cout - 1) * s.w_out_stride + (size_t)ic0 * 9;
+#pragma unroll
+        for (int m = 0; m < WP3; ++m) {
+            const int kl = kq + 4 * m;
+            wreg[m] = (real && kl < kvalid) ? src[kl] : 0.f;
+        }
+        const float *img = In + ((size_t)b * s.Cin + ic0) * s.H * s.W;
+#pragma unroll
+        for (int m = 0; m < XP3; ++m) {
+            const int e = st + 256 * m;
+            const int c = e % PCOL3, pr = (e / PCOL3) % PROW3, icl = e / (PCOL3 * PROW3);
+            const int r_img = r_in0 + pr, c_img = c_in0 + c;
+            const bool ok = e < NP3 && ic0 + icl < s.Cin && r_img >= 0 && r_img < s.H && c_img >= 0 && c_img < s.W;
+            xreg[m] = ok ? img[(unsigned)((icl * s.H + r_img) * s.W + c_img)] : 0.f;
+        }
+    };
+    [[maybe_unused]] auto stage_store = [&]() {
+        const int st = tid;
+        const int ocl = st >> 2, kq = st & 3;
+        if (ocl < OC) {
+#pragma unroll
+            for (int m = 0; m < WP3; ++m) wl[(kq + 4 * m) * MC_WSTRIDE + ocl] = wreg[m];
+        }
+#pragma unroll
+        for (int m = 0; m < XP3; ++m) {
+            const int e = st + 256 * m;
+            if (e < NP3) pl[e] = xreg[m];
+        }
+    };
+    if constexpr (KS == 3) stage_request(0);
     for (int ic0 = 0; ic0 < s.Cin; ic0 += MC_IC) {
-        const int kvalid = min(MC_IC, s.Cin - ic0) * taps;   // k values of this stage that exist
+        [[maybe_unused]] const int kvalid = min(MC_IC, s.Cin - ic0) * taps;   // k values of this stage that exist
         __syncthreads();   // the previous stage has been used
+        if constexpr (KS == 3) {
+            stage_store();
+        } else {
         // (loads in batches, all of a batch in flight before the first is stored)
         constexpr int WB = 9, PB = 6;
         if (w_on) {
@@ -279,7 +324,11 @@ __global__ __launch_bounds__(256) void corr_mfma_kernel(CorrShape s, const float
                 if (row < MC_IC * prow && lane < pcol) pl[row * pcol + lane] = tmp[m];
             }
         }
+        }
         __syncthreads();
+        if constexpr (KS == 3) {
+            if (ic0 + MC_IC < s.Cin) stage_request(ic0 + MC_IC);
+        }
         // k slot h of every instruction: input channel 2 * pair + h at one tap
         const float *wa = wl + (size_t)(h * taps) * MC_WSTRIDE + idx;
         const float *pb = pl + (size_t)h * prow * pcol + (RW * wave) * pcol + idx;
@@ -311,6 +360,13 @@ __global__ __launch_bounds__(256) void corr_mfma_kernel(CorrShape s, const float
             }
         }
     }
+    // the workgroup's biases go through LDS: one read from memory each instead of one per output
+    // (the condition is the same for the whole grid)
+    if (bias) {
+        __syncthreads();
+        if (tid < OC) wl[tid] = oc0 + tid < s.Cout ? bias[oc0 + tid] : 0.f;
+        __syncthreads();
+    }
     // register r of lane (idx, h): output channel 8 (r / 4) + 4 h + r % 4 of the tile, pixel idx of the row
     const int j = j0 + idx;
     if (j >= s.Wo) return;
@@ -322,9 +378,10 @@ __global__ __launch_bounds__(256) void corr_mfma_kernel(CorrShape s, const float
         for (int t = 0; t < OT; ++t)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int oc = oc0 + 32 * t + 8 * (r >> 2) + 4 * h + (r & 3);
-                if (oc < s.Cout)
-                    Out[(((size_t)b * s.Cout + oc) * s.Ho + i) * s.Wo + j] = conv_act(s.act, acc[t][q][r] + (bias ? bias[oc] : 0.f));
+                const int ocl = 32 * t + 8 * (r >> 2) + 4 * h + (r & 3);
+                if (oc0 + ocl < s.Cout)
+                    Out[(((size_t)b * s.Cout + oc0 + ocl) * s.Ho + i) * s.Wo + j] =
+                        conv_act(s.act, acc[t][q][r] + (bias ? wl[ocl] : 0.f));
             }
     }
 }

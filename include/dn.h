@@ -253,7 +253,8 @@ dn_status dn_conv_forward(const float *X_dev, const float *W_dev, const float *b
  * the other outputs' kernels); dW_dev [c_out][c_in][kh][kw], dbias_dev [c_out],
  * dX_dev [batch][c_in][h][w] or NULL.  workspace_dev: device memory of at least
  * dn_conv_backward_workspace_bytes(...) bytes (partial sums of the filter and bias gradients
- * over chunks of the batch; 0 from the query means the sizes are invalid); too small ->
+ * over chunks of the batch, and a rearranged copy of the filters for the input gradient; 0
+ * from the query means the sizes are invalid); too small ->
  * DN_ERR_SHAPE.  Sums are taken in a fixed order: results are bitwise reproducible. */
 size_t dn_conv_backward_workspace_bytes(int32_t batch, int32_t c_in, int32_t h, int32_t w, int32_t c_out,
                                         int32_t kh, int32_t kw, int32_t stride, int32_t pad);

@@ -208,7 +208,7 @@ hipError_t launch_corr_rows(const CorrShape &s, const float *In, const float *Wt
 // 80 words (staging writes run along k for a few channels at a time: stride 16 mod 32 spreads them
 // over the banks), the input as [channel][8 + kh - 1 rows][32 + kw - 1 columns], zeros outside
 // the image.  Filters must be stored [oc][ic][tap] (w_in_stride = taps, no flip): the input
-// gradient passes a flipped, transposed copy (conv_flip_filters_kernel).
+// gradient passes a flipped, transposed copy (written by conv_delta_kernel).
 constexpr int MC_COLS = 32, MC_IC = 8, MC_WSTRIDE = 80;
 typedef float v16f_t __attribute__((ext_vector_type(16)));
 
@@ -424,21 +424,23 @@ hipError_t launch_corr_mfma(const CorrShape &s, const float *In, const float *Wt
               : launch_corr_mfma_as<1, 2, 0>(s, In, Wt, bias, Out, stream);
 }
 
-// Wf[c][o][tap] = W[o][c][taps - 1 - tap]: the filters of the input gradient seen as a correlation.
-__global__ __launch_bounds__(256) void conv_flip_filters_kernel(const float *__restrict__ Wt, float *__restrict__ Wf,
-                                                                int c_out, int c_in, int taps)
-{
-    const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (e >= (size_t)c_out * c_in * taps) return;
-    const int tap = (int)(e % taps);
-    const int o = (int)((e / taps) % c_out), c = (int)(e / ((size_t)taps * c_out));
-    Wf[e] = Wt[((size_t)o * c_in + c) * taps + (taps - 1 - tap)];
-}
-
+// The first `delta_blocks` workgroups write delta = dA f'(Y).  The others, if there are any, write
+// the flipped, transposed filter copy the matrix-core input gradient reads, one element per thread:
+// Wf[c][o][tap] = W[o][c][taps - 1 - tap], the filters of the input gradient seen as a correlation.
 __global__ __launch_bounds__(256) void conv_delta_kernel(const float *__restrict__ dA, const float *__restrict__ Y,
-                                                         float *__restrict__ delta, size_t count, int act)
+                                                         float *__restrict__ delta, size_t count, int act,
+                                                         unsigned delta_blocks, const float *__restrict__ Wt,
+                                                         float *__restrict__ Wf, int c_out, int c_in, int taps)
 {
-    for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < count; e += (size_t)gridDim.x * 256)
+    if (blockIdx.x >= delta_blocks) {
+        const size_t e = (size_t)(blockIdx.x - delta_blocks) * 256 + threadIdx.x;
+        if (e >= (size_t)c_out * c_in * taps) return;
+        const int tap = (int)(e % taps);
+        const int o = (int)((e / taps) % c_out), c = (int)(e / ((size_t)taps * c_out));
+        Wf[e] = Wt[((size_t)o * c_in + c) * taps + (taps - 1 - tap)];
+        return;
+    }
+    for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < count; e += (size_t)delta_blocks * 256)
         delta[e] = dA[e] * conv_deriv(act, Y[e]);
 }
 
@@ -1132,7 +1134,7 @@ size_t dn_conv_backward_workspace_bytes(int32_t batch, int32_t c_in, int32_t h, 
     ConvShape s;
     if (conv_shape(batch, c_in, h, w, c_out, kh, kw, stride, pad, DN_ACT_LINEAR, s) != DN_OK) return 0;
     const DwPlan p = dw_plan(s);
-    return (p.filt + (size_t)s.Cout) * (size_t)p.chunks * sizeof(float);
+    return ((p.filt + (size_t)s.Cout) * (size_t)p.chunks + p.filt) * sizeof(float);   // partial sums, flipped filters
 }
 
 dn_status dn_conv_backward(const float *X_dev, const float *W_dev, const float *Y_dev, const float *dA_dev,
@@ -1146,15 +1148,23 @@ dn_status dn_conv_backward(const float *X_dev, const float *W_dev, const float *
     const dn_status st = conv_shape(batch, c_in, h, w, c_out, kh, kw, stride, pad, (int)act, s);
     if (st != DN_OK) return st;
     const DwPlan p = dw_plan(s);
-    if (workspace_bytes < (p.filt + (size_t)s.Cout) * (size_t)p.chunks * sizeof(float)) return DN_ERR_SHAPE;
+    if (workspace_bytes < ((p.filt + (size_t)s.Cout) * (size_t)p.chunks + p.filt) * sizeof(float)) return DN_ERR_SHAPE;
     if ((reinterpret_cast<uintptr_t>(workspace_dev) & 3) != 0) return DN_ERR_INVALID_ARG;
     hipStream_t stream = (hipStream_t)hip_stream;
     float *part = static_cast<float *>(workspace_dev);
     const size_t ny = (size_t)s.B * s.Cout * s.Ho * s.Wo;
     size_t blocks = (ny + 255) / 256;
     if (blocks > 256 * 16) blocks = 256 * 16;
-    hipLaunchKernelGGL(conv_delta_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, dA_dev, Y_dev, delta_dev, ny,
-                       s.act);
+    // the stride-1 input gradient is a correlation of delta with the flipped filters; on the matrix
+    // cores it reads a flipped, transposed copy of them, kept behind the partial sums
+    const int taps = s.KH * s.KW;
+    const CorrShape cm{s.B, s.Cout, s.Ho, s.Wo, s.Cin, s.KH, s.KW, s.KH - 1 - s.pad, s.KW - 1 - s.pad, s.H, s.W,
+                       DN_ACT_LINEAR, s.Cout * taps, taps, 0};
+    const bool dx_mfma = dX_dev && s.stride == 1 && corr_mfma_fits(cm);
+    float *flipped = part + (p.filt + (size_t)s.Cout) * (size_t)p.chunks;
+    const size_t flip_blocks = dx_mfma ? (p.filt + 255) / 256 : 0;
+    hipLaunchKernelGGL(conv_delta_kernel, dim3((unsigned)(blocks + flip_blocks)), dim3(256), 0, stream, dA_dev, Y_dev,
+                       delta_dev, ny, s.act, (unsigned)blocks, W_dev, flipped, s.Cout, s.Cin, taps);
     if (launched() != DN_OK) return DN_ERR_DEVICE;
     const dim3 grid_dw((unsigned)(p.groups * s.Cin), (unsigned)p.chunks);
     if (p.mfma_ig > 0) {
@@ -1186,23 +1196,13 @@ dn_status dn_conv_backward(const float *X_dev, const float *W_dev, const float *
                        dW_dev, dbias_dev, p.filt, s.Cout, p.chunks, 1.0f / (float)s.B);
     if (launched() != DN_OK) return DN_ERR_DEVICE;
     if (dX_dev && s.stride == 1) {
-        // the input gradient as a correlation of delta with the flipped filters
-        const int taps = s.KH * s.KW;
         const CorrShape c{s.B, s.Cout, s.Ho, s.Wo, s.Cin, s.KH, s.KW, s.KH - 1 - s.pad, s.KW - 1 - s.pad, s.H, s.W,
                           DN_ACT_LINEAR, taps, s.Cin * taps, 1};
-        // on the matrix cores with a flipped, transposed copy of the filters (in the workspace, whose partial
-        // sums have been consumed by now)
-        const CorrShape cm{c.B, c.Cin, c.H, c.W, c.Cout, c.KH, c.KW, c.pad_h, c.pad_w, c.Ho, c.Wo, c.act, s.Cout * taps, taps, 0};
         hipError_t e;
-        if (corr_mfma_fits(cm)) {
-            hipLaunchKernelGGL(conv_flip_filters_kernel, dim3((unsigned)((p.filt + 255) / 256)), dim3(256), 0, stream, W_dev,
-                               part, s.Cout, s.Cin, taps);
-            e = hipGetLastError();
-            if (e == hipSuccess) e = launch_corr_mfma(cm, delta_dev, part, nullptr, dX_dev, stream);
-        } else {
+        if (dx_mfma) e = launch_corr_mfma(cm, delta_dev, flipped, nullptr, dX_dev, stream);
+        else
             e = s.Cin >= 8 ? launch_corr_rows<8>(c, delta_dev, W_dev, nullptr, dX_dev, stream)
                            : launch_corr_rows<4>(c, delta_dev, W_dev, nullptr, dX_dev, stream);
-        }
         if (e != hipSuccess) return DN_ERR_DEVICE;
     } else if (dX_dev) {
         const int ci = s.Cin >= 8 ? 8 : (s.Cin >= 2 ? 4 : 1);

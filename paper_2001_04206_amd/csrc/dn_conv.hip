@@ -4,7 +4,8 @@
 // in include/dn.h).  Gather form throughout: every output element is owned by one thread, wave or
 // workgroup, so nothing is accumulated with atomics and every sum has a fixed order.  Stride-1
 // layers wide enough for 32 x 32 tiles run their forward product and input gradient on the matrix
-// cores (corr_mfma_kernel); everything else uses register-tiled vector kernels.
+// cores (corr_mfma_kernel), with 3 x 3 filters the filter gradient too (conv_dw_mfma_kernel);
+// everything else uses register-tiled vector kernels.
 #include "dn_internal.h"
 #include "dn_wave.h"
 

@@ -547,13 +547,16 @@ __global__ __launch_bounds__(256) void conv_dw_kernel(ConvShape s, const float *
 template <int KMAX, int CO>
 __global__ __launch_bounds__(256) void conv_dw_slide_kernel(ConvShape s, const float *__restrict__ X,
                                                             const float *__restrict__ delta, float *__restrict__ part,
-                                                            int images_per_chunk)
+                                                            int images_per_chunk, int bands, int rows_per_band)
 {
     __shared__ float red[4][CO * KMAX * KMAX + CO];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int pix = s.Ho * s.Wo;
     const int c = blockIdx.x % s.Cin, og = blockIdx.x / s.Cin;
-    const int b0 = blockIdx.y * images_per_chunk, b1 = min(s.B, b0 + images_per_chunk);
+    // a chunk is a group of images and a band of their output rows
+    const int band = blockIdx.y % bands;
+    const int b0 = (blockIdx.y / bands) * images_per_chunk, b1 = min(s.B, b0 + images_per_chunk);
+    const int i_lo = band * rows_per_band, i_hi = min(s.Ho, i_lo + rows_per_band);
     const int total = (b1 - b0) * s.Wo;
     const int off = KMAX - s.KH;   // window row u lives at index u + off
     int oc[CO];
@@ -578,15 +581,15 @@ __global__ __launch_bounds__(256) void conv_dw_slide_kernel(ConvShape s, const f
 #pragma unroll
         for (int v = 0; v < KMAX; ++v) col_ok[v] = v < s.KW && c0 + v >= 0 && c0 + v < s.W;
         float win[KMAX][KMAX];
-        // the window of output row -1: its rows 1 .. kh-1 are rows 0 .. kh-2 of output row 0
+        // the window of the output row before the band: its rows 1 .. kh-1 are rows 0 .. kh-2 of the band's first
 #pragma unroll
         for (int u = 0; u < KMAX; ++u) {
-            const int r = -1 - s.pad + (u - off);
+            const int r = i_lo - 1 - s.pad + (u - off);
             const bool row_ok = u >= off && r >= 0 && r < s.H;
 #pragma unroll
             for (int v = 0; v < KMAX; ++v) win[u][v] = (row_ok && col_ok[v]) ? x[(size_t)r * s.W + c0 + v] : 0.f;
         }
-        for (int i = 0; i < s.Ho; ++i) {
+        for (int i = i_lo; i < i_hi; ++i) {
 #pragma unroll
             for (int u = 0; u < KMAX - 1; ++u)
 #pragma unroll
@@ -1069,6 +1072,16 @@ DwPlan dw_plan(const ConvShape &s)
     p.mfma_ig = 0;
     p.bands = 1;
     p.rows_per_band = s.Ho;
+    // few channels and a small batch: the stride-1 kernel also cuts the images into bands of at
+    // least four output rows (a band reloads kh - 1 rows above it), towards two workgroups per CU
+    if (s.stride == 1 && per_chunk * p.chunks < 512) {
+        long bands = (512 + per_chunk * p.chunks - 1) / (per_chunk * p.chunks);
+        const long max_bands = s.Ho / 4 > 1 ? s.Ho / 4 : 1;
+        if (bands > max_bands) bands = max_bands;
+        p.rows_per_band = (int)((s.Ho + bands - 1) / bands);
+        p.bands = (s.Ho + p.rows_per_band - 1) / p.rows_per_band;
+        p.chunks *= p.bands;
+    }
     if (s.stride == 1 && s.KH == 3 && s.KW == 3 && s.Cout >= 32 && s.Cin >= 8 && s.Wo >= 16 && s.Wo % 4 == 0) {
         const int groups = (s.Cin + DWM_IG - 1) / DWM_IG;
         const int ig = (s.Cin + groups - 1) / groups;   // even groups
@@ -1176,13 +1189,13 @@ dn_status dn_conv_backward(const float *X_dev, const float *W_dev, const float *
                            (int)(reinterpret_cast<uintptr_t>(delta_dev) % 16 == 0));
     } else if (s.stride == 1 && p.co == 8)
         hipLaunchKernelGGL((conv_dw_slide_kernel<3, 8>), grid_dw, dim3(256), 0, stream, s, X_dev, delta_dev, part,
-                           p.images_per_chunk);
+                           p.images_per_chunk, p.bands, p.rows_per_band);
     else if (s.stride == 1 && p.co == 4)
         hipLaunchKernelGGL((conv_dw_slide_kernel<5, 4>), grid_dw, dim3(256), 0, stream, s, X_dev, delta_dev, part,
-                           p.images_per_chunk);
+                           p.images_per_chunk, p.bands, p.rows_per_band);
     else if (s.stride == 1)
         hipLaunchKernelGGL((conv_dw_slide_kernel<7, 2>), grid_dw, dim3(256), 0, stream, s, X_dev, delta_dev, part,
-                           p.images_per_chunk);
+                           p.images_per_chunk, p.bands, p.rows_per_band);
     else if (p.co == 8)
         hipLaunchKernelGGL((conv_dw_kernel<3, 8>), grid_dw, dim3(256), 0, stream, s, X_dev, delta_dev, part,
                            p.images_per_chunk);

@@ -238,6 +238,28 @@ double PFX(backward)(int L, const int32_t *n, const int32_t *acts, int loss, con
     return loss_sum / (double)B;
 }
 
+/*
+ * Derivative of each sample's loss with respect to that sample's input, from the deltas the
+ * backward pass left: dX[s][i] = sum_o W_1[o][i] delta_1[s][o]  (the propagation rule for
+ * the hidden layers taken one layer further; the input has no activation, so no derivative
+ * factor).  Per sample, not a batch mean: it is what a layer in front of the net receives as
+ * the derivative with respect to its own output.
+ */
+void PFX(input_gradient)(int L, const int32_t *n, const real *params, const real *D, int B, real *dX)
+{
+    (void)L;
+    const real *W = params + w_offset(n, 1);
+    const real *D1 = D + a_offset(n, 1, B);
+    const int nin = n[0], nout = n[1];
+    for (int s = 0; s < B; ++s)
+        for (int i = 0; i < nin; ++i) {
+            double t = 0.0;
+            for (int o = 0; o < nout; ++o)
+                t += (double)W[(size_t)o * nin + i] * (double)D1[(size_t)s * nout + o];
+            dX[(size_t)s * nin + i] = (real)t;
+        }
+}
+
 /* Update: dW <- mu*dW - lr*G ; W <- W + dW, for weights and biases alike. */
 void PFX(update)(size_t P, real *params, real *vel, const real *grads, real lr, real mu)
 {

@@ -58,6 +58,7 @@ class Oracle:
         self._forward = f("forward"); self._forward.restype = None
         self._backward = f("backward"); self._backward.restype = C.c_double
         self._update = f("update"); self._update.restype = None
+        self._input_gradient = f("input_gradient"); self._input_gradient.restype = None
         self._train_epoch = f("train_epoch"); self._train_epoch.restype = C.c_double
         self._evaluate = f("evaluate"); self._evaluate.restype = C.c_double
         self.P = int(self._param_count(C.c_int(self.L), self._ip(self.widths)))
@@ -136,6 +137,13 @@ class Oracle:
 
     def deltas(self) -> List[np.ndarray]:
         return self._acts_split(self.D, self._B)
+
+    def input_gradient(self) -> np.ndarray:
+        """dE_s/dx_s for every sample of the last backward(), [B][n_0]."""
+        dX = np.zeros((self._B, int(self.widths[0])), dtype=self.dtype)
+        self._input_gradient(C.c_int(self.L), self._ip(self.widths), self._rp(self.params),
+                             self._rp(self.D), C.c_int(self._B), self._rp(dX))
+        return dX
 
     def update(self, lr: float, momentum: float):
         self._update(C.c_size_t(self.P), self._rp(self.params), self._rp(self.vel),

@@ -186,7 +186,7 @@ def torch_net(W, b, acts, X, labels, loss):
     bt = [torch.tensor(v, dtype=torch.float64, requires_grad=True) for v in b]
 
     def closure(Xb, yb):
-        a = torch.tensor(Xb, dtype=torch.float64)
+        a = Xb if torch.is_tensor(Xb) else torch.tensor(Xb, dtype=torch.float64)
         for Wl, bl, act in zip(Wt, bt, acts):
             z = a @ Wl.T + bl
             if act == SIG:
@@ -256,6 +256,54 @@ def test_one_step_gradients_match_torch_autograd():
     G, g = o.get_grads()
     for a_, t_ in zip(G + g, Wt + bt):
         np.testing.assert_allclose(a_, t_.grad.numpy(), rtol=1e-11, atol=1e-14)
+
+
+@pytest.mark.parametrize("widths,acts,loss", [
+    ([5, 6, 3], [TANH, SOFTMAX], CE),
+    ([4, 3, 5, 2], [SIG, RELU, SIG], MSE),
+    ([6, 4], [SOFTMAX], CE),
+])
+def test_input_gradient_matches_finite_differences_and_library_autograd(widths, acts, loss):
+    """dE_s/dx_s per sample: central differences of the checker's own per-sample loss (forward
+    and loss only, one sample at a time), and torch's autograd on the textbook net (the batch-mean
+    loss's input gradient times B, since every sample's loss depends on its own input only)."""
+    rng = np.random.default_rng(33)
+    W, b = rand_net(rng, widths)
+    B = 5
+    X = rng.standard_normal((B, widths[0]))
+    labels = rng.integers(0, widths[-1], B).astype(np.int32)
+    o = Oracle("o64", widths, acts, loss)
+    o.set_params(W, b)
+    o.forward(X)
+    o.backward(labels)
+    dX = o.input_gradient()
+    assert dX.shape == X.shape
+    h = 1e-6
+    for s in range(B):
+        for i in range(widths[0]):
+            xp, xm = X[s:s + 1].copy(), X[s:s + 1].copy()
+            xp[0, i] += h
+            xm[0, i] -= h
+            fd = (o.loss_value(xp, labels[s:s + 1]) - o.loss_value(xm, labels[s:s + 1])) / (2 * h)
+            assert abs(dX[s, i] - fd) < 1e-7 * max(1.0, abs(fd)), (s, i, dX[s, i], fd)
+    Wt, bt, closure = torch_net(W, b, acts, X, labels, loss)
+    Xt = torch.tensor(X, dtype=torch.float64, requires_grad=True)
+    closure(Xt, labels).backward()
+    np.testing.assert_allclose(dX, Xt.grad.numpy() * B, rtol=1e-10, atol=1e-13)
+
+
+def test_input_gradient_of_one_linear_layer_is_delta_times_weights():
+    """One linear layer with squared error: dE/dx = (W x + b - y) W, written out."""
+    rng = np.random.default_rng(34)
+    W, b = rand_net(rng, [4, 3])
+    X = rng.standard_normal((2, 4))
+    labels = np.array([2, 0], dtype=np.int32)
+    o = Oracle("o64", [4, 3], [LIN], MSE)
+    o.set_params(W, b)
+    o.forward(X)
+    o.backward(labels)
+    expect = (X @ W[0].T + b[0] - onehot(labels, 3)) @ W[0]
+    np.testing.assert_allclose(o.input_gradient(), expect, rtol=1e-13, atol=1e-15)
 
 
 # ---------------------------------------------------------------- invariants ----

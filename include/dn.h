@@ -141,6 +141,21 @@ dn_status dn_forward(dn_net *net, const float *X_dev, int32_t batch, float *out_
 dn_status dn_backward(dn_net *net, const int32_t *labels_dev, int32_t batch, float *loss_dev);
 
 /*
+ * Derivative of every sample's loss with respect to that sample's input, for the batch
+ * of the last dn_backward: dX = Delta_1 W_1, the delta propagation above taken one layer
+ * further (the input has no activation, hence no derivative factor).  Per sample, not a
+ * batch mean.  It is what a layer placed in front of the net takes as the derivative with
+ * respect to its output (dn_maxpool_backward's dY_dev, dn_conv_backward's dA_dev), which
+ * makes the convolutional and pooling layers of the paper's engine ("Deep Netts Deep
+ * Learning Engine") trainable in front of a fully connected net.
+ *   dX_dev [batch][n_0] (device, written).  batch must equal the last dn_forward's batch
+ *   (DN_ERR_SHAPE).  DN_ERR_INVALID_ARG unless dn_backward was the last call to touch the
+ *   net's state: W_1 must still be the matrix the deltas were propagated through, so not
+ *   after dn_update, dn_set_params of layer 1, a new dn_forward, or the epoch calls.
+ */
+dn_status dn_input_gradient(dn_net *net, int32_t batch, float *dX_dev);
+
+/*
  * Update from the gradients of the last dn_backward (the paper's
  * learning-rate scaled weight and bias deltas):
  *   dW_l <- momentum * dW_l - lr * G_l ;  W_l <- W_l + dW_l     (same for b_l)
@@ -269,6 +284,17 @@ dn_status dn_maxpool_forward(const float *X_dev, float *Y_dev, int32_t batch, in
 dn_status dn_maxpool_backward(const float *X_dev, const float *dY_dev, float *dX_dev, int32_t batch,
                               int32_t channels, int32_t h, int32_t w, int32_t k, int32_t stride,
                               void *hip_stream);
+
+/*
+ * The update rule of dn_update for parameters the caller keeps itself (the filters and
+ * biases of a convolutional layer):  d <- momentum * d - lr * G ;  P <- P + d.
+ *   param_dev, grad_dev [count] (device); velocity_dev [count] (device) holds d between
+ *   calls (zero it before the first) and may be NULL when momentum is 0.
+ * Errors: INVALID_ARG (NULL param / grad, rates outside lr >= 0, 0 <= momentum < 1 or not
+ * finite, momentum > 0 without a velocity buffer), SHAPE (count < 1), DEVICE.
+ */
+dn_status dn_sgd_step(float *param_dev, const float *grad_dev, float *velocity_dev, int64_t count, float lr,
+                      float momentum, void *hip_stream);
 
 /*
  * Measurement hooks (the paper times its two offloaded methods with wall-clock

@@ -100,6 +100,7 @@ struct dn_net {
     const float *X = nullptr;
     int fwd_batch = 0;
     bool have_fwd = false, have_bwd = false;
+    bool w1_as_in_bwd = false;   // W_1 is still the matrix the last dn_backward propagated through
     // options
     int time_kernels = 0, gemm_variant = -1, online_mode = 0, online_min_tile = ON_DEFAULT_MIN_TILE,
         online_resident = 1, split_k_on = 1;
@@ -543,6 +544,7 @@ dn_status dn_net_destroy(dn_net *net)
 dn_status dn_set_params(dn_net *net, int32_t layer, const float *W_host, const float *b_host)
 {
     if (!net || layer < 1 || layer > net->L) return DN_ERR_INVALID_ARG;
+    if (layer == 1 && W_host) net->w1_as_in_bwd = false;
     const size_t nw = (size_t)net->n[layer] * net->n[layer - 1], nb = (size_t)net->n[layer];
     if (W_host) {
         DN_HIP(hipMemcpyAsync(net->W(layer), W_host, nw * sizeof(float), hipMemcpyHostToDevice, net->stream));
@@ -585,6 +587,7 @@ dn_status dn_forward(dn_net *net, const float *X_dev, int32_t batch, float *out_
     if (batch < 1 || batch > net->max_batch) return DN_ERR_SHAPE;
     net->have_fwd = false;
     net->have_bwd = false;
+    net->w1_as_in_bwd = false;
     dn_status st = run_forward(net, X_dev, batch, false);
     if (st != DN_OK) return st;
     const int L = net->L;
@@ -610,6 +613,27 @@ dn_status dn_backward(dn_net *net, const int32_t *labels_dev, int32_t batch, flo
     dn_status st = run_backward(net, net->X, batch, GRAD_STORE, 0.f, 0.f, false);
     if (st != DN_OK) return st;
     net->have_bwd = true;
+    net->w1_as_in_bwd = true;
+    return DN_OK;
+}
+
+dn_status dn_input_gradient(dn_net *net, int32_t batch, float *dX_dev)
+{
+    if (!net || !dX_dev) return DN_ERR_INVALID_ARG;
+    if (!net->have_bwd || !net->w1_as_in_bwd) return DN_ERR_INVALID_ARG;
+    if (batch != net->fwd_batch) return DN_ERR_SHAPE;
+    // the delta propagation of the hidden layers, one layer further: the input has no activation,
+    // so the derivative factor is that of the identity (the kernel still reads an operand of the
+    // output's shape for it: the input itself)
+    GemmArgs g{};
+    g.A = net->D(1); g.lda = net->n[1];
+    g.B = net->W(1); g.ldb = net->n[0];
+    g.M = batch; g.N = net->n[0]; g.K = net->n[1];
+    g.C = dX_dev; g.ldc = net->n[0];
+    g.aux = net->X;
+    g.act = DN_ACT_LINEAR;
+    net->split_k(g);
+    DN_HIP(launch_gemm(GEMM_DELTA, g, net->gemm_variant, net->stream));
     return DN_OK;
 }
 
@@ -617,10 +641,21 @@ dn_status dn_update(dn_net *net, float lr, float momentum)
 {
     if (!net || !rate_ok(lr, momentum)) return DN_ERR_INVALID_ARG;
     if (!net->have_bwd) return DN_ERR_INVALID_ARG;
+    net->w1_as_in_bwd = false;
     // parameters, velocities and gradients are three regions of one shape (padding holds zeros)
     DN_HIP(launch_update((float *)(net->arena + net->lo.off_params), (float *)(net->arena + net->lo.off_vel),
                          (const float *)(net->arena + net->lo.off_grads), net->lo.region / sizeof(float), lr,
                          momentum, net->stream));
+    return DN_OK;
+}
+
+dn_status dn_sgd_step(float *param_dev, const float *grad_dev, float *velocity_dev, int64_t count, float lr,
+                      float momentum, void *hip_stream)
+{
+    if (!param_dev || !grad_dev || !rate_ok(lr, momentum)) return DN_ERR_INVALID_ARG;
+    if (momentum != 0.f && !velocity_dev) return DN_ERR_INVALID_ARG;
+    if (count < 1) return DN_ERR_SHAPE;
+    DN_HIP(launch_update(param_dev, velocity_dev, grad_dev, (size_t)count, lr, momentum, (hipStream_t)hip_stream));
     return DN_OK;
 }
 
@@ -629,7 +664,7 @@ dn_status dn_train_epoch(dn_net *net, const float *X_dev, const int32_t *labels_
 {
     if (!net || !X_dev || !labels_dev || n_samples <= 0 || !rate_ok(lr, momentum)) return DN_ERR_INVALID_ARG;
     if (batch < 1 || batch > net->max_batch) return DN_ERR_SHAPE;
-    net->have_fwd = net->have_bwd = false;  // activations / gradients of the split API are overwritten
+    net->have_fwd = net->have_bwd = net->w1_as_in_bwd = false;  // activations / gradients of the split API are overwritten
     const bool timing = net->time_kernels != 0;
     net->timed = 0;
     const int L = net->L;
@@ -716,7 +751,7 @@ dn_status dn_evaluate(dn_net *net, const float *X_dev, const int32_t *labels_dev
 {
     if (!net || !X_dev || !labels_dev || n_samples <= 0) return DN_ERR_INVALID_ARG;
     if (batch < 1 || batch > net->max_batch) return DN_ERR_SHAPE;
-    net->have_fwd = net->have_bwd = false;  // the activations of the split API are overwritten
+    net->have_fwd = net->have_bwd = net->w1_as_in_bwd = false;  // the activations of the split API are overwritten
     const int L = net->L;
     DN_HIP(hipMemsetAsync(net->epoch_acc(), 0, 24, net->stream));
     for (int64_t s0 = 0; s0 < n_samples; s0 += batch) {

@@ -556,10 +556,19 @@ static unsigned grid_for(size_t count)
     return (unsigned)(g ? g : 1);
 }
 
+__global__ __launch_bounds__(256) void descent_kernel(float *__restrict__ p, const float *__restrict__ g, size_t count,
+                                                      float lr)
+{
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (size_t)gridDim.x * 256)
+        p[i] = p[i] + (-lr * g[i]);
+}
+
 hipError_t launch_update(float *p, float *v, const float *g, size_t count, float lr, float mu,
                          hipStream_t stream)
 {
-    hipLaunchKernelGGL(update_kernel, dim3(grid_for(count)), dim3(256), 0, stream, p, v, g, count, lr, mu);
+    // without a velocity buffer (momentum 0 only): plain gradient descent
+    if (!v) hipLaunchKernelGGL(descent_kernel, dim3(grid_for(count)), dim3(256), 0, stream, p, g, count, lr);
+    else hipLaunchKernelGGL(update_kernel, dim3(grid_for(count)), dim3(256), 0, stream, p, v, g, count, lr, mu);
     return hipGetLastError();
 }
 

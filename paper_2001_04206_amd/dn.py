@@ -28,7 +28,7 @@ EXPORTS = [
     "dn_train", "dn_evaluate", "dn_layer_backward_workspace_bytes", "dn_layer_backward_host",
     "dn_last_epoch_ms", "dn_kernel_time", "dn_set_option",
     "dn_conv_forward", "dn_conv_backward_workspace_bytes", "dn_conv_backward", "dn_maxpool_forward",
-    "dn_maxpool_backward",
+    "dn_maxpool_backward", "dn_input_gradient", "dn_sgd_step",
 ]
 
 _lib = None
@@ -63,6 +63,8 @@ def lib():
         l.dn_forward.argtypes = [vp, vp, i32, vp]
         l.dn_backward.argtypes = [vp, vp, i32, vp]
         l.dn_update.argtypes = [vp, f32, f32]
+        l.dn_input_gradient.argtypes = [vp, i32, vp]
+        l.dn_sgd_step.argtypes = [vp, vp, vp, i64, f32, f32, vp]
         l.dn_train_epoch.argtypes = [vp, vp, vp, i64, i32, f32, f32, C.POINTER(f32)]
         l.dn_train.argtypes = [vp, vp, vp, i64, i32, f32, f32, f32, i32, C.POINTER(i32), C.POINTER(f32)]
         l.dn_evaluate.argtypes = [vp, vp, vp, i64, i32, C.POINTER(f32), C.POINTER(i64)]
@@ -227,6 +229,21 @@ def dn_maxpool_backward(X, dY, dX, k: int, stride: int):
                "dn_maxpool_backward")
 
 
+def dn_sgd_step(param, grad, velocity, lr: float, momentum: float):
+    """The update rule of Net.dn_update for a parameter tensor the caller owns."""
+    import torch
+    f32 = torch.float32
+    _shape_check(grad, param.shape, "grad")
+    if velocity is not None:
+        _shape_check(velocity, param.shape, "velocity")
+    with torch.cuda.device(param.device):
+        stream = torch.cuda.current_stream(param.device)
+        _check(lib().dn_sgd_step(_dev_ptr(param, f32, "param"), _dev_ptr(grad, f32, "grad"),
+                                 None if velocity is None else _dev_ptr(velocity, f32, "velocity"),
+                                 int(param.numel()), float(lr), float(momentum), C.c_void_p(stream.cuda_stream)),
+               "dn_sgd_step")
+
+
 class Net:
     """One network on the current device.  Owns the arena tensor (torch
     allocation) and the library handle; method names follow include/dn.h."""
@@ -317,6 +334,12 @@ class Net:
         _check(lib().dn_backward(self._h, _dev_ptr(labels, t.int32, "labels"), int(labels.shape[0]),
                                  None if loss_out is None else _dev_ptr(loss_out, t.float32, "loss")),
                "dn_backward")
+
+    def dn_input_gradient(self, dX):
+        t = self._torch
+        _shape_check(dX, (int(dX.shape[0]), self.widths[0]), "dX")
+        _check(lib().dn_input_gradient(self._h, int(dX.shape[0]), _dev_ptr(dX, t.float32, "dX")),
+               "dn_input_gradient")
 
     def dn_update(self, lr: float, momentum: float):
         _check(lib().dn_update(self._h, float(lr), float(momentum)), "dn_update")

@@ -151,3 +151,12 @@ def test_conv_and_pool_argument_checks(lib):
     assert pool(stride=0) == dn.DN_ERR_INVALID_ARG
     assert pool(B=40000) == dn.DN_ERR_INVALID_ARG         # more planes than the launch grid holds
     assert lib.dn_maxpool_backward(p, p, None, 2, 3, 8, 8, 2, 2, None) == dn.DN_ERR_INVALID_ARG
+    # the stand-alone update rule and the input gradient
+    assert lib.dn_sgd_step(None, p, None, 10, 0.1, 0.0, None) == dn.DN_ERR_INVALID_ARG
+    assert lib.dn_sgd_step(p, None, None, 10, 0.1, 0.0, None) == dn.DN_ERR_INVALID_ARG
+    assert lib.dn_sgd_step(p, p, None, 10, 0.1, 0.5, None) == dn.DN_ERR_INVALID_ARG    # momentum without velocity
+    assert lib.dn_sgd_step(p, p, p, 10, -0.1, 0.0, None) == dn.DN_ERR_INVALID_ARG
+    assert lib.dn_sgd_step(p, p, p, 10, 0.1, 1.0, None) == dn.DN_ERR_INVALID_ARG
+    assert lib.dn_sgd_step(p, p, p, 10, float("nan"), 0.0, None) == dn.DN_ERR_INVALID_ARG
+    assert lib.dn_sgd_step(p, p, p, 0, 0.1, 0.0, None) == dn.DN_ERR_SHAPE
+    assert lib.dn_input_gradient(None, 4, p) == dn.DN_ERR_INVALID_ARG

@@ -32,7 +32,8 @@ CONV_CASES = [
     (16, 20, 22, 20, 35, 3, 3, 1, 1, TANH),       # two channel groups of 10 (no fifth tile), ragged bands and channels
     (16, 33, 9, 36, 70, 3, 3, 1, 1, SIG),         # groups of 17 and 16, two channel blocks, two column blocks
     (48, 16, 18, 18, 64, 3, 3, 1, 0, RELU),       # no padding, one group of 16
-    (96, 68, 4, 16, 256, 3, 3, 1, 1, TANH),       # two images per chunk
+    (97, 68, 4, 16, 256, 3, 3, 1, 1, TANH),       # two images per chunk, the last chunk has one
+    (48, 8, 17, 16, 32, 3, 3, 1, 1, SIG),         # the narrowest layer that takes this form: one half-filled channel tile, 17 rows in bands of 4
 ]
 
 

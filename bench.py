@@ -49,6 +49,150 @@ CONV_WORKLOADS = {
 }
 
 
+# A small convolutional classifier trained by plain gradient descent, every layer's forward,
+# backward and update on the device: conv 3x3 (ReLU) + 2x2 pooling blocks, then a dense net.
+# name: (batch, (c, h, w) of the input, output channels of the blocks, dense widths after the flatten)
+CNN_WORKLOADS = {
+    "cnn_3x32x32_c32_c64_fc512_10_b128": (128, (3, 32, 32), (32, 64), (512, 10)),
+}
+
+
+def bench_cnn(args, spec):
+    """One step = forward, backward and update of the whole classifier on one batch."""
+    import numpy as np
+    import torch
+    from paper_2001_04206_amd import dn
+    B, (C0, H0, W0), chans, dense = spec
+    RELU, SOFTMAX, CE, K, pad, lr = 3, 4, 1, 3, 1, 0.01
+    rng = np.random.default_rng(0)
+    Xh = rng.standard_normal((B, C0, H0, W0)).astype(np.float32)
+    labels_h = rng.integers(0, dense[-1], B).astype(np.int32)
+    dev = lambda a: torch.from_numpy(a).to("cuda:0")
+    f32 = dict(dtype=torch.float32, device="cuda:0")
+    blocks, cin, h, w = [], C0, H0, W0
+    for cout in chans:
+        Wh = (rng.standard_normal((cout, cin, K, K)) * np.sqrt(2.0 / (cin * K * K))).astype(np.float32)
+        blk = {"cin": cin, "cout": cout, "h": h, "w": w, "Wh": Wh, "bh": np.zeros(cout, dtype=np.float32)}
+        blk["W"], blk["b"] = dev(Wh), dev(blk["bh"])
+        blk["Y"] = torch.empty(B, cout, h, w, **f32)
+        blk["P"] = torch.empty(B, cout, h // 2, w // 2, **f32)
+        blk["dP"], blk["dY"], blk["delta"] = torch.empty_like(blk["P"]), torch.empty_like(blk["Y"]), torch.empty_like(blk["Y"])
+        blk["dW"], blk["db"] = torch.empty_like(blk["W"]), torch.empty_like(blk["b"])
+        blk["ws"] = torch.empty(dn.lib().dn_conv_backward_workspace_bytes(B, cin, h, w, cout, K, K, 1, pad),
+                                dtype=torch.uint8, device="cuda:0")
+        blocks.append(blk)
+        cin, h, w = cout, h // 2, w // 2
+    for i in range(1, len(blocks)):
+        blocks[i]["dX"] = blocks[i - 1]["dP"]    # a block's input gradient is the pooling gradient of the one before
+    blocks[0]["dX"] = None
+    flat = cin * h * w
+    widths = [flat] + list(dense)
+    acts = [RELU] * (len(dense) - 1) + [SOFTMAX]
+    Wd = [(rng.standard_normal((widths[l + 1], widths[l])) * np.sqrt(2.0 / widths[l])).astype(np.float32)
+          for l in range(len(dense))]
+    bd = [np.zeros(widths[l + 1], dtype=np.float32) for l in range(len(dense))]
+    net = dn.Net(widths, acts, CE, B)
+    net.set_all(Wd, bd)
+    X, labels = dev(Xh), dev(labels_h)
+
+    def forward():
+        a = X
+        for blk in blocks:
+            dn.dn_conv_forward(a, blk["W"], blk["b"], blk["Y"], 1, pad, RELU)
+            dn.dn_maxpool_forward(blk["Y"], blk["P"], 2, 2)
+            a = blk["P"]
+        net.dn_forward(a.view(B, flat))
+
+    def backward():
+        net.dn_backward(labels)
+        net.dn_input_gradient(blocks[-1]["dP"].view(B, flat))
+        for i in range(len(blocks) - 1, -1, -1):
+            blk = blocks[i]
+            a = X if i == 0 else blocks[i - 1]["P"]
+            dn.dn_maxpool_backward(blk["Y"], blk["dP"], blk["dY"], 2, 2)
+            dn.dn_conv_backward(a, blk["W"], blk["Y"], blk["dY"], blk["delta"], blk["dX"], blk["dW"], blk["db"], 1, pad,
+                                RELU, workspace=blk["ws"])
+
+    def update():
+        net.dn_update(lr, 0.0)
+        for blk in blocks:
+            dn.dn_sgd_step(blk["W"], blk["dW"], None, lr, 0.0)
+            dn.dn_sgd_step(blk["b"], blk["db"], None, lr, 0.0)
+
+    def step():
+        forward(); backward(); update()
+
+    steps = args.steps if args.steps > 0 else 200
+    warmup = args.warmup if args.warmup >= 0 else 10
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    # algorithmic flops of a step: three products per convolution (two for the first block, whose
+    # input gradient nobody needs) and three per dense layer (the first one's input gradient feeds the blocks)
+    conv_flop = [2.0 * B * b_["cout"] * b_["h"] * b_["w"] * b_["cin"] * K * K for b_ in blocks]
+    dense_flop = [2.0 * B * widths[l] * widths[l + 1] for l in range(len(dense))]
+    step_flop = sum(f * (2 if i == 0 else 3) for i, f in enumerate(conv_flop)) + 3.0 * sum(dense_flop)
+    # the phases bracketed by events on the stream they are enqueued on
+    ms = {"forward": 0.0, "backward": 0.0, "update": 0.0}
+    roofline = None
+    if not args.no_kernel_timing:
+        n_ev = min(steps, 50)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        for _ in range(n_ev):
+            ev[0].record(); forward()
+            ev[1].record(); backward()
+            ev[2].record(); update()
+            ev[3].record(); torch.cuda.synchronize()
+            for i, n in enumerate(ms):
+                ms[n] += ev[i].elapsed_time(ev[i + 1]) / n_ev
+        bwd_flop = sum(f * (1 if i == 0 else 2) for i, f in enumerate(conv_flop)) + 2.0 * sum(dense_flop)
+        ach = bwd_flop / (ms["backward"] * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "kernel": "backward phase (loss, dense deltas and gradients, input gradient, pooling and "
+                    "convolution gradients: all launches between the forward pass and the update)",
+                    "achieved": ach, "peak": PEAK_MFMA_F32_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_MFMA_F32_TFLOPS,
+                    "traffic": None, "avg_launch_us": ms["backward"] * 1e3}
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import dn_conv_oracle as co
+        from oracle.dn_oracle import Oracle
+        o = Oracle("o32", widths, acts, CE)
+        o.set_params(Wd, bd)
+        n = 1
+        while True:   # grow the sample until the checker works for about ten seconds
+            t1 = time.perf_counter()
+            a, Ys = Xh[:n], []
+            for blk in blocks:
+                Yo = co.conv_forward("o32", a, blk["Wh"], blk["bh"], 1, pad, RELU)
+                Ys.append((a, Yo))
+                a = co.maxpool_forward("o32", Yo, 2, 2)
+            o.forward(a.reshape(n, flat))
+            o.backward(labels_h[:n])
+            d = o.input_gradient().reshape(a.shape)
+            for blk, (a_in, Yo) in zip(reversed(blocks), reversed(Ys)):
+                dYo = co.maxpool_backward("o32", Yo, d, 2, 2)
+                _, d, _, _ = co.conv_backward("o32", a_in, blk["Wh"], Yo, dYo, 1, pad, RELU)
+            dt = time.perf_counter() - t1
+            if dt >= 5.0 or n >= B:
+                break
+            n = min(B, max(n + 1, int(n * min(8.0, 10.0 / max(dt, 1e-3)))))
+        cpu = {"value": n / dt, "unit": "samples/s", "cores": 1, "kind": "oracle",
+               "sample": "forward and backward of the first %d images of the same batch (no update), %.1f s" % (n, dt)}
+    net.close()
+    return {"metric": "training samples/sec (fwd+bwd+update)", "value": B * steps / wall,
+            "unit": "samples/s", "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": wall / steps * 1e3,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "config": {"workload": args.workload, "batch": B, "input": [C0, H0, W0], "conv_channels": list(chans),
+                       "filter": K, "pad": pad, "pool": "2x2 stride 2", "dense_widths": widths, "activation": "relu",
+                       "loss": "softmax + cross-entropy", "lr": lr, "momentum": 0.0},
+            "roofline": roofline, "cpu_baseline": cpu,
+            "phase_ms": ms, "total_tflops": step_flop * steps / wall / 1e12}
+
+
 def bench_conv(args, shape):
     """One step = forward and backward of the layer pair on one batch: convolution (ReLU), pooling,
     pooling backward, convolution backward (delta, filter / bias gradients, input gradient)."""
@@ -248,9 +392,16 @@ def main():
         print(json.dumps(bench_conv(args, CONV_WORKLOADS[args.workload])))
         return
 
+    if args.workload in CNN_WORKLOADS:
+        assert torch.cuda.is_available(), "bench.py needs the GPU"
+        dn.lib()
+        print(json.dumps(bench_cnn(args, CNN_WORKLOADS[args.workload])))
+        return
+
     table = workloads()
     if args.workload not in table:
-        sys.exit("unknown workload %r; choose from %s" % (args.workload, ", ".join(sorted(list(table) + list(CONV_WORKLOADS)))))
+        sys.exit("unknown workload %r; choose from %s"
+                 % (args.workload, ", ".join(sorted(list(table) + list(CONV_WORKLOADS) + list(CNN_WORKLOADS)))))
     make, bound = table[args.workload]
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     dn.lib()   # fails loudly if libdn.so has not been built

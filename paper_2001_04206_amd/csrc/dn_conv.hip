@@ -210,24 +210,27 @@ hipError_t launch_corr_rows(const CorrShape &s, const float *In, const float *Wt
 // over the banks), the input as [channel][8 + kh - 1 rows][32 + kw - 1 columns], zeros outside
 // the image.  Filters must be stored [oc][ic][tap] (w_in_stride = taps, no flip): the input
 // gradient passes a flipped, transposed copy (written by conv_delta_kernel).
-constexpr int MC_COLS = 32, MC_IC = 8, MC_WSTRIDE = 80;
+constexpr int MC_IC = 8, MC_WSTRIDE = 80;
 typedef float v16f_t __attribute__((ext_vector_type(16)));
 
-template <int OT, int RW, int KS>   // KS: filter edge known at compile time (3: the tap loop is unrolled), 0: any
+// KS: filter edge known at compile time (3: the tap loop is unrolled), 0: any.  TW: columns of the
+// workgroup's pixel tile, 32 (a 32-pixel accumulator tile is one output row) or 16 (two rows of 16:
+// images of at most 16 columns would leave half of every 32-column tile empty).
+template <int OT, int RW, int KS, int TW = 32>
 __global__ __launch_bounds__(256) void corr_mfma_kernel(CorrShape s, const float *__restrict__ In,
                                                         const float *__restrict__ Wt, const float *__restrict__ bias,
                                                         float *__restrict__ Out)
 {
     extern __shared__ __attribute__((aligned(16))) float lds[];
-    constexpr int OC = 32 * OT, MC_ROWS = 4 * RW;
+    constexpr int OC = 32 * OT, RPT = 32 / TW, MC_ROWS = 4 * RW * RPT;   // RPT: output rows per accumulator tile
     const int taps = s.KH * s.KW, kstage = MC_IC * taps;
-    const int prow = MC_ROWS + s.KH - 1, pcol = MC_COLS + s.KW - 1;   // staged input patch per channel
+    const int prow = MC_ROWS + s.KH - 1, pcol = TW + s.KW - 1;   // staged input patch per channel
     float *wl = lds;                                   // [kstage][MC_WSTRIDE]
     float *pl = lds + (size_t)kstage * MC_WSTRIDE;     // [MC_IC][prow][pcol]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int idx = lane & 31, h = lane >> 5;
-    const int col_tiles = (s.Wo + MC_COLS - 1) / MC_COLS;
-    const int i0 = (blockIdx.x / col_tiles) * MC_ROWS, j0 = (blockIdx.x % col_tiles) * MC_COLS;
+    const int col_tiles = (s.Wo + TW - 1) / TW;
+    const int i0 = (blockIdx.x / col_tiles) * MC_ROWS, j0 = (blockIdx.x % col_tiles) * TW;
     const int oc0 = blockIdx.y * OC, b = blockIdx.z;
     v16f_t acc[OT][RW];
 #pragma unroll
@@ -247,7 +250,7 @@ __global__ __launch_bounds__(256) void corr_mfma_kernel(CorrShape s, const float
     // first value is stored; the staging indices are recomputed from the thread
     // index every time rather than kept in registers across the product loop (the empty asm hides
     // that they repeat)
-    constexpr int PROW3 = MC_ROWS + 2, PCOL3 = MC_COLS + 2, NP3 = MC_IC * PROW3 * PCOL3;
+    constexpr int PROW3 = MC_ROWS + 2, PCOL3 = TW + 2, NP3 = MC_IC * PROW3 * PCOL3;
     constexpr int XP3 = KS == 3 ? (NP3 + 255) / 256 : 1, WP3 = KS == 3 ? MC_IC * 9 / 4 : 1;
     [[maybe_unused]] float wreg[WP3], xreg[XP3];
     [[maybe_unused]] auto stage_request = [&](int ic0) {
@@ -332,7 +335,7 @@ __global__ __launch_bounds__(256) void corr_mfma_kernel(CorrShape s, const float
         }
         // k slot h of every instruction: input channel 2 * pair + h at one tap
         const float *wa = wl + (size_t)(h * taps) * MC_WSTRIDE + idx;
-        const float *pb = pl + (size_t)h * prow * pcol + (RW * wave) * pcol + idx;
+        const float *pb = pl + (size_t)h * prow * pcol + (RW * wave * RPT + idx / TW) * pcol + idx % TW;
 #pragma unroll
         for (int pair = 0; pair < MC_IC / 2; ++pair) {
             const float *wp = wa + (size_t)(2 * pair * taps) * MC_WSTRIDE;
@@ -340,7 +343,7 @@ __global__ __launch_bounds__(256) void corr_mfma_kernel(CorrShape s, const float
             auto one_tap = [&](int tap, int po) {   // po: patch offset u * pcol + v of the tap
                 float xv[RW];
 #pragma unroll
-                for (int q = 0; q < RW; ++q) xv[q] = pp[po + q * pcol];
+                for (int q = 0; q < RW; ++q) xv[q] = pp[po + q * RPT * pcol];
                 const float *wq = wp + tap * MC_WSTRIDE;
 #pragma unroll
                 for (int t = 0; t < OT; ++t) {
@@ -368,12 +371,12 @@ __global__ __launch_bounds__(256) void corr_mfma_kernel(CorrShape s, const float
         if (tid < OC) wl[tid] = oc0 + tid < s.Cout ? bias[oc0 + tid] : 0.f;
         __syncthreads();
     }
-    // register r of lane (idx, h): output channel 8 (r / 4) + 4 h + r % 4 of the tile, pixel idx of the row
-    const int j = j0 + idx;
+    // register r of lane (idx, h): output channel 8 (r / 4) + 4 h + r % 4 of the tile, pixel idx of the tile's row(s)
+    const int j = j0 + idx % TW;
     if (j >= s.Wo) return;
 #pragma unroll
     for (int q = 0; q < RW; ++q) {
-        const int i = i0 + RW * wave + q;
+        const int i = i0 + (RW * wave + q) * RPT + idx / TW;
         if (i >= s.Ho) continue;
 #pragma unroll
         for (int t = 0; t < OT; ++t)
@@ -393,24 +396,24 @@ bool corr_mfma_fits(const CorrShape &s)
     return s.Cout >= 32 && s.Cin >= 8 && s.Wo >= 16 && s.w_in_stride == s.KH * s.KW && !s.flip;
 }
 
-template <int OT, int RW, int KS>
+template <int OT, int RW, int KS, int TW = 32>
 hipError_t launch_corr_mfma_as(const CorrShape &s, const float *In, const float *Wt, const float *bias, float *Out,
                                hipStream_t stream)
 {
-    constexpr int rows = 4 * RW;
+    constexpr int rows = 4 * RW * (32 / TW);
     const int taps = s.KH * s.KW;
     const size_t lds = sizeof(float) * ((size_t)MC_IC * taps * MC_WSTRIDE +
-                                        (size_t)MC_IC * (rows + s.KH - 1) * (MC_COLS + s.KW - 1));
+                                        (size_t)MC_IC * (rows + s.KH - 1) * (TW + s.KW - 1));
     static bool attr_set = false;   // 7 x 7 filters need up to 146 KB, more than the default limit of dynamic LDS
     if (!attr_set) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&corr_mfma_kernel<OT, RW, KS>),
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&corr_mfma_kernel<OT, RW, KS, TW>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const dim3 grid((unsigned)(((s.Ho + rows - 1) / rows) * ((s.Wo + MC_COLS - 1) / MC_COLS)),
+    const dim3 grid((unsigned)(((s.Ho + rows - 1) / rows) * ((s.Wo + TW - 1) / TW)),
                     (unsigned)((s.Cout + 32 * OT - 1) / (32 * OT)), (unsigned)s.B);
-    hipLaunchKernelGGL((corr_mfma_kernel<OT, RW, KS>), grid, dim3(256), lds, stream, s, In, Wt, bias, Out);
+    hipLaunchKernelGGL((corr_mfma_kernel<OT, RW, KS, TW>), grid, dim3(256), lds, stream, s, In, Wt, bias, Out);
     return hipGetLastError();
 }
 
@@ -418,9 +421,22 @@ hipError_t launch_corr_mfma(const CorrShape &s, const float *In, const float *Wt
                             hipStream_t stream)
 {
     const bool k3 = s.KH == 3 && s.KW == 3;
-    if (s.Cout > 32)
+    // 3 x 3: pixel tiles of 16 rows x 16 columns instead of 8 x 32 where they cover the image with less padding
+    const auto padded = [&](int rows, int cols) {
+        return (long)((s.Ho + rows - 1) / rows * rows) * ((s.Wo + cols - 1) / cols * cols);
+    };
+    const bool narrow = k3 && padded(16, 16) < padded(8, 32);
+    // ... and of half the rows when the full tiles would leave CUs without a workgroup
+    const long wg16 = (long)((s.Ho + 15) / 16) * ((s.Wo + 15) / 16) * s.B * ((s.Cout + 63) / 64);
+    const bool small = narrow && wg16 < 512;
+    if (s.Cout > 32) {
+        if (small) return launch_corr_mfma_as<2, 1, 3, 16>(s, In, Wt, bias, Out, stream);
+        if (narrow) return launch_corr_mfma_as<2, 2, 3, 16>(s, In, Wt, bias, Out, stream);
         return k3 ? launch_corr_mfma_as<2, 2, 3>(s, In, Wt, bias, Out, stream)
                   : launch_corr_mfma_as<2, 2, 0>(s, In, Wt, bias, Out, stream);
+    }
+    if (small) return launch_corr_mfma_as<1, 1, 3, 16>(s, In, Wt, bias, Out, stream);
+    if (narrow) return launch_corr_mfma_as<1, 2, 3, 16>(s, In, Wt, bias, Out, stream);
     return k3 ? launch_corr_mfma_as<1, 2, 3>(s, In, Wt, bias, Out, stream)
               : launch_corr_mfma_as<1, 2, 0>(s, In, Wt, bias, Out, stream);
 }
@@ -667,10 +683,13 @@ __global__ __launch_bounds__(256) void conv_dw_slide_kernel(ConvShape s, const f
 // constant per pixel pair.  The partial result goes to part[chunk][oc][ic][tap] like the other
 // filter-gradient kernels', the bias sums (input-channel group 0: sums of the delta values the
 // workgroup stages) behind it; conv_dw_reduce_kernel adds the chunks.
-constexpr int DWM_THREADS = 256, DWM_IG = 17, DWM_DSTRIDE = 129, DWM_PROW = 6, DWM_PCOL = 34;
-constexpr int DWM_DP = (2048 + DWM_THREADS - 1) / DWM_THREADS;                               // delta pieces per thread
-constexpr int DWM_XP = (DWM_IG * DWM_PROW * DWM_PCOL + DWM_THREADS - 1) / DWM_THREADS;   // input values per thread
+// TW: columns of a pixel block, 32 (4 rows) or 16 (8 rows; images of at most 16 columns would leave
+// half of every 32-column block empty).
+constexpr int DWM_THREADS = 256, DWM_IG = 17, DWM_DSTRIDE = 129;
+constexpr int DWM_DP = (2048 + DWM_THREADS - 1) / DWM_THREADS;   // delta pieces per thread
+constexpr int DWM_XMAX = DWM_IG * 6 * 34;                        // staged input values: the larger of the two block shapes
 
+template <int TW>
 __global__ __launch_bounds__(DWM_THREADS, 3) void conv_dw_mfma_kernel(ConvShape s, const float *__restrict__ X,
                                                                       const float *__restrict__ delta,
                                                                       float *__restrict__ part, int ig, int bands,
@@ -678,8 +697,11 @@ __global__ __launch_bounds__(DWM_THREADS, 3) void conv_dw_mfma_kernel(ConvShape 
                                                                       int delta_vec)
 {
     __shared__ __attribute__((aligned(16))) float dl[64 * DWM_DSTRIDE];
-    __shared__ float xl[DWM_IG * DWM_PROW * DWM_PCOL];
+    __shared__ float xl[DWM_XMAX];
     constexpr int taps = 9;
+    constexpr int BR = 128 / TW, DWM_PROW = BR + 2, DWM_PCOL = TW + 2;   // block rows; staged input rows and columns
+    constexpr int NX = DWM_IG * DWM_PROW * DWM_PCOL, DWM_XP = (NX + DWM_THREADS - 1) / DWM_THREADS;
+    static_assert(NX <= DWM_XMAX, "staged input exceeds its LDS array");
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int idx = lane & 31, h = lane >> 5;
     const int groups = (s.Cin + ig - 1) / ig;
@@ -708,21 +730,21 @@ __global__ __launch_bounds__(DWM_THREADS, 3) void conv_dw_mfma_kernel(ConvShape 
 #pragma unroll
     for (int m = 0; m < DWM_DP; ++m) bsum[m] = 0.f;
     for (int b = b_lo; b < b_hi; ++b)
-    for (int i0 = row_lo; i0 < row_hi; i0 += 4)
-        for (int j0 = 0; j0 < s.Wo; j0 += 32) {
+    for (int i0 = row_lo; i0 < row_hi; i0 += BR)
+        for (int j0 = 0; j0 < s.Wo; j0 += TW) {
             __syncthreads();   // the previous block has been used
             // The staging indices are recomputed from the thread index in every block rather than
             // kept in registers across the product loop (the empty asm hides that they repeat).
             int st = tid;
             asm volatile("" : "+v"(st));
-            // delta: 64 channels x 4 rows x 8 pieces of four pixels = 2048 pieces; input: nic x 6 x 34 values
+            // delta: 64 channels x BR rows x TW / 4 pieces of four pixels = 2048 pieces; input: nic x (BR + 2) x (TW + 2) values
             v4_t dreg[DWM_DP];
             float xreg[DWM_XP];
             const float *dblk = delta + ((size_t)b * s.Cout + oc0) * pix + (size_t)i0 * s.Wo + j0;
 #pragma unroll
             for (int m = 0; m < DWM_DP; ++m) {
                 const int e = st + DWM_THREADS * m;
-                const int q = e & 7, row = (e >> 3) & 3, ocl = e >> 5;
+                const int q = e % (TW / 4), row = (e / (TW / 4)) % BR, ocl = e >> 5;
                 const bool ok = e < 2048 && oc0 + ocl < s.Cout && i0 + row < row_hi && j0 + 4 * q < s.Wo;   // w_out is a multiple of 4
                 v4_t v = {0.f, 0.f, 0.f, 0.f};
                 if (ok) {
@@ -746,7 +768,7 @@ __global__ __launch_bounds__(DWM_THREADS, 3) void conv_dw_mfma_kernel(ConvShape 
             for (int m = 0; m < DWM_DP; ++m) {
                 const int e = st + DWM_THREADS * m;
                 if (e < 2048) {
-                    float *dst = dl + (e >> 5) * DWM_DSTRIDE + ((e >> 3) & 3) * 32 + 4 * (e & 7);
+                    float *dst = dl + (e >> 5) * DWM_DSTRIDE + 4 * (e & 31);   // pixel (row, 4 q) of the block = row * TW + 4 q
                     dst[0] = dreg[m][0]; dst[1] = dreg[m][1]; dst[2] = dreg[m][2]; dst[3] = dreg[m][3];
                     bsum[m] += (dreg[m][0] + dreg[m][1]) + (dreg[m][2] + dreg[m][3]);
                 }
@@ -754,18 +776,18 @@ __global__ __launch_bounds__(DWM_THREADS, 3) void conv_dw_mfma_kernel(ConvShape 
 #pragma unroll
             for (int m = 0; m < DWM_XP; ++m) {
                 const int e = st + DWM_THREADS * m;
-                if (e < DWM_IG * DWM_PROW * DWM_PCOL) xl[e] = xreg[m];
+                if (e < NX) xl[e] = xreg[m];
             }
             __syncthreads();
-            // 64 pixel pairs: pair t holds pixels 2 t and 2 t + 1 of block row t / 16; the wave
-            // multiplies the shared tile over block row `wave`.  (The lane's half h is in its base
+            // 64 pixel pairs: pair t holds pixels 2 t and 2 t + 1 of the block (row 2 t / TW, column 2 t % TW);
+            // the wave multiplies the shared tile over the pairs of quarter `wave`.  (The lane's half h is in its base
             // addresses, so every offset below is a constant.)
 #pragma unroll
             for (int row = 0; row < 4; ++row) {
                 if (row == wave && shared_on) {
 #pragma unroll
                     for (int t = 16 * row; t < 16 * row + 16; ++t) {
-                        const int xo = (t >> 4) * DWM_PCOL + ((2 * t) & 31);
+                        const int xo = (2 * t / TW) * DWM_PCOL + (2 * t) % TW;
                         const float d0 = da[2 * t], d1 = da[32 * DWM_DSTRIDE + 2 * t];
                         const float x = xb[xo], x4 = xs[xo];
                         acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(d0, x, acc0, 0, 0, 0);
@@ -776,7 +798,7 @@ __global__ __launch_bounds__(DWM_THREADS, 3) void conv_dw_mfma_kernel(ConvShape 
                 } else {
 #pragma unroll
                     for (int t = 16 * row; t < 16 * row + 16; ++t) {
-                        const float x = xb[(t >> 4) * DWM_PCOL + ((2 * t) & 31)];
+                        const float x = xb[(2 * t / TW) * DWM_PCOL + (2 * t) % TW];
                         acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(da[2 * t], x, acc0, 0, 0, 0);
                         acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(da[32 * DWM_DSTRIDE + 2 * t], x, acc1, 0, 0, 0);
                     }
@@ -1047,7 +1069,7 @@ dn_status launched() { return hipGetLastError() == hipSuccess ? DN_OK : DN_ERR_D
 struct DwPlan {
     int co, groups, chunks, images_per_chunk;
     size_t filt;
-    int mfma_ig, bands, rows_per_band;   // mfma_ig > 0: the matrix-core kernel (chunks = batch x bands)
+    int mfma_ig, mfma_tw, bands, rows_per_band;   // mfma_ig > 0: the matrix-core kernel, pixel blocks mfma_tw columns wide
 };
 
 DwPlan dw_plan(const ConvShape &s)
@@ -1070,6 +1092,7 @@ DwPlan dw_plan(const ConvShape &s)
     p.chunks = (s.B + p.images_per_chunk - 1) / p.images_per_chunk;
     p.filt = (size_t)s.Cout * s.Cin * s.KH * s.KW;
     p.mfma_ig = 0;
+    p.mfma_tw = 32;
     p.bands = 1;
     p.rows_per_band = s.Ho;
     // few channels and a small batch: the stride-1 kernel also cuts the images into bands of at
@@ -1092,9 +1115,15 @@ DwPlan dw_plan(const ConvShape &s)
         int ipc = (int)(wg_per_image * s.B / want);
         if (ipc < 1) ipc = 1;
         int bands = ipc > 1 ? 1 : (int)((want + wg_per_image * s.B - 1) / (wg_per_image * s.B));
-        const int max_bands = (s.Ho + 3) / 4;
+        // pixel blocks of 8 rows x 16 columns instead of 4 x 32 where they cover the image with less padding
+        const auto padded = [&](int rows, int cols) {
+            return (long)((s.Ho + rows - 1) / rows * rows) * ((s.Wo + cols - 1) / cols * cols);
+        };
+        p.mfma_tw = padded(8, 16) < padded(4, 32) ? 16 : 32;
+        const int br = 128 / p.mfma_tw;
+        const int max_bands = (s.Ho + br - 1) / br;
         if (bands > max_bands) bands = max_bands;
-        const int rows = ((s.Ho + bands - 1) / bands + 3) / 4 * 4;   // whole blocks of four rows
+        const int rows = ((s.Ho + bands - 1) / bands + br - 1) / br * br;   // whole blocks
         bands = (s.Ho + rows - 1) / rows;
         const int image_groups = (s.B + ipc - 1) / ipc;
         if (wg_per_image * image_groups * bands >= 192) {   // else too few workgroups to be worth it
@@ -1184,9 +1213,13 @@ dn_status dn_conv_backward(const float *X_dev, const float *W_dev, const float *
     if (p.mfma_ig > 0) {
         const int groups = (s.Cin + p.mfma_ig - 1) / p.mfma_ig;
         const dim3 grid((unsigned)(groups * ((s.Cout + 63) / 64)), (unsigned)p.chunks);
-        hipLaunchKernelGGL(conv_dw_mfma_kernel, grid, dim3(DWM_THREADS), 0, stream, s, X_dev, delta_dev, part, p.mfma_ig,
-                           p.bands, p.rows_per_band, p.images_per_chunk,
-                           (int)(reinterpret_cast<uintptr_t>(delta_dev) % 16 == 0));
+        const int vec = (int)(reinterpret_cast<uintptr_t>(delta_dev) % 16 == 0);
+        if (p.mfma_tw == 16)
+            hipLaunchKernelGGL(conv_dw_mfma_kernel<16>, grid, dim3(DWM_THREADS), 0, stream, s, X_dev, delta_dev, part,
+                               p.mfma_ig, p.bands, p.rows_per_band, p.images_per_chunk, vec);
+        else
+            hipLaunchKernelGGL(conv_dw_mfma_kernel<32>, grid, dim3(DWM_THREADS), 0, stream, s, X_dev, delta_dev, part,
+                               p.mfma_ig, p.bands, p.rows_per_band, p.images_per_chunk, vec);
     } else if (s.stride == 1 && p.co == 8)
         hipLaunchKernelGGL((conv_dw_slide_kernel<3, 8>), grid_dw, dim3(256), 0, stream, s, X_dev, delta_dev, part,
                            p.images_per_chunk, p.bands, p.rows_per_band);

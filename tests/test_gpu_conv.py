@@ -31,9 +31,12 @@ CONV_CASES = [
     # 3 x 3, stride 1, output width a multiple of 4 and enough workgroups: the filter gradient on the matrix cores
     (16, 20, 22, 20, 35, 3, 3, 1, 1, TANH),       # two channel groups of 10 (no fifth tile), ragged bands and channels
     (16, 33, 9, 36, 70, 3, 3, 1, 1, SIG),         # groups of 17 and 16, two channel blocks, two column blocks
-    (48, 16, 18, 18, 64, 3, 3, 1, 0, RELU),       # no padding, one group of 16
+    (96, 16, 18, 18, 64, 3, 3, 1, 0, RELU),       # no padding, one group of 16; 16 x 16 outputs: pixel blocks 16 columns wide
+    (96, 16, 16, 44, 64, 3, 3, 1, 1, TANH),       # 16-column blocks, three per row, the last ragged
+    (128, 8, 16, 16, 256, 3, 3, 1, 1, RELU),      # 16 x 16 pixel tiles at full height (enough workgroups), 64-channel tiles
+    (512, 8, 16, 16, 32, 3, 3, 1, 1, TANH),       # the same with 32-channel tiles
     (97, 68, 4, 16, 256, 3, 3, 1, 1, TANH),       # two images per chunk, the last chunk has one
-    (48, 8, 17, 16, 32, 3, 3, 1, 1, SIG),         # the narrowest layer that takes this form: one half-filled channel tile, 17 rows in bands of 4
+    (64, 8, 17, 16, 32, 3, 3, 1, 1, SIG),         # the narrowest layer that takes this form: one half-filled channel tile, 17 rows in bands of 8
 ]
 
 

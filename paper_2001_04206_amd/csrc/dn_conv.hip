@@ -671,14 +671,15 @@ __global__ __launch_bounds__(256) void conv_dw_slide_kernel(ConvShape s, const f
 // is the product dW[oc][n] = sum_pixel delta[oc][pixel] xs[n][pixel] with n = (input channel, tap) and
 // xs the input shifted by the tap.  A workgroup of four waves owns 64 output channels, a group of up
 // to 17 input channels (153 columns n in five 32-column tiles) and a part of the batch's pixels
-// (one image, or a band of its rows).  Wave w owns column tile w over all pixels and column tile
+// (several images, one image, or a band of its rows).  Wave w owns column tile w over all pixels and column tile
 // 4 over a quarter of them (the four quarters are added through LDS at the end, in wave order),
 // each for both 32-channel halves: four accumulator tiles.  One matrix instruction takes two
 // pixels: lane (idx, h) supplies delta of channel idx and the input under its column, both at
 // pixel 2 t + h; one input value read from LDS serves both channel halves.  The pixels are walked
-// in blocks of 4 output rows x 32 columns staged through LDS - delta as [channel][128 pixels] (row
-// stride 129 words; read from memory 16 bytes at a time), the input as [channel][6][34] with zeros
-// outside the image - all of a block's loads requested before the first is stored.  A column's
+// in blocks of 128 / TW output rows x TW columns staged through LDS - delta as [channel][128 pixels]
+// (row stride 129 words; read from memory 16 bytes at a time where the caller's pointer allows),
+// the input as [channel][block rows + 2][TW + 2] with zeros outside the image - all of a block's
+// loads requested before the first is stored.  A column's
 // LDS address is a per-lane base (its channel and tap, and the lane's pixel of the pair) plus a
 // constant per pixel pair.  The partial result goes to part[chunk][oc][ic][tap] like the other
 // filter-gradient kernels', the bias sums (input-channel group 0: sums of the delta values the

@@ -624,13 +624,14 @@ dn_status dn_input_gradient(dn_net *net, int32_t batch, float *dX_dev)
     if (batch != net->fwd_batch) return DN_ERR_SHAPE;
     // the delta propagation of the hidden layers, one layer further: the input has no activation,
     // so the derivative factor is that of the identity (the kernel still reads an operand of the
-    // output's shape for it: the input itself)
+    // output's shape for it, whose values the identity's derivative ignores: the output buffer
+    // itself, so that the caller's X need not outlive dn_backward)
     GemmArgs g{};
     g.A = net->D(1); g.lda = net->n[1];
     g.B = net->W(1); g.ldb = net->n[0];
     g.M = batch; g.N = net->n[0]; g.K = net->n[1];
     g.C = dX_dev; g.ldc = net->n[0];
-    g.aux = net->X;
+    g.aux = dX_dev;
     g.act = DN_ACT_LINEAR;
     net->split_k(g);
     DN_HIP(launch_gemm(GEMM_DELTA, g, net->gemm_variant, net->stream));

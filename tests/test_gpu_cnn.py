@@ -119,70 +119,102 @@ def test_sgd_step(dn, n, mu):
     assert e.value.status == dn.DN_ERR_INVALID_ARG
 
 
-def test_convolutional_classifier_training_steps(dn):
-    """conv 3x3 (ReLU) -> 2x2 pooling -> fully connected (tanh) -> softmax, cross-entropy, two
-    plain gradient-descent steps on a batch: every gradient and every updated parameter against
-    the checker's convolution, pooling and dense-net functions chained in the same order."""
-    announce("convolutional classifier: two training steps")
-    B, Cin, H, W, Cout, K, pad = 16, 3, 12, 12, 8, 3, 1
-    hidden, classes, lr = 24, 5, 0.05
-    rng = np.random.default_rng(17)
-    X = rng.standard_normal((B, Cin, H, W)).astype(np.float32)
-    labels = rng.integers(0, classes, B).astype(np.int32)
-    Wc = (rng.standard_normal((Cout, Cin, K, K)) * np.sqrt(2.0 / (Cin * K * K))).astype(np.float32)
-    bc = (rng.standard_normal(Cout) * 0.1).astype(np.float32)
-    flat = Cout * (H // 2) * (W // 2)
-    widths, acts = [flat, hidden, classes], [TANH, SOFTMAX]
-    Wd = [(rng.standard_normal((widths[l + 1], widths[l])) / np.sqrt(widths[l])).astype(np.float32) for l in range(2)]
-    bd = [(rng.standard_normal(widths[l + 1]) * 0.1).astype(np.float32) for l in range(2)]
-
+def run_classifier(dn, B, C0, H0, W0, chans, dense, steps, seed, lr=0.05):
+    """conv 3x3 (ReLU) + 2x2 pooling blocks, then a dense net (tanh hidden layers, softmax,
+    cross-entropy); `steps` plain gradient-descent steps on one batch.  Every gradient and every
+    updated parameter is compared with the checker's convolution, pooling and dense-net functions
+    chained in the same order."""
+    K, pad = 3, 1
+    rng = np.random.default_rng(seed)
+    X = rng.standard_normal((B, C0, H0, W0)).astype(np.float32)
+    labels = rng.integers(0, dense[-1], B).astype(np.int32)
+    f32 = dict(dtype=torch.float32, device="cuda:0")
+    blocks, cin, h, w = [], C0, H0, W0
+    for cout in chans:
+        blk = {"W_ref": (rng.standard_normal((cout, cin, K, K)) * np.sqrt(2.0 / (cin * K * K))).astype(np.float32),
+               "b_ref": (rng.standard_normal(cout) * 0.1).astype(np.float32)}
+        blk["W"], blk["b"] = dev(blk["W_ref"]), dev(blk["b_ref"])
+        blk["Y"] = torch.empty((B, cout, h, w), **f32)
+        blk["P"] = torch.empty((B, cout, h // 2, w // 2), **f32)
+        blk["dP"], blk["dY"], blk["delta"] = torch.empty_like(blk["P"]), torch.empty_like(blk["Y"]), torch.empty_like(blk["Y"])
+        blk["dW"], blk["db"] = torch.empty_like(blk["W"]), torch.empty_like(blk["b"])
+        blocks.append(blk)
+        cin, h, w = cout, h // 2, w // 2
+    flat = cin * h * w
+    widths = [flat] + list(dense)
+    acts = [TANH] * (len(dense) - 1) + [SOFTMAX]
+    Wd = [(rng.standard_normal((widths[l + 1], widths[l])) / np.sqrt(widths[l])).astype(np.float32) for l in range(len(dense))]
+    bd = [(rng.standard_normal(widths[l + 1]) * 0.1).astype(np.float32) for l in range(len(dense))]
     net = dn.Net(widths, acts, CE, B)
     net.set_all(Wd, bd)
     o = Oracle("o32", widths, acts, CE)
     o.set_params(Wd, bd)
-    Xd, yd, Wcd, bcd = dev(X), dev(labels), dev(Wc), dev(bc)
-    Wc_ref, bc_ref = Wc.copy(), bc.copy()
-    f32 = dict(dtype=torch.float32, device="cuda:0")
-    Y = torch.empty((B, Cout, H, W), **f32)
-    P = torch.empty((B, Cout, H // 2, W // 2), **f32)
-    dP = torch.empty_like(P)
-    dY, delta, dXin = torch.empty_like(Y), torch.empty_like(Y), torch.empty_like(Xd)
-    dWc, dbc = torch.empty_like(Wcd), torch.empty_like(bcd)
+    Xd, yd = dev(X), dev(labels)
+    dX0 = torch.empty_like(Xd)
     loss = torch.zeros(1, **f32)
-    for step in range(2):
-        # device: forward through the three layers, backward in reverse, then the updates
-        dn.dn_conv_forward(Xd, Wcd, bcd, Y, 1, pad, RELU)
-        dn.dn_maxpool_forward(Y, P, 2, 2)
-        net.dn_forward(P.view(B, flat))
+    for step in range(steps):
+        # device: forward through all layers, backward in reverse, then the updates
+        a = Xd
+        for blk in blocks:
+            dn.dn_conv_forward(a, blk["W"], blk["b"], blk["Y"], 1, pad, RELU)
+            dn.dn_maxpool_forward(blk["Y"], blk["P"], 2, 2)
+            a = blk["P"]
+        net.dn_forward(a.view(B, flat))
         net.dn_backward(yd, loss)
-        net.dn_input_gradient(dP.view(B, flat))
-        dn.dn_maxpool_backward(Y, dP, dY, 2, 2)
-        dn.dn_conv_backward(Xd, Wcd, Y, dY, delta, dXin, dWc, dbc, 1, pad, RELU)
+        net.dn_input_gradient(blocks[-1]["dP"].view(B, flat))
+        for i in range(len(blocks) - 1, -1, -1):
+            blk = blocks[i]
+            dn.dn_maxpool_backward(blk["Y"], blk["dP"], blk["dY"], 2, 2)
+            dn.dn_conv_backward(Xd if i == 0 else blocks[i - 1]["P"], blk["W"], blk["Y"], blk["dY"], blk["delta"],
+                                dX0 if i == 0 else blocks[i - 1]["dP"], blk["dW"], blk["db"], 1, pad, RELU)
         net.dn_update(lr, 0.0)
-        dn.dn_sgd_step(Wcd, dWc, None, lr, 0.0)
-        dn.dn_sgd_step(bcd, dbc, None, lr, 0.0)
+        for blk in blocks:
+            dn.dn_sgd_step(blk["W"], blk["dW"], None, lr, 0.0)
+            dn.dn_sgd_step(blk["b"], blk["db"], None, lr, 0.0)
         # checker
-        Yr = co.conv_forward("o32", X, Wc_ref, bc_ref, 1, pad, RELU)
-        Pr = co.maxpool_forward("o32", Yr, 2, 2)
-        o.forward(Pr.reshape(B, flat))
+        a_ref, kept = X, []
+        for blk in blocks:
+            Yr = co.conv_forward("o32", a_ref, blk["W_ref"], blk["b_ref"], 1, pad, RELU)
+            kept.append((a_ref, Yr))
+            a_ref = co.maxpool_forward("o32", Yr, 2, 2)
+        o.forward(a_ref.reshape(B, flat))
         loss_r = o.backward(labels)
-        dPr = o.input_gradient().reshape(Pr.shape)
-        dYr = co.maxpool_backward("o32", Yr, dPr, 2, 2)
-        _, dXr, dWr, dbr = co.conv_backward("o32", X, Wc_ref, Yr, dYr, 1, pad, RELU)
-        o.update(lr, 0.0)
-        Wc_ref = (Wc_ref - np.float32(lr) * dWr).astype(np.float32)
-        bc_ref = (bc_ref - np.float32(lr) * dbr).astype(np.float32)
+        d_ref = o.input_gradient().reshape(a_ref.shape)
         note = " step %d" % step
         assert abs(float(loss.cpu()[0]) - loss_r) <= TOL * max(1.0, abs(loss_r)), (float(loss.cpu()[0]), loss_r)
-        assert_close(P.cpu().numpy(), Pr, TOL, "pooled" + note)
-        assert_close(dP.cpu().numpy(), dPr, TOL, "dP" + note)
-        assert_close(dWc.cpu().numpy(), dWr, TOL, "dW conv" + note)
-        assert_close(dbc.cpu().numpy(), dbr, TOL, "db conv" + note)
-        assert_close(dXin.cpu().numpy(), dXr, TOL, "dX" + note)
-        assert_close(Wcd.cpu().numpy(), Wc_ref, TOL, "W conv" + note)
+        assert_close(blocks[-1]["P"].cpu().numpy(), a_ref, TOL, "pooled" + note)
+        for i in range(len(blocks) - 1, -1, -1):
+            blk, (in_ref, Yr) = blocks[i], kept[i]
+            assert_close(blk["dP"].cpu().numpy(), d_ref, TOL, "dP block %d%s" % (i, note))
+            dYr = co.maxpool_backward("o32", Yr, d_ref, 2, 2)
+            _, d_ref, dWr, dbr = co.conv_backward("o32", in_ref, blk["W_ref"], Yr, dYr, 1, pad, RELU)
+            assert_close(blk["dW"].cpu().numpy(), dWr, TOL, "dW block %d%s" % (i, note))
+            assert_close(blk["db"].cpu().numpy(), dbr, TOL, "db block %d%s" % (i, note))
+            blk["W_ref"] = (blk["W_ref"] - np.float32(lr) * dWr).astype(np.float32)
+            blk["b_ref"] = (blk["b_ref"] - np.float32(lr) * dbr).astype(np.float32)
+            assert_close(blk["W"].cpu().numpy(), blk["W_ref"], TOL, "W block %d%s" % (i, note))
+        assert_close(dX0.cpu().numpy(), d_ref, TOL, "dX" + note)
+        o.update(lr, 0.0)
         Wr, br = o.get_params()
-        for l in (1, 2):
+        for l in range(1, len(widths)):
             Wg, bg = net.dn_get_params(l)
             assert_close(Wg, Wr[l - 1], TOL, "W_%d%s" % (l, note))
             assert_close(bg, br[l - 1], TOL, "b_%d%s" % (l, note))
     net.close()
+
+
+def test_convolutional_classifier_training_steps(dn):
+    announce("convolutional classifier: two training steps")
+    run_classifier(dn, 16, 3, 12, 12, (8,), (24, 5), steps=2, seed=17)
+
+
+def test_two_block_classifier_training_steps(dn):
+    announce("convolutional classifier with two blocks: two training steps")
+    run_classifier(dn, 6, 2, 16, 20, (5, 9), (12, 10, 4), steps=2, seed=18)
+
+
+def test_classifier_at_the_benchmark_shape(dn):
+    """The classifier bench.py times (128 x 3 x 32 x 32, blocks of 32 and 64 channels, dense
+    4096-512-10), one step in the same launch configuration."""
+    announce("convolutional classifier at the benchmark shape")
+    run_classifier(dn, 128, 3, 32, 32, (32, 64), (512, 10), steps=1, seed=19, lr=0.01)

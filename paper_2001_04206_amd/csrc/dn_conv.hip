@@ -746,12 +746,19 @@ __global__ __launch_bounds__(DWM_THREADS, 3) void conv_dw_mfma_kernel(ConvShape 
             for (int m = 0; m < DWM_DP; ++m) {
                 const int e = st + DWM_THREADS * m;
                 const int q = e % (TW / 4), row = (e / (TW / 4)) % BR, ocl = e >> 5;
-                const bool ok = e < 2048 && oc0 + ocl < s.Cout && i0 + row < row_hi && j0 + 4 * q < s.Wo;   // w_out is a multiple of 4
+                const int left = s.Wo - (j0 + 4 * q);   // pixels of the row from this piece on
+                const bool ok = e < 2048 && oc0 + ocl < s.Cout && i0 + row < row_hi && left > 0;
                 v4_t v = {0.f, 0.f, 0.f, 0.f};
                 if (ok) {
                     const float *src = dblk + (unsigned)(ocl * pix + row * s.Wo + 4 * q);
-                    if (delta_vec) v = *reinterpret_cast<const v4_t *>(src);   // the caller's pointer is 16-byte aligned
-                    else { v[0] = src[0]; v[1] = src[1]; v[2] = src[2]; v[3] = src[3]; }
+                    // 16 bytes at once if the caller's pointer is 16-byte aligned and the rows are whole pieces
+                    if (delta_vec) v = *reinterpret_cast<const v4_t *>(src);
+                    else {
+                        v[0] = src[0];
+                        if (left > 1) v[1] = src[1];
+                        if (left > 2) v[2] = src[2];
+                        if (left > 3) v[3] = src[3];
+                    }
                 }
                 dreg[m] = v;
             }
@@ -1106,7 +1113,7 @@ DwPlan dw_plan(const ConvShape &s)
         p.bands = (s.Ho + p.rows_per_band - 1) / p.rows_per_band;
         p.chunks *= p.bands;
     }
-    if (s.stride == 1 && s.KH == 3 && s.KW == 3 && s.Cout >= 32 && s.Cin >= 8 && s.Wo >= 16 && s.Wo % 4 == 0) {
+    if (s.stride == 1 && s.KH == 3 && s.KW == 3 && s.Cout >= 32 && s.Cin >= 8 && s.Wo >= 14) {
         const int groups = (s.Cin + DWM_IG - 1) / DWM_IG;
         const int ig = (s.Cin + groups - 1) / groups;   // even groups
         // about three workgroups per CU: several images per chunk if the batch gives more, else
@@ -1214,7 +1221,7 @@ dn_status dn_conv_backward(const float *X_dev, const float *W_dev, const float *
     if (p.mfma_ig > 0) {
         const int groups = (s.Cin + p.mfma_ig - 1) / p.mfma_ig;
         const dim3 grid((unsigned)(groups * ((s.Cout + 63) / 64)), (unsigned)p.chunks);
-        const int vec = (int)(reinterpret_cast<uintptr_t>(delta_dev) % 16 == 0);
+        const int vec = (int)(reinterpret_cast<uintptr_t>(delta_dev) % 16 == 0 && s.Wo % 4 == 0);
         if (p.mfma_tw == 16)
             hipLaunchKernelGGL(conv_dw_mfma_kernel<16>, grid, dim3(DWM_THREADS), 0, stream, s, X_dev, delta_dev, part,
                                p.mfma_ig, p.bands, p.rows_per_band, p.images_per_chunk, vec);

@@ -33,6 +33,8 @@ CONV_CASES = [
     (16, 33, 9, 36, 70, 3, 3, 1, 1, SIG),         # groups of 17 and 16, two channel blocks, two column blocks
     (96, 16, 18, 18, 64, 3, 3, 1, 0, RELU),       # no padding, one group of 16; 16 x 16 outputs: pixel blocks 16 columns wide
     (96, 16, 16, 44, 64, 3, 3, 1, 1, TANH),       # 16-column blocks, three per row, the last ragged
+    (96, 16, 16, 16, 64, 3, 3, 1, 0, TANH),       # 14 x 14 outputs: rows are not whole 16-byte pieces, 16-column blocks
+    (16, 20, 24, 32, 35, 3, 3, 1, 0, SIG),        # 22 x 30 outputs: the same with 32-column blocks
     (128, 8, 16, 16, 256, 3, 3, 1, 1, RELU),      # 16 x 16 pixel tiles at full height (enough workgroups), 64-channel tiles
     (512, 8, 16, 16, 32, 3, 3, 1, 1, TANH),       # the same with 32-channel tiles
     (97, 68, 4, 16, 256, 3, 3, 1, 1, TANH),       # two images per chunk, the last chunk has one

@@ -249,7 +249,7 @@ def bench_conv(args, shape):
     if not args.no_kernel_timing:
         ach = 2.0 * fwd_flop / (ms["conv_backward"] * 1e-3) / 1e12   # filter gradient + input gradient
         # wide 3 x 3 layers take the matrix-core kernels for both gradients, the others plain vector kernels
-        on_mfma = Cout >= 32 and Cin >= 8 and Wo >= 16 and K == 3 and stride == 1
+        on_mfma = Cout >= 32 and Cin >= 8 and Wo >= 12 and K == 3 and stride == 1
         peak = PEAK_MFMA_F32_TFLOPS if on_mfma else PEAK_VALU_F32_TFLOPS
         roofline = {"bound": "mfma" if on_mfma else "alu",
                     "kernel": "conv_backward (delta, filter / bias gradient, chunk sum, input gradient: four launches)",

@@ -393,7 +393,9 @@ __global__ __launch_bounds__(256) void corr_mfma_kernel(CorrShape s, const float
 // Wide enough for the matrix-core form?  (Narrow layers would mostly multiply padding.)
 bool corr_mfma_fits(const CorrShape &s)
 {
-    return s.Cout >= 32 && s.Cin >= 8 && s.Wo >= 16 && s.w_in_stride == s.KH * s.KW && !s.flip;
+    // (3 x 3 filters have 16-column pixel tiles; the others' tiles are 32 columns wide)
+    const int min_w = s.KH == 3 && s.KW == 3 ? 12 : 16;
+    return s.Cout >= 32 && s.Cin >= 8 && s.Wo >= min_w && s.w_in_stride == s.KH * s.KW && !s.flip;
 }
 
 template <int OT, int RW, int KS, int TW = 32>
@@ -1113,7 +1115,7 @@ DwPlan dw_plan(const ConvShape &s)
         p.bands = (s.Ho + p.rows_per_band - 1) / p.rows_per_band;
         p.chunks *= p.bands;
     }
-    if (s.stride == 1 && s.KH == 3 && s.KW == 3 && s.Cout >= 32 && s.Cin >= 8 && s.Wo >= 14) {
+    if (s.stride == 1 && s.KH == 3 && s.KW == 3 && s.Cout >= 32 && s.Cin >= 8 && s.Wo >= 12) {
         const int groups = (s.Cin + DWM_IG - 1) / DWM_IG;
         const int ig = (s.Cin + groups - 1) / groups;   // even groups
         // about three workgroups per CU: several images per chunk if the batch gives more, else

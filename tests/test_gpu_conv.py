@@ -23,7 +23,7 @@ CONV_CASES = [
     (4, 3, 33, 31, 9, 3, 3, 3, 0, TANH),          # stride 3, ragged
     (1, 16, 1, 1, 8, 1, 1, 1, 0, SIG),            # one-pixel images: a dense layer
     (16, 8, 28, 28, 16, 5, 5, 1, 0, RELU),        # the size of a small image classifier's second layer
-    # wide enough for the matrix-core form (>= 32 output channels, >= 8 input channels, >= 16 columns):
+    # wide enough for the matrix-core form (>= 32 output channels, >= 8 input channels, >= 16 columns, >= 12 for 3 x 3 filters):
     (2, 9, 21, 19, 35, 3, 3, 1, 1, TANH),         # forward on the matrix cores; ragged channels, rows and columns
     (2, 40, 18, 37, 33, 5, 3, 1, 2, SIG),         # forward and input gradient; non-square filter, two column tiles
     (1, 8, 20, 40, 32, 7, 7, 1, 3, TANH),         # largest filter: the biggest LDS stage
@@ -35,6 +35,7 @@ CONV_CASES = [
     (96, 16, 16, 44, 64, 3, 3, 1, 1, TANH),       # 16-column blocks, three per row, the last ragged
     (96, 16, 16, 16, 64, 3, 3, 1, 0, TANH),       # 14 x 14 outputs: rows are not whole 16-byte pieces, 16-column blocks
     (16, 20, 24, 32, 35, 3, 3, 1, 0, SIG),        # 22 x 30 outputs: the same with 32-column blocks
+    (96, 16, 15, 15, 64, 3, 3, 1, 0, RELU),       # 13 x 13 outputs: close to the narrowest images the matrix-core kernels take
     (128, 8, 16, 16, 256, 3, 3, 1, 1, RELU),      # 16 x 16 pixel tiles at full height (enough workgroups), 64-channel tiles
     (512, 8, 16, 16, 32, 3, 3, 1, 1, TANH),       # the same with 32-channel tiles
     (97, 68, 4, 16, 256, 3, 3, 1, 1, TANH),       # two images per chunk, the last chunk has one

@@ -4,7 +4,7 @@
 // in include/dn.h).  Gather form throughout: every output element is owned by one thread, wave or
 // workgroup, so nothing is accumulated with atomics and every sum has a fixed order.  Stride-1
 // layers wide enough for 32 x 32 tiles run their forward product and input gradient on the matrix
-// cores (corr_mfma_kernel), with 3 x 3 filters the filter gradient too (conv_dw_mfma_kernel);
+// cores (corr_mfma_kernel), with 3 x 3 or 5 x 5 filters the filter gradient too (conv_dw_mfma_kernel);
 // everything else uses register-tiled vector kernels.
 #include "dn_internal.h"
 #include "dn_wave.h"
@@ -669,7 +669,7 @@ __global__ __launch_bounds__(256) void conv_dw_slide_kernel(ConvShape s, const f
     }
 }
 
-// The stride-1 filter gradient of 3 x 3 filters on the matrix cores, for wide layers.  Per image it
+// The stride-1 filter gradient of 3 x 3 and 5 x 5 filters on the matrix cores, for wide layers.  Per image it
 // is the product dW[oc][n] = sum_pixel delta[oc][pixel] xs[n][pixel] with n = (input channel, tap) and
 // xs the input shifted by the tap.  A workgroup of four waves owns 64 output channels, a group of up
 // to 17 input channels (153 columns n in five 32-column tiles) and a part of the batch's pixels
@@ -687,12 +687,14 @@ __global__ __launch_bounds__(256) void conv_dw_slide_kernel(ConvShape s, const f
 // filter-gradient kernels', the bias sums (input-channel group 0: sums of the delta values the
 // workgroup stages) behind it; conv_dw_reduce_kernel adds the chunks.
 // TW: columns of a pixel block, 32 (4 rows) or 16 (8 rows; images of at most 16 columns would leave
-// half of every 32-column block empty).
-constexpr int DWM_THREADS = 256, DWM_IG = 17, DWM_DSTRIDE = 129;
+// half of every 32-column block empty).  KS: filter edge, 3 or 5 (5 x 5: groups of up to 6 input
+// channels, 150 columns; the text above gives the figures for 3 x 3).
+constexpr int DWM_THREADS = 256, DWM_DSTRIDE = 129;
+constexpr int dwm_group(int ks) { return 160 / (ks * ks); }     // input channels whose columns fit five 32-column tiles
 constexpr int DWM_DP = (2048 + DWM_THREADS - 1) / DWM_THREADS;   // delta pieces per thread
-constexpr int DWM_XMAX = DWM_IG * 6 * 34;                        // staged input values: the larger of the two block shapes
+constexpr int DWM_XMAX = 17 * 6 * 34;                            // staged input values: the largest of the block shapes
 
-template <int TW>
+template <int TW, int KS>
 __global__ __launch_bounds__(DWM_THREADS, 3) void conv_dw_mfma_kernel(ConvShape s, const float *__restrict__ X,
                                                                       const float *__restrict__ delta,
                                                                       float *__restrict__ part, int ig, int bands,
@@ -701,8 +703,8 @@ __global__ __launch_bounds__(DWM_THREADS, 3) void conv_dw_mfma_kernel(ConvShape 
 {
     __shared__ __attribute__((aligned(16))) float dl[64 * DWM_DSTRIDE];
     __shared__ float xl[DWM_XMAX];
-    constexpr int taps = 9;
-    constexpr int BR = 128 / TW, DWM_PROW = BR + 2, DWM_PCOL = TW + 2;   // block rows; staged input rows and columns
+    constexpr int taps = KS * KS, DWM_IG = dwm_group(KS);
+    constexpr int BR = 128 / TW, DWM_PROW = BR + KS - 1, DWM_PCOL = TW + KS - 1;   // block rows; staged input rows and columns
     constexpr int NX = DWM_IG * DWM_PROW * DWM_PCOL, DWM_XP = (NX + DWM_THREADS - 1) / DWM_THREADS;
     static_assert(NX <= DWM_XMAX, "staged input exceeds its LDS array");
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -718,7 +720,7 @@ __global__ __launch_bounds__(DWM_THREADS, 3) void conv_dw_mfma_kernel(ConvShape 
     // a column's channel and tap as an offset into the staged input (0 for columns past the last one)
     auto column_base = [&](int n) {
         const int n_ic = n / taps, n_tap = n - n_ic * taps;
-        return n < nic * taps ? (n_ic * DWM_PROW + n_tap / 3) * DWM_PCOL + n_tap % 3 : 0;
+        return n < nic * taps ? (n_ic * DWM_PROW + n_tap / KS) * DWM_PCOL + n_tap % KS : 0;
     };
     const int n_own = 32 * wave + idx, n_shared = 128 + idx;
     const bool shared_on = nic * taps > 128;   // the fifth tile has columns
@@ -1115,8 +1117,9 @@ DwPlan dw_plan(const ConvShape &s)
         p.bands = (s.Ho + p.rows_per_band - 1) / p.rows_per_band;
         p.chunks *= p.bands;
     }
-    if (s.stride == 1 && s.KH == 3 && s.KW == 3 && s.Cout >= 32 && s.Cin >= 8 && s.Wo >= 12) {
-        const int groups = (s.Cin + DWM_IG - 1) / DWM_IG;
+    if (s.stride == 1 && s.KH == s.KW && (s.KH == 3 || s.KH == 5) && s.Cout >= 32 && s.Cin >= 8 && s.Wo >= 12) {
+        const int max_group = s.KH == 3 ? dwm_group(3) : dwm_group(5);
+        const int groups = (s.Cin + max_group - 1) / max_group;
         const int ig = (s.Cin + groups - 1) / groups;   // even groups
         // about three workgroups per CU: several images per chunk if the batch gives more, else
         // one image per chunk cut into bands of rows
@@ -1224,12 +1227,10 @@ dn_status dn_conv_backward(const float *X_dev, const float *W_dev, const float *
         const int groups = (s.Cin + p.mfma_ig - 1) / p.mfma_ig;
         const dim3 grid((unsigned)(groups * ((s.Cout + 63) / 64)), (unsigned)p.chunks);
         const int vec = (int)(reinterpret_cast<uintptr_t>(delta_dev) % 16 == 0 && s.Wo % 4 == 0);
-        if (p.mfma_tw == 16)
-            hipLaunchKernelGGL(conv_dw_mfma_kernel<16>, grid, dim3(DWM_THREADS), 0, stream, s, X_dev, delta_dev, part,
-                               p.mfma_ig, p.bands, p.rows_per_band, p.images_per_chunk, vec);
-        else
-            hipLaunchKernelGGL(conv_dw_mfma_kernel<32>, grid, dim3(DWM_THREADS), 0, stream, s, X_dev, delta_dev, part,
-                               p.mfma_ig, p.bands, p.rows_per_band, p.images_per_chunk, vec);
+        auto *kernel = s.KH == 3 ? (p.mfma_tw == 16 ? conv_dw_mfma_kernel<16, 3> : conv_dw_mfma_kernel<32, 3>)
+                                 : (p.mfma_tw == 16 ? conv_dw_mfma_kernel<16, 5> : conv_dw_mfma_kernel<32, 5>);
+        hipLaunchKernelGGL(kernel, grid, dim3(DWM_THREADS), 0, stream, s, X_dev, delta_dev, part, p.mfma_ig, p.bands,
+                           p.rows_per_band, p.images_per_chunk, vec);
     } else if (s.stride == 1 && p.co == 8)
         hipLaunchKernelGGL((conv_dw_slide_kernel<3, 8>), grid_dw, dim3(256), 0, stream, s, X_dev, delta_dev, part,
                            p.images_per_chunk, p.bands, p.rows_per_band);

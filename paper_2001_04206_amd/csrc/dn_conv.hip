@@ -246,19 +246,19 @@ __global__ __launch_bounds__(256) void corr_mfma_kernel(CorrShape s, const float
     const bool w_on = w_ocl < OC;
     const int w_oc = min(oc0 + w_ocl, s.Cout - 1);
     const bool w_real = oc0 + w_ocl < s.Cout;
-    // 3 x 3 filters: every load of a stage is requested at once, into registers, before the
+    // Filter edge known (3 x 3, 5 x 5): every load of a stage is requested at once, into registers, before the
     // first value is stored; the staging indices are recomputed from the thread
     // index every time rather than kept in registers across the product loop (the empty asm hides
     // that they repeat)
-    constexpr int PROW3 = MC_ROWS + 2, PCOL3 = TW + 2, NP3 = MC_IC * PROW3 * PCOL3;
-    constexpr int XP3 = KS == 3 ? (NP3 + 255) / 256 : 1, WP3 = KS == 3 ? MC_IC * 9 / 4 : 1;
+    constexpr int TAPS3 = KS * KS, PROW3 = MC_ROWS + KS - 1, PCOL3 = TW + KS - 1, NP3 = MC_IC * PROW3 * PCOL3;
+    constexpr int XP3 = KS > 0 ? (NP3 + 255) / 256 : 1, WP3 = KS > 0 ? MC_IC * TAPS3 / 4 : 1;
     [[maybe_unused]] float wreg[WP3], xreg[XP3];
     [[maybe_unused]] auto stage_request = [&](int ic0) {
         const int st = tid;
-        const int kvalid = min(MC_IC, s.Cin - ic0) * 9;
+        const int kvalid = min(MC_IC, s.Cin - ic0) * TAPS3;
         const int ocl = st >> 2, kq = st & 3;
         const bool real = ocl < OC && oc0 + ocl < s.Cout;
-        const float *src = Wt + (size_t)min(oc0 + ocl, s.Cout - 1) * s.w_out_stride + (size_t)ic0 * 9;
+        const float *src = Wt + (size_t)min(oc0 + ocl, s.Cout - 1) * s.w_out_stride + (size_t)ic0 * TAPS3;
 #pragma unroll
         for (int m = 0; m < WP3; ++m) {
             const int kl = kq + 4 * m;
@@ -287,11 +287,11 @@ __global__ __launch_bounds__(256) void corr_mfma_kernel(CorrShape s, const float
             if (e < NP3) pl[e] = xreg[m];
         }
     };
-    if constexpr (KS == 3) stage_request(0);
+    if constexpr (KS > 0) stage_request(0);
     for (int ic0 = 0; ic0 < s.Cin; ic0 += MC_IC) {
         [[maybe_unused]] const int kvalid = min(MC_IC, s.Cin - ic0) * taps;   // k values of this stage that exist
         __syncthreads();   // the previous stage has been used
-        if constexpr (KS == 3) {
+        if constexpr (KS > 0) {
             stage_store();
         } else {
         // (loads in batches, all of a batch in flight before the first is stored)
@@ -330,7 +330,7 @@ __global__ __launch_bounds__(256) void corr_mfma_kernel(CorrShape s, const float
         }
         }
         __syncthreads();
-        if constexpr (KS == 3) {
+        if constexpr (KS > 0) {
             if (ic0 + MC_IC < s.Cin) stage_request(ic0 + MC_IC);
         }
         // k slot h of every instruction: input channel 2 * pair + h at one tap
@@ -422,7 +422,7 @@ hipError_t launch_corr_mfma_as(const CorrShape &s, const float *In, const float 
 hipError_t launch_corr_mfma(const CorrShape &s, const float *In, const float *Wt, const float *bias, float *Out,
                             hipStream_t stream)
 {
-    const bool k3 = s.KH == 3 && s.KW == 3;
+    const bool k3 = s.KH == 3 && s.KW == 3, k5 = s.KH == 5 && s.KW == 5;
     // 3 x 3: pixel tiles of 16 rows x 16 columns instead of 8 x 32 where they cover the image with less padding
     const auto padded = [&](int rows, int cols) {
         return (long)((s.Ho + rows - 1) / rows * rows) * ((s.Wo + cols - 1) / cols * cols);
@@ -434,11 +434,13 @@ hipError_t launch_corr_mfma(const CorrShape &s, const float *In, const float *Wt
     if (s.Cout > 32) {
         if (small) return launch_corr_mfma_as<2, 1, 3, 16>(s, In, Wt, bias, Out, stream);
         if (narrow) return launch_corr_mfma_as<2, 2, 3, 16>(s, In, Wt, bias, Out, stream);
+        if (k5) return launch_corr_mfma_as<2, 2, 5>(s, In, Wt, bias, Out, stream);
         return k3 ? launch_corr_mfma_as<2, 2, 3>(s, In, Wt, bias, Out, stream)
                   : launch_corr_mfma_as<2, 2, 0>(s, In, Wt, bias, Out, stream);
     }
     if (small) return launch_corr_mfma_as<1, 1, 3, 16>(s, In, Wt, bias, Out, stream);
     if (narrow) return launch_corr_mfma_as<1, 2, 3, 16>(s, In, Wt, bias, Out, stream);
+    if (k5) return launch_corr_mfma_as<1, 2, 5>(s, In, Wt, bias, Out, stream);
     return k3 ? launch_corr_mfma_as<1, 2, 3>(s, In, Wt, bias, Out, stream)
               : launch_corr_mfma_as<1, 2, 0>(s, In, Wt, bias, Out, stream);
 }

@@ -36,6 +36,8 @@ CONV_CASES = [
     (96, 16, 16, 16, 64, 3, 3, 1, 0, TANH),       # 14 x 14 outputs: rows are not whole 16-byte pieces, 16-column blocks
     (16, 20, 24, 32, 35, 3, 3, 1, 0, SIG),        # 22 x 30 outputs: the same with 32-column blocks
     (96, 16, 15, 15, 64, 3, 3, 1, 0, RELU),       # 13 x 13 outputs: close to the narrowest images the matrix-core kernels take
+    (4, 40, 20, 24, 36, 5, 5, 1, 2, RELU),        # 5 x 5 forward product and input gradient with stages requested ahead, 64-channel tiles
+    (4, 33, 17, 20, 32, 5, 5, 1, 2, TANH),        # the same with 32-channel tiles forward; a last stage of one channel
     (64, 12, 20, 20, 40, 5, 5, 1, 2, TANH),       # 5 x 5 filter gradient on the matrix cores: two groups of 6 channels, 32-column blocks
     (96, 8, 18, 18, 33, 5, 5, 1, 0, SIG),         # 5 x 5, 14 x 14 outputs: 16-column blocks, ragged pieces
     (128, 8, 16, 16, 256, 3, 3, 1, 1, RELU),      # 16 x 16 pixel tiles at full height (enough workgroups), 64-channel tiles

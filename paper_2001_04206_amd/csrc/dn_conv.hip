@@ -4,7 +4,7 @@
 // in include/dn.h).  Gather form throughout: every output element is owned by one thread, wave or
 // workgroup, so nothing is accumulated with atomics and every sum has a fixed order.  Stride-1
 // layers wide enough for 32 x 32 tiles run their forward product and input gradient on the matrix
-// cores (corr_mfma_kernel), with 3 x 3 or 5 x 5 filters the filter gradient too (conv_dw_mfma_kernel);
+// cores (corr_mfma_kernel), with square filters of odd edge the filter gradient too (conv_dw_mfma_kernel);
 // everything else uses register-tiled vector kernels.
 #include "dn_internal.h"
 #include "dn_wave.h"
@@ -671,12 +671,14 @@ __global__ __launch_bounds__(256) void conv_dw_slide_kernel(ConvShape s, const f
     }
 }
 
-// The stride-1 filter gradient of 3 x 3 and 5 x 5 filters on the matrix cores, for wide layers.  Per image it
-// is the product dW[oc][n] = sum_pixel delta[oc][pixel] xs[n][pixel] with n = (input channel, tap) and
-// xs the input shifted by the tap.  A workgroup of four waves owns 64 output channels, a group of up
-// to 17 input channels (153 columns n in five 32-column tiles) and a part of the batch's pixels
-// (several images, one image, or a band of its rows).  Wave w owns column tile w over all pixels and column tile
-// 4 over a quarter of them (the four quarters are added through LDS at the end, in wave order),
+// The stride-1 filter gradient of square filters of edge 3, 5 or 7 on the matrix cores, for wide
+// layers (described for 3 x 3).  Per image it is the product
+// dW[oc][n] = sum_pixel delta[oc][pixel] xs[n][pixel] with n = (input channel, tap) and xs the
+// input shifted by the tap.  A workgroup of four waves owns 64 output channels, a group of up to
+// 17 input channels (153 columns n in five 32-column tiles) and a part of the batch's pixels
+// (several images, one image, or a band of its rows).  Wave w owns column tile w over all pixels
+// and column tile 4 over a quarter of them (the four quarters are added through LDS at the end, in
+// wave order),
 // each for both 32-channel halves: four accumulator tiles.  One matrix instruction takes two
 // pixels: lane (idx, h) supplies delta of channel idx and the input under its column, both at
 // pixel 2 t + h; one input value read from LDS serves both channel halves.  The pixels are walked
@@ -689,8 +691,8 @@ __global__ __launch_bounds__(256) void conv_dw_slide_kernel(ConvShape s, const f
 // filter-gradient kernels', the bias sums (input-channel group 0: sums of the delta values the
 // workgroup stages) behind it; conv_dw_reduce_kernel adds the chunks.
 // TW: columns of a pixel block, 32 (4 rows) or 16 (8 rows; images of at most 16 columns would leave
-// half of every 32-column block empty).  KS: filter edge, 3 or 5 (5 x 5: groups of up to 6 input
-// channels, 150 columns; the text above gives the figures for 3 x 3).
+// half of every 32-column block empty).  KS: filter edge, 3, 5 or 7 (5 x 5: groups of up to 6 input
+// channels, 150 columns; 7 x 7: 3 channels, 147 columns; the text above gives the figures for 3 x 3).
 constexpr int DWM_THREADS = 256, DWM_DSTRIDE = 129;
 constexpr int dwm_group(int ks) { return 160 / (ks * ks); }     // input channels whose columns fit five 32-column tiles
 constexpr int DWM_DP = (2048 + DWM_THREADS - 1) / DWM_THREADS;   // delta pieces per thread
@@ -1119,8 +1121,8 @@ DwPlan dw_plan(const ConvShape &s)
         p.bands = (s.Ho + p.rows_per_band - 1) / p.rows_per_band;
         p.chunks *= p.bands;
     }
-    if (s.stride == 1 && s.KH == s.KW && (s.KH == 3 || s.KH == 5) && s.Cout >= 32 && s.Cin >= 8 && s.Wo >= 12) {
-        const int max_group = s.KH == 3 ? dwm_group(3) : dwm_group(5);
+    if (s.stride == 1 && s.KH == s.KW && (s.KH == 3 || s.KH == 5 || s.KH == 7) && s.Cout >= 32 && s.Cin >= 8 && s.Wo >= 12) {
+        const int max_group = s.KH == 3 ? dwm_group(3) : (s.KH == 5 ? dwm_group(5) : dwm_group(7));
         const int groups = (s.Cin + max_group - 1) / max_group;
         const int ig = (s.Cin + groups - 1) / groups;   // even groups
         // about three workgroups per CU: several images per chunk if the batch gives more, else
@@ -1229,8 +1231,9 @@ dn_status dn_conv_backward(const float *X_dev, const float *W_dev, const float *
         const int groups = (s.Cin + p.mfma_ig - 1) / p.mfma_ig;
         const dim3 grid((unsigned)(groups * ((s.Cout + 63) / 64)), (unsigned)p.chunks);
         const int vec = (int)(reinterpret_cast<uintptr_t>(delta_dev) % 16 == 0 && s.Wo % 4 == 0);
-        auto *kernel = s.KH == 3 ? (p.mfma_tw == 16 ? conv_dw_mfma_kernel<16, 3> : conv_dw_mfma_kernel<32, 3>)
-                                 : (p.mfma_tw == 16 ? conv_dw_mfma_kernel<16, 5> : conv_dw_mfma_kernel<32, 5>);
+        auto *kernel = s.KH == 3   ? (p.mfma_tw == 16 ? conv_dw_mfma_kernel<16, 3> : conv_dw_mfma_kernel<32, 3>)
+                       : s.KH == 5 ? (p.mfma_tw == 16 ? conv_dw_mfma_kernel<16, 5> : conv_dw_mfma_kernel<32, 5>)
+                                   : (p.mfma_tw == 16 ? conv_dw_mfma_kernel<16, 7> : conv_dw_mfma_kernel<32, 7>);
         hipLaunchKernelGGL(kernel, grid, dim3(DWM_THREADS), 0, stream, s, X_dev, delta_dev, part, p.mfma_ig, p.bands,
                            p.rows_per_band, p.images_per_chunk, vec);
     } else if (s.stride == 1 && p.co == 8)

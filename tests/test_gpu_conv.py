@@ -40,6 +40,7 @@ CONV_CASES = [
     (4, 33, 17, 20, 32, 5, 5, 1, 2, TANH),        # the same with 32-channel tiles forward; a last stage of one channel
     (64, 12, 20, 20, 40, 5, 5, 1, 2, TANH),       # 5 x 5 filter gradient on the matrix cores: two groups of 6 channels, 32-column blocks
     (96, 8, 18, 18, 33, 5, 5, 1, 0, SIG),         # 5 x 5, 14 x 14 outputs: 16-column blocks, ragged pieces
+    (64, 9, 20, 20, 40, 7, 7, 1, 3, SIG),         # 7 x 7 filter gradient on the matrix cores: three groups of 3 channels
     (128, 8, 16, 16, 256, 3, 3, 1, 1, RELU),      # 16 x 16 pixel tiles at full height (enough workgroups), 64-channel tiles
     (512, 8, 16, 16, 32, 3, 3, 1, 1, TANH),       # the same with 32-channel tiles
     (97, 68, 4, 16, 256, 3, 3, 1, 1, TANH),       # two images per chunk, the last chunk has one

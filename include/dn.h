@@ -278,6 +278,27 @@ dn_status dn_conv_backward(const float *X_dev, const float *W_dev, const float *
                            void *workspace_dev, size_t workspace_bytes, int32_t batch, int32_t c_in, int32_t h,
                            int32_t w, int32_t c_out, int32_t kh, int32_t kw, int32_t stride, int32_t pad,
                            dn_act act, void *hip_stream);
+/*
+ * dn_conv_backward for callers that cannot allocate device memory at the point of the call and
+ * have no workspace to pass (code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc): the same launches, with the workspace taken from a fixed array that lives
+ * in the library's device image.  No device or host memory is allocated or freed by the call.
+ *   - Limit: the layer's dn_conv_backward_workspace_bytes(...) must not exceed
+ *     dn_conv_backward_static_limit() (32 MiB); larger layers -> DN_ERR_SHAPE, nothing launched.
+ *   - Every device the library runs on holds its own copy of the array (32 MiB of device memory
+ *     per device until the process ends).  The first call on a device looks its address up once;
+ *     that device must be current, as for every other call here.
+ *   - All calls on one device share the array: two calls whose device work may overlap (different
+ *     streams, or different host threads on one device) race on it.  Calls on one stream are
+ *     ordered and safe.  The array keeps the previous call's contents; each call writes every
+ *     word it reads before reading it, so nothing needs clearing.
+ * Arguments, results and all other errors are those of dn_conv_backward; results are the same bits.
+ */
+dn_status dn_conv_backward_static(const float *X_dev, const float *W_dev, const float *Y_dev, const float *dA_dev,
+                                  float *delta_dev, float *dX_dev, float *dW_dev, float *dbias_dev, int32_t batch,
+                                  int32_t c_in, int32_t h, int32_t w, int32_t c_out, int32_t kh, int32_t kw,
+                                  int32_t stride, int32_t pad, dn_act act, void *hip_stream);
+size_t dn_conv_backward_static_limit(void);
 dn_status dn_maxpool_forward(const float *X_dev, float *Y_dev, int32_t batch, int32_t channels, int32_t h,
                              int32_t w, int32_t k, int32_t stride, void *hip_stream);
 /* dX_dev [batch][channels][h][w] is overwritten (not accumulated into). */

@@ -6,6 +6,8 @@
 // layers wide enough for 32 x 32 tiles run their forward product and input gradient on the matrix
 // cores (corr_mfma_kernel), with square filters of odd edge the filter gradient too (conv_dw_mfma_kernel);
 // everything else uses register-tiled vector kernels.
+#include <mutex>
+
 #include "dn_internal.h"
 #include "dn_wave.h"
 
@@ -1154,6 +1156,49 @@ DwPlan dw_plan(const ConvShape &s)
     return p;
 }
 
+size_t conv_backward_scratch_bytes(const ConvShape &s, const DwPlan &p)
+{
+    return ((p.filt + (size_t)s.Cout) * (size_t)p.chunks + p.filt) * sizeof(float);   // partial sums, flipped filters
+}
+
+dn_status conv_backward_run(const ConvShape &s, const DwPlan &p, const float *X_dev, const float *W_dev,
+                            const float *Y_dev, const float *dA_dev, float *delta_dev, float *dX_dev, float *dW_dev,
+                            float *dbias_dev, float *part, hipStream_t stream);
+
+// ---- scratch memory of dn_conv_backward_static ---------------------------------------------
+// A fixed device array takes the place of the caller's workspace.  Each device the library runs
+// on holds its own copy at its own address for the life of the process; the address is looked up
+// once per device (with that device current) and only that pointer -- never the array's name,
+// which is a host-side stand-in -- is handed to kernels.
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+constexpr int kMaxDevices = 64;
+}  // namespace
+}  // namespace dn
+
+static __device__ __align__(256) unsigned char scratch[dn::kStaticScratchBytes];
+
+namespace dn {
+namespace {
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {nullptr};
+
+dn_status static_scratch(float **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return DN_ERR_DEVICE;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            return DN_ERR_DEVICE;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = static_cast<float *>(g_scratch_ptr[dev]);
+    return DN_OK;
+}
+
 }  // namespace
 
 }  // namespace dn
@@ -1193,8 +1238,7 @@ size_t dn_conv_backward_workspace_bytes(int32_t batch, int32_t c_in, int32_t h, 
 {
     ConvShape s;
     if (conv_shape(batch, c_in, h, w, c_out, kh, kw, stride, pad, DN_ACT_LINEAR, s) != DN_OK) return 0;
-    const DwPlan p = dw_plan(s);
-    return ((p.filt + (size_t)s.Cout) * (size_t)p.chunks + p.filt) * sizeof(float);   // partial sums, flipped filters
+    return conv_backward_scratch_bytes(s, dw_plan(s));
 }
 
 dn_status dn_conv_backward(const float *X_dev, const float *W_dev, const float *Y_dev, const float *dA_dev,
@@ -1208,10 +1252,44 @@ dn_status dn_conv_backward(const float *X_dev, const float *W_dev, const float *
     const dn_status st = conv_shape(batch, c_in, h, w, c_out, kh, kw, stride, pad, (int)act, s);
     if (st != DN_OK) return st;
     const DwPlan p = dw_plan(s);
-    if (workspace_bytes < ((p.filt + (size_t)s.Cout) * (size_t)p.chunks + p.filt) * sizeof(float)) return DN_ERR_SHAPE;
+    if (workspace_bytes < conv_backward_scratch_bytes(s, p)) return DN_ERR_SHAPE;
     if ((reinterpret_cast<uintptr_t>(workspace_dev) & 3) != 0) return DN_ERR_INVALID_ARG;
-    hipStream_t stream = (hipStream_t)hip_stream;
-    float *part = static_cast<float *>(workspace_dev);
+    return conv_backward_run(s, p, X_dev, W_dev, Y_dev, dA_dev, delta_dev, dX_dev, dW_dev, dbias_dev,
+                             static_cast<float *>(workspace_dev), (hipStream_t)hip_stream);
+}
+
+dn_status dn_conv_backward_static(const float *X_dev, const float *W_dev, const float *Y_dev, const float *dA_dev,
+                                  float *delta_dev, float *dX_dev, float *dW_dev, float *dbias_dev, int32_t batch,
+                                  int32_t c_in, int32_t h, int32_t w, int32_t c_out, int32_t kh, int32_t kw,
+                                  int32_t stride, int32_t pad, dn_act act, void *hip_stream)
+{
+    if (!X_dev || !W_dev || !Y_dev || !dA_dev || !delta_dev || !dW_dev || !dbias_dev) return DN_ERR_INVALID_ARG;
+    ConvShape s;
+    const dn_status st = conv_shape(batch, c_in, h, w, c_out, kh, kw, stride, pad, (int)act, s);
+    if (st != DN_OK) return st;
+    const DwPlan p = dw_plan(s);
+    if (conv_backward_scratch_bytes(s, p) > kStaticScratchBytes) return DN_ERR_SHAPE;   // layer too large for the fixed buffer
+    float *part = nullptr;
+    const dn_status sp = static_scratch(&part);
+    if (sp != DN_OK) return sp;
+    return conv_backward_run(s, p, X_dev, W_dev, Y_dev, dA_dev, delta_dev, dX_dev, dW_dev, dbias_dev, part,
+                             (hipStream_t)hip_stream);
+}
+
+size_t dn_conv_backward_static_limit(void) { return kStaticScratchBytes; }
+
+}  // extern "C"
+
+namespace dn {
+namespace {
+
+// The launches of dn_conv_backward / dn_conv_backward_static; `part` is the scratch memory (partial
+// sums of the filter and bias gradients, then the flipped filters), every word of which is written
+// by this call before it is read.
+dn_status conv_backward_run(const ConvShape &s, const DwPlan &p, const float *X_dev, const float *W_dev,
+                            const float *Y_dev, const float *dA_dev, float *delta_dev, float *dX_dev, float *dW_dev,
+                            float *dbias_dev, float *part, hipStream_t stream)
+{
     const size_t ny = (size_t)s.B * s.Cout * s.Ho * s.Wo;
     size_t blocks = (ny + 255) / 256;
     if (blocks > 256 * 16) blocks = 256 * 16;
@@ -1277,6 +1355,11 @@ dn_status dn_conv_backward(const float *X_dev, const float *W_dev, const float *
     }
     return DN_OK;
 }
+
+}  // namespace
+}  // namespace dn
+
+extern "C" {
 
 dn_status dn_maxpool_forward(const float *X_dev, float *Y_dev, int32_t batch, int32_t channels, int32_t h, int32_t w,
                              int32_t k, int32_t stride, void *hip_stream)

@@ -19,6 +19,7 @@
 #include <type_traits>
 
 #include "dn_internal.h"
+#include "dn_wave.h"
 
 namespace dn {
 
@@ -515,8 +516,10 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g0, float *smem, const
     // does not depend on arrival order) and runs the epilogue.  Partials travel as relaxed
     // device-scope atomic stores / loads, which go through to memory and bypass the per-XCD L2,
     // so no cache write-back or invalidation is needed (either would throw away the operand
-    // panels the other workgroups of the XCD are working from); the stores are complete before
-    // the workgroup counts itself in.
+    // panels the other workgroups of the XCD are working from).  Order: every wave waits until
+    // its own stores are acknowledged (drain_device_scope_stores), the workgroup barrier joins the
+    // waves, then thread 0 counts the workgroup in with a device-scope atomic; the last arriver's
+    // loads are issued after the barrier that follows its own count, hence after every partial.
     if (g0.sk > 1) {
         const int wpos = wm * T::WN + wn;
         const size_t tile_floats = (size_t)BM * BN;
@@ -531,8 +534,8 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g0, float *smem, const
                         __hip_atomic_store(&mine[((i * TN + j) * 16 + r) * 64 + lane], acc[i][j][r], __ATOMIC_RELAXED,
                                            __HIP_MEMORY_SCOPE_AGENT);
         }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // waits for this wave's stores
-        __syncthreads();
+        drain_device_scope_stores();   // every wave: its partial tile has reached device scope
+        __syncthreads();               // ... before thread 0 counts the workgroup in
         int *s_last = reinterpret_cast<int *>(smem);
         if (tid == 0) {
             const unsigned old = __hip_atomic_fetch_add(&g0.counters[tile_id], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

@@ -1434,7 +1434,8 @@ __global__ __launch_bounds__(ON_THREADS) void deep_batch_epoch_kernel(DeepPlan p
                     __hip_atomic_store(dst + (size_t)b * ly.n_out + c0 + r, a_own[b * ly.per + r], __ATOMIC_RELAXED,
                                        __HIP_MEMORY_SCOPE_AGENT);
                 }
-                __syncthreads();   // every thread's stores are complete
+                drain_device_scope_stores();   // every wave: its part of the slice has reached device scope
+                __syncthreads();               // ... before thread 0 announces the slice
                 if (tid == 0) ll_store(p.fa[l] + (size_t)par * p.grid + w, 0.f, seq);
             }
         }
@@ -1555,6 +1556,7 @@ __global__ __launch_bounds__(ON_THREADS) void deep_batch_epoch_kernel(DeepPlan p
                     __hip_atomic_store(dst + (size_t)b * ly.n_out + c0 + r, dl[b * ly.per + r], __ATOMIC_RELAXED,
                                        __HIP_MEMORY_SCOPE_AGENT);
                 }
+                drain_device_scope_stores();
                 __syncthreads();
                 if (tid == 0) ll_store(p.fd[l] + (size_t)par * p.grid + w, 0.f, seq);
             }

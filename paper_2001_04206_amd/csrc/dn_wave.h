@@ -39,6 +39,21 @@ __device__ __forceinline__ float wave_max(float v)
     return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
 }
 
+// Completes this wave's device-scope stores before it signals another workgroup.
+// Data that crosses workgroups is written with relaxed device-scope atomic stores, which the
+// hardware performs as write-through stores to the level all workgroups of the device share.  A
+// wave's memory counter reaches zero only when every store it has issued has been acknowledged
+// from that level (the compiler's own code for a device-scope release leans on the same fact), so
+// after this call -- and a workgroup barrier, when another wave does the signalling -- a flag or
+// counter written with a device-scope atomic is observed only after the data.  The workgroup-scope
+// release fence keeps the compiler from sinking stores below the wait.  Unlike a device-scope
+// release fence this does not write back the L2, which such stores never leave dirty.
+__device__ __forceinline__ void drain_device_scope_stores()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0);   // vmcnt, expcnt, lgkmcnt = 0
+}
+
 // Sum over each aligned group of 16 lanes (a DPP row); every lane of the group gets it.
 __device__ __forceinline__ float row16_sum(float v)
 {

@@ -29,6 +29,7 @@ EXPORTS = [
     "dn_last_epoch_ms", "dn_kernel_time", "dn_set_option",
     "dn_conv_forward", "dn_conv_backward_workspace_bytes", "dn_conv_backward", "dn_maxpool_forward",
     "dn_maxpool_backward", "dn_input_gradient", "dn_sgd_step",
+    "dn_conv_backward_static", "dn_conv_backward_static_limit",
 ]
 
 _lib = None
@@ -76,7 +77,7 @@ def lib():
         l.dn_kernel_time.argtypes = [vp, i32, C.POINTER(f32), C.POINTER(i64)]
         l.dn_set_option.argtypes = [vp, C.c_char_p, i64]
         for name in EXPORTS[2:]:
-            if name.endswith("_workspace_bytes"):
+            if name.endswith("_workspace_bytes") or name.endswith("_static_limit"):
                 getattr(l, name).restype = C.c_size_t
             else:
                 getattr(l, name).restype = C.c_int
@@ -203,6 +204,36 @@ def dn_conv_backward(X, W, Y, dA, delta, dX, dW, dbias, stride: int, pad: int, a
                                       _dev_ptr(dbias, f32, "dbias"), _dev_ptr(workspace, torch.uint8, "workspace"),
                                       C.c_size_t(int(workspace.numel())), B, Cin, H, Wd, Cout, KH, KW, int(stride),
                                       int(pad), int(act), C.c_void_p(stream.cuda_stream)), "dn_conv_backward")
+
+
+def dn_conv_backward_static_limit() -> int:
+    return int(lib().dn_conv_backward_static_limit())
+
+
+def dn_conv_backward_static(X, W, Y, dA, delta, dX, dW, dbias, stride: int, pad: int, act: int):
+    """dn_conv_backward with the library's fixed scratch array in place of a workspace: nothing is
+    allocated, here or in the library."""
+    import torch
+    B, Cin, H, Wd = (int(v) for v in X.shape)
+    Cout, Cin2, KH, KW = (int(v) for v in W.shape)
+    if Cin2 != Cin:
+        raise TypeError("filter channels do not match the input")
+    yshape = (B, Cout, conv_out_size(H, KH, stride, pad), conv_out_size(Wd, KW, stride, pad))
+    for t, name in ((Y, "Y"), (dA, "dA"), (delta, "delta")):
+        _shape_check(t, yshape, name)
+    _shape_check(dW, W.shape, "dW")
+    _shape_check(dbias, (Cout,), "dbias")
+    if dX is not None:
+        _shape_check(dX, X.shape, "dX")
+    f32 = torch.float32
+    with torch.cuda.device(X.device):
+        stream = torch.cuda.current_stream(X.device)
+        _check(lib().dn_conv_backward_static(_dev_ptr(X, f32, "X"), _dev_ptr(W, f32, "W"), _dev_ptr(Y, f32, "Y"),
+                                             _dev_ptr(dA, f32, "dA"), _dev_ptr(delta, f32, "delta"),
+                                             None if dX is None else _dev_ptr(dX, f32, "dX"),
+                                             _dev_ptr(dW, f32, "dW"), _dev_ptr(dbias, f32, "dbias"), B, Cin, H, Wd,
+                                             Cout, KH, KW, int(stride), int(pad), int(act),
+                                             C.c_void_p(stream.cuda_stream)), "dn_conv_backward_static")
 
 
 def dn_maxpool_forward(X, Y, k: int, stride: int):

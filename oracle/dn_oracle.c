@@ -110,10 +110,18 @@ static double act_deriv_from_output(int act, double a)
  * Feed forward: a_0 = x; for each layer, net input z = W a_prev + b and
  * a = f(z).  A softmax layer turns its row of net inputs into
  * exp(z - max z) / sum exp(z - max z).
- * kink_eps > 0 additionally counts ReLU units with |z| < kink_eps.
+ * kink_eps > 0 additionally counts ReLU units with |z| < kink_eps (the "kink
+ * census": units whose derivative a rounding difference could flip) and, when
+ * a log is given, records the first log->cap of them as triples
+ * (sample index = log->base + row, layer, unit).
  */
+typedef struct {
+    int64_t *triples; /* [cap][3] */
+    int64_t cap, n, base;
+} kink_log;
+
 static void forward_impl(int L, const int32_t *n, const int32_t *acts, const real *params,
-                         const real *X, int B, real *A, double kink_eps, int64_t *kinks)
+                         const real *X, int B, real *A, double kink_eps, int64_t *kinks, kink_log *log)
 {
     for (int l = 1; l <= L; ++l) {
         const real *W = params + w_offset(n, l);
@@ -128,8 +136,16 @@ static void forward_impl(int L, const int32_t *n, const int32_t *acts, const rea
                 double z = (double)b[o];
                 for (int k = 0; k < nin; ++k)
                     z += (double)W[(size_t)o * nin + k] * (double)Ain[(size_t)s * nin + k];
-                if (act == ACT_RELU && kink_eps > 0.0 && fabs(z) < kink_eps)
+                if (act == ACT_RELU && kink_eps > 0.0 && fabs(z) < kink_eps) {
                     kink_local++;
+                    if (log) {
+#pragma omp critical(kink_log_append)
+                        if (log->n < log->cap) {
+                            int64_t *t = log->triples + 3 * log->n++;
+                            t[0] = log->base + s; t[1] = l; t[2] = o;
+                        }
+                    }
+                }
                 Aout[(size_t)s * nout + o] = (real)act_apply(act, z);
             }
         }
@@ -155,7 +171,7 @@ static void forward_impl(int L, const int32_t *n, const int32_t *acts, const rea
 void PFX(forward)(int L, const int32_t *n, const int32_t *acts, const real *params,
                   const real *X, int B, real *A)
 {
-    forward_impl(L, n, acts, params, X, B, A, 0.0, NULL);
+    forward_impl(L, n, acts, params, X, B, A, 0.0, NULL, NULL);
 }
 
 /*
@@ -278,12 +294,15 @@ void PFX(update)(size_t P, real *params, real *vel, const real *grads, real lr, 
  * every batch's loss being taken before its own update.  n_steps_limit > 0
  * stops after that many batches (the returned loss then averages over the
  * samples actually visited).  Returns NaN if scratch memory cannot be had.
+ * kink_list (may be NULL) receives the first kink_cap census hits as triples
+ * (sample, layer, unit) in no particular order; *kinks is the full count.
  */
 double PFX(train_epoch)(int L, const int32_t *n, const int32_t *acts, int loss, real *params,
                         real *vel, const real *X, const int32_t *labels, int64_t N, int B,
                         real lr, real mu, int64_t n_steps_limit, double kink_eps,
-                        int64_t *kinks)
+                        int64_t *kinks, int64_t *kink_list, int64_t kink_cap)
 {
+    kink_log log = {kink_list, kink_list ? kink_cap : 0, 0, 0};
     const size_t P = PFX(param_count)(L, n);
     const size_t na = PFX(act_count)(L, n, B);
     real *A = (real *)malloc(na * sizeof(real));
@@ -300,7 +319,8 @@ double PFX(train_epoch)(int L, const int32_t *n, const int32_t *acts, int loss, 
         if (n_steps_limit > 0 && step >= n_steps_limit) break;
         const int b = (int)((N - s0) < B ? (N - s0) : B);
         const real *Xb = X + (size_t)s0 * (size_t)n[0];
-        forward_impl(L, n, acts, params, Xb, b, A, kink_eps, kinks);
+        log.base = s0;
+        forward_impl(L, n, acts, params, Xb, b, A, kink_eps, kinks, kink_list ? &log : NULL);
         double lb = PFX(backward)(L, n, acts, loss, params, Xb, labels + s0, b, A, D, G);
         PFX(update)(P, params, vel, G, lr, mu);
         loss_total += lb * (double)b;
@@ -331,7 +351,7 @@ double PFX(evaluate)(int L, const int32_t *n, const int32_t *acts, int loss, con
     int64_t hits = 0;
     for (int64_t s0 = 0; s0 < N; s0 += chunk) {
         const int b = (int)((N - s0) < chunk ? (N - s0) : chunk);
-        forward_impl(L, n, acts, params, X + (size_t)s0 * (size_t)n[0], b, A, 0.0, NULL);
+        forward_impl(L, n, acts, params, X + (size_t)s0 * (size_t)n[0], b, A, 0.0, NULL, NULL);
         const real *AL = A + a_offset(n, L, b);
         for (int s = 0; s < b; ++s) {
             const real *a = AL + (size_t)s * nL;

@@ -150,16 +150,20 @@ class Oracle:
                      self._rp(self.grads), self._real(lr), self._real(momentum))
 
     def train_epoch(self, X: np.ndarray, labels: np.ndarray, batch: int, lr: float,
-                    momentum: float, steps_limit: int = 0, kink_eps: float = 0.0):
-        """Returns (epoch loss, count of ReLU units with |z| < kink_eps)."""
+                    momentum: float, steps_limit: int = 0, kink_eps: float = 0.0, kink_cap: int = 0):
+        """Returns (epoch loss, count of ReLU units with |z| < kink_eps).  With kink_cap > 0 the
+        first kink_cap of those units are kept in self.kink_list as rows (sample, layer, unit)."""
         X = np.ascontiguousarray(X, dtype=self.dtype)
         labels = np.ascontiguousarray(labels, dtype=np.int32)
         kinks = C.c_int64(0)
+        buf = np.zeros((max(kink_cap, 1), 3), dtype=np.int64)
         loss = self._train_epoch(C.c_int(self.L), self._ip(self.widths), self._ip(self.acts),
                                  C.c_int(self.loss), self._rp(self.params), self._rp(self.vel),
                                  self._rp(X), self._ip(labels), C.c_int64(X.shape[0]),
                                  C.c_int(batch), self._real(lr), self._real(momentum),
-                                 C.c_int64(steps_limit), C.c_double(kink_eps), C.byref(kinks))
+                                 C.c_int64(steps_limit), C.c_double(kink_eps), C.byref(kinks),
+                                 buf.ctypes.data_as(C.c_void_p) if kink_cap > 0 else None, C.c_int64(kink_cap))
+        self.kink_list = buf[:min(int(kinks.value), kink_cap)] if kink_cap > 0 else buf[:0]
         return float(loss), int(kinks.value)
 
     def evaluate(self, X: np.ndarray, labels: np.ndarray) -> Tuple[float, int]:

@@ -459,6 +459,14 @@ def test_kink_census_counts_small_relu_net_inputs():
     _, kinks = o.train_epoch(X, np.zeros(3, dtype=np.int32), batch=1, lr=0.0, momentum=0.0,
                              kink_eps=1e-5)
     assert kinks == 2       # hidden unit 0 on samples 0 and 2
+    # the same census with the hits listed as (sample, layer, unit); a short list keeps the count
+    for batch in (1, 2):
+        _, kinks = o.train_epoch(X, np.zeros(3, dtype=np.int32), batch=batch, lr=0.0, momentum=0.0,
+                                 kink_eps=1e-5, kink_cap=8)
+        assert kinks == 2
+        assert sorted(map(tuple, o.kink_list.tolist())) == [(0, 1, 0), (2, 1, 0)]
+    _, kinks = o.train_epoch(X, np.zeros(3, dtype=np.int32), batch=3, lr=0.0, momentum=0.0, kink_eps=1e-5, kink_cap=1)
+    assert kinks == 2 and len(o.kink_list) == 1 and tuple(o.kink_list[0]) in [(0, 1, 0), (2, 1, 0)]
 
 
 # ------------------------------------------------- evaluation and stopping rule ----

@@ -175,6 +175,21 @@ void PFX(forward)(int L, const int32_t *n, const int32_t *acts, const real *para
 }
 
 /*
+ * Feed forward with the kink census of this batch: returns the number of ReLU units with
+ * |net input| < kink_eps and lists the first kink_cap of them in kink_list (may be NULL) as
+ * triples (row of the batch, layer, unit).  Activations are those of forward().
+ */
+int64_t PFX(forward_census)(int L, const int32_t *n, const int32_t *acts, const real *params,
+                            const real *X, int B, real *A, double kink_eps, int64_t *kink_list,
+                            int64_t kink_cap)
+{
+    int64_t kinks = 0;
+    kink_log log = {kink_list, kink_list ? kink_cap : 0, 0, 0};
+    forward_impl(L, n, acts, params, X, B, A, kink_eps, &kinks, kink_list ? &log : NULL);
+    return kinks;
+}
+
+/*
  * Loss error assessment and back propagation for one batch, given the
  * activations of the forward pass.  Writes deltas D (same layout as A) and the
  * batch-mean gradients (same layout as params).  Returns the batch-mean loss.

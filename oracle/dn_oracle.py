@@ -56,6 +56,7 @@ class Oracle:
         self._param_count = f("param_count"); self._param_count.restype = C.c_size_t
         self._act_count = f("act_count"); self._act_count.restype = C.c_size_t
         self._forward = f("forward"); self._forward.restype = None
+        self._forward_census = f("forward_census"); self._forward_census.restype = C.c_int64
         self._backward = f("backward"); self._backward.restype = C.c_double
         self._update = f("update"); self._update.restype = None
         self._input_gradient = f("input_gradient"); self._input_gradient.restype = None
@@ -116,15 +117,25 @@ class Oracle:
         return out
 
     # -- the steps -------------------------------------------------------------
-    def forward(self, X: np.ndarray) -> List[np.ndarray]:
+    def forward(self, X: np.ndarray, kink_eps: float = 0.0, kink_cap: int = 0) -> List[np.ndarray]:
+        """Activations A_1..A_L of the batch.  With kink_eps > 0 the batch's kink census is taken as
+        well: self.kinks = its count, self.kink_list = the first kink_cap hits as rows (row, layer, unit)."""
         X = np.ascontiguousarray(X, dtype=self.dtype)
         B = X.shape[0]
         na = int(self._act_count(C.c_int(self.L), self._ip(self.widths), C.c_int(B)))
         self.A = np.zeros(na, dtype=self.dtype)
         self.D = np.zeros(na, dtype=self.dtype)
         self._B, self._X = B, X
-        self._forward(C.c_int(self.L), self._ip(self.widths), self._ip(self.acts),
-                      self._rp(self.params), self._rp(X), C.c_int(B), self._rp(self.A))
+        if kink_eps > 0.0:
+            buf = np.zeros((max(kink_cap, 1), 3), dtype=np.int64)
+            self.kinks = int(self._forward_census(
+                C.c_int(self.L), self._ip(self.widths), self._ip(self.acts), self._rp(self.params), self._rp(X),
+                C.c_int(B), self._rp(self.A), C.c_double(kink_eps),
+                buf.ctypes.data_as(C.c_void_p) if kink_cap > 0 else None, C.c_int64(kink_cap)))
+            self.kink_list = buf[:min(self.kinks, kink_cap)]
+        else:
+            self._forward(C.c_int(self.L), self._ip(self.widths), self._ip(self.acts),
+                          self._rp(self.params), self._rp(X), C.c_int(B), self._rp(self.A))
         return self._acts_split(self.A, B)
 
     def backward(self, labels: np.ndarray) -> float:

@@ -20,13 +20,11 @@ def rel_err(got: np.ndarray, ref: np.ndarray):
     return float(l2), float(mx)
 
 
-def assert_close(got, ref, tol, what, tol_max=None):
-    """Relative L2 error within tol and max error within tol_max (default: tol)."""
-    tol_max = tol if tol_max is None else tol_max
+def assert_close(got, ref, tol, what):
+    """Relative L2 error and max error (relative to the reference's largest element) within tol."""
     assert np.all(np.isfinite(got)), what + ": non-finite values"
     if not np.any(ref):            # an all-zero reference (e.g. zero-initialised bias gradient) must match exactly-ish
         assert np.abs(got).max() <= 1e-12, what + ": expected zeros"
         return
     l2, mx = rel_err(got, ref)
-    assert l2 <= tol and mx <= tol_max, "%s: rel L2 %.3e (tol %.1e), rel max %.3e (tol %.1e)" % (
-        what, l2, tol, mx, tol_max)
+    assert l2 <= tol and mx <= tol, "%s: rel L2 %.3e, rel max %.3e (tol %.1e)" % (what, l2, mx, tol)

@@ -88,13 +88,7 @@ def check_epochs(dn, w, n_samples, epochs=1, tol=EPOCH_TOL, steps_note=""):
     Wr, br = o.get_params()
     for l in range(net.L):
         assert_close(W[l], Wr[l], tol, "W_%d after %d epoch(s) %s (kink census %d)" % (l + 1, epochs, steps_note, kinks))
-        # A ReLU net input within rounding of zero may take the other value of the derivative on
-        # the two sides.  One such flip moves single elements of the upstream biases by about
-        # lr |dA| / B; the biases start at zero and are small, so measured against their largest
-        # element that can exceed tol, while the tensor as a whole (L2) stays within tol.
-        tol_max = 10 * tol if kinks > 0 else tol
-        assert_close(b[l], br[l], tol, "b_%d after %d epoch(s) %s (kink census %d)" % (l + 1, epochs, steps_note, kinks),
-                     tol_max=tol_max)
+        assert_close(b[l], br[l], tol, "b_%d after %d epoch(s) %s (kink census %d)" % (l + 1, epochs, steps_note, kinks))
     net.close()
     return W, b
 
@@ -194,8 +188,7 @@ def test_epoch_narrow_layers(dnlib, widths, acts, loss, batch, n, momentum):
     Wr, br = o.get_params()
     for l in range(net.L):
         assert_close(W[l], Wr[l], EPOCH_TOL, "W_%d (kink census %d)" % (l + 1, kinks))
-        assert_close(b[l], br[l], EPOCH_TOL, "b_%d (kink census %d)" % (l + 1, kinks),
-                     tol_max=10 * EPOCH_TOL if kinks > 0 else EPOCH_TOL)
+        assert_close(b[l], br[l], EPOCH_TOL, "b_%d (kink census %d)" % (l + 1, kinks))
     net.close()
 
 
@@ -269,36 +262,19 @@ def test_epoch_digits_like_minibatch(dnlib):
 
 
 @pytest.mark.parametrize("B", [1, 8, 32, 128, 512, 2048])
-def test_epoch_tanh_sweep_prefix(dnlib, B):
-    n = 2048 if B < 2048 else 4096
-    announce("epoch cfg5 1024x4-10 B=%d on the first %d samples" % (B, n))
-    w = synth.tanh_sweep(B, n_samples=n)
-    check_epochs(dnlib, w, n, steps_note="(prefix of %d samples)" % n)
-
-
-def test_wide_relu_first_steps(dnlib):
-    announce("epoch cfg4 4096x3-1000 B=256, first 4 steps")
-    w = synth.wide_relu(n_samples=1024)
-    check_epochs(dnlib, w, 1024, steps_note="(first 4 steps)")
-
-
-@pytest.mark.parametrize("B", [1, 128, 2048])
-def test_tanh_sweep_full_size_invariants(dnlib, B):
-    """Full 16384-sample pass in the benchmarked configuration: properties that hold at any
-    size -- finite loss below the initial one, and (softmax + cross-entropy) conservation of the
-    output layer's bias sum and column sums."""
-    announce("full-size cfg5 B=%d invariants" % B)
+def test_epoch_tanh_sweep_full(dnlib, B):
+    """The whole 16384-sample pass of the batch-size sweep, in the configuration bench.py times:
+    every weight, every bias and the epoch loss against the checker."""
+    announce("epoch cfg5 1024x4-10 B=%d, all 16384 samples" % B)
     w = synth.tanh_sweep(B)
-    net = dnlib.Net(w.widths, w.acts, w.loss, B)
-    net.set_all(w.W, w.b)
-    X, y = to_dev(w)
-    loss = net.dn_train_epoch(X, y, B, w.lr, w.momentum)
-    W, b = net.get_all()
-    assert np.isfinite(loss) and 0.0 < loss < 10.0     # labels are random: no learnable signal
-    assert all(np.all(np.isfinite(t)) for t in W + b)
+    W, b = check_epochs(dnlib, w, w.n_samples, steps_note="(full pass)")
+    # softmax + cross-entropy conserves the output layer's bias sum and column sums
     assert abs(float(b[-1].sum())) < 1e-4
     np.testing.assert_allclose(W[-1].sum(axis=0), w.W[-1].sum(axis=0), atol=5e-4)
-    net.close()
+
+
+# the 4096-4096-4096-1000 workload (first 16 steps against the checker, then the invariants of its
+# full 256-step epoch) has a file of its own: test_gpu_wide_relu.py
 
 
 # ------------------------------------------------------------------- edge cases ----

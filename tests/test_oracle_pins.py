@@ -465,6 +465,12 @@ def test_kink_census_counts_small_relu_net_inputs():
                                  kink_eps=1e-5, kink_cap=8)
         assert kinks == 2
         assert sorted(map(tuple, o.kink_list.tolist())) == [(0, 1, 0), (2, 1, 0)]
+    # the census of a single forward pass: same hits, same activations as the plain forward pass
+    plain = o.forward(X)
+    with_census = o.forward(X, kink_eps=1e-5, kink_cap=8)
+    assert o.kinks == 2 and sorted(map(tuple, o.kink_list.tolist())) == [(0, 1, 0), (2, 1, 0)]
+    for a, c in zip(plain, with_census):
+        assert np.array_equal(a, c)
     _, kinks = o.train_epoch(X, np.zeros(3, dtype=np.int32), batch=3, lr=0.0, momentum=0.0, kink_eps=1e-5, kink_cap=1)
     assert kinks == 2 and len(o.kink_list) == 1 and tuple(o.kink_list[0]) in [(0, 1, 0), (2, 1, 0)]
 

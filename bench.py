@@ -39,7 +39,8 @@ def workloads():
     return w
 
 
-PEAK_VALU_F32_TFLOPS = 157.3  # fp32 vector rate: 256 CUs x 128 lanes x 2 flop x 2.4 GHz (needs packed fp32 instructions; plain v_fma_f32 gives half)
+PEAK_VALU_F32_TFLOPS = 78.6  # fp32 vector rate of this build: 256 CUs x 64 lanes x 2 flop x 2.4 GHz (plain v_fma_f32; the
+                             # library is compiled without packed fp32 instructions, which would double it)
 
 # A convolutional layer followed by 2x2 max pooling, batch of images resident on the device.
 # name: (batch, c_in, h, w, c_out, k, stride, pad)
@@ -329,6 +330,9 @@ def main():
     ap.add_argument("--steps", type=int, default=0, help="timed training steps (0: one pass over the data)")
     ap.add_argument("--warmup", type=int, default=-1, help="untimed steps (-1: workload default)")
     ap.add_argument("--workload", default="cfg4_4096x3_1000_b256")
+    ap.add_argument("--repeats", type=int, default=0,
+                    help="timed repeats of the --steps steps, each from the initial parameters; value is the median "
+                         "(0: at least 5, more while a repeat is short, up to 25)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-call-offload", action="store_true",
                     help="instead of a workload: time the paper's execution model (host operands copied in, one "
@@ -438,13 +442,26 @@ def main():
     net.set_all(w.W, w.b)
     if warmup:
         run(warmup)
-    net.set_all(w.W, w.b)            # timed region starts from the initial parameters
     net.dn_set_option("time_kernels", 0)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    dev_ms, loss = run(steps)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t1
+    # Timed repeats: each runs exactly `steps` steps from the initial parameters, bracketed by
+    # device synchronisation on both sides; the figure reported is the median repeat.
+    walls, dev_mss, loss = [], [], float("nan")
+    repeats = args.repeats if args.repeats > 0 else 5
+    r = 0
+    while r < repeats:
+        net.set_all(w.W, w.b)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        dev_ms_r, loss = run(steps)
+        torch.cuda.synchronize()
+        walls.append(time.perf_counter() - t1)
+        dev_mss.append(dev_ms_r)
+        r += 1
+        if r == 1 and args.repeats <= 0 and walls[0] < 0.1:      # short repeats: take more of them (about half a second in all)
+            repeats = max(5, min(25, int(0.5 / max(walls[0], 1e-6))))
+    order = sorted(range(len(walls)), key=lambda i: walls[i])
+    mid = order[len(order) // 2]
+    wall, dev_ms = walls[mid], dev_mss[mid]
     samples = sum(min(B, N - ((s % steps_per_pass) * B)) for s in range(steps))
     value = samples / wall
 
@@ -516,10 +533,23 @@ def main():
         dtc = time.perf_counter() - tc
         cpu = {"value": n_cpu / dtc, "unit": "samples/s", "cores": dn_oracle.threads(), "kind": "oracle",
                "sample": "first %d samples (%d steps) of the same workload, %.1f s" % (n_cpu, (n_cpu + B - 1) // B, dtc)}
+        # the same checker on one thread, on a smaller sample (about an eighth of the work)
+        all_threads = dn_oracle.threads()
+        n_one = min(n_cpu, int(max(B, n_cpu // 8) // B * B) or B)
+        o.set_params(w.W, w.b)
+        dn_oracle.set_threads(1)
+        tc = time.perf_counter()
+        o.train_epoch(w.X[:n_one], w.labels[:n_one], B, w.lr, w.momentum)
+        dt1 = time.perf_counter() - tc
+        dn_oracle.set_threads(all_threads)
+        cpu["value_1thread"] = n_one / dt1
+        cpu["sample_1thread"] = "first %d samples (%d steps), %.1f s" % (n_one, (n_one + B - 1) // B, dt1)
 
     out = {
         "metric": "training samples/sec (fwd+bwd+update)", "value": value, "unit": "samples/s",
         "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": wall * 1e3 / steps,
+        "repeats": len(walls), "value_min": samples / max(walls), "value_max": samples / min(walls),
+        "ms_per_step_min": min(walls) * 1e3 / steps, "ms_per_step_max": max(walls) * 1e3 / steps,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": args.workload, "widths": w.widths, "batch": B, "lr": w.lr,

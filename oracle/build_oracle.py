@@ -1,7 +1,8 @@
 """Compile the CPU checker (oracle/dn_oracle.c, oracle/dn_conv_oracle.c) into oracle/libdn_oracle.so.
 
-Each C file is built twice into one shared object: once with fp32 storage and
-fp64 accumulation (symbols o32_*), once all-fp64 (symbols o64_*).  Flags avoid
+Each C file is built three times into one shared object: fp32 storage with
+fp64 accumulation (symbols o32_*), all-fp64 (o64_*), and fp32 storage with fp32
+accumulation (o32a_*: not a reference, a measure of fp32 rounding drift).  Flags avoid
 -march=native and fused contraction so the library gives the same bits on any
 x86-64-v3 host.  Test infrastructure only.
 """
@@ -25,9 +26,9 @@ def build(force: bool = True) -> str:
     with tempfile.TemporaryDirectory() as tmp:
         objs = []
         for src in SRCS:
-            for store, pfx in (("float", "o32_"), ("double", "o64_")):
+            for store, acc, pfx in (("float", "double", "o32_"), ("double", "double", "o64_"), ("float", "float", "o32a_")):
                 obj = os.path.join(tmp, pfx + os.path.basename(src) + ".o")
-                cmd = ["gcc", *CFLAGS, "-DSTORE_T=" + store, "-DPFX(x)=" + pfx + "##x", "-c", src, "-o", obj]
+                cmd = ["gcc", *CFLAGS, "-DSTORE_T=" + store, "-DACC_T=" + acc, "-DPFX(x)=" + pfx + "##x", "-c", src, "-o", obj]
                 subprocess.run(cmd, check=True)
                 objs.append(obj)
         subprocess.run(["gcc", "-shared", "-fopenmp", "-o", LIB, *objs, "-lm"], check=True)

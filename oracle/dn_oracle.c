@@ -22,6 +22,7 @@
  *        fp32 once per stored element ("correctly rounded fp32 training").
  *   -DSTORE_T=double -DPFX(x)=o64_##x : everything in fp64 (used for finite
  *        differences and closed-form checks).
+ *   -DSTORE_T=float -DACC_T=float -DPFX(x)=o32a_##x : not a reference; see ACC_T below.
  *
  * Readings taken where the paper is silent (it prints no formulas):
  *   - minibatch gradient = mean over the samples of the batch; a short last
@@ -50,6 +51,16 @@
 #endif
 
 typedef STORE_T real;
+
+/* Type the long sums (net inputs, delta propagation, gradients) are accumulated in.  fp64 for the
+ * two reference builds.  A third build (o32a_: fp32 storage AND fp32 accumulation, inner index
+ * ascending) is not a reference: it is the same definition evaluated with rounding errors of the
+ * size an fp32 device path has, and serves to measure how far two valid fp32 evaluations can
+ * drift apart on ill-conditioned quantities (ReLU derivatives of net inputs next to zero). */
+#ifndef ACC_T
+#define ACC_T double
+#endif
+typedef ACC_T acc_t;
 
 enum { ACT_LINEAR = 0, ACT_SIGMOID = 1, ACT_TANH = 2, ACT_RELU = 3, ACT_SOFTMAX = 4 };
 enum { LOSS_MSE = 0, LOSS_CE = 1 };
@@ -133,10 +144,10 @@ static void forward_impl(int L, const int32_t *n, const int32_t *acts, const rea
 #pragma omp parallel for collapse(2) schedule(static) reduction(+ : kink_local)
         for (int s = 0; s < B; ++s) {
             for (int o = 0; o < nout; ++o) {
-                double z = (double)b[o];
+                acc_t z = (acc_t)b[o];
                 for (int k = 0; k < nin; ++k)
-                    z += (double)W[(size_t)o * nin + k] * (double)Ain[(size_t)s * nin + k];
-                if (act == ACT_RELU && kink_eps > 0.0 && fabs(z) < kink_eps) {
+                    z += (acc_t)W[(size_t)o * nin + k] * (acc_t)Ain[(size_t)s * nin + k];
+                if (act == ACT_RELU && kink_eps > 0.0 && fabs((double)z) < kink_eps) {
                     kink_local++;
                     if (log) {
 #pragma omp critical(kink_log_append)
@@ -146,7 +157,7 @@ static void forward_impl(int L, const int32_t *n, const int32_t *acts, const rea
                         }
                     }
                 }
-                Aout[(size_t)s * nout + o] = (real)act_apply(act, z);
+                Aout[(size_t)s * nout + o] = (real)act_apply(act, (double)z);
             }
         }
         if (kinks)
@@ -242,11 +253,11 @@ double PFX(backward)(int L, const int32_t *n, const int32_t *acts, int loss, con
 #pragma omp parallel for collapse(2) schedule(static)
             for (int s = 0; s < B; ++s) {
                 for (int i = 0; i < nin; ++i) {
-                    double t = 0.0;
+                    acc_t t = 0;
                     for (int o = 0; o < nout; ++o)
-                        t += (double)W[(size_t)o * nin + i] * (double)Dl[(size_t)s * nout + o];
+                        t += (acc_t)W[(size_t)o * nin + i] * (acc_t)Dl[(size_t)s * nout + o];
                     Dprev[(size_t)s * nin + i] =
-                        (real)(t * act_deriv_from_output(actp, (double)Aprev[(size_t)s * nin + i]));
+                        (real)((double)t * act_deriv_from_output(actp, (double)Aprev[(size_t)s * nin + i]));
                 }
             }
         }
@@ -255,15 +266,15 @@ double PFX(backward)(int L, const int32_t *n, const int32_t *acts, int loss, con
 #pragma omp parallel for schedule(static)
         for (int o = 0; o < nout; ++o) {
             for (int i = 0; i < nin; ++i) {
-                double acc = 0.0;
+                acc_t acc = 0;
                 for (int s = 0; s < B; ++s)
-                    acc += (double)Dl[(size_t)s * nout + o] * (double)Aprev[(size_t)s * nin + i];
-                G[(size_t)o * nin + i] = (real)(acc / (double)B);
+                    acc += (acc_t)Dl[(size_t)s * nout + o] * (acc_t)Aprev[(size_t)s * nin + i];
+                G[(size_t)o * nin + i] = (real)((double)acc / (double)B);
             }
-            double accb = 0.0;
+            acc_t accb = 0;
             for (int s = 0; s < B; ++s)
-                accb += (double)Dl[(size_t)s * nout + o];
-            g[o] = (real)(accb / (double)B);
+                accb += (acc_t)Dl[(size_t)s * nout + o];
+            g[o] = (real)((double)accb / (double)B);
         }
     }
     return loss_sum / (double)B;
@@ -394,6 +405,9 @@ double PFX(evaluate)(int L, const int32_t *n, const int32_t *acts, int loss, con
 #ifdef _OPENMP
 #include <omp.h>
 int PFX(threads)(void) { return omp_get_max_threads(); }
+/* Threads for the following calls (n < 1: leave as is).  Results do not depend on it. */
+void PFX(set_threads)(int n) { if (n >= 1) omp_set_num_threads(n); }
 #else
 int PFX(threads)(void) { return 1; }
+void PFX(set_threads)(int n) { (void)n; }
 #endif

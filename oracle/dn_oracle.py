@@ -7,6 +7,8 @@ Two precisions of the same C code:
   Oracle("o32") : fp32 storage, fp64 accumulation, one rounding per stored
                   element -- the parity reference for an fp32 device path.
   Oracle("o64") : all fp64 -- for finite differences and closed forms.
+  Oracle("o32a"): fp32 storage, fp32 accumulation -- NOT a reference: a second valid fp32
+                  evaluation, used to measure how far rounding alone moves ill-conditioned results.
 Parameters, velocities and gradients live in flat numpy vectors laid out as
 W_1, b_1, W_2, b_2, ... (row-major W_l [n_l, n_{l-1}]).
 """
@@ -40,13 +42,19 @@ def threads() -> int:
     return int(f())
 
 
+def set_threads(n: int) -> None:
+    """Threads for the checker's loops from now on (its results do not depend on the count)."""
+    lib = _load()
+    lib.o32_set_threads(C.c_int(int(n)))   # one OpenMP runtime: this sets it for every build of the checker
+
+
 class Oracle:
     def __init__(self, mode: str, widths: Sequence[int], acts: Sequence[int], loss: int):
-        assert mode in ("o32", "o64")
+        assert mode in ("o32", "o64", "o32a")
         lib = _load()
         self.mode = mode
-        self.dtype = np.float32 if mode == "o32" else np.float64
-        self._real = C.c_float if mode == "o32" else C.c_double
+        self.dtype = np.float64 if mode == "o64" else np.float32
+        self._real = C.c_double if mode == "o64" else C.c_float
         self.widths = np.asarray(widths, dtype=np.int32)
         self.acts = np.asarray(acts, dtype=np.int32)
         self.L = len(widths) - 1

@@ -452,6 +452,29 @@ def test_fp32_storage_mode_tracks_fp64_mode():
     assert np.linalg.norm(a.params - c.params) < 1e-5 * np.linalg.norm(c.params)
 
 
+def test_fp32_accumulating_build_is_the_same_definition_up_to_fp32_rounding():
+    """The o32a build (fp32 storage and fp32 sums) is only used to measure rounding drift; it must
+    still be the same computation: gradients and a short training run agree with the reference
+    build to fp32 rounding of the sums, on every activation / loss pair."""
+    for acts, loss in [([RELU, SOFTMAX], CE), ([TANH, SIG], MSE), ([SIG, LIN], MSE)]:
+        rng = np.random.default_rng(4)
+        widths = [19, 33, 6]
+        W = [rng.standard_normal((widths[l + 1], widths[l])).astype(np.float32) * 0.3 for l in range(2)]
+        b = [rng.standard_normal(widths[l + 1]).astype(np.float32) * 0.1 for l in range(2)]
+        X = rng.standard_normal((24, 19)).astype(np.float32)
+        y = rng.integers(0, 6, 24).astype(np.int32)
+        a, c = Oracle("o32", widths, acts, loss), Oracle("o32a", widths, acts, loss)
+        a.set_params(W, b); c.set_params(W, b)
+        a.forward(X); c.forward(X)
+        la, lc = a.backward(y), c.backward(y)
+        assert abs(la - lc) <= 1e-5 * abs(la)
+        assert np.linalg.norm(a.grads.astype(np.float64) - c.grads) <= 1e-5 * np.linalg.norm(a.grads)
+        ea, _ = a.train_epoch(X, y, 5, 0.05, 0.9)
+        ec, _ = c.train_epoch(X, y, 5, 0.05, 0.9)
+        assert abs(ea - ec) <= 1e-5 * abs(ea)
+        assert np.linalg.norm(a.params.astype(np.float64) - c.params) <= 1e-5 * np.linalg.norm(a.params)
+
+
 def test_kink_census_counts_small_relu_net_inputs():
     o = Oracle("o64", [1, 2, 2], [RELU, SOFTMAX], CE)
     o.set_params([np.array([[1.0], [1.0]]), np.zeros((2, 2))], [np.array([0.0, 5.0]), np.zeros(2)])

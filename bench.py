@@ -484,16 +484,19 @@ def main():
         for cid, cname in enumerate(dn.KERNEL_CLASS_NAMES):
             ms, n = net.dn_kernel_time(cid)
             if n:
-                classes[cname] = {"ms": ms, "launches": n}
+                classes[cname] = {"ms": ms, "launches": n, "flop": net.dn_kernel_flops(cid)}
         # per-launch figures of the last dn_train_epoch call (one pass or the remainder)
         last_steps = steps % steps_per_pass or min(steps, steps_per_pass)
         if "online" in classes:      # a persistent whole-epoch kernel ran: no matrix instructions, one launch
             bound = "hbm"
         if bound == "mfma":
-            dom = max((c for c in classes if c in flops), key=lambda c: classes[c]["ms"], default=None)
+            # the class of matrix-product launches with the largest summed time; its algorithmic flops
+            # (2 M N K per product, counted by the library per timed launch) / that time
+            dom = max((c for c in classes if classes[c]["flop"] > 0 and c != "output"), key=lambda c: classes[c]["ms"],
+                      default=None)
             if dom:
                 per_launch_ms = classes[dom]["ms"] / classes[dom]["launches"]
-                flop_per_launch = flops[dom] * last_steps / classes[dom]["launches"]
+                flop_per_launch = classes[dom]["flop"] / classes[dom]["launches"]
                 ach = flop_per_launch / (per_launch_ms * 1e-3) / 1e12
                 roofline = {"bound": "mfma", "kernel": dom, "achieved": ach, "peak": PEAK_MFMA_F32_TFLOPS,
                             "unit": "TFLOP/s", "frac": ach / PEAK_MFMA_F32_TFLOPS, "traffic": None,

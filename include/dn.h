@@ -334,12 +334,19 @@ typedef enum {
     DN_K_DELTA = 1,       /* Delta_{l-1} = (Delta_l W_l) * f'                */
     DN_K_GRAD_UPDATE = 2, /* G = Delta^T A / B and bias gradient, fused with the update */
     DN_K_OUTPUT = 3,      /* softmax / loss / Delta_L and loss reduction     */
-    DN_K_ONLINE = 4,      /* persistent batch-1 epoch kernel                 */
-    DN_K_CLASSES = 5
+    DN_K_ONLINE = 4,      /* persistent whole-epoch kernels                  */
+    DN_K_PAIR = 5,        /* two independent products of the backward pass in one launch: a layer's
+                             gradient / update with the delta product of the layer below, or the
+                             gradients / updates of the two lowest layers */
+    DN_K_CLASSES = 6
 } dn_kernel_class;
 
 dn_status dn_last_epoch_ms(dn_net *net, float *epoch_ms);
 dn_status dn_kernel_time(dn_net *net, int32_t kernel_class, float *ms_total, int64_t *launches);
+/* Algorithmic floating-point operations (2 x rows x columns x contraction length per product)
+ * of the timed launches of one class of the last dn_train_epoch; 0 for the classes that are not
+ * matrix products (DN_K_OUTPUT, DN_K_ONLINE). */
+dn_status dn_kernel_flops(dn_net *net, int32_t kernel_class, double *flops);
 
 /*
  * Tuning and diagnostics switches (all default 0):
@@ -348,6 +355,8 @@ dn_status dn_kernel_time(dn_net *net, int32_t kernel_class, float *ms_total, int
  *                    contraction from its shape; >= 0: force that configuration
  *   "split_k"        1 (default): forward / delta products with few output tiles split k across
  *                    workgroups (partials summed in a fixed order); 0: never
+ *   "pair_launch"    1 (default): independent products of a backward pass share a launch where their
+ *                    shapes allow; 0: one launch per product
  *   "online_mode"    0: choose automatically; 1: per-phase launches for batch 1;
  *                    2: persistent whole-epoch kernel for batch 1 (dn_train_epoch
  *                    returns DN_ERR_UNSUPPORTED if the net does not fit it: more than

@@ -83,6 +83,7 @@ bool compute_layout(const int32_t *widths, int32_t n_widths, int32_t max_batch, 
 struct TimedLaunch {
     hipEvent_t start, stop;
     int cls;
+    double flop;   // algorithmic flops of the launch (2 M N K per product)
 };
 
 }  // namespace
@@ -103,7 +104,7 @@ struct dn_net {
     bool w1_as_in_bwd = false;   // W_1 is still the matrix the last dn_backward propagated through
     // options
     int time_kernels = 0, gemm_variant = -1, online_mode = 0, online_min_tile = ON_DEFAULT_MIN_TILE,
-        online_resident = 1, split_k_on = 1;
+        online_resident = 1, split_k_on = 1, pair_launch = 1;
     // persistent batch-1 kernel
     OnlineGeom geom{};
     bool online_ok = false;
@@ -119,6 +120,7 @@ struct dn_net {
     int timed = 0;
     float epoch_ms = 0.f;
     double cls_ms[DN_K_CLASSES] = {0};
+    double cls_flop[DN_K_CLASSES] = {0};
     int64_t cls_launches[DN_K_CLASSES] = {0};
 
     float *W(int l) const { return (float *)(arena + lo.off_params + lo.W[l]); }
@@ -155,6 +157,8 @@ namespace {
         if (e_ != hipSuccess) return DN_ERR_DEVICE;    \
     } while (0)
 
+double product_flop(const GemmArgs &g) { return 2.0 * (double)g.M * (double)g.N * (double)g.K; }
+
 bool rate_ok(float lr, float mu)
 {
     return std::isfinite(lr) && std::isfinite(mu) && lr >= 0.f && mu >= 0.f && mu < 1.f;
@@ -164,7 +168,7 @@ bool rate_ok(float lr, float mu)
 struct ScopedTimer {
     dn_net *net;
     TimedLaunch *t = nullptr;
-    ScopedTimer(dn_net *n, int cls, bool enabled) : net(n)
+    ScopedTimer(dn_net *n, int cls, bool enabled, double flop = 0.0) : net(n)
     {
         if (!enabled || net->timed >= kMaxTimed) return;
         if ((int)net->pool.size() <= net->timed) {
@@ -178,6 +182,7 @@ struct ScopedTimer {
         }
         t = &net->pool[net->timed++];
         t->cls = cls;
+        t->flop = flop;
         (void)hipEventRecord(t->start, net->stream);
     }
     ~ScopedTimer()
@@ -202,47 +207,73 @@ dn_status run_forward(dn_net *net, const float *X, int B, bool timing, int last_
         g.bias = net->b(l);
         g.act = net->act[l];
         net->split_k(g);
-        ScopedTimer st(net, DN_K_FORWARD, timing);
+        ScopedTimer st(net, DN_K_FORWARD, timing, product_flop(g));
         DN_HIP(launch_gemm(GEMM_FWD, g, net->gemm_variant, net->stream));
     }
     return DN_OK;
 }
 
 // Back propagation of one batch from Delta_L.  mode GRAD_STORE leaves gradients in
-// the gradient region; the other modes update parameters in place, layer by layer,
-// each delta being propagated through W_l before W_l is touched.
-dn_status run_backward(dn_net *net, const float *X, int B, int mode, float lr, float mu, bool timing)
+// the gradient region; the other modes update parameters in place, each delta being
+// propagated through W_l before W_l is touched.  Products that do not depend on each other
+// share a launch where their shapes allow (launch_gemm_pair): with T_l the delta product through
+// W_l (giving Delta_{l-1}) and G_l the gradient / update of layer l, the order is
+//     T_L ; (G_L, T_{L-1}) ; (G_{L-1}, T_{L-2}) ; ... ; (G_3, T_2) ; (G_2, G_1)
+// -- every T_l still reads W_l before G_l writes it, and T_l precedes T_{l-1}.
+// have_top_delta: Delta_{L-1} came with the output error already (narrow last layer).
+dn_status run_backward(dn_net *net, const float *X, int B, int mode, float lr, float mu, bool timing,
+                       bool have_top_delta = false)
 {
     const float scale = (mode == GRAD_STORE) ? 1.0f / (float)B : lr / (float)B;
-    for (int l = net->L; l >= 1; --l) {
-        if (l > 1) {
-            GemmArgs g{};
-            g.A = net->D(l); g.lda = net->n[l];
-            g.B = net->W(l); g.ldb = net->n[l - 1];
-            g.M = B; g.N = net->n[l - 1]; g.K = net->n[l];
-            g.C = net->D(l - 1); g.ldc = net->n[l - 1];
-            g.aux = net->A(l - 1);
-            g.act = net->act[l - 1];
-            net->split_k(g);
-            ScopedTimer st(net, DN_K_DELTA, timing);
-            DN_HIP(launch_gemm(GEMM_DELTA, g, net->gemm_variant, net->stream));
+    const int L = net->L;
+    auto delta_args = [&](int l) {   // T_l, l >= 2
+        GemmArgs g{};
+        g.A = net->D(l); g.lda = net->n[l];
+        g.B = net->W(l); g.ldb = net->n[l - 1];
+        g.M = B; g.N = net->n[l - 1]; g.K = net->n[l];
+        g.C = net->D(l - 1); g.ldc = net->n[l - 1];
+        g.aux = net->A(l - 1);
+        g.act = net->act[l - 1];
+        net->split_k(g);
+        return g;
+    };
+    auto grad_args = [&](int l) {    // G_l
+        GemmArgs g{};
+        g.A = net->D(l); g.lda = net->n[l];
+        g.B = (l == 1) ? X : net->A(l - 1); g.ldb = net->n[l - 1];
+        g.M = net->n[l]; g.N = net->n[l - 1]; g.K = B;
+        g.C = (mode == GRAD_STORE) ? net->GW(l) : net->W(l);
+        g.ldc = net->n[l - 1];
+        g.V = net->VW(l);
+        g.gb = (mode == GRAD_STORE) ? net->Gb(l) : net->b(l);   // bias gradient / update rides along
+        g.vb = net->Vb(l);
+        g.scale = scale; g.mu = mu; g.mode = mode;
+        return g;
+    };
+    auto one = [&](GemmKind kind, const GemmArgs &g) -> dn_status {
+        ScopedTimer st(net, kind == GEMM_DELTA ? DN_K_DELTA : DN_K_GRAD_UPDATE, timing, product_flop(g));
+        DN_HIP(launch_gemm(kind, g, net->gemm_variant, net->stream));
+        return DN_OK;
+    };
+    auto two = [&](const GemmArgs &grad, GemmKind other, const GemmArgs &b) -> dn_status {
+        if (net->pair_launch && gemm_pair_fits(grad, other, b, net->gemm_variant)) {
+            ScopedTimer st(net, DN_K_PAIR, timing, product_flop(grad) + product_flop(b));
+            DN_HIP(launch_gemm_pair(grad, other, b, net->gemm_variant, net->stream));
+            return DN_OK;
         }
-        {
-            GemmArgs g{};
-            g.A = net->D(l); g.lda = net->n[l];
-            g.B = (l == 1) ? X : net->A(l - 1); g.ldb = net->n[l - 1];
-            g.M = net->n[l]; g.N = net->n[l - 1]; g.K = B;
-            g.C = (mode == GRAD_STORE) ? net->GW(l) : net->W(l);
-            g.ldc = net->n[l - 1];
-            g.V = net->VW(l);
-            g.gb = (mode == GRAD_STORE) ? net->Gb(l) : net->b(l);   // bias gradient / update rides along
-            g.vb = net->Vb(l);
-            g.scale = scale; g.mu = mu; g.mode = mode;
-            ScopedTimer st(net, DN_K_GRAD_UPDATE, timing);
-            DN_HIP(launch_gemm(GEMM_GRAD, g, net->gemm_variant, net->stream));
-        }
+        const dn_status st = one(GEMM_GRAD, grad);
+        return st != DN_OK ? st : one(other, b);
+    };
+    if (L > 1 && !have_top_delta) {
+        const dn_status st = one(GEMM_DELTA, delta_args(L));
+        if (st != DN_OK) return st;
     }
-    return DN_OK;
+    for (int l = L; l >= 3; --l) {
+        const dn_status st = two(grad_args(l), GEMM_DELTA, delta_args(l - 1));
+        if (st != DN_OK) return st;
+    }
+    if (L >= 2) return two(grad_args(2), GEMM_GRAD, grad_args(1));
+    return one(GEMM_GRAD, grad_args(1));
 }
 
 // A whole batch-1 epoch in persistent-kernel launches of at most 2^30 steps each.
@@ -407,12 +438,14 @@ void collect_times(dn_net *net)
 {
     for (int c = 0; c < DN_K_CLASSES; ++c) {
         net->cls_ms[c] = 0.0;
+        net->cls_flop[c] = 0.0;
         net->cls_launches[c] = 0;
     }
     for (int i = 0; i < net->timed; ++i) {
         float ms = 0.f;
         if (hipEventElapsedTime(&ms, net->pool[i].start, net->pool[i].stop) == hipSuccess) {
             net->cls_ms[net->pool[i].cls] += ms;
+            net->cls_flop[net->pool[i].cls] += net->pool[i].flop;
             net->cls_launches[net->pool[i].cls] += 1;
         }
     }
@@ -704,16 +737,19 @@ dn_status dn_train_epoch(dn_net *net, const float *X_dev, const int32_t *labels_
         dn_status st = run_forward(net, Xb, B, timing, fused_out ? L - 1 : L);
         if (st != DN_OK) return st;
         {
-            ScopedTimer t(net, DN_K_OUTPUT, timing);
+            // with a narrow last layer the launch also holds that layer's forward product and its delta product
+            const double out_flop = fused_out ? 2.0 * B * (double)net->n[L] * net->n[L - 1] * (L > 1 ? 2.0 : 1.0) : 0.0;
+            ScopedTimer t(net, DN_K_OUTPUT, timing, out_flop);
             if (fused_out)
                 DN_HIP(launch_narrow_output(L == 1 ? Xb : net->A(L - 1), net->W(L), net->b(L), labels_dev + s0, net->A(L),
                                             net->D(L), net->loss_rows(), net->loss_sums(), B, net->n[L], net->n[L - 1],
-                                            net->act[L], net->loss, net->stream));
+                                            net->act[L], net->loss, net->stream, L > 1 ? net->D(L - 1) : nullptr,
+                                            L > 1 ? net->act[L - 1] : 0));
             else
                 DN_HIP(launch_output_delta(net->A(L), net->D(L), labels_dev + s0, net->loss_rows(), B, net->n[L],
                                            net->act[L], net->loss, OUT_FUSED, net->stream, nullptr, net->loss_sums()));
         }
-        st = run_backward(net, Xb, B, mode, lr, momentum, timing);
+        st = run_backward(net, Xb, B, mode, lr, momentum, timing, fused_out && L > 1);
         if (st != DN_OK) return st;
     }
     if (!persistent) DN_HIP(launch_loss_sums_reduce(net->loss_sums(), rows_used, net->epoch_acc(), net->stream));
@@ -848,6 +884,13 @@ dn_status dn_kernel_time(dn_net *net, int32_t kernel_class, float *ms_total, int
     return DN_OK;
 }
 
+dn_status dn_kernel_flops(dn_net *net, int32_t kernel_class, double *flops)
+{
+    if (!net || !flops || kernel_class < 0 || kernel_class >= DN_K_CLASSES) return DN_ERR_INVALID_ARG;
+    *flops = net->cls_flop[kernel_class];
+    return DN_OK;
+}
+
 dn_status dn_set_option(dn_net *net, const char *name, int64_t value)
 {
     if (!net || !name) return DN_ERR_INVALID_ARG;
@@ -872,6 +915,9 @@ dn_status dn_set_option(dn_net *net, const char *name, int64_t value)
     } else if (!strcmp(name, "batch_mode")) {
         if (value < 0 || value > 2) return DN_ERR_INVALID_ARG;
         net->batch_mode = (int)value;
+    } else if (!strcmp(name, "pair_launch")) {
+        if (value != 0 && value != 1) return DN_ERR_INVALID_ARG;
+        net->pair_launch = (int)value;
     } else if (!strcmp(name, "split_k")) {
         if (value != 0 && value != 1) return DN_ERR_INVALID_ARG;
         net->split_k_on = (int)value;

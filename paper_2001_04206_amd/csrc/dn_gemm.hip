@@ -16,6 +16,7 @@
 // instructions pairing k = j (h = 0) with k = 4 + j (h = 1): a lane then needs
 // four consecutive k values of its row, one 128-bit LDS read when the tile is
 // stored k-contiguous.
+#include <atomic>
 #include <type_traits>
 
 #include "dn_internal.h"
@@ -589,21 +590,21 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g0, float *smem, const
     }
 }
 
+// The tile (and k split) a workgroup takes, and its work.  `block` counts the workgroups of this
+// product from zero.  Workgroups are dealt round-robin to the 8 XCDs; each XCD gets a contiguous
+// run of tiles so that tiles sharing operand panels meet in one L2.  Tiles are ordered in groups of
+// GN tile columns, m next, the columns of the group fastest: the ~128 tiles an XCD works on at a
+// time then form a compact block (16 x 8 tiles: 24 operand panels) rather than two full tile
+// columns (66 panels), which matters for the weight-gradient product, whose streaming
+// read-modify-write of W and the velocity keeps evicting the panels from the L2.
 template <class T, bool A_KC, bool B_KC, int EPI, bool VEC>
-__global__ __launch_bounds__(T::NT, T::OCC) void gemm_kernel(GemmArgs g, int tiles_m, int tiles_n)
+__device__ __forceinline__ void gemm_block(const GemmArgs &g, float *smem, int tiles_m, int tiles_n, int block)
 {
-    extern __shared__ __attribute__((aligned(16))) float smem[];
-    // Workgroups are dealt round-robin to the 8 XCDs; each XCD gets a contiguous run of tiles so
-    // that tiles sharing operand panels meet in one L2.  Tiles are ordered in groups of GN tile
-    // columns, m next, the columns of the group fastest: the ~128 tiles an XCD works on at a time
-    // then form a compact block (16 x 8 tiles: 24 operand panels) rather than two full tile
-    // columns (66 panels), which matters for the weight-gradient product, whose streaming
-    // read-modify-write of W and the velocity keeps evicting the panels from the L2.
     const int nt = tiles_m * tiles_n;
     const int sk = g.sk > 1 ? g.sk : 1;
     const int nwork = nt * sk;           // (tile, k split) pairs, splits of a tile adjacent
     const int per_xcd = (nwork + 7) / 8;
-    const int u = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    const int u = (block % 8) * per_xcd + block / 8;
     if (u >= nwork) return;
     const int v = u / sk, split = u - v * sk;
     constexpr int GN = 8;
@@ -616,6 +617,40 @@ __global__ __launch_bounds__(T::NT, T::OCC) void gemm_kernel(GemmArgs g, int til
         gemm_tile<T, A_KC, B_KC, EPI, VEC, VEC>(g, smem, m0, n0, v, split);
     else
         gemm_tile<T, A_KC, B_KC, EPI, VEC, false>(g, smem, m0, n0, v, split);
+}
+
+template <class T, bool A_KC, bool B_KC, int EPI, bool VEC>
+__global__ __launch_bounds__(T::NT, T::OCC) void gemm_kernel(GemmArgs g, int tiles_m, int tiles_n)
+{
+    extern __shared__ __attribute__((aligned(16))) float smem[];
+    gemm_block<T, A_KC, B_KC, EPI, VEC>(g, smem, tiles_m, tiles_n, (int)blockIdx.x);
+}
+
+// Two independent products in one launch (both with vector-loadable operands): workgroups
+// [0, blocks0) work on the first, the rest on the second.  blocks0 is a multiple of 8, so a
+// workgroup's XCD is the same function of its number within either product.  Used for pairs of
+// products of one backward pass that do not depend on each other (the weight gradient of layer l
+// with the delta product through W_{l-1}; the gradients of the two lowest layers): one launch
+// latency instead of two, and the second product's workgroups fill the compute units the first
+// one's last wave of tiles leaves idle.
+template <class T, bool A_KC_, bool B_KC_, int EPI_>
+struct Product {
+    using Tile = T;
+    static constexpr bool A_KC = A_KC_, B_KC = B_KC_;
+    static constexpr int EPI = EPI_;
+};
+
+template <class P0, class P1>
+__global__ __launch_bounds__(P0::Tile::NT, (P0::Tile::OCC < P1::Tile::OCC ? P0::Tile::OCC : P1::Tile::OCC))
+void gemm_pair_kernel(GemmArgs g0, int tiles_m0, int tiles_n0, int blocks0, GemmArgs g1, int tiles_m1, int tiles_n1)
+{
+    static_assert(P0::Tile::NT == P1::Tile::NT, "both products need the same workgroup size");
+    extern __shared__ __attribute__((aligned(16))) float smem[];
+    const int block = (int)blockIdx.x;
+    if (block < blocks0)
+        gemm_block<typename P0::Tile, P0::A_KC, P0::B_KC, P0::EPI, true>(g0, smem, tiles_m0, tiles_n0, block);
+    else
+        gemm_block<typename P1::Tile, P1::A_KC, P1::B_KC, P1::EPI, true>(g1, smem, tiles_m1, tiles_n1, block - blocks0);
 }
 
 // ---- tile configurations and dispatch ----------------------------------------
@@ -651,12 +686,14 @@ static hipError_t launch_vec(const GemmArgs &a, hipStream_t stream)
     if (grid <= 0 || grid > 0x7fffffffL) return hipErrorInvalidValue;
     constexpr size_t lds = smem_bytes<T, A_KC, B_KC>();
     static_assert(lds <= 160 * 1024, "tile does not fit the 160 KB LDS of a CU");
-    static bool attr_set = false;  // raise the dynamic-LDS limit once per instantiation
-    if (!attr_set) {
+    // raise the dynamic-LDS limit once per instantiation (nets may be driven from different
+    // threads: setting it twice is harmless, the flag only has to be read and written atomically)
+    static std::atomic<bool> attr_set{false};
+    if (!attr_set.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel<T, A_KC, B_KC, EPI, VEC>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        attr_set = true;
+        attr_set.store(true, std::memory_order_release);
     }
     hipLaunchKernelGGL((gemm_kernel<T, A_KC, B_KC, EPI, VEC>), dim3((unsigned)grid), dim3(T::NT), lds, stream, b,
                        tiles_m, tiles_n);
@@ -676,11 +713,13 @@ using V8 = Tile<128, 64, 16, 2, 2, 1, 2, 16, 2>;  // weight gradients, two workg
 using V9 = Tile<64, 64, 16, 2, 2, 1, 2, 8, 4>;    // weight gradients, four workgroups per CU
 using V10 = Tile<64, 64, 32, 2, 2, 2, 2, 0, 2>;   // weight gradients over long k (large batches): k split between two wave groups
 using V11 = Tile<64, 64, 16, 2, 2, 1, 2, 8, 3>;   // as V9 with three workgroups per CU: the momentum update then needs no register spills
+using V12 = Tile<32, 32, 64, 1, 1, 4, 2, 0, 3>;   // batch x width products beside a weight gradient in one launch: 256 threads like V11
 
 static const char *kVariantNames[] = {"128x128x16_r1",  "128x64x16_r2",   "64x64x64_k4_r2", "64x64x32_k4_r2",
                                       "32x64x32_k4_r2", "32x64x64_k8_r2", "32x32x64_k8_r2", "128x128x16_r2_pc16",
-                                      "128x64x16_r2_pc16_o2", "64x64x16_r2_pc8_o4", "64x64x32_k2_r2_o2", "64x64x16_r2_pc8_o3"};
-constexpr int kVariants = 12;
+                                      "128x64x16_r2_pc16_o2", "64x64x16_r2_pc8_o4", "64x64x32_k2_r2_o2", "64x64x16_r2_pc8_o3",
+                                      "32x32x64_k4_r2_o3"};
+constexpr int kVariants = 13;
 int gemm_variant_count() { return kVariants; }
 const char *gemm_variant_name(int v) { return (v >= 0 && v < kVariants) ? kVariantNames[v] : "?"; }
 
@@ -734,7 +773,85 @@ static int pick_variant(GemmKind kind, const GemmArgs &a)
     if (a.K <= 512 && tiles(128, 128) >= 256) return a.K >= 192 ? 7 : 0;
     if (tiles(128, 64) >= 256) return 1;
     if (tiles(32, 64) > 256) return 4;
-    return 6;
+    // few output tiles: 32 x 32 tiles whose waves split k.  Four waves at up to three workgroups per
+    // CU (variant 12) measured 3-5 % faster than eight waves at one (variant 6) on batch x 1024 x 1024
+    // forward / delta products for batches of 32 to 512; weight gradients keep the older choice
+    return kind != GEMM_GRAD ? 12 : 6;
+}
+
+// ---- two products in one launch ------------------------------------------------------
+static bool vec_ok(GemmKind kind, const GemmArgs &a)
+{
+    const bool a_kc = kind != GEMM_GRAD, b_kc = kind == GEMM_FWD;
+    const bool a_vec = (a.lda % 4 == 0) && ((a_kc ? a.K : a.M) % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.A) & 15) == 0);
+    const bool b_vec = (a.ldb % 4 == 0) && ((b_kc ? a.K : a.N) % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.B) & 15) == 0);
+    return a_vec && b_vec;
+}
+
+template <class P0, class P1>
+static hipError_t launch_pair_as(const GemmArgs &a0, const GemmArgs &a1, hipStream_t stream)
+{
+    using T0 = typename P0::Tile;
+    using T1 = typename P1::Tile;
+    GemmArgs b0 = a0, b1 = a1;
+    b0.sk = b1.sk = 1;    // no k split across workgroups: the launch has enough workgroups as it is
+    const int tm0 = (a0.M + T0::BM - 1) / T0::BM, tn0 = (a0.N + T0::BN - 1) / T0::BN;
+    const int tm1 = (a1.M + T1::BM - 1) / T1::BM, tn1 = (a1.N + T1::BN - 1) / T1::BN;
+    const long g0 = 8 * (((long)tm0 * tn0 + 7) / 8), g1 = 8 * (((long)tm1 * tn1 + 7) / 8);
+    if (g0 + g1 > 0x7fffffffL) return hipErrorInvalidValue;
+    constexpr size_t l0 = smem_bytes<T0, P0::A_KC, P0::B_KC>(), l1 = smem_bytes<T1, P1::A_KC, P1::B_KC>();
+    constexpr size_t lds = l0 > l1 ? l0 : l1;
+    static std::atomic<bool> attr_set{false};
+    if (!attr_set.load(std::memory_order_acquire)) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_pair_kernel<P0, P1>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_set.store(true, std::memory_order_release);
+    }
+    hipLaunchKernelGGL((gemm_pair_kernel<P0, P1>), dim3((unsigned)(g0 + g1)), dim3(T0::NT), lds, stream, b0, tm0, tn0,
+                       (int)g0, b1, tm1, tn1);
+    return hipGetLastError();
+}
+
+template <int EPI_GRAD>
+static hipError_t launch_pair_mode(GemmKind other, const GemmArgs &grad, const GemmArgs &b, hipStream_t stream)
+{
+    using PG = Product<V11, false, false, EPI_GRAD>;
+    if (other == GEMM_GRAD) return launch_pair_as<PG, PG>(grad, b, stream);
+    // the delta product goes first: its workgroups run longest
+    return launch_pair_as<Product<V12, true, false, EPI_DELTA>, PG>(b, grad, stream);
+}
+
+// Whether launch_gemm_pair would put these two products into one launch.
+bool gemm_pair_fits(const GemmArgs &grad, GemmKind other, const GemmArgs &b, int variant)
+{
+    auto tiles64 = [](const GemmArgs &a) { return (long)((a.M + 63) / 64) * ((a.N + 63) / 64); };
+    if (variant >= 0) return false;                        // a forced tile shape is honoured launch by launch
+    if (narrow_layer(grad.M) || !vec_ok(GEMM_GRAD, grad)) return false;
+    if (tiles64(grad) < 256 || grad.K > 512) return false; // the shapes the 64 x 64, three-per-CU gradient tile is chosen for
+    if (other == GEMM_GRAD)
+        return b.mode == grad.mode && !narrow_layer(b.M) && vec_ok(GEMM_GRAD, b) && tiles64(b) >= 256 && b.K <= 512;
+    if (other == GEMM_DELTA)   // a batch x width product of moderate size: 32 x 32 tiles, k split among the four waves
+        return !narrow_layer(b.K) && vec_ok(GEMM_DELTA, b) && b.M <= 512 && b.K <= 2048;
+    return false;
+}
+
+hipError_t launch_gemm_pair(const GemmArgs &grad, GemmKind other, const GemmArgs &b, int variant, hipStream_t stream)
+{
+    if (!gemm_pair_fits(grad, other, b, variant)) {
+        // one after the other; a delta product first, as its weights may be the ones the gradient updates
+        const hipError_t e = other == GEMM_DELTA ? launch_gemm(GEMM_DELTA, b, variant, stream)
+                                                 : launch_gemm(GEMM_GRAD, grad, variant, stream);
+        if (e != hipSuccess) return e;
+        return other == GEMM_DELTA ? launch_gemm(GEMM_GRAD, grad, variant, stream) : launch_gemm(other, b, variant, stream);
+    }
+    switch (grad.mode) {
+    case GRAD_STORE: return launch_pair_mode<EPI_GRAD_STORE>(other, grad, b, stream);
+    case GRAD_SGD: return launch_pair_mode<EPI_GRAD_SGD>(other, grad, b, stream);
+    case GRAD_SGD_KEEPV: return launch_pair_mode<EPI_GRAD_SGD_KEEPV>(other, grad, b, stream);
+    case GRAD_MOMENTUM: return launch_pair_mode<EPI_GRAD_MOMENTUM>(other, grad, b, stream);
+    default: return hipErrorInvalidValue;
+    }
 }
 
 hipError_t launch_gemm(GemmKind kind, const GemmArgs &a, int variant, hipStream_t stream)
@@ -761,6 +878,7 @@ hipError_t launch_gemm(GemmKind kind, const GemmArgs &a, int variant, hipStream_
     case 9: return launch_kind<V9>(kind, a, stream);
     case 10: return launch_kind<V10>(kind, a, stream);
     case 11: return launch_kind<V11>(kind, a, stream);
+    case 12: return launch_kind<V12>(kind, a, stream);
     default: return hipErrorInvalidValue;
     }
 }

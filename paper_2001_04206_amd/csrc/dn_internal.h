@@ -61,6 +61,12 @@ constexpr int GEMM_COUNTERS = 1024;
 // Enqueue one contraction on `stream`.  Returns hipSuccess or the launch error.
 // `variant` < 0 picks a tile configuration from the shape; >= 0 forces one.
 hipError_t launch_gemm(GemmKind kind, const GemmArgs &a, int variant, hipStream_t stream);
+// Two products of one backward pass that do not depend on each other -- the weight gradient
+// `grad` (GEMM_GRAD, any mode) and `other`: a delta product through ANOTHER layer's weights, or a
+// second weight gradient in the same mode -- in one launch when their shapes suit it
+// (gemm_pair_fits), else one after the other.
+bool gemm_pair_fits(const GemmArgs &grad, GemmKind other, const GemmArgs &b, int variant);
+hipError_t launch_gemm_pair(const GemmArgs &grad, GemmKind other, const GemmArgs &b, int variant, hipStream_t stream);
 int gemm_variant_count();
 const char *gemm_variant_name(int variant);
 
@@ -94,9 +100,11 @@ hipError_t launch_narrow_grad(const float *D, const float *Aprev, float *C, floa
                               int nl, int nin, int mode, float scale, float mu, hipStream_t stream);
 // Last layer with at most 16 outputs, training step: forward product, then softmax / loss / Delta_L as
 // launch_output_delta's phase OUT_FUSED, in one launch.  Aprev [B][nin], W [nl][nin], AL and DL [B][nl].
+// Dprev (optional, [B][nin]): also receives Delta_{L-1} = (Delta_L W_L) * f'_{act_prev}(Aprev), as
+// launch_narrow_delta would compute it.
 hipError_t launch_narrow_output(const float *Aprev, const float *W, const float *bias, const int32_t *labels,
                                 float *AL, float *DL, float *loss_rows, double *loss_sums, int B, int nl, int nin,
-                                int act, int loss, hipStream_t stream);
+                                int act, int loss, hipStream_t stream, float *Dprev = nullptr, int act_prev = 0);
 // Elementwise update of a parameter vector from a stored gradient (dn_update).
 hipError_t launch_update(float *p, float *v, const float *g, size_t count, float lr, float mu,
                          hipStream_t stream);

@@ -1737,12 +1737,32 @@ hipError_t online_prepare()
                                (int)ON_MAX_LDS_BYTES);
 }
 
+// The persistent kernels' workgroups wait for one another, so all of them must be on the device at
+// once.  That holds for an ordinary launch when the grid is no larger than what the device can hold
+// of this kernel at this LDS size (checked here from the occupancy query: workgroups per compute
+// unit x compute units) and nothing else occupies the compute units for long; work queued earlier on
+// the same stream has finished by the time the kernel starts.  Should a workgroup be kept waiting
+// anyway (other long-running work of the process on another stream), the bounded polls end the
+// launch with the abort flag instead of hanging.  (A cooperative launch gives the same residency
+// through a separate device queue; that queue's teardown crashed at process exit under the
+// profiler, and its only service here -- refusing grids that cannot be resident -- is this check.)
+template <class Kernel, class Plan>
+static hipError_t launch_resident(Kernel kernel, const Plan &plan, int grid, size_t lds_bytes, hipStream_t stream)
+{
+    int dev = 0, cus = 0, per_cu = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e == hipSuccess)
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(kernel), ON_THREADS, lds_bytes);
+    if (e != hipSuccess) return e;
+    if (grid < 1 || per_cu < 1 || (long)grid > (long)per_cu * cus) return hipErrorCooperativeLaunchTooLarge;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(ON_THREADS), lds_bytes, stream, plan);
+    return hipGetLastError();
+}
+
 hipError_t launch_online_epoch(const OnlineGeom &g, const OnlinePlan &plan, hipStream_t stream)
 {
-    OnlinePlan p = plan;
-    void *args[] = {&p};
-    return hipLaunchCooperativeKernel((const void *)online_epoch_kernel, dim3(g.grid), dim3(ON_THREADS), args,
-                                      (unsigned)(g.lds_floats * sizeof(float)), stream);
+    return launch_resident(online_epoch_kernel, plan, g.grid, (size_t)g.lds_floats * sizeof(float), stream);
 }
 
 bool batch_geometry(const int32_t *n, int L, int max_batch, int min_tile, bool want_v, BatchGeom &g)
@@ -1805,10 +1825,7 @@ hipError_t batch_prepare()
 
 hipError_t launch_batch_epoch(const BatchGeom &g, const BatchPlan &plan, hipStream_t stream)
 {
-    BatchPlan p = plan;
-    void *args[] = {&p};
-    return hipLaunchCooperativeKernel((const void *)batch_epoch_kernel, dim3(g.grid), dim3(ON_THREADS), args,
-                                      (unsigned)(g.lds_floats * sizeof(float)), stream);
+    return launch_resident(batch_epoch_kernel, plan, g.grid, (size_t)g.lds_floats * sizeof(float), stream);
 }
 
 bool deep_geometry(const int32_t *n, int L, int max_batch, int min_tile, DeepGeom &g)
@@ -1890,10 +1907,7 @@ hipError_t deep_prepare()
 
 hipError_t launch_deep_epoch(const DeepGeom &g, const DeepPlan &plan, hipStream_t stream)
 {
-    DeepPlan p = plan;
-    void *args[] = {&p};
-    return hipLaunchCooperativeKernel((const void *)deep_batch_epoch_kernel, dim3(g.grid), dim3(ON_THREADS), args,
-                                      (unsigned)(g.lds_floats * sizeof(float)), stream);
+    return launch_resident(deep_batch_epoch_kernel, plan, g.grid, (size_t)g.lds_floats * sizeof(float), stream);
 }
 
 }  // namespace dn

@@ -390,12 +390,18 @@ bool narrow_layer(int n_out) { return n_out >= 1 && n_out <= kNarrow; }
 // rows of the batch; its 256 threads split k (each W_L element a lane loads serves R rows), the
 // R * n_L dot products are summed across each wave and then across the four waves through LDS,
 // and wave w finishes rows w, w + 4, ... with every lane holding the row's z.
+// With Dprev given the launch also propagates the error one layer down: Delta_{L-1}[b][k] =
+// f'_{L-1}(A_{L-1}[b][k]) * sum_o Delta_L[b][o] W_L[o][k] -- every thread already holds its k
+// columns of W_L and of the row, so the delta product through a narrow last layer costs no
+// launch of its own.  Same arithmetic, in the same order, as narrow_delta_kernel.
 struct NarrowOutArgs {
     const float *Aprev, *W, *bias;
     const int32_t *labels;
     float *AL, *DL, *loss_rows;
     double *loss_sums;
     int B, nl, nin, act, loss;
+    float *Dprev;     // [B][nin] or nullptr
+    int act_prev;     // activation of layer L-1 (its derivative multiplies Dprev)
 };
 
 template <int R, int VEC>
@@ -403,6 +409,7 @@ __global__ __launch_bounds__(256) void narrow_output_kernel(NarrowOutArgs g)
 {
     typedef float vec_t __attribute__((ext_vector_type(VEC)));
     __shared__ float part[4][R][kNarrow];
+    __shared__ float dsh[R][kNarrow];   // Delta_L of the workgroup's rows, for the propagation phase
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int row0 = blockIdx.x * R;
     // what the last phase needs, requested before the k loop so that it is there by then
@@ -473,8 +480,10 @@ __global__ __launch_bounds__(256) void narrow_output_kernel(NarrowOutArgs g)
             for (int o = 0; o < kNarrow; ++o) mine = (o == lane) ? z[o] * inv : mine;
             e = logf(sum) - (zy - m);
             if (lane < g.nl) {
+                const float d = mine - (lane == y ? 1.0f : 0.0f);
                 g.AL[(size_t)row * g.nl + lane] = mine;
-                g.DL[(size_t)row * g.nl + lane] = mine - (lane == y ? 1.0f : 0.0f);
+                g.DL[(size_t)row * g.nl + lane] = d;
+                dsh[r][lane] = d;
             }
         } else {
             e = 0.f;
@@ -488,8 +497,10 @@ __global__ __launch_bounds__(256) void narrow_output_kernel(NarrowOutArgs g)
                 }
             if (lane < g.nl) {
                 const float diff = mine - (lane == y ? 1.0f : 0.0f);
+                const float d = diff * deriv_from_output(g.act, mine);
                 g.AL[(size_t)row * g.nl + lane] = mine;
-                g.DL[(size_t)row * g.nl + lane] = diff * deriv_from_output(g.act, mine);
+                g.DL[(size_t)row * g.nl + lane] = d;
+                dsh[r][lane] = d;
             }
         }
         if (lane == 0) {
@@ -497,15 +508,45 @@ __global__ __launch_bounds__(256) void narrow_output_kernel(NarrowOutArgs g)
             if (g.loss_sums) g.loss_sums[row] += (double)e;
         }
     }
+    if (!g.Dprev) return;
+    __syncthreads();
+    for (int k = threadIdx.x * VEC; k < g.nin; k += 256 * VEC) {
+        vec_t sum[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) sum[r] = 0.f;
+#pragma unroll
+        for (int o = 0; o < kNarrow; ++o) {
+            if (o < g.nl) {
+                const vec_t w = *reinterpret_cast<const vec_t *>(g.W + (size_t)o * g.nin + k);
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    const float dv = dsh[r][o];
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) sum[r][v] = fmaf(dv, w[v], sum[r][v]);
+                }
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            if (row0 + r < g.B) {
+                const size_t e = (size_t)(row0 + r) * g.nin + k;
+                const vec_t a = *reinterpret_cast<const vec_t *>(g.Aprev + e);
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) sum[r][v] *= deriv_from_output(g.act_prev, a[v]);
+                *reinterpret_cast<vec_t *>(g.Dprev + e) = sum[r];
+            }
+        }
+    }
 }
 
 hipError_t launch_narrow_output(const float *Aprev, const float *W, const float *bias, const int32_t *labels,
                                 float *AL, float *DL, float *loss_rows, double *loss_sums, int B, int nl, int nin,
-                                int act, int loss, hipStream_t stream)
+                                int act, int loss, hipStream_t stream, float *Dprev, int act_prev)
 {
     if (!narrow_layer(nl) || B < 1 || nin < 1) return hipErrorInvalidValue;
-    const bool vec = nin % 4 == 0 && ((reinterpret_cast<uintptr_t>(Aprev) | reinterpret_cast<uintptr_t>(W)) & 15) == 0;
-    NarrowOutArgs g{Aprev, W, bias, labels, AL, DL, loss_rows, loss_sums, B, nl, nin, act, loss};
+    const bool vec = nin % 4 == 0 && ((reinterpret_cast<uintptr_t>(Aprev) | reinterpret_cast<uintptr_t>(W) |
+                                        reinterpret_cast<uintptr_t>(Dprev)) & 15) == 0;
+    NarrowOutArgs g{Aprev, W, bias, labels, AL, DL, loss_rows, loss_sums, B, nl, nin, act, loss, Dprev, act_prev};
     const int R = B > 1024 ? 4 : 1;
     const unsigned grid = (unsigned)((B + R - 1) / R);
     if (R == 4 && vec) hipLaunchKernelGGL((narrow_output_kernel<4, 4>), dim3(grid), dim3(256), 0, stream, g);

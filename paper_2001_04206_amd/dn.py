@@ -19,14 +19,14 @@ LIB_PATH = os.path.join(_HERE, "libdn.so")
 DN_OK, DN_ERR_INVALID_ARG, DN_ERR_SHAPE, DN_ERR_UNSUPPORTED, DN_ERR_OOM, DN_ERR_DEVICE = range(6)
 DN_ACT_LINEAR, DN_ACT_SIGMOID, DN_ACT_TANH, DN_ACT_RELU, DN_ACT_SOFTMAX = range(5)
 DN_LOSS_MSE, DN_LOSS_CROSS_ENTROPY = 0, 1
-DN_K_FORWARD, DN_K_DELTA, DN_K_GRAD_UPDATE, DN_K_OUTPUT, DN_K_ONLINE = range(5)
-KERNEL_CLASS_NAMES = ["forward", "delta", "grad_update", "output", "online"]
+DN_K_FORWARD, DN_K_DELTA, DN_K_GRAD_UPDATE, DN_K_OUTPUT, DN_K_ONLINE, DN_K_PAIR = range(6)
+KERNEL_CLASS_NAMES = ["forward", "delta", "grad_update", "output", "online", "pair"]
 
 EXPORTS = [
     "dn_status_string", "dn_net_arena_bytes", "dn_net_create", "dn_net_destroy", "dn_set_params",
     "dn_get_params", "dn_get_grads", "dn_forward", "dn_backward", "dn_update", "dn_train_epoch",
     "dn_train", "dn_evaluate", "dn_layer_backward_workspace_bytes", "dn_layer_backward_host",
-    "dn_last_epoch_ms", "dn_kernel_time", "dn_set_option",
+    "dn_last_epoch_ms", "dn_kernel_time", "dn_kernel_flops", "dn_set_option",
     "dn_conv_forward", "dn_conv_backward_workspace_bytes", "dn_conv_backward", "dn_maxpool_forward",
     "dn_maxpool_backward", "dn_input_gradient", "dn_sgd_step",
     "dn_conv_backward_static", "dn_conv_backward_static_limit",
@@ -75,6 +75,7 @@ def lib():
                                              C.POINTER(f32), C.POINTER(f32), C.POINTER(f32)]
         l.dn_last_epoch_ms.argtypes = [vp, C.POINTER(f32)]
         l.dn_kernel_time.argtypes = [vp, i32, C.POINTER(f32), C.POINTER(i64)]
+        l.dn_kernel_flops.argtypes = [vp, i32, C.POINTER(C.c_double)]
         l.dn_set_option.argtypes = [vp, C.c_char_p, i64]
         for name in EXPORTS[2:]:
             if name.endswith("_workspace_bytes") or name.endswith("_static_limit"):
@@ -415,6 +416,11 @@ class Net:
         ms, n = C.c_float(0.0), C.c_int64(0)
         _check(lib().dn_kernel_time(self._h, kernel_class, C.byref(ms), C.byref(n)), "dn_kernel_time")
         return float(ms.value), int(n.value)
+
+    def dn_kernel_flops(self, kernel_class: int) -> float:
+        f = C.c_double(0.0)
+        _check(lib().dn_kernel_flops(self._h, kernel_class, C.byref(f)), "dn_kernel_flops")
+        return float(f.value)
 
     def dn_set_option(self, name: str, value: int):
         _check(lib().dn_set_option(self._h, name.encode(), int(value)), "dn_set_option")

@@ -8,8 +8,13 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 
+CAPTURE_MANAGER = None      # pytest's capture plugin: parity_util.announce() writes past it
+
+
 def pytest_configure(config):
+    global CAPTURE_MANAGER
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    CAPTURE_MANAGER = config.pluginmanager.getplugin("capturemanager")
 
 
 @pytest.fixture(scope="session", autouse=True)

@@ -5,9 +5,24 @@ import numpy as np
 
 
 def announce(msg: str):
-    """Name the case on the real stderr (past pytest's capture) before a GPU step."""
-    sys.__stderr__.write("[gpu-case] " + msg + "\n")
-    sys.__stderr__.flush()
+    """Name the case on the real stderr before a GPU step or a long checker run.  pytest captures
+    at the file-descriptor level, so its capture is suspended for the write: the line then shows
+    while the test is still running, which names the case if the run dies and shows that a long
+    test is alive."""
+    capman = None
+    try:
+        import conftest
+        capman = conftest.CAPTURE_MANAGER
+    except ImportError:
+        pass
+    if capman is not None:
+        capman.suspend_global_capture(in_=False)
+    try:
+        sys.__stderr__.write("[gpu-case] " + msg + "\n")
+        sys.__stderr__.flush()
+    finally:
+        if capman is not None:
+            capman.resume_global_capture()
 
 
 def rel_err(got: np.ndarray, ref: np.ndarray):

@@ -111,7 +111,7 @@ SMALL_CASES = [
 
 
 @pytest.mark.parametrize("widths,acts,loss,B", SMALL_CASES)
-@pytest.mark.parametrize("variant", [-1, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11])
+@pytest.mark.parametrize("variant", [-1, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12])
 def test_one_step_small_and_ragged(dnlib, widths, acts, loss, B, variant):
     announce("one_step_small widths=%s acts=%s loss=%d B=%d variant=%d" % (widths, acts, loss, B, variant))
     w = synth.make("small", widths, acts, loss, n_samples=2 * B, features="normal",
@@ -138,6 +138,49 @@ def test_one_step_split_k(dnlib, widths, acts, loss, B, variant, split_k):
     w = synth.make("splitk", widths, acts, loss, n_samples=2 * B, features="normal",
                    init="xavier_uniform", batch=B, lr=0.05, momentum=0.9, seed=7)
     check_one_step(dnlib, w, B, lr=0.05, mu=0.9, variant=variant, split_k=split_k)
+
+
+PAIR_CASES = [
+    # wide enough (>= 256 tiles of 64 x 64 per weight matrix, widths multiples of 4) for two independent
+    # products of the backward pass to share a launch: gradient of layer l with the delta product through
+    # W_{l-1}, and the gradients of the two lowest layers.  Ragged against every tile size involved.
+    ([1040, 1028, 1100, 24], [TANH, RELU, SOFTMAX], CE, 40, 0.9),
+    ([1028, 1092, 1032, 1040, 20], [RELU, TANH, SIG, LIN], MSE, 132, 0.0),
+    ([1024, 1024, 1024, 10], [TANH, TANH, SOFTMAX], CE, 516, 0.9),     # batch beyond the pairing limit of 512: one launch per product
+]
+
+
+@pytest.mark.parametrize("widths,acts,loss,B,mu", PAIR_CASES)
+@pytest.mark.parametrize("pair", [1, 0])
+def test_paired_backward_launches(dnlib, widths, acts, loss, B, mu, pair):
+    announce("paired backward launches widths=%s B=%d mu=%g pair_launch=%d" % (widths, B, mu, pair))
+    w = synth.make("pair", widths, acts, loss, n_samples=3 * B - 7, features="normal",
+                   init="xavier_uniform", batch=B, lr=0.05, momentum=mu, seed=23)
+    rng = np.random.default_rng(29)
+    w.b = [rng.standard_normal(n).astype(np.float32) * 0.1 for n in widths[1:]]
+    # the split API (gradients stored), then fused epochs (plain / last-step / momentum updates, short last batch)
+    net, o = make_pair(dnlib, w, B)
+    net.dn_set_option("pair_launch", pair)
+    X, y = to_dev(w)
+    out = torch.empty((B, widths[-1]), dtype=torch.float32, device="cuda:0")
+    net.dn_forward(X[:B].contiguous(), out)
+    net.dn_backward(y[:B].contiguous())
+    o.forward(w.X[:B]); o.backward(w.labels[:B])
+    G, g = net.get_all_grads()
+    Gr, gr = o.get_grads()
+    for l in range(net.L):
+        assert_close(G[l], Gr[l], STEP_TOL, "G_%d" % (l + 1))
+        assert_close(g[l], gr[l], STEP_TOL, "g_%d" % (l + 1))
+    for e in range(2):
+        got = net.dn_train_epoch(X, y, B, w.lr, mu)
+        ref, _ = o.train_epoch(w.X, w.labels, B, w.lr, mu)
+        assert abs(got - ref) <= EPOCH_TOL * abs(ref), (e, got, ref)
+    W, b = net.get_all()
+    Wr, br = o.get_params()
+    for l in range(net.L):
+        assert_close(W[l], Wr[l], EPOCH_TOL, "W_%d" % (l + 1))
+        assert_close(b[l], br[l], EPOCH_TOL, "b_%d" % (l + 1))
+    net.close()
 
 
 NARROW_CASES = [

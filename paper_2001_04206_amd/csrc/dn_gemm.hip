@@ -20,6 +20,7 @@
 #include <type_traits>
 
 #include "dn_internal.h"
+#include "dn_narrow.h"
 #include "dn_wave.h"
 
 namespace dn {
@@ -653,6 +654,22 @@ void gemm_pair_kernel(GemmArgs g0, int tiles_m0, int tiles_n0, int blocks0, Gemm
         gemm_block<typename P1::Tile, P1::A_KC, P1::B_KC, P1::EPI, true>(g1, smem, tiles_m1, tiles_n1, block - blocks0);
 }
 
+// A matrix-core product and the weight gradient / update of a layer with at most 16 outputs (vector
+// units, narrow_grad_block) in one launch: workgroups [0, blocks0) take the product's tiles, the
+// rest the narrow gradient.  Both use 256 threads.
+template <class P0>
+__global__ __launch_bounds__(P0::Tile::NT, P0::Tile::OCC)
+void gemm_narrow_grad_kernel(GemmArgs g0, int tiles_m0, int tiles_n0, int blocks0, NarrowGradArgs ng, int narrow_blocks)
+{
+    static_assert(P0::Tile::NT == 256, "the narrow gradient's workgroups have 256 threads");
+    extern __shared__ __attribute__((aligned(16))) float smem[];
+    const int block = (int)blockIdx.x;
+    if (block < blocks0)
+        gemm_block<typename P0::Tile, P0::A_KC, P0::B_KC, P0::EPI, true>(g0, smem, tiles_m0, tiles_n0, block);
+    else
+        narrow_grad_block<4>(ng, block - blocks0, narrow_blocks);
+}
+
 // ---- tile configurations and dispatch ----------------------------------------
 template <class T, bool A_KC, bool B_KC>
 constexpr size_t smem_bytes()
@@ -822,11 +839,37 @@ static hipError_t launch_pair_mode(GemmKind other, const GemmArgs &grad, const G
     return launch_pair_as<Product<V12, true, false, EPI_DELTA>, PG>(b, grad, stream);
 }
 
+static bool narrow_pair(const GemmArgs &grad, GemmKind other, const GemmArgs &b)
+{
+    // a narrow layer's gradient (dense operands, 16-byte pieces) beside a moderate batch x width delta product
+    const bool dense = grad.lda == grad.M && grad.ldb == grad.N && grad.ldc == grad.N;
+    const bool vec = grad.N % 4 == 0 && ((reinterpret_cast<uintptr_t>(grad.B) | reinterpret_cast<uintptr_t>(grad.C) |
+                                          reinterpret_cast<uintptr_t>(grad.V)) & 15) == 0;
+    return narrow_layer(grad.M) && dense && vec && other == GEMM_DELTA && !narrow_layer(b.K) && vec_ok(GEMM_DELTA, b) &&
+           b.M <= 512 && b.K <= 2048;
+}
+
+static hipError_t launch_narrow_pair(const GemmArgs &grad, const GemmArgs &delta, hipStream_t stream)
+{
+    using P0 = Product<V12, true, false, EPI_DELTA>;
+    GemmArgs d = delta;
+    d.sk = 1;
+    const int tm = (d.M + V12::BM - 1) / V12::BM, tn = (d.N + V12::BN - 1) / V12::BN;
+    const long g0 = 8 * (((long)tm * tn + 7) / 8);
+    const int nb = grad.N / 4 + 1;
+    NarrowGradArgs ng{grad.A, grad.B, grad.C, grad.V, grad.gb, grad.vb, grad.K, grad.M, grad.N, grad.mode, grad.scale, grad.mu};
+    constexpr size_t lds = smem_bytes<V12, true, false>();
+    hipLaunchKernelGGL((gemm_narrow_grad_kernel<P0>), dim3((unsigned)(g0 + nb)), dim3(256), lds, stream, d, tm, tn, (int)g0,
+                       ng, nb);
+    return hipGetLastError();
+}
+
 // Whether launch_gemm_pair would put these two products into one launch.
 bool gemm_pair_fits(const GemmArgs &grad, GemmKind other, const GemmArgs &b, int variant)
 {
     auto tiles64 = [](const GemmArgs &a) { return (long)((a.M + 63) / 64) * ((a.N + 63) / 64); };
     if (variant >= 0) return false;                        // a forced tile shape is honoured launch by launch
+    if (narrow_pair(grad, other, b)) return true;
     if (narrow_layer(grad.M) || !vec_ok(GEMM_GRAD, grad)) return false;
     if (tiles64(grad) < 256 || grad.K > 512) return false; // the shapes the 64 x 64, three-per-CU gradient tile is chosen for
     if (other == GEMM_GRAD)
@@ -838,6 +881,7 @@ bool gemm_pair_fits(const GemmArgs &grad, GemmKind other, const GemmArgs &b, int
 
 hipError_t launch_gemm_pair(const GemmArgs &grad, GemmKind other, const GemmArgs &b, int variant, hipStream_t stream)
 {
+    if (variant < 0 && narrow_pair(grad, other, b)) return launch_narrow_pair(grad, b, stream);
     if (!gemm_pair_fits(grad, other, b, variant)) {
         // one after the other; a delta product first, as its weights may be the ones the gradient updates
         const hipError_t e = other == GEMM_DELTA ? launch_gemm(GEMM_DELTA, b, variant, stream)

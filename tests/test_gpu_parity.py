@@ -147,6 +147,8 @@ PAIR_CASES = [
     ([1040, 1028, 1100, 24], [TANH, RELU, SOFTMAX], CE, 40, 0.9),
     ([1028, 1092, 1032, 1040, 20], [RELU, TANH, SIG, LIN], MSE, 132, 0.0),
     ([1024, 1024, 1024, 10], [TANH, TANH, SOFTMAX], CE, 516, 0.9),     # batch beyond the pairing limit of 512: one launch per product
+    ([1028, 1040, 1100, 12], [TANH, TANH, SOFTMAX], CE, 136, 0.9),     # narrow last layer: its gradient rides with the delta product below
+    ([516, 1040, 1100, 16], [RELU, SIG, SIG], MSE, 50, 0.0),           # the same with squared error and 16 outputs
 ]
 
 

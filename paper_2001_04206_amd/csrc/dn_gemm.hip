@@ -343,6 +343,32 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g0, float *smem, const
 #pragma unroll
         for (int q = 0; q < NPRE * (PRE_V ? 2 : 1); ++q) pre_load(q);
     }
+    // FWD: the biases of this wave's columns, requested here for the same reason (measured: fetched in
+    // the epilogue, that one cold load made the epilogue 2.5 us of a 9 us kernel)
+    float bias_pre[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        bias_pre[j] = 0.f;
+        if (EPI == EPI_FWD && WK == 1) {
+            const int col = n0 + wn * T::WTN + j * 32 + idx;
+            bias_pre[j] = g.bias[col < g.N ? col : 0];
+        }
+    }
+    // ... and with k-split wave groups, where every thread finishes four adjacent columns (below):
+    // those four biases (the thread's columns are the same in every pass: NT is a multiple of BN / 4)
+    static_assert(NT % (BN / 4) == 0, "a thread's epilogue columns must not depend on the pass");
+    const bool wide_out = EPI == EPI_FWD && WK > 1 && g.ldc % 4 == 0 &&
+                          ((reinterpret_cast<uintptr_t>(g.C) | reinterpret_cast<uintptr_t>(g.bias)) & 15) == 0;
+    v4f bias4 = {0.f, 0.f, 0.f, 0.f};
+    if (EPI == EPI_FWD && WK > 1) {
+        const int col = n0 + (tid % (BN / 4)) * 4;
+        if (wide_out && col + 4 <= g.N) {
+            bias4 = *reinterpret_cast<const v4f *>(g.bias + col);
+        } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) bias4[q] = g.bias[col + q < g.N ? col + q : 0];
+        }
+    }
 
     v16f acc[TM][TN];
 #pragma unroll
@@ -567,6 +593,42 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g0, float *smem, const
             }
         }
     }
+    // FWD with the k steps split among WK wave groups: only one group in WK holds the tile, and an
+    // activation such as tanh costs tens of instructions per element -- measured 2.5 us of a 9 us
+    // kernel when that one group ran the whole epilogue.  The sums go through LDS once more
+    // ([row][BN + 4]) and every thread of the workgroup finishes four adjacent columns of one row.
+    if (WK > 1 && EPI == EPI_FWD) {
+        constexpr int PITCH = BN + 4;
+        static_assert(WK == 1 || EPI != EPI_FWD || BM * PITCH <= 2 * STAGE, "the tile must fit the operand buffers");
+        __syncthreads();   // everyone has read what the k-split exchange left in LDS
+        if (lead) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        smem[(wm * T::WTM + i * 32 + 8 * (r / 4) + 4 * h + (r % 4)) * PITCH + wn * T::WTN + j * 32 + idx] = acc[i][j][r];
+        }
+        __syncthreads();
+        for (int e = tid; e < BM * BN / 4; e += NT) {
+            const int rl = e / (BN / 4), cl = (e % (BN / 4)) * 4;
+            const int row = m0 + rl, col = n0 + cl;
+            if (row >= g.M || col >= g.N) continue;
+            const v4f sv = *reinterpret_cast<const v4f *>(smem + rl * PITCH + cl);
+            v4f o;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) o[q] = act_fn(g.act, sv[q] + bias4[q]);
+            if (wide_out && col + 4 <= g.N) {
+                *reinterpret_cast<v4f *>(g.C + (size_t)row * g.ldc + col) = o;
+            } else {
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (col + q < g.N) g.C[(size_t)row * g.ldc + col + q] = o[q];
+            }
+        }
+        return;
+    }
     if (!lead) return;
 
     // Epilogue.  Lanes of one register cover 32 consecutive columns of one row.
@@ -576,8 +638,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g0, float *smem, const
         for (int j = 0; j < TN; ++j) {
             const int col = n0 + wn * T::WTN + j * 32 + idx;
             if (!FAST && col >= g.N) continue;
-            float bias = 0.f;
-            if (EPI == EPI_FWD) bias = g.bias[col];
+            const float bias = bias_pre[j];
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int row = m0 + wm * T::WTM + i * 32 + 8 * (r / 4) + 4 * h + (r % 4);

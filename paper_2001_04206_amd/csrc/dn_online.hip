@@ -54,7 +54,7 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 constexpr int kThreads = ON_THREADS;
 constexpr int kWaves = kThreads / 64;
 constexpr int kSpinLimit = 1 << 21;   // polls of ~0.5 us each: about a second
-constexpr int kPollBatch = 4;         // words each thread keeps in flight while polling
+constexpr int kPollBatch = 4;         // words each thread keeps in flight while polling (eight measured no faster)
 constexpr int kTmp = ON_TMP_FLOATS;
 
 enum UpdMode : int { UPD_SGD = 0, UPD_KEEPV = 1, UPD_MOMENTUM = 2 };

@@ -331,14 +331,11 @@ dn_status dn_sgd_step(float *param_dev, const float *grad_dev, float *velocity_d
  */
 typedef enum {
     DN_K_FORWARD = 0,     /* Z = A W^T + b, activation                       */
-    DN_K_DELTA = 1,       /* Delta_{l-1} = (Delta_l W_l) * f'                */
-    DN_K_GRAD_UPDATE = 2, /* G = Delta^T A / B and bias gradient, fused with the update */
+    DN_K_DELTA = 1,       /* Delta_{l-1} = (Delta_l W_l) * f' (a narrow last layer's gradient may ride along) */
+    DN_K_GRAD_UPDATE = 2, /* G = Delta^T A / B and bias gradient, fused with the update; several layers may share a launch */
     DN_K_OUTPUT = 3,      /* softmax / loss / Delta_L and loss reduction     */
     DN_K_ONLINE = 4,      /* persistent whole-epoch kernels                  */
-    DN_K_PAIR = 5,        /* two independent products of the backward pass in one launch: a layer's
-                             gradient / update with the delta product of the layer below, or the
-                             gradients / updates of the two lowest layers */
-    DN_K_CLASSES = 6
+    DN_K_CLASSES = 5
 } dn_kernel_class;
 
 dn_status dn_last_epoch_ms(dn_net *net, float *epoch_ms);
@@ -355,8 +352,9 @@ dn_status dn_kernel_flops(dn_net *net, int32_t kernel_class, double *flops);
  *                    contraction from its shape; >= 0: force that configuration
  *   "split_k"        1 (default): forward / delta products with few output tiles split k across
  *                    workgroups (partials summed in a fixed order); 0: never
- *   "pair_launch"    1 (default): independent products of a backward pass share a launch where their
- *                    shapes allow; 0: one launch per product
+ *   "merge_launches" 1 (default): the gradient / update products of a backward pass, independent of one
+ *                    another once every delta exists, share one launch where their shapes allow; 0: one
+ *                    launch per product
  *   "online_mode"    0: choose automatically; 1: per-phase launches for batch 1;
  *                    2: persistent whole-epoch kernel for batch 1 (dn_train_epoch
  *                    returns DN_ERR_UNSUPPORTED if the net does not fit it: more than

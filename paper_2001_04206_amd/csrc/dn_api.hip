@@ -104,7 +104,7 @@ struct dn_net {
     bool w1_as_in_bwd = false;   // W_1 is still the matrix the last dn_backward propagated through
     // options
     int time_kernels = 0, gemm_variant = -1, online_mode = 0, online_min_tile = ON_DEFAULT_MIN_TILE,
-        online_resident = 1, split_k_on = 1, pair_launch = 1;
+        online_resident = 1, split_k_on = 1, merge_launches = 1;
     // persistent batch-1 kernel
     OnlineGeom geom{};
     bool online_ok = false;
@@ -213,19 +213,21 @@ dn_status run_forward(dn_net *net, const float *X, int B, bool timing, int last_
     return DN_OK;
 }
 
-// Back propagation of one batch from Delta_L.  mode GRAD_STORE leaves gradients in
-// the gradient region; the other modes update parameters in place, each delta being
-// propagated through W_l before W_l is touched.  Products that do not depend on each other
-// share a launch where their shapes allow (launch_gemm_pair): with T_l the delta product through
-// W_l (giving Delta_{l-1}) and G_l the gradient / update of layer l, the order is
-//     T_L ; (G_L, T_{L-1}) ; (G_{L-1}, T_{L-2}) ; ... ; (G_3, T_2) ; (G_2, G_1)
-// -- every T_l still reads W_l before G_l writes it, and T_l precedes T_{l-1}.
+// Back propagation of one batch from Delta_L.  mode GRAD_STORE leaves gradients in the gradient
+// region; the other modes update parameters in place.  With T_l the delta product through W_l
+// (giving Delta_{l-1}) and G_l the gradient / update of layer l, the order is
+//     T_L, T_{L-1}, ..., T_2 (each needs the one before), then G_L .. G_1:
+// every T_l has read W_l before any G writes it, and once all deltas exist the G_l are independent
+// of one another, so those whose shapes allow share ONE launch (launch_gemm_grads).  A narrow last
+// layer's G_L rides with T_{L-1} instead (launch_delta_with_narrow_grad): its vector-unit work fits
+// beside the few tiles of a delta product.  merge_launches = 0: one launch per product.
 // have_top_delta: Delta_{L-1} came with the output error already (narrow last layer).
 dn_status run_backward(dn_net *net, const float *X, int B, int mode, float lr, float mu, bool timing,
                        bool have_top_delta = false)
 {
     const float scale = (mode == GRAD_STORE) ? 1.0f / (float)B : lr / (float)B;
     const int L = net->L;
+    const bool merge = net->merge_launches != 0;
     auto delta_args = [&](int l) {   // T_l, l >= 2
         GemmArgs g{};
         g.A = net->D(l); g.lda = net->n[l];
@@ -250,30 +252,52 @@ dn_status run_backward(dn_net *net, const float *X, int B, int mode, float lr, f
         g.scale = scale; g.mu = mu; g.mode = mode;
         return g;
     };
-    auto one = [&](GemmKind kind, const GemmArgs &g) -> dn_status {
-        ScopedTimer st(net, kind == GEMM_DELTA ? DN_K_DELTA : DN_K_GRAD_UPDATE, timing, product_flop(g));
-        DN_HIP(launch_gemm(kind, g, net->gemm_variant, net->stream));
-        return DN_OK;
-    };
-    auto two = [&](const GemmArgs &grad, GemmKind other, const GemmArgs &b) -> dn_status {
-        if (net->pair_launch && gemm_pair_fits(grad, other, b, net->gemm_variant)) {
-            ScopedTimer st(net, DN_K_PAIR, timing, product_flop(grad) + product_flop(b));
-            DN_HIP(launch_gemm_pair(grad, other, b, net->gemm_variant, net->stream));
-            return DN_OK;
+    if (L > ON_MAX_L + 56) return DN_ERR_UNSUPPORTED;
+    int top_grad = L;                // gradients L .. 1 are still to do
+    for (int l = L; l >= 2; --l) {
+        if (l == L && have_top_delta) continue;
+        const GemmArgs d = delta_args(l);
+        if (merge && l == L - 1 && top_grad == L) {
+            const GemmArgs gl = grad_args(L);
+            if (delta_narrow_grad_fits(d, gl, net->gemm_variant)) {
+                ScopedTimer st(net, DN_K_DELTA, timing, product_flop(d) + product_flop(gl));
+                DN_HIP(launch_delta_with_narrow_grad(d, gl, net->stream));
+                top_grad = L - 1;
+                continue;
+            }
         }
-        const dn_status st = one(GEMM_GRAD, grad);
-        return st != DN_OK ? st : one(other, b);
-    };
-    if (L > 1 && !have_top_delta) {
-        const dn_status st = one(GEMM_DELTA, delta_args(L));
-        if (st != DN_OK) return st;
+        ScopedTimer st(net, DN_K_DELTA, timing, product_flop(d));
+        DN_HIP(launch_gemm(GEMM_DELTA, d, net->gemm_variant, net->stream));
     }
-    for (int l = L; l >= 3; --l) {
-        const dn_status st = two(grad_args(l), GEMM_DELTA, delta_args(l - 1));
-        if (st != DN_OK) return st;
+    GemmArgs grads[ON_MAX_L + 56];
+    int n = 0;
+    for (int l = top_grad; l >= 1; --l) grads[n++] = grad_args(l);
+    if (!timing) {
+        DN_HIP(launch_gemm_grads(grads, n, net->gemm_variant, merge, net->stream, nullptr));
+        return DN_OK;
     }
-    if (L >= 2) return two(grad_args(2), GEMM_GRAD, grad_args(1));
-    return one(GEMM_GRAD, grad_args(1));
+    // timed: the shared launch (if any) and every single launch get an event pair of their own
+    int merged = 0;
+    {
+        // a dry run tells which products share the launch: they are timed together, the others one by one
+        bool in_shared[ON_MAX_L + 56];
+        gemm_grads_plan(grads, n, net->gemm_variant, merge, in_shared, &merged);
+        if (merged >= 2) {
+            GemmArgs shared[ON_MAX_L + 56];
+            int ns = 0;
+            double fs = 0.0;
+            for (int i = 0; i < n; ++i)
+                if (in_shared[i]) { shared[ns++] = grads[i]; fs += product_flop(grads[i]); }
+            ScopedTimer st(net, DN_K_GRAD_UPDATE, timing, fs);
+            DN_HIP(launch_gemm_grads(shared, ns, net->gemm_variant, true, net->stream, nullptr));
+        }
+        for (int i = 0; i < n; ++i) {
+            if (merged >= 2 && in_shared[i]) continue;
+            ScopedTimer st(net, DN_K_GRAD_UPDATE, timing, product_flop(grads[i]));
+            DN_HIP(launch_gemm(GEMM_GRAD, grads[i], net->gemm_variant, net->stream));
+        }
+    }
+    return DN_OK;
 }
 
 // A whole batch-1 epoch in persistent-kernel launches of at most 2^30 steps each.
@@ -915,9 +939,9 @@ dn_status dn_set_option(dn_net *net, const char *name, int64_t value)
     } else if (!strcmp(name, "batch_mode")) {
         if (value < 0 || value > 2) return DN_ERR_INVALID_ARG;
         net->batch_mode = (int)value;
-    } else if (!strcmp(name, "pair_launch")) {
+    } else if (!strcmp(name, "merge_launches")) {
         if (value != 0 && value != 1) return DN_ERR_INVALID_ARG;
-        net->pair_launch = (int)value;
+        net->merge_launches = (int)value;
     } else if (!strcmp(name, "split_k")) {
         if (value != 0 && value != 1) return DN_ERR_INVALID_ARG;
         net->split_k_on = (int)value;

@@ -458,12 +458,12 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g0, float *smem, const
     const int nfull = g.K / KT;  // k steps 0 .. nfull-1 are wholly inside k
     int t0 = 0;
     if (PC > 0) {
-        if (FAST && PC + R <= nfull) {
+        // (short contractions -- k = 128 has eight steps -- still get the mask-free form for the
+        // steps that allow it: all-or-nothing made them run masked throughout)
 #pragma unroll
-            for (int c = 0; c < PC; ++c) k_step(Full{}, c % R, c, c);
-        } else {
-#pragma unroll
-            for (int c = 0; c < PC; ++c) k_step(Ragged{}, c % R, c, c);
+        for (int c = 0; c < PC; ++c) {
+            if (FAST && c + R < nfull) k_step(Full{}, c % R, c, c);
+            else k_step(Ragged{}, c % R, c, c);
         }
         t0 = PC;
     }
@@ -688,32 +688,13 @@ __global__ __launch_bounds__(T::NT, T::OCC) void gemm_kernel(GemmArgs g, int til
     gemm_block<T, A_KC, B_KC, EPI, VEC>(g, smem, tiles_m, tiles_n, (int)blockIdx.x);
 }
 
-// Two independent products in one launch (both with vector-loadable operands): workgroups
-// [0, blocks0) work on the first, the rest on the second.  blocks0 is a multiple of 8, so a
-// workgroup's XCD is the same function of its number within either product.  Used for pairs of
-// products of one backward pass that do not depend on each other (the weight gradient of layer l
-// with the delta product through W_{l-1}; the gradients of the two lowest layers): one launch
-// latency instead of two, and the second product's workgroups fill the compute units the first
-// one's last wave of tiles leaves idle.
+// A product's template parameters as one type.
 template <class T, bool A_KC_, bool B_KC_, int EPI_>
 struct Product {
     using Tile = T;
     static constexpr bool A_KC = A_KC_, B_KC = B_KC_;
     static constexpr int EPI = EPI_;
 };
-
-template <class P0, class P1>
-__global__ __launch_bounds__(P0::Tile::NT, (P0::Tile::OCC < P1::Tile::OCC ? P0::Tile::OCC : P1::Tile::OCC))
-void gemm_pair_kernel(GemmArgs g0, int tiles_m0, int tiles_n0, int blocks0, GemmArgs g1, int tiles_m1, int tiles_n1)
-{
-    static_assert(P0::Tile::NT == P1::Tile::NT, "both products need the same workgroup size");
-    extern __shared__ __attribute__((aligned(16))) float smem[];
-    const int block = (int)blockIdx.x;
-    if (block < blocks0)
-        gemm_block<typename P0::Tile, P0::A_KC, P0::B_KC, P0::EPI, true>(g0, smem, tiles_m0, tiles_n0, block);
-    else
-        gemm_block<typename P1::Tile, P1::A_KC, P1::B_KC, P1::EPI, true>(g1, smem, tiles_m1, tiles_n1, block - blocks0);
-}
 
 // A matrix-core product and the weight gradient / update of a layer with at most 16 outputs (vector
 // units, narrow_grad_block) in one launch: workgroups [0, blocks0) take the product's tiles, the
@@ -729,6 +710,38 @@ void gemm_narrow_grad_kernel(GemmArgs g0, int tiles_m0, int tiles_n0, int blocks
         gemm_block<typename P0::Tile, P0::A_KC, P0::B_KC, P0::EPI, true>(g0, smem, tiles_m0, tiles_n0, block);
     else
         narrow_grad_block<4>(ng, block - blocks0, narrow_blocks);
+}
+
+// The weight gradients / updates of several layers in ONE launch: they only need the deltas, so once
+// every delta product of a backward pass has run they are all independent.  Workgroup numbers are
+// dealt out layer by layer (each layer's run starts at a multiple of 8, so a workgroup's XCD is the
+// same function of its number within the layer); the workgroups after the last matrix-core layer
+// take a narrow layer's gradient on the vector units, if there is one.  All layers use the same tile
+// shape and update mode.
+constexpr int MG_MAX = 8;
+struct MultiGradArgs {
+    int n;                       // matrix-core layers
+    int first[MG_MAX + 1];       // first workgroup of each layer; first[n] = first workgroup of the narrow layer
+    int tiles_m[MG_MAX], tiles_n[MG_MAX];
+    int narrow_blocks;           // 0: no narrow layer
+    GemmArgs g[MG_MAX];
+    NarrowGradArgs ng;
+};
+
+template <class T, int EPI>
+__global__ __launch_bounds__(T::NT, T::OCC) void gemm_multi_grad_kernel(MultiGradArgs m)
+{
+    static_assert(T::NT == 256, "the narrow gradient's workgroups have 256 threads");
+    extern __shared__ __attribute__((aligned(16))) float smem[];
+    const int block = (int)blockIdx.x;
+    if (block >= m.first[m.n]) {
+        narrow_grad_block<4>(m.ng, block - m.first[m.n], m.narrow_blocks);
+        return;
+    }
+    int p = 0;
+#pragma unroll
+    for (int q = 1; q < MG_MAX; ++q) p += (q < m.n && block >= m.first[q]) ? 1 : 0;
+    gemm_block<T, false, false, EPI, true>(m.g[p], smem, m.tiles_m[p], m.tiles_n[p], block - m.first[p]);
 }
 
 // ---- tile configurations and dispatch ----------------------------------------
@@ -857,7 +870,7 @@ static int pick_variant(GemmKind kind, const GemmArgs &a)
     return kind != GEMM_GRAD ? 12 : 6;
 }
 
-// ---- two products in one launch ------------------------------------------------------
+// ---- a delta product and a narrow layer's gradient in one launch ---------------------------
 static bool vec_ok(GemmKind kind, const GemmArgs &a)
 {
     const bool a_kc = kind != GEMM_GRAD, b_kc = kind == GEMM_FWD;
@@ -866,55 +879,24 @@ static bool vec_ok(GemmKind kind, const GemmArgs &a)
     return a_vec && b_vec;
 }
 
-template <class P0, class P1>
-static hipError_t launch_pair_as(const GemmArgs &a0, const GemmArgs &a1, hipStream_t stream)
+// Whether launch_delta_with_narrow_grad takes this pair: a narrow layer's gradient (dense operands,
+// 16-byte pieces) beside a moderate batch x width delta product through another layer's weights.
+bool delta_narrow_grad_fits(const GemmArgs &delta, const GemmArgs &grad, int variant)
 {
-    using T0 = typename P0::Tile;
-    using T1 = typename P1::Tile;
-    GemmArgs b0 = a0, b1 = a1;
-    b0.sk = b1.sk = 1;    // no k split across workgroups: the launch has enough workgroups as it is
-    const int tm0 = (a0.M + T0::BM - 1) / T0::BM, tn0 = (a0.N + T0::BN - 1) / T0::BN;
-    const int tm1 = (a1.M + T1::BM - 1) / T1::BM, tn1 = (a1.N + T1::BN - 1) / T1::BN;
-    const long g0 = 8 * (((long)tm0 * tn0 + 7) / 8), g1 = 8 * (((long)tm1 * tn1 + 7) / 8);
-    if (g0 + g1 > 0x7fffffffL) return hipErrorInvalidValue;
-    constexpr size_t l0 = smem_bytes<T0, P0::A_KC, P0::B_KC>(), l1 = smem_bytes<T1, P1::A_KC, P1::B_KC>();
-    constexpr size_t lds = l0 > l1 ? l0 : l1;
-    static std::atomic<bool> attr_set{false};
-    if (!attr_set.load(std::memory_order_acquire)) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_pair_kernel<P0, P1>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_set.store(true, std::memory_order_release);
-    }
-    hipLaunchKernelGGL((gemm_pair_kernel<P0, P1>), dim3((unsigned)(g0 + g1)), dim3(T0::NT), lds, stream, b0, tm0, tn0,
-                       (int)g0, b1, tm1, tn1);
-    return hipGetLastError();
-}
-
-template <int EPI_GRAD>
-static hipError_t launch_pair_mode(GemmKind other, const GemmArgs &grad, const GemmArgs &b, hipStream_t stream)
-{
-    using PG = Product<V11, false, false, EPI_GRAD>;
-    if (other == GEMM_GRAD) return launch_pair_as<PG, PG>(grad, b, stream);
-    // the delta product goes first: its workgroups run longest
-    return launch_pair_as<Product<V12, true, false, EPI_DELTA>, PG>(b, grad, stream);
-}
-
-static bool narrow_pair(const GemmArgs &grad, GemmKind other, const GemmArgs &b)
-{
-    // a narrow layer's gradient (dense operands, 16-byte pieces) beside a moderate batch x width delta product
     const bool dense = grad.lda == grad.M && grad.ldb == grad.N && grad.ldc == grad.N;
     const bool vec = grad.N % 4 == 0 && ((reinterpret_cast<uintptr_t>(grad.B) | reinterpret_cast<uintptr_t>(grad.C) |
                                           reinterpret_cast<uintptr_t>(grad.V)) & 15) == 0;
-    return narrow_layer(grad.M) && dense && vec && other == GEMM_DELTA && !narrow_layer(b.K) && vec_ok(GEMM_DELTA, b) &&
-           b.M <= 512 && b.K <= 2048;
+    return variant < 0 && narrow_layer(grad.M) && dense && vec && !narrow_layer(delta.K) && vec_ok(GEMM_DELTA, delta) &&
+           delta.M <= 512 && delta.K <= 2048;
 }
 
-static hipError_t launch_narrow_pair(const GemmArgs &grad, const GemmArgs &delta, hipStream_t stream)
+// The delta product `delta` (through W_{l-1}) and the gradient / update `grad` of a narrow layer l in
+// one launch (they do not depend on each other); call only if delta_narrow_grad_fits.
+hipError_t launch_delta_with_narrow_grad(const GemmArgs &delta, const GemmArgs &grad, hipStream_t stream)
 {
     using P0 = Product<V12, true, false, EPI_DELTA>;
     GemmArgs d = delta;
-    d.sk = 1;
+    d.sk = 1;   // the launch has enough workgroups as it is
     const int tm = (d.M + V12::BM - 1) / V12::BM, tn = (d.N + V12::BN - 1) / V12::BN;
     const long g0 = 8 * (((long)tm * tn + 7) / 8);
     const int nb = grad.N / 4 + 1;
@@ -925,38 +907,109 @@ static hipError_t launch_narrow_pair(const GemmArgs &grad, const GemmArgs &delta
     return hipGetLastError();
 }
 
-// Whether launch_gemm_pair would put these two products into one launch.
-bool gemm_pair_fits(const GemmArgs &grad, GemmKind other, const GemmArgs &b, int variant)
+// ---- the gradients of several layers in one launch ---------------------------------------
+static bool multi_grad_layer_fits(const GemmArgs &a)
 {
-    auto tiles64 = [](const GemmArgs &a) { return (long)((a.M + 63) / 64) * ((a.N + 63) / 64); };
-    if (variant >= 0) return false;                        // a forced tile shape is honoured launch by launch
-    if (narrow_pair(grad, other, b)) return true;
-    if (narrow_layer(grad.M) || !vec_ok(GEMM_GRAD, grad)) return false;
-    if (tiles64(grad) < 256 || grad.K > 512) return false; // the shapes the 64 x 64, three-per-CU gradient tile is chosen for
-    if (other == GEMM_GRAD)
-        return b.mode == grad.mode && !narrow_layer(b.M) && vec_ok(GEMM_GRAD, b) && tiles64(b) >= 256 && b.K <= 512;
-    if (other == GEMM_DELTA)   // a batch x width product of moderate size: 32 x 32 tiles, k split among the four waves
-        return !narrow_layer(b.K) && vec_ok(GEMM_DELTA, b) && b.M <= 512 && b.K <= 2048;
-    return false;
+    // shapes the 64 x 64, three-per-CU gradient tile suits: a short contraction (the batch) and a
+    // matrix of at least 64 such tiles
+    return !narrow_layer(a.M) && vec_ok(GEMM_GRAD, a) && a.K <= 512 && (long)((a.M + 63) / 64) * ((a.N + 63) / 64) >= 64;
 }
 
-hipError_t launch_gemm_pair(const GemmArgs &grad, GemmKind other, const GemmArgs &b, int variant, hipStream_t stream)
+static bool multi_grad_narrow_fits(const GemmArgs &a)
 {
-    if (variant < 0 && narrow_pair(grad, other, b)) return launch_narrow_pair(grad, b, stream);
-    if (!gemm_pair_fits(grad, other, b, variant)) {
-        // one after the other; a delta product first, as its weights may be the ones the gradient updates
-        const hipError_t e = other == GEMM_DELTA ? launch_gemm(GEMM_DELTA, b, variant, stream)
-                                                 : launch_gemm(GEMM_GRAD, grad, variant, stream);
+    const bool dense = a.lda == a.M && a.ldb == a.N && a.ldc == a.N;
+    const bool vec = a.N % 4 == 0 && ((reinterpret_cast<uintptr_t>(a.B) | reinterpret_cast<uintptr_t>(a.C) |
+                                       reinterpret_cast<uintptr_t>(a.V)) & 15) == 0;
+    return narrow_layer(a.M) && dense && vec;
+}
+
+template <int EPI>
+static hipError_t launch_multi_as(const MultiGradArgs &m, unsigned grid, hipStream_t stream)
+{
+    constexpr size_t lds = smem_bytes<V11, false, false>();
+    hipLaunchKernelGGL((gemm_multi_grad_kernel<V11, EPI>), dim3(grid), dim3(V11::NT), lds, stream, m);
+    return hipGetLastError();
+}
+
+// Which of the gradient products grads[0..n) (all GEMM_GRAD) launch_gemm_grads puts into its shared
+// launch: at most MG_MAX matrix-core layers and one narrow layer, all in the mode of grads[0]; none
+// when a tile shape is forced, `merge` is false or fewer than two qualify.
+void gemm_grads_plan(const GemmArgs *grads, int n, int variant, bool merge, bool *in_shared, int *merged_out)
+{
+    int wide = 0, narrow = 0;
+    for (int i = 0; i < n; ++i) in_shared[i] = false;
+    if (merge && variant < 0) {
+        for (int i = 0; i < n; ++i) {
+            if (grads[i].mode != grads[0].mode) continue;
+            if (wide < MG_MAX && multi_grad_layer_fits(grads[i])) {
+                in_shared[i] = true;
+                ++wide;
+            } else if (narrow < 1 && multi_grad_narrow_fits(grads[i])) {
+                in_shared[i] = true;
+                ++narrow;
+            }
+        }
+    }
+    if (wide + narrow < 2 || wide < 1) {
+        for (int i = 0; i < n; ++i) in_shared[i] = false;
+        wide = narrow = 0;
+    }
+    if (merged_out) *merged_out = wide + narrow;
+}
+
+// Enqueues the gradient products grads[0..n) (n <= 64): those gemm_grads_plan selects in one
+// launch, the others one by one.
+hipError_t launch_gemm_grads(const GemmArgs *grads, int n, int variant, bool merge, hipStream_t stream, int *merged_out)
+{
+    if (n < 1 || n > 64) return hipErrorInvalidValue;
+    bool taken[64];
+    int count = 0;
+    gemm_grads_plan(grads, n, variant, merge, taken, &count);
+    if (merged_out) *merged_out = count;
+    if (count >= 2) {
+        MultiGradArgs m{};
+        int narrow = -1;
+        for (int i = 0; i < n; ++i) {
+            if (!taken[i]) continue;
+            if (narrow_layer(grads[i].M)) {
+                narrow = i;
+            } else {
+                m.g[m.n] = grads[i];
+                m.g[m.n].sk = 1;
+                ++m.n;
+            }
+        }
+        long at = 0;
+        for (int p = 0; p < m.n; ++p) {
+            m.first[p] = (int)at;
+            m.tiles_m[p] = (m.g[p].M + V11::BM - 1) / V11::BM;
+            m.tiles_n[p] = (m.g[p].N + V11::BN - 1) / V11::BN;
+            at += 8 * (((long)m.tiles_m[p] * m.tiles_n[p] + 7) / 8);
+        }
+        m.first[m.n] = (int)at;
+        if (narrow >= 0) {
+            const GemmArgs &a = grads[narrow];
+            m.narrow_blocks = a.N / 4 + 1;
+            m.ng = NarrowGradArgs{a.A, a.B, a.C, a.V, a.gb, a.vb, a.K, a.M, a.N, a.mode, a.scale, a.mu};
+            at += m.narrow_blocks;
+        }
+        if (at > 0x7fffffffL) return hipErrorInvalidValue;
+        hipError_t e;
+        switch (grads[0].mode) {
+        case GRAD_STORE: e = launch_multi_as<EPI_GRAD_STORE>(m, (unsigned)at, stream); break;
+        case GRAD_SGD: e = launch_multi_as<EPI_GRAD_SGD>(m, (unsigned)at, stream); break;
+        case GRAD_SGD_KEEPV: e = launch_multi_as<EPI_GRAD_SGD_KEEPV>(m, (unsigned)at, stream); break;
+        case GRAD_MOMENTUM: e = launch_multi_as<EPI_GRAD_MOMENTUM>(m, (unsigned)at, stream); break;
+        default: e = hipErrorInvalidValue;
+        }
         if (e != hipSuccess) return e;
-        return other == GEMM_DELTA ? launch_gemm(GEMM_GRAD, grad, variant, stream) : launch_gemm(other, b, variant, stream);
     }
-    switch (grad.mode) {
-    case GRAD_STORE: return launch_pair_mode<EPI_GRAD_STORE>(other, grad, b, stream);
-    case GRAD_SGD: return launch_pair_mode<EPI_GRAD_SGD>(other, grad, b, stream);
-    case GRAD_SGD_KEEPV: return launch_pair_mode<EPI_GRAD_SGD_KEEPV>(other, grad, b, stream);
-    case GRAD_MOMENTUM: return launch_pair_mode<EPI_GRAD_MOMENTUM>(other, grad, b, stream);
-    default: return hipErrorInvalidValue;
+    for (int i = 0; i < n; ++i) {
+        if (taken[i]) continue;
+        const hipError_t e = launch_gemm(GEMM_GRAD, grads[i], variant, stream);
+        if (e != hipSuccess) return e;
     }
+    return hipSuccess;
 }
 
 hipError_t launch_gemm(GemmKind kind, const GemmArgs &a, int variant, hipStream_t stream)

@@ -61,12 +61,16 @@ constexpr int GEMM_COUNTERS = 1024;
 // Enqueue one contraction on `stream`.  Returns hipSuccess or the launch error.
 // `variant` < 0 picks a tile configuration from the shape; >= 0 forces one.
 hipError_t launch_gemm(GemmKind kind, const GemmArgs &a, int variant, hipStream_t stream);
-// Two products of one backward pass that do not depend on each other -- the weight gradient
-// `grad` (GEMM_GRAD, any mode) and `other`: a delta product through ANOTHER layer's weights, or a
-// second weight gradient in the same mode -- in one launch when their shapes suit it
-// (gemm_pair_fits), else one after the other.
-bool gemm_pair_fits(const GemmArgs &grad, GemmKind other, const GemmArgs &b, int variant);
-hipError_t launch_gemm_pair(const GemmArgs &grad, GemmKind other, const GemmArgs &b, int variant, hipStream_t stream);
+// A delta product through W_{l-1} and the gradient / update of a NARROW layer l (at most 16
+// outputs, vector units) in one launch: the two do not depend on each other.
+bool delta_narrow_grad_fits(const GemmArgs &delta, const GemmArgs &grad, int variant);
+hipError_t launch_delta_with_narrow_grad(const GemmArgs &delta, const GemmArgs &grad, hipStream_t stream);
+// The gradient / update products of several layers (GEMM_GRAD, same mode), which no longer depend
+// on one another once every delta of the backward pass exists: those whose shapes suit it share
+// one launch, the rest are launched one by one.  merged_out: products in the shared launch.
+hipError_t launch_gemm_grads(const GemmArgs *grads, int n, int variant, bool merge, hipStream_t stream, int *merged_out);
+// The selection launch_gemm_grads makes: in_shared[i] says whether product i goes into the shared launch.
+void gemm_grads_plan(const GemmArgs *grads, int n, int variant, bool merge, bool *in_shared, int *merged_out);
 int gemm_variant_count();
 const char *gemm_variant_name(int variant);
 

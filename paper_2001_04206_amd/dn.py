@@ -19,8 +19,8 @@ LIB_PATH = os.path.join(_HERE, "libdn.so")
 DN_OK, DN_ERR_INVALID_ARG, DN_ERR_SHAPE, DN_ERR_UNSUPPORTED, DN_ERR_OOM, DN_ERR_DEVICE = range(6)
 DN_ACT_LINEAR, DN_ACT_SIGMOID, DN_ACT_TANH, DN_ACT_RELU, DN_ACT_SOFTMAX = range(5)
 DN_LOSS_MSE, DN_LOSS_CROSS_ENTROPY = 0, 1
-DN_K_FORWARD, DN_K_DELTA, DN_K_GRAD_UPDATE, DN_K_OUTPUT, DN_K_ONLINE, DN_K_PAIR = range(6)
-KERNEL_CLASS_NAMES = ["forward", "delta", "grad_update", "output", "online", "pair"]
+DN_K_FORWARD, DN_K_DELTA, DN_K_GRAD_UPDATE, DN_K_OUTPUT, DN_K_ONLINE = range(5)
+KERNEL_CLASS_NAMES = ["forward", "delta", "grad_update", "output", "online"]
 
 EXPORTS = [
     "dn_status_string", "dn_net_arena_bytes", "dn_net_create", "dn_net_destroy", "dn_set_params",

@@ -141,28 +141,28 @@ def test_one_step_split_k(dnlib, widths, acts, loss, B, variant, split_k):
 
 
 PAIR_CASES = [
-    # wide enough (>= 256 tiles of 64 x 64 per weight matrix, widths multiples of 4) for two independent
-    # products of the backward pass to share a launch: gradient of layer l with the delta product through
-    # W_{l-1}, and the gradients of the two lowest layers.  Ragged against every tile size involved.
+    # weight matrices of at least 64 tiles of 64 x 64 with widths that are multiples of 4: the gradient /
+    # update products of all layers share one launch, and a narrow last layer's gradient rides with the
+    # delta product below it.  Ragged against every tile size involved.
     ([1040, 1028, 1100, 24], [TANH, RELU, SOFTMAX], CE, 40, 0.9),
     ([1028, 1092, 1032, 1040, 20], [RELU, TANH, SIG, LIN], MSE, 132, 0.0),
-    ([1024, 1024, 1024, 10], [TANH, TANH, SOFTMAX], CE, 516, 0.9),     # batch beyond the pairing limit of 512: one launch per product
-    ([1028, 1040, 1100, 12], [TANH, TANH, SOFTMAX], CE, 136, 0.9),     # narrow last layer: its gradient rides with the delta product below
+    ([1024, 1024, 1024, 10], [TANH, TANH, SOFTMAX], CE, 516, 0.9),     # batch beyond the limit of 512: one launch per product
+    ([1028, 1040, 1100, 12], [TANH, TANH, SOFTMAX], CE, 136, 0.9),     # narrow last layer: its gradient rides with the delta product below it
     ([516, 1040, 1100, 16], [RELU, SIG, SIG], MSE, 50, 0.0),           # the same with squared error and 16 outputs
 ]
 
 
 @pytest.mark.parametrize("widths,acts,loss,B,mu", PAIR_CASES)
 @pytest.mark.parametrize("pair", [1, 0])
-def test_paired_backward_launches(dnlib, widths, acts, loss, B, mu, pair):
-    announce("paired backward launches widths=%s B=%d mu=%g pair_launch=%d" % (widths, B, mu, pair))
+def test_merged_backward_launches(dnlib, widths, acts, loss, B, mu, pair):
+    announce("merged backward launches widths=%s B=%d mu=%g merge_launches=%d" % (widths, B, mu, pair))
     w = synth.make("pair", widths, acts, loss, n_samples=3 * B - 7, features="normal",
                    init="xavier_uniform", batch=B, lr=0.05, momentum=mu, seed=23)
     rng = np.random.default_rng(29)
     w.b = [rng.standard_normal(n).astype(np.float32) * 0.1 for n in widths[1:]]
     # the split API (gradients stored), then fused epochs (plain / last-step / momentum updates, short last batch)
     net, o = make_pair(dnlib, w, B)
-    net.dn_set_option("pair_launch", pair)
+    net.dn_set_option("merge_launches", pair)
     X, y = to_dev(w)
     out = torch.empty((B, widths[-1]), dtype=torch.float32, device="cuda:0")
     net.dn_forward(X[:B].contiguous(), out)

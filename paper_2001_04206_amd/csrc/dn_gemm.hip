@@ -731,10 +731,9 @@ struct MultiGradArgs {
 template <class T, int EPI>
 __global__ __launch_bounds__(T::NT, T::OCC) void gemm_multi_grad_kernel(MultiGradArgs m)
 {
-    static_assert(T::NT == 256, "the narrow gradient's workgroups have 256 threads");
     extern __shared__ __attribute__((aligned(16))) float smem[];
     const int block = (int)blockIdx.x;
-    if (block >= m.first[m.n]) {
+    if (T::NT == 256 && block >= m.first[m.n]) {   // (the narrow gradient's workgroups have 256 threads)
         narrow_grad_block<4>(m.ng, block - m.first[m.n], m.narrow_blocks);
         return;
     }
@@ -908,11 +907,16 @@ hipError_t launch_delta_with_narrow_grad(const GemmArgs &delta, const GemmArgs &
 }
 
 // ---- the gradients of several layers in one launch ---------------------------------------
-static bool multi_grad_layer_fits(const GemmArgs &a)
+// The shared launch uses one tile shape: the 64 x 64, three-per-CU gradient tile for short
+// contractions (batches up to 512), the 64 x 64 tile whose two wave groups split k for longer ones --
+// the choices pick_variant makes for large weight matrices.
+static bool long_k(const GemmArgs &a) { return a.K > 512; }
+
+static bool multi_grad_layer_fits(const GemmArgs &a, bool family_long_k)
 {
-    // shapes the 64 x 64, three-per-CU gradient tile suits: a short contraction (the batch) and a
-    // matrix of at least 64 such tiles
-    return !narrow_layer(a.M) && vec_ok(GEMM_GRAD, a) && a.K <= 512 && (long)((a.M + 63) / 64) * ((a.N + 63) / 64) >= 64;
+    // a matrix of at least 64 tiles of 64 x 64, contraction length in the family's range
+    return !narrow_layer(a.M) && vec_ok(GEMM_GRAD, a) && long_k(a) == family_long_k &&
+           (long)((a.M + 63) / 64) * ((a.N + 63) / 64) >= 64;
 }
 
 static bool multi_grad_narrow_fits(const GemmArgs &a)
@@ -923,12 +927,24 @@ static bool multi_grad_narrow_fits(const GemmArgs &a)
     return narrow_layer(a.M) && dense && vec;
 }
 
-template <int EPI>
+template <class T, int EPI>
 static hipError_t launch_multi_as(const MultiGradArgs &m, unsigned grid, hipStream_t stream)
 {
-    constexpr size_t lds = smem_bytes<V11, false, false>();
-    hipLaunchKernelGGL((gemm_multi_grad_kernel<V11, EPI>), dim3(grid), dim3(V11::NT), lds, stream, m);
+    constexpr size_t lds = smem_bytes<T, false, false>();
+    hipLaunchKernelGGL((gemm_multi_grad_kernel<T, EPI>), dim3(grid), dim3(T::NT), lds, stream, m);
     return hipGetLastError();
+}
+
+template <class T>
+static hipError_t launch_multi_mode(const MultiGradArgs &m, int mode, unsigned grid, hipStream_t stream)
+{
+    switch (mode) {
+    case GRAD_STORE: return launch_multi_as<T, EPI_GRAD_STORE>(m, grid, stream);
+    case GRAD_SGD: return launch_multi_as<T, EPI_GRAD_SGD>(m, grid, stream);
+    case GRAD_SGD_KEEPV: return launch_multi_as<T, EPI_GRAD_SGD_KEEPV>(m, grid, stream);
+    case GRAD_MOMENTUM: return launch_multi_as<T, EPI_GRAD_MOMENTUM>(m, grid, stream);
+    default: return hipErrorInvalidValue;
+    }
 }
 
 // Which of the gradient products grads[0..n) (all GEMM_GRAD) launch_gemm_grads puts into its shared
@@ -939,12 +955,13 @@ void gemm_grads_plan(const GemmArgs *grads, int n, int variant, bool merge, bool
     int wide = 0, narrow = 0;
     for (int i = 0; i < n; ++i) in_shared[i] = false;
     if (merge && variant < 0) {
+        const bool family = long_k(grads[0]);   // every layer of a backward pass contracts over the same batch
         for (int i = 0; i < n; ++i) {
             if (grads[i].mode != grads[0].mode) continue;
-            if (wide < MG_MAX && multi_grad_layer_fits(grads[i])) {
+            if (wide < MG_MAX && multi_grad_layer_fits(grads[i], family)) {
                 in_shared[i] = true;
                 ++wide;
-            } else if (narrow < 1 && multi_grad_narrow_fits(grads[i])) {
+            } else if (narrow < 1 && !family && multi_grad_narrow_fits(grads[i])) {
                 in_shared[i] = true;
                 ++narrow;
             }
@@ -979,6 +996,7 @@ hipError_t launch_gemm_grads(const GemmArgs *grads, int n, int variant, bool mer
                 ++m.n;
             }
         }
+        static_assert(V10::BM == V11::BM && V10::BN == V11::BN, "both families tile the matrices alike");
         long at = 0;
         for (int p = 0; p < m.n; ++p) {
             m.first[p] = (int)at;
@@ -994,14 +1012,8 @@ hipError_t launch_gemm_grads(const GemmArgs *grads, int n, int variant, bool mer
             at += m.narrow_blocks;
         }
         if (at > 0x7fffffffL) return hipErrorInvalidValue;
-        hipError_t e;
-        switch (grads[0].mode) {
-        case GRAD_STORE: e = launch_multi_as<EPI_GRAD_STORE>(m, (unsigned)at, stream); break;
-        case GRAD_SGD: e = launch_multi_as<EPI_GRAD_SGD>(m, (unsigned)at, stream); break;
-        case GRAD_SGD_KEEPV: e = launch_multi_as<EPI_GRAD_SGD_KEEPV>(m, (unsigned)at, stream); break;
-        case GRAD_MOMENTUM: e = launch_multi_as<EPI_GRAD_MOMENTUM>(m, (unsigned)at, stream); break;
-        default: e = hipErrorInvalidValue;
-        }
+        const hipError_t e = long_k(m.g[0]) ? launch_multi_mode<V10>(m, grads[0].mode, (unsigned)at, stream)
+                                            : launch_multi_mode<V11>(m, grads[0].mode, (unsigned)at, stream);
         if (e != hipSuccess) return e;
     }
     for (int i = 0; i < n; ++i) {

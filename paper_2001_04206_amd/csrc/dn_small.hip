@@ -329,15 +329,40 @@ __global__ __launch_bounds__(256) void narrow_output_kernel(NarrowOutArgs g)
     int label[(R + 3) / 4];
 #pragma unroll
     for (int i = 0; i < (R + 3) / 4; ++i) label[i] = g.labels[min(row0 + wave + 4 * i, g.B - 1)];
+    // the epoch's running loss sum of the row this lane will finish: read now, added to at the end
+    double sum_pre[(R + 3) / 4];
+#pragma unroll
+    for (int i = 0; i < (R + 3) / 4; ++i) {
+        const int row = row0 + wave + 4 * i;
+        sum_pre[i] = (g.loss_sums && lane == 0 && wave + 4 * i < R && row < g.B) ? g.loss_sums[row] : 0.0;
+    }
     float acc[R][kNarrow];
 #pragma unroll
     for (int r = 0; r < R; ++r)
 #pragma unroll
         for (int o = 0; o < kNarrow; ++o) acc[r][o] = 0.f;
-    for (int k = threadIdx.x * VEC; k < g.nin; k += 256 * VEC) {
+    // The thread's first piece of k stays in registers (its VEC columns of every row of W_L and of the
+    // R input rows): up to 256 * VEC inputs that is all of k, and the propagation phase at the end
+    // then needs no second trip to memory.
+    const int k_first = threadIdx.x * VEC;
+    const bool has_first = k_first < g.nin;
+    vec_t a0[R], w0[kNarrow];
+#pragma unroll
+    for (int r = 0; r < R; ++r)   // rows past the batch repeat the last row; their results are dropped
+        a0[r] = has_first ? *reinterpret_cast<const vec_t *>(g.Aprev + (size_t)min(row0 + r, g.B - 1) * g.nin + k_first) : (vec_t)0.f;
+#pragma unroll
+    for (int o = 0; o < kNarrow; ++o)
+        w0[o] = (has_first && o < g.nl) ? *reinterpret_cast<const vec_t *>(g.W + (size_t)o * g.nin + k_first) : (vec_t)0.f;
+#pragma unroll
+    for (int o = 0; o < kNarrow; ++o)
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) acc[r][o] = fmaf(a0[r][v], w0[o][v], acc[r][o]);
+    for (int k = k_first + 256 * VEC; k < g.nin; k += 256 * VEC) {
         vec_t a[R];
 #pragma unroll
-        for (int r = 0; r < R; ++r)   // rows past the batch repeat the last row; their results are dropped
+        for (int r = 0; r < R; ++r)
             a[r] = *reinterpret_cast<const vec_t *>(g.Aprev + (size_t)min(row0 + r, g.B - 1) * g.nin + k);
 #pragma unroll
         for (int o = 0; o < kNarrow; ++o) {
@@ -417,19 +442,20 @@ __global__ __launch_bounds__(256) void narrow_output_kernel(NarrowOutArgs g)
         }
         if (lane == 0) {
             g.loss_rows[row] = e;
-            if (g.loss_sums) g.loss_sums[row] += (double)e;
+            if (g.loss_sums) g.loss_sums[row] = sum_pre[i] + (double)e;
         }
     }
     if (!g.Dprev) return;
     __syncthreads();
-    for (int k = threadIdx.x * VEC; k < g.nin; k += 256 * VEC) {
+    for (int k = k_first; k < g.nin; k += 256 * VEC) {
+        const bool first = k == k_first;
         vec_t sum[R];
 #pragma unroll
         for (int r = 0; r < R; ++r) sum[r] = 0.f;
 #pragma unroll
         for (int o = 0; o < kNarrow; ++o) {
             if (o < g.nl) {
-                const vec_t w = *reinterpret_cast<const vec_t *>(g.W + (size_t)o * g.nin + k);
+                const vec_t w = first ? w0[o] : *reinterpret_cast<const vec_t *>(g.W + (size_t)o * g.nin + k);
 #pragma unroll
                 for (int r = 0; r < R; ++r) {
                     const float dv = dsh[r][o];
@@ -442,7 +468,7 @@ __global__ __launch_bounds__(256) void narrow_output_kernel(NarrowOutArgs g)
         for (int r = 0; r < R; ++r) {
             if (row0 + r < g.B) {
                 const size_t e = (size_t)(row0 + r) * g.nin + k;
-                const vec_t a = *reinterpret_cast<const vec_t *>(g.Aprev + e);
+                const vec_t a = first ? a0[r] : *reinterpret_cast<const vec_t *>(g.Aprev + e);
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) sum[r][v] *= deriv_from_output(g.act_prev, a[v]);
                 *reinterpret_cast<vec_t *>(g.Dprev + e) = sum[r];

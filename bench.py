@@ -536,9 +536,11 @@ def main():
         dtc = time.perf_counter() - tc
         cpu = {"value": n_cpu / dtc, "unit": "samples/s", "cores": dn_oracle.threads(), "kind": "oracle",
                "sample": "first %d samples (%d steps) of the same workload, %.1f s" % (n_cpu, (n_cpu + B - 1) // B, dtc)}
-        # the same checker on one thread, on a smaller sample (about an eighth of the work)
+        # the same checker on one thread, on about a sixteenth of that work: whole steps where a step
+        # is small, else the first samples as one short batch (the per-sample work is the same)
         all_threads = dn_oracle.threads()
-        n_one = min(n_cpu, int(max(B, n_cpu // 8) // B * B) or B)
+        n_one = max(1, n_cpu // 16)
+        n_one = n_one // B * B if n_one >= B else n_one
         o.set_params(w.W, w.b)
         dn_oracle.set_threads(1)
         tc = time.perf_counter()
@@ -546,7 +548,8 @@ def main():
         dt1 = time.perf_counter() - tc
         dn_oracle.set_threads(all_threads)
         cpu["value_1thread"] = n_one / dt1
-        cpu["sample_1thread"] = "first %d samples (%d steps), %.1f s" % (n_one, (n_one + B - 1) // B, dt1)
+        cpu["sample_1thread"] = ("first %d samples (%d steps), %.1f s" % (n_one, n_one // B, dt1) if n_one >= B
+                                 else "first %d samples as one short batch, %.1f s" % (n_one, dt1))
 
     out = {
         "metric": "training samples/sec (fwd+bwd+update)", "value": value, "unit": "samples/s",

@@ -360,7 +360,9 @@ bool batch_pays(const dn_net *net, int batch)
 bool deep_pays(const dn_net *net, int batch)
 {
     (void)net;
-    return batch <= 24;   // 1024-1024-1024-1024-10: 74 against 100 us/step at batch 16, 104 against 101 at batch 32
+    // 1024-1024-1024-1024-10, us/step persistent against one launch per phase: batch 4: 61 / 76,
+    // batch 8: 66 / 76, batch 16: 75 / 76, batch 24: 97 / 77
+    return batch <= 16;
 }
 
 // A whole minibatch epoch of a one- or two-layer net in persistent-kernel launches.

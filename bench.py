@@ -7,7 +7,14 @@ checker timed beside it.
 
 A step is one training step (one batch) of the chosen workload; inputs and
 parameters are resident in device memory before the timed region starts.
-Prints one JSON line.
+Protocol: W warm-up steps, then at least five timed repeats of exactly K steps,
+each from the initial parameters and bracketed by device synchronisation;
+`value` and `ms_per_step` are the median repeat, `value_min` / `value_max` the
+slowest and fastest.  One more pass over the same steps runs with every kernel
+launch bracketed by HIP events on the library's stream: the `roofline` object
+comes from those durations and from the algorithmic flop counts the library
+keeps per launch.  The CPU checker is then timed on a bounded sample of the same
+workload with all host threads and with one.  Prints one JSON line.
 """
 from __future__ import annotations
 
@@ -539,7 +546,7 @@ def main():
         # the same checker on one thread, on about a sixteenth of that work: whole steps where a step
         # is small, else the first samples as one short batch (the per-sample work is the same)
         all_threads = dn_oracle.threads()
-        n_one = max(1, n_cpu // 16)
+        n_one = n_cpu if dtc < 2.0 else max(1, n_cpu // 16)     # a sample that took under two seconds is taken whole
         n_one = n_one // B * B if n_one >= B else n_one
         o.set_params(w.W, w.b)
         dn_oracle.set_threads(1)

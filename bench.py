@@ -485,6 +485,7 @@ def main():
         net.dn_set_option("time_kernels", 0)
 
     flops, step_bytes = step_costs(w.widths, B, w.momentum)
+    schedule = net.dn_last_schedule()
     roofline = None
     classes = {}
     if not args.no_kernel_timing:
@@ -518,7 +519,7 @@ def main():
                 timed_steps = min(last_steps, classes["output"]["launches"])   # one output-error launch per step
             if total_ms > 0:
                 ach = step_bytes * timed_steps / (total_ms * 1e-3) / 1e9
-                roofline = {"bound": "hbm", "kernel": ("online_epoch_kernel" if B == 1 else "batch_epoch_kernel") if "online" in classes
+                roofline = {"bound": "hbm", "kernel": dn.SCHEDULE_KERNELS.get(schedule, "persistent kernel") if "online" in classes
                             else "all kernels of a step", "achieved": ach,
                             "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS, "traffic": None,
                             "avg_launch_us": total_ms * 1e3 / sum(c["launches"] for c in classes.values()),

@@ -339,6 +339,17 @@ typedef enum {
 } dn_kernel_class;
 
 dn_status dn_last_epoch_ms(dn_net *net, float *epoch_ms);
+/* How the last dn_train_epoch of this net ran its steps (the epoch loop of section "The Deep Netts
+ * Work-flow"): DN_SCHED_NONE before the first call. */
+enum {
+    DN_SCHED_NONE = 0,
+    DN_SCHED_LAUNCHES = 1,        /* one launch per product (or per few products) of every step */
+    DN_SCHED_PER_SAMPLE = 2,      /* batch 1: the general persistent whole-epoch kernel */
+    DN_SCHED_TWO_COPY = 3,        /* batch 1: the persistent kernel with row and column copies of the inner weights */
+    DN_SCHED_MINIBATCH = 4,       /* the persistent minibatch kernel for one- and two-layer nets */
+    DN_SCHED_MINIBATCH_DEEP = 5   /* the persistent minibatch kernel for deeper nets */
+};
+dn_status dn_last_schedule(dn_net *net, int32_t *schedule);
 dn_status dn_kernel_time(dn_net *net, int32_t kernel_class, float *ms_total, int64_t *launches);
 /* Algorithmic floating-point operations (2 x rows x columns x contraction length per product)
  * of the timed launches of one class of the last dn_train_epoch; 0 for the classes that are not
@@ -370,6 +381,10 @@ dn_status dn_kernel_flops(dn_net *net, int32_t kernel_class, double *flops);
  *                    own before the layer is spread over more workgroups (default 4096)
  *   "online_resident"  1 (default): the persistent kernel keeps its weight slices in LDS
  *                    when they fit; 0: always stream them from device memory
+ *   "online_twin"    1 (default): batch 1 with momentum 0 on a net of three to eight layers, every
+ *                    width but the last a multiple of 4, whose slices fit in LDS twice, runs on the
+ *                    persistent kernel that keeps a row copy and a column copy of the inner weights
+ *                    (no partial sums cross workgroups); 0: always the general persistent kernel
  * Unknown names or values out of range give DN_ERR_INVALID_ARG.
  */
 dn_status dn_set_option(dn_net *net, const char *name, int64_t value);

@@ -1,5 +1,6 @@
 // Host side of libdn: argument validation, arena layout, the schedule of
 // kernel launches for each entry point of include/dn.h, and launch timing.
+#include <algorithm>
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
@@ -68,7 +69,7 @@ bool compute_layout(const int32_t *widths, int32_t n_widths, int32_t max_batch, 
     lo.off_hit_rows = o; o += align_up((size_t)max_batch * sizeof(float));
     lo.off_loss_sums = o; o += align_up((size_t)max_batch * sizeof(double));
     lo.off_scalars = o; o += kAlign;
-    lo.online_bytes = online_exchange_bytes_bound(widths, L);
+    lo.online_bytes = std::max(online_exchange_bytes_bound(widths, L), twin_exchange_bytes_bound(widths, L));
     lo.off_online = o; o += align_up(lo.online_bytes);
     lo.off_gemm_ws = o; o += align_up(GEMM_WS_FLOATS * sizeof(float));
     lo.off_gemm_counters = o; o += align_up(GEMM_COUNTERS * sizeof(unsigned));
@@ -104,10 +105,12 @@ struct dn_net {
     bool w1_as_in_bwd = false;   // W_1 is still the matrix the last dn_backward propagated through
     // options
     int time_kernels = 0, gemm_variant = -1, online_mode = 0, online_min_tile = ON_DEFAULT_MIN_TILE,
-        online_resident = 1, split_k_on = 1, merge_launches = 1;
+        online_resident = 1, online_twin = 1, split_k_on = 1, merge_launches = 1;
     // persistent batch-1 kernel
     OnlineGeom geom{};
     bool online_ok = false;
+    bool twin_ready = false;   // the two-copy batch-1 kernel's LDS limit is raised
+    int last_schedule = DN_SCHED_NONE;   // how the last dn_train_epoch ran
     uint32_t online_seq = 0;   // last step number stamped into the exchange buffers
     // persistent minibatch kernel (one- and two-layer nets)
     bool batch_ok = false, deep_ok = false;
@@ -300,11 +303,61 @@ dn_status run_backward(dn_net *net, const float *X, int B, int mode, float lr, f
     return DN_OK;
 }
 
+// A whole batch-1 epoch of plain gradient descent with the two-copy kernel (same exchange region
+// and step numbering as run_online, so either may follow the other).
+dn_status run_twin(dn_net *net, const TwinGeom &g, const float *X, const int32_t *labels, int64_t n_samples, float lr,
+                   bool timing)
+{
+    const int L = net->L;
+    TwinPlan p{};
+    p.L = L;
+    for (int l = 1; l <= L; ++l) {
+        TwinLayer &y = p.layer[l];
+        y.W = net->W(l); y.b = net->b(l); y.VW = net->VW(l); y.Vb = net->Vb(l);
+        y.n_in = net->n[l - 1]; y.n_out = net->n[l]; y.act = net->act[l];
+        y.per = g.per[l]; y.P = g.P[l];
+        y.r_kshift = g.r_kshift[l]; y.r_seg = g.r_seg[l]; y.c_kshift = g.c_kshift[l]; y.c_seg = g.c_seg[l];
+        p.act_x[l] = net->exchange() + g.off_act[l];
+        p.dl_x[l] = net->exchange() + g.off_dl[l];
+        p.lds_a[l] = g.lds_a[l]; p.lds_own_a[l] = g.lds_own_a[l]; p.lds_own_d[l] = g.lds_own_d[l];
+        p.lds_b[l] = g.lds_b[l]; p.lds_r[l] = g.lds_r[l]; p.lds_c[l] = g.lds_c[l];
+    }
+    p.abort_flag = net->abort_flag();
+    p.loss_acc = net->epoch_acc();
+    p.lr = lr; p.loss = net->loss;
+    p.lds_x = g.lds_x; p.lds_d = g.lds_d; p.lds_wL = g.lds_wL; p.lds_out = g.lds_out; p.lds_kpart = g.lds_kpart;
+    const int64_t chunk = (int64_t)1 << 30;
+    for (int64_t s0 = 0; s0 < n_samples; s0 += chunk) {
+        const int64_t n = (n_samples - s0) < chunk ? (n_samples - s0) : chunk;
+        if ((uint64_t)net->online_seq + (uint64_t)n + 2 > 0xffffffffull) {   // step numbers would wrap
+            DN_HIP(hipMemsetAsync(net->exchange(), 0, net->lo.online_bytes, net->stream));
+            net->online_seq = 0;
+        }
+        p.X = X + (size_t)s0 * net->n[0];
+        p.labels = labels + s0;
+        p.n_samples = n;
+        p.keep_v = (s0 + n >= n_samples) ? 1 : 0;
+        p.seq0 = net->online_seq;
+        ScopedTimer st(net, DN_K_ONLINE, timing);
+        DN_HIP(launch_twin_epoch(g, p, net->stream));
+        net->online_seq += (uint32_t)n;
+    }
+    return DN_OK;
+}
+
 // A whole batch-1 epoch in persistent-kernel launches of at most 2^30 steps each.
 dn_status run_online(dn_net *net, const float *X, const int32_t *labels, int64_t n_samples, float lr, float mu,
                      bool timing)
 {
     const int L = net->L;
+    if (mu == 0.f && net->online_twin && net->twin_ready) {
+        // three or more layers that fit in LDS twice over: no partial sums cross workgroups
+        TwinGeom tg;
+        if (twin_geometry(net->n.data(), L, net->online_min_tile, tg) && tg.grid <= net->device_cus) {
+            net->last_schedule = DN_SCHED_TWO_COPY;
+            return run_twin(net, tg, X, labels, n_samples, lr, timing);
+        }
+    }
     OnlineGeom g;   // same slices as net->geom; LDS residency depends on whether velocities are read
     if (!online_geometry(net->n.data(), L, net->online_min_tile, mu != 0.f, g)) return DN_ERR_UNSUPPORTED;
     OnlinePlan p{};
@@ -552,6 +605,10 @@ dn_status dn_net_create(const int32_t *widths, int32_t n_widths, const dn_act *a
         net->online_ok = net->geom.grid <= net->device_cus && online_prepare() == hipSuccess;
         (void)hipGetLastError();
     }
+    if (net->device_cus > 0 && lo.online_bytes > 0) {
+        net->twin_ready = twin_exchange_bytes_bound(net->n.data(), L) > 0 && twin_prepare() == hipSuccess;
+        (void)hipGetLastError();
+    }
     if (lo.batch_bytes > 0 && net->device_cus > 0) {
         BatchGeom bg;
         net->batch_ok = batch_geometry(net->n.data(), L, max_batch, net->online_min_tile, true, bg) &&
@@ -737,14 +794,18 @@ dn_status dn_train_epoch(dn_net *net, const float *X_dev, const int32_t *labels_
     if (batch > 1 && net->batch_mode == 2 && !pbatch && !pdeep) return DN_ERR_UNSUPPORTED;
     DN_HIP(hipMemsetAsync(net->epoch_acc(), 0, sizeof(double) + sizeof(int), net->stream));
     DN_HIP(hipEventRecord(net->ev_epoch0, net->stream));
+    net->last_schedule = DN_SCHED_LAUNCHES;
     if (persistent) {
+        net->last_schedule = DN_SCHED_PER_SAMPLE;   // run_online changes it if the two-copy kernel takes the pass
         dn_status st = run_online(net, X_dev, labels_dev, n_samples, lr, momentum, timing);
         if (st != DN_OK) return st;
     } else if (pbatch) {
+        net->last_schedule = DN_SCHED_MINIBATCH;
         dn_status st = run_batch_persistent(net, X_dev, labels_dev, n_samples, batch, lr, momentum, timing);
         if (st != DN_OK) return st;
         persistent = true;
     } else if (pdeep) {
+        net->last_schedule = DN_SCHED_MINIBATCH_DEEP;
         dn_status st = run_deep_persistent(net, X_dev, labels_dev, n_samples, batch, lr, timing);
         if (st != DN_OK) return st;
         persistent = true;
@@ -902,6 +963,13 @@ dn_status dn_last_epoch_ms(dn_net *net, float *epoch_ms)
     return DN_OK;
 }
 
+dn_status dn_last_schedule(dn_net *net, int32_t *schedule)
+{
+    if (!net || !schedule) return DN_ERR_INVALID_ARG;
+    *schedule = net->last_schedule;
+    return DN_OK;
+}
+
 dn_status dn_kernel_time(dn_net *net, int32_t kernel_class, float *ms_total, int64_t *launches)
 {
     if (!net || kernel_class < 0 || kernel_class >= DN_K_CLASSES) return DN_ERR_INVALID_ARG;
@@ -950,6 +1018,9 @@ dn_status dn_set_option(dn_net *net, const char *name, int64_t value)
     } else if (!strcmp(name, "online_resident")) {
         if (value != 0 && value != 1) return DN_ERR_INVALID_ARG;
         net->online_resident = (int)value;
+    } else if (!strcmp(name, "online_twin")) {
+        if (value != 0 && value != 1) return DN_ERR_INVALID_ARG;
+        net->online_twin = (int)value;
     } else {
         return DN_ERR_INVALID_ARG;
     }

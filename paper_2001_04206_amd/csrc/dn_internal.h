@@ -258,6 +258,54 @@ size_t deep_exchange_bytes_bound(const int32_t *n, int L, int max_batch);
 hipError_t deep_prepare();
 hipError_t launch_deep_epoch(const DeepGeom &g, const DeepPlan &plan, hipStream_t stream);
 
+// ---- persistent batch-1 epoch kernel with two copies of the inner weights (dn_twin.hip) ----
+// Plain gradient descent, three or more layers, everything resident in LDS.  A workgroup owns a
+// block of units of every hidden layer and keeps their rows of W_l (forward, update) and, for
+// l >= 2, the columns of W_l that leave its units of layer l-1 (stored transposed: delta
+// propagation without partial sums over workgroups); the narrow last layer is kept whole by every
+// workgroup.  Both copies of a weight receive the same fused multiply-add from the same operands,
+// so they stay equal bit for bit.  What crosses workgroups per step: the activation vectors of
+// layers 1..L-1 and the delta vectors of layers L-1..2, one stamped word per number.
+struct TwinGeom {
+    bool ok;
+    int L, grid;
+    int per[ON_MAX_L + 1], P[ON_MAX_L + 1];            // hidden layers 1..L-1: units per workgroup, owners
+    int r_kshift[ON_MAX_L + 1], r_seg[ON_MAX_L + 1];   // own rows x a_{l-1}: segments per row (log2), segment length
+    int c_kshift[ON_MAX_L + 1], c_seg[ON_MAX_L + 1];   // own columns x delta_l, l = 2..L-1
+    size_t off_act[ON_MAX_L + 1], off_dl[ON_MAX_L + 1], words;   // exchange region, in 64-bit words
+    int lds_x, lds_a[ON_MAX_L + 1], lds_d, lds_own_a[ON_MAX_L + 1], lds_own_d[ON_MAX_L + 1], lds_b[ON_MAX_L + 1];
+    int lds_r[ON_MAX_L + 1], lds_c[ON_MAX_L + 1], lds_wL, lds_out, lds_kpart, lds_floats;
+};
+
+struct TwinLayer {
+    float *W, *b, *VW, *Vb;
+    int n_in, n_out, act, per, P, r_kshift, r_seg, c_kshift, c_seg;
+};
+
+struct TwinPlan {
+    int L;
+    TwinLayer layer[ON_MAX_L + 1];              // 1..L
+    unsigned long long *act_x[ON_MAX_L + 1];    // [2][n_l]  activations of layers 1..L-1
+    unsigned long long *dl_x[ON_MAX_L + 1];     // [2][n_l]  deltas of layers 2..L-1
+    int *abort_flag;
+    double *loss_acc;
+    const float *X;
+    const int32_t *labels;
+    int64_t n_samples;
+    float lr;
+    int loss, keep_v;
+    uint32_t seq0;
+    int lds_x, lds_a[ON_MAX_L + 1], lds_d, lds_own_a[ON_MAX_L + 1], lds_own_d[ON_MAX_L + 1], lds_b[ON_MAX_L + 1];
+    int lds_r[ON_MAX_L + 1], lds_c[ON_MAX_L + 1], lds_wL, lds_out, lds_kpart;
+};
+
+// false if the net does not suit the kernel (fewer than three layers, a width that is not a multiple
+// of 4, output layer too wide, slices beyond LDS).
+bool twin_geometry(const int32_t *n, int L, int min_tile, TwinGeom &g);
+size_t twin_exchange_bytes_bound(const int32_t *n, int L);
+hipError_t twin_prepare();
+hipError_t launch_twin_epoch(const TwinGeom &g, const TwinPlan &plan, hipStream_t stream);
+
 // Slices and buffer offsets for widths n[0..L]; false if the net does not fit the kernel
 // (too many layers, output layer too wide, LDS).  want_v: velocity slices are read every step
 // (momentum), so they must fit in LDS next to the weights for the slices to be resident.

@@ -21,12 +21,17 @@ DN_ACT_LINEAR, DN_ACT_SIGMOID, DN_ACT_TANH, DN_ACT_RELU, DN_ACT_SOFTMAX = range(
 DN_LOSS_MSE, DN_LOSS_CROSS_ENTROPY = 0, 1
 DN_K_FORWARD, DN_K_DELTA, DN_K_GRAD_UPDATE, DN_K_OUTPUT, DN_K_ONLINE = range(5)
 KERNEL_CLASS_NAMES = ["forward", "delta", "grad_update", "output", "online"]
+(DN_SCHED_NONE, DN_SCHED_LAUNCHES, DN_SCHED_PER_SAMPLE, DN_SCHED_TWO_COPY, DN_SCHED_MINIBATCH,
+ DN_SCHED_MINIBATCH_DEEP) = range(6)
+# the kernel behind each persistent schedule
+SCHEDULE_KERNELS = {DN_SCHED_PER_SAMPLE: "online_epoch_kernel", DN_SCHED_TWO_COPY: "twin_epoch_kernel",
+                    DN_SCHED_MINIBATCH: "batch_epoch_kernel", DN_SCHED_MINIBATCH_DEEP: "deep_batch_epoch_kernel"}
 
 EXPORTS = [
     "dn_status_string", "dn_net_arena_bytes", "dn_net_create", "dn_net_destroy", "dn_set_params",
     "dn_get_params", "dn_get_grads", "dn_forward", "dn_backward", "dn_update", "dn_train_epoch",
     "dn_train", "dn_evaluate", "dn_layer_backward_workspace_bytes", "dn_layer_backward_host",
-    "dn_last_epoch_ms", "dn_kernel_time", "dn_kernel_flops", "dn_set_option",
+    "dn_last_epoch_ms", "dn_last_schedule", "dn_kernel_time", "dn_kernel_flops", "dn_set_option",
     "dn_conv_forward", "dn_conv_backward_workspace_bytes", "dn_conv_backward", "dn_maxpool_forward",
     "dn_maxpool_backward", "dn_input_gradient", "dn_sgd_step",
     "dn_conv_backward_static", "dn_conv_backward_static_limit",
@@ -74,6 +79,7 @@ def lib():
         l.dn_layer_backward_host.argtypes = [vp, vp, f32, i32, i32, vp, vp, vp, vp, C.c_size_t, vp,
                                              C.POINTER(f32), C.POINTER(f32), C.POINTER(f32)]
         l.dn_last_epoch_ms.argtypes = [vp, C.POINTER(f32)]
+        l.dn_last_schedule.argtypes = [vp, C.POINTER(i32)]
         l.dn_kernel_time.argtypes = [vp, i32, C.POINTER(f32), C.POINTER(i64)]
         l.dn_kernel_flops.argtypes = [vp, i32, C.POINTER(C.c_double)]
         l.dn_set_option.argtypes = [vp, C.c_char_p, i64]
@@ -411,6 +417,11 @@ class Net:
         ms = C.c_float(0.0)
         _check(lib().dn_last_epoch_ms(self._h, C.byref(ms)), "dn_last_epoch_ms")
         return float(ms.value)
+
+    def dn_last_schedule(self) -> int:
+        v = C.c_int32(0)
+        _check(lib().dn_last_schedule(self._h, C.byref(v)), "dn_last_schedule")
+        return int(v.value)
 
     def dn_kernel_time(self, kernel_class: int) -> Tuple[float, int]:
         ms, n = C.c_float(0.0), C.c_int64(0)

@@ -91,6 +91,7 @@ def test_null_handles_are_rejected(lib):
     assert lib.dn_get_params(None, 1, None, None) == dn.DN_ERR_INVALID_ARG
     assert lib.dn_get_grads(None, 1, None, None) == dn.DN_ERR_INVALID_ARG
     assert lib.dn_last_epoch_ms(None, C.byref(f)) == dn.DN_ERR_INVALID_ARG
+    assert lib.dn_last_schedule(None, None) == dn.DN_ERR_INVALID_ARG
     assert lib.dn_kernel_time(None, 0, C.byref(f), None) == dn.DN_ERR_INVALID_ARG
     assert lib.dn_set_option(None, b"time_kernels", 1) == dn.DN_ERR_INVALID_ARG
 

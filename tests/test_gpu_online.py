@@ -25,8 +25,9 @@ def dnlib():
     return dn
 
 
-def run_pair(dn, w, n, passes, mode, min_tile=None, tol=1e-4, biases=True, resident=1):
-    """`passes` = list of momenta; one pass over the first n samples per entry."""
+def run_pair(dn, w, n, passes, mode, min_tile=None, tol=1e-4, biases=True, resident=1, twin=1, twin_expected=None):
+    """`passes` = list of momenta; one pass over the first n samples per entry.  twin=0 keeps
+    plain-gradient-descent passes of deeper nets on the general persistent kernel."""
     if biases:
         rng = np.random.default_rng(11)
         w.b = [rng.standard_normal(k).astype(np.float32) * 0.1 for k in w.widths[1:]]
@@ -36,12 +37,16 @@ def run_pair(dn, w, n, passes, mode, min_tile=None, tol=1e-4, biases=True, resid
     if min_tile is not None:
         net.dn_set_option("online_min_tile", min_tile)
     net.dn_set_option("online_resident", resident)
+    net.dn_set_option("online_twin", twin)
     o = Oracle("o32", w.widths, w.acts, w.loss)
     o.set_params(w.W, w.b)
     X = torch.from_numpy(w.X[:n]).to("cuda:0")
     y = torch.from_numpy(w.labels[:n]).to("cuda:0")
     for mu in passes:
         got = net.dn_train_epoch(X, y, 1, w.lr, mu)
+        if mode == PERSISTENT and twin_expected is not None:
+            want = dn.DN_SCHED_TWO_COPY if (twin_expected and mu == 0.0) else dn.DN_SCHED_PER_SAMPLE
+            assert net.dn_last_schedule() == want, (net.dn_last_schedule(), want)
         ref, _ = o.train_epoch(w.X[:n], w.labels[:n], 1, w.lr, mu)
         assert np.isfinite(got)
         assert abs(got - ref) <= tol * max(abs(ref), 1e-6), (got, ref)
@@ -80,7 +85,53 @@ def test_persistent_epochs_match_checker(dnlib, widths, acts, loss, min_tile, re
     w = synth.make("online", widths, acts, loss, n_samples=48, features="normal", init="xavier_uniform",
                    batch=1, lr=0.005, momentum=0.0, seed=4)
     # plain SGD pass (leaves velocity = last step's delta), then two momentum passes on top of it
-    run_pair(dnlib, w, 48, [0.0, 0.5, 0.5], PERSISTENT, min_tile, resident=resident)
+    run_pair(dnlib, w, 48, [0.0, 0.5, 0.5], PERSISTENT, min_tile, resident=resident, twin=0)
+
+
+TWIN_SHAPES = [
+    # three or more layers, every width but the last a multiple of 4, slices that fit in LDS twice
+    ([32, 64, 48, 10], [TANH, SIG, SOFTMAX], CE),
+    ([20, 40, 32, 52, 24, 6], [TANH, SIG, RELU, TANH, SOFTMAX], CE),   # five layers
+    ([64, 2048, 1024, 10], [TANH, TANH, SOFTMAX], CE),                # fits with 16-weight tiles only
+    ([16, 4100, 24, 10], [TANH, RELU, SOFTMAX], CE),                  # layers owned by different numbers of workgroups
+    ([12, 8, 4, 3], [SIG, TANH, SIG], MSE),                           # squared error, one workgroup
+    ([256, 512, 512, 7], [RELU, TANH, LIN], MSE),
+    ([1024, 1024, 1024, 1024, 10], [TANH, TANH, TANH, SOFTMAX], CE),  # the shape of the batch sweep
+]
+
+
+@pytest.mark.parametrize("widths,acts,loss", TWIN_SHAPES)
+@pytest.mark.parametrize("min_tile", [None, 16])
+def test_two_copy_persistent_epochs_match_checker(dnlib, widths, acts, loss, min_tile):
+    """Plain-gradient-descent passes run on the kernel that keeps row and column copies of the
+    inner weights; the momentum pass that follows (general kernel) starts from the velocity the
+    last plain step left, so that state is checked too; then a plain pass again."""
+    announce("online two-copy persistent widths=%s min_tile=%s" % (widths, min_tile))
+    w = synth.make("online", widths, acts, loss, n_samples=48, features="normal", init="xavier_uniform",
+                   batch=1, lr=0.005, momentum=0.0, seed=4)
+    fits = not (widths == [64, 2048, 1024, 10] and min_tile is None)   # 64-row tiles of that net exceed LDS
+    run_pair(dnlib, w, 48, [0.0, 0.0, 0.5, 0.0], PERSISTENT, min_tile, twin_expected=fits)
+
+
+def test_two_copy_and_general_kernel_agree(dnlib):
+    """The same plain pass on both persistent kernels: results within rounding of each other."""
+    announce("online two-copy against the general persistent kernel")
+    w = synth.make("online", [64, 128, 96, 10], [TANH, TANH, SOFTMAX], CE, n_samples=64, features="normal",
+                   init="xavier_uniform", batch=1, lr=0.01, momentum=0.0, seed=9)
+    outs = []
+    for twin in (1, 0):
+        net = dnlib.Net(w.widths, w.acts, w.loss, 1)
+        net.set_all(w.W, w.b)
+        net.dn_set_option("online_mode", PERSISTENT)
+        net.dn_set_option("online_twin", twin)
+        X = torch.from_numpy(w.X).to("cuda:0")
+        y = torch.from_numpy(w.labels).to("cuda:0")
+        loss = net.dn_train_epoch(X, y, 1, w.lr, 0.0)
+        outs.append((loss, net.get_all()))
+        net.close()
+    assert abs(outs[0][0] - outs[1][0]) <= 1e-5 * abs(outs[1][0])
+    for a, b in zip(outs[0][1][0] + outs[0][1][1], outs[1][1][0] + outs[1][1][1]):
+        assert_close(a, b, 1e-5, "two-copy vs general")
 
 
 @pytest.mark.parametrize("widths,acts,loss", SHAPES[:6])
@@ -150,7 +201,7 @@ def test_digits_like_online_prefix_per_phase(dnlib):
 def test_tanh_sweep_b1_prefix_persistent(dnlib):
     announce("cfg5 1024x4-10 B=1, first 2048 steps, persistent")
     w = synth.tanh_sweep(1, n_samples=2048)
-    W, b = run_pair(dnlib, w, 2048, [0.0], PERSISTENT, tol=1e-3, biases=False)
+    W, b = run_pair(dnlib, w, 2048, [0.0], PERSISTENT, tol=1e-3, biases=False, twin_expected=True)
     assert abs(float(b[-1].sum())) < 1e-4      # softmax + cross-entropy conserves the output bias sum
 
 

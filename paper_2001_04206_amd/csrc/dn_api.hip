@@ -317,6 +317,9 @@ dn_status run_twin(dn_net *net, const TwinGeom &g, const float *X, const int32_t
         y.n_in = net->n[l - 1]; y.n_out = net->n[l]; y.act = net->act[l];
         y.per = g.per[l]; y.P = g.P[l];
         y.r_kshift = g.r_kshift[l]; y.r_seg = g.r_seg[l]; y.c_kshift = g.c_kshift[l]; y.c_seg = g.c_seg[l];
+        const int stride = ON_THREADS * 4;
+        y.inv_in = 1.0f / (float)y.n_in; y.r_rs = stride / y.n_in; y.r_ks = stride % y.n_in;
+        y.inv_out = 1.0f / (float)y.n_out; y.c_rs = stride / y.n_out; y.c_ks = stride % y.n_out;
         p.act_x[l] = net->exchange() + g.off_act[l];
         p.dl_x[l] = net->exchange() + g.off_dl[l];
         p.lds_a[l] = g.lds_a[l]; p.lds_own_a[l] = g.lds_own_a[l]; p.lds_own_d[l] = g.lds_own_d[l];

@@ -280,6 +280,10 @@ struct TwinGeom {
 struct TwinLayer {
     float *W, *b, *VW, *Vb;
     int n_in, n_out, act, per, P, r_kshift, r_seg, c_kshift, c_seg;
+    // a thread walks an LDS tile of rows of n floats in strides of ON_THREADS float4s: quotient and
+    // remainder of that stride by n, and 1 / n, for tiles with rows of n_in (r_*) and n_out (c_*) floats
+    float inv_in, inv_out;
+    int r_rs, r_ks, c_rs, c_ks;
 };
 
 struct TwinPlan {

@@ -36,16 +36,22 @@
 namespace dn {
 namespace {
 
-// T[r][k] = fma(-(lr * d), a, T[r][k]) over an LDS tile of nr rows of n floats (n a multiple of 4);
-// the delta d belongs to the row (ON_ROWS: d = dv[r], a = av[k]) or to the column (d = dv[k],
-// a = av[r]).  vel (optional, device memory, rows `n` apart): receives the applied change.
+// T[r][k] = fma(-(lr * d), a, T[r][k]) over an LDS tile of nr rows of n floats (n a multiple of 4,
+// nr * n below 2^24); the delta d belongs to the row (ON_ROWS: d = dv[r], a = av[k]) or to the column
+// (d = dv[k], a = av[r]).  vel (optional, device memory, rows `n` apart): receives the applied change.
+// A thread walks the tile in steps of kThreads float4s: (row, column) advance by (rs, ks), the
+// quotient and remainder of that stride by n, which the host supplies with 1 / n.
 template <bool ON_ROWS>
 __device__ __forceinline__ void rank1_update(float *T, int n, int nr, const float *dv, const float *av, float lr,
-                                             float *vel)
+                                             float *vel, float inv_n, int rs, int ks)
 {
     const int total = nr * n;
-    for (int i = threadIdx.x * 4; i < total; i += kThreads * 4) {
-        const int r = i / n, k = i - r * n;
+    int i = threadIdx.x * 4;
+    int r = (int)((float)i * inv_n);   // off by at most one: corrected exactly
+    if (r * n > i) --r;
+    else if ((r + 1) * n <= i) ++r;
+    int k = i - r * n;
+    for (; i < total; i += kThreads * 4) {
         v4f w = *(const v4f *)(T + i);
         v4f nld, a;
         if (ON_ROWS) {
@@ -64,6 +70,9 @@ __device__ __forceinline__ void rank1_update(float *T, int n, int nr, const floa
         w.w = __builtin_fmaf(nld.w, a.w, w.w);
         *(v4f *)(T + i) = w;
         if (vel) *(v4f *)(vel + (size_t)r * n + k) = (v4f){nld.x * a.x, nld.y * a.y, nld.z * a.z, nld.w * a.w};
+        r += rs;
+        k += ks;
+        if (k >= n) { k -= n; ++r; }
     }
 }
 
@@ -112,12 +121,26 @@ __global__ __launch_bounds__(ON_THREADS) void twin_epoch_kernel(TwinPlan p)
     double loss_acc = 0.0;
     __syncthreads();
 
-    // own rows (nr of them, n long, in LDS at T) times the vector v: kpart[r * kf + segment]
-    auto rows_times = [&](const float *T, int n, int nr, int kshift, int seg, const float *v) {
+    // rows of an LDS tile T (nr of them, n long) times the vector v; fin(r, sum) finishes a row.  A
+    // row is cut into 2^kshift segments so that a few rows still occupy every wave; the segment sums
+    // meet in kpart (one barrier), and a second barrier holds the other waves back while a few threads
+    // finish the rows: waves that run ahead into the next poll spin on loads and take issue slots from
+    // the waves that still compute (measured: 14.8 -> 14.0 us per step on 1024-1024-1024-1024-10; one
+    // wave per row without any barrier: 17.2 us).
+    auto product = [&](const float *T, int n, int nr, int kshift, int seg, const float *v, auto fin) {
         if ((nr << kshift) <= kWaves) fwd_rows<4, 1>(T, n, nr, kshift, seg, v, kpart);
         else fwd_rows<4, 4>(T, n, nr, kshift, seg, v, kpart);
+        __syncthreads();
+        for (int r = tid; r < nr; r += kThreads) {
+            float sum = 0.f;
+            for (int ks = 0; ks < (1 << kshift); ++ks) sum += kpart[(r << kshift) + ks];
+            fin(r, sum);
+        }
+        __syncthreads();
     };
 
+    const int per1p = (p.layer[1].per + 3) & ~3;
+    bool pending_c2 = false;   // the column copy of W_2 still lacks the previous step's update
     constexpr int XR = 4;
     for (int64_t s = 0; s < p.n_samples; ++s) {
         const uint32_t seq = p.seq0 + 1u + (uint32_t)s;
@@ -125,6 +148,11 @@ __global__ __launch_bounds__(ON_THREADS) void twin_epoch_kernel(TwinPlan p)
         const bool keepv = p.keep_v && s == p.n_samples - 1;   // the epoch's last step also leaves the applied change as velocity
         const float *x = xa0 + (size_t)(s & 1) * n0p;
         const bool more = s + 1 < p.n_samples;
+        // layer 1's own activations alternate between two buffers: the deferred update of the
+        // column copy of W_2 (below) still needs the previous step's
+        float *a1_cur = lds + p.lds_own_a[1] + (int)(s & 1) * per1p;
+        const float *a1_prev = lds + p.lds_own_a[1] + (int)((s + 1) & 1) * per1p;
+        auto own_a = [&](int l) { return l == 1 ? a1_cur : lds + p.lds_own_a[l]; };
         float xr[XR];
         int y_next = 0;
         bool aborted = false;
@@ -144,26 +172,43 @@ __global__ __launch_bounds__(ON_THREADS) void twin_epoch_kernel(TwinPlan p)
                     if (s_abort) { aborted = true; break; }
                     xin = dst;
                 }
-                rows_times(lds + p.lds_r[l], ly.n_in, nr, ly.r_kshift, ly.r_seg, xin);
-                __syncthreads();
-                float *a_own = lds + p.lds_own_a[l];
+                float *a_own = own_a(l);
                 const float *bl = lds + p.lds_b[l];
-                for (int r = tid; r < nr; r += kThreads) {
-                    float z = bl[r];
-                    for (int ks = 0; ks < (1 << ly.r_kshift); ++ks) z += kpart[(r << ly.r_kshift) + ks];
-                    const float a = act_fn(ly.act, z);
+                u64 *pub = p.act_x[l] + (size_t)par * ly.n_out + r0;
+                const int act = ly.act;
+                product(lds + p.lds_r[l], ly.n_in, nr, ly.r_kshift, ly.r_seg, xin, [&](int r, float sum) {
+                    const float a = act_fn(act, sum + bl[r]);
                     a_own[r] = a;
-                    ll_store(p.act_x[l] + (size_t)par * ly.n_out + r0 + r, a, seq);
+                    ll_store(pub + r, a, seq);
+                });
+            }
+            if (l == 1) {
+                // work that fits the wait for the other workgroups' activations: the next sample's
+                // features are requested, and the column copy of W_2 takes the previous step's update
+                if (more) {
+                    const float *xn = p.X + (size_t)(s + 1) * n0;
+#pragma unroll
+                    for (int u = 0; u < XR; ++u) {
+                        const int k = tid + u * kThreads;
+                        xr[u] = (need_x && k < n0) ? xn[k] : 0.f;
+                    }
+                    y_next = p.labels[s + 1];
+                }
+                if (pending_c2) {
+                    const TwinLayer &l2 = p.layer[2];
+                    rank1_update<false>(lds + p.lds_c[2], l2.n_out, nr_of(1), d_full, a1_prev, p.lr, nullptr, l2.inv_out,
+                                        l2.c_rs, l2.c_ks);
+                    pending_c2 = false;
                 }
             }
-            if (l == 1 && more) {   // the next sample's features travel while this step runs
-                const float *xn = p.X + (size_t)(s + 1) * n0;
+            if (l == L - 1 && more && need_x) {   // the features requested above go to the other input buffer
+                float *xn = xa0 + (size_t)((s + 1) & 1) * n0p;
 #pragma unroll
                 for (int u = 0; u < XR; ++u) {
                     const int k = tid + u * kThreads;
-                    xr[u] = (need_x && k < n0) ? xn[k] : 0.f;
+                    if (k < n0) xn[k] = xr[u];
                 }
-                y_next = p.labels[s + 1];
+                for (int k = tid + XR * kThreads; k < n0; k += kThreads) xn[k] = p.X[(size_t)(s + 1) * n0 + k];
             }
         }
         if (aborted) break;
@@ -176,59 +221,73 @@ __global__ __launch_bounds__(ON_THREADS) void twin_epoch_kernel(TwinPlan p)
                        &s_abort);
             __syncthreads();
             if (s_abort) break;
-            for (int k = wave; k < nL; k += kWaves) {
-                const float *wr = WL + k * nLin;
-                float acc = 0.f;
+            for (int k = wave; k < nL; k += 2 * kWaves) {   // two rows of W_L per wave at a time
+                const int k2 = k + kWaves;
+                const float *wr = WL + k * nLin, *wr2 = WL + (k2 < nL ? k2 : k) * nLin;
+                float acc = 0.f, acc2 = 0.f;
                 for (int j = lane * 4; j < nLin; j += 256) {
-                    const v4f wv = *(const v4f *)(wr + j), av = *(const v4f *)(aLm1 + j);
+                    const v4f av = *(const v4f *)(aLm1 + j);
+                    const v4f wv = *(const v4f *)(wr + j), wv2 = *(const v4f *)(wr2 + j);
                     acc += wv.x * av.x + wv.y * av.y + wv.z * av.z + wv.w * av.w;
+                    acc2 += wv2.x * av.x + wv2.y * av.y + wv2.z * av.z + wv2.w * av.w;
                 }
                 acc = wave_sum(acc);
-                if (lane == 0) zL[k] = acc + bL[k];
+                acc2 = wave_sum(acc2);
+                if (lane == 0) {
+                    zL[k] = acc + bL[k];
+                    if (k2 < nL) zL[k2] = acc2 + bL[k2];
+                }
+            }
+            __syncthreads();
+            // wave 0: delta_L first (everyone waits for it); the loss and the bias update follow
+            // after the barrier, beside the other waves' work
+            int y = y_cur;
+            y = y < 0 ? 0 : (y >= nL ? nL - 1 : y);
+            const int k0 = lane, k1 = lane + 64;
+            float d0 = 0.f, d1 = 0.f, e_m = 0.f, e_sum = 1.f, f0 = 0.f, f1 = 0.f;
+            if (wave == 0) {
+                const float z0 = k0 < nL ? zL[k0] : -INFINITY, z1 = k1 < nL ? zL[k1] : -INFINITY;
+                if (p.loss == DN_LOSS_CROSS_ENTROPY) {
+                    e_m = wave_max(fmaxf(z0, z1));
+                    const float e0 = k0 < nL ? expf(z0 - e_m) : 0.f, e1 = k1 < nL ? expf(z1 - e_m) : 0.f;
+                    e_sum = wave_sum(e0 + e1);
+                    const float inv = 1.0f / e_sum;
+                    d0 = e0 * inv - (k0 == y ? 1.0f : 0.0f);
+                    d1 = e1 * inv - (k1 == y ? 1.0f : 0.0f);
+                } else {
+                    const float a0 = act_fn(last.act, z0), a1 = act_fn(last.act, z1);
+                    f0 = a0 - (k0 == y ? 1.0f : 0.0f);
+                    f1 = a1 - (k1 == y ? 1.0f : 0.0f);
+                    d0 = f0 * act_deriv(last.act, a0);
+                    d1 = f1 * act_deriv(last.act, a1);
+                }
+                if (k0 < nL) dL[k0] = d0;
+                if (k1 < nL) dL[k1] = d1;
             }
             __syncthreads();
             if (wave == 0) {
-                int y = y_cur;
-                y = y < 0 ? 0 : (y >= nL ? nL - 1 : y);
-                const int k0 = lane, k1 = lane + 64;
-                const float z0 = k0 < nL ? zL[k0] : -INFINITY, z1 = k1 < nL ? zL[k1] : -INFINITY;
-                float d0, d1, e;
-                if (p.loss == DN_LOSS_CROSS_ENTROPY) {
-                    const float m = wave_max(fmaxf(z0, z1));
-                    const float e0 = k0 < nL ? expf(z0 - m) : 0.f, e1 = k1 < nL ? expf(z1 - m) : 0.f;
-                    const float sum = wave_sum(e0 + e1);
-                    const float inv = 1.0f / sum;
-                    d0 = e0 * inv - (k0 == y ? 1.0f : 0.0f);
-                    d1 = e1 * inv - (k1 == y ? 1.0f : 0.0f);
-                    e = logf(sum) - (zL[y] - m);
-                } else {
-                    const float a0 = act_fn(last.act, z0), a1 = act_fn(last.act, z1);
-                    const float f0 = a0 - (k0 == y ? 1.0f : 0.0f), f1 = a1 - (k1 == y ? 1.0f : 0.0f);
-                    d0 = f0 * act_deriv(last.act, a0);
-                    d1 = f1 * act_deriv(last.act, a1);
-                    e = wave_sum((k0 < nL ? 0.5f * f0 * f0 : 0.f) + (k1 < nL ? 0.5f * f1 * f1 : 0.f));
+                if (w == 0) {
+                    float e;
+                    if (p.loss == DN_LOSS_CROSS_ENTROPY) e = logf(e_sum) - (zL[y] - e_m);
+                    else e = wave_sum((k0 < nL ? 0.5f * f0 * f0 : 0.f) + (k1 < nL ? 0.5f * f1 * f1 : 0.f));
+                    if (lane == 0) loss_acc += (double)e;
                 }
                 if (k0 < nL) {
-                    dL[k0] = d0;
                     bL[k0] = bL[k0] - p.lr * d0;
                     if (keepv && w == 0) last.Vb[k0] = -(p.lr * d0);
                 }
                 if (k1 < nL) {
-                    dL[k1] = d1;
                     bL[k1] = bL[k1] - p.lr * d1;
                     if (keepv && w == 0) last.Vb[k1] = -(p.lr * d1);
                 }
-                if (lane == 0) loss_acc += (double)e;
-            }
-            __syncthreads();
-            // deltas of the own units of layer L-1 through the last layer's weights before their
-            // update: sixteen lanes per unit
-            {
+            } else {
+                // deltas of the own units of layer L-1 through the last layer's weights before their
+                // update: sixteen lanes per unit, on the waves beside wave 0
                 const int c0 = r0_of(L - 1), nc = nr_of(L - 1);
-                const float *a_own = lds + p.lds_own_a[L - 1];
+                const float *a_own = own_a(L - 1);
                 float *d_own = lds + p.lds_own_d[L - 1];
                 const int actp = p.layer[L - 1].act;
-                for (int t = tid; t < nc * 16; t += kThreads) {
+                for (int t = tid - 64; t < nc * 16; t += kThreads - 64) {
                     const int j = t >> 4, g = t & 15;
                     float sacc = 0.f;
                     for (int k = g; k < nL; k += 16) sacc += WL[k * nLin + c0 + j] * dL[k];
@@ -236,12 +295,13 @@ __global__ __launch_bounds__(ON_THREADS) void twin_epoch_kernel(TwinPlan p)
                     if (g == 0) {
                         const float d = sacc * act_deriv(actp, a_own[j]);
                         d_own[j] = d;
-                        if (L - 1 >= 2) ll_store(p.dl_x[L - 1] + (size_t)par * nLin + c0 + j, d, seq);
+                        ll_store(p.dl_x[L - 1] + (size_t)par * nLin + c0 + j, d, seq);
                     }
                 }
             }
             __syncthreads();
-            rank1_update<true>(WL, nLin, nL, dL, aLm1, p.lr, (keepv && w == 0) ? last.VW : nullptr);
+            rank1_update<true>(WL, nLin, nL, dL, aLm1, p.lr, (keepv && w == 0) ? last.VW : nullptr, last.inv_in, last.r_rs,
+                               last.r_ks);
         }
 
         // ---- backward through the hidden layers ----
@@ -252,7 +312,7 @@ __global__ __launch_bounds__(ON_THREADS) void twin_epoch_kernel(TwinPlan p)
                 const float *d_own = lds + p.lds_own_d[l];
                 const float *ain = (l == 1) ? x : (lds + p.lds_a[l - 1]);
                 rank1_update<true>(lds + p.lds_r[l], ly.n_in, nr, d_own, ain, p.lr,
-                                   keepv ? ly.VW + (size_t)r0 * ly.n_in : nullptr);
+                                   keepv ? ly.VW + (size_t)r0 * ly.n_in : nullptr, ly.inv_in, ly.r_rs, ly.r_ks);
                 float *bl = lds + p.lds_b[l];
                 for (int r = tid; r < nr; r += kThreads) {
                     bl[r] = bl[r] - p.lr * d_own[r];
@@ -268,39 +328,31 @@ __global__ __launch_bounds__(ON_THREADS) void twin_epoch_kernel(TwinPlan p)
                                p.abort_flag, &s_abort);
                     __syncthreads();
                     if (s_abort) { aborted = true; break; }
-                    rows_times(lds + p.lds_c[l], ly.n_out, np, ly.c_kshift, ly.c_seg, d_full);
-                    __syncthreads();
-                    const float *a_own = lds + p.lds_own_a[l - 1];
+                    const float *a_own = own_a(l - 1);
                     float *d_prev = lds + p.lds_own_d[l - 1];
-                    for (int j = tid; j < np; j += kThreads) {
-                        float sacc = 0.f;
-                        for (int ks = 0; ks < (1 << ly.c_kshift); ++ks) sacc += kpart[(j << ly.c_kshift) + ks];
-                        const float d = sacc * act_deriv(lp.act, a_own[j]);
+                    u64 *pub = p.dl_x[l - 1] + (size_t)par * lp.n_out + c0;
+                    const int actp = lp.act;
+                    const bool publish = l - 1 >= 2;
+                    product(lds + p.lds_c[l], ly.n_out, np, ly.c_kshift, ly.c_seg, d_full, [&](int j, float sum) {
+                        const float d = sum * act_deriv(actp, a_own[j]);
                         d_prev[j] = d;
-                        if (l - 1 >= 2) ll_store(p.dl_x[l - 1] + (size_t)par * lp.n_out + c0 + j, d, seq);
+                        if (publish) ll_store(pub + j, d, seq);
+                    });
+                    if (l == 2 && more) {
+                        // nothing waits for this update before the next step's backward pass: it runs
+                        // in the next step, while layer 1's activations travel
+                        pending_c2 = true;
+                    } else {
+                        __syncthreads();
+                        rank1_update<false>(lds + p.lds_c[l], ly.n_out, np, d_full, a_own, p.lr, nullptr, ly.inv_out, ly.c_rs,
+                                            ly.c_ks);
                     }
-                    __syncthreads();
-                    rank1_update<false>(lds + p.lds_c[l], ly.n_out, np, d_full, a_own, p.lr, nullptr);
                 }
             }
             __syncthreads();
         }
         if (aborted) break;
-
-        // ---- next sample into the other input buffer ----
-        if (more) {
-            float *xn = xa0 + (size_t)((s + 1) & 1) * n0p;
-            if (need_x) {
-#pragma unroll
-                for (int u = 0; u < XR; ++u) {
-                    const int k = tid + u * kThreads;
-                    if (k < n0) xn[k] = xr[u];
-                }
-                for (int k = tid + XR * kThreads; k < n0; k += kThreads) xn[k] = p.X[(size_t)(s + 1) * n0 + k];
-            }
-            y_cur = y_next;
-        }
-        __syncthreads();
+        y_cur = y_next;
     }
 
     // ---- epilogue: row copies (and workgroup 0's last layer) back to device memory ----
@@ -366,7 +418,7 @@ bool twin_geometry(const int32_t *n, int L, int min_tile, TwinGeom &g)
     g.lds_x = (int)f; f += 2 * pad4(n[0]);
     for (int l = 1; l <= L - 1; ++l) {
         g.lds_a[l] = (int)f; f += pad4(n[l]);
-        g.lds_own_a[l] = (int)f; f += pad4(g.per[l]);
+        g.lds_own_a[l] = (int)f; f += (l == 1 ? 2 : 1) * pad4(g.per[l]);   // layer 1: two buffers, alternating steps
         g.lds_own_d[l] = (int)f; f += pad4(g.per[l]);
         g.lds_b[l] = (int)f; f += pad4(g.per[l]);
         if (l >= 2) dmax = std::max(dmax, pad4(n[l]));

@@ -81,8 +81,8 @@ const char *dn_status_string(dn_status s);
 size_t dn_net_arena_bytes(const int32_t *widths, int32_t n_widths, int32_t max_batch);
 
 /*
- * Build a network (the paper's "build the artificial neural network" step;
- * layer types and counts are the configuration parameters it lists).
+ * Build a network (the network construction step of section "The Deep Netts
+ * Work-flow"; layer types and counts are the configuration parameters it lists).
  *   widths      n_0..n_L, n_widths = L+1 >= 2, all > 0           (host)
  *   acts        L activations, one per layer                     (host)
  *   loss        loss function of the output layer
@@ -105,9 +105,9 @@ dn_status dn_net_destroy(dn_net *net);
 /*
  * Copy parameters of layer `layer` (1..L) between host and device.  W_host is
  * [n_l][n_{l-1}], b_host is [n_l]; either may be NULL to skip it.
- * dn_set_params also zeroes that layer's velocity (the paper's "initialize the
- * values of weights and biases" step is done by the caller, who passes the
- * initial values here).  dn_get_grads reads the batch-mean gradients left by
+ * dn_set_params also zeroes that layer's velocity (the weight and bias
+ * initialisation step of section "The Deep Netts Work-flow" is done by the caller,
+ * who passes the initial values here).  dn_get_grads reads the batch-mean gradients left by
  * the last dn_backward.
  */
 dn_status dn_set_params(dn_net *net, int32_t layer, const float *W_host, const float *b_host);
@@ -181,8 +181,8 @@ dn_status dn_train_epoch(dn_net *net, const float *X_dev, const int32_t *labels_
                          float *mean_loss_host);
 
 /*
- * Training run with the work-flow's stopping rule: the configuration parameters the paper
- * lists include "the maximum error that can be tolerated", and back propagation goes on
+ * Training run with the work-flow's stopping rule (section "The Deep Netts Work-flow"): a
+ * largest tolerated error is among the configuration parameters, and back propagation goes on
  * while the loss error assessment finds the network above it.  Here the rule is applied per
  * epoch: epochs of dn_train_epoch are run until an epoch's loss (as dn_train_epoch reports
  * it) is <= max_error or max_epochs epochs have run.
@@ -217,8 +217,8 @@ dn_status dn_evaluate(dn_net *net, const float *X_dev, const int32_t *labels_dev
  *     deltaWeights[o][i] = -learning_rate * gradients[o][i]
  *     deltaBiases[o]     = -learning_rate * deltas[o]
  * (the argument list is the one the paper prints for its softmax output layer: deltas, inputs,
- * gradients, deltaWeights, deltaBiases, colsOut, colsInput, learningRate; the sign is the
- * reading "the delta is what gets added to the weight").  It exists to measure that execution
+ * gradients, deltaWeights, deltaBiases, colsOut, colsInput, learningRate; the sign is read so
+ * that a delta is the quantity added to the weight).  It exists to measure that execution
  * model -- copies around every call -- next to the device-resident dn_train_epoch; the paper
  * finds the copies dominate for small data and names their removal as future work.
  *   deltas_host [cols_out], inputs_host [cols_input]                              (host, read)

@@ -109,6 +109,7 @@ struct dn_net {
     // persistent batch-1 kernel
     OnlineGeom geom{};
     bool online_ok = false;
+    bool online_prepared = false, batch_prepared = false, deep_prepared = false;   // LDS limits raised at creation
     bool twin_ready = false;   // the two-copy batch-1 kernel's LDS limit is raised
     int last_schedule = DN_SCHED_NONE;   // how the last dn_train_epoch ran
     uint32_t online_seq = 0;   // last step number stamped into the exchange buffers
@@ -159,6 +160,26 @@ namespace {
         hipError_t e_ = (expr);                        \
         if (e_ != hipSuccess) return DN_ERR_DEVICE;    \
     } while (0)
+
+// Which persistent kernels this net fits with the current tile option ("online_min_tile").
+void refresh_persistent(dn_net *net)
+{
+    const int L = net->L;
+    net->online_ok = net->batch_ok = net->deep_ok = false;
+    if (net->device_cus <= 0) return;
+    if (net->online_prepared && online_geometry(net->n.data(), L, net->online_min_tile, false, net->geom))
+        net->online_ok = net->geom.grid <= net->device_cus;
+    if (net->batch_prepared) {
+        BatchGeom bg;   // with velocities: the larger of the two LDS layouts
+        net->batch_ok = batch_geometry(net->n.data(), L, net->max_batch, net->online_min_tile, true, bg) &&
+                        bg.grid <= net->device_cus;
+    }
+    if (net->deep_prepared) {
+        DeepGeom dg;
+        net->deep_ok = deep_geometry(net->n.data(), L, net->max_batch, net->online_min_tile, dg) &&
+                       dg.grid <= net->device_cus;
+    }
+}
 
 double product_flop(const GemmArgs &g) { return 2.0 * (double)g.M * (double)g.N * (double)g.K; }
 
@@ -603,27 +624,15 @@ dn_status dn_net_create(const int32_t *widths, int32_t n_widths, const dn_act *a
             net->device_cus = 0;
         (void)hipGetLastError();
     }
-    if (net->device_cus > 0 && lo.online_bytes > 0 &&
-        online_geometry(net->n.data(), L, net->online_min_tile, false, net->geom)) {
-        net->online_ok = net->geom.grid <= net->device_cus && online_prepare() == hipSuccess;
+    if (net->device_cus > 0) {
+        // the kernels' LDS limits are raised once; whether a net fits follows the tile option
+        net->online_prepared = lo.online_bytes > 0 && online_prepare() == hipSuccess;
+        net->twin_ready = lo.online_bytes > 0 && twin_exchange_bytes_bound(net->n.data(), L) > 0 && twin_prepare() == hipSuccess;
+        net->batch_prepared = lo.batch_bytes > 0 && batch_prepare() == hipSuccess;
+        net->deep_prepared = lo.deep_bytes > 0 && deep_prepare() == hipSuccess;
         (void)hipGetLastError();
     }
-    if (net->device_cus > 0 && lo.online_bytes > 0) {
-        net->twin_ready = twin_exchange_bytes_bound(net->n.data(), L) > 0 && twin_prepare() == hipSuccess;
-        (void)hipGetLastError();
-    }
-    if (lo.batch_bytes > 0 && net->device_cus > 0) {
-        BatchGeom bg;
-        net->batch_ok = batch_geometry(net->n.data(), L, max_batch, net->online_min_tile, true, bg) &&
-                        bg.grid <= net->device_cus && batch_prepare() == hipSuccess;
-        (void)hipGetLastError();
-    }
-    if (lo.deep_bytes > 0 && net->device_cus > 0) {
-        DeepGeom dg;
-        net->deep_ok = deep_geometry(net->n.data(), L, max_batch, net->online_min_tile, dg) &&
-                       dg.grid <= net->device_cus && deep_prepare() == hipSuccess;
-        (void)hipGetLastError();
-    }
+    refresh_persistent(net);
     // parameters, velocities and gradients start at zero; exchange words start unstamped
     if (hipMemsetAsync(net->arena, 0, 3 * lo.region, net->stream) != hipSuccess ||
         hipMemsetAsync(net->arena + lo.off_scalars, 0, kAlign, net->stream) != hipSuccess ||
@@ -797,22 +806,27 @@ dn_status dn_train_epoch(dn_net *net, const float *X_dev, const int32_t *labels_
     if (batch > 1 && net->batch_mode == 2 && !pbatch && !pdeep) return DN_ERR_UNSUPPORTED;
     DN_HIP(hipMemsetAsync(net->epoch_acc(), 0, sizeof(double) + sizeof(int), net->stream));
     DN_HIP(hipEventRecord(net->ev_epoch0, net->stream));
+    // A persistent path that turns out not to fit (its geometry is recomputed for this call's momentum
+    // and the current tile option) reports DN_ERR_UNSUPPORTED before it launches anything: in automatic
+    // mode the epoch then runs with one launch per product instead.
     net->last_schedule = DN_SCHED_LAUNCHES;
     if (persistent) {
         net->last_schedule = DN_SCHED_PER_SAMPLE;   // run_online changes it if the two-copy kernel takes the pass
         dn_status st = run_online(net, X_dev, labels_dev, n_samples, lr, momentum, timing);
-        if (st != DN_OK) return st;
+        if (st == DN_ERR_UNSUPPORTED && net->online_mode == 0) persistent = false;
+        else if (st != DN_OK) return st;
     } else if (pbatch) {
         net->last_schedule = DN_SCHED_MINIBATCH;
         dn_status st = run_batch_persistent(net, X_dev, labels_dev, n_samples, batch, lr, momentum, timing);
-        if (st != DN_OK) return st;
-        persistent = true;
+        if (st == DN_OK) persistent = true;
+        else if (st != DN_ERR_UNSUPPORTED || net->batch_mode != 0) return st;
     } else if (pdeep) {
         net->last_schedule = DN_SCHED_MINIBATCH_DEEP;
         dn_status st = run_deep_persistent(net, X_dev, labels_dev, n_samples, batch, lr, timing);
-        if (st != DN_OK) return st;
-        persistent = true;
+        if (st == DN_OK) persistent = true;
+        else if (st != DN_ERR_UNSUPPORTED || net->batch_mode != 0) return st;
     }
+    if (!persistent) net->last_schedule = DN_SCHED_LAUNCHES;
     // Launch-per-product path.  The epoch's loss is kept as one running sum per batch row, added
     // to by the output kernel of each step, and reduced once after the last step.
     const int rows_used = (int)(n_samples < batch ? n_samples : batch);
@@ -1006,9 +1020,8 @@ dn_status dn_set_option(dn_net *net, const char *name, int64_t value)
         if (!online_geometry(net->n.data(), net->L, (int)value, false, g) || g.grid > net->device_cus)
             return DN_ERR_INVALID_ARG;
         if (hipStreamSynchronize(net->stream) != hipSuccess) return DN_ERR_DEVICE;
-        net->geom = g;
         net->online_min_tile = (int)value;
-        net->online_ok = true;
+        refresh_persistent(net);   // the minibatch kernels cut their slices by the same option
     } else if (!strcmp(name, "batch_mode")) {
         if (value < 0 || value > 2) return DN_ERR_INVALID_ARG;
         net->batch_mode = (int)value;

@@ -6,6 +6,7 @@
 // layers wide enough for 32 x 32 tiles run their forward product and input gradient on the matrix
 // cores (corr_mfma_kernel), with square filters of odd edge the filter gradient too (conv_dw_mfma_kernel);
 // everything else uses register-tiled vector kernels.
+#include <atomic>
 #include <mutex>
 
 #include "dn_internal.h"
@@ -408,12 +409,14 @@ hipError_t launch_corr_mfma_as(const CorrShape &s, const float *In, const float 
     const int taps = s.KH * s.KW;
     const size_t lds = sizeof(float) * ((size_t)MC_IC * taps * MC_WSTRIDE +
                                         (size_t)MC_IC * (rows + s.KH - 1) * (TW + s.KW - 1));
-    static bool attr_set = false;   // 7 x 7 filters need up to 146 KB, more than the default limit of dynamic LDS
-    if (!attr_set) {
+    // 7 x 7 filters need up to 146 KB, more than the default limit of dynamic LDS (the calls are stateless and
+    // may come from several threads: setting the limit twice is harmless, the flag is read and written atomically)
+    static std::atomic<bool> attr_set{false};
+    if (!attr_set.load(std::memory_order_acquire)) {
         const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&corr_mfma_kernel<OT, RW, KS, TW>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
         if (e != hipSuccess) return e;
-        attr_set = true;
+        attr_set.store(true, std::memory_order_release);
     }
     const dim3 grid((unsigned)(((s.Ho + rows - 1) / rows) * ((s.Wo + TW - 1) / TW)),
                     (unsigned)((s.Cout + 32 * OT - 1) / (32 * OT)), (unsigned)s.B);

@@ -288,6 +288,35 @@ def test_persistent_minibatch_epochs_match_checker(dnlib, widths, acts, loss, B,
     net.close()
 
 
+def test_tile_option_refits_the_minibatch_kernel(dnlib):
+    """Slices as large as "online_min_tile" asks for can exceed LDS: the automatic choice then runs
+    the epoch with one launch per product (same result) instead of failing, and a forced
+    persistent kernel is refused."""
+    announce("persistent minibatch: tile option beyond LDS falls back to launches")
+    w = synth.make("batch", [2048, 64, 10], [TANH, SOFTMAX], CE, n_samples=40, features="normal",
+                   init="xavier_uniform", batch=8, lr=0.05, momentum=0.9, seed=5)
+    X = torch.from_numpy(w.X).to("cuda:0")
+    y = torch.from_numpy(w.labels).to("cuda:0")
+    outs = []
+    for tile in (None, 1 << 22):
+        net = dnlib.Net(w.widths, w.acts, w.loss, 8)
+        net.set_all(w.W, w.b)
+        if tile is not None:
+            net.dn_set_option("online_min_tile", tile)
+        loss = net.dn_train_epoch(X, y, 8, w.lr, w.momentum)
+        assert net.dn_last_schedule() == (dnlib.DN_SCHED_MINIBATCH if tile is None else dnlib.DN_SCHED_LAUNCHES)
+        outs.append((loss, net.get_all()))
+        if tile is not None:
+            net.dn_set_option("batch_mode", 2)
+            with pytest.raises(dnlib.DnError) as e:
+                net.dn_train_epoch(X, y, 8, w.lr, w.momentum)
+            assert e.value.status == dnlib.DN_ERR_UNSUPPORTED
+        net.close()
+    assert abs(outs[0][0] - outs[1][0]) <= 1e-5 * abs(outs[1][0])
+    for a, b in zip(outs[0][1][0] + outs[0][1][1], outs[1][1][0] + outs[1][1][1]):
+        assert_close(a, b, 1e-5, "persistent minibatch vs launches")
+
+
 def test_persistent_minibatch_refused_for_three_layers(dnlib):
     announce("persistent minibatch refused for a three-layer net")
     w = synth.make("pbatch", [8, 12, 9, 4], [TANH, TANH, SOFTMAX], CE, n_samples=8, features="normal",

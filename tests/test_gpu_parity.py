@@ -237,19 +237,43 @@ def test_epoch_narrow_layers(dnlib, widths, acts, loss, batch, n, momentum):
     net.close()
 
 
+def _epoch_params(dnlib, w, split_k):
+    net = dnlib.Net(w.widths, w.acts, w.loss, w.batch)
+    net.set_all(w.W, w.b)
+    net.dn_set_option("split_k", split_k)
+    net.dn_set_option("batch_mode", 1)          # one launch per product: the path that splits k
+    X, y = to_dev(w)
+    loss = net.dn_train_epoch(X, y, w.batch, w.lr, w.momentum)
+    W, b = net.get_all()
+    net.close()
+    return loss, W + b
+
+
 def test_split_k_is_bitwise_reproducible(dnlib):
     announce("determinism: k split across workgroups, two runs")
     w = synth.tanh_sweep(32, n_samples=256)
-    outs = []
-    for _ in range(2):
-        net = dnlib.Net(w.widths, w.acts, w.loss, w.batch)
-        net.set_all(w.W, w.b)
-        X, y = to_dev(w)
-        net.dn_train_epoch(X, y, w.batch, w.lr, w.momentum)
-        outs.append(net.get_all())
-        net.close()
-    for a, b in zip(outs[0][0] + outs[0][1], outs[1][0] + outs[1][1]):
-        assert np.array_equal(a, b)
+    a, b = _epoch_params(dnlib, w, 1), _epoch_params(dnlib, w, 1)
+    assert a[0] == b[0]
+    for x, y in zip(a[1], b[1]):
+        assert np.array_equal(x, y)
+
+
+@pytest.mark.parametrize("widths,acts,loss,B", SPLIT_K_CASES)
+def test_split_k_order_is_fixed(dnlib, widths, acts, loss, B):
+    """The partial tiles of a k split are added in split order by whichever workgroup arrives last,
+    so two epochs with the split give the same bits whatever the arrival order was; the same epoch
+    without the split adds the same terms in another order and agrees to rounding."""
+    announce("determinism: k split, widths=%s B=%d, two runs and against no split" % (widths, B))
+    w = synth.make("splitk", widths, acts, loss, n_samples=6 * B + 3, features="normal",
+                   init="xavier_uniform", batch=B, lr=0.002, momentum=0.5, seed=7)
+    a, b, c = _epoch_params(dnlib, w, 1), _epoch_params(dnlib, w, 1), _epoch_params(dnlib, w, 0)
+    assert np.isfinite(a[0]) and all(np.all(np.isfinite(x)) for x in a[1])
+    assert a[0] == b[0]
+    for x, y in zip(a[1], b[1]):
+        assert np.array_equal(x, y)
+    assert abs(a[0] - c[0]) <= 1e-5 * abs(c[0])
+    for x, y in zip(a[1], c[1]):
+        assert_close(x, y, 1e-5, "k split against no split")
 
 
 # --------------------------------------------------- the five named workloads ----

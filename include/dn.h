@@ -381,10 +381,11 @@ dn_status dn_kernel_flops(dn_net *net, int32_t kernel_class, double *flops);
  *                    own before the layer is spread over more workgroups (default 4096)
  *   "online_resident"  1 (default): the persistent kernel keeps its weight slices in LDS
  *                    when they fit; 0: always stream them from device memory
- *   "online_twin"    1 (default): batch 1 with momentum 0 on a net of three to eight layers, every
- *                    width but the last a multiple of 4, whose slices fit in LDS twice, runs on the
- *                    persistent kernel that keeps a row copy and a column copy of the inner weights
- *                    (no partial sums cross workgroups); 0: always the general persistent kernel
+ *   "online_twin"    1 (default): batch 1 with momentum 0 on a net of two to eight layers, every
+ *                    width but the last a multiple of 4, whose slices fit in LDS (the inner layers'
+ *                    twice, the last layer whole), runs on the persistent kernel that keeps a row copy
+ *                    and a column copy of the inner weights and repeats the last layer in every
+ *                    workgroup (no partial sums cross workgroups); 0: always the general persistent kernel
  * Unknown names or values out of range give DN_ERR_INVALID_ARG.
  */
 dn_status dn_set_option(dn_net *net, const char *name, int64_t value);

@@ -375,7 +375,7 @@ dn_status run_online(dn_net *net, const float *X, const int32_t *labels, int64_t
 {
     const int L = net->L;
     if (mu == 0.f && net->online_twin && net->twin_ready) {
-        // three or more layers that fit in LDS twice over: no partial sums cross workgroups
+        // slices that fit in LDS with a second copy of the inner layers: no partial sums cross workgroups
         TwinGeom tg;
         if (twin_geometry(net->n.data(), L, net->online_min_tile, tg) && tg.grid <= net->device_cus) {
             net->last_schedule = DN_SCHED_TWO_COPY;

@@ -259,7 +259,7 @@ hipError_t deep_prepare();
 hipError_t launch_deep_epoch(const DeepGeom &g, const DeepPlan &plan, hipStream_t stream);
 
 // ---- persistent batch-1 epoch kernel with two copies of the inner weights (dn_twin.hip) ----
-// Plain gradient descent, three or more layers, everything resident in LDS.  A workgroup owns a
+// Plain gradient descent, two or more layers, everything resident in LDS.  A workgroup owns a
 // block of units of every hidden layer and keeps their rows of W_l (forward, update) and, for
 // l >= 2, the columns of W_l that leave its units of layer l-1 (stored transposed: delta
 // propagation without partial sums over workgroups); the narrow last layer is kept whole by every
@@ -303,7 +303,7 @@ struct TwinPlan {
     int lds_r[ON_MAX_L + 1], lds_c[ON_MAX_L + 1], lds_wL, lds_out, lds_kpart;
 };
 
-// false if the net does not suit the kernel (fewer than three layers, a width that is not a multiple
+// false if the net does not suit the kernel (fewer than two layers, a width that is not a multiple
 // of 4, output layer too wide, slices beyond LDS).
 bool twin_geometry(const int32_t *n, int L, int min_tile, TwinGeom &g);
 size_t twin_exchange_bytes_bound(const int32_t *n, int L);

@@ -1,5 +1,5 @@
-// Per-sample (batch 1) training of nets with three or more layers, plain gradient descent, as ONE
-// persistent kernel per epoch with every weight resident in LDS -- twice.
+// Per-sample (batch 1) training of nets with two or more layers, plain gradient descent, as ONE
+// persistent kernel per epoch with every weight resident in LDS -- the inner ones twice.
 //
 // The general per-sample kernel (dn_online.hip) keeps one copy of each weight (the rows of W_l
 // with the workgroup that owns the layer's units), so propagating a delta through W_l gives every
@@ -144,6 +144,19 @@ __global__ __launch_bounds__(ON_THREADS) void twin_epoch_kernel(TwinPlan p)
         __syncthreads();
     };
 
+    // Takes in a whole exchange vector (n words at src) into dst.  A net that one workgroup owns
+    // alone has nobody to wait for: its own values (own[0..n)) are copied instead.
+    const bool single = gridDim.x == 1;
+    auto take_in = [&](const u64 *src, int n, float *dst, const float *own, uint32_t seq) {
+        if (single) {
+            for (int q = tid; q < n; q += kThreads) dst[q] = own[q];
+        } else {
+            poll_words(n, seq, [&](int q) { return src + (size_t)q * kWordStride; }, [&](int q, float v) { dst[q] = v; },
+                       p.abort_flag, &s_abort);
+        }
+        __syncthreads();
+    };
+
     const int per1p = (p.layer[1].per + 3) & ~3;
     bool pending_c2 = false;   // the column copy of W_2 still lacks the previous step's update
     constexpr int XR = 4;
@@ -171,9 +184,7 @@ __global__ __launch_bounds__(ON_THREADS) void twin_epoch_kernel(TwinPlan p)
                 if (l > 1) {
                     float *dst = lds + p.lds_a[l - 1];
                     const u64 *src = p.act_x[l - 1] + (size_t)par * ly.n_in * kWordStride;
-                    poll_words(ly.n_in, seq, [&](int q) { return src + (size_t)q * kWordStride; }, [&](int q, float v) { dst[q] = v; },
-                               p.abort_flag, &s_abort);
-                    __syncthreads();
+                    take_in(src, ly.n_in, dst, own_a(l - 1), seq);
                     if (s_abort) { aborted = true; break; }
                     xin = dst;
                 }
@@ -184,7 +195,7 @@ __global__ __launch_bounds__(ON_THREADS) void twin_epoch_kernel(TwinPlan p)
                 product(lds + p.lds_r[l], ly.n_in, nr, ly.r_kshift, ly.r_seg, xin, [&](int r, float sum) {
                     const float a = act_fn(act, sum + bl[r]);
                     a_own[r] = a;
-                    ll_store(pub + (size_t)r * kWordStride, a, seq);
+                    if (!single) ll_store(pub + (size_t)r * kWordStride, a, seq);
                 });
             }
             if (l == 1) {
@@ -222,9 +233,7 @@ __global__ __launch_bounds__(ON_THREADS) void twin_epoch_kernel(TwinPlan p)
         {
             float *aLm1 = lds + p.lds_a[L - 1];
             const u64 *src = p.act_x[L - 1] + (size_t)par * nLin * kWordStride;
-            poll_words(nLin, seq, [&](int q) { return src + (size_t)q * kWordStride; }, [&](int q, float v) { aLm1[q] = v; }, p.abort_flag,
-                       &s_abort);
-            __syncthreads();
+            take_in(src, nLin, aLm1, own_a(L - 1), seq);
             if (s_abort) break;
             for (int k = wave; k < nL; k += 2 * kWaves) {   // two rows of W_L per wave at a time
                 const int k2 = k + kWaves;
@@ -300,7 +309,7 @@ __global__ __launch_bounds__(ON_THREADS) void twin_epoch_kernel(TwinPlan p)
                     if (g == 0) {
                         const float d = sacc * act_deriv(actp, a_own[j]);
                         d_own[j] = d;
-                        ll_store(p.dl_x[L - 1] + ((size_t)par * nLin + c0 + j) * kWordStride, d, seq);
+                        if (L >= 3 && !single) ll_store(p.dl_x[L - 1] + ((size_t)par * nLin + c0 + j) * kWordStride, d, seq);
                     }
                 }
             }
@@ -329,15 +338,13 @@ __global__ __launch_bounds__(ON_THREADS) void twin_epoch_kernel(TwinPlan p)
                 const int c0 = r0_of(l - 1), np = nr_of(l - 1);
                 if (np > 0) {   // deltas of the own units of layer l-1, then the column copy's update
                     const u64 *src = p.dl_x[l] + (size_t)par * ly.n_out * kWordStride;
-                    poll_words(ly.n_out, seq, [&](int q) { return src + (size_t)q * kWordStride; }, [&](int q, float v) { d_full[q] = v; },
-                               p.abort_flag, &s_abort);
-                    __syncthreads();
+                    take_in(src, ly.n_out, d_full, lds + p.lds_own_d[l], seq);
                     if (s_abort) { aborted = true; break; }
                     const float *a_own = own_a(l - 1);
                     float *d_prev = lds + p.lds_own_d[l - 1];
                     u64 *pub = p.dl_x[l - 1] + ((size_t)par * lp.n_out + c0) * kWordStride;
                     const int actp = lp.act;
-                    const bool publish = l - 1 >= 2;
+                    const bool publish = l - 1 >= 2 && !single;
                     product(lds + p.lds_c[l], ly.n_out, np, ly.c_kshift, ly.c_seg, d_full, [&](int j, float sum) {
                         const float d = sum * act_deriv(actp, a_own[j]);
                         d_prev[j] = d;
@@ -383,7 +390,7 @@ __global__ __launch_bounds__(ON_THREADS) void twin_epoch_kernel(TwinPlan p)
 bool twin_geometry(const int32_t *n, int L, int min_tile, TwinGeom &g)
 {
     g = TwinGeom{};
-    if (L < 3 || L > ON_MAX_L) return false;
+    if (L < 2 || L > ON_MAX_L) return false;
     if (n[L] > ON_MAX_NL) return false;
     for (int l = 0; l < L; ++l)
         if (n[l] % 4 != 0) return false;     // LDS rows are read and written as float4
@@ -444,7 +451,7 @@ bool twin_geometry(const int32_t *n, int L, int min_tile, TwinGeom &g)
 
 size_t twin_exchange_bytes_bound(const int32_t *n, int L)
 {
-    if (L < 3 || L > ON_MAX_L || n[L] > ON_MAX_NL) return 0;
+    if (L < 2 || L > ON_MAX_L || n[L] > ON_MAX_NL) return 0;
     size_t words = 0;
     for (int l = 1; l <= L - 1; ++l) words += 4 * (size_t)n[l] * kWordStride;
     const size_t bytes = words * sizeof(u64);

@@ -89,7 +89,10 @@ def test_persistent_epochs_match_checker(dnlib, widths, acts, loss, min_tile, re
 
 
 TWIN_SHAPES = [
-    # three or more layers, every width but the last a multiple of 4, slices that fit in LDS twice
+    # two or more layers, every width but the last a multiple of 4, slices that fit in LDS twice
+    ([784, 128, 10], [RELU, SOFTMAX], CE),                            # two layers: one exchange per step
+    ([4, 16, 3], [SIG, SIG], MSE),                                    # one workgroup owns the whole net
+    ([340, 3000, 10], [TANH, SOFTMAX], CE),
     ([32, 64, 48, 10], [TANH, SIG, SOFTMAX], CE),
     ([20, 40, 32, 52, 24, 6], [TANH, SIG, RELU, TANH, SOFTMAX], CE),   # five layers
     ([64, 2048, 1024, 10], [TANH, TANH, SOFTMAX], CE),                # fits with 16-weight tiles only

@@ -347,7 +347,8 @@ enum {
     DN_SCHED_PER_SAMPLE = 2,      /* batch 1: the general persistent whole-epoch kernel */
     DN_SCHED_TWO_COPY = 3,        /* batch 1: the persistent kernel with row and column copies of the inner weights */
     DN_SCHED_MINIBATCH = 4,       /* the persistent minibatch kernel for one- and two-layer nets */
-    DN_SCHED_MINIBATCH_DEEP = 5   /* the persistent minibatch kernel for deeper nets */
+    DN_SCHED_MINIBATCH_DEEP = 5,  /* the persistent minibatch kernel for deeper nets */
+    DN_SCHED_ONE_WAVE = 6         /* batch 1, every layer at most 64 wide: one wavefront runs the epoch */
 };
 dn_status dn_last_schedule(dn_net *net, int32_t *schedule);
 dn_status dn_kernel_time(dn_net *net, int32_t kernel_class, float *ms_total, int64_t *launches);
@@ -386,6 +387,9 @@ dn_status dn_kernel_flops(dn_net *net, int32_t kernel_class, double *flops);
  *                    twice, the last layer whole), runs on the persistent kernel that keeps a row copy
  *                    and a column copy of the inner weights and repeats the last layer in every
  *                    workgroup (no partial sums cross workgroups); 0: always the general persistent kernel
+ *   "online_tiny"    1 (default): batch 1 on a net whose layers are all at most 64 wide (and whose
+ *                    parameters fit in LDS, twice with momentum) runs on a single wavefront that keeps
+ *                    the whole net in LDS; 0: such nets take the other batch-1 schedules
  * Unknown names or values out of range give DN_ERR_INVALID_ARG.
  */
 dn_status dn_set_option(dn_net *net, const char *name, int64_t value);

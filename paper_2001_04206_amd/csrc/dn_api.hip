@@ -105,12 +105,13 @@ struct dn_net {
     bool w1_as_in_bwd = false;   // W_1 is still the matrix the last dn_backward propagated through
     // options
     int time_kernels = 0, gemm_variant = -1, online_mode = 0, online_min_tile = ON_DEFAULT_MIN_TILE,
-        online_resident = 1, online_twin = 1, split_k_on = 1, merge_launches = 1;
+        online_resident = 1, online_twin = 1, online_tiny = 1, split_k_on = 1, merge_launches = 1;
     // persistent batch-1 kernel
     OnlineGeom geom{};
     bool online_ok = false;
     bool online_prepared = false, batch_prepared = false, deep_prepared = false;   // LDS limits raised at creation
     bool twin_ready = false;   // the two-copy batch-1 kernel's LDS limit is raised
+    bool tiny_ready = false;   // the one-wave batch-1 kernel's LDS limit is raised
     int last_schedule = DN_SCHED_NONE;   // how the last dn_train_epoch ran
     uint32_t online_seq = 0;   // last step number stamped into the exchange buffers
     // persistent minibatch kernel (one- and two-layer nets)
@@ -324,6 +325,23 @@ dn_status run_backward(dn_net *net, const float *X, int B, int mode, float lr, f
     return DN_OK;
 }
 
+// A whole batch-1 epoch of a very small net on one wavefront.
+dn_status run_tiny(dn_net *net, TinyPlan &p, const float *X, const int32_t *labels, int64_t n_samples, float lr, float mu,
+                   bool timing)
+{
+    for (int l = 1; l <= net->L; ++l) {
+        TinyLayer &y = p.layer[l];
+        y.W = net->W(l); y.b = net->b(l); y.VW = net->VW(l); y.Vb = net->Vb(l);
+        y.act = net->act[l];
+    }
+    p.loss_acc = net->epoch_acc();
+    p.X = X; p.labels = labels; p.n_samples = n_samples;
+    p.lr = lr; p.mu = mu; p.loss = net->loss; p.keep_v = 1;
+    ScopedTimer st(net, DN_K_ONLINE, timing);
+    DN_HIP(launch_tiny_epoch(p, net->stream));
+    return DN_OK;
+}
+
 // A whole batch-1 epoch of plain gradient descent with the two-copy kernel (same exchange region
 // and step numbering as run_online, so either may follow the other).
 dn_status run_twin(dn_net *net, const TwinGeom &g, const float *X, const int32_t *labels, int64_t n_samples, float lr,
@@ -374,6 +392,13 @@ dn_status run_online(dn_net *net, const float *X, const int32_t *labels, int64_t
                      bool timing)
 {
     const int L = net->L;
+    if (net->online_tiny && net->tiny_ready) {
+        TinyPlan tp;   // every layer at most 64 wide: one wavefront runs the epoch
+        if (tiny_plan(net->n.data(), L, mu != 0.f, tp)) {
+            net->last_schedule = DN_SCHED_ONE_WAVE;
+            return run_tiny(net, tp, X, labels, n_samples, lr, mu, timing);
+        }
+    }
     if (mu == 0.f && net->online_twin && net->twin_ready) {
         // slices that fit in LDS with a second copy of the inner layers: no partial sums cross workgroups
         TwinGeom tg;
@@ -628,6 +653,7 @@ dn_status dn_net_create(const int32_t *widths, int32_t n_widths, const dn_act *a
         // the kernels' LDS limits are raised once; whether a net fits follows the tile option
         net->online_prepared = lo.online_bytes > 0 && online_prepare() == hipSuccess;
         net->twin_ready = lo.online_bytes > 0 && twin_exchange_bytes_bound(net->n.data(), L) > 0 && twin_prepare() == hipSuccess;
+        net->tiny_ready = tiny_prepare() == hipSuccess;
         net->batch_prepared = lo.batch_bytes > 0 && batch_prepare() == hipSuccess;
         net->deep_prepared = lo.deep_bytes > 0 && deep_prepare() == hipSuccess;
         (void)hipGetLastError();
@@ -1034,6 +1060,9 @@ dn_status dn_set_option(dn_net *net, const char *name, int64_t value)
     } else if (!strcmp(name, "online_resident")) {
         if (value != 0 && value != 1) return DN_ERR_INVALID_ARG;
         net->online_resident = (int)value;
+    } else if (!strcmp(name, "online_tiny")) {
+        if (value != 0 && value != 1) return DN_ERR_INVALID_ARG;
+        net->online_tiny = (int)value;
     } else if (!strcmp(name, "online_twin")) {
         if (value != 0 && value != 1) return DN_ERR_INVALID_ARG;
         net->online_twin = (int)value;

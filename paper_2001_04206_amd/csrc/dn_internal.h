@@ -310,6 +310,35 @@ size_t twin_exchange_bytes_bound(const int32_t *n, int L);
 hipError_t twin_prepare();
 hipError_t launch_twin_epoch(const TwinGeom &g, const TwinPlan &plan, hipStream_t stream);
 
+// ---- batch-1 epochs of very small nets on one wavefront (dn_tiny.hip) ----
+// Every width at most 64: lane j is unit j of each layer; parameters, activations and deltas in LDS.
+struct TinyLayer {
+    float *W, *b, *VW, *Vb;
+    int n_in, n_out, act;
+    int pitch;                    // floats between rows of W_l in LDS (odd)
+    int rs, ks;                   // quotient and remainder of 64 by n_in
+    int lds_w, lds_v, lds_b, lds_vb;
+};
+
+struct TinyPlan {
+    int L;
+    TinyLayer layer[ON_MAX_L + 1];                   // 1..L
+    int lds_act[ON_MAX_L + 1], lds_dl[ON_MAX_L + 1]; // activations (0: the features, two buffers) and deltas
+    double *loss_acc;
+    const float *X;
+    const int32_t *labels;
+    int64_t n_samples;
+    float lr, mu;
+    int loss, keep_v;
+    int lds_floats;
+};
+
+// Fills the shape-dependent fields; false if a layer is wider than 64 or the parameters (with their
+// velocities if want_v) exceed LDS.
+bool tiny_plan(const int32_t *n, int L, bool want_v, TinyPlan &p);
+hipError_t tiny_prepare();
+hipError_t launch_tiny_epoch(const TinyPlan &plan, hipStream_t stream);
+
 // Slices and buffer offsets for widths n[0..L]; false if the net does not fit the kernel
 // (too many layers, output layer too wide, LDS).  want_v: velocity slices are read every step
 // (momentum), so they must fit in LDS next to the weights for the slices to be resident.

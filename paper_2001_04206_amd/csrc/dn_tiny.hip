@@ -1,0 +1,243 @@
+// Per-sample (batch 1) training of very small nets -- every layer at most 64 units wide -- as one
+// wavefront that runs the whole epoch.
+//
+// A net like 4-16-3 has a few hundred weights: spread over workgroups, or even over the waves of one
+// workgroup, a training step is nothing but barriers and exchanges.  Here lane j of a single wave is
+// unit j of every layer.  Weights, biases, (with momentum) their velocities, the activations and the
+// deltas of one sample live in LDS; a step is the textbook sequence -- feed forward, output error and
+// loss, deltas through the weights from before the update, rank-1 update of every layer -- with no
+// waiting on anybody.  Weight rows sit an odd number of floats apart, so the lanes of a forward
+// product (one row each, same column) and of a delta product (same row, one column each) touch
+// different LDS banks.  The next sample's features are requested a step ahead.
+#include <algorithm>
+
+#include "dn_internal.h"
+#include "dn_persist.h"
+#include "dn_wave.h"
+
+namespace dn {
+namespace {
+
+// L is a template parameter so that the layer loops unroll and every layer's shape and LDS offsets
+// stay in scalar registers for the whole epoch (read from the argument block each time, they cost a
+// scalar-memory round trip per use, several per layer and step).
+template <int L>
+__global__ __launch_bounds__(64) void tiny_epoch_kernel(TinyPlan p)
+{
+    extern __shared__ __align__(16) float lds[];
+    const int lane = threadIdx.x;
+    const int n0 = p.layer[1].n_in, nL = p.layer[L].n_out;
+    const bool with_v = p.mu != 0.f;
+
+    // ---- prologue: parameters (and velocities, if they are read) into LDS ----
+#pragma unroll
+    for (int l = 1; l <= L; ++l) {
+        const TinyLayer &ly = p.layer[l];
+        for (int e = lane; e < ly.n_out * ly.n_in; e += 64) {
+            const int j = e / ly.n_in, k = e - j * ly.n_in;
+            lds[ly.lds_w + j * ly.pitch + k] = ly.W[e];
+            if (with_v) lds[ly.lds_v + j * ly.pitch + k] = ly.VW[e];
+        }
+        if (lane < ly.n_out) {
+            lds[ly.lds_b + lane] = ly.b[lane];
+            if (with_v) lds[ly.lds_vb + lane] = ly.Vb[lane];
+        }
+    }
+    if (lane < n0) lds[p.lds_act[0] + lane] = p.X[lane];
+    // Features travel two steps ahead of their use, labels 64 at a time (lane i holds the label of
+    // step 64 b + i), both as vector loads: a scalar load in flight would hold up every wait for LDS.
+    float x_1 = (1 < p.n_samples && lane < n0) ? p.X[(size_t)n0 + lane] : 0.f;   // features of step s + 1
+    int y_block = 0;
+    double loss_acc = 0.0;
+    __syncthreads();
+
+    for (int64_t s = 0; s < p.n_samples; ++s) {
+        const int mode = with_v ? UPD_MOMENTUM : ((p.keep_v && s == p.n_samples - 1) ? UPD_KEEPV : UPD_SGD);
+        const float *x = lds + p.lds_act[0] + (int)(s & 1) * 64;
+        const bool more = s + 1 < p.n_samples;
+        if ((s & 63) == 0) y_block = p.labels[min(s + lane, p.n_samples - 1)];
+        const int y_cur = __builtin_amdgcn_readlane(y_block, (int)(s & 63));
+        const float x_2 = (s + 2 < p.n_samples && lane < n0) ? p.X[(size_t)(s + 2) * n0 + lane] : 0.f;
+
+        // ---- feed forward: lane j is unit j ----
+        const float *ain = x;
+#pragma unroll
+        for (int l = 1; l <= L; ++l) {
+            const TinyLayer &ly = p.layer[l];
+            float *aout = lds + p.lds_act[l];
+            if (lane < ly.n_out) {
+                const float *wr = lds + ly.lds_w + lane * ly.pitch;
+                float z = lds[ly.lds_b + lane];
+                int k = 0;
+                for (; k + 4 <= ly.n_in; k += 4)
+                    z += wr[k] * ain[k] + wr[k + 1] * ain[k + 1] + wr[k + 2] * ain[k + 2] + wr[k + 3] * ain[k + 3];
+                for (; k < ly.n_in; ++k) z += wr[k] * ain[k];
+                aout[lane] = act_fn(ly.act, z);   // a softmax layer keeps its net inputs here
+            }
+            __syncthreads();
+            ain = aout;
+        }
+
+        // ---- output error and loss ----
+        {
+            const TinyLayer &ly = p.layer[L];
+            const float *aL = lds + p.lds_act[L];
+            int y = y_cur;
+            y = y < 0 ? 0 : (y >= nL ? nL - 1 : y);
+            const bool on = lane < nL;
+            const float t = lane == y ? 1.0f : 0.0f;
+            float d, e;
+            if (p.loss == DN_LOSS_CROSS_ENTROPY) {
+                const float z = on ? aL[lane] : -INFINITY;
+                const float m = wave_max(z);
+                const float ex = on ? expf(z - m) : 0.f;
+                const float sum = wave_sum(ex);
+                d = ex * (1.0f / sum) - t;
+                e = logf(sum) - (aL[y] - m);
+            } else {
+                const float a = on ? aL[lane] : 0.f;
+                const float f = a - t;
+                d = f * act_deriv(ly.act, a);
+                e = wave_sum(on ? 0.5f * f * f : 0.f);
+            }
+            if (on) lds[p.lds_dl[L] + lane] = d;
+            if (lane == 0) loss_acc += (double)e;
+            __syncthreads();
+        }
+
+        // ---- back propagation in reverse order: delta of the layer below from the weights before
+        //      their update, then the update of this layer ----
+#pragma unroll
+        for (int l = L; l >= 1; --l) {
+            const TinyLayer &ly = p.layer[l];
+            const float *dl = lds + p.lds_dl[l];
+            const float *aprev = (l == 1) ? x : (lds + p.lds_act[l - 1]);
+            float *W = lds + ly.lds_w, *V = lds + ly.lds_v;
+            if (l > 1) {
+                if (lane < ly.n_in) {   // lane k is unit k of layer l-1
+                    float sacc = 0.f;
+                    for (int j = 0; j < ly.n_out; ++j) sacc += W[j * ly.pitch + lane] * dl[j];
+                    lds[p.lds_dl[l - 1] + lane] = sacc * act_deriv(p.layer[l - 1].act, aprev[lane]);
+                }
+                __syncthreads();
+            }
+            // rank-1 update: element e = lane + 64 i of the n_out x n_in matrix, (row, column) advanced
+            // by the quotient and remainder of 64 by n_in
+            int j = lane / ly.n_in, k = lane - j * ly.n_in;
+            for (int e = lane; e < ly.n_out * ly.n_in; e += 64) {
+                const int idx = j * ly.pitch + k;
+                float v = with_v ? V[idx] : 0.f;
+                W[idx] = apply_update(W[idx], (p.lr * dl[j]) * aprev[k], v, p.mu, mode);
+                if (mode == UPD_MOMENTUM) V[idx] = v;
+                else if (mode == UPD_KEEPV) ly.VW[j * ly.n_in + k] = v;
+                j += ly.rs;
+                k += ly.ks;
+                if (k >= ly.n_in) { k -= ly.n_in; ++j; }
+            }
+            if (lane < ly.n_out) {
+                float v = with_v ? lds[ly.lds_vb + lane] : 0.f;
+                lds[ly.lds_b + lane] = apply_update(lds[ly.lds_b + lane], p.lr * dl[lane], v, p.mu, mode);
+                if (mode == UPD_MOMENTUM) lds[ly.lds_vb + lane] = v;
+                else if (mode == UPD_KEEPV) ly.Vb[lane] = v;
+            }
+            __syncthreads();
+        }
+
+        if (more && lane < n0) lds[p.lds_act[0] + (int)((s + 1) & 1) * 64 + lane] = x_1;
+        x_1 = x_2;
+        __syncthreads();
+    }
+
+    // ---- epilogue: parameters back to device memory ----
+#pragma unroll
+    for (int l = 1; l <= L; ++l) {
+        const TinyLayer &ly = p.layer[l];
+        for (int e = lane; e < ly.n_out * ly.n_in; e += 64) {
+            const int j = e / ly.n_in, k = e - j * ly.n_in;
+            ly.W[e] = lds[ly.lds_w + j * ly.pitch + k];
+            if (with_v) ly.VW[e] = lds[ly.lds_v + j * ly.pitch + k];
+        }
+        if (lane < ly.n_out) {
+            ly.b[lane] = lds[ly.lds_b + lane];
+            if (with_v) ly.Vb[lane] = lds[ly.lds_vb + lane];
+        }
+    }
+    if (lane == 0) *p.loss_acc += loss_acc;
+}
+
+}  // namespace
+
+// ---- host side -------------------------------------------------------------------
+
+bool tiny_plan(const int32_t *n, int L, bool want_v, TinyPlan &p)
+{
+    p = TinyPlan{};
+    if (L < 1 || L > ON_MAX_L) return false;
+    for (int l = 0; l <= L; ++l)
+        if (n[l] > 64) return false;
+    p.L = L;
+    int f = 0;
+    p.lds_act[0] = f; f += 2 * 64;                      // the sample's features, two buffers
+    for (int l = 1; l <= L; ++l) {
+        p.lds_act[l] = f; f += 64;
+        p.lds_dl[l] = f; f += 64;
+    }
+    for (int l = 1; l <= L; ++l) {
+        TinyLayer &y = p.layer[l];
+        y.n_in = n[l - 1]; y.n_out = n[l];
+        y.pitch = n[l - 1] | 1;                          // odd: rows start in different banks
+        y.rs = 64 / y.n_in; y.ks = 64 % y.n_in;
+        y.lds_w = f; f += y.n_out * y.pitch;
+        y.lds_v = f; if (want_v) f += y.n_out * y.pitch;
+        y.lds_b = f; f += 64;
+        y.lds_vb = f; if (want_v) f += 64;
+    }
+    if ((size_t)f * sizeof(float) > ON_MAX_LDS_BYTES) return false;
+    p.lds_floats = f;
+    return true;
+}
+
+namespace {
+
+template <int L>
+hipError_t tiny_prepare_one()
+{
+    return hipFuncSetAttribute((const void *)tiny_epoch_kernel<L>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                               (int)ON_MAX_LDS_BYTES);
+}
+
+template <int L>
+void tiny_launch_one(const TinyPlan &plan, hipStream_t stream)
+{
+    hipLaunchKernelGGL(tiny_epoch_kernel<L>, dim3(1), dim3(64), (size_t)plan.lds_floats * sizeof(float), stream, plan);
+}
+
+}  // namespace
+
+hipError_t tiny_prepare()
+{
+    static_assert(ON_MAX_L == 8, "one instantiation per depth");
+    const hipError_t e[] = {tiny_prepare_one<1>(), tiny_prepare_one<2>(), tiny_prepare_one<3>(), tiny_prepare_one<4>(),
+                            tiny_prepare_one<5>(), tiny_prepare_one<6>(), tiny_prepare_one<7>(), tiny_prepare_one<8>()};
+    for (hipError_t x : e)
+        if (x != hipSuccess) return x;
+    return hipSuccess;
+}
+
+hipError_t launch_tiny_epoch(const TinyPlan &plan, hipStream_t stream)
+{
+    switch (plan.L) {
+    case 1: tiny_launch_one<1>(plan, stream); break;
+    case 2: tiny_launch_one<2>(plan, stream); break;
+    case 3: tiny_launch_one<3>(plan, stream); break;
+    case 4: tiny_launch_one<4>(plan, stream); break;
+    case 5: tiny_launch_one<5>(plan, stream); break;
+    case 6: tiny_launch_one<6>(plan, stream); break;
+    case 7: tiny_launch_one<7>(plan, stream); break;
+    case 8: tiny_launch_one<8>(plan, stream); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace dn

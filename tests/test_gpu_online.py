@@ -25,9 +25,10 @@ def dnlib():
     return dn
 
 
-def run_pair(dn, w, n, passes, mode, min_tile=None, tol=1e-4, biases=True, resident=1, twin=1, twin_expected=None):
+def run_pair(dn, w, n, passes, mode, min_tile=None, tol=1e-4, biases=True, resident=1, twin=1, twin_expected=None, tiny=0):
     """`passes` = list of momenta; one pass over the first n samples per entry.  twin=0 keeps
-    plain-gradient-descent passes of deeper nets on the general persistent kernel."""
+    plain-gradient-descent passes of deeper nets on the general persistent kernel; tiny=1 lets nets
+    with no layer wider than 64 run on the one-wavefront kernel."""
     if biases:
         rng = np.random.default_rng(11)
         w.b = [rng.standard_normal(k).astype(np.float32) * 0.1 for k in w.widths[1:]]
@@ -38,13 +39,16 @@ def run_pair(dn, w, n, passes, mode, min_tile=None, tol=1e-4, biases=True, resid
         net.dn_set_option("online_min_tile", min_tile)
     net.dn_set_option("online_resident", resident)
     net.dn_set_option("online_twin", twin)
+    net.dn_set_option("online_tiny", tiny)
     o = Oracle("o32", w.widths, w.acts, w.loss)
     o.set_params(w.W, w.b)
     X = torch.from_numpy(w.X[:n]).to("cuda:0")
     y = torch.from_numpy(w.labels[:n]).to("cuda:0")
     for mu in passes:
         got = net.dn_train_epoch(X, y, 1, w.lr, mu)
-        if mode == PERSISTENT and twin_expected is not None:
+        if tiny:
+            assert net.dn_last_schedule() == dn.DN_SCHED_ONE_WAVE, net.dn_last_schedule()
+        elif mode == PERSISTENT and twin_expected is not None:
             want = dn.DN_SCHED_TWO_COPY if (twin_expected and mu == 0.0) else dn.DN_SCHED_PER_SAMPLE
             assert net.dn_last_schedule() == want, (net.dn_last_schedule(), want)
         ref, _ = o.train_epoch(w.X[:n], w.labels[:n], 1, w.lr, mu)
@@ -114,6 +118,44 @@ def test_two_copy_persistent_epochs_match_checker(dnlib, widths, acts, loss, min
                    batch=1, lr=0.005, momentum=0.0, seed=4)
     fits = not (widths == [64, 2048, 1024, 10] and min_tile is None)   # 64-row tiles of that net exceed LDS
     run_pair(dnlib, w, 48, [0.0, 0.0, 0.5, 0.0], PERSISTENT, min_tile, twin_expected=fits)
+
+
+TINY_SHAPES = [
+    # no layer wider than 64
+    ([4, 16, 3], [SIG, SIG], MSE),
+    ([37, 64, 5], [TANH, LIN], MSE),
+    ([20, 40, 30, 50, 24, 6], [TANH, SIG, RELU, TANH, SOFTMAX], CE),
+    ([64, 64, 64, 64], [RELU, TANH, SOFTMAX], CE),
+    ([9, 1], [SIG], MSE),
+    ([1, 1, 2], [TANH, SOFTMAX], CE),
+    ([3, 5, 7, 2, 9, 4, 6, 8, 10], [TANH, SIG, TANH, LIN, RELU, SIG, TANH, SOFTMAX], CE),   # eight layers
+]
+
+
+@pytest.mark.parametrize("widths,acts,loss", TINY_SHAPES)
+def test_one_wave_epochs_match_checker(dnlib, widths, acts, loss):
+    """Nets with no layer wider than 64 run whole epochs on one wavefront: a plain pass (which
+    leaves the last step's change as velocity), two momentum passes, a plain pass again."""
+    announce("online one-wave widths=%s" % (widths,))
+    w = synth.make("online", widths, acts, loss, n_samples=48, features="normal", init="xavier_uniform",
+                   batch=1, lr=0.005, momentum=0.0, seed=4)
+    run_pair(dnlib, w, 48, [0.0, 0.5, 0.5, 0.0], PERSISTENT, tiny=1)
+
+
+def test_one_wave_single_sample_and_refusal(dnlib):
+    announce("online one-wave: one sample; a 65-wide layer goes elsewhere")
+    w = synth.make("online", [12, 20, 4], [TANH, SOFTMAX], CE, n_samples=1, features="normal",
+                   init="xavier_uniform", batch=1, lr=0.05, momentum=0.0, seed=2)
+    run_pair(dnlib, w, 1, [0.0, 0.5], PERSISTENT, tiny=1)
+    w = synth.make("online", [12, 65, 4], [TANH, SOFTMAX], CE, n_samples=8, features="normal",
+                   init="xavier_uniform", batch=1, lr=0.05, momentum=0.0, seed=2)
+    net = dnlib.Net(w.widths, w.acts, w.loss, 1)
+    net.set_all(w.W, w.b)
+    X = torch.from_numpy(w.X).to("cuda:0")
+    y = torch.from_numpy(w.labels).to("cuda:0")
+    assert np.isfinite(net.dn_train_epoch(X, y, 1, w.lr, 0.0))
+    assert net.dn_last_schedule() != dnlib.DN_SCHED_ONE_WAVE
+    net.close()
 
 
 def test_two_copy_and_general_kernel_agree(dnlib):
@@ -193,6 +235,12 @@ def test_iris_like_ten_epochs_persistent(dnlib):
     announce("cfg1 4-16-3 B=1, 10 epochs, persistent")
     w = synth.iris_like()
     run_pair(dnlib, w, w.n_samples, [0.0] * 10, PERSISTENT, tol=1e-3, biases=False)
+
+
+def test_iris_like_ten_epochs_one_wave(dnlib):
+    announce("cfg1 4-16-3 B=1, 10 epochs, one wavefront (the default schedule for this net)")
+    w = synth.iris_like()
+    run_pair(dnlib, w, w.n_samples, [0.0] * 10, PERSISTENT, tol=1e-3, biases=False, tiny=1)
 
 
 def test_digits_like_online_prefix_per_phase(dnlib):

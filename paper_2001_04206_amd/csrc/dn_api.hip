@@ -462,9 +462,9 @@ bool batch_pays(const dn_net *net, int batch)
 bool deep_pays(const dn_net *net, int batch)
 {
     (void)net;
-    // 1024-1024-1024-1024-10, us/step persistent against one launch per phase: batch 4: 61 / 76,
-    // batch 8: 66 / 76, batch 16: 75 / 76, batch 24: 97 / 77
-    return batch <= 16;
+    // 1024-1024-1024-1024-10, us/step persistent against one launch per product (7 launches): batch 4: 48 / 76,
+    // batch 8: 49 / 76, batch 16: 51 / 77, batch 24: 57 / 77, batch 32: 58 / 75, batch 48: 79 / 72, batch 64: 86 / 70
+    return batch <= 32;
 }
 
 // A whole minibatch epoch of a one- or two-layer net in persistent-kernel launches.

@@ -1033,18 +1033,27 @@ __global__ __launch_bounds__(ON_THREADS) void batch_epoch_kernel(BatchPlan p)
 // device-scope atomic loads that bypass the per-XCD L2 (matrices other workgroups wrote moments
 // ago).  (Invalidating the caches once per exchange and then loading plainly was measured: the
 // invalidation alone costs about 10 us per exchange, more than the bypassing loads.)
+// A loader is built from the matrix's first element (wave uniform) and reads the four floats at an
+// element offset.  The bypassing form is one 16-byte buffer load with the device-scope cache policy
+// (the policy a device-scope atomic load gets); four 4-byte atomic loads per float4 were the first
+// version and cost four times the memory instructions.  The data needs no atomicity: it was complete
+// before its producer's stamp became visible, and is read after the stamp was seen.
 struct PlainLoad {
-    static __device__ __forceinline__ v4f ld(const float *p) { return *(const v4f *)p; }
+    const float *base;
+    __device__ __forceinline__ explicit PlainLoad(const float *b) : base(b) {}
+    __device__ __forceinline__ v4f ld(int off) const { return *(const v4f *)(base + off); }
 };
 struct CoherentLoad {
-    static __device__ __forceinline__ v4f ld(const float *p)
+    typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+    __amdgpu_buffer_rsrc_t rsrc;
+    // raw buffer over [b, b + 2 GB): 32-bit byte offsets, no stride; 0x00020000: 32-bit data format
+    __device__ __forceinline__ explicit CoherentLoad(const float *b)
+        : rsrc(__builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(b), 0, 0x7fffffff, 0x00020000)) {}
+    __device__ __forceinline__ v4f ld(int off) const
     {
-        v4f v;
-        v.x = __hip_atomic_load(p + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        v.y = __hip_atomic_load(p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        v.z = __hip_atomic_load(p + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        v.w = __hip_atomic_load(p + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        return v;
+        constexpr int kDeviceScope = 16;   // the sc1 bit of the cache policy operand
+        const v4u u = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off * 4, 0, kDeviceScope);
+        return (v4f){__uint_as_float(u.x), __uint_as_float(u.y), __uint_as_float(u.z), __uint_as_float(u.w)};
     }
 };
 
@@ -1055,6 +1064,7 @@ template <class Load, class Fin>
 __device__ __forceinline__ void tile_times_rows(const float *__restrict__ M, int n, int Bs, const float *T, int nr, Fin fin)
 {
     constexpr int MAXIT = PD_MAX_BATCH / (kWaves * 4);
+    const Load load(M);
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int sg = lane >> 4, g = lane & 15;
     const int nk4 = n / 4;
@@ -1075,7 +1085,7 @@ __device__ __forceinline__ void tile_times_rows(const float *__restrict__ M, int
 #pragma unroll
                     for (int j = 0; j < 16; ++j) {
                         const int k4 = (c * 16 + j) * 16 + g;
-                        x[j] = Load::ld(M + (size_t)b * n + (k4 < nk4 ? k4 : 0) * 4);
+                        x[j] = load.ld(b * n + (k4 < nk4 ? k4 : 0) * 4);
                     }
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
@@ -1112,13 +1122,13 @@ __device__ __forceinline__ void tile_times_rows(const float *__restrict__ M, int
 }
 
 template <int NQ, class Load>
-__device__ __forceinline__ void rank_accumulate(v4f (&acc)[4], const float *__restrict__ Mcol, int n, int bbeg, int bend,
+__device__ __forceinline__ void rank_accumulate(v4f (&acc)[4], const Load &load, int col, int n, int bbeg, int bend,
                                                 int Bs, const float *D, int dper, int rc)
 {
     for (int bb0 = bbeg; bb0 < bend; bb0 += 8) {
         v4f x[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) x[u] = Load::ld(Mcol + (size_t)min(bb0 + u, Bs - 1) * n);
+        for (int u = 0; u < 8; ++u) x[u] = load.ld(min(bb0 + u, Bs - 1) * n + col);
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const float on = (bb0 + u < bend) ? 1.f : 0.f;
@@ -1139,6 +1149,7 @@ __device__ __forceinline__ void tile_rank_update(float *T, float *Vrows, int n, 
                                                  const float *__restrict__ M, int Bs, float scale, bool keepv, float *tmp,
                                                  int halves)
 {
+    const Load load(M);
     const int tid = threadIdx.x;
     const int nk4 = n / 4;
     const int half = (halves == 2 && tid >= kThreads / 2) ? 1 : 0;
@@ -1154,12 +1165,12 @@ __device__ __forceinline__ void tile_rank_update(float *T, float *Vrows, int n, 
 #pragma unroll
             for (int q = 0; q < 4; ++q) acc[q] = (v4f){0.f, 0.f, 0.f, 0.f};
             if (on) {
-                const float *Mcol = M + k4 * 4;
+                const int col = k4 * 4;
                 switch (min(4, nr - rc)) {
-                case 1: rank_accumulate<1, Load>(acc, Mcol, n, bbeg, bend, Bs, D, dper, rc); break;
-                case 2: rank_accumulate<2, Load>(acc, Mcol, n, bbeg, bend, Bs, D, dper, rc); break;
-                case 3: rank_accumulate<3, Load>(acc, Mcol, n, bbeg, bend, Bs, D, dper, rc); break;
-                default: rank_accumulate<4, Load>(acc, Mcol, n, bbeg, bend, Bs, D, dper, rc); break;
+                case 1: rank_accumulate<1, Load>(acc, load, col, n, bbeg, bend, Bs, D, dper, rc); break;
+                case 2: rank_accumulate<2, Load>(acc, load, col, n, bbeg, bend, Bs, D, dper, rc); break;
+                case 3: rank_accumulate<3, Load>(acc, load, col, n, bbeg, bend, Bs, D, dper, rc); break;
+                default: rank_accumulate<4, Load>(acc, load, col, n, bbeg, bend, Bs, D, dper, rc); break;
                 }
             }
             if (halves == 2) {

@@ -425,8 +425,13 @@ dn_status run_online(dn_net *net, const float *X, const int32_t *labels, int64_t
     p.abort_flag = net->abort_flag();
     p.loss_acc = net->epoch_acc();
     p.lr = lr; p.mu = mu; p.loss = net->loss;
-    p.resident = (net->online_resident != 0) ? g.resident : 0;
-    if (!p.resident) g.lds_floats = g.lds_work_floats;   // slice images are laid out last: drop them
+    p.resident = g.resident;
+    p.part_rows = g.part_rows;
+    if (net->online_resident == 0) {   // slice images are laid out last: drop them
+        p.resident = 0;
+        p.part_rows = 0;
+        g.lds_floats = g.lds_work_floats;
+    }
     p.lds_x = g.lds_x; p.lds_out = g.lds_out; p.lds_kpart = g.lds_kpart; p.lds_tmp = g.lds_tmp;
     const int64_t chunk = (int64_t)1 << 30;
     for (int64_t s0 = 0; s0 < n_samples; s0 += chunk) {

@@ -142,6 +142,7 @@ struct OnlineGeom {
     int lds_b[ON_MAX_L + 1];  // own biases, then their velocities
     int lds_w[ON_MAX_L + 1], lds_v[ON_MAX_L + 1];   // own weight / velocity slices when resident
     int resident;             // bit l: layer l's slices are kept in LDS
+    int part_rows;            // layer 1 not resident: this many rows of each workgroup's block are kept in LDS anyway
     int lds_out, lds_kpart, lds_tmp, lds_work_floats, lds_floats;
 };
 
@@ -167,6 +168,7 @@ struct OnlinePlan {
     int lds_x, lds_a[ON_MAX_L + 1], lds_own_a[ON_MAX_L + 1], lds_own_d[ON_MAX_L + 1];
     int lds_b[ON_MAX_L + 1], lds_w[ON_MAX_L + 1], lds_v[ON_MAX_L + 1];
     int resident;                               // bit l: layer l's weight slice is kept in LDS for the whole launch
+    int part_rows;                              // rows of layer 1's block kept in LDS when the whole block does not fit
     int lds_out, lds_kpart, lds_tmp;
 };
 

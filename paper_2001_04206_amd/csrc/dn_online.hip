@@ -128,11 +128,14 @@ __device__ __forceinline__ void gather_partials(const u64 *src, int P, int strid
 // weight is rewritten with the update.  Waves split the columns in chunks of 64*VEC and,
 // when there are fewer chunks than waves, the rows as well (partials meet in sred).
 // The block's partial of W^T delta is published to part_out[k], k < n_in.
-template <int VEC, int RU>
-__device__ __forceinline__ void bwd_rows(float *__restrict__ Wt, float *Vt, int n_in, int nr,
-                                         const float *dl, const float *ain, float lr, float mu, int mode,
-                                         float *sred, u64 *part_out, uint32_t seq)
+// (MODE, the update rule, is a template parameter of the three backward sweeps: tested per element
+// at run time it puts a branch around every multiply-add of the unrolled loops.)
+template <int VEC, int RU, int MODE>
+__device__ __forceinline__ void bwd_rows_m(float *__restrict__ Wt, float *Vt, int n_in, int nr,
+                                           const float *dl, const float *ain, float lr, float mu,
+                                           float *sred, u64 *part_out, uint32_t seq)
 {
+    constexpr int mode = MODE;
     constexpr int CW = 64 * VEC;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int C = (n_in + CW - 1) / CW;
@@ -232,12 +235,23 @@ __device__ __forceinline__ void bwd_rows(float *__restrict__ Wt, float *Vt, int 
     }
 }
 
+template <int VEC, int RU>
+__device__ __forceinline__ void bwd_rows(float *__restrict__ Wt, float *Vt, int n_in, int nr,
+                                         const float *dl, const float *ain, float lr, float mu, int mode,
+                                         float *sred, u64 *part_out, uint32_t seq)
+{
+    if (mode == UPD_SGD) bwd_rows_m<VEC, RU, UPD_SGD>(Wt, Vt, n_in, nr, dl, ain, lr, mu, sred, part_out, seq);
+    else if (mode == UPD_KEEPV) bwd_rows_m<VEC, RU, UPD_KEEPV>(Wt, Vt, n_in, nr, dl, ain, lr, mu, sred, part_out, seq);
+    else bwd_rows_m<VEC, RU, UPD_MOMENTUM>(Wt, Vt, n_in, nr, dl, ain, lr, mu, sred, part_out, seq);
+}
+
 // Backward of a block of rows of the first layer (no delta is needed for the input): the
 // block is a contiguous run of nr * n_in weights, updated in place.
-template <int VEC, int RU>
-__device__ __forceinline__ void bwd_flat(float *__restrict__ Wb, float *Vb, int n_in, int nr,
-                                         const float *dl, const float *ain, float lr, float mu, int mode)
+template <int VEC, int RU, int MODE>
+__device__ __forceinline__ void bwd_flat_m(float *__restrict__ Wb, float *Vb, int n_in, int nr,
+                                           const float *dl, const float *ain, float lr, float mu)
 {
+    constexpr int mode = MODE;
     const int total = nr * n_in;
     const float inv_n = 1.0f / (float)n_in;
     for (int i0 = threadIdx.x * VEC; i0 < total; i0 += kThreads * VEC * RU) {
@@ -306,6 +320,124 @@ __device__ __forceinline__ void bwd_flat(float *__restrict__ Wb, float *Vb, int 
     }
 }
 
+template <int VEC, int RU>
+__device__ __forceinline__ void bwd_flat(float *__restrict__ Wb, float *Vb, int n_in, int nr,
+                                         const float *dl, const float *ain, float lr, float mu, int mode)
+{
+    if (mode == UPD_SGD) bwd_flat_m<VEC, RU, UPD_SGD>(Wb, Vb, n_in, nr, dl, ain, lr, mu);
+    else if (mode == UPD_KEEPV) bwd_flat_m<VEC, RU, UPD_KEEPV>(Wb, Vb, n_in, nr, dl, ain, lr, mu);
+    else bwd_flat_m<VEC, RU, UPD_MOMENTUM>(Wb, Vb, n_in, nr, dl, ain, lr, mu);
+}
+
+// One sweep over a block of rows of the FIRST layer, for rows of at most 512 floats (whole float4s):
+//   UPDATE  W[r][k] = update(W[r][k], (lr dl[r]) a[k])          (the rank-1 step; no delta is needed below layer 1)
+//   DOT     out[r]  = sum_k W[r][k] xd[k], from the row as just updated
+// Per-sample training allows both in one pass: the update of W_1 is the last thing a step does and
+// the product W_1 x of the next sample the first thing the next step does, so the row that was just
+// updated is multiplied with the next sample while it is still in registers -- 8 bytes per weight
+// and step through memory (read, write) instead of 12 (read; read, write).
+// Sixteen lanes share a row (four rows per wave at a time, two such groups in flight): a lane owns
+// the float4 columns g, g + 16, ... of every row and keeps its pieces of a and xd in registers, so a
+// row costs its loads, its multiply-adds, its stores and one four-step butterfly -- no index
+// arithmetic and no LDS traffic per element.  Wt / Vt: LDS or device memory.
+// NI: float4 columns per lane (rows of up to 64 NI floats).  Every load is issued unconditionally (clamped
+// address, contribution masked): loads behind a branch make the compiler wait for each before the next.
+// MODE (the update rule) is a template parameter as well: tested per element at run time it put a
+// branch around every multiply-add (measured: 7 us per 64 rows against 0.5 us).
+template <bool UPDATE, bool DOT, int NI, int MODE>
+__device__ __forceinline__ void sweep_rows16_n(float *__restrict__ Wt, float *__restrict__ Vt, int n, int nr, const float *dl,
+                                               const float *a, const float *xd, float lr, float mu, float *out)
+{
+    constexpr int mode = MODE;
+    constexpr int RU = 2;   // row groups in flight
+    constexpr int jn = NI;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int sg = lane >> 4, g = lane & 15;
+    const int n4 = n >> 2;
+    v4f a4[NI], x4[NI];
+#pragma unroll
+    for (int j = 0; j < NI; ++j) {
+        const int c = g + 16 * j;
+        const bool on = c < n4;
+        a4[j] = (UPDATE && on) ? *(const v4f *)(a + 4 * c) : (v4f){0.f, 0.f, 0.f, 0.f};
+        x4[j] = (DOT && on) ? *(const v4f *)(xd + 4 * c) : (v4f){0.f, 0.f, 0.f, 0.f};
+    }
+    for (int base = 0; base < nr; base += 32 * RU) {
+        v4f wv[RU][NI];
+        int row[RU];
+#pragma unroll
+        for (int u = 0; u < RU; ++u) {
+            row[u] = base + u * 32 + wave * 4 + sg;
+            const float *wp = Wt + (size_t)min(row[u], nr - 1) * n;
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+                if (j < jn) wv[u][j] = *(const v4f *)(wp + 4 * min(g + 16 * j, n4 - 1));
+        }
+#pragma unroll
+        for (int u = 0; u < RU; ++u) {
+            const bool rin = row[u] < nr;
+            const int rc = min(row[u], nr - 1);
+            float acc = 0.f;
+            if (UPDATE) {
+                const float ld = lr * dl[rc];
+                float *wp = Wt + (size_t)rc * n, *vp = Vt + (size_t)rc * n;
+                v4f vrow[NI];
+                if (mode == UPD_MOMENTUM) {
+#pragma unroll
+                    for (int j = 0; j < NI; ++j) vrow[j] = *(const v4f *)(vp + 4 * min(g + 16 * j, n4 - 1));
+                } else {
+#pragma unroll
+                    for (int j = 0; j < NI; ++j) vrow[j] = (v4f){0.f, 0.f, 0.f, 0.f};
+                }
+#pragma unroll
+                for (int j = 0; j < NI; ++j) {
+                    if (j < jn) {
+                        const int c = g + 16 * j;
+                        const bool on = rin && c < n4;
+                        const v4f vv = vrow[j];
+                        v4f t;
+                        float v0 = vv.x, v1 = vv.y, v2 = vv.z, v3 = vv.w;
+                        t.x = apply_update(wv[u][j].x, ld * a4[j].x, v0, mu, mode);
+                        t.y = apply_update(wv[u][j].y, ld * a4[j].y, v1, mu, mode);
+                        t.z = apply_update(wv[u][j].z, ld * a4[j].z, v2, mu, mode);
+                        t.w = apply_update(wv[u][j].w, ld * a4[j].w, v3, mu, mode);
+                        wv[u][j] = t;
+                        if (on) {
+                            *(v4f *)(wp + 4 * c) = t;
+                            if (mode != UPD_SGD) *(v4f *)(vp + 4 * c) = (v4f){v0, v1, v2, v3};
+                        }
+                    }
+                }
+            }
+            if (DOT) {
+#pragma unroll
+                for (int j = 0; j < NI; ++j)
+                    if (j < jn)
+                        acc += wv[u][j].x * x4[j].x + wv[u][j].y * x4[j].y + wv[u][j].z * x4[j].z + wv[u][j].w * x4[j].w;
+                acc = row16_sum(acc);
+                if (g == 0 && rin) out[row[u]] = acc;
+            }
+        }
+    }
+}
+
+template <bool UPDATE, bool DOT, int MODE>
+__device__ __forceinline__ void sweep_rows16_m(float *__restrict__ Wt, float *__restrict__ Vt, int n, int nr, const float *dl,
+                                               const float *a, const float *xd, float lr, float mu, float *out)
+{
+    if ((n >> 2) <= 64) sweep_rows16_n<UPDATE, DOT, 4, MODE>(Wt, Vt, n, nr, dl, a, xd, lr, mu, out);
+    else sweep_rows16_n<UPDATE, DOT, 8, MODE>(Wt, Vt, n, nr, dl, a, xd, lr, mu, out);
+}
+
+template <bool UPDATE, bool DOT>
+__device__ __forceinline__ void sweep_rows16(float *__restrict__ Wt, float *__restrict__ Vt, int n, int nr, const float *dl,
+                                             const float *a, const float *xd, float lr, float mu, int mode, float *out)
+{
+    if (!UPDATE || mode == UPD_SGD) sweep_rows16_m<UPDATE, DOT, UPD_SGD>(Wt, Vt, n, nr, dl, a, xd, lr, mu, out);
+    else if (mode == UPD_KEEPV) sweep_rows16_m<UPDATE, DOT, UPD_KEEPV>(Wt, Vt, n, nr, dl, a, xd, lr, mu, out);
+    else sweep_rows16_m<UPDATE, DOT, UPD_MOMENTUM>(Wt, Vt, n, nr, dl, a, xd, lr, mu, out);
+}
+
 // Last layer, forward: this workgroup's partial of z_L from its nc own columns of W_L
 // (Wt = first own column of row 0, rows `stride` apart).
 __device__ __forceinline__ void fwd_cols(const float *__restrict__ Wt, int stride, int nL, int nc,
@@ -337,10 +469,12 @@ __device__ __forceinline__ void fwd_cols(const float *__restrict__ Wt, int strid
 // Last layer, backward: for each own column j: s_j = sum_k W_L[k][j] delta_L[k] from the
 // weights before the update, then the column is updated.  d_own[j] = s_j f'(a_own[j]) when
 // a previous layer exists.
-__device__ __forceinline__ void bwd_cols(float *__restrict__ Wt, int stride, float *Vt, int vstride, int nL,
-                                         int nc, const float *a_own, const float *dL, float lr, float mu,
-                                         int mode, float *d_own, int act_prev)
+template <int MODE>
+__device__ __forceinline__ void bwd_cols_m(float *__restrict__ Wt, int stride, float *Vt, int vstride, int nL,
+                                           int nc, const float *a_own, const float *dL, float lr, float mu,
+                                           float *d_own, int act_prev)
 {
+    constexpr int mode = MODE;
     constexpr int KB = 16;
     for (int j = threadIdx.x; j < nc; j += kThreads) {
         const float a = a_own[j];
@@ -378,6 +512,15 @@ __device__ __forceinline__ void bwd_cols(float *__restrict__ Wt, int stride, flo
     }
 }
 
+__device__ __forceinline__ void bwd_cols(float *__restrict__ Wt, int stride, float *Vt, int vstride, int nL,
+                                         int nc, const float *a_own, const float *dL, float lr, float mu,
+                                         int mode, float *d_own, int act_prev)
+{
+    if (mode == UPD_SGD) bwd_cols_m<UPD_SGD>(Wt, stride, Vt, vstride, nL, nc, a_own, dL, lr, mu, d_own, act_prev);
+    else if (mode == UPD_KEEPV) bwd_cols_m<UPD_KEEPV>(Wt, stride, Vt, vstride, nL, nc, a_own, dL, lr, mu, d_own, act_prev);
+    else bwd_cols_m<UPD_MOMENTUM>(Wt, stride, Vt, vstride, nL, nc, a_own, dL, lr, mu, d_own, act_prev);
+}
+
 __global__ __launch_bounds__(ON_THREADS) void online_epoch_kernel(OnlinePlan p)
 {
     extern __shared__ __align__(16) float lds[];
@@ -389,6 +532,9 @@ __global__ __launch_bounds__(ON_THREADS) void online_epoch_kernel(OnlinePlan p)
     const OnlineLayer &last = p.layer[L];
     // layer l's weight slice lives in LDS (bit l of p.resident), and with momentum its velocity slice too
     auto res_of = [&](int l) { return ((p.resident >> l) & 1) != 0; };
+    // layer 1 too large for LDS: the first p.part_rows rows of the workgroup's block live there all
+    // the same (every weight kept in LDS saves its three trips through device memory per step)
+    const int part1 = (L >= 2 && !res_of(1)) ? max(0, min(p.part_rows, min(p.layer[1].per, p.layer[1].n_out - w * p.layer[1].per))) : 0;
     const bool with_v = p.mu != 0.f;
 
     // slices owned by this workgroup
@@ -424,6 +570,10 @@ __global__ __launch_bounds__(ON_THREADS) void online_epoch_kernel(OnlinePlan p)
         }
         if (res_of(l) && nr > 0) copy_floats(lds + p.lds_w[l], ly.W + (size_t)r0 * ly.n_in, nr * ly.n_in);
         if (res_of(l) && with_v && nr > 0) copy_floats(lds + p.lds_v[l], ly.VW + (size_t)r0 * ly.n_in, nr * ly.n_in);
+        if (l == 1 && part1 > 0) {
+            copy_floats(lds + p.lds_w[1], ly.W + (size_t)r0 * ly.n_in, part1 * ly.n_in);
+            if (with_v) copy_floats(lds + p.lds_v[1], ly.VW + (size_t)r0 * ly.n_in, part1 * ly.n_in);
+        }
     }
     const bool res_last = res_of(L), vres_last = res_last && with_v;
     if (res_last)
@@ -437,6 +587,11 @@ __global__ __launch_bounds__(ON_THREADS) void online_epoch_kernel(OnlinePlan p)
     int y_cur = p.labels[0];
     double loss_acc = 0.0;
     __syncthreads();
+
+    // A first layer that is streamed (wholly or in part) and has short rows takes the one-pass
+    // sweep: update of W_1 and the next sample's products with it together (sweep_rows16).
+    const bool fast1 = L >= 2 && !res_of(1) && p.layer[1].vec4 != 0 && n0 <= 512 && p.layer[1].kshift == 0;
+    bool have_z1 = false;   // kpart already holds layer 1's products with the current sample
 
     constexpr int XR = 4;
     for (int64_t s = 0; s < p.n_samples; ++s) {
@@ -460,6 +615,18 @@ __global__ __launch_bounds__(ON_THREADS) void online_epoch_kernel(OnlinePlan p)
                 y_next = p.labels[s + 1];                                                         \
             }                                                                                     \
         } while (0)
+        // the prefetched features of the next sample into the other input buffer
+        auto store_next_x = [&]() {
+            float *xn = xa0 + (size_t)((s + 1) & 1) * n0p;
+            if (need_x) {
+#pragma unroll
+                for (int u = 0; u < XR; ++u) {
+                    const int k = tid + u * kThreads;
+                    if (k < n0) xn[k] = xr[u];
+                }
+                for (int k = tid + XR * kThreads; k < n0; k += kThreads) xn[k] = p.X[(size_t)(s + 1) * n0 + k];
+            }
+        };
 
         // ---- forward through the row-split layers 1..L-1 -------------------------------
         for (int l = 1; l < L; ++l) {
@@ -486,10 +653,23 @@ __global__ __launch_bounds__(ON_THREADS) void online_epoch_kernel(OnlinePlan p)
                         if (ly.vec4) fwd_rows<4, 4>(Wt, ly.n_in, nr, ly.kshift, ly.seg, xin, kpart);
                         else fwd_rows<1, 4>(Wt, ly.n_in, nr, ly.kshift, ly.seg, xin, kpart);
                     }
+                } else if (l == 1 && fast1) {
+                    if (!have_z1) {   // (otherwise the previous step's sweep left the products in kpart)
+                        if (part1 > 0)
+                            sweep_rows16<false, true>(lds + p.lds_w[1], nullptr, ly.n_in, part1, nullptr, nullptr, xin, 0.f, 0.f,
+                                                      UPD_SGD, kpart);
+                        sweep_rows16<false, true>(ly.W + (size_t)(r0 + part1) * ly.n_in, nullptr, ly.n_in, nr - part1, nullptr,
+                                                  nullptr, xin, 0.f, 0.f, UPD_SGD, kpart + part1);
+                    }
                 } else {
-                    const float *Wt = ly.W + (size_t)r0 * ly.n_in;   // streamed: four rows of loads in flight per wave (two and eight measured slower)
-                    if (ly.vec4) fwd_rows<4, 4>(Wt, ly.n_in, nr, ly.kshift, ly.seg, xin, kpart);
-                    else fwd_rows<1, 4>(Wt, ly.n_in, nr, ly.kshift, ly.seg, xin, kpart);
+                    const int nl = (l == 1) ? part1 : 0;   // rows held in LDS; the rest is streamed
+                    if (nl > 0) {
+                        if (ly.vec4) fwd_rows<4, 4>(lds + p.lds_w[1], ly.n_in, nl, ly.kshift, ly.seg, xin, kpart);
+                        else fwd_rows<1, 4>(lds + p.lds_w[1], ly.n_in, nl, ly.kshift, ly.seg, xin, kpart);
+                    }
+                    const float *Wt = ly.W + (size_t)(r0 + nl) * ly.n_in;   // streamed: four rows of loads in flight per wave (two and eight measured slower)
+                    if (ly.vec4) fwd_rows<4, 4>(Wt, ly.n_in, nr - nl, ly.kshift, ly.seg, xin, kpart + (nl << ly.kshift));
+                    else fwd_rows<1, 4>(Wt, ly.n_in, nr - nl, ly.kshift, ly.seg, xin, kpart + (nl << ly.kshift));
                 }
                 __syncthreads();
                 float *a_own = lds + p.lds_own_a[l];
@@ -604,6 +784,40 @@ __global__ __launch_bounds__(ON_THREADS) void online_epoch_kernel(OnlinePlan p)
                 const bool small = (l >= 2) ? (nr <= (C >= kWaves ? 1 : kWaves / C)) : (nr * ly.n_in <= kThreads * vec);
                 if (small) DN_BWD_ROWS(lds + p.lds_w[l], 1);
                 else DN_BWD_ROWS(lds + p.lds_w[l], 4);
+            } else if (l == 1 && fast1) {
+                // The next sample's features go to the other input buffer first: the sweep multiplies
+                // each row with them right after updating it, which is layer 1's forward product of
+                // the next step.  Rows held in LDS first, then the streamed rest of the block.
+                float *xnext = xa0 + (size_t)((s + 1) & 1) * n0p;
+                if (more) {
+                    store_next_x();
+                    __syncthreads();
+                }
+                float *Vl = with_v ? (lds + p.lds_v[1]) : (ly.VW + (size_t)r0 * ly.n_in);
+                float *Wg = ly.W + (size_t)(r0 + part1) * ly.n_in, *Vg = ly.VW + (size_t)(r0 + part1) * ly.n_in;
+                if (more) {
+                    if (part1 > 0)
+                        sweep_rows16<true, true>(lds + p.lds_w[1], Vl, ly.n_in, part1, d_own, ain, xnext, p.lr, p.mu, mode, kpart);
+                    sweep_rows16<true, true>(Wg, Vg, ly.n_in, nr - part1, d_own + part1, ain, xnext, p.lr, p.mu, mode,
+                                             kpart + part1);
+                } else {
+                    if (part1 > 0)
+                        sweep_rows16<true, false>(lds + p.lds_w[1], Vl, ly.n_in, part1, d_own, ain, nullptr, p.lr, p.mu, mode, kpart);
+                    sweep_rows16<true, false>(Wg, Vg, ly.n_in, nr - part1, d_own + part1, ain, nullptr, p.lr, p.mu, mode,
+                                              kpart + part1);
+                }
+                have_z1 = more;
+            } else if (l == 1 && part1 > 0) {
+                // the rows held in LDS, then the streamed rest of the block
+                float *Vl = with_v ? (lds + p.lds_v[1]) : (ly.VW + (size_t)r0 * ly.n_in);
+                float *Wg = ly.W + (size_t)(r0 + part1) * ly.n_in, *Vg = ly.VW + (size_t)(r0 + part1) * ly.n_in;
+                if (ly.vec4) {
+                    bwd_flat<4, 4>(lds + p.lds_w[1], Vl, ly.n_in, part1, d_own, ain, p.lr, p.mu, mode);
+                    bwd_flat<4, 4>(Wg, Vg, ly.n_in, nr - part1, d_own + part1, ain, p.lr, p.mu, mode);
+                } else {
+                    bwd_flat<1, 4>(lds + p.lds_w[1], Vl, ly.n_in, part1, d_own, ain, p.lr, p.mu, mode);
+                    bwd_flat<1, 4>(Wg, Vg, ly.n_in, nr - part1, d_own + part1, ain, p.lr, p.mu, mode);
+                }
             } else {
                 DN_BWD_ROWS(ly.W + (size_t)r0 * ly.n_in, 4);
             }
@@ -618,17 +832,9 @@ __global__ __launch_bounds__(ON_THREADS) void online_epoch_kernel(OnlinePlan p)
         }
         if (aborted) break;
 
-        // ---- next sample into the other input buffer ------------------------------------
+        // ---- next sample into the other input buffer (the one-pass sweep has done it already) ----
         if (more) {
-            float *xn = xa0 + (size_t)((s + 1) & 1) * n0p;
-            if (need_x) {
-#pragma unroll
-                for (int u = 0; u < XR; ++u) {
-                    const int k = tid + u * kThreads;
-                    if (k < n0) xn[k] = xr[u];
-                }
-                for (int k = tid + XR * kThreads; k < n0; k += kThreads) xn[k] = p.X[(size_t)(s + 1) * n0 + k];
-            }
+            if (!fast1) store_next_x();
             y_cur = y_next;
         }
         __syncthreads();
@@ -649,6 +855,10 @@ __global__ __launch_bounds__(ON_THREADS) void online_epoch_kernel(OnlinePlan p)
         }
         if (res_of(l) && nr > 0) copy_floats(ly.W + (size_t)r0 * ly.n_in, lds + p.lds_w[l], nr * ly.n_in);
         if (res_of(l) && with_v && nr > 0) copy_floats(ly.VW + (size_t)r0 * ly.n_in, lds + p.lds_v[l], nr * ly.n_in);
+        if (l == 1 && part1 > 0) {
+            copy_floats(ly.W + (size_t)r0 * ly.n_in, lds + p.lds_w[1], part1 * ly.n_in);
+            if (with_v) copy_floats(ly.VW + (size_t)r0 * ly.n_in, lds + p.lds_v[1], part1 * ly.n_in);
+        }
     }
     if (res_last)
         for (int i = tid; i < nL * nc; i += kThreads) {
@@ -1563,6 +1773,16 @@ bool online_geometry(const int32_t *n, int L, int min_tile, bool want_v, OnlineG
         g.resident |= 1 << best;
         g.lds_w[best] = (int)f; f += best_t;
         if (want_v) { g.lds_v[best] = (int)f; f += best_t; }
+    }
+    // What is left takes the first rows of layer 1's block when the whole block does not fit (a
+    // multiple of four rows, so that every piece stays 16-byte aligned).
+    if (L >= 2 && !taken[1]) {
+        const int64_t rows = ((budget - f) / (copies * (int64_t)n[0])) & ~(int64_t)3;
+        if (rows >= 4 && rows < g.per[1]) {
+            g.part_rows = (int)rows;
+            g.lds_w[1] = (int)f; f += rows * n[0];
+            if (want_v) { g.lds_v[1] = (int)f; f += rows * n[0]; }
+        }
     }
     g.lds_floats = (int)f;
     g.ok = true;

@@ -76,6 +76,12 @@ SHAPES = [
     ([16, 4100, 24, 10], [TANH, RELU, SOFTMAX], CE),        # column chunks >= waves (float4 rows)
     ([16, 1030, 24, 128], [SIG, TANH, SOFTMAX], CE),        # column chunks >= waves (scalar rows), widest output
     ([340, 3000, 10], [TANH, SOFTMAX], CE),                 # the paper's benchmark shape, narrower hidden layer
+    ([2000, 5000, 10], [TANH, SOFTMAX], CE),                # first layer beyond LDS: part of each block resident, the rest streamed
+    ([2000, 5000, 40, 10], [SIG, TANH, SOFTMAX], CE),       # the same under a middle layer
+    ([1999, 5003, 7], [TANH, LIN], MSE),                    # the same with rows that are not whole float4s
+    ([400, 30000, 10], [TANH, SOFTMAX], CE),                # streamed first layer with short rows: update and next forward product in one sweep
+    ([256, 20000, 24, 10], [SIG, TANH, SOFTMAX], CE),       # the same under a middle layer
+    ([36, 70000, 3], [RELU, SIG], MSE),                     # very short rows (fewer float4s than the sixteen lanes of a row)
 ]
 
 
@@ -86,8 +92,9 @@ def test_persistent_epochs_match_checker(dnlib, widths, acts, loss, min_tile, re
     """resident=1 keeps the workgroups' weight slices in LDS where they fit (all of these shapes
     except the widest); resident=0 streams them from device memory."""
     announce("online persistent widths=%s min_tile=%s resident=%d" % (widths, min_tile, resident))
+    # (thousands of inputs and outputs per unit: a smaller rate keeps the 48 steps from driving the loss to rounding level)
     w = synth.make("online", widths, acts, loss, n_samples=48, features="normal", init="xavier_uniform",
-                   batch=1, lr=0.005, momentum=0.0, seed=4)
+                   batch=1, lr=0.0001 if max(widths) >= 5000 else 0.005, momentum=0.0, seed=4)
     # plain SGD pass (leaves velocity = last step's delta), then two momentum passes on top of it
     run_pair(dnlib, w, 48, [0.0, 0.5, 0.5], PERSISTENT, min_tile, resident=resident, twin=0)
 

@@ -529,6 +529,12 @@ def main():
         t = hbm_traffic(args.workload)
         if t is not None:     # per launch, like `achieved`: a persistent launch covers timed_steps steps
             roofline["traffic"] = t[0] * (roofline.get("timed_steps", 1) if t[1] == "step" else 1)
+            if roofline["bound"] == "hbm" and roofline.get("avg_launch_us"):
+                # what the counters saw moving, as a rate: `achieved` is the algorithmic figure (three
+                # trips per weight and step at batch 1), which a kernel that keeps weights on chip or
+                # fuses two of the trips undercuts -- it can then exceed the peak; this one cannot
+                roofline["traffic_rate"] = roofline["traffic"] / (roofline["avg_launch_us"] * 1e-6) / 1e9
+                roofline["traffic_frac"] = roofline["traffic_rate"] / PEAK_HBM_GBS
 
     cpu = None
     if not args.no_cpu_baseline:

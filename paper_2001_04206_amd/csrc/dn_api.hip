@@ -467,8 +467,8 @@ bool batch_pays(const dn_net *net, int batch)
 bool deep_pays(const dn_net *net, int batch)
 {
     (void)net;
-    // 1024-1024-1024-1024-10, us/step persistent against one launch per product (7 launches): batch 4: 48 / 76,
-    // batch 8: 49 / 76, batch 16: 51 / 77, batch 24: 57 / 77, batch 32: 58 / 75, batch 48: 79 / 72, batch 64: 86 / 70
+    // 1024-1024-1024-1024-10, us/step persistent against one launch per product (7 launches): batch 4: 37 / 76,
+    // batch 8: 38 / 76, batch 16: 43 / 77, batch 24: 57 / 77, batch 32: 58 / 75, batch 48: 77 / 72, batch 64: 85 / 71
     return batch <= 32;
 }
 

@@ -325,9 +325,12 @@ dn_status dn_sgd_step(float *param_dev, const float *grad_dev, float *velocity_d
  * last kernel of the last dn_train_epoch, from HIP events on the net's stream.
  *
  * dn_kernel_time: with dn_set_option("time_kernels", 1), every kernel launch of
- * dn_train_epoch is bracketed by HIP events on the net's stream (up to 16384
- * launches per epoch; later ones run untimed).  After the epoch this returns,
- * for one kernel class, the summed duration and the number of timed launches.
+ * dn_train_epoch is timed with a pair of HIP events on the net's stream (up to
+ * 16384 launches per epoch; later ones run untimed).  The launches of the
+ * launch-per-product path carry their events themselves (the kernel's own start
+ * and end, as a profiler's kernel trace shows them); a persistent whole-epoch
+ * kernel is bracketed by recorded events.  After the epoch this returns, for
+ * one kernel class, the summed duration and the number of timed launches.
  */
 typedef enum {
     DN_K_FORWARD = 0,     /* Z = A W^T + b, activation                       */

@@ -154,6 +154,12 @@ struct dn_net {
     }
 };
 
+LaunchEvents &dn::launch_events()
+{
+    static thread_local LaunchEvents ev;
+    return ev;
+}
+
 namespace {
 
 #define DN_HIP(expr)                                   \
@@ -189,11 +195,14 @@ bool rate_ok(float lr, float mu)
     return std::isfinite(lr) && std::isfinite(mu) && lr >= 0.f && mu >= 0.f && mu < 1.f;
 }
 
-// Brackets one launch with events when per-launch timing is on.
+// Times one launch when per-launch timing is on.  bind: the scope holds exactly one kernel launch
+// made through launch_kernel, which takes the event pair along (the kernel's own start and end);
+// otherwise the events are recorded around whatever the scope enqueues.
 struct ScopedTimer {
     dn_net *net;
     TimedLaunch *t = nullptr;
-    ScopedTimer(dn_net *n, int cls, bool enabled, double flop = 0.0) : net(n)
+    bool bind;
+    ScopedTimer(dn_net *n, int cls, bool enabled, double flop = 0.0, bool bind_to_launch = false) : net(n), bind(bind_to_launch)
     {
         if (!enabled || net->timed >= kMaxTimed) return;
         if ((int)net->pool.size() <= net->timed) {
@@ -208,11 +217,25 @@ struct ScopedTimer {
         t = &net->pool[net->timed++];
         t->cls = cls;
         t->flop = flop;
-        (void)hipEventRecord(t->start, net->stream);
+        if (bind) {
+            LaunchEvents &ev = launch_events();
+            ev.start = t->start;
+            ev.stop = t->stop;
+            ev.bound = false;
+        } else {
+            (void)hipEventRecord(t->start, net->stream);
+        }
     }
     ~ScopedTimer()
     {
-        if (t) (void)hipEventRecord(t->stop, net->stream);
+        if (!t) return;
+        if (bind) {
+            LaunchEvents &ev = launch_events();
+            if (!ev.bound) --net->timed;   // nothing was launched (an error on the way): the pair stays unused
+            ev = LaunchEvents{};
+        } else {
+            (void)hipEventRecord(t->stop, net->stream);
+        }
     }
 };
 
@@ -232,7 +255,7 @@ dn_status run_forward(dn_net *net, const float *X, int B, bool timing, int last_
         g.bias = net->b(l);
         g.act = net->act[l];
         net->split_k(g);
-        ScopedTimer st(net, DN_K_FORWARD, timing, product_flop(g));
+        ScopedTimer st(net, DN_K_FORWARD, timing, product_flop(g), true);
         DN_HIP(launch_gemm(GEMM_FWD, g, net->gemm_variant, net->stream));
     }
     return DN_OK;
@@ -285,13 +308,13 @@ dn_status run_backward(dn_net *net, const float *X, int B, int mode, float lr, f
         if (merge && l == L - 1 && top_grad == L) {
             const GemmArgs gl = grad_args(L);
             if (delta_narrow_grad_fits(d, gl, net->gemm_variant)) {
-                ScopedTimer st(net, DN_K_DELTA, timing, product_flop(d) + product_flop(gl));
+                ScopedTimer st(net, DN_K_DELTA, timing, product_flop(d) + product_flop(gl), true);
                 DN_HIP(launch_delta_with_narrow_grad(d, gl, net->stream));
                 top_grad = L - 1;
                 continue;
             }
         }
-        ScopedTimer st(net, DN_K_DELTA, timing, product_flop(d));
+        ScopedTimer st(net, DN_K_DELTA, timing, product_flop(d), true);
         DN_HIP(launch_gemm(GEMM_DELTA, d, net->gemm_variant, net->stream));
     }
     GemmArgs grads[ON_MAX_L + 56];
@@ -313,12 +336,12 @@ dn_status run_backward(dn_net *net, const float *X, int B, int mode, float lr, f
             double fs = 0.0;
             for (int i = 0; i < n; ++i)
                 if (in_shared[i]) { shared[ns++] = grads[i]; fs += product_flop(grads[i]); }
-            ScopedTimer st(net, DN_K_GRAD_UPDATE, timing, fs);
+            ScopedTimer st(net, DN_K_GRAD_UPDATE, timing, fs, true);
             DN_HIP(launch_gemm_grads(shared, ns, net->gemm_variant, true, net->stream, nullptr));
         }
         for (int i = 0; i < n; ++i) {
             if (merged >= 2 && in_shared[i]) continue;
-            ScopedTimer st(net, DN_K_GRAD_UPDATE, timing, product_flop(grads[i]));
+            ScopedTimer st(net, DN_K_GRAD_UPDATE, timing, product_flop(grads[i]), true);
             DN_HIP(launch_gemm(GEMM_GRAD, grads[i], net->gemm_variant, net->stream));
         }
     }
@@ -874,7 +897,7 @@ dn_status dn_train_epoch(dn_net *net, const float *X_dev, const int32_t *labels_
         {
             // with a narrow last layer the launch also holds that layer's forward product and its delta product
             const double out_flop = fused_out ? 2.0 * B * (double)net->n[L] * net->n[L - 1] * (L > 1 ? 2.0 : 1.0) : 0.0;
-            ScopedTimer t(net, DN_K_OUTPUT, timing, out_flop);
+            ScopedTimer t(net, DN_K_OUTPUT, timing, out_flop, true);
             if (fused_out)
                 DN_HIP(launch_narrow_output(L == 1 ? Xb : net->A(L - 1), net->W(L), net->b(L), labels_dev + s0, net->A(L),
                                             net->D(L), net->loss_rows(), net->loss_sums(), B, net->n[L], net->n[L - 1],

@@ -785,8 +785,7 @@ static hipError_t launch_vec(const GemmArgs &a, hipStream_t stream)
         if (e != hipSuccess) return e;
         attr_set.store(true, std::memory_order_release);
     }
-    hipLaunchKernelGGL((gemm_kernel<T, A_KC, B_KC, EPI, VEC>), dim3((unsigned)grid), dim3(T::NT), lds, stream, b,
-                       tiles_m, tiles_n);
+    launch_kernel(gemm_kernel<T, A_KC, B_KC, EPI, VEC>, dim3((unsigned)grid), dim3(T::NT), lds, stream, b, tiles_m, tiles_n);
     return hipGetLastError();
 }
 
@@ -901,8 +900,7 @@ hipError_t launch_delta_with_narrow_grad(const GemmArgs &delta, const GemmArgs &
     const int nb = grad.N / 4 + 1;
     NarrowGradArgs ng{grad.A, grad.B, grad.C, grad.V, grad.gb, grad.vb, grad.K, grad.M, grad.N, grad.mode, grad.scale, grad.mu};
     constexpr size_t lds = smem_bytes<V12, true, false>();
-    hipLaunchKernelGGL((gemm_narrow_grad_kernel<P0>), dim3((unsigned)(g0 + nb)), dim3(256), lds, stream, d, tm, tn, (int)g0,
-                       ng, nb);
+    launch_kernel(gemm_narrow_grad_kernel<P0>, dim3((unsigned)(g0 + nb)), dim3(256), lds, stream, d, tm, tn, (int)g0, ng, nb);
     return hipGetLastError();
 }
 
@@ -931,7 +929,7 @@ template <class T, int EPI>
 static hipError_t launch_multi_as(const MultiGradArgs &m, unsigned grid, hipStream_t stream)
 {
     constexpr size_t lds = smem_bytes<T, false, false>();
-    hipLaunchKernelGGL((gemm_multi_grad_kernel<T, EPI>), dim3(grid), dim3(T::NT), lds, stream, m);
+    launch_kernel(gemm_multi_grad_kernel<T, EPI>, dim3(grid), dim3(T::NT), lds, stream, m);
     return hipGetLastError();
 }
 

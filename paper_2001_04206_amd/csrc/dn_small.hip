@@ -177,8 +177,8 @@ hipError_t launch_output_delta(float *AL, float *DL, const int32_t *labels, floa
                                double *loss_sums)
 {
     if (phase == OUT_EVAL && !hit_rows) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(output_delta_kernel, dim3(B), dim3(256), 0, stream, AL, DL, labels, loss_rows, nL, act,
-                       loss, phase, hit_rows, loss_sums);
+    launch_kernel(output_delta_kernel, dim3(B), dim3(256), 0, stream, AL, DL, labels, loss_rows, nL, act, loss, phase,
+                  hit_rows, loss_sums);
     return hipGetLastError();
 }
 
@@ -487,10 +487,10 @@ hipError_t launch_narrow_output(const float *Aprev, const float *W, const float 
     NarrowOutArgs g{Aprev, W, bias, labels, AL, DL, loss_rows, loss_sums, B, nl, nin, act, loss, Dprev, act_prev};
     const int R = B > 1024 ? 4 : 1;
     const unsigned grid = (unsigned)((B + R - 1) / R);
-    if (R == 4 && vec) hipLaunchKernelGGL((narrow_output_kernel<4, 4>), dim3(grid), dim3(256), 0, stream, g);
-    else if (R == 4) hipLaunchKernelGGL((narrow_output_kernel<4, 1>), dim3(grid), dim3(256), 0, stream, g);
-    else if (vec) hipLaunchKernelGGL((narrow_output_kernel<1, 4>), dim3(grid), dim3(256), 0, stream, g);
-    else hipLaunchKernelGGL((narrow_output_kernel<1, 1>), dim3(grid), dim3(256), 0, stream, g);
+    if (R == 4 && vec) launch_kernel(narrow_output_kernel<4, 4>, dim3(grid), dim3(256), 0, stream, g);
+    else if (R == 4) launch_kernel(narrow_output_kernel<4, 1>, dim3(grid), dim3(256), 0, stream, g);
+    else if (vec) launch_kernel(narrow_output_kernel<1, 4>, dim3(grid), dim3(256), 0, stream, g);
+    else launch_kernel(narrow_output_kernel<1, 1>, dim3(grid), dim3(256), 0, stream, g);
     return hipGetLastError();
 }
 
@@ -507,9 +507,9 @@ hipError_t launch_narrow_delta(const float *D, const float *W, const float *Apre
     if (rows < 4) rows = 4;
     const unsigned gy = (unsigned)((B + rows - 1) / rows);
     if (vec)
-        hipLaunchKernelGGL(narrow_delta_kernel<4>, dim3(gx, gy), dim3(256), 0, stream, D, W, Aprev, C, B, nl, nin, act, rows);
+        launch_kernel(narrow_delta_kernel<4>, dim3(gx, gy), dim3(256), 0, stream, D, W, Aprev, C, B, nl, nin, act, rows);
     else
-        hipLaunchKernelGGL(narrow_delta_kernel<1>, dim3(gx, gy), dim3(256), 0, stream, D, W, Aprev, C, B, nl, nin, act, rows);
+        launch_kernel(narrow_delta_kernel<1>, dim3(gx, gy), dim3(256), 0, stream, D, W, Aprev, C, B, nl, nin, act, rows);
     return hipGetLastError();
 }
 
@@ -522,9 +522,9 @@ hipError_t launch_narrow_grad(const float *D, const float *Aprev, float *C, floa
     NarrowGradArgs g{D, Aprev, C, V, gb, vb, B, nl, nin, mode, scale, mu};
     const unsigned grid = (unsigned)(vec ? nin / 4 : nin) + 1;
     if (vec)
-        hipLaunchKernelGGL(narrow_grad_kernel<4>, dim3(grid), dim3(256), 0, stream, g);
+        launch_kernel(narrow_grad_kernel<4>, dim3(grid), dim3(256), 0, stream, g);
     else
-        hipLaunchKernelGGL(narrow_grad_kernel<1>, dim3(grid), dim3(256), 0, stream, g);
+        launch_kernel(narrow_grad_kernel<1>, dim3(grid), dim3(256), 0, stream, g);
     return hipGetLastError();
 }
 

@@ -317,6 +317,61 @@ dn_status dn_maxpool_backward(const float *X_dev, const float *dY_dev, float *dX
 dn_status dn_sgd_step(float *param_dev, const float *grad_dev, float *velocity_dev, int64_t count, float lr,
                       float momentum, void *hip_stream);
 
+/* ---- a convolutional classifier as one network ---------------------------------
+ * The layer sequence of the paper's engine (section "Deep Netts Deep Learning Engine":
+ * convolutional, maximum pooling, fully connected and softmax output layers) as one
+ * object: n_blocks blocks of [convolution -> activation -> optional maximum pooling] on
+ * images [c][h][w], the last block's output flattened ([channel][row][column] order) into
+ * a fully connected net of widths [flat, dense_widths[0], ..., dense_widths[n_dense-1]].
+ * dn_cnn_train_epoch runs the work-flow's three training parts (section "The Deep Netts
+ * Work-flow") for every batch of an epoch -- feed forward through every layer, loss, the
+ * error backwards through every layer (each delta from the parameters as they were before
+ * this step's update), then the update of every layer by the rule of dn_update -- without
+ * returning to the host between steps.  Every step is one of the calls above, enqueued on
+ * one stream; results are those calls' results.
+ *   blocks        n_blocks >= 1 descriptions (host): square k x k filters (k <= 7, pad < k),
+ *                 `act` a dn_act other than softmax, pool_k = 0 for no pooling
+ *   dense_widths  n_dense >= 1 widths after the flatten (host); dense_acts one dn_act each
+ *   arena_dev     device memory, 256-byte aligned, >= dn_cnn_arena_bytes(...) (0 from the
+ *                 query: invalid sizes); holds filters, their velocities and gradients, the
+ *                 activations and gradients between the layers, the convolution workspaces
+ *                 and the fully connected net's arena.  It must stay alive, and must not be
+ *                 written by the caller, until dn_cnn_destroy.
+ * Filters, biases and velocities start at zero: call dn_cnn_set_filters (W_host
+ * [c_out][c_in][k][k], bias_host [c_out]; either may be NULL; zeroes that block's
+ * velocity) and, for the fully connected part, dn_set_params on dn_cnn_dense(net), a handle
+ * that lives as long as the dn_cnn and must not be destroyed by the caller (layer l of it
+ * is the l-th fully connected layer; dn_cnn_flat_size gives its n_0).
+ * dn_cnn_get_filter_grads reads the batch-mean filter gradients of the last training step.
+ * dn_cnn_forward: out_dev [batch][n_L] (device) receives the output layer; may be NULL.
+ * dn_cnn_train_epoch: X_dev [n_samples][c][h][w], labels_dev [n_samples] int32 (device);
+ * samples in index order, `batch` per step, the last step may be short; mean_loss_host as
+ * for dn_train_epoch.
+ * Errors: INVALID_ARG (NULL, misaligned arena, bad rates, block index), SHAPE (invalid
+ * sizes, arena too small, batch outside 1..max_batch), UNSUPPORTED / OOM / DEVICE as for
+ * dn_net_create and the layer calls.
+ */
+typedef struct dn_cnn dn_cnn;
+typedef struct {
+    int32_t c_out, k, stride, pad; /* convolution */
+    int32_t act;                   /* dn_act applied to its output */
+    int32_t pool_k, pool_stride;   /* maximum pooling after it; pool_k = 0: none */
+} dn_conv_block;
+size_t dn_cnn_arena_bytes(int32_t c, int32_t h, int32_t w, const dn_conv_block *blocks, int32_t n_blocks,
+                          const int32_t *dense_widths, int32_t n_dense, int32_t max_batch);
+dn_status dn_cnn_create(int32_t c, int32_t h, int32_t w, const dn_conv_block *blocks, int32_t n_blocks,
+                        const int32_t *dense_widths, int32_t n_dense, const dn_act *dense_acts, dn_loss loss,
+                        int32_t max_batch, void *arena_dev, size_t arena_bytes, void *hip_stream, dn_cnn **out);
+dn_status dn_cnn_destroy(dn_cnn *net);
+dn_net *dn_cnn_dense(dn_cnn *net);
+int32_t dn_cnn_flat_size(const dn_cnn *net);
+dn_status dn_cnn_set_filters(dn_cnn *net, int32_t block, const float *W_host, const float *bias_host);
+dn_status dn_cnn_get_filters(dn_cnn *net, int32_t block, float *W_host, float *bias_host);
+dn_status dn_cnn_get_filter_grads(dn_cnn *net, int32_t block, float *dW_host, float *dbias_host);
+dn_status dn_cnn_forward(dn_cnn *net, const float *X_dev, int32_t batch, float *out_dev);
+dn_status dn_cnn_train_epoch(dn_cnn *net, const float *X_dev, const int32_t *labels_dev, int64_t n_samples,
+                             int32_t batch, float lr, float momentum, float *mean_loss_host);
+
 /*
  * Measurement hooks (the paper times its two offloaded methods with wall-clock
  * timers, section "Experimental Evaluation"; here the device itself is timed).

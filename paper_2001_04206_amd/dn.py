@@ -36,6 +36,8 @@ EXPORTS = [
     "dn_conv_forward", "dn_conv_backward_workspace_bytes", "dn_conv_backward", "dn_maxpool_forward",
     "dn_maxpool_backward", "dn_input_gradient", "dn_sgd_step",
     "dn_conv_backward_static", "dn_conv_backward_static_limit",
+    "dn_cnn_arena_bytes", "dn_cnn_create", "dn_cnn_destroy", "dn_cnn_dense", "dn_cnn_flat_size",
+    "dn_cnn_set_filters", "dn_cnn_get_filters", "dn_cnn_get_filter_grads", "dn_cnn_forward", "dn_cnn_train_epoch",
 ]
 
 _lib = None
@@ -84,9 +86,22 @@ def lib():
         l.dn_kernel_time.argtypes = [vp, i32, C.POINTER(f32), C.POINTER(i64)]
         l.dn_kernel_flops.argtypes = [vp, i32, C.POINTER(C.c_double)]
         l.dn_set_option.argtypes = [vp, C.c_char_p, i64]
+        l.dn_cnn_arena_bytes.argtypes = [i32, i32, i32, vp, i32, vp, i32, i32]
+        l.dn_cnn_create.argtypes = [i32, i32, i32, vp, i32, vp, i32, vp, C.c_int, i32, vp, C.c_size_t, vp, C.POINTER(vp)]
+        l.dn_cnn_destroy.argtypes = [vp]
+        l.dn_cnn_dense.argtypes = [vp]
+        l.dn_cnn_flat_size.argtypes = [vp]
+        for f in (l.dn_cnn_set_filters, l.dn_cnn_get_filters, l.dn_cnn_get_filter_grads):
+            f.argtypes = [vp, i32, vp, vp]
+        l.dn_cnn_forward.argtypes = [vp, vp, i32, vp]
+        l.dn_cnn_train_epoch.argtypes = [vp, vp, vp, i64, i32, f32, f32, C.POINTER(f32)]
         for name in EXPORTS[2:]:
-            if name.endswith("_workspace_bytes") or name.endswith("_static_limit"):
+            if name.endswith("_workspace_bytes") or name.endswith("_static_limit") or name.endswith("_arena_bytes"):
                 getattr(l, name).restype = C.c_size_t
+            elif name == "dn_cnn_dense":
+                getattr(l, name).restype = vp
+            elif name == "dn_cnn_flat_size":
+                getattr(l, name).restype = i32
             else:
                 getattr(l, name).restype = C.c_int
         _lib = l
@@ -288,13 +303,17 @@ class Net:
     allocation) and the library handle; method names follow include/dn.h."""
 
     def __init__(self, widths: Sequence[int], acts: Sequence[int], loss: int, max_batch: int,
-                 device: str = "cuda:0"):
+                 device: str = "cuda:0", _borrowed=None):
         import torch
         self._torch = torch
         self.widths = [int(w) for w in widths]
         self.L = len(self.widths) - 1
         self.max_batch = int(max_batch)
         self.device = torch.device(device)
+        self._owned = _borrowed is None
+        if _borrowed is not None:      # a handle that another object (Cnn) owns and destroys
+            self._h = _borrowed
+            return
         nbytes = dn_net_arena_bytes(self.widths, self.max_batch)
         if nbytes == 0:
             raise DnError(DN_ERR_SHAPE, "dn_net_arena_bytes")
@@ -312,7 +331,8 @@ class Net:
 
     def close(self):
         if getattr(self, "_h", None):
-            lib().dn_net_destroy(self._h)
+            if self._owned:
+                lib().dn_net_destroy(self._h)
             self._h = None
 
     def __del__(self):
@@ -436,3 +456,99 @@ class Net:
 
     def dn_set_option(self, name: str, value: int):
         _check(lib().dn_set_option(self._h, name.encode(), int(value)), "dn_set_option")
+
+
+class Cnn:
+    """A convolutional classifier on the current device (dn_cnn_* of include/dn.h): blocks of
+    (c_out, k, stride, pad, act, pool_k, pool_stride) in front of a fully connected net.  Owns
+    the arena tensor and the library handle; `dense` is the fully connected part as a Net."""
+
+    def __init__(self, c: int, h: int, w: int, blocks: Sequence[Sequence[int]], dense_widths: Sequence[int],
+                 dense_acts: Sequence[int], loss: int, max_batch: int, device: str = "cuda:0"):
+        import torch
+        self._torch = torch
+        self.shape = (int(c), int(h), int(w))
+        self.blocks = [tuple(int(v) for v in b) for b in blocks]
+        if any(len(b) != 7 for b in self.blocks):
+            raise DnError(DN_ERR_INVALID_ARG, "dn_cnn_create")
+        self.max_batch = int(max_batch)
+        self.device = torch.device(device)
+        b_arr, b_p = _i32([v for b in self.blocks for v in b])
+        w_arr, w_p = _i32(dense_widths)
+        a_arr, a_p = _i32(dense_acts)
+        nbytes = int(lib().dn_cnn_arena_bytes(c, h, w, b_p, len(self.blocks), w_p, len(w_arr), self.max_batch))
+        if nbytes == 0:
+            raise DnError(DN_ERR_SHAPE, "dn_cnn_arena_bytes")
+        self.arena = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        self.stream = torch.cuda.current_stream(self.device)
+        handle = C.c_void_p()
+        with torch.cuda.device(self.device):
+            st = lib().dn_cnn_create(c, h, w, b_p, len(self.blocks), w_p, len(w_arr), a_p, int(loss), self.max_batch,
+                                     C.c_void_p(self.arena.data_ptr()), nbytes, C.c_void_p(self.stream.cuda_stream),
+                                     C.byref(handle))
+        _check(st, "dn_cnn_create")
+        self._h = handle
+        self.flat = int(lib().dn_cnn_flat_size(self._h))
+        self.dense = Net([self.flat] + [int(v) for v in dense_widths], dense_acts, loss, self.max_batch, device,
+                         _borrowed=C.c_void_p(lib().dn_cnn_dense(self._h)))
+        # filter shapes, block by block
+        self.filter_shapes, cin = [], int(c)
+        for b in self.blocks:
+            self.filter_shapes.append((b[0], cin, b[1], b[1]))
+            cin = b[0]
+
+    def close(self):
+        if getattr(self, "_h", None):
+            self.dense.close()
+            lib().dn_cnn_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def dn_cnn_set_filters(self, block: int, W: Optional[np.ndarray], bias: Optional[np.ndarray]):
+        if not 0 <= block < len(self.blocks):
+            raise DnError(DN_ERR_INVALID_ARG, "dn_cnn_set_filters")
+        Wc = None if W is None else np.ascontiguousarray(W, dtype=np.float32)
+        bc = None if bias is None else np.ascontiguousarray(bias, dtype=np.float32)
+        if Wc is not None and Wc.shape != self.filter_shapes[block]:
+            raise DnError(DN_ERR_SHAPE, "dn_cnn_set_filters")
+        if bc is not None and bc.shape != (self.filter_shapes[block][0],):
+            raise DnError(DN_ERR_SHAPE, "dn_cnn_set_filters")
+        _check(lib().dn_cnn_set_filters(self._h, block, None if Wc is None else Wc.ctypes.data_as(C.c_void_p),
+                                        None if bc is None else bc.ctypes.data_as(C.c_void_p)), "dn_cnn_set_filters")
+
+    def _get(self, fn, name, block):
+        if not 0 <= block < len(self.blocks):      # the host buffers below are sized from the block's shape
+            raise DnError(DN_ERR_INVALID_ARG, name)
+        W = np.empty(self.filter_shapes[block], dtype=np.float32)
+        b = np.empty(self.filter_shapes[block][0], dtype=np.float32)
+        _check(fn(self._h, block, W.ctypes.data_as(C.c_void_p), b.ctypes.data_as(C.c_void_p)), name)
+        return W, b
+
+    def dn_cnn_get_filters(self, block: int):
+        return self._get(lib().dn_cnn_get_filters, "dn_cnn_get_filters", block)
+
+    def dn_cnn_get_filter_grads(self, block: int):
+        return self._get(lib().dn_cnn_get_filter_grads, "dn_cnn_get_filter_grads", block)
+
+    def dn_cnn_forward(self, X, out=None):
+        t = self._torch
+        _shape_check(X, (int(X.shape[0]),) + self.shape, "X")
+        _check(lib().dn_cnn_forward(self._h, _dev_ptr(X, t.float32, "X"), int(X.shape[0]),
+                                    None if out is None else _dev_ptr(out, t.float32, "out")), "dn_cnn_forward")
+
+    def dn_cnn_train_epoch(self, X, labels, batch: int, lr: float, momentum: float,
+                           n_samples: Optional[int] = None) -> float:
+        t = self._torch
+        _shape_check(X, (int(X.shape[0]),) + self.shape, "X")
+        n = int(X.shape[0]) if n_samples is None else int(n_samples)
+        if n > int(X.shape[0]) or n > int(labels.shape[0]):
+            raise DnError(DN_ERR_SHAPE, "dn_cnn_train_epoch")
+        loss = C.c_float(0.0)
+        _check(lib().dn_cnn_train_epoch(self._h, _dev_ptr(X, t.float32, "X"), _dev_ptr(labels, t.int32, "labels"), n,
+                                        int(batch), float(lr), float(momentum), C.byref(loss)), "dn_cnn_train_epoch")
+        return float(loss.value)

@@ -161,3 +161,47 @@ def test_conv_and_pool_argument_checks(lib):
     assert lib.dn_sgd_step(p, p, p, 10, float("nan"), 0.0, None) == dn.DN_ERR_INVALID_ARG
     assert lib.dn_sgd_step(p, p, p, 0, 0.1, 0.0, None) == dn.DN_ERR_SHAPE
     assert lib.dn_input_gradient(None, 4, p) == dn.DN_ERR_INVALID_ARG
+
+
+def test_cnn_object_argument_checks(lib):
+    """Sizes of a convolutional classifier are checked on the host: the arena query returns 0 for
+    invalid ones, creation refuses bad arguments before anything is enqueued."""
+    def blocks(*rows):
+        arr = np.ascontiguousarray(rows, dtype=np.int32)
+        return arr, arr.ctypes.data_as(C.c_void_p), len(rows)
+    dense = np.array([16, 5], dtype=np.int32)
+    dp = dense.ctypes.data_as(C.c_void_p)
+    acts = np.array([2, 4], dtype=np.int32)
+    ap = acts.ctypes.data_as(C.c_void_p)
+    good, gp, gn = blocks((8, 3, 1, 1, 3, 2, 2), (4, 3, 1, 1, 2, 0, 0))
+    need = lib.dn_cnn_arena_bytes(3, 12, 12, gp, gn, dp, 2, 16)
+    # at least the filters three times over, the two convolution outputs twice, and the dense net
+    dense_widths = np.array([4 * 6 * 6, 16, 5], dtype=np.int32)
+    dense_need = lib.dn_net_arena_bytes(dense_widths.ctypes.data_as(C.c_void_p), 3, 16)
+    assert need >= 3 * 4 * (8 * 3 * 9 + 4 * 8 * 9) + 2 * 4 * 16 * (8 * 12 * 12 + 4 * 6 * 6) + dense_need and need % 256 == 0
+    assert lib.dn_cnn_arena_bytes(3, 12, 12, gp, gn, dp, 2, 32) > need                    # grows with the batch
+    for bad in ((8, 9, 1, 1, 3, 2, 2),      # 9 x 9 filters
+                (8, 3, 1, 3, 3, 2, 2),      # padding as wide as the filter
+                (8, 3, 0, 1, 3, 2, 2),      # stride 0
+                (8, 3, 1, 1, 4, 2, 2),      # softmax inside a block
+                (8, 3, 1, 1, 3, 13, 2),     # pooling window larger than the image
+                (0, 3, 1, 1, 3, 2, 2)):     # no output channels
+        _, bp, bn = blocks(bad)
+        assert lib.dn_cnn_arena_bytes(3, 12, 12, bp, bn, dp, 2, 16) == 0, bad
+    assert lib.dn_cnn_arena_bytes(3, 12, 12, gp, 0, dp, 2, 16) == 0
+    assert lib.dn_cnn_arena_bytes(3, 12, 12, gp, gn, dp, 0, 16) == 0
+    assert lib.dn_cnn_arena_bytes(3, 12, 12, gp, gn, dp, 2, 0) == 0
+    assert lib.dn_cnn_arena_bytes(3, 12, 12, None, gn, dp, 2, 16) == 0
+    out = C.c_void_p()
+    create = lambda arena, nbytes, o=C.byref(out): lib.dn_cnn_create(3, 12, 12, gp, gn, dp, 2, ap, 1, 16, C.c_void_p(arena),
+                                                                     C.c_size_t(nbytes), None, o)
+    assert create(0x10000, need, None) == dn.DN_ERR_INVALID_ARG
+    assert create(0, need) == dn.DN_ERR_INVALID_ARG
+    assert create(0x10010, need) == dn.DN_ERR_INVALID_ARG          # misaligned arena
+    assert create(0x10000, need - 1) == dn.DN_ERR_SHAPE            # arena too small
+    assert out.value is None
+    assert lib.dn_cnn_destroy(None) == dn.DN_ERR_INVALID_ARG
+    assert lib.dn_cnn_dense(None) is None and lib.dn_cnn_flat_size(None) == 0
+    assert lib.dn_cnn_forward(None, None, 1, None) == dn.DN_ERR_INVALID_ARG
+    assert lib.dn_cnn_train_epoch(None, None, None, 1, 1, 0.1, 0.0, None) == dn.DN_ERR_INVALID_ARG
+    assert lib.dn_cnn_set_filters(None, 0, None, None) == dn.DN_ERR_INVALID_ARG

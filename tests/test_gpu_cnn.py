@@ -218,3 +218,170 @@ def test_classifier_at_the_benchmark_shape(dn):
     4096-512-10), one step in the same launch configuration."""
     announce("convolutional classifier at the benchmark shape")
     run_classifier(dn, 128, 3, 32, 32, (32, 64), (512, 10), steps=1, seed=19, lr=0.01)
+
+
+def reference_cnn_epoch(shape, blocks, filters, biases, o, X, labels, batch, lr, mu, vel):
+    """One epoch of the classifier on the CPU checker's functions, in the order of the chain
+    rule: per batch forward through every block and the dense net, backward, then the update
+    v <- mu v - lr g, p <- p + v of every parameter.  filters / biases / vel are updated in
+    place; returns the epoch's mean loss."""
+    n, acc = X.shape[0], 0.0
+    for s0 in range(0, n, batch):
+        xb, yb = X[s0:s0 + batch], labels[s0:s0 + batch]
+        B = xb.shape[0]
+        a, kept = xb, []
+        for i, (cout, k, stride, pad, act, pk, ps) in enumerate(blocks):
+            Y = co.conv_forward("o32", a, filters[i], biases[i], stride, pad, act)
+            out = co.maxpool_forward("o32", Y, pk, ps) if pk > 0 else Y
+            kept.append((a, Y))
+            a = out
+        o.forward(a.reshape(B, -1))
+        acc += o.backward(yb) * B
+        d = o.input_gradient().reshape(a.shape)
+        grads = [None] * len(blocks)
+        for i in range(len(blocks) - 1, -1, -1):
+            cout, k, stride, pad, act, pk, ps = blocks[i]
+            a_in, Y = kept[i]
+            dA = co.maxpool_backward("o32", Y, d, pk, ps) if pk > 0 else d
+            _, d, dW, db = co.conv_backward("o32", a_in, filters[i], Y, dA, stride, pad, act)
+            grads[i] = (dW, db)
+        o.update(lr, mu)
+        for i, (dW, db) in enumerate(grads):
+            for p, g, v in ((filters[i], dW, vel[i][0]), (biases[i], db, vel[i][1])):
+                v[...] = (np.float32(mu) * v - np.float32(lr) * g).astype(np.float32)
+                p[...] = (p + v).astype(np.float32)
+    return acc / n
+
+
+CNN_OBJECT_CASES = [
+    # (c, h, w), blocks (c_out, k, stride, pad, act, pool_k, pool_stride), dense widths, n, batch, momentum
+    ((3, 12, 12), [(8, 3, 1, 1, RELU, 2, 2)], (24, 5), 40, 16, 0.0),                       # ragged last batch
+    ((2, 16, 20), [(5, 3, 1, 1, RELU, 2, 2), (9, 3, 1, 1, TANH, 0, 0)], (12, 4), 18, 6, 0.9),   # a block without pooling, momentum
+    ((1, 28, 28), [(6, 5, 1, 0, RELU, 2, 2), (16, 5, 1, 0, RELU, 2, 2)], (32, 10), 20, 10, 0.5),  # 5 x 5 filters, no padding
+    ((4, 9, 11), [(7, 3, 2, 1, SIG, 3, 2)], (10, 3), 9, 4, 0.0),                           # stride 2, overlapping 3 x 3 pooling
+]
+
+
+@pytest.mark.parametrize("shape,blocks,dense,n,batch,mu", CNN_OBJECT_CASES)
+def test_cnn_object_epochs_match_checker(dn, shape, blocks, dense, n, batch, mu):
+    """dn_cnn_train_epoch (every layer's forward, backward and update enqueued by the library,
+    two epochs) against the checker's functions chained by reference_cnn_epoch: loss of each
+    epoch, every filter, bias and dense parameter, then dn_cnn_forward's output."""
+    announce("cnn object shape=%s blocks=%s dense=%s n=%d batch=%d momentum=%g" % (shape, blocks, dense, n, batch, mu))
+    c, h, w = shape
+    rng = np.random.default_rng(23)
+    X = rng.standard_normal((n, c, h, w)).astype(np.float32)
+    labels = rng.integers(0, dense[-1], n).astype(np.int32)
+    acts = [TANH] * (len(dense) - 1) + [SOFTMAX]
+    net = dn.Cnn(c, h, w, blocks, dense, acts, CE, batch)
+    filters, biases, vel, cin = [], [], [], c
+    for i, (cout, k, stride, pad, act, pk, ps) in enumerate(blocks):
+        filters.append((rng.standard_normal((cout, cin, k, k)) * np.sqrt(2.0 / (cin * k * k))).astype(np.float32))
+        biases.append((rng.standard_normal(cout) * 0.1).astype(np.float32))
+        vel.append((np.zeros_like(filters[i]), np.zeros_like(biases[i])))
+        net.dn_cnn_set_filters(i, filters[i], biases[i])
+        cin = cout
+    widths = [net.flat] + list(dense)
+    Wd = [(rng.standard_normal((widths[l + 1], widths[l])) / np.sqrt(widths[l])).astype(np.float32) for l in range(len(dense))]
+    bd = [(rng.standard_normal(widths[l + 1]) * 0.1).astype(np.float32) for l in range(len(dense))]
+    net.dense.set_all(Wd, bd)
+    o = Oracle("o32", widths, acts, CE)
+    o.set_params(Wd, bd)
+    Xd, yd = dev(X), dev(labels)
+    lr = 0.05
+    for epoch in range(2):
+        loss = net.dn_cnn_train_epoch(Xd, yd, batch, lr, mu)
+        loss_r = reference_cnn_epoch(shape, blocks, filters, biases, o, X, labels, batch, lr, mu, vel)
+        assert abs(loss - loss_r) <= TOL * max(1.0, abs(loss_r)), (epoch, loss, loss_r)
+        for i in range(len(blocks)):
+            Wg, bg = net.dn_cnn_get_filters(i)
+            assert_close(Wg, filters[i], TOL, "filters of block %d, epoch %d" % (i, epoch))
+            assert_close(bg, biases[i], TOL, "biases of block %d, epoch %d" % (i, epoch))
+        Wr, br = o.get_params()
+        for l in range(1, len(widths)):
+            Wg, bg = net.dense.dn_get_params(l)
+            assert_close(Wg, Wr[l - 1], TOL, "W_%d, epoch %d" % (l, epoch))
+            assert_close(bg, br[l - 1], TOL, "b_%d, epoch %d" % (l, epoch))
+    # inference through the whole stack
+    B = min(batch, n)
+    out = torch.empty((B, dense[-1]), dtype=torch.float32, device="cuda:0")
+    net.dn_cnn_forward(Xd[:B].contiguous(), out)
+    a = X[:B]
+    for i, (cout, k, stride, pad, act, pk, ps) in enumerate(blocks):
+        a = co.conv_forward("o32", a, filters[i], biases[i], stride, pad, act)
+        if pk > 0:
+            a = co.maxpool_forward("o32", a, pk, ps)
+    assert_close(out.cpu().numpy(), o.forward(a.reshape(B, -1))[-1], TOL, "network output")
+    net.close()
+
+
+def test_cnn_object_equals_the_composed_calls(dn):
+    """The epoch loop adds nothing of its own: one dn_cnn_train_epoch step leaves the same bits as
+    the same calls made one by one from here (run_classifier's order)."""
+    announce("cnn object against the composed calls, bit for bit")
+    B, c, h, w, cout, K, pad, lr = 8, 3, 10, 10, 6, 3, 1, 0.05
+    rng = np.random.default_rng(5)
+    X = rng.standard_normal((B, c, h, w)).astype(np.float32)
+    labels = rng.integers(0, 4, B).astype(np.int32)
+    Wf = (rng.standard_normal((cout, c, K, K)) * 0.3).astype(np.float32)
+    bf = (rng.standard_normal(cout) * 0.1).astype(np.float32)
+    flat = cout * (h // 2) * (w // 2)
+    Wd = [(rng.standard_normal((4, flat)) / np.sqrt(flat)).astype(np.float32)]
+    bd = [np.zeros(4, dtype=np.float32)]
+    net = dn.Cnn(c, h, w, [(cout, K, 1, pad, RELU, 2, 2)], (4,), [SOFTMAX], CE, B)
+    net.dn_cnn_set_filters(0, Wf, bf)
+    net.dense.set_all(Wd, bd)
+    Xd, yd = dev(X), dev(labels)
+    net.dn_cnn_train_epoch(Xd, yd, B, lr, 0.0)
+    # the same step from single calls
+    f32 = dict(dtype=torch.float32, device="cuda:0")
+    W, b = dev(Wf), dev(bf)
+    Y, P = torch.empty((B, cout, h, w), **f32), torch.empty((B, cout, h // 2, w // 2), **f32)
+    dP, dY, delta = torch.empty_like(P), torch.empty_like(Y), torch.empty_like(Y)
+    dW, db = torch.empty_like(W), torch.empty_like(b)
+    dense = dn.Net([flat, 4], [SOFTMAX], CE, B)
+    dense.set_all(Wd, bd)
+    dn.dn_conv_forward(Xd, W, b, Y, 1, pad, RELU)
+    dn.dn_maxpool_forward(Y, P, 2, 2)
+    dense.dn_forward(P.view(B, flat))
+    dense.dn_backward(yd)
+    dense.dn_input_gradient(dP.view(B, flat))
+    dn.dn_maxpool_backward(Y, dP, dY, 2, 2)
+    dn.dn_conv_backward(Xd, W, Y, dY, delta, None, dW, db, 1, pad, RELU)
+    dense.dn_update(lr, 0.0)
+    dn.dn_sgd_step(W, dW, None, lr, 0.0)
+    dn.dn_sgd_step(b, db, None, lr, 0.0)
+    Wg, bg = net.dn_cnn_get_filters(0)
+    assert np.array_equal(Wg, W.cpu().numpy()) and np.array_equal(bg, b.cpu().numpy())
+    W1, b1 = net.dense.dn_get_params(1)
+    W2, b2 = dense.dn_get_params(1)
+    assert np.array_equal(W1, W2) and np.array_equal(b1, b2)
+    dense.close()
+    net.close()
+
+
+def test_cnn_object_argument_errors(dn):
+    announce("cnn object: argument errors")
+    with pytest.raises(dn.DnError) as e:
+        dn.Cnn(3, 8, 8, [(4, 9, 1, 1, RELU, 2, 2)], (5,), [SOFTMAX], CE, 4)          # 9 x 9 filters
+    assert e.value.status == dn.DN_ERR_SHAPE
+    with pytest.raises(dn.DnError) as e:
+        dn.Cnn(3, 8, 8, [(4, 3, 1, 1, SOFTMAX, 2, 2)], (5,), [SOFTMAX], CE, 4)       # softmax inside a block
+    assert e.value.status == dn.DN_ERR_SHAPE
+    with pytest.raises(dn.DnError) as e:
+        dn.Cnn(3, 8, 8, [(4, 3, 1, 1, RELU, 2, 2)], (5,), [TANH], CE, 4)             # cross-entropy without softmax
+    assert e.value.status == dn.DN_ERR_UNSUPPORTED
+    net = dn.Cnn(3, 8, 8, [(4, 3, 1, 1, RELU, 2, 2)], (5,), [SOFTMAX], CE, 4)
+    X = torch.zeros((6, 3, 8, 8), dtype=torch.float32, device="cuda:0")
+    y = torch.zeros(6, dtype=torch.int32, device="cuda:0")
+    with pytest.raises(dn.DnError) as e:
+        net.dn_cnn_train_epoch(X, y, 5, 0.1, 0.0)                                     # batch above max_batch
+    assert e.value.status == dn.DN_ERR_SHAPE
+    with pytest.raises(dn.DnError) as e:
+        net.dn_cnn_train_epoch(X, y, 4, 0.1, 1.0)                                     # momentum outside [0, 1)
+    assert e.value.status == dn.DN_ERR_INVALID_ARG
+    with pytest.raises(dn.DnError) as e:
+        net.dn_cnn_set_filters(1, None, None)                                         # no such block
+    assert e.value.status == dn.DN_ERR_INVALID_ARG
+    assert net.dn_cnn_train_epoch(X, y, 4, 0.0, 0.0) == pytest.approx(np.log(5.0), rel=1e-5)   # zero parameters, zero rate: uniform output
+    net.close()

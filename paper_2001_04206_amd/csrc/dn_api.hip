@@ -69,7 +69,8 @@ bool compute_layout(const int32_t *widths, int32_t n_widths, int32_t max_batch, 
     lo.off_hit_rows = o; o += align_up((size_t)max_batch * sizeof(float));
     lo.off_loss_sums = o; o += align_up((size_t)max_batch * sizeof(double));
     lo.off_scalars = o; o += kAlign;
-    lo.online_bytes = std::max(online_exchange_bytes_bound(widths, L), twin_exchange_bytes_bound(widths, L));
+    lo.online_bytes = std::max({online_exchange_bytes_bound(widths, L), twin_exchange_bytes_bound(widths, L),
+                                wide_exchange_bytes_bound(widths, L)});
     lo.off_online = o; o += align_up(lo.online_bytes);
     lo.off_gemm_ws = o; o += align_up(GEMM_WS_FLOATS * sizeof(float));
     lo.off_gemm_counters = o; o += align_up(GEMM_COUNTERS * sizeof(unsigned));
@@ -105,13 +106,15 @@ struct dn_net {
     bool w1_as_in_bwd = false;   // W_1 is still the matrix the last dn_backward propagated through
     // options
     int time_kernels = 0, gemm_variant = -1, online_mode = 0, online_min_tile = ON_DEFAULT_MIN_TILE,
-        online_resident = 1, online_twin = 1, online_tiny = 1, split_k_on = 1, merge_launches = 1;
+        online_resident = 1, online_twin = 1, online_tiny = 1, online_wide = 1, split_k_on = 1, merge_launches = 1;
     // persistent batch-1 kernel
     OnlineGeom geom{};
     bool online_ok = false;
     bool online_prepared = false, batch_prepared = false, deep_prepared = false;   // LDS limits raised at creation
     bool twin_ready = false;   // the two-copy batch-1 kernel's LDS limit is raised
     bool tiny_ready = false;   // the one-wave batch-1 kernel's LDS limit is raised
+    bool wide_ready = false;   // the wide-hidden-layer batch-1 kernel's LDS limit is raised
+    bool wide_ok = false;      // ... and the net suits it (plain gradient descent only)
     int last_schedule = DN_SCHED_NONE;   // how the last dn_train_epoch ran
     uint32_t online_seq = 0;   // last step number stamped into the exchange buffers
     // persistent minibatch kernel (one- and two-layer nets)
@@ -172,8 +175,13 @@ namespace {
 void refresh_persistent(dn_net *net)
 {
     const int L = net->L;
-    net->online_ok = net->batch_ok = net->deep_ok = false;
+    net->online_ok = net->batch_ok = net->deep_ok = net->wide_ok = false;
     if (net->device_cus <= 0) return;
+    if (net->wide_ready) {
+        WideGeom wg;
+        net->wide_ok = wide_geometry(net->n.data(), L, net->device_cus, wg) &&
+                       wg.words * sizeof(unsigned long long) <= net->lo.online_bytes;
+    }
     if (net->online_prepared && online_geometry(net->n.data(), L, net->online_min_tile, false, net->geom))
         net->online_ok = net->geom.grid <= net->device_cus;
     if (net->batch_prepared) {
@@ -410,6 +418,41 @@ dn_status run_twin(dn_net *net, const TwinGeom &g, const float *X, const int32_t
     return DN_OK;
 }
 
+// Batch-1 epochs of a two-layer net with a wide hidden layer: most of W_1 stays in LDS and registers.
+dn_status run_wide(dn_net *net, const WideGeom &g, const float *X, const int32_t *labels, int64_t n_samples, float lr,
+                   bool timing)
+{
+    WidePlan p{};
+    p.W1 = net->W(1); p.b1 = net->b(1); p.VW1 = net->VW(1); p.Vb1 = net->Vb(1);
+    p.W2 = net->W(2); p.b2 = net->b(2); p.VW2 = net->VW(2); p.Vb2 = net->Vb(2);
+    p.z_x = net->exchange();
+    p.abort_flag = net->abort_flag();
+    p.loss_acc = net->epoch_acc();
+    p.n0 = net->n[0]; p.n1 = net->n[1]; p.nL = net->n[2];
+    p.act1 = net->act[1]; p.actL = net->act[2]; p.loss = net->loss;
+    p.per = g.per; p.lds_rows = g.lds_rows;
+    p.lr = lr;
+    p.lds_x = g.lds_x; p.lds_a = g.lds_a; p.lds_d = g.lds_d; p.lds_b = g.lds_b; p.lds_z = g.lds_z; p.lds_w2 = g.lds_w2;
+    p.lds_zall = g.lds_zall; p.lds_out = g.lds_out; p.lds_w1 = g.lds_w1;
+    const int64_t chunk = (int64_t)1 << 30;
+    for (int64_t s0 = 0; s0 < n_samples; s0 += chunk) {
+        const int64_t n = (n_samples - s0) < chunk ? (n_samples - s0) : chunk;
+        if ((uint64_t)net->online_seq + (uint64_t)n + 2 > 0xffffffffull) {   // step numbers would wrap
+            DN_HIP(hipMemsetAsync(net->exchange(), 0, net->lo.online_bytes, net->stream));
+            net->online_seq = 0;
+        }
+        p.X = X + (size_t)s0 * net->n[0];
+        p.labels = labels + s0;
+        p.n_samples = n;
+        p.keep_v = (s0 + n >= n_samples) ? 1 : 0;
+        p.seq0 = net->online_seq;
+        ScopedTimer st(net, DN_K_ONLINE, timing);
+        DN_HIP(launch_wide_epoch(g, p, net->stream));
+        net->online_seq += (uint32_t)n;
+    }
+    return DN_OK;
+}
+
 // A whole batch-1 epoch in persistent-kernel launches of at most 2^30 steps each.
 dn_status run_online(dn_net *net, const float *X, const int32_t *labels, int64_t n_samples, float lr, float mu,
                      bool timing)
@@ -428,6 +471,14 @@ dn_status run_online(dn_net *net, const float *X, const int32_t *labels, int64_t
         if (twin_geometry(net->n.data(), L, net->online_min_tile, tg) && tg.grid <= net->device_cus) {
             net->last_schedule = DN_SCHED_TWO_COPY;
             return run_twin(net, tg, X, labels, n_samples, lr, timing);
+        }
+    }
+    if (mu == 0.f && net->online_wide && net->wide_ok) {
+        // two layers, the hidden one too wide for LDS: most of its rows stay in LDS and registers
+        WideGeom wg;
+        if (wide_geometry(net->n.data(), L, net->device_cus, wg)) {
+            net->last_schedule = DN_SCHED_WIDE_HIDDEN;
+            return run_wide(net, wg, X, labels, n_samples, lr, timing);
         }
     }
     OnlineGeom g;   // same slices as net->geom; LDS residency depends on whether velocities are read
@@ -682,6 +733,7 @@ dn_status dn_net_create(const int32_t *widths, int32_t n_widths, const dn_act *a
         net->online_prepared = lo.online_bytes > 0 && online_prepare() == hipSuccess;
         net->twin_ready = lo.online_bytes > 0 && twin_exchange_bytes_bound(net->n.data(), L) > 0 && twin_prepare() == hipSuccess;
         net->tiny_ready = tiny_prepare() == hipSuccess;
+        net->wide_ready = lo.online_bytes > 0 && wide_exchange_bytes_bound(net->n.data(), L) > 0 && wide_prepare() == hipSuccess;
         net->batch_prepared = lo.batch_bytes > 0 && batch_prepare() == hipSuccess;
         net->deep_prepared = lo.deep_bytes > 0 && deep_prepare() == hipSuccess;
         (void)hipGetLastError();
@@ -851,8 +903,11 @@ dn_status dn_train_epoch(dn_net *net, const float *X_dev, const int32_t *labels_
     const bool timing = net->time_kernels != 0;
     net->timed = 0;
     const int L = net->L;
-    bool persistent = batch == 1 && net->online_mode != 1 && net->online_ok;
-    if (batch == 1 && net->online_mode == 2 && !net->online_ok) return DN_ERR_UNSUPPORTED;
+    // (a two-layer net with a very wide hidden layer may suit only the kernel for such nets, which does plain
+    // gradient descent)
+    const bool online_fit = net->online_ok || (momentum == 0.f && net->online_wide && net->wide_ok);
+    bool persistent = batch == 1 && net->online_mode != 1 && online_fit;
+    if (batch == 1 && net->online_mode == 2 && !online_fit) return DN_ERR_UNSUPPORTED;
     const bool pbatch = batch > 1 && net->batch_mode != 1 && net->batch_ok &&
                         (net->batch_mode == 2 || batch_pays(net, batch));
     const bool pdeep = batch > 1 && net->batch_mode != 1 && net->deep_ok && momentum == 0.f &&
@@ -1094,6 +1149,9 @@ dn_status dn_set_option(dn_net *net, const char *name, int64_t value)
     } else if (!strcmp(name, "online_twin")) {
         if (value != 0 && value != 1) return DN_ERR_INVALID_ARG;
         net->online_twin = (int)value;
+    } else if (!strcmp(name, "online_wide")) {
+        if (value != 0 && value != 1) return DN_ERR_INVALID_ARG;
+        net->online_wide = (int)value;
     } else {
         return DN_ERR_INVALID_ARG;
     }

@@ -336,6 +336,44 @@ size_t twin_exchange_bytes_bound(const int32_t *n, int L);
 hipError_t twin_prepare();
 hipError_t launch_twin_epoch(const TwinGeom &g, const TwinPlan &plan, hipStream_t stream);
 
+// ---- batch-1 epochs of two-layer nets with a wide hidden layer and a narrow output layer (dn_wide.hip) ----
+// A workgroup (256 threads: one wave per SIMD, so a lane may hold 512 registers) owns a block of hidden
+// units; their rows of W_1 live in LDS, in registers (WIDE_REG_ROWS rows per group of sixteen lanes,
+// WIDE_NI float4 pieces per lane and row) and, for the rest, in device memory.  What crosses workgroups
+// per step: one partial net input per output unit and workgroup.
+constexpr int WIDE_THREADS = 256;
+constexpr int WIDE_NI = 6;          // rows of at most 64 * WIDE_NI = 384 inputs
+constexpr int WIDE_REG_ROWS = 12;   // 24 registers each per lane: 288 of a lane's 512 (13 rows spill)
+constexpr int WIDE_MAX_NL = 16;     // output units
+struct WideGeom {
+    bool ok;
+    int per, grid;        // hidden units per workgroup, workgroups
+    int lds_rows;         // rows of a workgroup's block that live in LDS
+    size_t words;         // exchange region, in 64-bit words
+    int lds_x, lds_a, lds_d, lds_b, lds_z, lds_w2, lds_zall, lds_out, lds_w1, lds_floats;
+};
+
+struct WidePlan {
+    float *W1, *b1, *W2, *b2, *VW1, *Vb1, *VW2, *Vb2;
+    unsigned long long *z_x;    // [2][grid][nL] partial net inputs of the output layer
+    int *abort_flag;
+    double *loss_acc;
+    const float *X;
+    const int32_t *labels;
+    int64_t n_samples;
+    int n0, n1, nL, act1, actL, loss, per, lds_rows, keep_v;
+    float lr;
+    uint32_t seq0;
+    int lds_x, lds_a, lds_d, lds_b, lds_z, lds_w2, lds_zall, lds_out, lds_w1;
+};
+
+// false if the net does not suit the kernel (not two layers, inputs not a multiple of 4 or above 384,
+// more than 16 outputs, or a hidden layer whose rows all fit in LDS anyway).
+bool wide_geometry(const int32_t *n, int L, int max_wg, WideGeom &g);
+size_t wide_exchange_bytes_bound(const int32_t *n, int L);
+hipError_t wide_prepare();
+hipError_t launch_wide_epoch(const WideGeom &g, const WidePlan &plan, hipStream_t stream);
+
 // ---- batch-1 epochs of very small nets on one wavefront (dn_tiny.hip) ----
 // Every width at most 64: lane j is unit j of each layer; parameters, activations and deltas in LDS.
 struct TinyLayer {

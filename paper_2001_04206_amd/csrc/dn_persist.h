@@ -12,7 +12,13 @@ namespace {
 typedef unsigned long long u64;
 typedef float v4f __attribute__((ext_vector_type(4)));
 
+// Threads per workgroup: ON_THREADS unless the including file sets DN_PERSIST_THREADS first (a
+// kernel that wants fewer, fatter threads: half the threads may hold twice the registers each).
+#ifdef DN_PERSIST_THREADS
+constexpr int kThreads = DN_PERSIST_THREADS;
+#else
 constexpr int kThreads = ON_THREADS;
+#endif
 constexpr int kWaves = kThreads / 64;
 constexpr int kSpinLimit = 1 << 21;   // polls of ~0.5 us each: about a second
 constexpr int kPollBatch = 4;         // words each thread keeps in flight while polling (eight measured no faster)
@@ -190,10 +196,10 @@ static hipError_t launch_resident(Kernel kernel, const Plan &plan, int grid, siz
     hipError_t e = hipGetDevice(&dev);
     if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     if (e == hipSuccess)
-        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(kernel), ON_THREADS, lds_bytes);
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(kernel), kThreads, lds_bytes);
     if (e != hipSuccess) return e;
     if (grid < 1 || per_cu < 1 || (long)grid > (long)per_cu * cus) return hipErrorCooperativeLaunchTooLarge;
-    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(ON_THREADS), lds_bytes, stream, plan);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(kThreads), lds_bytes, stream, plan);
     return hipGetLastError();
 }
 

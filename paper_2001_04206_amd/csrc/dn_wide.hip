@@ -1,0 +1,426 @@
+// Per-sample (batch 1) training, plain gradient descent, of two-layer nets whose hidden layer is
+// too wide for LDS and whose output layer is narrow -- the shape of the network the paper trains
+// (340 inputs, 100000 hidden units, 10 softmax outputs; section "Experimental Evaluation") -- as
+// ONE persistent kernel per epoch that keeps most of W_1 on the chip.
+//
+// A workgroup owns a block of hidden units: their rows of W_1, their biases, their columns of W_2.
+// What a step needs from other workgroups is one number per output unit and workgroup (the partial
+// net inputs of the output layer), exchanged as stamped words (dn_persist.h); everything else is
+// local.  The cost of a step is then the sweep over the own rows of W_1 -- the rank-1 update
+// W_1[r] -= lr delta_r x, fused with the next sample's product z_r = W_1[r] x' on the row while it
+// is at hand -- and the sweep is as fast as the rows are near:
+//   tier 1   rows in LDS (what is left of it after the small vectors and the columns of W_2);
+//   tier 2   rows in REGISTERS: sixteen lanes share a row, a lane keeps its 6 float4 pieces of RR
+//            rows for the whole launch (24 RR registers), so 16 RR rows per workgroup never leave
+//            the register file between the launch's first and last step;
+//   tier 3   the remaining rows stream from and to device memory, 8 bytes per weight and step.
+// A workgroup has 256 threads, one wave per SIMD, which lets a lane hold 512 registers (256 plus the
+// 256 accumulation registers, which the compiler uses as a second home for values it cannot keep in
+// the first 256): the sweep's working set is about 170 registers per lane whatever the thread count,
+// so fewer, fatter threads leave more of the register file to the weights.  RR = 12 keeps 288
+// registers per lane for them.  For the paper's network (391 rows of 340 floats per workgroup) that is
+// 93 rows in LDS, 192 in registers and 106 streamed: a quarter of the bytes the all-streaming sweep moves.
+// At the end of the launch tiers 1 and 2, the biases and the columns of W_2 go back to device memory.
+#include <algorithm>
+#include <type_traits>
+
+#define DN_PERSIST_THREADS 256   // = WIDE_THREADS
+#include "dn_internal.h"
+#include "dn_persist.h"
+#include "dn_wave.h"
+
+namespace dn {
+namespace {
+
+static_assert(kThreads == WIDE_THREADS, "the thread count is set before dn_persist.h is included");
+constexpr int WNI = WIDE_NI;   // float4 pieces of a row per lane (rows of up to 64 * WNI floats)
+constexpr int kPass = kWaves * 4;   // rows a workgroup works on at a time: sixteen lanes each
+#ifndef WIDE_STREAM_RU
+#define WIDE_STREAM_RU 2        // row groups of the streamed tier in flight per wave
+#endif
+
+// This lane's pieces of a vector of n4 float4s (zeros past the end).
+__device__ __forceinline__ void lane_pieces(v4f (&dst)[WNI], const float *src, int n4, int g)
+{
+#pragma unroll
+    for (int j = 0; j < WNI; ++j) {
+        const int c = g + 16 * j;
+        dst[j] = c < n4 ? *(const v4f *)(src + 4 * c) : (v4f){0.f, 0.f, 0.f, 0.f};
+    }
+}
+
+__device__ __forceinline__ float dot_pieces(const v4f (&w)[WNI], const v4f (&x)[WNI])
+{
+    float acc = 0.f;
+#pragma unroll
+    for (int j = 0; j < WNI; ++j) acc += w[j].x * x[j].x + w[j].y * x[j].y + w[j].z * x[j].z + w[j].w * x[j].w;
+    return acc;
+}
+
+// Rows in memory (LDS or device): nr rows of n floats at Wt; row r of the block takes delta dl[r]
+// and leaves its product with the next sample in out[r].  Sixteen lanes per row, four rows per wave
+// at a time, RU such groups in flight.  Loads are unconditional (clamped addresses); columns past
+// the end hold zeros in a4 / x4 and are never stored.  keepv: the applied change also goes to Vt.
+template <bool UPDATE, bool DOT, int RU>
+__device__ __forceinline__ void sweep_mem(float *__restrict__ Wt, float *__restrict__ Vt, int n, int nr, const float *dl,
+                                          const v4f (&a4)[WNI], const v4f (&x4)[WNI], float lr, bool keepv, float *out)
+{
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int sg = lane >> 4, g = lane & 15;
+    const int n4 = n >> 2;
+    for (int base = 0; base < nr; base += kPass * RU) {
+        v4f wv[RU][WNI];
+        int row[RU];
+#pragma unroll
+        for (int u = 0; u < RU; ++u) {
+            row[u] = base + u * kPass + wave * 4 + sg;
+            const float *wp = Wt + (size_t)min(row[u], nr - 1) * n;
+#pragma unroll
+            for (int j = 0; j < WNI; ++j) wv[u][j] = *(const v4f *)(wp + 4 * min(g + 16 * j, n4 - 1));
+        }
+#pragma unroll
+        for (int u = 0; u < RU; ++u) {
+            const bool rin = row[u] < nr;
+            const int rc = min(row[u], nr - 1);
+            if (UPDATE) {
+                const float ld = lr * dl[rc];
+                float *wp = Wt + (size_t)rc * n;
+#pragma unroll
+                for (int j = 0; j < WNI; ++j) {
+                    const int c = g + 16 * j;
+                    const v4f dv = (v4f){ld * a4[j].x, ld * a4[j].y, ld * a4[j].z, ld * a4[j].w};
+                    wv[u][j] = wv[u][j] - dv;
+                    if (rin && c < n4) {
+                        *(v4f *)(wp + 4 * c) = wv[u][j];
+                        if (keepv) *(v4f *)(Vt + (size_t)rc * n + 4 * c) = -dv;
+                    }
+                }
+            }
+            if (DOT) {
+                const float acc = row16_sum(dot_pieces(wv[u], x4));
+                if (g == 0 && rin) out[row[u]] = acc;
+            }
+        }
+    }
+}
+
+// Rows in registers: wres[i] is this lane's part of row i * kPass + wave * 4 + sg of the tier.
+template <bool UPDATE, bool DOT, int RR>
+__device__ __forceinline__ void sweep_regs(v4f (&wres)[RR > 0 ? RR : 1][WNI], float *__restrict__ Vt, int n, int nr,
+                                           const float *dl, const v4f (&a4)[WNI], const v4f (&x4)[WNI], float lr, bool keepv,
+                                           float *out)
+{
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int sg = lane >> 4, g = lane & 15;
+    const int n4 = n >> 2;
+#pragma unroll
+    for (int i = 0; i < RR; ++i) {
+        const int row = i * kPass + wave * 4 + sg;
+        const bool rin = row < nr;
+        const int rc = rin ? row : 0;
+        if (UPDATE) {
+            const float ld = rin ? lr * dl[rc] : 0.f;
+#pragma unroll
+            for (int j = 0; j < WNI; ++j) {
+                const v4f dv = (v4f){ld * a4[j].x, ld * a4[j].y, ld * a4[j].z, ld * a4[j].w};
+                wres[i][j] = wres[i][j] - dv;
+                if (keepv && rin && g + 16 * j < n4) *(v4f *)(Vt + (size_t)rc * n + 4 * (g + 16 * j)) = -dv;
+            }
+        }
+        if (DOT) {
+            const float acc = row16_sum(dot_pieces(wres[i], x4));
+            if (g == 0 && rin) out[row] = acc;
+        }
+        // one row at a time: interleaving the rows' arithmetic would need a second set of registers
+        // for the rows in flight, and the registers are what this tier is short of
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+// The three tiers of a workgroup's rows: streamed (ns rows at Ws), registers (nrr), LDS (nl rows at Wl);
+// local row numbers run LDS, registers, streamed.  V: the block's rows of the velocity (device memory).
+struct SweepArgs {
+    float *Ws, *Wl, *V;
+    const float *d;
+    float *z;
+    int n, nl, nrr, ns;
+    float lr;
+};
+
+template <bool U, bool D, int RR>
+__device__ __forceinline__ void sweep_all(v4f (&wres)[RR > 0 ? RR : 1][WNI], const SweepArgs &sa, const v4f (&a4)[WNI],
+                                          const v4f (&x4)[WNI], bool keepv)
+{
+    const int first_s = sa.nl + sa.nrr;
+    if (sa.ns > 0)
+        sweep_mem<U, D, WIDE_STREAM_RU>(sa.Ws, sa.V + (size_t)first_s * sa.n, sa.n, sa.ns, sa.d + first_s, a4, x4, sa.lr, keepv,
+                                        sa.z + first_s);
+    if (RR > 0 && sa.nrr > 0)
+        sweep_regs<U, D, RR>(wres, sa.V + (size_t)sa.nl * sa.n, sa.n, sa.nrr, sa.d + sa.nl, a4, x4, sa.lr, keepv, sa.z + sa.nl);
+    if (sa.nl > 0) sweep_mem<U, D, 1>(sa.Wl, sa.V, sa.n, sa.nl, sa.d, a4, x4, sa.lr, keepv, sa.z);
+}
+
+template <int RR>
+__global__ __launch_bounds__(kThreads) void wide_epoch_kernel(WidePlan p)
+{
+    extern __shared__ __align__(16) float lds[];
+    __shared__ int s_abort;
+    const int w = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int sg = lane >> 4, g = lane & 15;
+    const int n0 = p.n0, n1 = p.n1, nL = p.nL, per = p.per, perp = (per + 3) & ~3, grid = (int)gridDim.x;
+    const int n4 = n0 >> 2, n0p = (n0 + 3) & ~3;
+    const int r0 = w * per, nr = max(0, min(per, n1 - r0));
+    // the three tiers of the own rows
+    const int nl = min(p.lds_rows, nr);
+    const int nrr = min(kPass * RR, nr - nl);
+    const int ns = nr - nl - nrr;
+    float *xbuf = lds + p.lds_x;
+    float *a_own = lds + p.lds_a, *d_own = lds + p.lds_d, *b1 = lds + p.lds_b, *z1 = lds + p.lds_z;
+    float *W2c = lds + p.lds_w2;                    // [nL][perp]: the own columns of W_2
+    float *zall = lds + p.lds_zall;                 // [grid][nL] partial net inputs of the output layer
+    float *zL = lds + p.lds_out, *dL = zL + WIDE_MAX_NL, *bL = dL + WIDE_MAX_NL;
+    float *W1l = lds + p.lds_w1;                    // tier 1
+    float *W1r = p.W1 + (size_t)(r0 + nl) * n0;     // tier 2's rows in device memory (prologue / epilogue)
+    float *W1s = p.W1 + (size_t)(r0 + nl + nrr) * n0;   // tier 3
+    float *V1 = p.VW1 + (size_t)r0 * n0;
+
+    // ---- prologue ----
+    if (tid == 0) s_abort = 0;
+    for (int k = tid; k < nL; k += kThreads) bL[k] = p.b2[k];
+    for (int j = tid; j < nr; j += kThreads) b1[j] = p.b1[r0 + j];
+    for (int i = tid; i < nL * perp; i += kThreads) {
+        const int k = i / perp, j = i - k * perp;
+        W2c[i] = j < nr ? p.W2[(size_t)k * n1 + r0 + j] : 0.f;
+    }
+    copy_floats(W1l, p.W1 + (size_t)r0 * n0, nl * n0);
+    v4f wres[RR > 0 ? RR : 1][WNI];
+#pragma unroll
+    for (int i = 0; i < RR; ++i) {
+        const int row = min(i * kPass + wave * 4 + sg, max(nrr - 1, 0));
+#pragma unroll
+        for (int j = 0; j < WNI; ++j) {
+            const int c = g + 16 * j;
+            wres[i][j] = (nrr > 0 && c < n4) ? *(const v4f *)(W1r + (size_t)row * n0 + 4 * c) : (v4f){0.f, 0.f, 0.f, 0.f};
+        }
+    }
+    for (int k = tid; k < n0; k += kThreads) xbuf[k] = p.X[k];
+    int y_cur = p.labels[0];
+    double loss_acc = 0.0;
+    __syncthreads();
+
+    // one sweep over all three tiers: rows take d_own, products with x4 go to z1
+    const SweepArgs sa{W1s, W1l, V1, d_own, z1, n0, nl, nrr, ns, p.lr};
+    {   // the first sample's products with W_1
+        v4f a4[WNI], x4[WNI];
+        lane_pieces(x4, xbuf, n4, g);
+#pragma unroll
+        for (int j = 0; j < WNI; ++j) a4[j] = (v4f){0.f, 0.f, 0.f, 0.f};
+        sweep_all<false, true, RR>(wres, sa, a4, x4, false);
+    }
+    __syncthreads();
+
+    for (int64_t s = 0; s < p.n_samples; ++s) {
+        const uint32_t seq = p.seq0 + 1u + (uint32_t)s;
+        const int par = (int)(seq & 1u);
+        const bool more = s + 1 < p.n_samples;
+        const bool keepv = p.keep_v && !more;   // the epoch's last step also leaves the applied change as velocity
+        const float *x = xbuf + (size_t)(s & 1) * n0p;
+        float *xn = xbuf + (size_t)((s + 1) & 1) * n0p;
+
+        // ---- hidden layer: activations of the own units, then their share of the output layer's net inputs ----
+        for (int j = tid; j < nr; j += kThreads) a_own[j] = act_fn(p.act1, z1[j] + b1[j]);
+        for (int j = nr + tid; j < perp; j += kThreads) a_own[j] = 0.f;
+        __syncthreads();
+        u64 *pub = p.z_x + ((size_t)par * grid + w) * nL;
+        for (int k = wave; k < nL; k += kWaves) {
+            const float *wr = W2c + k * perp;
+            float acc = 0.f;
+            for (int j = lane * 4; j < perp; j += 256) {
+                const v4f av = *(const v4f *)(a_own + j), wv = *(const v4f *)(wr + j);
+                acc += wv.x * av.x + wv.y * av.y + wv.z * av.z + wv.w * av.w;
+            }
+            acc = wave_sum(acc);
+            if (lane == 0) {
+                if (grid > 1) ll_store(pub + k, acc, seq);
+                else zall[k] = acc;
+            }
+        }
+        // while the partials travel: the next sample's features and label
+        constexpr int XR = (64 * WNI + kThreads - 1) / kThreads;
+        float xr[XR];
+        int y_next = 0;
+        if (more) {
+#pragma unroll
+            for (int u = 0; u < XR; ++u) {
+                const int k = tid + u * kThreads;
+                xr[u] = k < n0 ? p.X[(size_t)(s + 1) * n0 + k] : 0.f;
+            }
+            y_next = p.labels[s + 1];
+        }
+        if (grid > 1) {
+            const u64 *src = p.z_x + (size_t)par * grid * nL;
+            poll_words(grid * nL, seq, [&](int q) { return src + q; }, [&](int q, float v) { zall[q] = v; }, p.abort_flag,
+                       &s_abort);
+        }
+        if (more) {
+#pragma unroll
+            for (int u = 0; u < XR; ++u) {
+                const int k = tid + u * kThreads;
+                if (k < n0) xn[k] = xr[u];
+            }
+        }
+        __syncthreads();
+        if (s_abort) break;
+        // z_L = sum of the partials in workgroup order (the same order everywhere) + b_L
+        for (int k = wave; k < nL; k += kWaves) {
+            float acc = 0.f;
+            for (int q = lane; q < grid; q += 64) acc += zall[q * nL + k];
+            acc = wave_sum(acc);
+            if (lane == 0) zL[k] = acc + bL[k];
+        }
+        __syncthreads();
+
+        // ---- output layer, repeated by every workgroup: loss and delta_L (wave 0) ----
+        int y = y_cur;
+        y = y < 0 ? 0 : (y >= nL ? nL - 1 : y);
+        if (wave == 0) {
+            const int k0 = lane;
+            const float z0 = k0 < nL ? zL[k0] : -INFINITY;
+            float d0, e;
+            if (p.loss == DN_LOSS_CROSS_ENTROPY) {
+                const float e_m = wave_max(z0);
+                const float e0 = k0 < nL ? expf(z0 - e_m) : 0.f;
+                const float e_sum = wave_sum(e0);
+                d0 = e0 * (1.0f / e_sum) - (k0 == y ? 1.0f : 0.0f);
+                e = logf(e_sum) - (zL[y] - e_m);
+            } else {
+                const float a0 = act_fn(p.actL, z0);
+                const float f0 = a0 - (k0 == y ? 1.0f : 0.0f);
+                d0 = f0 * act_deriv(p.actL, a0);
+                e = wave_sum(k0 < nL ? 0.5f * f0 * f0 : 0.f);
+            }
+            if (k0 < nL) {
+                dL[k0] = d0;
+                bL[k0] = bL[k0] - p.lr * d0;
+                if (keepv && w == 0) p.Vb2[k0] = -(p.lr * d0);
+            }
+            if (w == 0 && lane == 0) loss_acc += (double)e;
+        }
+        __syncthreads();
+
+        // ---- deltas of the own hidden units through W_2 as it was; W_2's own columns and b_1 updated ----
+        for (int j = tid; j < nr; j += kThreads) {
+            const float a = a_own[j];
+            float sacc = 0.f;
+            for (int k = 0; k < nL; ++k) {
+                const float wv = W2c[k * perp + j], dk = dL[k];
+                sacc += wv * dk;
+                const float ch = -((p.lr * dk) * a);
+                W2c[k * perp + j] = wv + ch;
+                if (keepv) p.VW2[(size_t)k * n1 + r0 + j] = ch;
+            }
+            const float d = sacc * act_deriv(p.act1, a);
+            d_own[j] = d;
+            b1[j] = b1[j] - p.lr * d;
+            if (keepv) p.Vb1[r0 + j] = -(p.lr * d);
+        }
+        __syncthreads();
+
+        // ---- the sweep over the own rows of W_1: this step's update, the next step's products ----
+        {
+            v4f a4[WNI], x4[WNI];
+            lane_pieces(a4, x, n4, g);
+            // (ONE instance of the sweep inside the loop: with one per case -- more steps to come, last
+            // step, last step leaving velocities -- the register rows met in a join after three separate
+            // updates and the compiler kept a second set of registers for them.  After the last step the
+            // products are taken with whatever the other input buffer holds and nobody reads them.)
+            lane_pieces(x4, xn, n4, g);
+            sweep_all<true, true, RR>(wres, sa, a4, x4, keepv);
+        }
+        __syncthreads();
+        y_cur = y_next;
+    }
+
+    // ---- epilogue: everything the workgroup kept on the chip goes back to device memory ----
+    __syncthreads();
+    copy_floats(p.W1 + (size_t)r0 * n0, W1l, nl * n0);
+#pragma unroll
+    for (int i = 0; i < RR; ++i) {
+        const int row = i * kPass + wave * 4 + sg;
+#pragma unroll
+        for (int j = 0; j < WNI; ++j) {
+            const int c = g + 16 * j;
+            if (row < nrr && c < n4) *(v4f *)(W1r + (size_t)row * n0 + 4 * c) = wres[i][j];
+        }
+    }
+    for (int j = tid; j < nr; j += kThreads) p.b1[r0 + j] = b1[j];
+    for (int i = tid; i < nL * perp; i += kThreads) {
+        const int k = i / perp, j = i - k * perp;
+        if (j < nr) p.W2[(size_t)k * n1 + r0 + j] = W2c[i];
+    }
+    if (w == 0) {
+        for (int k = tid; k < nL; k += kThreads) p.b2[k] = bL[k];
+        if (tid == 0) *p.loss_acc += loss_acc;
+    }
+}
+
+}  // namespace
+
+// ---- host side -------------------------------------------------------------------
+
+bool wide_geometry(const int32_t *n, int L, int max_wg, WideGeom &g)
+{
+    g = WideGeom{};
+    if (L != 2) return false;
+    const int n0 = n[0], n1 = n[1], nL = n[2];
+    if (n0 % 4 != 0 || n0 < 4 || n0 > 64 * WIDE_NI || nL > WIDE_MAX_NL || n1 < 1) return false;
+    if (max_wg < 1) return false;
+    if (max_wg > ON_MAX_WG) max_wg = ON_MAX_WG;
+    auto pad4 = [](int v) { return (v + 3) & ~3; };
+    const int per = (n1 + max_wg - 1) / max_wg;
+    const int grid = (n1 + per - 1) / per;
+    if ((int64_t)per * n0 > ((int64_t)1 << 24)) return false;
+    g.per = per;
+    g.grid = grid;
+    int64_t f = 0;
+    g.lds_x = (int)f; f += 2 * pad4(n0);
+    g.lds_a = (int)f; f += pad4(per);
+    g.lds_d = (int)f; f += pad4(per);
+    g.lds_b = (int)f; f += pad4(per);
+    g.lds_z = (int)f; f += pad4(per);
+    g.lds_w2 = (int)f; f += (int64_t)nL * pad4(per);
+    g.lds_zall = (int)f; f += pad4(grid * nL);
+    g.lds_out = (int)f; f += 3 * WIDE_MAX_NL;
+    g.lds_w1 = (int)f;
+    const int64_t room = (int64_t)(ON_MAX_LDS_BYTES / sizeof(float)) - f;
+    if (room < 0) return false;
+    int rows = (int)std::min<int64_t>(room / n0, per);
+    // the kernel is for layers that do NOT fit: a net whose rows all fit in LDS belongs to the kernels that
+    // keep every weight there
+    if (rows >= per) return false;
+    g.lds_rows = rows;
+    f += (int64_t)rows * n0;
+    g.lds_floats = (int)f;
+    g.words = 2 * (size_t)grid * nL;
+    g.ok = true;
+    return true;
+}
+
+size_t wide_exchange_bytes_bound(const int32_t *n, int L)
+{
+    if (L != 2 || n[2] > WIDE_MAX_NL) return 0;
+    return 2 * (size_t)ON_MAX_WG * WIDE_MAX_NL * sizeof(u64);
+}
+
+hipError_t wide_prepare()
+{
+    return hipFuncSetAttribute((const void *)wide_epoch_kernel<WIDE_REG_ROWS>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                               (int)ON_MAX_LDS_BYTES);
+}
+
+hipError_t launch_wide_epoch(const WideGeom &g, const WidePlan &plan, hipStream_t stream)
+{
+    return launch_resident(wide_epoch_kernel<WIDE_REG_ROWS>, plan, g.grid, (size_t)g.lds_floats * sizeof(float), stream);
+}
+
+}  // namespace dn

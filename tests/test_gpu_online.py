@@ -25,10 +25,13 @@ def dnlib():
     return dn
 
 
-def run_pair(dn, w, n, passes, mode, min_tile=None, tol=1e-4, biases=True, resident=1, twin=1, twin_expected=None, tiny=0):
+def run_pair(dn, w, n, passes, mode, min_tile=None, tol=1e-4, biases=True, resident=1, twin=1, twin_expected=None, tiny=0,
+             wide=0):
     """`passes` = list of momenta; one pass over the first n samples per entry.  twin=0 keeps
     plain-gradient-descent passes of deeper nets on the general persistent kernel; tiny=1 lets nets
-    with no layer wider than 64 run on the one-wavefront kernel."""
+    with no layer wider than 64 run on the one-wavefront kernel; wide=1 lets two-layer nets with a
+    hidden layer beyond LDS run on the kernel that keeps rows of W_1 in LDS and registers (its
+    plain-gradient-descent passes must then report that schedule)."""
     if biases:
         rng = np.random.default_rng(11)
         w.b = [rng.standard_normal(k).astype(np.float32) * 0.1 for k in w.widths[1:]]
@@ -40,6 +43,7 @@ def run_pair(dn, w, n, passes, mode, min_tile=None, tol=1e-4, biases=True, resid
     net.dn_set_option("online_resident", resident)
     net.dn_set_option("online_twin", twin)
     net.dn_set_option("online_tiny", tiny)
+    net.dn_set_option("online_wide", wide)
     o = Oracle("o32", w.widths, w.acts, w.loss)
     o.set_params(w.W, w.b)
     X = torch.from_numpy(w.X[:n]).to("cuda:0")
@@ -48,6 +52,9 @@ def run_pair(dn, w, n, passes, mode, min_tile=None, tol=1e-4, biases=True, resid
         got = net.dn_train_epoch(X, y, 1, w.lr, mu)
         if tiny:
             assert net.dn_last_schedule() == dn.DN_SCHED_ONE_WAVE, net.dn_last_schedule()
+        elif wide:
+            want = dn.DN_SCHED_WIDE_HIDDEN if mu == 0.0 else dn.DN_SCHED_PER_SAMPLE
+            assert net.dn_last_schedule() == want, (net.dn_last_schedule(), want)
         elif mode == PERSISTENT and twin_expected is not None:
             want = dn.DN_SCHED_TWO_COPY if (twin_expected and mu == 0.0) else dn.DN_SCHED_PER_SAMPLE
             assert net.dn_last_schedule() == want, (net.dn_last_schedule(), want)
@@ -263,12 +270,59 @@ def test_tanh_sweep_b1_prefix_persistent(dnlib):
     assert abs(float(b[-1].sum())) < 1e-4      # softmax + cross-entropy conserves the output bias sum
 
 
-def test_paper_shape_first_steps(dnlib):
+@pytest.mark.parametrize("wide", [0, 1])
+def test_paper_shape_first_steps(dnlib, wide):
     """340 -> 100000 (tanh) -> 10 softmax, the network of the paper's benchmark application,
-    full size, every weight compared after 24 steps."""
-    announce("paper shape 340-100000-10 B=1, 24 steps, persistent")
+    full size, every weight compared after 24 steps: on the general persistent kernel (wide=0) and
+    on the kernel for wide hidden layers, which is what the library picks for it."""
+    announce("paper shape 340-100000-10 B=1, 24 steps, persistent, wide=%d" % wide)
     w = synth.paper_shape(n_samples=24)
-    run_pair(dnlib, w, 24, [0.0], PERSISTENT, tol=1e-4, biases=False)
+    run_pair(dnlib, w, 24, [0.0], PERSISTENT, tol=1e-4, biases=False, wide=wide)
+
+
+WIDE_SHAPES = [
+    # two layers, inputs a multiple of 4 and at most 384, at most 16 outputs, a hidden layer beyond LDS;
+    # last column: whether the general persistent kernel takes the net too (the momentum pass runs on it)
+    ([340, 100000, 10], [TANH, SOFTMAX], CE, True),     # the paper's network: rows in LDS, in registers and streamed
+    ([340, 99991, 10], [TANH, SOFTMAX], CE, True),      # a last workgroup with fewer rows than the others
+    ([384, 50000, 16], [SIG, SOFTMAX], CE, True),       # the longest rows and the widest output the kernel takes
+    ([128, 90000, 7], [RELU, SIG], MSE, True),          # short rows: LDS and registers hold the whole block, nothing streams
+    ([64, 700000, 3], [TANH, SIG], MSE, False),         # many rows per workgroup: most of them streamed
+    ([8, 1000000, 2], [TANH, SOFTMAX], CE, False),      # rows of two float4s: fourteen of a row's sixteen lanes idle
+]
+
+
+@pytest.mark.parametrize("widths,acts,loss,momentum_pass", WIDE_SHAPES)
+def test_wide_hidden_layer_epochs_match_checker(dnlib, widths, acts, loss, momentum_pass):
+    """Plain-gradient-descent passes on the wide-hidden-layer kernel against the checker; where the
+    general persistent kernel takes the net as well, a momentum pass on it in between (it starts
+    from the velocities the first pass left)."""
+    announce("online wide-hidden-layer kernel widths=%s" % (widths,))
+    w = synth.make("wide", widths, acts, loss, n_samples=20, features="normal", init="xavier_uniform",
+                   batch=1, lr=0.0005, momentum=0.0, seed=6)
+    run_pair(dnlib, w, 20, [0.0, 0.5, 0.0] if momentum_pass else [0.0, 0.0], PERSISTENT, wide=1)
+
+
+def test_wide_hidden_layer_kernel_edges(dnlib):
+    """One sample (no next sample to take products with); two epochs in a row (the stamps of the
+    second continue the first's); and nets the kernel must leave to the others."""
+    announce("online wide-hidden-layer kernel: single sample, consecutive epochs, refusals")
+    w = synth.make("wide1", [340, 100000, 10], [TANH, SOFTMAX], CE, n_samples=5, features="normal", init="xavier_uniform",
+                   batch=1, lr=0.0005, momentum=0.0, seed=8)
+    run_pair(dnlib, w, 1, [0.0], PERSISTENT, wide=1)
+    run_pair(dnlib, w, 5, [0.0, 0.0, 0.0], PERSISTENT, wide=1)
+    for widths, acts in (([340, 3000, 10], [TANH, SOFTMAX]),            # the hidden layer fits in LDS
+                         ([400, 100000, 10], [TANH, SOFTMAX]),          # more than 384 inputs
+                         ([338, 100000, 10], [TANH, SOFTMAX]),          # inputs not a multiple of 4
+                         ([340, 100000, 24], [TANH, SOFTMAX]),          # more than 16 outputs
+                         ([340, 100000, 64, 10], [TANH, TANH, SOFTMAX])):   # three layers
+        v = synth.make("notwide", widths, acts, CE, n_samples=2, features="normal", init="xavier_uniform",
+                       batch=1, lr=0.0005, momentum=0.0, seed=9)
+        net = dnlib.Net(v.widths, v.acts, v.loss, 1)
+        net.set_all(v.W, v.b)      # (automatic choice of the schedule: whatever takes the net, only not this kernel)
+        net.dn_train_epoch(torch.from_numpy(v.X).to("cuda:0"), torch.from_numpy(v.labels).to("cuda:0"), 1, v.lr, 0.0)
+        assert net.dn_last_schedule() not in (dnlib.DN_SCHED_NONE, dnlib.DN_SCHED_WIDE_HIDDEN), widths
+        net.close()
 
 
 # ------------------------------- the paper's per-call execution model (copies around every call) ----

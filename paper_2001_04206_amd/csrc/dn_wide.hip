@@ -35,9 +35,6 @@ namespace {
 static_assert(kThreads == WIDE_THREADS, "the thread count is set before dn_persist.h is included");
 constexpr int WNI = WIDE_NI;   // float4 pieces of a row per lane (rows of up to 64 * WNI floats)
 constexpr int kPass = kWaves * 4;   // rows a workgroup works on at a time: sixteen lanes each
-#ifndef WIDE_STREAM_RU
-#define WIDE_STREAM_RU 2        // row groups of the streamed tier in flight per wave
-#endif
 
 // This lane's pieces of a vector of n4 float4s (zeros past the end).
 __device__ __forceinline__ void lane_pieces(v4f (&dst)[WNI], const float *src, int n4, int g)
@@ -59,81 +56,95 @@ __device__ __forceinline__ float dot_pieces(const v4f (&w)[WNI], const v4f (&x)[
 
 // Rows in memory (LDS or device): nr rows of n floats at Wt; row r of the block takes delta dl[r]
 // and leaves its product with the next sample in out[r].  Sixteen lanes per row, four rows per wave
-// at a time, RU such groups in flight.  Loads are unconditional (clamped addresses); columns past
-// the end hold zeros in a4 / x4 and are never stored.  keepv: the applied change also goes to Vt.
-template <bool UPDATE, bool DOT, int RU>
-__device__ __forceinline__ void sweep_mem(float *__restrict__ Wt, float *__restrict__ Vt, int n, int nr, const float *dl,
-                                          const v4f (&a4)[WNI], const v4f (&x4)[WNI], float lr, bool keepv, float *out)
+// at a time, RU such groups in flight.  A pass is split in two -- its loads, and everything that
+// needs them -- so that other work can be put between the two.  Loads are unconditional (clamped
+// addresses); columns past the end hold zeros in a4 / x4 and are never stored.  The update is one
+// fused multiply-add per weight, w = fma(-(lr delta_r), a_k, w); keepv: the applied change also goes to Vt.
+template <int RU>
+__device__ __forceinline__ void pass_load(v4f (&wv)[RU][WNI], const float *__restrict__ Wt, int n, int nr, int base)
 {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int sg = lane >> 4, g = lane & 15;
     const int n4 = n >> 2;
-    for (int base = 0; base < nr; base += kPass * RU) {
-        v4f wv[RU][WNI];
-        int row[RU];
 #pragma unroll
-        for (int u = 0; u < RU; ++u) {
-            row[u] = base + u * kPass + wave * 4 + sg;
-            const float *wp = Wt + (size_t)min(row[u], nr - 1) * n;
+    for (int u = 0; u < RU; ++u) {
+        const int row = base + u * kPass + wave * 4 + sg;
+        const float *wp = Wt + (size_t)min(row, nr - 1) * n;
 #pragma unroll
-            for (int j = 0; j < WNI; ++j) wv[u][j] = *(const v4f *)(wp + 4 * min(g + 16 * j, n4 - 1));
-        }
+        for (int j = 0; j < WNI; ++j) wv[u][j] = *(const v4f *)(wp + 4 * min(g + 16 * j, n4 - 1));
+    }
+}
+
+__device__ __forceinline__ v4f fma4(float s, const v4f &a, const v4f &w)
+{
+    return (v4f){__builtin_fmaf(s, a.x, w.x), __builtin_fmaf(s, a.y, w.y), __builtin_fmaf(s, a.z, w.z), __builtin_fmaf(s, a.w, w.w)};
+}
+
+template <bool UPDATE, bool DOT, int RU>
+__device__ __forceinline__ void pass_finish(v4f (&wv)[RU][WNI], float *__restrict__ Wt, float *__restrict__ Vt, int n, int nr,
+                                            int base, const float *dl, const v4f (&a4)[WNI], const v4f (&x4)[WNI], float lr,
+                                            bool keepv, float *out)
+{
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int sg = lane >> 4, g = lane & 15;
+    const int n4 = n >> 2;
 #pragma unroll
-        for (int u = 0; u < RU; ++u) {
-            const bool rin = row[u] < nr;
-            const int rc = min(row[u], nr - 1);
-            if (UPDATE) {
-                const float ld = lr * dl[rc];
-                float *wp = Wt + (size_t)rc * n;
+    for (int u = 0; u < RU; ++u) {
+        const int row = base + u * kPass + wave * 4 + sg;
+        const bool rin = row < nr;
+        const int rc = min(row, nr - 1);
+        if (UPDATE) {
+            const float nld = -(lr * dl[rc]);
+            float *wp = Wt + (size_t)rc * n;
 #pragma unroll
-                for (int j = 0; j < WNI; ++j) {
-                    const int c = g + 16 * j;
-                    const v4f dv = (v4f){ld * a4[j].x, ld * a4[j].y, ld * a4[j].z, ld * a4[j].w};
-                    wv[u][j] = wv[u][j] - dv;
-                    if (rin && c < n4) {
-                        *(v4f *)(wp + 4 * c) = wv[u][j];
-                        if (keepv) *(v4f *)(Vt + (size_t)rc * n + 4 * c) = -dv;
-                    }
+            for (int j = 0; j < WNI; ++j) {
+                const int c = g + 16 * j;
+                wv[u][j] = fma4(nld, a4[j], wv[u][j]);
+                if (rin && c < n4) {
+                    *(v4f *)(wp + 4 * c) = wv[u][j];
+                    if (keepv) *(v4f *)(Vt + (size_t)rc * n + 4 * c) = a4[j] * nld;
                 }
             }
-            if (DOT) {
-                const float acc = row16_sum(dot_pieces(wv[u], x4));
-                if (g == 0 && rin) out[row[u]] = acc;
-            }
+        }
+        if (DOT) {
+            const float acc = row16_sum(dot_pieces(wv[u], x4));
+            if (g == 0 && rin) out[row] = acc;
         }
     }
 }
 
-// Rows in registers: wres[i] is this lane's part of row i * kPass + wave * 4 + sg of the tier.
-template <bool UPDATE, bool DOT, int RR>
-__device__ __forceinline__ void sweep_regs(v4f (&wres)[RR > 0 ? RR : 1][WNI], float *__restrict__ Vt, int n, int nr,
-                                           const float *dl, const v4f (&a4)[WNI], const v4f (&x4)[WNI], float lr, bool keepv,
-                                           float *out)
+template <bool UPDATE, bool DOT, int RU>
+__device__ __forceinline__ void sweep_mem(float *__restrict__ Wt, float *__restrict__ Vt, int n, int nr, const float *dl,
+                                          const v4f (&a4)[WNI], const v4f (&x4)[WNI], float lr, bool keepv, float *out,
+                                          int first_base = 0)
 {
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int sg = lane >> 4, g = lane & 15;
+    for (int base = first_base; base < nr; base += kPass * RU) {
+        v4f wv[RU][WNI];
+        pass_load<RU>(wv, Wt, n, nr, base);
+        pass_finish<UPDATE, DOT, RU>(wv, Wt, Vt, n, nr, base, dl, a4, x4, lr, keepv, out);
+    }
+}
+
+// A row in registers: wrow is this lane's part of row `row` of the tier (nr rows).
+template <bool UPDATE, bool DOT>
+__device__ __forceinline__ void reg_row(v4f (&wrow)[WNI], int row, float *__restrict__ Vt, int n, int nr, const float *dl,
+                                        const v4f (&a4)[WNI], const v4f (&x4)[WNI], float lr, bool keepv, float *out)
+{
+    const int g = threadIdx.x & 15;
     const int n4 = n >> 2;
+    const bool rin = row < nr;
+    const int rc = rin ? row : 0;
+    if (UPDATE) {
+        const float nld = rin ? -(lr * dl[rc]) : 0.f;
 #pragma unroll
-    for (int i = 0; i < RR; ++i) {
-        const int row = i * kPass + wave * 4 + sg;
-        const bool rin = row < nr;
-        const int rc = rin ? row : 0;
-        if (UPDATE) {
-            const float ld = rin ? lr * dl[rc] : 0.f;
-#pragma unroll
-            for (int j = 0; j < WNI; ++j) {
-                const v4f dv = (v4f){ld * a4[j].x, ld * a4[j].y, ld * a4[j].z, ld * a4[j].w};
-                wres[i][j] = wres[i][j] - dv;
-                if (keepv && rin && g + 16 * j < n4) *(v4f *)(Vt + (size_t)rc * n + 4 * (g + 16 * j)) = -dv;
-            }
+        for (int j = 0; j < WNI; ++j) {
+            wrow[j] = fma4(nld, a4[j], wrow[j]);
+            if (keepv && rin && g + 16 * j < n4) *(v4f *)(Vt + (size_t)rc * n + 4 * (g + 16 * j)) = a4[j] * nld;
         }
-        if (DOT) {
-            const float acc = row16_sum(dot_pieces(wres[i], x4));
-            if (g == 0 && rin) out[row] = acc;
-        }
-        // one row at a time: interleaving the rows' arithmetic would need a second set of registers
-        // for the rows in flight, and the registers are what this tier is short of
-        __builtin_amdgcn_sched_barrier(0);
+    }
+    if (DOT) {
+        const float acc = row16_sum(dot_pieces(wrow, x4));
+        if (g == 0 && rin) out[row] = acc;
     }
 }
 
@@ -147,17 +158,65 @@ struct SweepArgs {
     float lr;
 };
 
+// One stage of the sweep: the loads of streamed pass i + 1 go out (into nxt), register row i and LDS
+// pass i are worked on while they travel, then streamed pass i (loaded a stage ago into cur) is
+// finished.  Passes are sixteen rows (one row per group of sixteen lanes).
+struct StageArgs {
+    float *Ws, *Vs, *Vr, *Wl, *Vl;
+    const float *ds, *dr, *dl;
+    float *zs, *zr, *zl;
+    int n, ns, nrr, nl, npass, nlpass;
+    float lr;
+    bool keepv;
+};
+
+template <bool U, bool D>
+__device__ __forceinline__ void sweep_stage(v4f (&cur)[1][WNI], v4f (&nxt)[1][WNI], v4f (&wrow)[WNI], int i, int last,
+                                            const StageArgs &t, const v4f (&a4)[WNI], const v4f (&x4)[WNI])
+{
+    const int wave = threadIdx.x >> 6, sg = (threadIdx.x & 63) >> 4;
+    // (the pass's first row is made opaque: as a constant, every address of every unrolled stage is
+    // loop invariant over the steps, and the compiler computes them all once and keeps them in registers)
+    int base = i * kPass;
+    asm volatile("" : "+s"(base));
+    if (i + 1 < t.npass && i + 1 < last) pass_load<1>(nxt, t.Ws, t.n, t.ns, base + kPass);
+    reg_row<U, D>(wrow, i * kPass + wave * 4 + sg, t.Vr, t.n, t.nrr, t.dr, a4, x4, t.lr, t.keepv, t.zr);
+    if (i < t.nlpass) {
+        v4f wl[1][WNI];
+        pass_load<1>(wl, t.Wl, t.n, t.nl, base);
+        pass_finish<U, D, 1>(wl, t.Wl, t.Vl, t.n, t.nl, base, t.dl, a4, x4, t.lr, t.keepv, t.zl);
+    }
+    if (i < t.npass) pass_finish<U, D, 1>(cur, t.Ws, t.Vs, t.n, t.ns, base, t.ds, a4, x4, t.lr, t.keepv, t.zs);
+}
+
+// One sweep over all three tiers.  The streamed rows wait for memory, the register and LDS rows for
+// next to nothing, and with one wave per SIMD there is nobody else to fill the wait: the tiers are
+// therefore interleaved by hand, one stage per register row (RR of them, RR even), the streamed
+// passes double-buffered.  Streamed and LDS passes beyond RR follow in plain loops.
+// wres[i] is this lane's part of row i * kPass + wave * 4 + sg of the register tier.
 template <bool U, bool D, int RR>
 __device__ __forceinline__ void sweep_all(v4f (&wres)[RR > 0 ? RR : 1][WNI], const SweepArgs &sa, const v4f (&a4)[WNI],
                                           const v4f (&x4)[WNI], bool keepv)
 {
+    static_assert(RR % 2 == 0, "stages come in pairs (two buffers for the streamed passes)");
     const int first_s = sa.nl + sa.nrr;
-    if (sa.ns > 0)
-        sweep_mem<U, D, WIDE_STREAM_RU>(sa.Ws, sa.V + (size_t)first_s * sa.n, sa.n, sa.ns, sa.d + first_s, a4, x4, sa.lr, keepv,
-                                        sa.z + first_s);
-    if (RR > 0 && sa.nrr > 0)
-        sweep_regs<U, D, RR>(wres, sa.V + (size_t)sa.nl * sa.n, sa.n, sa.nrr, sa.d + sa.nl, a4, x4, sa.lr, keepv, sa.z + sa.nl);
-    if (sa.nl > 0) sweep_mem<U, D, 1>(sa.Wl, sa.V, sa.n, sa.nl, sa.d, a4, x4, sa.lr, keepv, sa.z);
+    StageArgs t;
+    t.Ws = sa.Ws; t.Vs = sa.V + (size_t)first_s * sa.n; t.Vr = sa.V + (size_t)sa.nl * sa.n; t.Wl = sa.Wl; t.Vl = sa.V;
+    t.ds = sa.d + first_s; t.dr = sa.d + sa.nl; t.dl = sa.d;
+    t.zs = sa.z + first_s; t.zr = sa.z + sa.nl; t.zl = sa.z;
+    t.n = sa.n; t.ns = sa.ns; t.nrr = sa.nrr; t.nl = sa.nl;
+    t.npass = (sa.ns + kPass - 1) / kPass;
+    t.nlpass = (sa.nl + kPass - 1) / kPass;
+    t.lr = sa.lr; t.keepv = keepv;
+    v4f bufa[1][WNI], bufb[1][WNI];
+    if (RR > 0 && t.npass > 0) pass_load<1>(bufa, t.Ws, t.n, t.ns, 0);
+#pragma unroll
+    for (int i = 0; i < RR; i += 2) {
+        sweep_stage<U, D>(bufa, bufb, wres[i], i, RR, t, a4, x4);
+        sweep_stage<U, D>(bufb, bufa, wres[i + 1], i + 1, RR, t, a4, x4);
+    }
+    if (t.npass > RR) sweep_mem<U, D, 1>(t.Ws, t.Vs, t.n, t.ns, t.ds, a4, x4, t.lr, keepv, t.zs, RR * kPass);
+    if (t.nlpass > RR) sweep_mem<U, D, 1>(t.Wl, t.Vl, t.n, t.nl, t.dl, a4, x4, t.lr, keepv, t.zl, RR * kPass);
 }
 
 template <int RR>

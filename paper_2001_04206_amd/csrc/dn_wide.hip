@@ -158,9 +158,9 @@ struct SweepArgs {
     float lr;
 };
 
-// One stage of the sweep: the loads of streamed pass i + 1 go out (into nxt), register row i and LDS
-// pass i are worked on while they travel, then streamed pass i (loaded a stage ago into cur) is
-// finished.  Passes are sixteen rows (one row per group of sixteen lanes).
+// One stage of the sweep: streamed pass i (in cur, loaded two stages ago) is finished, the loads of
+// pass i + 2 go out into the buffer this frees, and register row i and LDS pass i are worked on while
+// they travel.  Passes are sixteen rows (one row per group of sixteen lanes).
 struct StageArgs {
     float *Ws, *Vs, *Vr, *Wl, *Vl;
     const float *ds, *dr, *dl;
@@ -171,32 +171,44 @@ struct StageArgs {
 };
 
 template <bool U, bool D>
-__device__ __forceinline__ void sweep_stage(v4f (&cur)[1][WNI], v4f (&nxt)[1][WNI], v4f (&wrow)[WNI], int i, int last,
-                                            const StageArgs &t, const v4f (&a4)[WNI], const v4f (&x4)[WNI])
+__device__ __forceinline__ void sweep_stage(v4f (&cur)[1][WNI], v4f (&wrow)[WNI], int i, int last, const StageArgs &t,
+                                            const v4f (&a4)[WNI], const v4f (&x4)[WNI])
 {
     const int wave = threadIdx.x >> 6, sg = (threadIdx.x & 63) >> 4;
     // (the pass's first row is made opaque: as a constant, every address of every unrolled stage is
     // loop invariant over the steps, and the compiler computes them all once and keeps them in registers)
     int base = i * kPass;
     asm volatile("" : "+s"(base));
-    if (i + 1 < t.npass && i + 1 < last) pass_load<1>(nxt, t.Ws, t.n, t.ns, base + kPass);
+    if (i < t.npass) pass_finish<U, D, 1>(cur, t.Ws, t.Vs, t.n, t.ns, base, t.ds, a4, x4, t.lr, t.keepv, t.zs);
+    if (i + 2 < t.npass && i + 2 < last) pass_load<1>(cur, t.Ws, t.n, t.ns, base + 2 * kPass);
     reg_row<U, D>(wrow, i * kPass + wave * 4 + sg, t.Vr, t.n, t.nrr, t.dr, a4, x4, t.lr, t.keepv, t.zr);
     if (i < t.nlpass) {
         v4f wl[1][WNI];
         pass_load<1>(wl, t.Wl, t.n, t.nl, base);
         pass_finish<U, D, 1>(wl, t.Wl, t.Vl, t.n, t.nl, base, t.dl, a4, x4, t.lr, t.keepv, t.zl);
     }
-    if (i < t.npass) pass_finish<U, D, 1>(cur, t.Ws, t.Vs, t.n, t.ns, base, t.ds, a4, x4, t.lr, t.keepv, t.zs);
+}
+
+// The first two streamed passes of the NEXT sweep, requested as soon as a sweep has written them (a
+// thread reads back the rows and columns it wrote itself): they travel while the step's small
+// phases -- the exchange of the partial net inputs, the output stage, the deltas -- run.
+__device__ __forceinline__ void sweep_preload(v4f (&bufa)[1][WNI], v4f (&bufb)[1][WNI], const float *Ws, int n, int ns)
+{
+    int base = 0;
+    asm volatile("" : "+s"(base));
+    if (ns > 0) pass_load<1>(bufa, Ws, n, ns, base);
+    if (ns > kPass) pass_load<1>(bufb, Ws, n, ns, base + kPass);
 }
 
 // One sweep over all three tiers.  The streamed rows wait for memory, the register and LDS rows for
 // next to nothing, and with one wave per SIMD there is nobody else to fill the wait: the tiers are
 // therefore interleaved by hand, one stage per register row (RR of them, RR even), the streamed
-// passes double-buffered.  Streamed and LDS passes beyond RR follow in plain loops.
+// passes two ahead in two buffers.  On entry bufa / bufb hold streamed passes 0 and 1 (sweep_preload);
+// on exit they hold them again, for the next sweep.  Streamed and LDS passes beyond RR follow in plain loops.
 // wres[i] is this lane's part of row i * kPass + wave * 4 + sg of the register tier.
 template <bool U, bool D, int RR>
-__device__ __forceinline__ void sweep_all(v4f (&wres)[RR > 0 ? RR : 1][WNI], const SweepArgs &sa, const v4f (&a4)[WNI],
-                                          const v4f (&x4)[WNI], bool keepv)
+__device__ __forceinline__ void sweep_all(v4f (&wres)[RR > 0 ? RR : 1][WNI], v4f (&bufa)[1][WNI], v4f (&bufb)[1][WNI],
+                                          const SweepArgs &sa, const v4f (&a4)[WNI], const v4f (&x4)[WNI], bool keepv)
 {
     static_assert(RR % 2 == 0, "stages come in pairs (two buffers for the streamed passes)");
     const int first_s = sa.nl + sa.nrr;
@@ -208,15 +220,14 @@ __device__ __forceinline__ void sweep_all(v4f (&wres)[RR > 0 ? RR : 1][WNI], con
     t.npass = (sa.ns + kPass - 1) / kPass;
     t.nlpass = (sa.nl + kPass - 1) / kPass;
     t.lr = sa.lr; t.keepv = keepv;
-    v4f bufa[1][WNI], bufb[1][WNI];
-    if (RR > 0 && t.npass > 0) pass_load<1>(bufa, t.Ws, t.n, t.ns, 0);
 #pragma unroll
     for (int i = 0; i < RR; i += 2) {
-        sweep_stage<U, D>(bufa, bufb, wres[i], i, RR, t, a4, x4);
-        sweep_stage<U, D>(bufb, bufa, wres[i + 1], i + 1, RR, t, a4, x4);
+        sweep_stage<U, D>(bufa, wres[i], i, RR, t, a4, x4);
+        sweep_stage<U, D>(bufb, wres[i + 1], i + 1, RR, t, a4, x4);
     }
     if (t.npass > RR) sweep_mem<U, D, 1>(t.Ws, t.Vs, t.n, t.ns, t.ds, a4, x4, t.lr, keepv, t.zs, RR * kPass);
     if (t.nlpass > RR) sweep_mem<U, D, 1>(t.Wl, t.Vl, t.n, t.nl, t.dl, a4, x4, t.lr, keepv, t.zl, RR * kPass);
+    sweep_preload(bufa, bufb, t.Ws, t.n, t.ns);
 }
 
 template <int RR>
@@ -269,12 +280,14 @@ __global__ __launch_bounds__(kThreads) void wide_epoch_kernel(WidePlan p)
 
     // one sweep over all three tiers: rows take d_own, products with x4 go to z1
     const SweepArgs sa{W1s, W1l, V1, d_own, z1, n0, nl, nrr, ns, p.lr};
+    v4f bufa[1][WNI], bufb[1][WNI];   // streamed passes 0 and 1 of the next sweep, in flight between sweeps
     {   // the first sample's products with W_1
         v4f a4[WNI], x4[WNI];
         lane_pieces(x4, xbuf, n4, g);
 #pragma unroll
         for (int j = 0; j < WNI; ++j) a4[j] = (v4f){0.f, 0.f, 0.f, 0.f};
-        sweep_all<false, true, RR>(wres, sa, a4, x4, false);
+        sweep_preload(bufa, bufb, W1s, n0, ns);
+        sweep_all<false, true, RR>(wres, bufa, bufb, sa, a4, x4, false);
     }
     __syncthreads();
 
@@ -394,7 +407,7 @@ __global__ __launch_bounds__(kThreads) void wide_epoch_kernel(WidePlan p)
             // updates and the compiler kept a second set of registers for them.  After the last step the
             // products are taken with whatever the other input buffer holds and nobody reads them.)
             lane_pieces(x4, xn, n4, g);
-            sweep_all<true, true, RR>(wres, sa, a4, x4, keepv);
+            sweep_all<true, true, RR>(wres, bufa, bufb, sa, a4, x4, keepv);
         }
         __syncthreads();
         y_cur = y_next;

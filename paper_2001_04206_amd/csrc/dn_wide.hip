@@ -202,7 +202,7 @@ __device__ __forceinline__ void sweep_preload(v4f (&bufa)[1][WNI], v4f (&bufb)[1
 
 // One sweep over all three tiers.  The streamed rows wait for memory, the register and LDS rows for
 // next to nothing, and with one wave per SIMD there is nobody else to fill the wait: the tiers are
-// therefore interleaved by hand, one stage per register row (RR of them, RR even), the streamed
+// therefore interleaved by hand, one stage per register row (RR of them), the streamed
 // passes two ahead in two buffers.  On entry bufa / bufb hold streamed passes 0 and 1 (sweep_preload);
 // on exit they hold them again, for the next sweep.  Streamed and LDS passes beyond RR follow in plain loops.
 // wres[i] is this lane's part of row i * kPass + wave * 4 + sg of the register tier.
@@ -210,7 +210,6 @@ template <bool U, bool D, int RR>
 __device__ __forceinline__ void sweep_all(v4f (&wres)[RR > 0 ? RR : 1][WNI], v4f (&bufa)[1][WNI], v4f (&bufb)[1][WNI],
                                           const SweepArgs &sa, const v4f (&a4)[WNI], const v4f (&x4)[WNI], bool keepv)
 {
-    static_assert(RR % 2 == 0, "stages come in pairs (two buffers for the streamed passes)");
     const int first_s = sa.nl + sa.nrr;
     StageArgs t;
     t.Ws = sa.Ws; t.Vs = sa.V + (size_t)first_s * sa.n; t.Vr = sa.V + (size_t)sa.nl * sa.n; t.Wl = sa.Wl; t.Vl = sa.V;
@@ -221,10 +220,11 @@ __device__ __forceinline__ void sweep_all(v4f (&wres)[RR > 0 ? RR : 1][WNI], v4f
     t.nlpass = (sa.nl + kPass - 1) / kPass;
     t.lr = sa.lr; t.keepv = keepv;
 #pragma unroll
-    for (int i = 0; i < RR; i += 2) {
+    for (int i = 0; i + 1 < RR; i += 2) {   // stages in pairs: even streamed passes go through bufa, odd ones through bufb
         sweep_stage<U, D>(bufa, wres[i], i, RR, t, a4, x4);
         sweep_stage<U, D>(bufb, wres[i + 1], i + 1, RR, t, a4, x4);
     }
+    if (RR % 2 == 1) sweep_stage<U, D>(bufa, wres[RR - 1], RR - 1, RR, t, a4, x4);
     if (t.npass > RR) sweep_mem<U, D, 1>(t.Ws, t.Vs, t.n, t.ns, t.ds, a4, x4, t.lr, keepv, t.zs, RR * kPass);
     if (t.nlpass > RR) sweep_mem<U, D, 1>(t.Wl, t.Vl, t.n, t.nl, t.dl, a4, x4, t.lr, keepv, t.zl, RR * kPass);
     sweep_preload(bufa, bufb, t.Ws, t.n, t.ns);

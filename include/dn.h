@@ -446,11 +446,11 @@ dn_status dn_kernel_flops(dn_net *net, int32_t kernel_class, double *flops);
  *                    twice, the last layer whole), runs on the persistent kernel that keeps a row copy
  *                    and a column copy of the inner weights and repeats the last layer in every
  *                    workgroup (no partial sums cross workgroups); 0: always the general persistent kernel
- *   "online_wide"    1 (default): batch 1 with momentum 0 on a two-layer net whose hidden layer does
- *                    not fit in LDS, with at most 384 inputs (a multiple of 4) and at most 16 outputs --
- *                    the paper's 340-100000-10 network -- runs on the persistent kernel that keeps most
- *                    rows of W_1 in LDS and in registers for the whole epoch and streams the rest;
- *                    0: such nets take the general persistent kernel
+ *   "online_wide"    1 (default): batch 1 on a two-layer net whose hidden layer does not fit in LDS,
+ *                    with at most 384 inputs (a multiple of 4) and at most 16 outputs -- the paper's
+ *                    340-100000-10 network -- runs on the persistent kernel that keeps most rows of W_1
+ *                    (with momentum: and of its velocities) in LDS and in registers for the whole epoch
+ *                    and streams the rest; 0: such nets take the general persistent kernel
  *   "online_tiny"    1 (default): batch 1 on a net whose layers are all at most 64 wide (and whose
  *                    parameters fit in LDS, twice with momentum) runs on a single wavefront that keeps
  *                    the whole net in LDS; 0: such nets take the other batch-1 schedules

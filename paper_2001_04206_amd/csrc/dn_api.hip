@@ -114,7 +114,7 @@ struct dn_net {
     bool twin_ready = false;   // the two-copy batch-1 kernel's LDS limit is raised
     bool tiny_ready = false;   // the one-wave batch-1 kernel's LDS limit is raised
     bool wide_ready = false;   // the wide-hidden-layer batch-1 kernel's LDS limit is raised
-    bool wide_ok = false;      // ... and the net suits it (plain gradient descent only)
+    bool wide_ok = false;      // ... and the net suits it
     int last_schedule = DN_SCHED_NONE;   // how the last dn_train_epoch ran
     uint32_t online_seq = 0;   // last step number stamped into the exchange buffers
     // persistent minibatch kernel (one- and two-layer nets)
@@ -179,7 +179,7 @@ void refresh_persistent(dn_net *net)
     if (net->device_cus <= 0) return;
     if (net->wide_ready) {
         WideGeom wg;
-        net->wide_ok = wide_geometry(net->n.data(), L, net->device_cus, wg) &&
+        net->wide_ok = wide_geometry(net->n.data(), L, net->device_cus, false, wg) &&
                        wg.words * sizeof(unsigned long long) <= net->lo.online_bytes;
     }
     if (net->online_prepared && online_geometry(net->n.data(), L, net->online_min_tile, false, net->geom))
@@ -420,7 +420,7 @@ dn_status run_twin(dn_net *net, const TwinGeom &g, const float *X, const int32_t
 
 // Batch-1 epochs of a two-layer net with a wide hidden layer: most of W_1 stays in LDS and registers.
 dn_status run_wide(dn_net *net, const WideGeom &g, const float *X, const int32_t *labels, int64_t n_samples, float lr,
-                   bool timing)
+                   float mu, bool timing)
 {
     WidePlan p{};
     p.W1 = net->W(1); p.b1 = net->b(1); p.VW1 = net->VW(1); p.Vb1 = net->Vb(1);
@@ -431,8 +431,9 @@ dn_status run_wide(dn_net *net, const WideGeom &g, const float *X, const int32_t
     p.n0 = net->n[0]; p.n1 = net->n[1]; p.nL = net->n[2];
     p.act1 = net->act[1]; p.actL = net->act[2]; p.loss = net->loss;
     p.per = g.per; p.lds_rows = g.lds_rows;
-    p.lr = lr;
+    p.lr = lr; p.mu = mu;
     p.lds_x = g.lds_x; p.lds_a = g.lds_a; p.lds_d = g.lds_d; p.lds_b = g.lds_b; p.lds_z = g.lds_z; p.lds_w2 = g.lds_w2;
+    p.lds_vb = g.lds_vb; p.lds_vw2 = g.lds_vw2;
     p.lds_zall = g.lds_zall; p.lds_out = g.lds_out; p.lds_w1 = g.lds_w1;
     const int64_t chunk = (int64_t)1 << 30;
     for (int64_t s0 = 0; s0 < n_samples; s0 += chunk) {
@@ -473,12 +474,12 @@ dn_status run_online(dn_net *net, const float *X, const int32_t *labels, int64_t
             return run_twin(net, tg, X, labels, n_samples, lr, timing);
         }
     }
-    if (mu == 0.f && net->online_wide && net->wide_ok) {
+    if (net->online_wide && net->wide_ok) {
         // two layers, the hidden one too wide for LDS: most of its rows stay in LDS and registers
         WideGeom wg;
-        if (wide_geometry(net->n.data(), L, net->device_cus, wg)) {
+        if (wide_geometry(net->n.data(), L, net->device_cus, mu != 0.f, wg)) {
             net->last_schedule = DN_SCHED_WIDE_HIDDEN;
-            return run_wide(net, wg, X, labels, n_samples, lr, timing);
+            return run_wide(net, wg, X, labels, n_samples, lr, mu, timing);
         }
     }
     OnlineGeom g;   // same slices as net->geom; LDS residency depends on whether velocities are read
@@ -903,9 +904,13 @@ dn_status dn_train_epoch(dn_net *net, const float *X_dev, const int32_t *labels_
     const bool timing = net->time_kernels != 0;
     net->timed = 0;
     const int L = net->L;
-    // (a two-layer net with a very wide hidden layer may suit only the kernel for such nets, which does plain
-    // gradient descent)
-    const bool online_fit = net->online_ok || (momentum == 0.f && net->online_wide && net->wide_ok);
+    // (a two-layer net with a very wide hidden layer may suit only the kernel for such nets)
+    bool wide_fit = false;
+    if (net->online_wide && net->wide_ok) {
+        WideGeom wg;
+        wide_fit = wide_geometry(net->n.data(), net->L, net->device_cus, momentum != 0.f, wg);
+    }
+    const bool online_fit = net->online_ok || wide_fit;
     bool persistent = batch == 1 && net->online_mode != 1 && online_fit;
     if (batch == 1 && net->online_mode == 2 && !online_fit) return DN_ERR_UNSUPPORTED;
     const bool pbatch = batch > 1 && net->batch_mode != 1 && net->batch_ok &&

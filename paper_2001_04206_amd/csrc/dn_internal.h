@@ -344,13 +344,14 @@ hipError_t launch_twin_epoch(const TwinGeom &g, const TwinPlan &plan, hipStream_
 constexpr int WIDE_THREADS = 256;
 constexpr int WIDE_NI = 6;          // rows of at most 64 * WIDE_NI = 384 inputs
 constexpr int WIDE_REG_ROWS = 12;   // 24 registers each per lane: 288 of a lane's 512 (13 rows spill)
+constexpr int WIDE_REG_ROWS_MOMENTUM = 4;   // with momentum a row brings its velocities: 48 registers each
 constexpr int WIDE_MAX_NL = 16;     // output units
 struct WideGeom {
     bool ok;
     int per, grid;        // hidden units per workgroup, workgroups
     int lds_rows;         // rows of a workgroup's block that live in LDS
     size_t words;         // exchange region, in 64-bit words
-    int lds_x, lds_a, lds_d, lds_b, lds_z, lds_w2, lds_zall, lds_out, lds_w1, lds_floats;
+    int lds_x, lds_a, lds_d, lds_b, lds_z, lds_w2, lds_vb, lds_vw2, lds_zall, lds_out, lds_w1, lds_floats;
 };
 
 struct WidePlan {
@@ -362,14 +363,14 @@ struct WidePlan {
     const int32_t *labels;
     int64_t n_samples;
     int n0, n1, nL, act1, actL, loss, per, lds_rows, keep_v;
-    float lr;
+    float lr, mu;
     uint32_t seq0;
-    int lds_x, lds_a, lds_d, lds_b, lds_z, lds_w2, lds_zall, lds_out, lds_w1;
+    int lds_x, lds_a, lds_d, lds_b, lds_z, lds_w2, lds_vb, lds_vw2, lds_zall, lds_out, lds_w1;
 };
 
 // false if the net does not suit the kernel (not two layers, inputs not a multiple of 4 or above 384,
 // more than 16 outputs, or a hidden layer whose rows all fit in LDS anyway).
-bool wide_geometry(const int32_t *n, int L, int max_wg, WideGeom &g);
+bool wide_geometry(const int32_t *n, int L, int max_wg, bool want_v, WideGeom &g);
 size_t wide_exchange_bytes_bound(const int32_t *n, int L);
 hipError_t wide_prepare();
 hipError_t launch_wide_epoch(const WideGeom &g, const WidePlan &plan, hipStream_t stream);

@@ -54,14 +54,45 @@ __device__ __forceinline__ float dot_pieces(const v4f (&w)[WNI], const v4f (&x)[
     return acc;
 }
 
-// Rows in memory (LDS or device): nr rows of n floats at Wt; row r of the block takes delta dl[r]
-// and leaves its product with the next sample in out[r].  Sixteen lanes per row, four rows per wave
-// at a time, RU such groups in flight.  A pass is split in two -- its loads, and everything that
-// needs them -- so that other work can be put between the two.  Loads are unconditional (clamped
-// addresses); columns past the end hold zeros in a4 / x4 and are never stored.  The update is one
-// fused multiply-add per weight, w = fma(-(lr delta_r), a_k, w); keepv: the applied change also goes to Vt.
-template <int RU>
-__device__ __forceinline__ void pass_load(v4f (&wv)[RU][WNI], const float *__restrict__ Wt, int n, int nr, int base)
+// A lane's part of one row: its pieces of the weights and, with momentum, of the velocities.
+template <bool MOM>
+struct RowPart {
+    v4f w[WNI];
+    v4f v[WNI];
+};
+template <>
+struct RowPart<false> {
+    v4f w[WNI];
+};
+
+__device__ __forceinline__ v4f fma4(float s, const v4f &a, const v4f &w)
+{
+    return (v4f){__builtin_fmaf(s, a.x, w.x), __builtin_fmaf(s, a.y, w.y), __builtin_fmaf(s, a.z, w.z), __builtin_fmaf(s, a.w, w.w)};
+}
+
+// The update of one row part by the rule of dn_update, g = (lr delta_r) a_k:
+//   plain gradient descent   w = fma(-(lr delta_r), a_k, w)
+//   momentum                 v = fma(mu, v, -(lr delta_r) a_k);  w = w + v
+template <bool MOM>
+__device__ __forceinline__ void update_piece(RowPart<MOM> &r, int j, float nld, float mu, const v4f (&a4)[WNI])
+{
+    if constexpr (MOM) {
+        r.v[j] = fma4(mu, r.v[j], a4[j] * nld);
+        r.w[j] = r.w[j] + r.v[j];
+    } else {
+        r.w[j] = fma4(nld, a4[j], r.w[j]);
+    }
+}
+
+// Rows in memory (LDS or device): nr rows of n floats at Wt (their velocities at Vt); row r of the
+// block takes delta dl[r] and leaves its product with the next sample in out[r].  Sixteen lanes per
+// row, four rows per wave at a time, RU such groups in flight.  A pass is split in two -- its loads,
+// and everything that needs them -- so that other work can be put between the two.  Loads are
+// unconditional (clamped addresses); columns past the end hold zeros in a4 / x4 and are never stored.
+// Without momentum Vt is written only when keepv is set (the applied change, for a later momentum epoch).
+template <bool MOM, int RU>
+__device__ __forceinline__ void pass_load(RowPart<MOM> (&r)[RU], const float *__restrict__ Wt, const float *__restrict__ Vt,
+                                          int n, int nr, int base)
 {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int sg = lane >> 4, g = lane & 15;
@@ -69,21 +100,20 @@ __device__ __forceinline__ void pass_load(v4f (&wv)[RU][WNI], const float *__res
 #pragma unroll
     for (int u = 0; u < RU; ++u) {
         const int row = base + u * kPass + wave * 4 + sg;
-        const float *wp = Wt + (size_t)min(row, nr - 1) * n;
+        const size_t at = (size_t)min(row, nr - 1) * n;
 #pragma unroll
-        for (int j = 0; j < WNI; ++j) wv[u][j] = *(const v4f *)(wp + 4 * min(g + 16 * j, n4 - 1));
+        for (int j = 0; j < WNI; ++j) {
+            const int c4 = 4 * min(g + 16 * j, n4 - 1);
+            r[u].w[j] = *(const v4f *)(Wt + at + c4);
+            if constexpr (MOM) r[u].v[j] = *(const v4f *)(Vt + at + c4);
+        }
     }
 }
 
-__device__ __forceinline__ v4f fma4(float s, const v4f &a, const v4f &w)
-{
-    return (v4f){__builtin_fmaf(s, a.x, w.x), __builtin_fmaf(s, a.y, w.y), __builtin_fmaf(s, a.z, w.z), __builtin_fmaf(s, a.w, w.w)};
-}
-
-template <bool UPDATE, bool DOT, int RU>
-__device__ __forceinline__ void pass_finish(v4f (&wv)[RU][WNI], float *__restrict__ Wt, float *__restrict__ Vt, int n, int nr,
+template <bool MOM, bool UPDATE, bool DOT, int RU>
+__device__ __forceinline__ void pass_finish(RowPart<MOM> (&r)[RU], float *__restrict__ Wt, float *__restrict__ Vt, int n, int nr,
                                             int base, const float *dl, const v4f (&a4)[WNI], const v4f (&x4)[WNI], float lr,
-                                            bool keepv, float *out)
+                                            float mu, bool keepv, float *out)
 {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int sg = lane >> 4, g = lane & 15;
@@ -95,40 +125,44 @@ __device__ __forceinline__ void pass_finish(v4f (&wv)[RU][WNI], float *__restric
         const int rc = min(row, nr - 1);
         if (UPDATE) {
             const float nld = -(lr * dl[rc]);
-            float *wp = Wt + (size_t)rc * n;
+            const size_t at = (size_t)rc * n;
 #pragma unroll
             for (int j = 0; j < WNI; ++j) {
                 const int c = g + 16 * j;
-                wv[u][j] = fma4(nld, a4[j], wv[u][j]);
+                update_piece<MOM>(r[u], j, nld, mu, a4);
                 if (rin && c < n4) {
-                    *(v4f *)(wp + 4 * c) = wv[u][j];
-                    if (keepv) *(v4f *)(Vt + (size_t)rc * n + 4 * c) = a4[j] * nld;
+                    *(v4f *)(Wt + at + 4 * c) = r[u].w[j];
+                    if constexpr (MOM) {
+                        *(v4f *)(Vt + at + 4 * c) = r[u].v[j];
+                    } else {
+                        if (keepv) *(v4f *)(Vt + at + 4 * c) = a4[j] * nld;
+                    }
                 }
             }
         }
         if (DOT) {
-            const float acc = row16_sum(dot_pieces(wv[u], x4));
+            const float acc = row16_sum(dot_pieces(r[u].w, x4));
             if (g == 0 && rin) out[row] = acc;
         }
     }
 }
 
-template <bool UPDATE, bool DOT, int RU>
+template <bool MOM, bool UPDATE, bool DOT, int RU>
 __device__ __forceinline__ void sweep_mem(float *__restrict__ Wt, float *__restrict__ Vt, int n, int nr, const float *dl,
-                                          const v4f (&a4)[WNI], const v4f (&x4)[WNI], float lr, bool keepv, float *out,
+                                          const v4f (&a4)[WNI], const v4f (&x4)[WNI], float lr, float mu, bool keepv, float *out,
                                           int first_base = 0)
 {
     for (int base = first_base; base < nr; base += kPass * RU) {
-        v4f wv[RU][WNI];
-        pass_load<RU>(wv, Wt, n, nr, base);
-        pass_finish<UPDATE, DOT, RU>(wv, Wt, Vt, n, nr, base, dl, a4, x4, lr, keepv, out);
+        RowPart<MOM> r[RU];
+        pass_load<MOM, RU>(r, Wt, Vt, n, nr, base);
+        pass_finish<MOM, UPDATE, DOT, RU>(r, Wt, Vt, n, nr, base, dl, a4, x4, lr, mu, keepv, out);
     }
 }
 
-// A row in registers: wrow is this lane's part of row `row` of the tier (nr rows).
-template <bool UPDATE, bool DOT>
-__device__ __forceinline__ void reg_row(v4f (&wrow)[WNI], int row, float *__restrict__ Vt, int n, int nr, const float *dl,
-                                        const v4f (&a4)[WNI], const v4f (&x4)[WNI], float lr, bool keepv, float *out)
+// A row in registers: r is this lane's part of row `row` of the tier (nr rows).
+template <bool MOM, bool UPDATE, bool DOT>
+__device__ __forceinline__ void reg_row(RowPart<MOM> &r, int row, float *__restrict__ Vt, int n, int nr, const float *dl,
+                                        const v4f (&a4)[WNI], const v4f (&x4)[WNI], float lr, float mu, bool keepv, float *out)
 {
     const int g = threadIdx.x & 15;
     const int n4 = n >> 2;
@@ -138,24 +172,25 @@ __device__ __forceinline__ void reg_row(v4f (&wrow)[WNI], int row, float *__rest
         const float nld = rin ? -(lr * dl[rc]) : 0.f;
 #pragma unroll
         for (int j = 0; j < WNI; ++j) {
-            wrow[j] = fma4(nld, a4[j], wrow[j]);
-            if (keepv && rin && g + 16 * j < n4) *(v4f *)(Vt + (size_t)rc * n + 4 * (g + 16 * j)) = a4[j] * nld;
+            update_piece<MOM>(r, j, nld, mu, a4);
+            if (!MOM && keepv && rin && g + 16 * j < n4) *(v4f *)(Vt + (size_t)rc * n + 4 * (g + 16 * j)) = a4[j] * nld;
         }
     }
     if (DOT) {
-        const float acc = row16_sum(dot_pieces(wrow, x4));
+        const float acc = row16_sum(dot_pieces(r.w, x4));
         if (g == 0 && rin) out[row] = acc;
     }
 }
 
-// The three tiers of a workgroup's rows: streamed (ns rows at Ws), registers (nrr), LDS (nl rows at Wl);
-// local row numbers run LDS, registers, streamed.  V: the block's rows of the velocity (device memory).
+// The three tiers of a workgroup's rows: streamed (ns rows at Ws), registers (nrr), LDS (nl rows at Wl,
+// with momentum their velocities at Vl); local row numbers run LDS, registers, streamed.  V: the
+// block's rows of the velocity in device memory.
 struct SweepArgs {
-    float *Ws, *Wl, *V;
+    float *Ws, *Wl, *Vl, *V;
     const float *d;
     float *z;
     int n, nl, nrr, ns;
-    float lr;
+    float lr, mu;
 };
 
 // One stage of the sweep: streamed pass i (in cur, loaded two stages ago) is finished, the loads of
@@ -166,12 +201,12 @@ struct StageArgs {
     const float *ds, *dr, *dl;
     float *zs, *zr, *zl;
     int n, ns, nrr, nl, npass, nlpass;
-    float lr;
+    float lr, mu;
     bool keepv;
 };
 
-template <bool U, bool D>
-__device__ __forceinline__ void sweep_stage(v4f (&cur)[1][WNI], v4f (&wrow)[WNI], int i, int last, const StageArgs &t,
+template <bool MOM, bool U, bool D>
+__device__ __forceinline__ void sweep_stage(RowPart<MOM> (&cur)[1], RowPart<MOM> &wrow, int i, int last, const StageArgs &t,
                                             const v4f (&a4)[WNI], const v4f (&x4)[WNI])
 {
     const int wave = threadIdx.x >> 6, sg = (threadIdx.x & 63) >> 4;
@@ -179,25 +214,27 @@ __device__ __forceinline__ void sweep_stage(v4f (&cur)[1][WNI], v4f (&wrow)[WNI]
     // loop invariant over the steps, and the compiler computes them all once and keeps them in registers)
     int base = i * kPass;
     asm volatile("" : "+s"(base));
-    if (i < t.npass) pass_finish<U, D, 1>(cur, t.Ws, t.Vs, t.n, t.ns, base, t.ds, a4, x4, t.lr, t.keepv, t.zs);
-    if (i + 2 < t.npass && i + 2 < last) pass_load<1>(cur, t.Ws, t.n, t.ns, base + 2 * kPass);
-    reg_row<U, D>(wrow, i * kPass + wave * 4 + sg, t.Vr, t.n, t.nrr, t.dr, a4, x4, t.lr, t.keepv, t.zr);
+    if (i < t.npass) pass_finish<MOM, U, D, 1>(cur, t.Ws, t.Vs, t.n, t.ns, base, t.ds, a4, x4, t.lr, t.mu, t.keepv, t.zs);
+    if (i + 2 < t.npass && i + 2 < last) pass_load<MOM, 1>(cur, t.Ws, t.Vs, t.n, t.ns, base + 2 * kPass);
+    reg_row<MOM, U, D>(wrow, i * kPass + wave * 4 + sg, t.Vr, t.n, t.nrr, t.dr, a4, x4, t.lr, t.mu, t.keepv, t.zr);
     if (i < t.nlpass) {
-        v4f wl[1][WNI];
-        pass_load<1>(wl, t.Wl, t.n, t.nl, base);
-        pass_finish<U, D, 1>(wl, t.Wl, t.Vl, t.n, t.nl, base, t.dl, a4, x4, t.lr, t.keepv, t.zl);
+        RowPart<MOM> wl[1];
+        pass_load<MOM, 1>(wl, t.Wl, t.Vl, t.n, t.nl, base);
+        pass_finish<MOM, U, D, 1>(wl, t.Wl, t.Vl, t.n, t.nl, base, t.dl, a4, x4, t.lr, t.mu, t.keepv, t.zl);
     }
 }
 
 // The first two streamed passes of the NEXT sweep, requested as soon as a sweep has written them (a
 // thread reads back the rows and columns it wrote itself): they travel while the step's small
 // phases -- the exchange of the partial net inputs, the output stage, the deltas -- run.
-__device__ __forceinline__ void sweep_preload(v4f (&bufa)[1][WNI], v4f (&bufb)[1][WNI], const float *Ws, int n, int ns)
+template <bool MOM>
+__device__ __forceinline__ void sweep_preload(RowPart<MOM> (&bufa)[1], RowPart<MOM> (&bufb)[1], const float *Ws, const float *Vs,
+                                              int n, int ns)
 {
     int base = 0;
     asm volatile("" : "+s"(base));
-    if (ns > 0) pass_load<1>(bufa, Ws, n, ns, base);
-    if (ns > kPass) pass_load<1>(bufb, Ws, n, ns, base + kPass);
+    if (ns > 0) pass_load<MOM, 1>(bufa, Ws, Vs, n, ns, base);
+    if (ns > kPass) pass_load<MOM, 1>(bufb, Ws, Vs, n, ns, base + kPass);
 }
 
 // One sweep over all three tiers.  The streamed rows wait for memory, the register and LDS rows for
@@ -205,32 +242,33 @@ __device__ __forceinline__ void sweep_preload(v4f (&bufa)[1][WNI], v4f (&bufb)[1
 // therefore interleaved by hand, one stage per register row (RR of them), the streamed
 // passes two ahead in two buffers.  On entry bufa / bufb hold streamed passes 0 and 1 (sweep_preload);
 // on exit they hold them again, for the next sweep.  Streamed and LDS passes beyond RR follow in plain loops.
-// wres[i] is this lane's part of row i * kPass + wave * 4 + sg of the register tier.
-template <bool U, bool D, int RR>
-__device__ __forceinline__ void sweep_all(v4f (&wres)[RR > 0 ? RR : 1][WNI], v4f (&bufa)[1][WNI], v4f (&bufb)[1][WNI],
+// res[i] is this lane's part of row i * kPass + wave * 4 + sg of the register tier.
+template <bool MOM, bool U, bool D, int RR>
+__device__ __forceinline__ void sweep_all(RowPart<MOM> (&res)[RR > 0 ? RR : 1], RowPart<MOM> (&bufa)[1], RowPart<MOM> (&bufb)[1],
                                           const SweepArgs &sa, const v4f (&a4)[WNI], const v4f (&x4)[WNI], bool keepv)
 {
     const int first_s = sa.nl + sa.nrr;
     StageArgs t;
-    t.Ws = sa.Ws; t.Vs = sa.V + (size_t)first_s * sa.n; t.Vr = sa.V + (size_t)sa.nl * sa.n; t.Wl = sa.Wl; t.Vl = sa.V;
+    t.Ws = sa.Ws; t.Vs = sa.V + (size_t)first_s * sa.n; t.Vr = sa.V + (size_t)sa.nl * sa.n; t.Wl = sa.Wl;
+    t.Vl = MOM ? sa.Vl : sa.V;   // the LDS rows' velocities: beside them with momentum, else device memory (written on request)
     t.ds = sa.d + first_s; t.dr = sa.d + sa.nl; t.dl = sa.d;
     t.zs = sa.z + first_s; t.zr = sa.z + sa.nl; t.zl = sa.z;
     t.n = sa.n; t.ns = sa.ns; t.nrr = sa.nrr; t.nl = sa.nl;
     t.npass = (sa.ns + kPass - 1) / kPass;
     t.nlpass = (sa.nl + kPass - 1) / kPass;
-    t.lr = sa.lr; t.keepv = keepv;
+    t.lr = sa.lr; t.mu = sa.mu; t.keepv = keepv;
 #pragma unroll
     for (int i = 0; i + 1 < RR; i += 2) {   // stages in pairs: even streamed passes go through bufa, odd ones through bufb
-        sweep_stage<U, D>(bufa, wres[i], i, RR, t, a4, x4);
-        sweep_stage<U, D>(bufb, wres[i + 1], i + 1, RR, t, a4, x4);
+        sweep_stage<MOM, U, D>(bufa, res[i], i, RR, t, a4, x4);
+        sweep_stage<MOM, U, D>(bufb, res[i + 1], i + 1, RR, t, a4, x4);
     }
-    if (RR % 2 == 1) sweep_stage<U, D>(bufa, wres[RR - 1], RR - 1, RR, t, a4, x4);
-    if (t.npass > RR) sweep_mem<U, D, 1>(t.Ws, t.Vs, t.n, t.ns, t.ds, a4, x4, t.lr, keepv, t.zs, RR * kPass);
-    if (t.nlpass > RR) sweep_mem<U, D, 1>(t.Wl, t.Vl, t.n, t.nl, t.dl, a4, x4, t.lr, keepv, t.zl, RR * kPass);
-    sweep_preload(bufa, bufb, t.Ws, t.n, t.ns);
+    if (RR % 2 == 1) sweep_stage<MOM, U, D>(bufa, res[RR - 1], RR - 1, RR, t, a4, x4);
+    if (t.npass > RR) sweep_mem<MOM, U, D, 1>(t.Ws, t.Vs, t.n, t.ns, t.ds, a4, x4, t.lr, t.mu, keepv, t.zs, RR * kPass);
+    if (t.nlpass > RR) sweep_mem<MOM, U, D, 1>(t.Wl, t.Vl, t.n, t.nl, t.dl, a4, x4, t.lr, t.mu, keepv, t.zl, RR * kPass);
+    sweep_preload<MOM>(bufa, bufb, t.Ws, t.Vs, t.n, t.ns);
 }
 
-template <int RR>
+template <int RR, bool MOM>
 __global__ __launch_bounds__(kThreads) void wide_epoch_kernel(WidePlan p)
 {
     extern __shared__ __align__(16) float lds[];
@@ -249,7 +287,9 @@ __global__ __launch_bounds__(kThreads) void wide_epoch_kernel(WidePlan p)
     float *W2c = lds + p.lds_w2;                    // [nL][perp]: the own columns of W_2
     float *zall = lds + p.lds_zall;                 // [grid][nL] partial net inputs of the output layer
     float *zL = lds + p.lds_out, *dL = zL + WIDE_MAX_NL, *bL = dL + WIDE_MAX_NL;
-    float *W1l = lds + p.lds_w1;                    // tier 1
+    float *W1l = lds + p.lds_w1;                    // tier 1 (with momentum its velocities follow at V1l)
+    float *V1l = W1l + (size_t)p.lds_rows * n0;
+    float *vb1 = lds + p.lds_vb, *VW2c = lds + p.lds_vw2, *vbL = bL + WIDE_MAX_NL;   // velocities of b_1, the W_2 columns, b_2 (momentum)
     float *W1r = p.W1 + (size_t)(r0 + nl) * n0;     // tier 2's rows in device memory (prologue / epilogue)
     float *W1s = p.W1 + (size_t)(r0 + nl + nrr) * n0;   // tier 3
     float *V1 = p.VW1 + (size_t)r0 * n0;
@@ -263,14 +303,26 @@ __global__ __launch_bounds__(kThreads) void wide_epoch_kernel(WidePlan p)
         W2c[i] = j < nr ? p.W2[(size_t)k * n1 + r0 + j] : 0.f;
     }
     copy_floats(W1l, p.W1 + (size_t)r0 * n0, nl * n0);
-    v4f wres[RR > 0 ? RR : 1][WNI];
+    if (MOM) {
+        copy_floats(V1l, V1, nl * n0);
+        for (int k = tid; k < nL; k += kThreads) vbL[k] = p.Vb2[k];
+        for (int j = tid; j < nr; j += kThreads) vb1[j] = p.Vb1[r0 + j];
+        for (int i = tid; i < nL * perp; i += kThreads) {
+            const int k = i / perp, j = i - k * perp;
+            VW2c[i] = j < nr ? p.VW2[(size_t)k * n1 + r0 + j] : 0.f;
+        }
+    }
+    RowPart<MOM> wres[RR > 0 ? RR : 1];
 #pragma unroll
     for (int i = 0; i < RR; ++i) {
         const int row = min(i * kPass + wave * 4 + sg, max(nrr - 1, 0));
 #pragma unroll
         for (int j = 0; j < WNI; ++j) {
             const int c = g + 16 * j;
-            wres[i][j] = (nrr > 0 && c < n4) ? *(const v4f *)(W1r + (size_t)row * n0 + 4 * c) : (v4f){0.f, 0.f, 0.f, 0.f};
+            const bool on = nrr > 0 && c < n4;
+            const size_t at = (size_t)(nl + row) * n0 + 4 * min(c, n4 - 1);
+            wres[i].w[j] = on ? *(const v4f *)(p.W1 + (size_t)r0 * n0 + at) : (v4f){0.f, 0.f, 0.f, 0.f};
+            if constexpr (MOM) wres[i].v[j] = on ? *(const v4f *)(V1 + at) : (v4f){0.f, 0.f, 0.f, 0.f};
         }
     }
     for (int k = tid; k < n0; k += kThreads) xbuf[k] = p.X[k];
@@ -279,15 +331,15 @@ __global__ __launch_bounds__(kThreads) void wide_epoch_kernel(WidePlan p)
     __syncthreads();
 
     // one sweep over all three tiers: rows take d_own, products with x4 go to z1
-    const SweepArgs sa{W1s, W1l, V1, d_own, z1, n0, nl, nrr, ns, p.lr};
-    v4f bufa[1][WNI], bufb[1][WNI];   // streamed passes 0 and 1 of the next sweep, in flight between sweeps
+    const SweepArgs sa{W1s, W1l, V1l, V1, d_own, z1, n0, nl, nrr, ns, p.lr, p.mu};
+    RowPart<MOM> bufa[1], bufb[1];   // streamed passes 0 and 1 of the next sweep, in flight between sweeps
     {   // the first sample's products with W_1
         v4f a4[WNI], x4[WNI];
         lane_pieces(x4, xbuf, n4, g);
 #pragma unroll
         for (int j = 0; j < WNI; ++j) a4[j] = (v4f){0.f, 0.f, 0.f, 0.f};
-        sweep_preload(bufa, bufb, W1s, n0, ns);
-        sweep_all<false, true, RR>(wres, bufa, bufb, sa, a4, x4, false);
+        sweep_preload<MOM>(bufa, bufb, W1s, V1 + (size_t)(nl + nrr) * n0, n0, ns);
+        sweep_all<MOM, false, true, RR>(wres, bufa, bufb, sa, a4, x4, false);
     }
     __syncthreads();
 
@@ -295,7 +347,7 @@ __global__ __launch_bounds__(kThreads) void wide_epoch_kernel(WidePlan p)
         const uint32_t seq = p.seq0 + 1u + (uint32_t)s;
         const int par = (int)(seq & 1u);
         const bool more = s + 1 < p.n_samples;
-        const bool keepv = p.keep_v && !more;   // the epoch's last step also leaves the applied change as velocity
+        const bool keepv = !MOM && p.keep_v && !more;   // plain gradient descent: the epoch's last step also leaves the applied change as velocity
         const float *x = xbuf + (size_t)(s & 1) * n0p;
         float *xn = xbuf + (size_t)((s + 1) & 1) * n0p;
 
@@ -373,8 +425,14 @@ __global__ __launch_bounds__(kThreads) void wide_epoch_kernel(WidePlan p)
             }
             if (k0 < nL) {
                 dL[k0] = d0;
-                bL[k0] = bL[k0] - p.lr * d0;
-                if (keepv && w == 0) p.Vb2[k0] = -(p.lr * d0);
+                if (MOM) {
+                    const float vv = p.mu * vbL[k0] - p.lr * d0;
+                    vbL[k0] = vv;
+                    bL[k0] = bL[k0] + vv;
+                } else {
+                    bL[k0] = bL[k0] - p.lr * d0;
+                    if (keepv && w == 0) p.Vb2[k0] = -(p.lr * d0);
+                }
             }
             if (w == 0 && lane == 0) loss_acc += (double)e;
         }
@@ -387,14 +445,24 @@ __global__ __launch_bounds__(kThreads) void wide_epoch_kernel(WidePlan p)
             for (int k = 0; k < nL; ++k) {
                 const float wv = W2c[k * perp + j], dk = dL[k];
                 sacc += wv * dk;
-                const float ch = -((p.lr * dk) * a);
+                float ch = -((p.lr * dk) * a);
+                if (MOM) {
+                    ch = __builtin_fmaf(p.mu, VW2c[k * perp + j], ch);
+                    VW2c[k * perp + j] = ch;
+                }
                 W2c[k * perp + j] = wv + ch;
                 if (keepv) p.VW2[(size_t)k * n1 + r0 + j] = ch;
             }
             const float d = sacc * act_deriv(p.act1, a);
             d_own[j] = d;
-            b1[j] = b1[j] - p.lr * d;
-            if (keepv) p.Vb1[r0 + j] = -(p.lr * d);
+            if (MOM) {
+                const float vv = p.mu * vb1[j] - p.lr * d;
+                vb1[j] = vv;
+                b1[j] = b1[j] + vv;
+            } else {
+                b1[j] = b1[j] - p.lr * d;
+                if (keepv) p.Vb1[r0 + j] = -(p.lr * d);
+            }
         }
         __syncthreads();
 
@@ -407,7 +475,7 @@ __global__ __launch_bounds__(kThreads) void wide_epoch_kernel(WidePlan p)
             // updates and the compiler kept a second set of registers for them.  After the last step the
             // products are taken with whatever the other input buffer holds and nobody reads them.)
             lane_pieces(x4, xn, n4, g);
-            sweep_all<true, true, RR>(wres, bufa, bufb, sa, a4, x4, keepv);
+            sweep_all<MOM, true, true, RR>(wres, bufa, bufb, sa, a4, x4, keepv);
         }
         __syncthreads();
         y_cur = y_next;
@@ -416,22 +484,35 @@ __global__ __launch_bounds__(kThreads) void wide_epoch_kernel(WidePlan p)
     // ---- epilogue: everything the workgroup kept on the chip goes back to device memory ----
     __syncthreads();
     copy_floats(p.W1 + (size_t)r0 * n0, W1l, nl * n0);
+    if (MOM) copy_floats(V1, V1l, nl * n0);
 #pragma unroll
     for (int i = 0; i < RR; ++i) {
         const int row = i * kPass + wave * 4 + sg;
 #pragma unroll
         for (int j = 0; j < WNI; ++j) {
             const int c = g + 16 * j;
-            if (row < nrr && c < n4) *(v4f *)(W1r + (size_t)row * n0 + 4 * c) = wres[i][j];
+            if (row < nrr && c < n4) {
+                *(v4f *)(W1r + (size_t)row * n0 + 4 * c) = wres[i].w[j];
+                if constexpr (MOM) *(v4f *)(V1 + (size_t)(nl + row) * n0 + 4 * c) = wres[i].v[j];
+            }
         }
     }
-    for (int j = tid; j < nr; j += kThreads) p.b1[r0 + j] = b1[j];
+    for (int j = tid; j < nr; j += kThreads) {
+        p.b1[r0 + j] = b1[j];
+        if (MOM) p.Vb1[r0 + j] = vb1[j];
+    }
     for (int i = tid; i < nL * perp; i += kThreads) {
         const int k = i / perp, j = i - k * perp;
-        if (j < nr) p.W2[(size_t)k * n1 + r0 + j] = W2c[i];
+        if (j < nr) {
+            p.W2[(size_t)k * n1 + r0 + j] = W2c[i];
+            if (MOM) p.VW2[(size_t)k * n1 + r0 + j] = VW2c[i];
+        }
     }
     if (w == 0) {
-        for (int k = tid; k < nL; k += kThreads) p.b2[k] = bL[k];
+        for (int k = tid; k < nL; k += kThreads) {
+            p.b2[k] = bL[k];
+            if (MOM) p.Vb2[k] = vbL[k];
+        }
         if (tid == 0) *p.loss_acc += loss_acc;
     }
 }
@@ -440,7 +521,7 @@ __global__ __launch_bounds__(kThreads) void wide_epoch_kernel(WidePlan p)
 
 // ---- host side -------------------------------------------------------------------
 
-bool wide_geometry(const int32_t *n, int L, int max_wg, WideGeom &g)
+bool wide_geometry(const int32_t *n, int L, int max_wg, bool want_v, WideGeom &g)
 {
     g = WideGeom{};
     if (L != 2) return false;
@@ -461,17 +542,20 @@ bool wide_geometry(const int32_t *n, int L, int max_wg, WideGeom &g)
     g.lds_b = (int)f; f += pad4(per);
     g.lds_z = (int)f; f += pad4(per);
     g.lds_w2 = (int)f; f += (int64_t)nL * pad4(per);
+    g.lds_vb = (int)f; if (want_v) f += pad4(per);
+    g.lds_vw2 = (int)f; if (want_v) f += (int64_t)nL * pad4(per);
     g.lds_zall = (int)f; f += pad4(grid * nL);
-    g.lds_out = (int)f; f += 3 * WIDE_MAX_NL;
+    g.lds_out = (int)f; f += 4 * WIDE_MAX_NL;
     g.lds_w1 = (int)f;
     const int64_t room = (int64_t)(ON_MAX_LDS_BYTES / sizeof(float)) - f;
     if (room < 0) return false;
-    int rows = (int)std::min<int64_t>(room / n0, per);
+    // rows of W_1 in LDS; with momentum each brings its row of velocities
+    int rows = (int)std::min<int64_t>(room / ((int64_t)n0 * (want_v ? 2 : 1)), per);
     // the kernel is for layers that do NOT fit: a net whose rows all fit in LDS belongs to the kernels that
     // keep every weight there
-    if (rows >= per) return false;
+    if ((int64_t)per * n0 <= room) return false;
     g.lds_rows = rows;
-    f += (int64_t)rows * n0;
+    f += (int64_t)rows * n0 * (want_v ? 2 : 1);
     g.lds_floats = (int)f;
     g.words = 2 * (size_t)grid * nL;
     g.ok = true;
@@ -486,13 +570,19 @@ size_t wide_exchange_bytes_bound(const int32_t *n, int L)
 
 hipError_t wide_prepare()
 {
-    return hipFuncSetAttribute((const void *)wide_epoch_kernel<WIDE_REG_ROWS>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                               (int)ON_MAX_LDS_BYTES);
+    hipError_t e = hipFuncSetAttribute((const void *)wide_epoch_kernel<WIDE_REG_ROWS, false>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)ON_MAX_LDS_BYTES);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute((const void *)wide_epoch_kernel<WIDE_REG_ROWS_MOMENTUM, true>,
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)ON_MAX_LDS_BYTES);
 }
 
 hipError_t launch_wide_epoch(const WideGeom &g, const WidePlan &plan, hipStream_t stream)
 {
-    return launch_resident(wide_epoch_kernel<WIDE_REG_ROWS>, plan, g.grid, (size_t)g.lds_floats * sizeof(float), stream);
+    if (plan.mu != 0.f)
+        return launch_resident(wide_epoch_kernel<WIDE_REG_ROWS_MOMENTUM, true>, plan, g.grid, (size_t)g.lds_floats * sizeof(float),
+                               stream);
+    return launch_resident(wide_epoch_kernel<WIDE_REG_ROWS, false>, plan, g.grid, (size_t)g.lds_floats * sizeof(float), stream);
 }
 
 }  // namespace dn

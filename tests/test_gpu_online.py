@@ -30,8 +30,8 @@ def run_pair(dn, w, n, passes, mode, min_tile=None, tol=1e-4, biases=True, resid
     """`passes` = list of momenta; one pass over the first n samples per entry.  twin=0 keeps
     plain-gradient-descent passes of deeper nets on the general persistent kernel; tiny=1 lets nets
     with no layer wider than 64 run on the one-wavefront kernel; wide=1 lets two-layer nets with a
-    hidden layer beyond LDS run on the kernel that keeps rows of W_1 in LDS and registers (its
-    plain-gradient-descent passes must then report that schedule)."""
+    hidden layer beyond LDS run on the kernel that keeps rows of W_1 in LDS and registers (every
+    pass must then report that schedule)."""
     if biases:
         rng = np.random.default_rng(11)
         w.b = [rng.standard_normal(k).astype(np.float32) * 0.1 for k in w.widths[1:]]
@@ -53,8 +53,7 @@ def run_pair(dn, w, n, passes, mode, min_tile=None, tol=1e-4, biases=True, resid
         if tiny:
             assert net.dn_last_schedule() == dn.DN_SCHED_ONE_WAVE, net.dn_last_schedule()
         elif wide:
-            want = dn.DN_SCHED_WIDE_HIDDEN if mu == 0.0 else dn.DN_SCHED_PER_SAMPLE
-            assert net.dn_last_schedule() == want, (net.dn_last_schedule(), want)
+            assert net.dn_last_schedule() == dn.DN_SCHED_WIDE_HIDDEN, net.dn_last_schedule()
         elif mode == PERSISTENT and twin_expected is not None:
             want = dn.DN_SCHED_TWO_COPY if (twin_expected and mu == 0.0) else dn.DN_SCHED_PER_SAMPLE
             assert net.dn_last_schedule() == want, (net.dn_last_schedule(), want)
@@ -281,26 +280,25 @@ def test_paper_shape_first_steps(dnlib, wide):
 
 
 WIDE_SHAPES = [
-    # two layers, inputs a multiple of 4 and at most 384, at most 16 outputs, a hidden layer beyond LDS;
-    # last column: whether the general persistent kernel takes the net too (the momentum pass runs on it)
-    ([340, 100000, 10], [TANH, SOFTMAX], CE, True),     # the paper's network: rows in LDS, in registers and streamed
-    ([340, 99991, 10], [TANH, SOFTMAX], CE, True),      # a last workgroup with fewer rows than the others
-    ([384, 50000, 16], [SIG, SOFTMAX], CE, True),       # the longest rows and the widest output the kernel takes
-    ([128, 90000, 7], [RELU, SIG], MSE, True),          # short rows: LDS and registers hold the whole block, nothing streams
-    ([64, 700000, 3], [TANH, SIG], MSE, False),         # many rows per workgroup: most of them streamed
-    ([8, 1000000, 2], [TANH, SOFTMAX], CE, False),      # rows of two float4s: fourteen of a row's sixteen lanes idle
+    # two layers, inputs a multiple of 4 and at most 384, at most 16 outputs, a hidden layer beyond LDS
+    ([340, 100000, 10], [TANH, SOFTMAX], CE),     # the paper's network: rows in LDS, in registers and streamed
+    ([340, 99991, 10], [TANH, SOFTMAX], CE),      # a last workgroup with fewer rows than the others
+    ([384, 50000, 16], [SIG, SOFTMAX], CE),       # the longest rows and the widest output the kernel takes
+    ([128, 90000, 7], [RELU, SIG], MSE),          # short rows: without momentum LDS and registers hold the whole block
+    ([64, 700000, 3], [TANH, SIG], MSE),          # many rows per workgroup: most of them streamed
+    ([8, 1000000, 2], [TANH, SOFTMAX], CE),       # rows of two float4s: fourteen of a row's sixteen lanes idle
 ]
 
 
-@pytest.mark.parametrize("widths,acts,loss,momentum_pass", WIDE_SHAPES)
-def test_wide_hidden_layer_epochs_match_checker(dnlib, widths, acts, loss, momentum_pass):
-    """Plain-gradient-descent passes on the wide-hidden-layer kernel against the checker; where the
-    general persistent kernel takes the net as well, a momentum pass on it in between (it starts
-    from the velocities the first pass left)."""
+@pytest.mark.parametrize("widths,acts,loss", WIDE_SHAPES)
+def test_wide_hidden_layer_epochs_match_checker(dnlib, widths, acts, loss):
+    """Four passes on the wide-hidden-layer kernel against the checker: plain gradient descent (its last
+    step leaves the applied change as velocity), two momentum passes that start from it (rows and
+    velocities side by side in LDS and registers), plain gradient descent again."""
     announce("online wide-hidden-layer kernel widths=%s" % (widths,))
     w = synth.make("wide", widths, acts, loss, n_samples=20, features="normal", init="xavier_uniform",
                    batch=1, lr=0.0005, momentum=0.0, seed=6)
-    run_pair(dnlib, w, 20, [0.0, 0.5, 0.0] if momentum_pass else [0.0, 0.0], PERSISTENT, wide=1)
+    run_pair(dnlib, w, 20, [0.0, 0.5, 0.9, 0.0], PERSISTENT, wide=1)
 
 
 def test_wide_hidden_layer_kernel_edges(dnlib):
@@ -309,8 +307,8 @@ def test_wide_hidden_layer_kernel_edges(dnlib):
     announce("online wide-hidden-layer kernel: single sample, consecutive epochs, refusals")
     w = synth.make("wide1", [340, 100000, 10], [TANH, SOFTMAX], CE, n_samples=5, features="normal", init="xavier_uniform",
                    batch=1, lr=0.0005, momentum=0.0, seed=8)
-    run_pair(dnlib, w, 1, [0.0], PERSISTENT, wide=1)
-    run_pair(dnlib, w, 5, [0.0, 0.0, 0.0], PERSISTENT, wide=1)
+    run_pair(dnlib, w, 1, [0.0, 0.5], PERSISTENT, wide=1)
+    run_pair(dnlib, w, 5, [0.0, 0.0, 0.5, 0.5], PERSISTENT, wide=1)
     for widths, acts in (([340, 3000, 10], [TANH, SOFTMAX]),            # the hidden layer fits in LDS
                          ([400, 100000, 10], [TANH, SOFTMAX]),          # more than 384 inputs
                          ([338, 100000, 10], [TANH, SOFTMAX]),          # inputs not a multiple of 4

@@ -1,4 +1,4 @@
-// Per-sample (batch 1) training, plain gradient descent, of two-layer nets whose hidden layer is
+// Per-sample (batch 1) training, with or without momentum, of two-layer nets whose hidden layer is
 // too wide for LDS and whose output layer is narrow -- the shape of the network the paper trains
 // (340 inputs, 100000 hidden units, 10 softmax outputs; section "Experimental Evaluation") -- as
 // ONE persistent kernel per epoch that keeps most of W_1 on the chip.
@@ -20,6 +20,8 @@
 // so fewer, fatter threads leave more of the register file to the weights.  RR = 12 keeps 288
 // registers per lane for them.  For the paper's network (391 rows of 340 floats per workgroup) that is
 // 93 rows in LDS, 192 in registers and 106 streamed: a quarter of the bytes the all-streaming sweep moves.
+// With momentum every row brings its row of velocities along, in the same tier (LDS rows side by side,
+// 48 registers per register row, four of them; streamed rows move 16 bytes per weight and step).
 // At the end of the launch tiers 1 and 2, the biases and the columns of W_2 go back to device memory.
 #include <algorithm>
 #include <type_traits>

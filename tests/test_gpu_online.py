@@ -526,3 +526,32 @@ def test_persistent_deep_minibatch_is_bitwise_reproducible(dnlib):
     assert outs[0][0] == outs[1][0]
     for a, b in zip(outs[0][1][0] + outs[0][1][1], outs[1][1][0] + outs[1][1][1]):
         assert np.array_equal(a, b)
+
+
+def test_every_benchmark_workload_takes_its_intended_schedule(dnlib):
+    """The automatic choice of dn_train_epoch for the shapes bench.py times (a few steps of each):
+    a silent fall-back to a slower schedule would still pass every parity test."""
+    announce("schedules of the benchmark workloads")
+    S = dnlib
+    cases = [
+        (synth.iris_like(), S.DN_SCHED_ONE_WAVE),
+        (synth.digits_like_online(n_samples=8), S.DN_SCHED_TWO_COPY),
+        (synth.digits_like_minibatch(n_samples=256), S.DN_SCHED_MINIBATCH),
+        (synth.wide_relu(n_samples=512), S.DN_SCHED_LAUNCHES),
+        (synth.tanh_sweep(1, n_samples=8), S.DN_SCHED_TWO_COPY),
+        (synth.tanh_sweep(8, n_samples=32), S.DN_SCHED_MINIBATCH_DEEP),
+        (synth.tanh_sweep(32, n_samples=64), S.DN_SCHED_MINIBATCH_DEEP),
+        (synth.tanh_sweep(128, n_samples=256), S.DN_SCHED_LAUNCHES),
+        (synth.tanh_sweep(512, n_samples=1024), S.DN_SCHED_LAUNCHES),
+        (synth.tanh_sweep(2048, n_samples=2048), S.DN_SCHED_LAUNCHES),
+        (synth.paper_shape(n_samples=4), S.DN_SCHED_WIDE_HIDDEN),
+    ]
+    for w, want in cases:
+        net = S.Net(w.widths, w.acts, w.loss, w.batch)
+        net.set_all(w.W, w.b)
+        assert net.dn_last_schedule() == S.DN_SCHED_NONE
+        loss = net.dn_train_epoch(torch.from_numpy(w.X).to("cuda:0"), torch.from_numpy(w.labels).to("cuda:0"), w.batch,
+                                  w.lr, w.momentum)
+        assert np.isfinite(loss), w.name
+        assert net.dn_last_schedule() == want, (w.name, net.dn_last_schedule(), want)
+        net.close()

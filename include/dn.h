@@ -407,7 +407,8 @@ enum {
     DN_SCHED_MINIBATCH = 4,       /* the persistent minibatch kernel for one- and two-layer nets */
     DN_SCHED_MINIBATCH_DEEP = 5,  /* the persistent minibatch kernel for deeper nets */
     DN_SCHED_ONE_WAVE = 6,        /* batch 1, every layer at most 64 wide: one wavefront runs the epoch */
-    DN_SCHED_WIDE_HIDDEN = 7      /* batch 1, two layers, a hidden layer too wide for LDS: rows in LDS, registers and memory */
+    DN_SCHED_WIDE_HIDDEN = 7,     /* batch 1, two layers, a hidden layer too wide for LDS: rows in LDS, registers and memory */
+    DN_SCHED_ONE_WAVE_REGISTERS = 8 /* batch 1, two layers at most 64 wide, no momentum: one wavefront, the net in its registers */
 };
 dn_status dn_last_schedule(dn_net *net, int32_t *schedule);
 dn_status dn_kernel_time(dn_net *net, int32_t kernel_class, float *ms_total, int64_t *launches);
@@ -453,7 +454,9 @@ dn_status dn_kernel_flops(dn_net *net, int32_t kernel_class, double *flops);
  *                    and streams the rest; 0: such nets take the general persistent kernel
  *   "online_tiny"    1 (default): batch 1 on a net whose layers are all at most 64 wide (and whose
  *                    parameters fit in LDS, twice with momentum) runs on a single wavefront that keeps
- *                    the whole net in LDS; 0: such nets take the other batch-1 schedules
+ *                    the whole net in LDS -- in its registers, for two layers and momentum 0; 2: the
+ *                    same wavefront, always with the net in LDS; 0: such nets take the other batch-1
+ *                    schedules
  * Unknown names or values out of range give DN_ERR_INVALID_ARG.
  */
 dn_status dn_set_option(dn_net *net, const char *name, int64_t value);

@@ -368,6 +368,8 @@ dn_status run_tiny(dn_net *net, TinyPlan &p, const float *X, const int32_t *labe
     p.loss_acc = net->epoch_acc();
     p.X = X; p.labels = labels; p.n_samples = n_samples;
     p.lr = lr; p.mu = mu; p.loss = net->loss; p.keep_v = 1;
+    p.in_registers = (net->online_tiny == 1 && net->L == 2 && mu == 0.f) ? 1 : 0;
+    net->last_schedule = p.in_registers ? DN_SCHED_ONE_WAVE_REGISTERS : DN_SCHED_ONE_WAVE;
     ScopedTimer st(net, DN_K_ONLINE, timing);
     DN_HIP(launch_tiny_epoch(p, net->stream));
     return DN_OK;
@@ -462,7 +464,6 @@ dn_status run_online(dn_net *net, const float *X, const int32_t *labels, int64_t
     if (net->online_tiny && net->tiny_ready) {
         TinyPlan tp;   // every layer at most 64 wide: one wavefront runs the epoch
         if (tiny_plan(net->n.data(), L, mu != 0.f, tp)) {
-            net->last_schedule = DN_SCHED_ONE_WAVE;
             return run_tiny(net, tp, X, labels, n_samples, lr, mu, timing);
         }
     }
@@ -1149,7 +1150,7 @@ dn_status dn_set_option(dn_net *net, const char *name, int64_t value)
         if (value != 0 && value != 1) return DN_ERR_INVALID_ARG;
         net->online_resident = (int)value;
     } else if (!strcmp(name, "online_tiny")) {
-        if (value != 0 && value != 1) return DN_ERR_INVALID_ARG;
+        if (value < 0 || value > 2) return DN_ERR_INVALID_ARG;
         net->online_tiny = (int)value;
     } else if (!strcmp(name, "online_twin")) {
         if (value != 0 && value != 1) return DN_ERR_INVALID_ARG;

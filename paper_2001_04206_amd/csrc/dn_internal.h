@@ -396,6 +396,7 @@ struct TinyPlan {
     float lr, mu;
     int loss, keep_v;
     int lds_floats;
+    int in_registers;   // two-layer nets without momentum may take the form that keeps the net in registers
 };
 
 // Fills the shape-dependent fields; false if a layer is wider than 64 or the parameters (with their

@@ -165,6 +165,121 @@ __global__ __launch_bounds__(64) void tiny_epoch_kernel(TinyPlan p)
     if (lane == 0) *p.loss_acc += loss_acc;
 }
 
+// ---- two-layer nets, plain gradient descent: the whole net in the wave's registers ----
+// With two layers the LDS round trips of the kernel above (one per dependent phase, ~120 cycles each,
+// and nothing else for the lone wave to do meanwhile) can go entirely.  Lane j is hidden unit j and
+// keeps row j of W_1; lane k is output unit k and keeps row k of W_2; lane j also keeps column j of
+// W_2 (the weights that leave its unit), so that the delta of unit j is a product of registers too.
+// A vector that every lane needs -- the features, the hidden activations, the output deltas -- is
+// read lane by lane into scalar registers (one cross-lane read per element) and enters the
+// multiply-adds as a scalar operand.  Both copies of W_2 take the same fused multiply-add from the
+// same operands and stay equal bit for bit; the row copy goes back to device memory at the end.
+// N0 / N1 / N2: compile-time bounds of the three widths (the loops unroll to them; entries past the
+// real widths hold zeros).  No LDS, no barrier, nobody to wait for.
+__device__ __forceinline__ float lane_read(float v, int l)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), l));
+}
+
+template <int N0, int N1, int N2>
+__global__ __launch_bounds__(64) void tiny_regs_epoch_kernel(TinyPlan p)
+{
+    const int lane = threadIdx.x;
+    const TinyLayer &l1 = p.layer[1], &l2 = p.layer[2];
+    const int n0 = l1.n_in, n1 = l1.n_out, n2 = l2.n_out;
+    const bool hid = lane < n1, outl = lane < n2;
+    float w1[N0], w2r[N1], w2c[N2];
+#pragma unroll
+    for (int i = 0; i < N0; ++i) w1[i] = (hid && i < n0) ? l1.W[lane * n0 + i] : 0.f;
+#pragma unroll
+    for (int j = 0; j < N1; ++j) w2r[j] = (outl && j < n1) ? l2.W[lane * n1 + j] : 0.f;
+#pragma unroll
+    for (int k = 0; k < N2; ++k) w2c[k] = (hid && k < n2) ? l2.W[k * n1 + lane] : 0.f;
+    float b1 = hid ? l1.b[lane] : 0.f, b2 = outl ? l2.b[lane] : 0.f;
+    // features travel two steps ahead of their use (lane i holds feature i), labels 64 at a time
+    float x_cur = lane < n0 ? p.X[lane] : 0.f;
+    float x_1 = (1 < p.n_samples && lane < n0) ? p.X[(size_t)n0 + lane] : 0.f;
+    int y_block = 0;
+    double loss_acc = 0.0;
+
+    for (int64_t s = 0; s < p.n_samples; ++s) {
+        const bool keepv = p.keep_v && s == p.n_samples - 1;   // the epoch's last step also leaves the applied change as velocity
+        if ((s & 63) == 0) y_block = p.labels[min(s + lane, p.n_samples - 1)];
+        int y = __builtin_amdgcn_readlane(y_block, (int)(s & 63));
+        y = y < 0 ? 0 : (y >= n2 ? n2 - 1 : y);
+        const float x_2 = (s + 2 < p.n_samples && lane < n0) ? p.X[(size_t)(s + 2) * n0 + lane] : 0.f;
+
+        // ---- feed forward ----
+        float z1 = b1;
+#pragma unroll
+        for (int i = 0; i < N0; ++i) z1 = __builtin_fmaf(w1[i], lane_read(x_cur, i), z1);
+        const float a1 = hid ? act_fn(l1.act, z1) : 0.f;
+        float z2 = b2;
+#pragma unroll
+        for (int j = 0; j < N1; ++j) z2 = __builtin_fmaf(w2r[j], lane_read(a1, j), z2);
+
+        // ---- output error and loss ----
+        const float t = lane == y ? 1.0f : 0.0f;
+        float d2, e;
+        if (p.loss == DN_LOSS_CROSS_ENTROPY) {
+            const float z = outl ? z2 : -INFINITY;
+            const float m = wave_max(z);
+            const float ex = outl ? expf(z - m) : 0.f;
+            const float sum = wave_sum(ex);
+            d2 = outl ? ex * (1.0f / sum) - t : 0.f;
+            e = logf(sum) - (lane_read(z2, y) - m);
+        } else {
+            const float a2 = outl ? act_fn(l2.act, z2) : 0.f;
+            const float f = outl ? a2 - t : 0.f;
+            d2 = f * act_deriv(l2.act, a2);
+            e = wave_sum(0.5f * f * f);
+        }
+        if (lane == 0) loss_acc += (double)e;
+
+        // ---- deltas of the hidden units through W_2 as it was ----
+        float sacc = 0.f;
+#pragma unroll
+        for (int k = 0; k < N2; ++k) sacc = __builtin_fmaf(w2c[k], lane_read(d2, k), sacc);
+        const float d1 = hid ? sacc * act_deriv(l1.act, a1) : 0.f;
+
+        // ---- updates: w = fma(-(lr delta), input, w) ----
+        const float nld2 = -(p.lr * d2), nld1 = -(p.lr * d1);
+#pragma unroll
+        for (int j = 0; j < N1; ++j) {
+            const float aj = lane_read(a1, j);
+            w2r[j] = __builtin_fmaf(nld2, aj, w2r[j]);
+            if (keepv && outl && j < n1) l2.VW[lane * n1 + j] = nld2 * aj;
+        }
+#pragma unroll
+        for (int k = 0; k < N2; ++k) w2c[k] = __builtin_fmaf(lane_read(nld2, k), a1, w2c[k]);
+        b2 += nld2;
+#pragma unroll
+        for (int i = 0; i < N0; ++i) {
+            const float xi = lane_read(x_cur, i);
+            w1[i] = __builtin_fmaf(nld1, xi, w1[i]);
+            if (keepv && hid && i < n0) l1.VW[lane * n0 + i] = nld1 * xi;
+        }
+        b1 += nld1;
+        if (keepv) {
+            if (outl) l2.Vb[lane] = nld2;
+            if (hid) l1.Vb[lane] = nld1;
+        }
+        x_cur = x_1;
+        x_1 = x_2;
+    }
+
+    // ---- epilogue ----
+#pragma unroll
+    for (int i = 0; i < N0; ++i)
+        if (hid && i < n0) l1.W[lane * n0 + i] = w1[i];
+#pragma unroll
+    for (int j = 0; j < N1; ++j)
+        if (outl && j < n1) l2.W[lane * n1 + j] = w2r[j];
+    if (hid) l1.b[lane] = b1;
+    if (outl) l2.b[lane] = b2;
+    if (lane == 0) *p.loss_acc += loss_acc;
+}
+
 }  // namespace
 
 // ---- host side -------------------------------------------------------------------
@@ -224,8 +339,37 @@ hipError_t tiny_prepare()
     return hipSuccess;
 }
 
+namespace {
+
+// The register form's compile-time bounds: the smallest of {4, 16, 64} x {16, 64} x {4, 16, 64} that holds the widths.
+template <int N0, int N1>
+void tiny_regs_launch_n2(const TinyPlan &plan, hipStream_t stream)
+{
+    const int n2 = plan.layer[2].n_out;
+    if (n2 <= 4) hipLaunchKernelGGL((tiny_regs_epoch_kernel<N0, N1, 4>), dim3(1), dim3(64), 0, stream, plan);
+    else if (n2 <= 16) hipLaunchKernelGGL((tiny_regs_epoch_kernel<N0, N1, 16>), dim3(1), dim3(64), 0, stream, plan);
+    else hipLaunchKernelGGL((tiny_regs_epoch_kernel<N0, N1, 64>), dim3(1), dim3(64), 0, stream, plan);
+}
+
+template <int N0>
+void tiny_regs_launch_n1(const TinyPlan &plan, hipStream_t stream)
+{
+    if (plan.layer[1].n_out <= 16) tiny_regs_launch_n2<N0, 16>(plan, stream);
+    else tiny_regs_launch_n2<N0, 64>(plan, stream);
+}
+
+}  // namespace
+
 hipError_t launch_tiny_epoch(const TinyPlan &plan, hipStream_t stream)
 {
+    if (plan.in_registers) {   // two layers, plain gradient descent: no LDS at all
+        if (plan.L != 2 || plan.mu != 0.f) return hipErrorInvalidValue;
+        const int n0 = plan.layer[1].n_in;
+        if (n0 <= 4) tiny_regs_launch_n1<4>(plan, stream);
+        else if (n0 <= 16) tiny_regs_launch_n1<16>(plan, stream);
+        else tiny_regs_launch_n1<64>(plan, stream);
+        return hipGetLastError();
+    }
     switch (plan.L) {
     case 1: tiny_launch_one<1>(plan, stream); break;
     case 2: tiny_launch_one<2>(plan, stream); break;

@@ -28,8 +28,9 @@ def dnlib():
 def run_pair(dn, w, n, passes, mode, min_tile=None, tol=1e-4, biases=True, resident=1, twin=1, twin_expected=None, tiny=0,
              wide=0):
     """`passes` = list of momenta; one pass over the first n samples per entry.  twin=0 keeps
-    plain-gradient-descent passes of deeper nets on the general persistent kernel; tiny=1 lets nets
-    with no layer wider than 64 run on the one-wavefront kernel; wide=1 lets two-layer nets with a
+    plain-gradient-descent passes of deeper nets on the general persistent kernel; tiny=1 or 2 lets nets
+    with no layer wider than 64 run on one wavefront (1: plain passes of two-layer nets keep the net in
+    registers, 2: every pass keeps it in LDS); wide=1 lets two-layer nets with a
     hidden layer beyond LDS run on the kernel that keeps rows of W_1 in LDS and registers (every
     pass must then report that schedule)."""
     if biases:
@@ -51,7 +52,9 @@ def run_pair(dn, w, n, passes, mode, min_tile=None, tol=1e-4, biases=True, resid
     for mu in passes:
         got = net.dn_train_epoch(X, y, 1, w.lr, mu)
         if tiny:
-            assert net.dn_last_schedule() == dn.DN_SCHED_ONE_WAVE, net.dn_last_schedule()
+            regs = tiny == 1 and len(w.widths) == 3 and mu == 0.0
+            want = dn.DN_SCHED_ONE_WAVE_REGISTERS if regs else dn.DN_SCHED_ONE_WAVE
+            assert net.dn_last_schedule() == want, (net.dn_last_schedule(), want)
         elif wide:
             assert net.dn_last_schedule() == dn.DN_SCHED_WIDE_HIDDEN, net.dn_last_schedule()
         elif mode == PERSISTENT and twin_expected is not None:
@@ -142,17 +145,25 @@ TINY_SHAPES = [
     ([9, 1], [SIG], MSE),
     ([1, 1, 2], [TANH, SOFTMAX], CE),
     ([3, 5, 7, 2, 9, 4, 6, 8, 10], [TANH, SIG, TANH, LIN, RELU, SIG, TANH, SOFTMAX], CE),   # eight layers
+    # two layers at and around the sizes the register-resident form is built for
+    ([64, 64, 64], [TANH, SOFTMAX], CE),
+    ([5, 17, 16], [RELU, SIG], MSE),
+    ([16, 16, 4], [SIG, LIN], MSE),
+    ([17, 3, 17], [TANH, TANH], MSE),
 ]
 
 
+@pytest.mark.parametrize("form", [1, 2], ids=["registers", "lds"])
 @pytest.mark.parametrize("widths,acts,loss", TINY_SHAPES)
-def test_one_wave_epochs_match_checker(dnlib, widths, acts, loss):
+def test_one_wave_epochs_match_checker(dnlib, widths, acts, loss, form):
     """Nets with no layer wider than 64 run whole epochs on one wavefront: a plain pass (which
-    leaves the last step's change as velocity), two momentum passes, a plain pass again."""
-    announce("online one-wave widths=%s" % (widths,))
+    leaves the last step's change as velocity), two momentum passes, a plain pass again.  Form 1
+    lets plain passes of two-layer nets keep the whole net in registers; form 2 keeps every
+    pass on the kernel that holds the net in LDS."""
+    announce("online one-wave widths=%s form=%d" % (widths, form))
     w = synth.make("online", widths, acts, loss, n_samples=48, features="normal", init="xavier_uniform",
                    batch=1, lr=0.005, momentum=0.0, seed=4)
-    run_pair(dnlib, w, 48, [0.0, 0.5, 0.5, 0.0], PERSISTENT, tiny=1)
+    run_pair(dnlib, w, 48, [0.0, 0.5, 0.5, 0.0], PERSISTENT, tiny=form)
 
 
 def test_one_wave_single_sample_and_refusal(dnlib):
@@ -167,7 +178,7 @@ def test_one_wave_single_sample_and_refusal(dnlib):
     X = torch.from_numpy(w.X).to("cuda:0")
     y = torch.from_numpy(w.labels).to("cuda:0")
     assert np.isfinite(net.dn_train_epoch(X, y, 1, w.lr, 0.0))
-    assert net.dn_last_schedule() != dnlib.DN_SCHED_ONE_WAVE
+    assert net.dn_last_schedule() not in (dnlib.DN_SCHED_ONE_WAVE, dnlib.DN_SCHED_ONE_WAVE_REGISTERS)
     net.close()
 
 
@@ -250,10 +261,11 @@ def test_iris_like_ten_epochs_persistent(dnlib):
     run_pair(dnlib, w, w.n_samples, [0.0] * 10, PERSISTENT, tol=1e-3, biases=False)
 
 
-def test_iris_like_ten_epochs_one_wave(dnlib):
-    announce("cfg1 4-16-3 B=1, 10 epochs, one wavefront (the default schedule for this net)")
+@pytest.mark.parametrize("form", [1, 2], ids=["registers", "lds"])
+def test_iris_like_ten_epochs_one_wave(dnlib, form):
+    announce("cfg1 4-16-3 B=1, 10 epochs, one wavefront (the default schedule for this net), form %d" % form)
     w = synth.iris_like()
-    run_pair(dnlib, w, w.n_samples, [0.0] * 10, PERSISTENT, tol=1e-3, biases=False, tiny=1)
+    run_pair(dnlib, w, w.n_samples, [0.0] * 10, PERSISTENT, tol=1e-3, biases=False, tiny=form)
 
 
 def test_digits_like_online_prefix_per_phase(dnlib):
@@ -534,7 +546,7 @@ def test_every_benchmark_workload_takes_its_intended_schedule(dnlib):
     announce("schedules of the benchmark workloads")
     S = dnlib
     cases = [
-        (synth.iris_like(), S.DN_SCHED_ONE_WAVE),
+        (synth.iris_like(), S.DN_SCHED_ONE_WAVE_REGISTERS),
         (synth.digits_like_online(n_samples=8), S.DN_SCHED_TWO_COPY),
         (synth.digits_like_minibatch(n_samples=256), S.DN_SCHED_MINIBATCH),
         (synth.wide_relu(n_samples=512), S.DN_SCHED_LAUNCHES),

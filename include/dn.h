@@ -408,7 +408,9 @@ enum {
     DN_SCHED_MINIBATCH_DEEP = 5,  /* the persistent minibatch kernel for deeper nets */
     DN_SCHED_ONE_WAVE = 6,        /* batch 1, every layer at most 64 wide: one wavefront runs the epoch */
     DN_SCHED_WIDE_HIDDEN = 7,     /* batch 1, two layers, a hidden layer too wide for LDS: rows in LDS, registers and memory */
-    DN_SCHED_ONE_WAVE_REGISTERS = 8 /* batch 1, two layers at most 64 wide, no momentum: one wavefront, the net in its registers */
+    DN_SCHED_ONE_WAVE_REGISTERS = 8, /* batch 1, two layers at most 64 wide, no momentum: one wavefront, the net in its registers */
+    DN_SCHED_ONE_WORKGROUP = 9     /* batch 1, two layers, no momentum, W_1 within one compute unit's registers: one workgroup
+                                      (the last few samples of a call may run on another batch-1 schedule) */
 };
 dn_status dn_last_schedule(dn_net *net, int32_t *schedule);
 dn_status dn_kernel_time(dn_net *net, int32_t kernel_class, float *ms_total, int64_t *launches);
@@ -452,6 +454,10 @@ dn_status dn_kernel_flops(dn_net *net, int32_t kernel_class, double *flops);
  *                    340-100000-10 network -- runs on the persistent kernel that keeps most rows of W_1
  *                    (with momentum: and of its velocities) in LDS and in registers for the whole epoch
  *                    and streams the rest; 0: such nets take the general persistent kernel
+ *   "online_solo"    1 (default): batch 1 without momentum on a two-layer net with at most 256 hidden units,
+ *                    at most 16 outputs and at most 1568 / 784 / 392 inputs (for up to 64 / 128 / 256
+ *                    hidden units) runs on ONE workgroup that keeps W_1 in its registers and reads the
+ *                    samples through scalar loads; 0: such nets take the other batch-1 schedules
  *   "online_tiny"    1 (default): batch 1 on a net whose layers are all at most 64 wide (and whose
  *                    parameters fit in LDS, twice with momentum) runs on a single wavefront that keeps
  *                    the whole net in LDS -- in its registers, for two layers and momentum 0; 2: the

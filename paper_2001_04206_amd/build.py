@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libdn.so")
-SOURCES = ["dn_api.hip", "dn_gemm.hip", "dn_small.hip", "dn_online.hip", "dn_twin.hip", "dn_tiny.hip", "dn_wide.hip", "dn_conv.hip", "dn_cnn.hip"]
+SOURCES = ["dn_api.hip", "dn_gemm.hip", "dn_small.hip", "dn_online.hip", "dn_twin.hip", "dn_solo.hip", "dn_tiny.hip", "dn_wide.hip", "dn_conv.hip", "dn_cnn.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     # keep the compiler from forming packed fp32 instructions

@@ -106,7 +106,7 @@ struct dn_net {
     bool w1_as_in_bwd = false;   // W_1 is still the matrix the last dn_backward propagated through
     // options
     int time_kernels = 0, gemm_variant = -1, online_mode = 0, online_min_tile = ON_DEFAULT_MIN_TILE,
-        online_resident = 1, online_twin = 1, online_tiny = 1, online_wide = 1, split_k_on = 1, merge_launches = 1;
+        online_resident = 1, online_twin = 1, online_tiny = 1, online_solo = 1, online_wide = 1, split_k_on = 1, merge_launches = 1;
     // persistent batch-1 kernel
     OnlineGeom geom{};
     bool online_ok = false;
@@ -456,7 +456,34 @@ dn_status run_wide(dn_net *net, const WideGeom &g, const float *X, const int32_t
     return DN_OK;
 }
 
-// A whole batch-1 epoch in persistent-kernel launches of at most 2^30 steps each.
+// Batch-1 steps of a two-layer net on one workgroup that keeps W_1 in its registers (plain gradient descent).
+dn_status run_solo(dn_net *net, const SoloGeom &g, const float *X, const int32_t *labels, int64_t n_samples, float lr,
+                   bool keep_v, bool timing)
+{
+    SoloPlan p{};
+    p.W1 = net->W(1); p.b1 = net->b(1); p.VW1 = net->VW(1); p.Vb1 = net->Vb(1);
+    p.W2 = net->W(2); p.b2 = net->b(2); p.VW2 = net->VW(2); p.Vb2 = net->Vb(2);
+    p.loss_acc = net->epoch_acc();
+    p.n0 = net->n[0]; p.n1 = net->n[1]; p.n2 = net->n[2];
+    p.act1 = net->act[1]; p.act2 = net->act[2]; p.loss = net->loss;
+    p.lr = lr;
+    const int64_t chunk = (int64_t)1 << 30;   // the kernel counts its steps in 32 bits
+    for (int64_t s0 = 0; s0 < n_samples; s0 += chunk) {
+        const int64_t n = (n_samples - s0) < chunk ? (n_samples - s0) : chunk;
+        p.X = X + (size_t)s0 * net->n[0];
+        p.labels = labels + s0;
+        p.n_samples = n;
+        p.keep_v = (keep_v && s0 + n >= n_samples) ? 1 : 0;
+        ScopedTimer st(net, DN_K_ONLINE, timing);
+        DN_HIP(launch_solo_epoch(g, p, net->stream));
+    }
+    return DN_OK;
+}
+
+dn_status run_online_shared(dn_net *net, const float *X, const int32_t *labels, int64_t n_samples, float lr, float mu,
+                            bool timing);
+
+// A whole batch-1 epoch on the persistent kernel that suits the net.
 dn_status run_online(dn_net *net, const float *X, const int32_t *labels, int64_t n_samples, float lr, float mu,
                      bool timing)
 {
@@ -467,6 +494,34 @@ dn_status run_online(dn_net *net, const float *X, const int32_t *labels, int64_t
             return run_tiny(net, tp, X, labels, n_samples, lr, mu, timing);
         }
     }
+    bool solo_ran = false;
+    if (mu == 0.f && net->online_solo) {
+        // two layers, W_1 within one compute unit's registers: one workgroup, no exchange through memory.
+        // Its scalar reads of a sample may run past the row's end; the last tail_steps samples, where
+        // that would leave the array, go to the kernels below (which must then be known to fit).
+        SoloGeom sg;
+        if (solo_geometry(net->n.data(), L, sg) && n_samples > sg.tail_steps && (sg.tail_steps == 0 || net->online_ok)) {
+            const int64_t n_solo = n_samples - sg.tail_steps;
+            dn_status st = run_solo(net, sg, X, labels, n_solo, lr, sg.tail_steps == 0, timing);
+            if (st != DN_OK) return st;
+            net->last_schedule = DN_SCHED_ONE_WORKGROUP;
+            if (sg.tail_steps == 0) return DN_OK;
+            X += (size_t)n_solo * net->n[0];
+            labels += n_solo;
+            n_samples = sg.tail_steps;
+            solo_ran = true;
+        }
+    }
+    dn_status st = run_online_shared(net, X, labels, n_samples, lr, mu, timing);
+    if (solo_ran && st == DN_OK) net->last_schedule = DN_SCHED_ONE_WORKGROUP;
+    return st;
+}
+
+// ... on the kernels whose workgroups exchange through device memory, in launches of at most 2^30 steps each.
+dn_status run_online_shared(dn_net *net, const float *X, const int32_t *labels, int64_t n_samples, float lr, float mu,
+                            bool timing)
+{
+    const int L = net->L;
     if (mu == 0.f && net->online_twin && net->twin_ready) {
         // slices that fit in LDS with a second copy of the inner layers: no partial sums cross workgroups
         TwinGeom tg;
@@ -1152,6 +1207,9 @@ dn_status dn_set_option(dn_net *net, const char *name, int64_t value)
     } else if (!strcmp(name, "online_tiny")) {
         if (value < 0 || value > 2) return DN_ERR_INVALID_ARG;
         net->online_tiny = (int)value;
+    } else if (!strcmp(name, "online_solo")) {
+        if (value != 0 && value != 1) return DN_ERR_INVALID_ARG;
+        net->online_solo = (int)value;
     } else if (!strcmp(name, "online_twin")) {
         if (value != 0 && value != 1) return DN_ERR_INVALID_ARG;
         net->online_twin = (int)value;

@@ -405,6 +405,31 @@ bool tiny_plan(const int32_t *n, int L, bool want_v, TinyPlan &p);
 hipError_t tiny_prepare();
 hipError_t launch_tiny_epoch(const TinyPlan &plan, hipStream_t stream);
 
+// ---- two-layer nets on one workgroup (dn_solo.hip) ----
+constexpr int SOLO_THREADS = 512;   // eight waves, two per SIMD: 256 registers a lane
+constexpr int SOLO_MAX_OUT = 16;
+
+struct SoloGeom {
+    int ug;           // groups of 64 hidden units (1, 2 or 4); 8 / ug column segments
+    int c;            // columns of W_1 per lane (the kernel is compiled per value)
+    int tail_steps;   // last steps of a sample array the kernel must not be given (its reads would pass the array's end)
+};
+
+struct SoloPlan {
+    float *W1, *b1, *W2, *b2, *VW1, *Vb1, *VW2, *Vb2;
+    double *loss_acc;
+    const float *X;          // only ever read (the kernel reads it through the constant address space)
+    const int32_t *labels;
+    int64_t n_samples;
+    int n0, n1, n2, act1, act2, loss, keep_v;
+    float lr;
+};
+
+// False unless the net has two layers, at most 256 hidden units, at most SOLO_MAX_OUT outputs and a
+// row of W_1 fits the registers of the lanes that share it.
+bool solo_geometry(const int32_t *n, int L, SoloGeom &g);
+hipError_t launch_solo_epoch(const SoloGeom &g, const SoloPlan &plan, hipStream_t stream);
+
 // Slices and buffer offsets for widths n[0..L]; false if the net does not fit the kernel
 // (too many layers, output layer too wide, LDS).  want_v: velocity slices are read every step
 // (momentum), so they must fit in LDS next to the weights for the slices to be resident.

@@ -22,12 +22,13 @@ DN_LOSS_MSE, DN_LOSS_CROSS_ENTROPY = 0, 1
 DN_K_FORWARD, DN_K_DELTA, DN_K_GRAD_UPDATE, DN_K_OUTPUT, DN_K_ONLINE = range(5)
 KERNEL_CLASS_NAMES = ["forward", "delta", "grad_update", "output", "online"]
 (DN_SCHED_NONE, DN_SCHED_LAUNCHES, DN_SCHED_PER_SAMPLE, DN_SCHED_TWO_COPY, DN_SCHED_MINIBATCH,
- DN_SCHED_MINIBATCH_DEEP, DN_SCHED_ONE_WAVE, DN_SCHED_WIDE_HIDDEN, DN_SCHED_ONE_WAVE_REGISTERS) = range(9)
+ DN_SCHED_MINIBATCH_DEEP, DN_SCHED_ONE_WAVE, DN_SCHED_WIDE_HIDDEN, DN_SCHED_ONE_WAVE_REGISTERS,
+ DN_SCHED_ONE_WORKGROUP) = range(10)
 # the kernel behind each persistent schedule
 SCHEDULE_KERNELS = {DN_SCHED_PER_SAMPLE: "online_epoch_kernel", DN_SCHED_TWO_COPY: "twin_epoch_kernel",
                     DN_SCHED_MINIBATCH: "batch_epoch_kernel", DN_SCHED_MINIBATCH_DEEP: "deep_batch_epoch_kernel",
                     DN_SCHED_ONE_WAVE: "tiny_epoch_kernel", DN_SCHED_WIDE_HIDDEN: "wide_epoch_kernel",
-                    DN_SCHED_ONE_WAVE_REGISTERS: "tiny_regs_epoch_kernel"}
+                    DN_SCHED_ONE_WAVE_REGISTERS: "tiny_regs_epoch_kernel", DN_SCHED_ONE_WORKGROUP: "solo_epoch_kernel"}
 
 EXPORTS = [
     "dn_status_string", "dn_net_arena_bytes", "dn_net_create", "dn_net_destroy", "dn_set_params",

@@ -26,13 +26,14 @@ def dnlib():
 
 
 def run_pair(dn, w, n, passes, mode, min_tile=None, tol=1e-4, biases=True, resident=1, twin=1, twin_expected=None, tiny=0,
-             wide=0):
+             wide=0, solo=0):
     """`passes` = list of momenta; one pass over the first n samples per entry.  twin=0 keeps
     plain-gradient-descent passes of deeper nets on the general persistent kernel; tiny=1 or 2 lets nets
     with no layer wider than 64 run on one wavefront (1: plain passes of two-layer nets keep the net in
     registers, 2: every pass keeps it in LDS); wide=1 lets two-layer nets with a
     hidden layer beyond LDS run on the kernel that keeps rows of W_1 in LDS and registers (every
-    pass must then report that schedule)."""
+    pass must then report that schedule); solo=1 lets plain passes of two-layer nets whose W_1 fits one
+    compute unit's registers run on one workgroup (solo=2: ... but this call has too few samples for it)."""
     if biases:
         rng = np.random.default_rng(11)
         w.b = [rng.standard_normal(k).astype(np.float32) * 0.1 for k in w.widths[1:]]
@@ -45,6 +46,7 @@ def run_pair(dn, w, n, passes, mode, min_tile=None, tol=1e-4, biases=True, resid
     net.dn_set_option("online_twin", twin)
     net.dn_set_option("online_tiny", tiny)
     net.dn_set_option("online_wide", wide)
+    net.dn_set_option("online_solo", 1 if solo else 0)
     o = Oracle("o32", w.widths, w.acts, w.loss)
     o.set_params(w.W, w.b)
     X = torch.from_numpy(w.X[:n]).to("cuda:0")
@@ -55,6 +57,9 @@ def run_pair(dn, w, n, passes, mode, min_tile=None, tol=1e-4, biases=True, resid
             regs = tiny == 1 and len(w.widths) == 3 and mu == 0.0
             want = dn.DN_SCHED_ONE_WAVE_REGISTERS if regs else dn.DN_SCHED_ONE_WAVE
             assert net.dn_last_schedule() == want, (net.dn_last_schedule(), want)
+        elif solo:
+            one = solo == 1 and mu == 0.0
+            assert (net.dn_last_schedule() == dn.DN_SCHED_ONE_WORKGROUP) == one, (net.dn_last_schedule(), mu)
         elif wide:
             assert net.dn_last_schedule() == dn.DN_SCHED_WIDE_HIDDEN, net.dn_last_schedule()
         elif mode == PERSISTENT and twin_expected is not None:
@@ -164,6 +169,50 @@ def test_one_wave_epochs_match_checker(dnlib, widths, acts, loss, form):
     w = synth.make("online", widths, acts, loss, n_samples=48, features="normal", init="xavier_uniform",
                    batch=1, lr=0.005, momentum=0.0, seed=4)
     run_pair(dnlib, w, 48, [0.0, 0.5, 0.5, 0.0], PERSISTENT, tiny=form)
+
+
+SOLO_SHAPES = [
+    # two layers, W_1 within one compute unit's registers; (unit groups, columns per lane, samples left to other kernels)
+    ([784, 128, 10], [SIG, SOFTMAX], CE),      # 2, 196, 0: the 784-128-10 benchmark shape
+    ([100, 100, 10], [TANH, SOFTMAX], CE),     # 2, 32, 1
+    ([1500, 50, 16], [RELU, SOFTMAX], CE),     # 1, 196, 1
+    ([300, 256, 3], [SIG, SIG], MSE),          # 4, 196, 1
+    ([5, 200, 2], [TANH, LIN], MSE),           # 4, 32, 12
+    ([65, 70, 16], [SIG, TANH], MSE),          # 2, 32, 1
+    ([392, 129, 1], [TANH, SIG], MSE),         # 4, 196, 0
+    ([512, 64, 12], [RELU, SOFTMAX], CE),      # 1, 64, 0
+    ([200, 40, 5], [SIG, SOFTMAX], CE),        # 1, 32, 1
+    ([1000, 30, 4], [TANH, LIN], MSE),         # 1, 128, 1
+    ([250, 120, 7], [RELU, SOFTMAX], CE),      # 2, 64, 1
+    ([500, 90, 10], [SIG, SOFTMAX], CE),       # 2, 128, 1
+    ([128, 250, 16], [TANH, SOFTMAX], CE),     # 4, 64, 0
+    ([255, 130, 2], [SIG, SIG], MSE),          # 4, 128, 1
+]
+
+
+@pytest.mark.parametrize("widths,acts,loss", SOLO_SHAPES)
+def test_one_workgroup_epochs_match_checker(dnlib, widths, acts, loss):
+    """Two-layer nets whose first weight matrix fits one compute unit's registers: a plain pass on one
+    workgroup (which leaves the last step's change as velocity), a momentum pass (another kernel), a
+    plain pass again."""
+    announce("online one-workgroup widths=%s" % (widths,))
+    w = synth.make("online", widths, acts, loss, n_samples=40, features="normal", init="xavier_uniform",
+                   batch=1, lr=0.005, momentum=0.0, seed=6)
+    run_pair(dnlib, w, 40, [0.0, 0.5, 0.0], PERSISTENT, solo=1)
+
+
+def test_one_workgroup_edges(dnlib):
+    announce("online one-workgroup: one sample; fewer samples than the kernel leaves to others; not two layers")
+    w = synth.make("online", [784, 128, 10], [SIG, SOFTMAX], CE, n_samples=1, features="normal",
+                   init="xavier_uniform", batch=1, lr=0.05, momentum=0.0, seed=2)
+    run_pair(dnlib, w, 1, [0.0, 0.0], PERSISTENT, solo=1)
+    w = synth.make("online", [5, 200, 2], [TANH, LIN], MSE, n_samples=12, features="normal",
+                   init="xavier_uniform", batch=1, lr=0.05, momentum=0.0, seed=2)
+    run_pair(dnlib, w, 12, [0.0], PERSISTENT, solo=2)      # 12 samples, all 12 would be left over
+    run_pair(dnlib, w, 12, [0.0], 0, solo=2)               # (automatic mode)
+    w = synth.make("online", [100, 80, 70, 10], [TANH, TANH, SOFTMAX], CE, n_samples=8, features="normal",
+                   init="xavier_uniform", batch=1, lr=0.05, momentum=0.0, seed=2)
+    run_pair(dnlib, w, 8, [0.0], PERSISTENT, solo=2)
 
 
 def test_one_wave_single_sample_and_refusal(dnlib):
@@ -547,7 +596,7 @@ def test_every_benchmark_workload_takes_its_intended_schedule(dnlib):
     S = dnlib
     cases = [
         (synth.iris_like(), S.DN_SCHED_ONE_WAVE_REGISTERS),
-        (synth.digits_like_online(n_samples=8), S.DN_SCHED_TWO_COPY),
+        (synth.digits_like_online(n_samples=8), S.DN_SCHED_ONE_WORKGROUP),
         (synth.digits_like_minibatch(n_samples=256), S.DN_SCHED_MINIBATCH),
         (synth.wide_relu(n_samples=512), S.DN_SCHED_LAUNCHES),
         (synth.tanh_sweep(1, n_samples=8), S.DN_SCHED_TWO_COPY),

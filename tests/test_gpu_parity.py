@@ -149,6 +149,7 @@ PAIR_CASES = [
     ([1024, 1024, 1024, 10], [TANH, TANH, SOFTMAX], CE, 516, 0.9),     # batch beyond the limit of 512: one launch per product
     ([1028, 1040, 1100, 12], [TANH, TANH, SOFTMAX], CE, 136, 0.9),     # narrow last layer: its gradient rides with the delta product below it
     ([516, 1040, 1100, 16], [RELU, SIG, SIG], MSE, 50, 0.0),           # the same with squared error and 16 outputs
+    ([2052, 2060, 2100, 24], [TANH, RELU, SOFTMAX], CE, 24, 0.9),      # 33 x 33 tiles and more per layer, an odd count
 ]
 
 

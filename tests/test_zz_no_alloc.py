@@ -4,6 +4,7 @@ calls in a row on one device, the second with a smaller layer, so the second cal
 one's contents in the shared array.  Both run the same launches, so the results must be the same
 bits; the larger case is also held against the CPU checker."""
 import ctypes as C
+import gc
 
 import numpy as np
 import pytest
@@ -70,12 +71,17 @@ def test_static_scratch_matches_workspace_entry_point_twice():
     # everything is allocated before the two static calls; they run back to back on one stream
     outs = [_buffers(*c[3]) for c in prepared]
     torch.cuda.synchronize()
-    before = torch.cuda.memory_allocated()
+    # Allocations between here and the second call's end are counted, not bytes in use: the collector may
+    # free tensors of earlier tests at any moment, which lowers the bytes in use but never the count.
+    gc.collect()
+    allocs_before = torch.cuda.memory_stats()["allocation.all.allocated"]
+    free_before = torch.cuda.mem_get_info()[0]
     for (shape, pad, act, _, _), got in zip(prepared, outs):
         announce("no-alloc: static entry point, shape %s" % (shape,))
         assert _raw_call(True, got, shape, 1, pad, act) == dn.DN_OK
     torch.cuda.synchronize()
-    assert torch.cuda.memory_allocated() == before
+    assert torch.cuda.memory_stats()["allocation.all.allocated"] == allocs_before   # none through torch
+    assert torch.cuda.mem_get_info()[0] >= free_before                                # none from the device either
     for (shape, pad, act, host, ref), got in zip(prepared, outs):
         for name in ("delta", "dX", "dW", "db"):
             assert torch.equal(got[name], ref[name]), "%s differs at shape %s" % (name, shape)

@@ -227,14 +227,14 @@ __global__ __launch_bounds__(64) void tiny_regs_epoch_kernel(TinyPlan p)
             const float ex = outl ? expf(z - m) : 0.f;
             const float sum = wave_sum(ex);
             d2 = outl ? ex * (1.0f / sum) - t : 0.f;
-            e = logf(sum) - (lane_read(z2, y) - m);
+            e = lane == 0 ? logf(sum) - (lane_read(z2, y) - m) : 0.f;
         } else {
             const float a2 = outl ? act_fn(l2.act, z2) : 0.f;
             const float f = outl ? a2 - t : 0.f;
             d2 = f * act_deriv(l2.act, a2);
-            e = wave_sum(0.5f * f * f);
+            e = 0.5f * f * f;   // this lane's share: the lanes' sums meet once, after the last step
         }
-        if (lane == 0) loss_acc += (double)e;
+        loss_acc += (double)e;
 
         // ---- deltas of the hidden units through W_2 as it was ----
         float sacc = 0.f;
@@ -277,7 +277,14 @@ __global__ __launch_bounds__(64) void tiny_regs_epoch_kernel(TinyPlan p)
         if (outl && j < n1) l2.W[lane * n1 + j] = w2r[j];
     if (hid) l1.b[lane] = b1;
     if (outl) l2.b[lane] = b2;
-    if (lane == 0) *p.loss_acc += loss_acc;
+    // the lanes' loss sums, added in lane order
+    double total = 0.0;
+    for (int l = 0; l < 64; ++l) {
+        const unsigned lo = __builtin_amdgcn_readlane((int)(__builtin_bit_cast(unsigned long long, loss_acc) & 0xffffffffu), l);
+        const unsigned hi = __builtin_amdgcn_readlane((int)(__builtin_bit_cast(unsigned long long, loss_acc) >> 32), l);
+        total += __builtin_bit_cast(double, ((unsigned long long)hi << 32) | lo);
+    }
+    if (lane == 0) *p.loss_acc += total;
 }
 
 }  // namespace

@@ -181,9 +181,30 @@ __device__ __forceinline__ float lane_read(float v, int l)
     return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), l));
 }
 
+// Elements base .. base + Q - 1 of a vector spread over the lanes, as Q scalar registers at once: the
+// empty statement needs all of them together, so the cross-lane reads are issued back to back and
+// the multiply-adds that use them follow without the wait states a scalar register needs right after
+// a vector instruction has written it.  (Left alone the compiler reads, waits and uses one at a time.)
+template <int Q>
+struct LaneQ { float v[Q]; };
+template <int Q>
+__device__ __forceinline__ LaneQ<Q> lane_read_q(float v, int base)
+{
+    static_assert(Q == 4 || Q == 8, "four or eight at a time");
+    LaneQ<Q> r;
+#pragma unroll
+    for (int q = 0; q < Q; ++q) r.v[q] = lane_read(v, base + q);
+    if constexpr (Q == 4)
+        asm volatile("" : "+s"(r.v[0]), "+s"(r.v[1]), "+s"(r.v[2]), "+s"(r.v[3]));
+    else
+        asm volatile("" : "+s"(r.v[0]), "+s"(r.v[1]), "+s"(r.v[2]), "+s"(r.v[3]), "+s"(r.v[4]), "+s"(r.v[5]), "+s"(r.v[6]), "+s"(r.v[7]));
+    return r;
+}
+
 template <int N0, int N1, int N2>
 __global__ __launch_bounds__(64) void tiny_regs_epoch_kernel(TinyPlan p)
 {
+    constexpr int Q0 = N0 >= 8 ? 8 : 4, Q1 = N1 >= 8 ? 8 : 4, Q2 = N2 >= 8 ? 8 : 4;   // cross-lane reads at a time
     const int lane = threadIdx.x;
     const TinyLayer &l1 = p.layer[1], &l2 = p.layer[2];
     const int n0 = l1.n_in, n1 = l1.n_out, n2 = l2.n_out;
@@ -212,11 +233,19 @@ __global__ __launch_bounds__(64) void tiny_regs_epoch_kernel(TinyPlan p)
         // ---- feed forward ----
         float z1 = b1;
 #pragma unroll
-        for (int i = 0; i < N0; ++i) z1 = __builtin_fmaf(w1[i], lane_read(x_cur, i), z1);
+        for (int i = 0; i < N0; i += Q0) {
+            const LaneQ<Q0> xs = lane_read_q<Q0>(x_cur, i);
+#pragma unroll
+            for (int q = 0; q < Q0; ++q) z1 = __builtin_fmaf(w1[i + q], xs.v[q], z1);
+        }
         const float a1 = hid ? act_fn(l1.act, z1) : 0.f;
         float z2 = b2;
 #pragma unroll
-        for (int j = 0; j < N1; ++j) z2 = __builtin_fmaf(w2r[j], lane_read(a1, j), z2);
+        for (int j = 0; j < N1; j += Q1) {
+            const LaneQ<Q1> as = lane_read_q<Q1>(a1, j);
+#pragma unroll
+            for (int q = 0; q < Q1; ++q) z2 = __builtin_fmaf(w2r[j + q], as.v[q], z2);
+        }
 
         // ---- output error and loss ----
         const float t = lane == y ? 1.0f : 0.0f;
@@ -239,28 +268,46 @@ __global__ __launch_bounds__(64) void tiny_regs_epoch_kernel(TinyPlan p)
         // ---- deltas of the hidden units through W_2 as it was ----
         float sacc = 0.f;
 #pragma unroll
-        for (int k = 0; k < N2; ++k) sacc = __builtin_fmaf(w2c[k], lane_read(d2, k), sacc);
+        for (int k = 0; k < N2; k += Q2) {
+            const LaneQ<Q2> ds = lane_read_q<Q2>(d2, k);
+#pragma unroll
+            for (int q = 0; q < Q2; ++q) sacc = __builtin_fmaf(w2c[k + q], ds.v[q], sacc);
+        }
         const float d1 = hid ? sacc * act_deriv(l1.act, a1) : 0.f;
 
         // ---- updates: w = fma(-(lr delta), input, w) ----
         const float nld2 = -(p.lr * d2), nld1 = -(p.lr * d1);
 #pragma unroll
-        for (int j = 0; j < N1; ++j) {
-            const float aj = lane_read(a1, j);
-            w2r[j] = __builtin_fmaf(nld2, aj, w2r[j]);
-            if (keepv && outl && j < n1) l2.VW[lane * n1 + j] = nld2 * aj;
+        for (int j = 0; j < N1; j += Q1) {
+            const LaneQ<Q1> as = lane_read_q<Q1>(a1, j);
+#pragma unroll
+            for (int q = 0; q < Q1; ++q) w2r[j + q] = __builtin_fmaf(nld2, as.v[q], w2r[j + q]);
         }
 #pragma unroll
-        for (int k = 0; k < N2; ++k) w2c[k] = __builtin_fmaf(lane_read(nld2, k), a1, w2c[k]);
+        for (int k = 0; k < N2; k += Q2) {
+            const LaneQ<Q2> gs = lane_read_q<Q2>(nld2, k);
+#pragma unroll
+            for (int q = 0; q < Q2; ++q) w2c[k + q] = __builtin_fmaf(gs.v[q], a1, w2c[k + q]);
+        }
         b2 += nld2;
 #pragma unroll
-        for (int i = 0; i < N0; ++i) {
-            const float xi = lane_read(x_cur, i);
-            w1[i] = __builtin_fmaf(nld1, xi, w1[i]);
-            if (keepv && hid && i < n0) l1.VW[lane * n0 + i] = nld1 * xi;
+        for (int i = 0; i < N0; i += Q0) {
+            const LaneQ<Q0> xs = lane_read_q<Q0>(x_cur, i);
+#pragma unroll
+            for (int q = 0; q < Q0; ++q) w1[i + q] = __builtin_fmaf(nld1, xs.v[q], w1[i + q]);
         }
         b1 += nld1;
         if (keepv) {
+            // (the widths as the compiler cannot see through them: the bounds tests below would
+            // otherwise be computed once before the loop and held in scalar registers through every step)
+            int n0v = n0, n1v = n1;
+            asm volatile("" : "+s"(n0v), "+s"(n1v));
+#pragma unroll
+            for (int j = 0; j < N1; ++j)
+                if (outl && j < n1v) l2.VW[lane * n1v + j] = nld2 * lane_read(a1, j);
+#pragma unroll
+            for (int i = 0; i < N0; ++i)
+                if (hid && i < n0v) l1.VW[lane * n0v + i] = nld1 * lane_read(x_cur, i);
             if (outl) l2.Vb[lane] = nld2;
             if (hid) l1.Vb[lane] = nld1;
         }

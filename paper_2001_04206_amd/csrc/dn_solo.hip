@@ -200,7 +200,6 @@ __global__ __launch_bounds__(SOLO_THREADS) __attribute__((amdgpu_waves_per_eu(2,
 #pragma unroll
             for (int u = 0; u < UG; ++u) {
                 w2r[kk][u] = __builtin_fmaf(g, a1[u], w2r[kk][u]);
-                if (keepv && k < n2 && lane + 64 * u < n1) p.VW2[k * n1 + lane + 64 * u] = g * a1[u];
             }
         }
         b2 += nld2;
@@ -243,9 +242,21 @@ __global__ __launch_bounds__(SOLO_THREADS) __attribute__((amdgpu_waves_per_eu(2,
             }
         }
         if (keepv) {
+            // (the widths as the compiler cannot see through them: the bounds tests below would otherwise be
+            // computed once before the loop and held in scalar registers through every step)
+            int n0v = n0, n1v = n1, n2v = n2;
+            asm volatile("" : "+s"(n0v), "+s"(n1v), "+s"(n2v));
 #pragma unroll
             for (int c = 0; c < C; ++c)
-                if (hid && c0 + c < n0) p.VW1[(size_t)unit * n0 + c0 + c] = nld1 * x[c];
+                if (hid && c0 + c < n0v) p.VW1[(size_t)unit * n0v + c0 + c] = nld1 * x[c];
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk) {
+                const int k = wave + 8 * kk;
+                const float g = solo_lane_read(nld2, k & 63);
+#pragma unroll
+                for (int u = 0; u < UG; ++u)
+                    if (k < n2v && lane + 64 * u < n1v) p.VW2[k * n1v + lane + 64 * u] = g * a1[u];
+            }
             if (seg == 0 && hid) p.Vb1[unit] = nld1;
             if (wave == 0 && outl) p.Vb2[lane] = nld2;
         }
@@ -253,14 +264,18 @@ __global__ __launch_bounds__(SOLO_THREADS) __attribute__((amdgpu_waves_per_eu(2,
     asm volatile("" ::"v"(pf));
 
     // ---- epilogue ----
+    // (the widths once more as the compiler cannot see through them: the prologue's bounds tests are
+    // the same ones, and it would keep all of them in scalar registers across the whole step loop)
+    int n0e = n0, n1e = n1, n2e = n2;
+    asm volatile("" : "+s"(n0e), "+s"(n1e), "+s"(n2e));
 #pragma unroll
     for (int c = 0; c < C; ++c)
-        if (hid && c0 + c < n0) p.W1[(size_t)unit * n0 + c0 + c] = w[c];
+        if (unit < n1e && c0 + c < n0e) p.W1[(size_t)unit * n0e + c0 + c] = w[c];
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk)
 #pragma unroll
         for (int u = 0; u < UG; ++u)
-            if (wave + 8 * kk < n2 && lane + 64 * u < n1) p.W2[(wave + 8 * kk) * n1 + lane + 64 * u] = w2r[kk][u];
+            if (wave + 8 * kk < n2e && lane + 64 * u < n1e) p.W2[(wave + 8 * kk) * n1e + lane + 64 * u] = w2r[kk][u];
     if (seg == 0 && hid) p.b1[unit] = b1;
     if (wave == 0 && outl) p.b2[lane] = b2;
     if (threadIdx.x == 0) *p.loss_acc += loss_sum;

@@ -81,12 +81,18 @@ __device__ __forceinline__ void rank1_update(float *T, int n, int nr, const floa
     }
 }
 
+// (The depth is a template parameter: with the layer loops of a step unrolled, a layer's shape, pointers
+// and LDS offsets are fixed places in the argument block, which the compiler reads once and keeps in
+// scalar registers -- or in the lanes of a vector register when those run out -- for the whole
+// epoch.  With a run-time depth every use was a scalar load from the argument block, several dozen
+// a step, each a round trip a lone wave waits out.)
+template <int LT>
 __global__ __launch_bounds__(ON_THREADS) void twin_epoch_kernel(TwinPlan p)
 {
     extern __shared__ __align__(16) float lds[];
     __shared__ int s_abort;
     const int w = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int L = p.L;
+    constexpr int L = LT;
     const int n0 = p.layer[1].n_in;
     const TwinLayer &last = p.layer[L];
     const int nL = last.n_out, nLin = last.n_in;
@@ -176,6 +182,7 @@ __global__ __launch_bounds__(ON_THREADS) void twin_epoch_kernel(TwinPlan p)
         bool aborted = false;
 
         // ---- forward through the hidden layers ----
+#pragma unroll
         for (int l = 1; l < L; ++l) {
             const TwinLayer &ly = p.layer[l];
             const int r0 = r0_of(l), nr = nr_of(l);
@@ -319,6 +326,7 @@ __global__ __launch_bounds__(ON_THREADS) void twin_epoch_kernel(TwinPlan p)
         }
 
         // ---- backward through the hidden layers ----
+#pragma unroll
         for (int l = L - 1; l >= 1; --l) {
             const TwinLayer &ly = p.layer[l];
             const int r0 = r0_of(l), nr = nr_of(l);
@@ -458,15 +466,45 @@ size_t twin_exchange_bytes_bound(const int32_t *n, int L)
     return bytes > ((size_t)1 << 30) ? 0 : bytes;
 }
 
+namespace {
+
+template <int LT>
+hipError_t twin_prepare_one()
+{
+    return hipFuncSetAttribute((const void *)twin_epoch_kernel<LT>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                               (int)ON_MAX_LDS_BYTES);
+}
+
+template <int LT>
+hipError_t twin_launch_one(const TwinGeom &g, const TwinPlan &plan, hipStream_t stream)
+{
+    return launch_resident(twin_epoch_kernel<LT>, plan, g.grid, (size_t)g.lds_floats * sizeof(float), stream);
+}
+
+}  // namespace
+
 hipError_t twin_prepare()
 {
-    return hipFuncSetAttribute((const void *)twin_epoch_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                               (int)ON_MAX_LDS_BYTES);
+    static_assert(ON_MAX_L == 8, "one instantiation per depth from two layers on");
+    const hipError_t e[] = {twin_prepare_one<2>(), twin_prepare_one<3>(), twin_prepare_one<4>(), twin_prepare_one<5>(),
+                            twin_prepare_one<6>(), twin_prepare_one<7>(), twin_prepare_one<8>()};
+    for (hipError_t x : e)
+        if (x != hipSuccess) return x;
+    return hipSuccess;
 }
 
 hipError_t launch_twin_epoch(const TwinGeom &g, const TwinPlan &plan, hipStream_t stream)
 {
-    return launch_resident(twin_epoch_kernel, plan, g.grid, (size_t)g.lds_floats * sizeof(float), stream);
+    switch (plan.L) {
+    case 2: return twin_launch_one<2>(g, plan, stream);
+    case 3: return twin_launch_one<3>(g, plan, stream);
+    case 4: return twin_launch_one<4>(g, plan, stream);
+    case 5: return twin_launch_one<5>(g, plan, stream);
+    case 6: return twin_launch_one<6>(g, plan, stream);
+    case 7: return twin_launch_one<7>(g, plan, stream);
+    case 8: return twin_launch_one<8>(g, plan, stream);
+    default: return hipErrorInvalidValue;
+    }
 }
 
 }  // namespace dn

@@ -125,6 +125,10 @@ TWIN_SHAPES = [
     ([12, 8, 4, 3], [SIG, TANH, SIG], MSE),                           # squared error, one workgroup
     ([256, 512, 512, 7], [RELU, TANH, LIN], MSE),
     ([1024, 1024, 1024, 1024, 10], [TANH, TANH, TANH, SOFTMAX], CE),  # the shape of the batch sweep
+    # the kernel is compiled per depth: six, seven and eight layers
+    ([16, 24, 32, 24, 16, 12, 5], [TANH, SIG, RELU, TANH, SIG, SOFTMAX], CE),
+    ([12, 20, 16, 28, 16, 20, 12, 4], [SIG, TANH, SIG, TANH, RELU, TANH, LIN], MSE),
+    ([8, 16, 12, 16, 20, 16, 12, 8, 3], [TANH, SIG, TANH, SIG, TANH, RELU, TANH, SOFTMAX], CE),
 ]
 
 

@@ -965,12 +965,14 @@ __device__ __forceinline__ void fwd_batch(const float *__restrict__ Xb, int n0, 
 // their deltas, the rank-B updates of the own rows and columns) is local; X is read from
 // device memory (L2) twice per step.  A one-layer net is the same with its input features in
 // the role of the hidden units.
+template <int LT>   // the depth, one or two layers, at compile time: the branches on it go
 __global__ __launch_bounds__(ON_THREADS) void batch_epoch_kernel(BatchPlan p)
 {
     extern __shared__ __align__(16) float lds[];
     __shared__ int s_abort;
     const int w = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int L = p.L, n0 = p.n0, nL = p.nL, nL1 = p.nL + 1, per = p.per, maxB = p.max_batch;
+    constexpr int L = LT;
+    const int n0 = p.n0, nL = p.nL, nL1 = p.nL + 1, per = p.per, maxB = p.max_batch;
     const int c0 = w * per;
     const int nr = max(0, min(per, p.n_mid - c0));   // own hidden units (L = 2) or input features (L = 1)
     const bool with_v = p.with_v != 0;
@@ -1945,13 +1947,18 @@ size_t batch_exchange_bytes_bound(const int32_t *n, int L, int max_batch)
 
 hipError_t batch_prepare()
 {
-    return hipFuncSetAttribute((const void *)batch_epoch_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+    hipError_t e = hipFuncSetAttribute((const void *)batch_epoch_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)ON_MAX_LDS_BYTES);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute((const void *)batch_epoch_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                (int)ON_MAX_LDS_BYTES);
 }
 
 hipError_t launch_batch_epoch(const BatchGeom &g, const BatchPlan &plan, hipStream_t stream)
 {
-    return launch_resident(batch_epoch_kernel, plan, g.grid, (size_t)g.lds_floats * sizeof(float), stream);
+    if (plan.L == 1) return launch_resident(batch_epoch_kernel<1>, plan, g.grid, (size_t)g.lds_floats * sizeof(float), stream);
+    if (plan.L == 2) return launch_resident(batch_epoch_kernel<2>, plan, g.grid, (size_t)g.lds_floats * sizeof(float), stream);
+    return hipErrorInvalidValue;
 }
 
 bool deep_geometry(const int32_t *n, int L, int max_batch, int min_tile, DeepGeom &g)
